@@ -1,0 +1,336 @@
+"""CPU oracle for the cache-hit denoising step of a DeepCache-style video UNet.
+
+TEST INFRASTRUCTURE ONLY. This file is the slow, plain reference that the HIP path is
+checked against. Only the test-suite, the smoke check and the benchmark's CPU-baseline
+leg may import it; the product path never does, and nothing here imports the product.
+
+Everything is the plain definition of the operation, in float64 by default (pass
+``dtype=np.float32`` to ``Oracle`` for a single-precision run). Tensors are in the
+paper's order ("Feature chunk" section): a feature map is [B, F, C, H, W]; internally
+the batch and frame axes are flattened to N = B*F, i.e. arrays are [N, C, H, W].
+numpy ``matmul`` is used as a step where the definition is a contraction; there is no
+blocking, fusion or re-ordering beyond what the definitions below state.
+
+What is computed (citations are to the paper's sections / equations):
+
+* U-Net skip structure, "Feature Calculation" paragraph, eq. U_i = Concat(D_i, U_{i+1}):
+  the shallowest up block consumes the channel-concatenation of the shallow skip feature
+  D_m and the deep feature U_{m+1} (skip channels first).
+* DeepCache reuse rule, "Asynchronous Swapping" section, cache equation and the text
+  after it: the deep feature U_{m+1} computed at a *normal* step t is stored and, at the
+  *cache* steps t+1 .. t+n-1, only D_m and U_m are recomputed and the stored feature is
+  used in the concatenation. ``full_step`` is the normal step, ``cached_step`` the cache
+  step.
+* Cache swapping, same section: the stored feature lives in host memory and is brought
+  back when required; it is a pure copy ("does not affect generation quality").
+* Feature chunk, "Feature chunk and Sliced Decoding" section, eq. Chunk(F): feature maps
+  are processed in pieces. Here every operator is chunked only along an axis it is
+  independent over (frames for per-frame operators, spatial positions for temporal
+  attention, query tokens for spatial attention), so chunking is exact; the chunked
+  variants below really loop over slices.
+
+The operators inside the shallow blocks (the paper does not spell them out; these are
+the standard definitions):
+  conv3x3      cross-correlation, zero padding 1, stride 1 or 2, plus bias
+  group_norm   per frame and per group of C/G consecutive channels, biased variance
+  silu         x / (1 + exp(-x))
+  attention    bias-free Q/K/V projections, h heads of size d, softmax(QK^T/sqrt(d))V,
+               output projection with bias
+  up2          nearest-neighbour 2x upsampling
+
+Pins: tests/test_oracle_ops.py, tests/test_oracle_step.py (brute force on tiny inputs,
+closed forms, library second opinions, the method's invariants). Output *values* of a
+whole step are not printed anywhere in the paper; they are pinned by those tests only.
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, List, Optional
+
+import numpy as np
+
+Weights = Dict[str, np.ndarray]
+
+
+# --------------------------------------------------------------------------------------
+# Operators
+# --------------------------------------------------------------------------------------
+
+def conv3x3(x: np.ndarray, w: np.ndarray, b: np.ndarray, stride: int = 1) -> np.ndarray:
+    """y[n,o,i,j] = b[o] + sum_{c,a,e} w[o,c,a,e] * x[n,c,stride*i+a-1,stride*j+e-1], zero outside.
+
+    x [N,Cin,H,W], w [Cout,Cin,3,3], b [Cout] -> y [N,Cout,H/stride,W/stride].
+    """
+    N, Cin, H, W = x.shape
+    Cout = w.shape[0]
+    assert w.shape == (Cout, Cin, 3, 3) and b.shape == (Cout,)
+    assert stride in (1, 2) and H % stride == 0 and W % stride == 0
+    Ho, Wo = H // stride, W // stride
+    xp = np.zeros((N, Cin, H + 2, W + 2), dtype=x.dtype)
+    xp[:, :, 1:H + 1, 1:W + 1] = x
+    y = np.empty((N, Cout, Ho, Wo), dtype=x.dtype)
+    y[...] = b[None, :, None, None]
+    for a in range(3):
+        for e in range(3):
+            # padded index of input row for output row i is stride*i + a
+            patch = xp[:, :, a:a + stride * Ho:stride, e:e + stride * Wo:stride]
+            patch = np.ascontiguousarray(patch).reshape(N, Cin, Ho * Wo)
+            w_tap = np.ascontiguousarray(w[:, :, a, e])  # [Cout, Cin]
+            y += np.matmul(w_tap[None], patch).reshape(N, Cout, Ho, Wo)
+    return y
+
+
+def group_norm(x: np.ndarray, gamma: np.ndarray, beta: np.ndarray, groups: int, eps: float) -> np.ndarray:
+    """Per (frame, group): mean and biased variance over (C/G)*H*W elements, then affine."""
+    N, C, H, W = x.shape
+    assert C % groups == 0
+    xg = x.reshape(N, groups, (C // groups) * H * W)
+    mu = xg.mean(axis=2, keepdims=True)
+    var = ((xg - mu) ** 2).mean(axis=2, keepdims=True)
+    y = ((xg - mu) / np.sqrt(var + x.dtype.type(eps))).reshape(N, C, H, W)
+    return y * gamma[None, :, None, None] + beta[None, :, None, None]
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    return x / (1.0 + np.exp(-x))
+
+
+def softmax_rows(s: np.ndarray) -> np.ndarray:
+    e = s - s.max(axis=-1, keepdims=True)
+    np.exp(e, out=e)
+    e /= e.sum(axis=-1, keepdims=True)
+    return e
+
+
+def attention(xq: np.ndarray, xkv: np.ndarray, wq, wk, wv, wo, bo, heads: int) -> np.ndarray:
+    """Multi-head self-attention of query rows xq [.., Lq, C] against rows xkv [.., L, C].
+
+    Q = xq Wq^T, K = xkv Wk^T, V = xkv Wv^T; per head softmax(Q K^T / sqrt(d)) V; heads merged;
+    Y = O Wo^T + bo. (xq is xkv itself, or a slice of its rows when queries are chunked.)
+    """
+    C = xq.shape[-1]
+    d = C // heads
+    assert heads * d == C
+    q = xq @ wq.T
+    k = xkv @ wk.T
+    v = xkv @ wv.T
+    o = np.empty_like(q)
+    scale = 1.0 / math.sqrt(d)
+    for hd in range(heads):
+        sl = slice(hd * d, (hd + 1) * d)
+        qh, kh, vh = (np.ascontiguousarray(t[..., sl]) for t in (q, k, v))
+        s = (qh @ np.swapaxes(kh, -1, -2)) * q.dtype.type(scale)
+        o[..., sl] = softmax_rows(s) @ vh
+    return o @ wo.T + bo
+
+
+def up2(z: np.ndarray) -> np.ndarray:
+    """Nearest-neighbour 2x: out[n,c,i,j] = z[n,c,i//2,j//2]."""
+    return np.repeat(np.repeat(z, 2, axis=2), 2, axis=3)
+
+
+def _chunks(total: int, size: int):
+    """Consecutive [start, stop) ranges of at most `size`; size <= 0 or >= total means one range."""
+    if size <= 0 or size >= total:
+        yield 0, total
+        return
+    for s in range(0, total, size):
+        yield s, min(s + size, total)
+
+
+# --------------------------------------------------------------------------------------
+# The stage
+# --------------------------------------------------------------------------------------
+
+class Oracle:
+    """Full (normal) and cached steps of one shallow stage, plus a host/device cache bank.
+
+    ``cfg`` is any object with attributes B, F, H, W, C_lat, C, C_deep, groups, n_res,
+    heads, head_dim, gn_eps. ``weights`` maps names ("conv_in.w", "res0.gn_g", ...,
+    see ``required_weights``) to arrays in PyTorch order ([Cout, Cin, 3, 3] / [Cout, Cin]).
+    """
+
+    def __init__(self, cfg, weights: Weights, dtype=np.float64, host_slots: int = 1, dev_slots: int = 2):
+        self.cfg = cfg
+        self.dtype = np.dtype(dtype)
+        self.w = {k: np.asarray(v, dtype=self.dtype) for k, v in weights.items()}
+        self.frame_chunk = 0
+        self.token_chunk = 0
+        self.dev: List[Optional[np.ndarray]] = [None] * dev_slots
+        self.host: List[Optional[np.ndarray]] = [None] * host_slots
+        c = cfg
+        if c.C % c.groups or c.C_deep % c.groups or (c.C + c.C_deep) % c.groups:
+            raise ValueError("channel counts must be divisible by the number of groups")
+        if c.heads * c.head_dim != c.C:
+            raise ValueError("heads * head_dim must equal C")
+        if c.H % 2 or c.W % 2:
+            raise ValueError("H and W must be even")
+
+    # ---- chunk control --------------------------------------------------------------
+    def set_chunk(self, frame_chunk: int, token_chunk: int) -> None:
+        if frame_chunk < 0 or token_chunk < 0:
+            raise ValueError("chunk sizes must be >= 0")
+        self.frame_chunk, self.token_chunk = frame_chunk, token_chunk
+
+    def _token_chunk(self) -> int:
+        c = self.cfg
+        if self.token_chunk > 0:
+            return self.token_chunk
+        if self.frame_chunk > 0 and self.frame_chunk < c.B * c.F:
+            # same number of (frame, position) rows per pass as a frame chunk has
+            return -(-(self.frame_chunk * c.H * c.W) // (c.B * c.F))
+        return 0
+
+    # ---- blocks ---------------------------------------------------------------------
+    def _gn(self, x, prefix):
+        return group_norm(x, self.w[prefix + ".gn_g"], self.w[prefix + ".gn_b"], self.cfg.groups, self.cfg.gn_eps)
+
+    def res_block(self, h, prefix):
+        """h + conv3x3(SiLU(GN(h)))."""
+        return h + conv3x3(silu(self._gn(h, prefix)), self.w[prefix + ".w"], self.w[prefix + ".b"])
+
+    def _attn_w(self, prefix):
+        w = self.w
+        return (w[prefix + ".wq"], w[prefix + ".wk"], w[prefix + ".wv"], w[prefix + ".wo"], w[prefix + ".bo"])
+
+    def spatial_block(self, h):
+        """Per frame: tokens = spatial positions (t = i*W + j); h += Attn(GN(h)). Queries chunked."""
+        N, C, H, W = h.shape
+        g = self._gn(h, "sattn")
+        out = h.copy()
+        for n in range(N):
+            X = g[n].reshape(C, H * W).T  # [T, C]
+            for t0, t1 in _chunks(H * W, self._token_chunk()):
+                Y = attention(X[t0:t1], X, *self._attn_w("sattn"), self.cfg.heads)  # [tq, C]
+                out[n].reshape(C, H * W)[:, t0:t1] += Y.T
+        return out
+
+    def temporal_block(self, h):
+        """Per batch element and spatial position: tokens = the F frames; h += Attn(GN(h)).
+        GroupNorm statistics are per frame over the whole frame; positions are chunked."""
+        c = self.cfg
+        N, C, H, W = h.shape
+        B, F = c.B, N // c.B
+        g = self._gn(h, "tattn").reshape(B, F, C, H * W)
+        out = h.copy().reshape(B, F, C, H * W)
+        for p0, p1 in _chunks(H * W, self._token_chunk()):
+            X = np.transpose(g[:, :, :, p0:p1], (0, 3, 1, 2))  # [B, positions, F, C]
+            Y = attention(X, X, *self._attn_w("tattn"), c.heads)  # [B, positions, F, C]
+            out[:, :, :, p0:p1] += np.transpose(Y, (0, 2, 3, 1))
+        return out.reshape(N, C, H, W)
+
+    def shallow_down(self, x):
+        """D_m: conv_in, n_res residual blocks, spatial block; per-frame work in frame chunks."""
+        c = self.cfg
+        N = x.shape[0]
+        h = np.empty((N, c.C, c.H, c.W), dtype=self.dtype)
+        for n0, n1 in _chunks(N, self.frame_chunk):
+            t = conv3x3(x[n0:n1], self.w["conv_in.w"], self.w["conv_in.b"])
+            for i in range(c.n_res):
+                t = self.res_block(t, f"res{i}")
+            h[n0:n1] = self.spatial_block(t)
+        return self.temporal_block(h)
+
+    def deep_branch(self, s):
+        """Stand-in for everything below the shallow stage: stride-2 conv then one residual block."""
+        N = s.shape[0]
+        c = self.cfg
+        deep = np.empty((N, c.C_deep, c.H // 2, c.W // 2), dtype=self.dtype)
+        for n0, n1 in _chunks(N, self.frame_chunk):
+            d0 = conv3x3(s[n0:n1], self.w["down.w"], self.w["down.b"], stride=2)
+            deep[n0:n1] = self.res_block(d0, "dres")
+        return deep
+
+    def shallow_up(self, s, deep):
+        """U_m: Concat(skip, up2(deep)) -> GN -> SiLU -> conv3x3 -> GN -> SiLU -> conv_out."""
+        c = self.cfg
+        N = s.shape[0]
+        eps = np.empty((N, c.C_lat, c.H, c.W), dtype=self.dtype)
+        for n0, n1 in _chunks(N, self.frame_chunk):
+            cat = np.concatenate([s[n0:n1], up2(deep[n0:n1])], axis=1)
+            u = conv3x3(silu(self._gn(cat, "up")), self.w["up.w"], self.w["up.b"])
+            eps[n0:n1] = conv3x3(silu(self._gn(u, "out")), self.w["out.w"], self.w["out.b"])
+        return eps
+
+    # ---- steps ----------------------------------------------------------------------
+    def _flat(self, x):
+        c = self.cfg
+        x = np.asarray(x, dtype=self.dtype)
+        assert x.shape == (c.B, c.F, c.C_lat, c.H, c.W), x.shape
+        return x.reshape(c.B * c.F, c.C_lat, c.H, c.W)
+
+    def full_step(self, x, dev_slot: int = 0):
+        """Normal step: recompute everything; the deep feature goes into device slot `dev_slot`."""
+        c = self.cfg
+        s = self.shallow_down(self._flat(x))
+        deep = self.deep_branch(s)
+        self.dev[dev_slot] = deep
+        return self.shallow_up(s, deep).reshape(c.B, c.F, c.C_lat, c.H, c.W)
+
+    def cached_step(self, x, dev_slot: int = 0):
+        """Cache step: only the shallow branch is recomputed; the deep feature is read from the slot."""
+        c = self.cfg
+        if self.dev[dev_slot] is None:
+            raise RuntimeError("cached step on an empty device slot")
+        s = self.shallow_down(self._flat(x))
+        return self.shallow_up(s, self.dev[dev_slot]).reshape(c.B, c.F, c.C_lat, c.H, c.W)
+
+    # ---- cache bank -----------------------------------------------------------------
+    def cache_write(self, dev_slot: int, deep) -> None:
+        c = self.cfg
+        deep = np.asarray(deep, dtype=self.dtype)
+        assert deep.shape == (c.B * c.F, c.C_deep, c.H // 2, c.W // 2)
+        self.dev[dev_slot] = deep.copy()
+
+    def swap_out(self, dev_slot: int, host_slot: int) -> None:
+        if self.dev[dev_slot] is None:
+            raise RuntimeError("swap-out of an empty device slot")
+        buf = np.empty_like(self.dev[dev_slot])
+        np.copyto(buf, self.dev[dev_slot])
+        self.host[host_slot] = buf
+
+    def swap_in(self, host_slot: int, dev_slot: int) -> None:
+        if self.host[host_slot] is None:
+            raise RuntimeError("swap-in from an empty host slot")
+        buf = np.empty_like(self.host[host_slot])
+        np.copyto(buf, self.host[host_slot])
+        self.dev[dev_slot] = buf
+
+
+def required_weights(cfg) -> List[str]:
+    names = ["conv_in.w", "conv_in.b"]
+    for i in range(cfg.n_res):
+        names += [f"res{i}.{k}" for k in ("gn_g", "gn_b", "w", "b")]
+    for blk in ("sattn", "tattn"):
+        names += [f"{blk}.{k}" for k in ("gn_g", "gn_b", "wq", "wk", "wv", "wo", "bo")]
+    names += ["down.w", "down.b", "dres.gn_g", "dres.gn_b", "dres.w", "dres.b",
+              "up.gn_g", "up.gn_b", "up.w", "up.b", "out.gn_g", "out.gn_b", "out.w", "out.b"]
+    return names
+
+
+def run_schedule(oracle: Oracle, x0, steps: int, interval: int, dt: Optional[float] = None):
+    """Denoising loop of the "Asynchronous Swapping" section: a normal step when t is a multiple
+    of `interval`, a cache step otherwise. After each normal step the deep feature is swapped out
+    to host slot (refresh index mod host slots); every cache step reads a device slot that was
+    refilled from the host bank (alternating device slots). The latent update between steps is
+    the fixed rule x <- x - dt * eps (dt = 1/steps), a stand-in for the sampler.
+    Returns (list of x_t fed to each step, list of eps_t)."""
+    dt = 1.0 / steps if dt is None else dt
+    x = np.asarray(x0, dtype=oracle.dtype)
+    xs, outs = [], []
+    refresh = -1
+    n_dev, n_host = len(oracle.dev), len(oracle.host)
+    for t in range(steps):
+        xs.append(x.copy())
+        if t % interval == 0:
+            refresh += 1
+            slot = t % n_dev
+            eps = oracle.full_step(x, slot)
+            oracle.swap_out(slot, refresh % n_host)
+        else:
+            slot = t % n_dev
+            oracle.swap_in(refresh % n_host, slot)
+            eps = oracle.cached_step(x, slot)
+        outs.append(eps)
+        x = x - oracle.dtype.type(dt) * eps
+    return xs, outs

@@ -1,0 +1,167 @@
+"""Seeded synthetic inputs for the cached-step stage of a DeepCache-style video UNet.
+
+This module only *describes shapes and draws random numbers*. It holds none of the
+method's arithmetic (no convolution, normalisation, attention, caching): both the CPU
+oracle's tests and the HIP path's tests import it so that the two sides receive
+bit-identical arrays.
+
+Shapes follow the 5-D feature-map convention of the paper's "Feature chunk" section,
+{batch, frames, channels, height, width}, with batch = 2 standing for the conditional
+and unconditional halves of classifier-free guidance.
+
+Recipe
+------
+* One ``numpy.random.default_rng(seed)`` stream per tensor family (weights / latents /
+  injected deep feature), drawn in the fixed order of :func:`weight_manifest`.
+* Convolution and projection weights and all biases ~ N(0, 0.02).
+* GroupNorm scale = 1 + N(0, 0.02), GroupNorm shift ~ N(0, 0.02) (a literal N(0, 0.02)
+  scale would shrink every activation fifty-fold and make absolute tolerances vacuous).
+* Latents and injected deep features ~ N(0, 1).
+* Everything is drawn as float32. For bf16 workloads the arrays are then rounded once to
+  the nearest bf16-representable value (ties to even) and still *stored* as float32, so
+  that a float64 consumer and a bf16 consumer see exactly the same numbers.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, List, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class StageConfig:
+    """Shape of one shallow UNet stage plus its chunking / schedule parameters."""
+
+    name: str
+    B: int
+    F: int
+    H: int
+    W: int
+    C_lat: int
+    C: int
+    C_deep: int
+    groups: int
+    n_res: int
+    heads: int
+    head_dim: int
+    dtype: str  # "f32" or "bf16"
+    frame_chunk: int = 0  # 0 = unchunked
+    token_chunk: int = 0  # 0 = derived from frame_chunk / unchunked
+    gn_eps: float = 1e-5
+
+    @property
+    def N(self) -> int:  # frames of the flattened (batch, frame) axis
+        return self.B * self.F
+
+    @property
+    def T(self) -> int:  # tokens (spatial positions) per frame
+        return self.H * self.W
+
+    def with_(self, **kw) -> "StageConfig":
+        return replace(self, **kw)
+
+    def cached_step_flops(self) -> float:
+        """Algorithmic FLOPs of one cached step (unpadded head_dim, no recompute)."""
+        N, T, P = self.N, self.T, self.N * self.T
+        C, Cd, Cl = self.C, self.C_deep, self.C_lat
+
+        def conv(ci, co):
+            return 2.0 * 9 * ci * co * P
+
+        f = conv(Cl, C) + self.n_res * conv(C, C)
+        proj = 8.0 * C * C * P
+        f += proj + 4.0 * T * T * self.head_dim * self.heads * N
+        f += proj + 4.0 * self.F * self.F * self.head_dim * self.heads * self.B * T
+        f += conv(C + Cd, C) + conv(C, Cl)
+        return f
+
+
+# The workloads: a tiny fp32 stage, an AnimateDiff-like stage (512x512 video -> 64x64
+# latents, 16 frames), an SVD-XT-like stage (576x1024 -> 72x128 latents, 25 frames) and a
+# stress instance. They are shape-faithful stand-ins for the pretrained models the paper
+# measured, which are not available here.
+CONFIGS: Dict[str, StageConfig] = {
+    "tiny": StageConfig("tiny", B=1, F=8, H=32, W=32, C_lat=4, C=64, C_deep=128, groups=32,
+                        n_res=1, heads=1, head_dim=64, dtype="f32", frame_chunk=2),
+    "animatediff": StageConfig("animatediff", B=2, F=16, H=64, W=64, C_lat=4, C=320, C_deep=640,
+                               groups=32, n_res=2, heads=8, head_dim=40, dtype="bf16",
+                               frame_chunk=4),
+    "svdxt": StageConfig("svdxt", B=2, F=25, H=72, W=128, C_lat=4, C=320, C_deep=640,
+                         groups=32, n_res=2, heads=5, head_dim=64, dtype="bf16",
+                         frame_chunk=5, token_chunk=2304),
+    "stress": StageConfig("stress", B=2, F=32, H=96, W=96, C_lat=4, C=320, C_deep=640,
+                          groups=32, n_res=2, heads=8, head_dim=40, dtype="bf16",
+                          frame_chunk=8),
+}
+
+
+def weight_manifest(cfg: StageConfig) -> List[Tuple[str, Tuple[int, ...], str]]:
+    """(name, shape, kind) in generation order. kind: 'w' weight/bias, 'g' GN scale, 'b' GN shift."""
+    C, Cd, Cl = cfg.C, cfg.C_deep, cfg.C_lat
+    m: List[Tuple[str, Tuple[int, ...], str]] = []
+    m += [("conv_in.w", (C, Cl, 3, 3), "w"), ("conv_in.b", (C,), "w")]
+    for i in range(cfg.n_res):
+        m += [(f"res{i}.gn_g", (C,), "g"), (f"res{i}.gn_b", (C,), "b"),
+              (f"res{i}.w", (C, C, 3, 3), "w"), (f"res{i}.b", (C,), "w")]
+    for blk in ("sattn", "tattn"):
+        m += [(f"{blk}.gn_g", (C,), "g"), (f"{blk}.gn_b", (C,), "b"),
+              (f"{blk}.wq", (C, C), "w"), (f"{blk}.wk", (C, C), "w"),
+              (f"{blk}.wv", (C, C), "w"), (f"{blk}.wo", (C, C), "w"),
+              (f"{blk}.bo", (C,), "w")]
+    m += [("down.w", (Cd, C, 3, 3), "w"), ("down.b", (Cd,), "w")]
+    m += [("dres.gn_g", (Cd,), "g"), ("dres.gn_b", (Cd,), "b"),
+          ("dres.w", (Cd, Cd, 3, 3), "w"), ("dres.b", (Cd,), "w")]
+    m += [("up.gn_g", (C + Cd,), "g"), ("up.gn_b", (C + Cd,), "b"),
+          ("up.w", (C, C + Cd, 3, 3), "w"), ("up.b", (C,), "w")]
+    m += [("out.gn_g", (C,), "g"), ("out.gn_b", (C,), "b"),
+          ("out.w", (Cl, C, 3, 3), "w"), ("out.b", (Cl,), "w")]
+    return m
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bf16-representable float32 (ties to even)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    u = (u + 0x7FFF + lsb) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def _finish(a: np.ndarray, cfg: StageConfig) -> np.ndarray:
+    a = a.astype(np.float32)
+    return round_to_bf16(a) if cfg.dtype == "bf16" else a
+
+
+def make_weights(cfg: StageConfig, seed: int = 0, sharp: float = 1.0) -> Dict[str, np.ndarray]:
+    """Draw every weight of the stage. ``sharp`` multiplies the query/key projections so that
+    attention logits get a standard deviation well above 1 (a peaked softmax)."""
+    rng = np.random.default_rng(seed)
+    out: Dict[str, np.ndarray] = {}
+    for name, shape, kind in weight_manifest(cfg):
+        a = rng.standard_normal(shape, dtype=np.float32) * np.float32(0.02)
+        if kind == "g":
+            a = a + np.float32(1.0)
+        if sharp != 1.0 and (name.endswith(".wq") or name.endswith(".wk")):
+            a = a * np.float32(sharp)
+        out[name] = _finish(a, cfg)
+    return out
+
+
+def make_latents(cfg: StageConfig, seed: int = 1) -> np.ndarray:
+    """Noisy latents x, shape [B, F, C_lat, H, W], ~N(0,1)."""
+    rng = np.random.default_rng(seed)
+    return _finish(rng.standard_normal((cfg.B, cfg.F, cfg.C_lat, cfg.H, cfg.W), dtype=np.float32), cfg)
+
+
+def make_deep(cfg: StageConfig, seed: int = 2) -> np.ndarray:
+    """A stand-in cached deep feature, shape [B*F, C_deep, H/2, W/2], ~N(0,1)."""
+    rng = np.random.default_rng(seed)
+    return _finish(rng.standard_normal((cfg.N, cfg.C_deep, cfg.H // 2, cfg.W // 2), dtype=np.float32), cfg)
+
+
+def make_activation(shape, seed: int, dtype: str = "f32", scale: float = 1.0) -> np.ndarray:
+    """A generic ~N(0, scale^2) activation tensor for single-operator tests."""
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal(shape, dtype=np.float32) * np.float32(scale)
+    return round_to_bf16(a) if dtype == "bf16" else a

@@ -1,0 +1,116 @@
+"""A deliberately naive scalar evaluator of the stage, written straight from the operator
+definitions with Python loops and Python floats (double precision). It exists only to pin
+the numpy oracle on tiny inputs; it shares nothing with it."""
+import math
+
+
+def zeros(*shape):
+    if len(shape) == 1:
+        return [0.0] * shape[0]
+    return [zeros(*shape[1:]) for _ in range(shape[0])]
+
+
+def conv3x3(x, w, b, stride=1):
+    N, Cin, H, W = len(x), len(x[0]), len(x[0][0]), len(x[0][0][0])
+    Cout = len(w)
+    Ho, Wo = H // stride, W // stride
+    y = zeros(N, Cout, Ho, Wo)
+    for n in range(N):
+        for o in range(Cout):
+            for i in range(Ho):
+                for j in range(Wo):
+                    acc = b[o]
+                    for c in range(Cin):
+                        for a in range(3):
+                            for e in range(3):
+                                ii = stride * i + a - 1
+                                jj = stride * j + e - 1
+                                if 0 <= ii < H and 0 <= jj < W:
+                                    acc += w[o][c][a][e] * x[n][c][ii][jj]
+                    y[n][o][i][j] = acc
+    return y
+
+
+def group_norm_silu(x, gamma, beta, G, eps, act=True):
+    N, C, H, W = len(x), len(x[0]), len(x[0][0]), len(x[0][0][0])
+    cg = C // G
+    y = zeros(N, C, H, W)
+    for n in range(N):
+        for g in range(G):
+            vals = [x[n][c][i][j] for c in range(g * cg, (g + 1) * cg) for i in range(H) for j in range(W)]
+            mu = sum(vals) / len(vals)
+            var = sum((v - mu) ** 2 for v in vals) / len(vals)
+            r = 1.0 / math.sqrt(var + eps)
+            for c in range(g * cg, (g + 1) * cg):
+                for i in range(H):
+                    for j in range(W):
+                        t = (x[n][c][i][j] - mu) * r * gamma[c] + beta[c]
+                        y[n][c][i][j] = t / (1.0 + math.exp(-t)) if act else t
+    return y
+
+
+def attn_rows(X, wq, wk, wv, wo, bo, heads):
+    """X: list of L rows of C floats -> list of L rows of C floats."""
+    L, C = len(X), len(X[0])
+    d = C // heads
+
+    def lin(row, w):
+        return [sum(w[o][c] * row[c] for c in range(C)) for o in range(C)]
+
+    Q = [lin(r, wq) for r in X]
+    K = [lin(r, wk) for r in X]
+    V = [lin(r, wv) for r in X]
+    O = zeros(L, C)
+    for hd in range(heads):
+        for i in range(L):
+            s = [sum(Q[i][hd * d + k] * K[j][hd * d + k] for k in range(d)) / math.sqrt(d) for j in range(L)]
+            m = max(s)
+            e = [math.exp(v - m) for v in s]
+            z = sum(e)
+            for k in range(d):
+                O[i][hd * d + k] = sum(e[j] / z * V[j][hd * d + k] for j in range(L))
+    return [[bo[o] + sum(wo[o][c] * O[i][c] for c in range(C)) for o in range(C)] for i in range(L)]
+
+
+def stage(cfg, w, x, deep_in=None):
+    """x: nested list [N][C_lat][H][W]. Returns (eps, deep). If deep_in is given it is used
+    (cached step) instead of running the deep branch (full step)."""
+    N, H, W, C, G = cfg.B * cfg.F, cfg.H, cfg.W, cfg.C, cfg.groups
+    h = conv3x3(x, w["conv_in.w"], w["conv_in.b"])
+    for r in range(cfg.n_res):
+        t = conv3x3(group_norm_silu(h, w[f"res{r}.gn_g"], w[f"res{r}.gn_b"], G, cfg.gn_eps),
+                    w[f"res{r}.w"], w[f"res{r}.b"])
+        h = [[[[h[n][c][i][j] + t[n][c][i][j] for j in range(W)] for i in range(H)] for c in range(C)] for n in range(N)]
+    # spatial attention: tokens are positions of one frame
+    g = group_norm_silu(h, w["sattn.gn_g"], w["sattn.gn_b"], G, cfg.gn_eps, act=False)
+    for n in range(N):
+        X = [[g[n][c][i][j] for c in range(C)] for i in range(H) for j in range(W)]
+        Y = attn_rows(X, w["sattn.wq"], w["sattn.wk"], w["sattn.wv"], w["sattn.wo"], w["sattn.bo"], cfg.heads)
+        for i in range(H):
+            for j in range(W):
+                for c in range(C):
+                    h[n][c][i][j] += Y[i * W + j][c]
+    # temporal attention: tokens are the frames of one (batch, position)
+    g = group_norm_silu(h, w["tattn.gn_g"], w["tattn.gn_b"], G, cfg.gn_eps, act=False)
+    for bb in range(cfg.B):
+        for i in range(H):
+            for j in range(W):
+                X = [[g[bb * cfg.F + f][c][i][j] for c in range(C)] for f in range(cfg.F)]
+                Y = attn_rows(X, w["tattn.wq"], w["tattn.wk"], w["tattn.wv"], w["tattn.wo"], w["tattn.bo"], cfg.heads)
+                for f in range(cfg.F):
+                    for c in range(C):
+                        h[bb * cfg.F + f][c][i][j] += Y[f][c]
+    if deep_in is None:
+        d0 = conv3x3(h, w["down.w"], w["down.b"], stride=2)
+        t = conv3x3(group_norm_silu(d0, w["dres.gn_g"], w["dres.gn_b"], G, cfg.gn_eps), w["dres.w"], w["dres.b"])
+        Cd = cfg.C_deep
+        deep = [[[[d0[n][c][i][j] + t[n][c][i][j] for j in range(W // 2)] for i in range(H // 2)]
+                 for c in range(Cd)] for n in range(N)]
+    else:
+        deep = deep_in
+    cat = [[h[n][c] for c in range(C)] +
+           [[[deep[n][c][i // 2][j // 2] for j in range(W)] for i in range(H)] for c in range(cfg.C_deep)]
+           for n in range(N)]
+    u = conv3x3(group_norm_silu(cat, w["up.gn_g"], w["up.gn_b"], G, cfg.gn_eps), w["up.w"], w["up.b"])
+    eps = conv3x3(group_norm_silu(u, w["out.gn_g"], w["out.gn_b"], G, cfg.gn_eps), w["out.w"], w["out.b"])
+    return eps, deep
