@@ -1,0 +1,226 @@
+/*
+ * lightcache.h - C ABI of the MI355X (gfx950) library for the cache-hit denoising step of a
+ * DeepCache-style video UNet with asynchronous cache swapping and feature chunking.
+ *
+ * Method references are to the LightCache paper (arXiv 2510.05367):
+ *   [FC]   "Feature Calculation" paragraph, eq. U_i = Concat(D_i, U_{i+1})
+ *   [AS]   "Asynchronous Swapping" section (DeepCache cache equation, refresh interval n,
+ *          cached features kept on the CPU and brought back in the background)
+ *   [CHK]  "Feature chunk and Sliced Decoding" section, eq. Chunk(F)
+ *
+ * Conventions
+ *   - Every pointer argument is annotated [device] or [host]. Device pointers must be valid on
+ *     the GPU that was current when lc_create() was called.
+ *   - Public tensors use the paper's order [B, F, C, H, W] ([CHK]); B*F is written N. Elements
+ *     are lc_config.dtype (float, or bf16 stored as uint16).
+ *   - Every function returns lc_status; on error no output argument is written and a message is
+ *     available from lc_last_error(). Nothing aborts or throws across this boundary.
+ *   - Step and swap calls only *enqueue* work (on the compute stream and the side stream given
+ *     to lc_create) and return; lc_sync() drains both. Ordering between a step and a swap that
+ *     touch the same device slot is enforced inside the library with events.
+ *   - After lc_set_workspace() no call allocates or frees device memory.
+ */
+#ifndef LIGHTCACHE_H
+#define LIGHTCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lc_ctx lc_ctx; /* opaque; owned by the library */
+
+typedef enum {
+  LC_OK = 0,
+  LC_ERR_ARG = 1,   /* NULL pointer, slot out of range, negative chunk, bad enum */
+  LC_ERR_SHAPE = 2, /* configuration the kernels do not support */
+  LC_ERR_STATE = 3, /* call order: empty slot, weights / workspace not set */
+  LC_ERR_NOMEM = 4, /* workspace too small, host allocation failed */
+  LC_ERR_HIP = 5    /* a HIP runtime call failed */
+} lc_status;
+
+typedef enum { LC_F32 = 0, LC_BF16 = 1 } lc_dtype;
+
+/* Shape of the shallow stage. Requirements (else LC_ERR_SHAPE): all > 0; H, W even;
+ * C, C_deep multiples of 64; C, C_deep and C + C_deep divisible by groups; heads * head_dim == C;
+ * head_dim a multiple of 8 and <= 64; C_lat <= 16; n_res <= LC_MAX_RES; 1 <= dev_slots <= 8;
+ * 0 <= host_slots <= 64. */
+typedef struct lc_config {
+  int32_t B, F, H, W;      /* batch (2 with classifier-free guidance), frames, latent size */
+  int32_t C_lat, C, C_deep; /* latent channels, stage channels, deep-feature channels (at H/2 x W/2) */
+  int32_t groups, n_res;   /* GroupNorm groups; residual blocks on the down side */
+  int32_t heads, head_dim;
+  int32_t dtype;           /* lc_dtype: storage type of activations, weights, x, eps, cache */
+  float gn_eps;
+  int32_t host_slots;      /* entries of the pinned host cache bank */
+  int32_t dev_slots;       /* device buffers for deep features (2 = double buffered) */
+} lc_config;
+
+#define LC_MAX_RES 4
+
+/* Weights, all [device], element type lc_config.dtype, PyTorch layouts:
+ * conv w [Cout, Cin, 3, 3], linear w [Cout, Cin], vectors [C]. The library makes packed private
+ * copies during lc_load_weights(); the caller's buffers may be freed afterwards. */
+typedef struct lc_gnconv_w { const void *gn_g, *gn_b, *w, *b; } lc_gnconv_w;
+typedef struct lc_attn_w { const void *gn_g, *gn_b, *wq, *wk, *wv, *wo, *bo; } lc_attn_w;
+typedef struct lc_weights {
+  const void *conv_in_w, *conv_in_b; /* C_lat -> C */
+  lc_gnconv_w res[LC_MAX_RES];       /* GN(C) -> SiLU -> conv C -> C, + identity */
+  lc_attn_w sattn, tattn;            /* spatial / temporal self-attention blocks */
+  const void *down_w, *down_b;       /* deep stand-in: stride-2 conv C -> C_deep */
+  lc_gnconv_w dres;                  /* deep stand-in: residual block at C_deep */
+  lc_gnconv_w up;                    /* GN(C + C_deep) -> SiLU -> conv (C + C_deep) -> C */
+  lc_gnconv_w out;                   /* GN(C) -> SiLU -> conv C -> C_lat */
+} lc_weights;
+
+/* Counters since lc_create (or the last lc_reset_stats). Times are GPU times from events. */
+typedef struct lc_stats {
+  int64_t full_steps, cached_steps, swaps_out, swaps_in;
+  int64_t bytes_out, bytes_in;      /* bytes moved device->host / host->device */
+  double ms_out, ms_in;             /* summed copy durations (completed copies only) */
+  size_t workspace_bytes;           /* arena bytes in use for the current chunk setting */
+  size_t weight_bytes;              /* device bytes of the packed private weight copies */
+  size_t host_bank_bytes;           /* pinned host bytes */
+} lc_stats;
+
+/* Kernel families for per-kernel timing (lc_set_profiling / lc_get_profile). */
+enum {
+  LC_K_CONV_IN = 0, LC_K_GN_STATS, LC_K_GN_FINAL, LC_K_GN_APPLY, LC_K_CONV_RES, LC_K_QKV,
+  LC_K_SATTN, LC_K_TATTN, LC_K_PROJ, LC_K_CAT_APPLY, LC_K_CONV_UP, LC_K_CONV_OUT, LC_K_DEEP,
+  LC_K_COUNT
+};
+typedef struct lc_profile { double ms[LC_K_COUNT]; int64_t launches[LC_K_COUNT]; } lc_profile;
+
+/* ---- host-only helpers (no GPU needed) ------------------------------------------------- */
+
+/* Validates a configuration against the requirements above. cfg: [host]. */
+lc_status lc_check_config(const lc_config* cfg);
+
+/* Bytes of one cache entry (deep feature [N, C_deep, H/2, W/2]); 0 if cfg is invalid. */
+size_t lc_cache_entry_bytes(const lc_config* cfg);
+
+/* Footprint model: arena bytes lc_set_workspace() needs for the given chunk setting (persistent
+ * skip feature + dev_slots cache entries + chunk-sized scratch). frame_chunk / token_chunk as in
+ * lc_set_chunk(). Returns 0 if cfg is invalid or a chunk is negative. */
+size_t lc_workspace_bytes(const lc_config* cfg, int frame_chunk, int token_chunk);
+
+/* Message of the most recent error on this ctx (ctx == NULL: of the calling thread's last
+ * ctx-less call). Never NULL; valid until the next call on the same ctx / thread. */
+const char* lc_last_error(const lc_ctx* ctx);
+
+/* ---- lifetime -------------------------------------------------------------------------- */
+
+/* Creates a context on the current device. compute_stream / side_stream: hipStream_t handles
+ * owned by the caller (e.g. torch.cuda.Stream().cuda_stream), default priority, distinct, must
+ * outlive the ctx. Allocates the pinned host bank (host_slots entries). */
+lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_stream, lc_ctx** out);
+
+/* Drains both streams and frees everything the library owns. NULL is a no-op. */
+lc_status lc_destroy(lc_ctx* ctx);
+
+/* Packs the weights into private device copies (allocates; synchronises the compute stream). */
+lc_status lc_load_weights(lc_ctx* ctx, const lc_weights* w /* [host] struct of [device] ptrs */);
+
+/* Hands the library a caller-owned arena ([device], 256-byte aligned, >= lc_workspace_bytes for
+ * the current chunk setting, else LC_ERR_NOMEM). Cache slots become empty. The arena must stay
+ * valid until lc_destroy or the next lc_set_workspace. */
+lc_status lc_set_workspace(lc_ctx* ctx, void* arena, size_t bytes);
+
+/* ---- the method ------------------------------------------------------------------------ */
+
+/* Feature chunk ([CHK]). frame_chunk = frames of the flattened B*F axis processed per pass by
+ * the per-frame operators; token_chunk = spatial positions per pass of temporal attention and
+ * query tokens per pass of spatial attention. 0 = unchunked; values above the axis length clamp;
+ * a chunk that does not divide the axis gives a short last pass. If token_chunk == 0 and
+ * frame_chunk > 0, temporal attention uses ceil(frame_chunk * H*W / (B*F)) positions per pass
+ * (as many rows as a frame chunk). Chunking never changes results (each output is reduced in the
+ * same order). LC_ERR_NOMEM if a workspace is set and is too small for the new setting. */
+lc_status lc_set_chunk(lc_ctx* ctx, int frame_chunk, int token_chunk);
+
+/* Normal step ([AS]: the steps t = 0, n, 2n, ...): shallow down branch, deep stand-in, shallow
+ * up branch on Concat(skip, deep) ([FC]); the deep feature is left in device slot dev_slot.
+ * x [device, B,F,C_lat,H,W] -> eps [device, same shape]. Both must stay valid until the compute
+ * stream has been synchronised. */
+lc_status lc_full_step(lc_ctx* ctx, const void* x, void* eps, int dev_slot);
+
+/* Cache step ([AS]): only the shallow branch is recomputed; the deep feature is read from device
+ * slot dev_slot (filled by lc_full_step, lc_swap_in or lc_cache_write; LC_ERR_STATE if empty).
+ * If a swap-in into that slot is in flight the step waits for it on the GPU, just before the up
+ * branch. */
+lc_status lc_cached_step(lc_ctx* ctx, const void* x, void* eps, int dev_slot);
+
+/* Asynchronous cache swapping ([AS]). Both enqueue one copy on the side stream and return.
+ * swap_out: device slot -> host bank entry, after the work that produced the slot.
+ * swap_in : host bank entry -> device slot, after the last enqueued step that reads the slot.
+ * LC_ERR_STATE on an empty source. */
+lc_status lc_swap_out(lc_ctx* ctx, int dev_slot, int host_slot);
+lc_status lc_swap_in(lc_ctx* ctx, int host_slot, int dev_slot);
+
+/* Blocks the host until both streams are idle. */
+lc_status lc_sync(lc_ctx* ctx);
+
+/* ---- cache access for tests and for injecting a deep feature ---------------------------- */
+
+/* Fills device slot from / copies it to a tensor in public layout [N, C_deep, H/2, W/2]
+ * ([device], cfg dtype), on the compute stream. The slot's internal layout is private. */
+lc_status lc_cache_write(lc_ctx* ctx, int dev_slot, const void* deep);
+lc_status lc_cache_read(lc_ctx* ctx, int dev_slot, void* deep);
+
+/* Raw views for byte-exact checks (no copy, no sync): *ptr [host] for a bank entry, [device]
+ * for a slot; *bytes = lc_cache_entry_bytes. */
+lc_status lc_cache_peek(lc_ctx* ctx, int host_slot, const void** ptr, size_t* bytes);
+lc_status lc_cache_dev_peek(lc_ctx* ctx, int dev_slot, const void** ptr, size_t* bytes);
+
+/* ---- measurement ------------------------------------------------------------------------ */
+
+lc_status lc_get_stats(lc_ctx* ctx, lc_stats* out /* [host] */); /* synchronises the side stream */
+lc_status lc_reset_stats(lc_ctx* ctx);
+
+/* mask: bit k set = bracket every launch of kernel family k (LC_K_*) with events on the compute
+ * stream. lc_get_profile() synchronises, sums the brackets into out and clears them. At most
+ * 16384 brackets are kept between two lc_get_profile calls; further launches are not timed. */
+lc_status lc_set_profiling(lc_ctx* ctx, uint32_t mask);
+lc_status lc_get_profile(lc_ctx* ctx, lc_profile* out /* [host] */);
+
+/* ---- single operators (the same kernels the steps launch; used by the parity tests and the
+ *      benchmark). Activations are in the library's internal channels-last layout
+ *      [rows, channels] with rows = frame-major pixels; all pointers [device], cfg dtype.
+ *      Each call enqueues on the compute stream. `frames` counts frames of H x W pixels
+ *      (H/2 x W/2 where stated). -------------------------------------------------------------- */
+
+typedef enum {
+  LC_L_RES0 = 0, /* .. LC_L_RES0 + n_res - 1 */
+  LC_L_SATTN = 8, LC_L_TATTN = 9, LC_L_DRES = 10, LC_L_UP = 11, LC_L_OUT = 12, LC_L_DOWN = 13
+} lc_layer;
+
+/* y = [SiLU](GroupNorm(x)) with the scale/shift of `layer`; channels = that layer's input width
+ * (C, or C_deep at H/2 x W/2 for LC_L_DRES). */
+lc_status lc_op_group_norm(lc_ctx* ctx, int layer, const void* x, void* y, int frames, int silu);
+/* y = [res +] conv3x3(x) + bias of `layer` (LC_L_RESi, LC_L_DRES at H/2 x W/2, LC_L_UP with
+ * C + C_deep input channels, LC_L_DOWN stride 2: x at H x W -> y at H/2 x W/2). res may be NULL
+ * or equal to y. */
+lc_status lc_op_conv3x3(lc_ctx* ctx, int layer, const void* x, const void* res, void* y, int frames);
+/* qkv[rows, 3C] = x[rows, C] [Wq;Wk;Wv]^T of LC_L_SATTN / LC_L_TATTN. */
+lc_status lc_op_qkv(lc_ctx* ctx, int layer, const void* x, void* qkv, int64_t rows);
+/* y[rows, C] = res + a[rows, C] Wo^T + bo of LC_L_SATTN / LC_L_TATTN. res may equal y. */
+lc_status lc_op_proj(lc_ctx* ctx, int layer, const void* a, const void* res, void* y, int64_t rows);
+/* Spatial attention core: per frame and head, softmax(QK^T/sqrt(d))V over the H*W tokens of the
+ * frame, for query tokens [q0, q1). qkv [frames*H*W, 3C] -> out [frames*H*W, C]. */
+lc_status lc_op_spatial_attention(lc_ctx* ctx, const void* qkv, void* out, int frames, int q0, int q1);
+/* Temporal attention core: qkv [(B*F) * positions, 3C] (frame-major) -> out [(B*F)*positions, C];
+ * per batch element, position and head attention over the F frames. */
+lc_status lc_op_temporal_attention(lc_ctx* ctx, const void* qkv, void* out, int positions);
+/* h[frames*H*W, C] = conv_in(x[frames, C_lat, H, W]). */
+lc_status lc_op_conv_in(lc_ctx* ctx, const void* x, void* h, int frames);
+/* catn[frames*H*W, C + C_deep] = SiLU(GN_up(Concat(skip, up2(deep)))) ([FC]); deep is
+ * [frames*(H/2)*(W/2), C_deep] channels-last. */
+lc_status lc_op_concat_norm(lc_ctx* ctx, const void* skip, const void* deep, void* catn, int frames);
+/* eps[frames, C_lat, H, W] = conv_out(SiLU(GN_out(u))), u [frames*H*W, C]. */
+lc_status lc_op_conv_out(lc_ctx* ctx, const void* u, void* eps, int frames);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIGHTCACHE_H */

@@ -1,0 +1,868 @@
+// Host side of the C ABI declared in include/lightcache.h: configuration checks, the arena plan
+// (footprint model), packed weights, the step driver with its chunk loops, and the cache bank
+// (pinned host entries, device slots, side-stream copies ordered by events).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/lightcache.h"
+#include "lc_internal.h"
+
+using namespace lc;
+
+namespace {
+
+thread_local std::string g_err = "";
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+  int fc, tc, qc;  // effective frame chunk, temporal position chunk, spatial query chunk
+  size_t off_h, off_slots, slot_bytes, off_partH, off_partD, off_scale, off_shift, off_ws, ws_bytes, total;
+};
+
+struct GnW { float *gamma, *beta; };
+struct ConvW { void* w; float* b; };
+struct AttnW { GnW gn; void* wqkv; void* wo; float* bo; };
+struct Packed {
+  float* cin_w; float* cin_b;
+  GnW res_gn[LC_MAX_RES]; ConvW res[LC_MAX_RES];
+  AttnW sattn, tattn;
+  ConvW down; GnW dres_gn; ConvW dres;
+  GnW up_gn; ConvW up; GnW out_gn; ConvW out;
+};
+
+struct EvPair { hipEvent_t a, b; int kind; int64_t bytes; };
+
+}  // namespace
+
+struct lc_ctx {
+  lc_config cfg;
+  hipStream_t cs, ss;
+  int device;
+  int frame_chunk, token_chunk;
+  Plan plan;
+  char* arena;
+  size_t arena_bytes;
+  bool have_weights;
+  void* wblob;
+  size_t wblob_bytes;
+  Packed pw;
+  // cache bank
+  std::vector<void*> host;
+  std::vector<char> host_filled, dev_filled;
+  std::vector<hipEvent_t> ev_produced, ev_consumed, ev_in_done, ev_rd_done, ev_out_done;
+  std::vector<char> in_pending;
+  // stats
+  lc_stats st;
+  std::vector<EvPair> copy_pool, copy_pending;
+  // profiling
+  uint32_t prof_mask;
+  std::vector<EvPair> prof_pool;
+  size_t prof_used;
+  std::string err;
+};
+
+namespace {
+
+lc_status fail(lc_ctx* c, lc_status code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_err = buf;
+  return code;
+}
+
+#define LC_HIP(c, expr)                                                                          \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess) return fail(c, LC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+
+lc_status check_cfg(lc_ctx* c, const lc_config* g) {
+  if (!g) return fail(c, LC_ERR_ARG, "config is NULL");
+  if (g->dtype != LC_F32 && g->dtype != LC_BF16) return fail(c, LC_ERR_ARG, "dtype must be LC_F32 or LC_BF16");
+  if (g->B <= 0 || g->F <= 0 || g->H <= 0 || g->W <= 0 || g->C_lat <= 0 || g->C <= 0 || g->C_deep <= 0 ||
+      g->groups <= 0 || g->n_res < 0 || g->heads <= 0 || g->head_dim <= 0)
+    return fail(c, LC_ERR_SHAPE, "all sizes must be positive");
+  if (g->H % 2 || g->W % 2) return fail(c, LC_ERR_SHAPE, "H and W must be even (deep feature is at H/2 x W/2)");
+  if (g->C % 64 || g->C_deep % 64) return fail(c, LC_ERR_SHAPE, "C and C_deep must be multiples of 64");
+  if (g->C > 1024 || g->C_deep > 1024) return fail(c, LC_ERR_SHAPE, "C and C_deep must be <= 1024");
+  if (g->C % g->groups || g->C_deep % g->groups || (g->C + g->C_deep) % g->groups)
+    return fail(c, LC_ERR_SHAPE, "C, C_deep and C + C_deep must be divisible by groups");
+  if (g->groups > 256) return fail(c, LC_ERR_SHAPE, "groups must be <= 256");
+  if (g->heads * g->head_dim != g->C) return fail(c, LC_ERR_SHAPE, "heads * head_dim must equal C");
+  const int d = g->head_dim;
+  if (!(d == 8 || d == 16 || d == 32 || d == 40 || d == 64))
+    return fail(c, LC_ERR_SHAPE, "head_dim must be one of 8, 16, 32, 40, 64");
+  if (g->C_lat > 16) return fail(c, LC_ERR_SHAPE, "C_lat must be <= 16");
+  if (g->n_res > LC_MAX_RES) return fail(c, LC_ERR_SHAPE, "n_res must be <= %d", LC_MAX_RES);
+  if (g->dev_slots < 1 || g->dev_slots > 8) return fail(c, LC_ERR_SHAPE, "dev_slots must be in [1, 8]");
+  if (g->host_slots < 0 || g->host_slots > 64) return fail(c, LC_ERR_SHAPE, "host_slots must be in [0, 64]");
+  if (!(g->gn_eps > 0.f)) return fail(c, LC_ERR_SHAPE, "gn_eps must be positive");
+  if ((int64_t)g->B * g->F * g->H * g->W > (int64_t)1 << 28) return fail(c, LC_ERR_SHAPE, "too many pixels");
+  return LC_OK;
+}
+
+Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
+  Plan p;
+  const int64_t N = (int64_t)g.B * g.F, T = (int64_t)g.H * g.W;
+  const size_t es = dtype_size(g.dtype);
+  p.fc = (frame_chunk <= 0 || frame_chunk > N) ? (int)N : frame_chunk;
+  if (token_chunk > 0) p.tc = (int)std::min<int64_t>(token_chunk, T);
+  else if (p.fc < N) p.tc = (int)(((int64_t)p.fc * T + N - 1) / N);
+  else p.tc = (int)T;
+  p.qc = token_chunk > 0 ? (int)std::min<int64_t>(token_chunk, T) : (int)T;
+  size_t off = 0;
+  p.off_h = off; off += align_up((size_t)(N * T * g.C) * es);
+  p.slot_bytes = align_up((size_t)(N * (T / 4) * g.C_deep) * es);
+  p.off_slots = off; off += p.slot_bytes * g.dev_slots;
+  // partH also serves the half-resolution GroupNorm of the deep stand-in
+  const size_t ph = std::max((size_t)stat_splits((int)T) * g.C, (size_t)stat_splits((int)(T / 4)) * g.C_deep);
+  p.off_partH = off; off += align_up((size_t)N * ph * 2 * sizeof(float));
+  p.off_partD = off; off += align_up((size_t)N * stat_splits((int)(T / 4)) * g.C_deep * 2 * sizeof(float));
+  p.off_scale = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
+  p.off_shift = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
+  const int64_t pc = (int64_t)p.fc * T;   // pixels of a frame chunk
+  const int64_t rt = N * p.tc;            // rows of a temporal pass
+  int64_t elems = 4 * g.C * std::max(pc, rt);                       // tn + qkv
+  elems = std::max(elems, pc * (2 * (int64_t)g.C + g.C_deep));      // catn + u
+  elems = std::max(elems, 2 * (pc / 4) * (int64_t)g.C_deep);        // deep stand-in: d0 + dn
+  p.ws_bytes = align_up((size_t)elems * es) + kAlign;
+  p.off_ws = off; off += p.ws_bytes;
+  p.total = off;
+  return p;
+}
+
+struct Prof {
+  lc_ctx* c; int kind; bool on; size_t idx;
+  Prof(lc_ctx* c_, int k) : c(c_), kind(k), on(false), idx(0) {
+    if ((c->prof_mask >> k) & 1u) {
+      if (c->prof_used < c->prof_pool.size()) {
+        idx = c->prof_used++;
+        c->prof_pool[idx].kind = k;
+        on = hipEventRecord(c->prof_pool[idx].a, c->cs) == hipSuccess;
+      }
+    }
+  }
+  ~Prof() { if (on) (void)hipEventRecord(c->prof_pool[idx].b, c->cs); }
+};
+
+#define LC_LAUNCH(c, kind, expr)                                                                  \
+  do {                                                                                            \
+    hipError_t e_;                                                                                \
+    { Prof pr_(c, kind); e_ = (expr); }                                                           \
+    if (e_ != hipSuccess) return fail(c, LC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));     \
+  } while (0)
+
+inline char* slot_ptr(lc_ctx* c, int s) { return c->arena + c->plan.off_slots + c->plan.slot_bytes * s; }
+inline char* h_ptr(lc_ctx* c) { return c->arena + c->plan.off_h; }
+inline float* partH(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partH); }
+inline float* partD(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partD); }
+inline float* scale_p(lc_ctx* c) { return (float*)(c->arena + c->plan.off_scale); }
+inline float* shift_p(lc_ctx* c) { return (float*)(c->arena + c->plan.off_shift); }
+inline char* ws_ptr(lc_ctx* c) { return c->arena + c->plan.off_ws; }
+
+RowMap dense_map() { return RowMap{0, 0, 1 << 30}; }
+
+// GroupNorm statistics of `frames` contiguous frames of [rows_per_frame, C] -> scale/shift (first
+// `frames` entries of the scale/shift scratch).
+lc_status gn_scale_shift(lc_ctx* c, const void* x, int frames, int rows_per_frame, int C, const GnW& w) {
+  const lc_config& g = c->cfg;
+  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, x, partH(c), frames, rows_per_frame, C));
+  LC_LAUNCH(c, LC_K_GN_FINAL,
+            launch_gn_finalize(c->cs, partH(c), C, stat_splits(rows_per_frame), rows_per_frame, 1.f, nullptr, 0, 0,
+                               0, 0.f, w.gamma, w.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), frames));
+  return LC_OK;
+}
+
+lc_status gn_full(lc_ctx* c, const void* x, int frames, int rows_per_frame, int C, const GnW& w, void* y, int silu) {
+  lc_status s = gn_scale_shift(c, x, frames, rows_per_frame, C, w);
+  if (s != LC_OK) return s;
+  RowMap m{0, 0, rows_per_frame};
+  m.seg_stride = rows_per_frame;  // dense frames: segment f starts at f * rows_per_frame
+  LC_LAUNCH(c, LC_K_GN_APPLY, launch_gn_apply(c->cs, c->cfg.dtype, x, m, y, (int64_t)frames * rows_per_frame, C,
+                                              scale_p(c), shift_p(c), silu));
+  return LC_OK;
+}
+
+ConvDesc conv_desc(const lc_config& g, const ConvW& w, int Cin, int Cout, int frames, int H, int W, int stride,
+                   const void* x, const void* res, void* y) {
+  ConvDesc d;
+  memset(&d, 0, sizeof d);
+  d.dt = g.dtype; d.taps = 9; d.stride = stride; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
+  d.w = w.w; d.bias = w.b; d.frames = frames; d.H = H; d.W = W; d.x = x; d.res = res; d.y = y;
+  d.out_map = dense_map();
+  return d;
+}
+
+ConvDesc linear_desc(const lc_config& g, const void* w, const float* bias, int Cin, int Cout, int64_t rows,
+                     RowMap out_map, const void* x, const void* res, void* y) {
+  ConvDesc d;
+  memset(&d, 0, sizeof d);
+  d.dt = g.dtype; d.taps = 1; d.stride = 1; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
+  d.w = w; d.bias = bias; d.rows = rows; d.out_map = out_map; d.x = x; d.res = res; d.y = y;
+  return d;
+}
+
+lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
+  const lc_config& g = c->cfg;
+  const Plan& p = c->plan;
+  const int N = g.B * g.F, T = g.H * g.W, C = g.C, Cd = g.C_deep;
+  const size_t es = dtype_size(g.dtype);
+  char* h = h_ptr(c);
+  char* ws = ws_ptr(c);
+  const Packed& w = c->pw;
+
+  // ---- shallow down branch D_m, per frame chunk
+  for (int n0 = 0; n0 < N; n0 += p.fc) {
+    const int nf = std::min(p.fc, N - n0);
+    const int64_t pc = (int64_t)nf * T;
+    char* hc = h + (size_t)n0 * T * C * es;
+    char* tn = ws;
+    char* qkv = ws + (size_t)pc * C * es;
+    LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, (const char*)x + (size_t)n0 * g.C_lat * T * es, hc, nf,
+                                              g.H, g.W, g.C_lat, C, w.cin_w, w.cin_b));
+    for (int i = 0; i < g.n_res; ++i) {
+      lc_status s = gn_full(c, hc, nf, T, C, w.res_gn[i], tn, 1);
+      if (s != LC_OK) return s;
+      LC_LAUNCH(c, LC_K_CONV_RES, launch_conv(c->cs, conv_desc(g, w.res[i], C, C, nf, g.H, g.W, 1, tn, hc, hc)));
+    }
+    lc_status s = gn_full(c, hc, nf, T, C, w.sattn.gn, tn, 0);
+    if (s != LC_OK) return s;
+    LC_LAUNCH(c, LC_K_QKV,
+              launch_conv(c->cs, linear_desc(g, w.sattn.wqkv, nullptr, C, 3 * C, pc, dense_map(), tn, nullptr, qkv)));
+    for (int q0 = 0; q0 < T; q0 += p.qc)
+      LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, tn, nf, T, g.heads, g.head_dim, q0,
+                                                        std::min(q0 + p.qc, T)));
+    LC_LAUNCH(c, LC_K_PROJ,
+              launch_conv(c->cs, linear_desc(g, w.sattn.wo, w.sattn.bo, C, C, pc, dense_map(), tn, hc, hc)));
+  }
+
+  // ---- temporal block: per-frame statistics over whole frames, then per position chunk
+  {
+    lc_status s = gn_scale_shift(c, h, N, T, C, w.tattn.gn);
+    if (s != LC_OK) return s;
+    for (int p0 = 0; p0 < T; p0 += p.tc) {
+      const int np = std::min(p.tc, T - p0);
+      const int64_t rows = (int64_t)N * np;
+      RowMap m{p0, T, np};
+      char* tn = ws;
+      char* qkv = ws + (size_t)rows * C * es;
+      LC_LAUNCH(c, LC_K_GN_APPLY, launch_gn_apply(c->cs, g.dtype, h, m, tn, rows, C, scale_p(c), shift_p(c), 0));
+      LC_LAUNCH(c, LC_K_QKV,
+                launch_conv(c->cs, linear_desc(g, w.tattn.wqkv, nullptr, C, 3 * C, rows, dense_map(), tn, nullptr, qkv)));
+      LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, tn, g.B, g.F, np, g.heads, g.head_dim));
+      LC_LAUNCH(c, LC_K_PROJ, launch_conv(c->cs, linear_desc(g, w.tattn.wo, w.tattn.bo, C, C, rows, m, tn, h, h)));
+    }
+  }
+
+  char* deep = slot_ptr(c, slot);
+  if (full) {
+    // the slot may still be the source of a swap-out or the target of a swap-in on the side stream
+    LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_rd_done[slot], 0));
+    LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
+    c->in_pending[slot] = 0;
+    for (int n0 = 0; n0 < N; n0 += p.fc) {
+      const int nf = std::min(p.fc, N - n0);
+      const int64_t pq = (int64_t)nf * (T / 4);
+      char* hc = h + (size_t)n0 * T * C * es;
+      char* d0 = ws;
+      char* dn = ws + (size_t)pq * Cd * es;
+      char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
+      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, conv_desc(g, w.down, C, Cd, nf, g.H, g.W, 2, hc, nullptr, d0)));
+      lc_status s = gn_full(c, d0, nf, T / 4, Cd, w.dres_gn, dn, 1);
+      if (s != LC_OK) return s;
+      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, conv_desc(g, w.dres, Cd, Cd, nf, g.H / 2, g.W / 2, 1, dn, d0, dc)));
+    }
+    LC_HIP(c, hipEventRecord(c->ev_produced[slot], c->cs));
+    c->dev_filled[slot] = 1;
+  } else if (c->in_pending[slot]) {
+    LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
+    c->in_pending[slot] = 0;
+  }
+
+  // ---- shallow up branch U_m on Concat(skip, up2(deep)), per frame chunk
+  for (int n0 = 0; n0 < N; n0 += p.fc) {
+    const int nf = std::min(p.fc, N - n0);
+    const int64_t pc = (int64_t)nf * T;
+    char* hc = h + (size_t)n0 * T * C * es;
+    char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
+    char* catn = ws;
+    char* u = ws + (size_t)pc * (C + Cd) * es;
+    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, hc, partH(c), nf, T, C));
+    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, dc, partD(c), nf, T / 4, Cd));
+    LC_LAUNCH(c, LC_K_GN_FINAL,
+              launch_gn_finalize(c->cs, partH(c), C, stat_splits(T), T, 1.f, partD(c), Cd, stat_splits(T / 4), T / 4,
+                                 4.f, w.up_gn.gamma, w.up_gn.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), nf));
+    LC_LAUNCH(c, LC_K_CAT_APPLY,
+              launch_concat_apply(c->cs, g.dtype, hc, dc, catn, nf, g.H, g.W, C, Cd, scale_p(c), shift_p(c)));
+    LC_LAUNCH(c, LC_K_CONV_UP, launch_conv(c->cs, conv_desc(g, w.up, C + Cd, C, nf, g.H, g.W, 1, catn, nullptr, u)));
+    lc_status s = gn_full(c, u, nf, T, C, w.out_gn, catn, 1);
+    if (s != LC_OK) return s;
+    ConvDesc d = conv_desc(g, w.out, C, 16, nf, g.H, g.W, 1, catn, nullptr,
+                           (char*)eps + (size_t)n0 * g.C_lat * T * es);
+    d.Cout_store = g.C_lat;
+    d.planar_out = 1;
+    LC_LAUNCH(c, LC_K_CONV_OUT, launch_conv(c->cs, d));
+  }
+  LC_HIP(c, hipEventRecord(c->ev_consumed[slot], c->cs));
+  return LC_OK;
+}
+
+lc_status step_checks(lc_ctx* c, const void* x, void* eps, int slot) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!x || !eps) return fail(c, LC_ERR_ARG, "x and eps must not be NULL");
+  if (slot < 0 || slot >= c->cfg.dev_slots) return fail(c, LC_ERR_ARG, "device slot %d out of range", slot);
+  if (!c->have_weights) return fail(c, LC_ERR_STATE, "weights not loaded");
+  if (!c->arena) return fail(c, LC_ERR_STATE, "workspace not set");
+  return LC_OK;
+}
+
+lc_status op_checks(lc_ctx* c, int frames) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!c->have_weights) return fail(c, LC_ERR_STATE, "weights not loaded");
+  if (!c->arena) return fail(c, LC_ERR_STATE, "workspace not set");
+  if (frames <= 0 || frames > c->cfg.B * c->cfg.F) return fail(c, LC_ERR_ARG, "frames out of range");
+  return LC_OK;
+}
+
+bool layer_gn(lc_ctx* c, int layer, GnW* gn, int* Cn, int* rows_div) {
+  const lc_config& g = c->cfg;
+  *rows_div = 1;
+  *Cn = g.C;
+  if (layer >= LC_L_RES0 && layer < LC_L_RES0 + g.n_res) { *gn = c->pw.res_gn[layer]; return true; }
+  switch (layer) {
+    case LC_L_SATTN: *gn = c->pw.sattn.gn; return true;
+    case LC_L_TATTN: *gn = c->pw.tattn.gn; return true;
+    case LC_L_OUT: *gn = c->pw.out_gn; return true;
+    case LC_L_DRES: *gn = c->pw.dres_gn; *Cn = g.C_deep; *rows_div = 4; return true;
+    default: return false;
+  }
+}
+
+}  // namespace
+
+// =================================================================================================
+extern "C" {
+
+const char* lc_last_error(const lc_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+lc_status lc_check_config(const lc_config* cfg) { return check_cfg(nullptr, cfg); }
+
+size_t lc_cache_entry_bytes(const lc_config* cfg) {
+  if (check_cfg(nullptr, cfg) != LC_OK) return 0;
+  return (size_t)cfg->B * cfg->F * (cfg->H / 2) * (cfg->W / 2) * cfg->C_deep * dtype_size(cfg->dtype);
+}
+
+size_t lc_workspace_bytes(const lc_config* cfg, int frame_chunk, int token_chunk) {
+  if (check_cfg(nullptr, cfg) != LC_OK) return 0;
+  if (frame_chunk < 0 || token_chunk < 0) { g_err = "chunk sizes must be >= 0"; return 0; }
+  return make_plan(*cfg, frame_chunk, token_chunk).total;
+}
+
+lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_stream, lc_ctx** out) {
+  if (!out) return fail(nullptr, LC_ERR_ARG, "out is NULL");
+  lc_status s = check_cfg(nullptr, cfg);
+  if (s != LC_OK) return s;
+  if (!compute_stream || !side_stream || compute_stream == side_stream)
+    return fail(nullptr, LC_ERR_ARG, "compute and side streams must be two distinct non-default streams");
+  int dev = 0;
+  LC_HIP(nullptr, hipGetDevice(&dev));
+  lc_ctx* c = new (std::nothrow) lc_ctx();
+  if (!c) return fail(nullptr, LC_ERR_NOMEM, "out of host memory");
+  c->cfg = *cfg;
+  c->cs = (hipStream_t)compute_stream;
+  c->ss = (hipStream_t)side_stream;
+  c->device = dev;
+  c->frame_chunk = c->token_chunk = 0;
+  c->plan = make_plan(c->cfg, 0, 0);
+  c->arena = nullptr; c->arena_bytes = 0;
+  c->have_weights = false; c->wblob = nullptr; c->wblob_bytes = 0;
+  memset(&c->pw, 0, sizeof c->pw);
+  memset(&c->st, 0, sizeof c->st);
+  c->prof_mask = 0; c->prof_used = 0;
+  const size_t entry = lc_cache_entry_bytes(cfg);
+  auto bail = [&](lc_status code, const char* what, hipError_t e) {
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    lc_destroy(c);
+    return code;
+  };
+  for (int i = 0; i < cfg->host_slots; ++i) {
+    void* p = nullptr;
+    hipError_t e = hipHostMalloc(&p, entry, hipHostMallocDefault);
+    if (e != hipSuccess) return bail(LC_ERR_NOMEM, "hipHostMalloc (pinned cache bank)", e);
+    c->host.push_back(p);
+  }
+  c->host_filled.assign(cfg->host_slots, 0);
+  c->dev_filled.assign(cfg->dev_slots, 0);
+  c->in_pending.assign(cfg->dev_slots, 0);
+  auto mk = [&](std::vector<hipEvent_t>& v, int n, unsigned flags) -> hipError_t {
+    for (int i = 0; i < n; ++i) {
+      hipEvent_t e;
+      hipError_t r = hipEventCreateWithFlags(&e, flags);
+      if (r != hipSuccess) return r;
+      v.push_back(e);
+    }
+    return hipSuccess;
+  };
+  hipError_t e;
+  if ((e = mk(c->ev_produced, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
+      (e = mk(c->ev_consumed, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
+      (e = mk(c->ev_in_done, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
+      (e = mk(c->ev_rd_done, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
+      (e = mk(c->ev_out_done, cfg->host_slots, hipEventDisableTiming)) != hipSuccess)
+    return bail(LC_ERR_HIP, "hipEventCreate", e);
+  for (int i = 0; i < 256; ++i) {
+    EvPair pr{};
+    if ((e = hipEventCreate(&pr.a)) != hipSuccess) return bail(LC_ERR_HIP, "hipEventCreate", e);
+    if ((e = hipEventCreate(&pr.b)) != hipSuccess) { (void)hipEventDestroy(pr.a); return bail(LC_ERR_HIP, "hipEventCreate", e); }
+    c->copy_pool.push_back(pr);
+  }
+  c->st.host_bank_bytes = entry * cfg->host_slots;
+  *out = c;
+  return LC_OK;
+}
+
+lc_status lc_destroy(lc_ctx* c) {
+  if (!c) return LC_OK;
+  (void)hipStreamSynchronize(c->cs);
+  (void)hipStreamSynchronize(c->ss);
+  for (void* p : c->host) (void)hipHostFree(p);
+  for (auto* v : {&c->ev_produced, &c->ev_consumed, &c->ev_in_done, &c->ev_rd_done, &c->ev_out_done})
+    for (hipEvent_t e : *v) (void)hipEventDestroy(e);
+  for (auto* v : {&c->copy_pool, &c->copy_pending, &c->prof_pool})
+    for (EvPair& pr : *v) { (void)hipEventDestroy(pr.a); (void)hipEventDestroy(pr.b); }
+  if (c->wblob) (void)hipFree(c->wblob);
+  delete c;
+  return LC_OK;
+}
+
+lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!w) return fail(c, LC_ERR_ARG, "weights is NULL");
+  const lc_config& g = c->cfg;
+  const int C = g.C, Cd = g.C_deep, Cl = g.C_lat, dt = g.dtype;
+  const size_t es = dtype_size(dt);
+  // every pointer the configuration uses must be present
+  auto need_gc = [](const lc_gnconv_w& x) { return x.gn_g && x.gn_b && x.w && x.b; };
+  auto need_at = [](const lc_attn_w& x) { return x.gn_g && x.gn_b && x.wq && x.wk && x.wv && x.wo && x.bo; };
+  bool ok = w->conv_in_w && w->conv_in_b && need_at(w->sattn) && need_at(w->tattn) && w->down_w && w->down_b &&
+            need_gc(w->dres) && need_gc(w->up) && need_gc(w->out);
+  for (int i = 0; i < g.n_res; ++i) ok = ok && need_gc(w->res[i]);
+  if (!ok) return fail(c, LC_ERR_ARG, "a weight pointer is NULL");
+
+  // ---- layout of the private blob
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  const size_t o_cin_w = take((size_t)Cl * 9 * C * 4), o_cin_b = take((size_t)C * 4);
+  size_t o_res_g[LC_MAX_RES], o_res_b[LC_MAX_RES], o_res_w[LC_MAX_RES], o_res_bias[LC_MAX_RES];
+  for (int i = 0; i < g.n_res; ++i) {
+    o_res_g[i] = take((size_t)C * 4); o_res_b[i] = take((size_t)C * 4);
+    o_res_w[i] = take((size_t)C * 9 * C * es); o_res_bias[i] = take((size_t)C * 4);
+  }
+  size_t o_at[2][5];
+  for (int k = 0; k < 2; ++k) {
+    o_at[k][0] = take((size_t)C * 4); o_at[k][1] = take((size_t)C * 4);
+    o_at[k][2] = take((size_t)3 * C * C * es); o_at[k][3] = take((size_t)C * C * es); o_at[k][4] = take((size_t)C * 4);
+  }
+  const size_t o_down_w = take((size_t)Cd * 9 * C * es), o_down_b = take((size_t)Cd * 4);
+  const size_t o_dres_g = take((size_t)Cd * 4), o_dres_b = take((size_t)Cd * 4);
+  const size_t o_dres_w = take((size_t)Cd * 9 * Cd * es), o_dres_bias = take((size_t)Cd * 4);
+  const size_t o_up_g = take((size_t)(C + Cd) * 4), o_up_b = take((size_t)(C + Cd) * 4);
+  const size_t o_up_w = take((size_t)C * 9 * (C + Cd) * es), o_up_bias = take((size_t)C * 4);
+  const size_t o_out_g = take((size_t)C * 4), o_out_b = take((size_t)C * 4);
+  const size_t o_out_w = take((size_t)16 * 9 * C * es), o_out_bias = take((size_t)16 * 4);
+
+  LC_HIP(c, hipStreamSynchronize(c->cs));
+  if (c->wblob) { LC_HIP(c, hipFree(c->wblob)); c->wblob = nullptr; c->have_weights = false; }
+  void* blob = nullptr;
+  if (hipMalloc(&blob, off) != hipSuccess) return fail(c, LC_ERR_NOMEM, "hipMalloc of %zu bytes for packed weights failed", off);
+  c->wblob = blob; c->wblob_bytes = off;
+  char* b = (char*)blob;
+  Packed& p = c->pw;
+  hipStream_t s = c->cs;
+#define F32(src, dst_off, n, npad) LC_HIP(c, launch_to_f32(s, dt, src, (float*)(b + dst_off), n, npad))
+#define CW(src, dst_off, co, ci, taps, copad) LC_HIP(c, launch_pack_conv_w(s, dt, src, b + dst_off, co, ci, taps, copad))
+  LC_HIP(c, launch_pack_conv_in_w(s, dt, w->conv_in_w, (float*)(b + o_cin_w), C, Cl));
+  F32(w->conv_in_b, o_cin_b, C, C);
+  p.cin_w = (float*)(b + o_cin_w); p.cin_b = (float*)(b + o_cin_b);
+  for (int i = 0; i < g.n_res; ++i) {
+    F32(w->res[i].gn_g, o_res_g[i], C, C); F32(w->res[i].gn_b, o_res_b[i], C, C);
+    CW(w->res[i].w, o_res_w[i], C, C, 9, C); F32(w->res[i].b, o_res_bias[i], C, C);
+    p.res_gn[i] = GnW{(float*)(b + o_res_g[i]), (float*)(b + o_res_b[i])};
+    p.res[i] = ConvW{b + o_res_w[i], (float*)(b + o_res_bias[i])};
+  }
+  const lc_attn_w* aw[2] = {&w->sattn, &w->tattn};
+  AttnW* ap[2] = {&p.sattn, &p.tattn};
+  for (int k = 0; k < 2; ++k) {
+    F32(aw[k]->gn_g, o_at[k][0], C, C); F32(aw[k]->gn_b, o_at[k][1], C, C);
+    // rows [0,C) = Wq, [C,2C) = Wk, [2C,3C) = Wv; linear weights are already [Cout][Cin]
+    LC_HIP(c, launch_copy_rows(s, dt, aw[k]->wq, b + o_at[k][2], (int64_t)C * C));
+    LC_HIP(c, launch_copy_rows(s, dt, aw[k]->wk, b + o_at[k][2] + (size_t)C * C * es, (int64_t)C * C));
+    LC_HIP(c, launch_copy_rows(s, dt, aw[k]->wv, b + o_at[k][2] + (size_t)2 * C * C * es, (int64_t)C * C));
+    LC_HIP(c, launch_copy_rows(s, dt, aw[k]->wo, b + o_at[k][3], (int64_t)C * C));
+    F32(aw[k]->bo, o_at[k][4], C, C);
+    *ap[k] = AttnW{GnW{(float*)(b + o_at[k][0]), (float*)(b + o_at[k][1])}, b + o_at[k][2], b + o_at[k][3],
+                   (float*)(b + o_at[k][4])};
+  }
+  CW(w->down_w, o_down_w, Cd, C, 9, Cd); F32(w->down_b, o_down_b, Cd, Cd);
+  p.down = ConvW{b + o_down_w, (float*)(b + o_down_b)};
+  F32(w->dres.gn_g, o_dres_g, Cd, Cd); F32(w->dres.gn_b, o_dres_b, Cd, Cd);
+  CW(w->dres.w, o_dres_w, Cd, Cd, 9, Cd); F32(w->dres.b, o_dres_bias, Cd, Cd);
+  p.dres_gn = GnW{(float*)(b + o_dres_g), (float*)(b + o_dres_b)};
+  p.dres = ConvW{b + o_dres_w, (float*)(b + o_dres_bias)};
+  F32(w->up.gn_g, o_up_g, C + Cd, C + Cd); F32(w->up.gn_b, o_up_b, C + Cd, C + Cd);
+  CW(w->up.w, o_up_w, C, C + Cd, 9, C); F32(w->up.b, o_up_bias, C, C);
+  p.up_gn = GnW{(float*)(b + o_up_g), (float*)(b + o_up_b)};
+  p.up = ConvW{b + o_up_w, (float*)(b + o_up_bias)};
+  F32(w->out.gn_g, o_out_g, C, C); F32(w->out.gn_b, o_out_b, C, C);
+  CW(w->out.w, o_out_w, Cl, C, 9, 16); F32(w->out.b, o_out_bias, Cl, 16);
+  p.out_gn = GnW{(float*)(b + o_out_g), (float*)(b + o_out_b)};
+  p.out = ConvW{b + o_out_w, (float*)(b + o_out_bias)};
+#undef F32
+#undef CW
+  LC_HIP(c, hipStreamSynchronize(s));
+  c->have_weights = true;
+  c->st.weight_bytes = off;
+  return LC_OK;
+}
+
+lc_status lc_set_workspace(lc_ctx* c, void* arena, size_t bytes) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!arena) return fail(c, LC_ERR_ARG, "arena is NULL");
+  if ((uintptr_t)arena % kAlign) return fail(c, LC_ERR_ARG, "arena must be 256-byte aligned");
+  if (bytes < c->plan.total)
+    return fail(c, LC_ERR_NOMEM, "workspace of %zu bytes is smaller than the %zu needed", bytes, c->plan.total);
+  LC_HIP(c, hipStreamSynchronize(c->cs));
+  LC_HIP(c, hipStreamSynchronize(c->ss));
+  c->arena = (char*)arena;
+  c->arena_bytes = bytes;
+  std::fill(c->dev_filled.begin(), c->dev_filled.end(), 0);
+  std::fill(c->in_pending.begin(), c->in_pending.end(), 0);
+  c->st.workspace_bytes = c->plan.total;
+  return LC_OK;
+}
+
+lc_status lc_set_chunk(lc_ctx* c, int frame_chunk, int token_chunk) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (frame_chunk < 0 || token_chunk < 0) return fail(c, LC_ERR_ARG, "chunk sizes must be >= 0");
+  Plan np = make_plan(c->cfg, frame_chunk, token_chunk);
+  if (c->arena && np.total > c->arena_bytes)
+    return fail(c, LC_ERR_NOMEM, "chunk setting needs %zu bytes, workspace has %zu", np.total, c->arena_bytes);
+  // the persistent regions (skip feature, cache slots) sit at chunk-independent offsets, so a
+  // filled slot stays valid across a chunk change
+  c->frame_chunk = frame_chunk;
+  c->token_chunk = token_chunk;
+  c->plan = np;
+  c->st.workspace_bytes = np.total;
+  return LC_OK;
+}
+
+lc_status lc_full_step(lc_ctx* c, const void* x, void* eps, int dev_slot) {
+  lc_status s = step_checks(c, x, eps, dev_slot);
+  if (s != LC_OK) return s;
+  s = run_step(c, x, eps, dev_slot, true);
+  if (s == LC_OK) c->st.full_steps++;
+  return s;
+}
+
+lc_status lc_cached_step(lc_ctx* c, const void* x, void* eps, int dev_slot) {
+  lc_status s = step_checks(c, x, eps, dev_slot);
+  if (s != LC_OK) return s;
+  if (!c->dev_filled[dev_slot]) return fail(c, LC_ERR_STATE, "cached step on empty device slot %d", dev_slot);
+  s = run_step(c, x, eps, dev_slot, false);
+  if (s == LC_OK) c->st.cached_steps++;
+  return s;
+}
+
+static lc_status swap_common(lc_ctx* c, int dev_slot, int host_slot) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (dev_slot < 0 || dev_slot >= c->cfg.dev_slots) return fail(c, LC_ERR_ARG, "device slot %d out of range", dev_slot);
+  if (host_slot < 0 || host_slot >= c->cfg.host_slots) return fail(c, LC_ERR_ARG, "host slot %d out of range", host_slot);
+  if (!c->arena) return fail(c, LC_ERR_STATE, "workspace not set");
+  return LC_OK;
+}
+
+static EvPair* take_copy_pair(lc_ctx* c) {
+  if (c->copy_pool.empty()) return nullptr;
+  c->copy_pending.push_back(c->copy_pool.back());
+  c->copy_pool.pop_back();
+  return &c->copy_pending.back();
+}
+
+lc_status lc_swap_out(lc_ctx* c, int dev_slot, int host_slot) {
+  lc_status s = swap_common(c, dev_slot, host_slot);
+  if (s != LC_OK) return s;
+  if (!c->dev_filled[dev_slot]) return fail(c, LC_ERR_STATE, "swap-out of empty device slot %d", dev_slot);
+  const size_t bytes = lc_cache_entry_bytes(&c->cfg);
+  LC_HIP(c, hipStreamWaitEvent(c->ss, c->ev_produced[dev_slot], 0));
+  EvPair* pr = take_copy_pair(c);
+  if (pr) { pr->kind = 0; pr->bytes = (int64_t)bytes; LC_HIP(c, hipEventRecord(pr->a, c->ss)); }
+  LC_HIP(c, hipMemcpyAsync(c->host[host_slot], slot_ptr(c, dev_slot), bytes, hipMemcpyDeviceToHost, c->ss));
+  if (pr) LC_HIP(c, hipEventRecord(pr->b, c->ss));
+  LC_HIP(c, hipEventRecord(c->ev_rd_done[dev_slot], c->ss));
+  LC_HIP(c, hipEventRecord(c->ev_out_done[host_slot], c->ss));
+  c->host_filled[host_slot] = 1;
+  c->st.swaps_out++;
+  c->st.bytes_out += (int64_t)bytes;
+  return LC_OK;
+}
+
+lc_status lc_swap_in(lc_ctx* c, int host_slot, int dev_slot) {
+  lc_status s = swap_common(c, dev_slot, host_slot);
+  if (s != LC_OK) return s;
+  if (!c->host_filled[host_slot]) return fail(c, LC_ERR_STATE, "swap-in from empty host slot %d", host_slot);
+  const size_t bytes = lc_cache_entry_bytes(&c->cfg);
+  // after the last enqueued reader / writer of the device slot on the compute stream
+  LC_HIP(c, hipStreamWaitEvent(c->ss, c->ev_consumed[dev_slot], 0));
+  LC_HIP(c, hipStreamWaitEvent(c->ss, c->ev_produced[dev_slot], 0));
+  EvPair* pr = take_copy_pair(c);
+  if (pr) { pr->kind = 1; pr->bytes = (int64_t)bytes; LC_HIP(c, hipEventRecord(pr->a, c->ss)); }
+  LC_HIP(c, hipMemcpyAsync(slot_ptr(c, dev_slot), c->host[host_slot], bytes, hipMemcpyHostToDevice, c->ss));
+  if (pr) LC_HIP(c, hipEventRecord(pr->b, c->ss));
+  LC_HIP(c, hipEventRecord(c->ev_in_done[dev_slot], c->ss));
+  c->in_pending[dev_slot] = 1;
+  c->dev_filled[dev_slot] = 1;
+  c->st.swaps_in++;
+  c->st.bytes_in += (int64_t)bytes;
+  return LC_OK;
+}
+
+lc_status lc_sync(lc_ctx* c) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  LC_HIP(c, hipStreamSynchronize(c->cs));
+  LC_HIP(c, hipStreamSynchronize(c->ss));
+  return LC_OK;
+}
+
+lc_status lc_cache_write(lc_ctx* c, int dev_slot, const void* deep) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!deep) return fail(c, LC_ERR_ARG, "deep is NULL");
+  if (dev_slot < 0 || dev_slot >= c->cfg.dev_slots) return fail(c, LC_ERR_ARG, "device slot %d out of range", dev_slot);
+  if (!c->arena) return fail(c, LC_ERR_STATE, "workspace not set");
+  const lc_config& g = c->cfg;
+  LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_rd_done[dev_slot], 0));
+  LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[dev_slot], 0));
+  c->in_pending[dev_slot] = 0;
+  LC_HIP(c, launch_planar_to_cl(c->cs, g.dtype, deep, slot_ptr(c, dev_slot), g.B * g.F, g.C_deep, (g.H / 2) * (g.W / 2)));
+  LC_HIP(c, hipEventRecord(c->ev_produced[dev_slot], c->cs));
+  c->dev_filled[dev_slot] = 1;
+  return LC_OK;
+}
+
+lc_status lc_cache_read(lc_ctx* c, int dev_slot, void* deep) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!deep) return fail(c, LC_ERR_ARG, "deep is NULL");
+  if (dev_slot < 0 || dev_slot >= c->cfg.dev_slots) return fail(c, LC_ERR_ARG, "device slot %d out of range", dev_slot);
+  if (!c->arena) return fail(c, LC_ERR_STATE, "workspace not set");
+  if (!c->dev_filled[dev_slot]) return fail(c, LC_ERR_STATE, "device slot %d is empty", dev_slot);
+  const lc_config& g = c->cfg;
+  if (c->in_pending[dev_slot]) {
+    LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[dev_slot], 0));
+    c->in_pending[dev_slot] = 0;
+  }
+  LC_HIP(c, launch_cl_to_planar(c->cs, g.dtype, slot_ptr(c, dev_slot), deep, g.B * g.F, g.C_deep, (g.H / 2) * (g.W / 2)));
+  LC_HIP(c, hipEventRecord(c->ev_consumed[dev_slot], c->cs));
+  return LC_OK;
+}
+
+lc_status lc_cache_peek(lc_ctx* c, int host_slot, const void** ptr, size_t* bytes) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!ptr || !bytes) return fail(c, LC_ERR_ARG, "output pointer is NULL");
+  if (host_slot < 0 || host_slot >= c->cfg.host_slots) return fail(c, LC_ERR_ARG, "host slot %d out of range", host_slot);
+  if (!c->host_filled[host_slot]) return fail(c, LC_ERR_STATE, "host slot %d is empty", host_slot);
+  *ptr = c->host[host_slot];
+  *bytes = lc_cache_entry_bytes(&c->cfg);
+  return LC_OK;
+}
+
+lc_status lc_cache_dev_peek(lc_ctx* c, int dev_slot, const void** ptr, size_t* bytes) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!ptr || !bytes) return fail(c, LC_ERR_ARG, "output pointer is NULL");
+  if (dev_slot < 0 || dev_slot >= c->cfg.dev_slots) return fail(c, LC_ERR_ARG, "device slot %d out of range", dev_slot);
+  if (!c->arena) return fail(c, LC_ERR_STATE, "workspace not set");
+  if (!c->dev_filled[dev_slot]) return fail(c, LC_ERR_STATE, "device slot %d is empty", dev_slot);
+  *ptr = slot_ptr(c, dev_slot);
+  *bytes = lc_cache_entry_bytes(&c->cfg);
+  return LC_OK;
+}
+
+lc_status lc_get_stats(lc_ctx* c, lc_stats* out) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!out) return fail(c, LC_ERR_ARG, "out is NULL");
+  LC_HIP(c, hipStreamSynchronize(c->ss));
+  for (EvPair& pr : c->copy_pending) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, pr.a, pr.b) == hipSuccess) (pr.kind == 0 ? c->st.ms_out : c->st.ms_in) += ms;
+    c->copy_pool.push_back(pr);
+  }
+  c->copy_pending.clear();
+  *out = c->st;
+  return LC_OK;
+}
+
+lc_status lc_reset_stats(lc_ctx* c) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  lc_stats tmp;
+  lc_status s = lc_get_stats(c, &tmp);
+  if (s != LC_OK) return s;
+  const size_t ws = c->st.workspace_bytes, wb = c->st.weight_bytes, hb = c->st.host_bank_bytes;
+  memset(&c->st, 0, sizeof c->st);
+  c->st.workspace_bytes = ws; c->st.weight_bytes = wb; c->st.host_bank_bytes = hb;
+  return LC_OK;
+}
+
+lc_status lc_set_profiling(lc_ctx* c, uint32_t mask) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (mask && c->prof_pool.empty()) {
+    for (int i = 0; i < 4096; ++i) {
+      EvPair pr{};
+      LC_HIP(c, hipEventCreate(&pr.a));
+      hipError_t e = hipEventCreate(&pr.b);
+      if (e != hipSuccess) { (void)hipEventDestroy(pr.a); return fail(c, LC_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e)); }
+      c->prof_pool.push_back(pr);
+    }
+  }
+  c->prof_mask = mask;
+  return LC_OK;
+}
+
+lc_status lc_get_profile(lc_ctx* c, lc_profile* out) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!out) return fail(c, LC_ERR_ARG, "out is NULL");
+  LC_HIP(c, hipStreamSynchronize(c->cs));
+  lc_profile pf;
+  memset(&pf, 0, sizeof pf);
+  for (size_t i = 0; i < c->prof_used; ++i) {
+    float ms = 0.f;
+    const EvPair& pr = c->prof_pool[i];
+    if (hipEventElapsedTime(&ms, pr.a, pr.b) == hipSuccess) {
+      pf.ms[pr.kind] += ms;
+      pf.launches[pr.kind]++;
+    }
+  }
+  c->prof_used = 0;
+  *out = pf;
+  return LC_OK;
+}
+
+// ---- single operators -------------------------------------------------------------------------
+
+lc_status lc_op_group_norm(lc_ctx* c, int layer, const void* x, void* y, int frames, int silu) {
+  lc_status s = op_checks(c, frames);
+  if (s != LC_OK) return s;
+  if (!x || !y) return fail(c, LC_ERR_ARG, "NULL tensor");
+  GnW gn; int Cn, div;
+  if (!layer_gn(c, layer, &gn, &Cn, &div)) return fail(c, LC_ERR_ARG, "layer %d has no plain GroupNorm", layer);
+  return gn_full(c, x, frames, c->cfg.H * c->cfg.W / div, Cn, gn, y, silu);
+}
+
+lc_status lc_op_conv3x3(lc_ctx* c, int layer, const void* x, const void* res, void* y, int frames) {
+  lc_status s = op_checks(c, frames);
+  if (s != LC_OK) return s;
+  if (!x || !y) return fail(c, LC_ERR_ARG, "NULL tensor");
+  const lc_config& g = c->cfg;
+  ConvDesc d;
+  if (layer >= LC_L_RES0 && layer < LC_L_RES0 + g.n_res) d = conv_desc(g, c->pw.res[layer], g.C, g.C, frames, g.H, g.W, 1, x, res, y);
+  else if (layer == LC_L_DRES) d = conv_desc(g, c->pw.dres, g.C_deep, g.C_deep, frames, g.H / 2, g.W / 2, 1, x, res, y);
+  else if (layer == LC_L_UP) d = conv_desc(g, c->pw.up, g.C + g.C_deep, g.C, frames, g.H, g.W, 1, x, res, y);
+  else if (layer == LC_L_DOWN) d = conv_desc(g, c->pw.down, g.C, g.C_deep, frames, g.H, g.W, 2, x, res, y);
+  else return fail(c, LC_ERR_ARG, "layer %d is not a 3x3 convolution", layer);
+  const int kind = layer == LC_L_UP ? LC_K_CONV_UP : (layer == LC_L_DOWN || layer == LC_L_DRES) ? LC_K_DEEP : LC_K_CONV_RES;
+  LC_LAUNCH(c, kind, launch_conv(c->cs, d));
+  return LC_OK;
+}
+
+lc_status lc_op_qkv(lc_ctx* c, int layer, const void* x, void* qkv, int64_t rows) {
+  lc_status s = op_checks(c, 1);
+  if (s != LC_OK) return s;
+  if (!x || !qkv || rows <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
+  if (layer != LC_L_SATTN && layer != LC_L_TATTN) return fail(c, LC_ERR_ARG, "layer %d is not an attention block", layer);
+  const AttnW& a = layer == LC_L_SATTN ? c->pw.sattn : c->pw.tattn;
+  LC_LAUNCH(c, LC_K_QKV, launch_conv(c->cs, linear_desc(c->cfg, a.wqkv, nullptr, c->cfg.C, 3 * c->cfg.C, rows, dense_map(), x, nullptr, qkv)));
+  return LC_OK;
+}
+
+lc_status lc_op_proj(lc_ctx* c, int layer, const void* a_in, const void* res, void* y, int64_t rows) {
+  lc_status s = op_checks(c, 1);
+  if (s != LC_OK) return s;
+  if (!a_in || !y || rows <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
+  if (layer != LC_L_SATTN && layer != LC_L_TATTN) return fail(c, LC_ERR_ARG, "layer %d is not an attention block", layer);
+  const AttnW& a = layer == LC_L_SATTN ? c->pw.sattn : c->pw.tattn;
+  LC_LAUNCH(c, LC_K_PROJ, launch_conv(c->cs, linear_desc(c->cfg, a.wo, a.bo, c->cfg.C, c->cfg.C, rows, dense_map(), a_in, res, y)));
+  return LC_OK;
+}
+
+lc_status lc_op_spatial_attention(lc_ctx* c, const void* qkv, void* out, int frames, int q0, int q1) {
+  lc_status s = op_checks(c, frames);
+  if (s != LC_OK) return s;
+  if (!qkv || !out) return fail(c, LC_ERR_ARG, "NULL tensor");
+  const lc_config& g = c->cfg;
+  if (q0 < 0 || q1 > g.H * g.W || q0 >= q1) return fail(c, LC_ERR_ARG, "query range out of bounds");
+  LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, out, frames, g.H * g.W, g.heads, g.head_dim, q0, q1));
+  return LC_OK;
+}
+
+lc_status lc_op_temporal_attention(lc_ctx* c, const void* qkv, void* out, int positions) {
+  lc_status s = op_checks(c, 1);
+  if (s != LC_OK) return s;
+  if (!qkv || !out || positions <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
+  const lc_config& g = c->cfg;
+  LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, out, g.B, g.F, positions, g.heads, g.head_dim));
+  return LC_OK;
+}
+
+lc_status lc_op_conv_in(lc_ctx* c, const void* x, void* h, int frames) {
+  lc_status s = op_checks(c, frames);
+  if (s != LC_OK) return s;
+  if (!x || !h) return fail(c, LC_ERR_ARG, "NULL tensor");
+  const lc_config& g = c->cfg;
+  LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, x, h, frames, g.H, g.W, g.C_lat, g.C, c->pw.cin_w, c->pw.cin_b));
+  return LC_OK;
+}
+
+lc_status lc_op_concat_norm(lc_ctx* c, const void* skip, const void* deep, void* catn, int frames) {
+  lc_status s = op_checks(c, frames);
+  if (s != LC_OK) return s;
+  if (!skip || !deep || !catn) return fail(c, LC_ERR_ARG, "NULL tensor");
+  const lc_config& g = c->cfg;
+  const int T = g.H * g.W, C = g.C, Cd = g.C_deep;
+  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, skip, partH(c), frames, T, C));
+  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, deep, partD(c), frames, T / 4, Cd));
+  LC_LAUNCH(c, LC_K_GN_FINAL,
+            launch_gn_finalize(c->cs, partH(c), C, stat_splits(T), T, 1.f, partD(c), Cd, stat_splits(T / 4), T / 4, 4.f,
+                               c->pw.up_gn.gamma, c->pw.up_gn.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), frames));
+  LC_LAUNCH(c, LC_K_CAT_APPLY, launch_concat_apply(c->cs, g.dtype, skip, deep, catn, frames, g.H, g.W, C, Cd, scale_p(c), shift_p(c)));
+  return LC_OK;
+}
+
+lc_status lc_op_conv_out(lc_ctx* c, const void* u, void* eps, int frames) {
+  lc_status s = op_checks(c, frames);
+  if (s != LC_OK) return s;
+  if (!u || !eps) return fail(c, LC_ERR_ARG, "NULL tensor");
+  const lc_config& g = c->cfg;
+  const int T = g.H * g.W;
+  // normalised copy goes to the chunk scratch; it must hold frames * T * C elements
+  if ((size_t)frames * T * g.C * dtype_size(g.dtype) > c->plan.ws_bytes)
+    return fail(c, LC_ERR_NOMEM, "chunk scratch too small for %d frames", frames);
+  char* un = ws_ptr(c);
+  s = gn_full(c, u, frames, T, g.C, c->pw.out_gn, un, 1);
+  if (s != LC_OK) return s;
+  ConvDesc d = conv_desc(g, c->pw.out, g.C, 16, frames, g.H, g.W, 1, un, nullptr, eps);
+  d.Cout_store = g.C_lat;
+  d.planar_out = 1;
+  LC_LAUNCH(c, LC_K_CONV_OUT, launch_conv(c->cs, d));
+  return LC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+// Shared device-side helpers for the gfx950 kernels: storage types, 16-byte vector access,
+// MFMA wrappers with their lane layouts, wavefront reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lc {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return static_cast<float>(v); }
+template <class T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return static_cast<bf16_t>(v); }  // RNE
+
+// A 16-byte packet of storage elements: 8 bf16 or 4 float.
+template <class T> struct Vec16;
+template <> struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  bf16x8 v;
+  __device__ __forceinline__ float get(int i) const { return static_cast<float>(v[i]); }
+  __device__ __forceinline__ void set(int i, float f) { v[i] = static_cast<bf16_t>(f); }
+};
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  f32x4 v;
+  __device__ __forceinline__ float get(int i) const { return v[i]; }
+  __device__ __forceinline__ void set(int i, float f) { v[i] = f; }
+};
+template <class T> __device__ __forceinline__ Vec16<T> load16(const T* p) {
+  return *reinterpret_cast<const Vec16<T>*>(p);
+}
+template <class T> __device__ __forceinline__ void store16(T* p, const Vec16<T>& v) {
+  *reinterpret_cast<Vec16<T>*>(p) = v;
+}
+template <class T> __device__ __forceinline__ Vec16<T> zero16() {
+  Vec16<T> z;
+#pragma unroll
+  for (int i = 0; i < Vec16<T>::N; ++i) z.set(i, 0.f);
+  return z;
+}
+
+__device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
+
+// ---------------------------------------------------------------------------------------
+// MFMA 16x16 tiles, D[16x16] += A[16xK] * B[Kx16], one wavefront.
+//   lane l supplies A[i = l%16][k-slots of group l/16] and B[same k-slots][j = l%16]
+//   lane l receives D[i = 4*(l/16) + r][j = l%16], r = 0..3
+// bf16: one instruction covers K = 32; the lane's k-slots are 8*(l/16) .. 8*(l/16)+7 (a 16-byte
+//       packet). fp32: one instruction covers K = 4; the lane's k-slot is l/16 (one float).
+// `Frag` is what one lane holds for one 16-byte packet of its row; `mma` issues as many
+// instructions as the packet holds k-steps for this lane group arrangement.
+// ---------------------------------------------------------------------------------------
+template <class T> struct Mma16;
+template <> struct Mma16<bf16_t> {
+  // a 64-byte (32 element) K-slab per instruction; lane group g reads elements [8g, 8g+8)
+  static constexpr int kSlab = 32;  // elements of K consumed per `mma`
+  typedef bf16x8 Frag;
+  static __device__ __forceinline__ Frag load(const bf16_t* row_slab, int g) {
+    return *reinterpret_cast<const bf16x8*>(row_slab + 8 * g);
+  }
+  static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x4& d) {
+    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, d, 0, 0, 0);
+  }
+};
+template <> struct Mma16<float> {
+  // a 64-byte (16 element) K-slab per `mma` = 4 instructions of K = 4; lane group g reads
+  // elements {g, 4+g, 8+g, 12+g}
+  static constexpr int kSlab = 16;
+  struct Frag { float v[4]; };
+  static __device__ __forceinline__ Frag load(const float* row_slab, int g) {
+    Frag f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) f.v[s] = row_slab[4 * s + g];
+    return f;
+  }
+  static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x4& d) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) d = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[s], b.v[s], d, 0, 0, 0);
+  }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Source-row mapping of a dense block of `rows` rows onto a larger row-major matrix:
+// dense row r lives at source row  base + (r / rows_per_seg) * seg_stride + (r % rows_per_seg).
+// A frame chunk is one segment; a token chunk takes `rows_per_seg` positions out of every frame.
+struct RowMap {
+  int64_t base;
+  int64_t seg_stride;
+  int rows_per_seg;
+  __host__ __device__ __forceinline__ int64_t operator()(int64_t r) const {
+    return base + (r / rows_per_seg) * seg_stride + (r % rows_per_seg);
+  }
+};
+
+}  // namespace lc

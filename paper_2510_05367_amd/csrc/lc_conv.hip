@@ -1,0 +1,267 @@
+// Implicit-GEMM 3x3 convolution and per-row linear layers on MFMA (gfx950), channels-last.
+//
+// The product is computed transposed, D[cout][pixel] = sum_k W[cout][k] * X[pixel][k], with
+// k = tap * Cin + ci, so that one lane ends up holding 4 consecutive output channels of one
+// pixel (a single 8- or 16-byte store into the channels-last output). One workgroup of 4
+// wavefronts owns a tile of BCO output channels x 128 pixels (8 image rows x 16 columns for a
+// convolution, 128 consecutive rows for a linear layer) and walks K in steps of 128 bytes per
+// row: both operand tiles of a step are staged in LDS (row stride 144 bytes: consecutive rows
+// start 16 bytes apart modulo 128, so 16-byte fragment reads of 8 consecutive rows hit disjoint
+// banks), double buffered, with the next step's global loads in flight during the MFMAs.
+// Out-of-image taps and ragged tiles are zero-filled at load time and masked at store time.
+#include "lc_internal.h"
+
+namespace lc {
+
+struct ConvArgs {
+  const void* x;
+  const void* w;
+  const float* bias;
+  const void* res;
+  void* y;
+  int Cin, Cout_store, ldw;  // ldw = taps * Cin (row length of w)
+  int frames, H, W, Ho, Wo, tiles_x, tiles_y;
+  int64_t rows;
+  RowMap out_map;
+};
+
+constexpr int kRowBytes = 128;  // K bytes per row per step
+constexpr int kLdsRow = 144;    // LDS row stride in bytes
+
+template <int BCO, int BPX>
+constexpr int conv_lds_bytes() { return 2 * (BCO + BPX) * kLdsRow; }
+
+template <class T, int TAPS, int STRIDE, int WCO, int WPX, int CO_T, int PX_T, bool PLANAR>
+__global__ __launch_bounds__(256) void conv_kernel(ConvArgs a) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int BKC = kRowBytes / (int)sizeof(T);  // K elements per step
+  constexpr int BCO = WCO * CO_T * 16;
+  constexpr int BPX = WPX * PX_T * 16;
+  constexpr int XP = BPX / 32;         // x packets per thread per step
+  constexpr int WP = (BCO + 31) / 32;  // w packets per thread per step
+  static_assert(WCO * WPX == 4, "4 wavefronts");
+  static_assert(BPX % 32 == 0, "pixel tile");
+  typedef Mma16<T> M;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  auto w_lds = [&](int b) { return smem + b * (BCO + BPX) * kLdsRow; };
+  auto x_lds = [&](int b) { return smem + b * (BCO + BPX) * kLdsRow + BCO * kLdsRow; };
+
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int wco = wid / WPX, wpx = wid % WPX;
+  const int co0 = blockIdx.y * BCO;
+  const T* __restrict__ X = (const T*)a.x;
+  const T* __restrict__ Wt = (const T*)a.w;
+
+  // ---- which pixels this workgroup owns
+  int frame = 0, ty0 = 0, tx0 = 0;
+  int64_t row0 = 0;
+  if (TAPS == 9) {
+    int t = blockIdx.x;
+    tx0 = (t % a.tiles_x) * 16;
+    t /= a.tiles_x;
+    ty0 = (t % a.tiles_y) * (BPX / 16);
+    frame = t / a.tiles_y;
+  } else {
+    row0 = (int64_t)blockIdx.x * BPX;
+  }
+
+  // ---- loader bookkeeping: this thread moves packet kp of rows lrow + 32*i
+  const int kp = tid & 7, lrow = tid >> 3;
+  int ld_oy[XP], ld_ox[XP];
+  bool ld_ok[XP];
+#pragma unroll
+  for (int i = 0; i < XP; ++i) {
+    const int p = lrow + 32 * i;
+    if (TAPS == 9) {
+      ld_oy[i] = ty0 + p / 16;
+      ld_ox[i] = tx0 + p % 16;
+      ld_ok[i] = ld_oy[i] < a.Ho && ld_ox[i] < a.Wo;
+    } else {
+      ld_oy[i] = 0;
+      ld_ox[i] = 0;
+      ld_ok[i] = row0 + p < a.rows;
+    }
+  }
+  Vec16<T> xv[XP], wv[WP];
+
+  auto load_global = [&](int step) {
+    const int slab = step / TAPS, tap = step - slab * TAPS;
+    const int kofs = slab * BKC + kp * VEC;
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+      bool ok = ld_ok[i];
+      int64_t off;
+      if (TAPS == 9) {
+        const int iy = ld_oy[i] * STRIDE + tap / 3 - 1, ix = ld_ox[i] * STRIDE + tap % 3 - 1;
+        ok = ok && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+        off = (((int64_t)frame * a.H + iy) * a.W + ix) * a.Cin + kofs;
+      } else {
+        off = (row0 + lrow + 32 * i) * a.Cin + kofs;
+      }
+      xv[i] = ok ? load16(X + off) : zero16<T>();
+    }
+#pragma unroll
+    for (int i = 0; i < WP; ++i) {
+      const int r = lrow + 32 * i;
+      if (BCO % 32 == 0 || r < BCO)
+        wv[i] = load16(Wt + (int64_t)(co0 + r) * a.ldw + tap * a.Cin + kofs);
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < XP; ++i)
+      *reinterpret_cast<Vec16<T>*>(x_lds(buf) + (lrow + 32 * i) * kLdsRow + kp * 16) = xv[i];
+#pragma unroll
+    for (int i = 0; i < WP; ++i) {
+      const int r = lrow + 32 * i;
+      if (BCO % 32 == 0 || r < BCO) *reinterpret_cast<Vec16<T>*>(w_lds(buf) + r * kLdsRow + kp * 16) = wv[i];
+    }
+  };
+
+  f32x4 acc[CO_T][PX_T];
+#pragma unroll
+  for (int i = 0; i < CO_T; ++i)
+#pragma unroll
+    for (int j = 0; j < PX_T; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int fr = lane & 15, fg = lane >> 4;
+  const int nsteps = TAPS * (a.Cin / BKC);
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int s = 0; s < nsteps; ++s) {
+    const int buf = s & 1;
+    if (s + 1 < nsteps) load_global(s + 1);
+    const unsigned char* wl = w_lds(buf) + (wco * CO_T * 16 + fr) * kLdsRow;
+    const unsigned char* xl = x_lds(buf) + (wpx * PX_T * 16 + fr) * kLdsRow;
+#pragma unroll
+    for (int kk = 0; kk < kRowBytes / 64; ++kk) {
+      typename M::Frag fa[CO_T], fb[PX_T];
+#pragma unroll
+      for (int i = 0; i < CO_T; ++i) fa[i] = M::load((const T*)(wl + i * 16 * kLdsRow + kk * 64), fg);
+#pragma unroll
+      for (int j = 0; j < PX_T; ++j) fb[j] = M::load((const T*)(xl + j * 16 * kLdsRow + kk * 64), fg);
+#pragma unroll
+      for (int i = 0; i < CO_T; ++i)
+#pragma unroll
+        for (int j = 0; j < PX_T; ++j) M::mma(fa[i], fb[j], acc[i][j]);
+    }
+    if (s + 1 < nsteps) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane holds channels co + 0..3 of pixel (tile j, column fr)
+  T* Y = (T*)a.y;
+  const T* R = (const T*)a.res;  // may alias Y (in-place residual)
+#pragma unroll
+  for (int j = 0; j < PX_T; ++j) {
+    const int p = wpx * PX_T * 16 + j * 16 + fr;
+    int64_t orow;
+    int oy = 0, ox = 0;
+    bool ok;
+    if (TAPS == 9) {
+      oy = ty0 + p / 16;
+      ox = tx0 + p % 16;
+      ok = oy < a.Ho && ox < a.Wo;
+      orow = ((int64_t)frame * a.Ho + oy) * a.Wo + ox;
+    } else {
+      ok = row0 + p < a.rows;
+      orow = ok ? a.out_map(row0 + p) : 0;
+    }
+    if (!ok) continue;
+#pragma unroll
+    for (int i = 0; i < CO_T; ++i) {
+      const int co = co0 + wco * CO_T * 16 + i * 16 + 4 * fg;
+      if (PLANAR) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (co + r < a.Cout_store) {
+            float v = acc[i][j][r] + (a.bias ? a.bias[co + r] : 0.f);
+            Y[(((int64_t)frame * a.Cout_store + co + r) * a.Ho + oy) * a.Wo + ox] = from_f32<T>(v);
+          }
+        }
+      } else {
+        if (co >= a.Cout_store) continue;
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = acc[i][j][r] + (a.bias ? a.bias[co + r] : 0.f);
+        const int64_t o = orow * a.Cout_store + co;
+        if (sizeof(T) == 2) {
+          if (R) {
+            bf16x4 rv = *reinterpret_cast<const bf16x4*>((const bf16_t*)R + o);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] += static_cast<float>(rv[r]);
+          }
+          bf16x4 ov;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ov[r] = static_cast<bf16_t>(v[r]);
+          *reinterpret_cast<bf16x4*>((bf16_t*)Y + o) = ov;
+        } else {
+          if (R) {
+            f32x4 rv = *reinterpret_cast<const f32x4*>((const float*)R + o);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] += rv[r];
+          }
+          *reinterpret_cast<f32x4*>((float*)Y + o) = f32x4{v[0], v[1], v[2], v[3]};
+        }
+      }
+    }
+  }
+}
+
+template <class T, int TAPS, int STRIDE, int WCO, int WPX, int CO_T, int PX_T, bool PLANAR>
+static hipError_t run(hipStream_t s, const ConvDesc& d) {
+  constexpr int BCO = WCO * CO_T * 16, BPX = WPX * PX_T * 16;
+  constexpr int lds = conv_lds_bytes<BCO, BPX>();
+  auto kern = conv_kernel<T, TAPS, STRIDE, WCO, WPX, CO_T, PX_T, PLANAR>;
+  static bool attr_done = false;  // per instantiation
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  ConvArgs a;
+  a.x = d.x; a.w = d.w; a.bias = d.bias; a.res = d.res; a.y = d.y;
+  a.Cin = d.Cin; a.Cout_store = d.Cout_store; a.ldw = d.taps * d.Cin;
+  a.frames = d.frames; a.H = d.H; a.W = d.W;
+  a.Ho = d.H / d.stride; a.Wo = d.W / d.stride;
+  a.tiles_x = (a.Wo + 15) / 16; a.tiles_y = (a.Ho + BPX / 16 - 1) / (BPX / 16);
+  a.rows = d.rows; a.out_map = d.out_map;
+  dim3 grid;
+  if (TAPS == 9) {
+    if (d.frames <= 0) return hipSuccess;
+    grid = dim3((unsigned)(a.tiles_x * a.tiles_y * d.frames), d.Cout / BCO);
+  } else {
+    if (d.rows <= 0) return hipSuccess;
+    grid = dim3((unsigned)((d.rows + BPX - 1) / BPX), d.Cout / BCO);
+  }
+  kern<<<grid, 256, lds, s>>>(a);
+  return hipGetLastError();
+}
+
+template <class T>
+static hipError_t dispatch(hipStream_t s, const ConvDesc& d) {
+  const int esz = (int)sizeof(T);
+  if (d.Cin % (kRowBytes / esz) != 0) return hipErrorInvalidValue;
+  if (d.planar_out) {
+    if (d.taps != 9 || d.stride != 1 || d.Cout != 16 || d.res) return hipErrorInvalidValue;
+    return run<T, 9, 1, 1, 4, 1, 2, true>(s, d);
+  }
+  if (d.Cout_store != d.Cout || d.Cout % 4) return hipErrorInvalidValue;
+  const bool wide = d.Cout % 160 == 0;
+  if (!wide && d.Cout % 64 != 0) return hipErrorInvalidValue;
+  if (d.taps == 9 && d.stride == 1)
+    return wide ? run<T, 9, 1, 2, 2, 5, 4, false>(s, d) : run<T, 9, 1, 2, 2, 2, 4, false>(s, d);
+  if (d.taps == 9 && d.stride == 2)
+    return wide ? run<T, 9, 2, 2, 2, 5, 4, false>(s, d) : run<T, 9, 2, 2, 2, 2, 4, false>(s, d);
+  if (d.taps == 1)
+    return wide ? run<T, 1, 1, 2, 2, 5, 4, false>(s, d) : run<T, 1, 1, 2, 2, 2, 4, false>(s, d);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_conv(hipStream_t s, const ConvDesc& d) {
+  if (d.taps == 9 && (d.H % d.stride || d.W % d.stride)) return hipErrorInvalidValue;
+  return d.dt == kBF16 ? dispatch<bf16_t>(s, d) : dispatch<float>(s, d);
+}
+
+}  // namespace lc

@@ -1,0 +1,81 @@
+// Host-side declarations of the kernel launchers (one per kernel family). Every launcher only
+// enqueues on `s`; none allocates. Activations are channels-last [rows, channels].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lc_common.h"
+
+namespace lc {
+
+enum Dtype { kF32 = 0, kBF16 = 1 };
+inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
+
+// ---- GroupNorm ([rows, C] channels-last; statistics per frame and group) -------------------
+constexpr int kStatRows = 64;  // rows summed by one block of the statistics kernel
+inline int stat_splits(int rows_per_frame) { return (rows_per_frame + kStatRows - 1) / kStatRows; }
+
+// partial[frame][split][c][2] = (sum, sum of squares) over the rows of the split.
+hipError_t launch_gn_stats(hipStream_t s, int dt, const void* x, float* partial, int frames,
+                           int rows_per_frame, int C);
+// Combines per-channel partial sums of up to two sources (channels [0,CA) from A with weight wA
+// per element, channels [CA, CA+CB) from B with weight wB: B is the half-resolution deep feature
+// whose every element appears 4 times after 2x nearest upsampling) into per-frame, per-channel
+// scale/shift:  y = x * scale + shift.  scale/shift: [frames][CA+CB].
+hipError_t launch_gn_finalize(hipStream_t s, const float* partA, int CA, int splitsA, int rowsA, float wA,
+                              const float* partB, int CB, int splitsB, int rowsB, float wB,
+                              const float* gamma, const float* beta, int groups, float eps,
+                              float* scale, float* shift, int frames);
+// y[r][c] = act(x[map(r)][c] * scale[f][c] + shift[f][c]),  f = r / map.rows_per_seg.
+hipError_t launch_gn_apply(hipStream_t s, int dt, const void* x, RowMap map, void* y, int64_t rows, int C,
+                           const float* scale, const float* shift, int silu);
+// catn[r][0:C] from skip[r], catn[r][C:C+Cd] from deep[(frame, y/2, x/2)], normalised + SiLU.
+hipError_t launch_concat_apply(hipStream_t s, int dt, const void* skip, const void* deep, void* catn,
+                               int frames, int H, int W, int C, int Cd, const float* scale,
+                               const float* shift);
+
+// ---- implicit-GEMM convolution / linear layers (MFMA) ---------------------------------------
+struct ConvDesc {
+  int dt;
+  int taps;    // 9 (3x3, zero padding 1) or 1 (per-row linear layer)
+  int stride;  // 1 or 2 (taps == 9 only)
+  int Cin, Cout;  // Cout here is the padded width of `w` rows, a multiple of the cout tile
+  int Cout_store; // channels actually stored (<= Cout)
+  const void* w;      // [Cout][taps*Cin], storage dtype
+  const float* bias;  // [Cout] or nullptr
+  // taps == 9: x is [frames][H][W][Cin]; y / res are [frames][H/stride][W/stride][Cout_store]
+  int frames, H, W;
+  // taps == 1: x is dense [rows][Cin]; y / res rows go through out_map
+  int64_t rows;
+  RowMap out_map;
+  const void* x;
+  const void* res;  // nullptr or same indexing as y
+  void* y;
+  // epilogue variant: 0 = channels-last store; 1 = planar store [frame][Cout_store][H][W]
+  int planar_out;
+};
+hipError_t launch_conv(hipStream_t s, const ConvDesc& d);
+
+// ---- attention cores -----------------------------------------------------------------------
+// qkv [frames*T][3C] -> out [frames*T][C]; queries [q0,q1) of every frame.
+hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qkv, void* out, int frames, int T,
+                                    int heads, int d, int q0, int q1);
+// qkv [(B*F)*P][3C] frame-major -> out same rows x C; attention over the F frames.
+hipError_t launch_temporal_attention(hipStream_t s, int dt, const void* qkv, void* out, int B, int F, int P,
+                                     int heads, int d);
+
+// ---- small kernels -------------------------------------------------------------------------
+// h[frames*H*W][C] = conv3x3(x[frames][Cl][H][W]); w_packed float [Cl*9][C], bias float [C].
+hipError_t launch_conv_in(hipStream_t s, int dt, const void* x, void* h, int frames, int H, int W, int Cl, int C,
+                          const float* w_packed, const float* bias);
+// planar [frames][C][HW] <-> channels-last [frames][HW][C]
+hipError_t launch_planar_to_cl(hipStream_t s, int dt, const void* src, void* dst, int frames, int C, int HW);
+hipError_t launch_cl_to_planar(hipStream_t s, int dt, const void* src, void* dst, int frames, int C, int HW);
+// weight packing (run once at load time)
+hipError_t launch_pack_conv_w(hipStream_t s, int dt, const void* w, void* packed, int Cout, int Cin, int taps,
+                              int Cout_padded);  // [Cout][Cin][taps] -> [Cout_padded][taps][Cin]
+hipError_t launch_pack_conv_in_w(hipStream_t s, int dt, const void* w, float* packed, int C, int Cl);
+hipError_t launch_to_f32(hipStream_t s, int dt, const void* src, float* dst, int n, int n_padded);
+hipError_t launch_copy_rows(hipStream_t s, int dt, const void* src, void* dst, int64_t elems);
+
+}  // namespace lc

@@ -1,0 +1,156 @@
+// Small kernels: the C_lat -> C input convolution (write-bound), layout changes between the
+// public planar order [frame][C][H*W] and the internal channels-last order, weight packing.
+#include "lc_internal.h"
+
+namespace lc {
+
+// ---------------------------------------------------------------------------------------------
+// conv_in: 3x3, zero padding, C_lat (<= 16) input channels. One thread = one pixel x one 16-byte
+// packet of output channels; the packed weights [C_lat*9][C] are read through the vector cache.
+template <class T>
+__global__ __launch_bounds__(256) void conv_in_kernel(const T* __restrict__ x, T* __restrict__ h, int frames, int H,
+                                                      int W, int Cl, int C, const float* __restrict__ wp,
+                                                      const float* __restrict__ bias) {
+  constexpr int VEC = Vec16<T>::N;
+  const int cv = C / VEC;
+  const int64_t total = (int64_t)frames * H * W * cv;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t pix = i / cv;
+  const int c0 = (int)(i - pix * cv) * VEC;
+  const int hw = H * W;
+  const int f = (int)(pix / hw);
+  const int p = (int)(pix - (int64_t)f * hw);
+  const int yy = p / W, xx = p - yy * W;
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = bias[c0 + e];
+  for (int cl = 0; cl < Cl; ++cl) {
+    const T* plane = x + ((int64_t)f * Cl + cl) * hw;
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+      const int iy = yy + a - 1;
+#pragma unroll
+      for (int b = 0; b < 3; ++b) {
+        const int ix = xx + b - 1;
+        if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+        const float v = to_f32(plane[iy * W + ix]);
+        const float* wr = wp + (int64_t)((cl * 3 + a) * 3 + b) * C + c0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v, wr[e], acc[e]);
+      }
+    }
+  }
+  Vec16<T> o;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) o.set(e, acc[e]);
+  store16(h + pix * C + c0, o);
+}
+
+hipError_t launch_conv_in(hipStream_t s, int dt, const void* x, void* h, int frames, int H, int W, int Cl, int C,
+                          const float* w_packed, const float* bias) {
+  if (frames <= 0) return hipSuccess;
+  const int vec = dt == kBF16 ? 8 : 4;
+  const int64_t total = (int64_t)frames * H * W * (C / vec);
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (dt == kBF16)
+    conv_in_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)x, (bf16_t*)h, frames, H, W, Cl, C, w_packed, bias);
+  else
+    conv_in_kernel<float><<<blocks, 256, 0, s>>>((const float*)x, (float*)h, frames, H, W, Cl, C, w_packed, bias);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Batched 2-D transpose: src [f][R][S] -> dst [f][S][R] through a 32x33 LDS tile.
+template <class T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ src, T* __restrict__ dst, int R, int S) {
+  __shared__ T tile[32][33];
+  const int f = blockIdx.z;
+  const int s0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const T* sp = src + (int64_t)f * R * S;
+  T* dp = dst + (int64_t)f * R * S;
+  for (int k = ty; k < 32; k += 8)
+    if (r0 + k < R && s0 + tx < S) tile[k][tx] = sp[(int64_t)(r0 + k) * S + s0 + tx];
+  __syncthreads();
+  for (int k = ty; k < 32; k += 8)
+    if (s0 + k < S && r0 + tx < R) dp[(int64_t)(s0 + k) * R + r0 + tx] = tile[tx][k];
+}
+
+template <class T>
+static hipError_t transpose(hipStream_t s, const void* src, void* dst, int frames, int R, int S) {
+  if (frames <= 0) return hipSuccess;
+  dim3 grid((S + 31) / 32, (R + 31) / 32, frames);
+  transpose_kernel<T><<<grid, 256, 0, s>>>((const T*)src, (T*)dst, R, S);
+  return hipGetLastError();
+}
+hipError_t launch_planar_to_cl(hipStream_t s, int dt, const void* src, void* dst, int frames, int C, int HW) {
+  return dt == kBF16 ? transpose<uint16_t>(s, src, dst, frames, C, HW) : transpose<uint32_t>(s, src, dst, frames, C, HW);
+}
+hipError_t launch_cl_to_planar(hipStream_t s, int dt, const void* src, void* dst, int frames, int C, int HW) {
+  return dt == kBF16 ? transpose<uint16_t>(s, src, dst, frames, HW, C) : transpose<uint32_t>(s, src, dst, frames, HW, C);
+}
+
+// ---------------------------------------------------------------------------------------------
+template <class T>
+__global__ void pack_conv_w_kernel(const T* __restrict__ w, T* __restrict__ packed, int Cout, int Cin, int taps,
+                                   int Cout_padded) {
+  const int64_t total = (int64_t)Cout_padded * taps * Cin;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int ci = (int)(i % Cin);
+  const int tap = (int)((i / Cin) % taps);
+  const int co = (int)(i / ((int64_t)Cin * taps));
+  packed[i] = co < Cout ? w[((int64_t)co * Cin + ci) * taps + tap] : from_f32<T>(0.f);
+}
+hipError_t launch_pack_conv_w(hipStream_t s, int dt, const void* w, void* packed, int Cout, int Cin, int taps,
+                              int Cout_padded) {
+  const int64_t total = (int64_t)Cout_padded * taps * Cin;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (dt == kBF16)
+    pack_conv_w_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)w, (bf16_t*)packed, Cout, Cin, taps, Cout_padded);
+  else
+    pack_conv_w_kernel<float><<<blocks, 256, 0, s>>>((const float*)w, (float*)packed, Cout, Cin, taps, Cout_padded);
+  return hipGetLastError();
+}
+
+template <class T>
+__global__ void pack_conv_in_w_kernel(const T* __restrict__ w, float* __restrict__ packed, int C, int Cl) {
+  const int total = C * Cl * 9;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = i % C;
+  const int k = i / C;  // cl*9 + tap
+  packed[i] = to_f32(w[(int64_t)c * Cl * 9 + k]);
+}
+hipError_t launch_pack_conv_in_w(hipStream_t s, int dt, const void* w, float* packed, int C, int Cl) {
+  const unsigned blocks = (unsigned)((C * Cl * 9 + 255) / 256);
+  if (dt == kBF16) pack_conv_in_w_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)w, packed, C, Cl);
+  else pack_conv_in_w_kernel<float><<<blocks, 256, 0, s>>>((const float*)w, packed, C, Cl);
+  return hipGetLastError();
+}
+
+template <class T>
+__global__ void to_f32_kernel(const T* __restrict__ src, float* __restrict__ dst, int n, int n_padded) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n_padded) dst[i] = i < n ? to_f32(src[i]) : 0.f;
+}
+hipError_t launch_to_f32(hipStream_t s, int dt, const void* src, float* dst, int n, int n_padded) {
+  const unsigned blocks = (unsigned)((n_padded + 255) / 256);
+  if (dt == kBF16) to_f32_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)src, dst, n, n_padded);
+  else to_f32_kernel<float><<<blocks, 256, 0, s>>>((const float*)src, dst, n, n_padded);
+  return hipGetLastError();
+}
+
+__global__ void copy_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+hipError_t launch_copy_rows(hipStream_t s, int dt, const void* src, void* dst, int64_t elems) {
+  const int64_t words = elems * (int64_t)dtype_size(dt) / 4;
+  if (words <= 0) return hipSuccess;
+  copy_kernel<<<(unsigned)((words + 255) / 256), 256, 0, s>>>((const uint32_t*)src, (uint32_t*)dst, words);
+  return hipGetLastError();
+}
+
+}  // namespace lc

@@ -1,0 +1,58 @@
+"""Helpers for the GPU parity tests: layout plumbing between the public planar order and the
+library's channels-last rows, and the error measures the tolerances are stated in."""
+import numpy as np
+import torch
+
+from paper_2510_05367_amd import binding as lcb
+from paper_2510_05367_amd import synth
+
+# Tolerances (HIP path vs float64 oracle on identical, already-rounded inputs):
+#   fp32 storage: rel-L2 <= 1e-4
+#   bf16 storage: rel-L2 <= 1e-2 and max-abs <= 2e-2 (on the step output eps, whose scale is O(1))
+TOL = {"f32": dict(rel=1e-4, abs=None), "bf16": dict(rel=1e-2, abs=2e-2)}
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def check(name, got, ref, dtype, abs_scale=1.0):
+    """got: torch tensor or array; ref: float64 array of the same shape."""
+    g = got.float().cpu().numpy() if isinstance(got, torch.Tensor) else np.asarray(got)
+    assert g.shape == ref.shape, (name, g.shape, ref.shape)
+    assert np.all(np.isfinite(g)), f"{name}: non-finite values"
+    r = rel_l2(g, ref)
+    m = float(np.max(np.abs(g.astype(np.float64) - ref)))
+    tol = TOL[dtype]
+    msg = f"{name}: rel-L2 {r:.3e} (tol {tol['rel']:.0e}), max-abs {m:.3e}"
+    print(msg, flush=True)
+    assert r <= tol["rel"], msg
+    if tol["abs"] is not None:
+        assert m <= tol["abs"] * abs_scale, msg
+    return r, m
+
+
+def planar_to_rows(a):
+    """[N, C, H, W] -> [N*H*W, C]"""
+    N, C, H, W = a.shape
+    return np.ascontiguousarray(a.transpose(0, 2, 3, 1)).reshape(N * H * W, C)
+
+
+def rows_to_planar(r, N, C, H, W):
+    return np.ascontiguousarray(r.reshape(N, H, W, C).transpose(0, 3, 1, 2))
+
+
+def make_stage(cfg, seed=0, sharp=1.0, **kw):
+    w = synth.make_weights(cfg, seed, sharp=sharp)
+    return lcb.Stage(cfg, w, **kw), w
+
+
+def dev(stage, a):
+    """numpy float32 (already representable in the stage dtype) -> device tensor of the stage dtype."""
+    return stage.to_device(np.ascontiguousarray(a, dtype=np.float32))
+
+
+def host(t):
+    return t.float().cpu().numpy().astype(np.float64)

@@ -1,0 +1,97 @@
+"""CPU-side checks of the boundary: the shared library loads without a GPU, exports every symbol
+the header declares, and its host-only entry points validate their arguments."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_05367_amd import binding as lcb
+from paper_2510_05367_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "lightcache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_symbols()
+    assert len(names) >= 25
+    lib = lcb.lib()
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in lightcache.h but not exported"
+    # and the binding knows a prototype for each of them
+    assert sorted(lcb.PROTOTYPES) == names
+
+
+def test_struct_sizes_match_header_layout():
+    assert ctypes.sizeof(lcb.lc_config) == 15 * 4
+    assert ctypes.sizeof(lcb.lc_weights) == 8 * (2 + 4 * lcb.LC_MAX_RES + 7 + 7 + 2 + 4 + 4 + 4)
+    assert ctypes.sizeof(lcb.lc_profile) == 16 * len(lcb.KERNEL_FAMILIES)
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_named_configs_are_valid(name):
+    c = lcb.make_config(synth.CONFIGS[name], host_slots=2, dev_slots=2)
+    lcb.lc_check_config(c)
+    cfg = synth.CONFIGS[name]
+    es = 2 if cfg.dtype == "bf16" else 4
+    assert lcb.lc_cache_entry_bytes(c) == cfg.N * cfg.C_deep * (cfg.H // 2) * (cfg.W // 2) * es
+
+
+@pytest.mark.parametrize("field,value", [("H", 31), ("W", 7), ("C", 100), ("C_deep", 96), ("groups", 7),
+                                         ("heads", 3), ("head_dim", 24), ("C_lat", 17), ("n_res", 5),
+                                         ("dev_slots", 0), ("host_slots", 65), ("B", 0), ("gn_eps", 0.0)])
+def test_bad_configs_are_rejected(field, value):
+    c = lcb.make_config(synth.CONFIGS["tiny"])
+    setattr(c, field, value)
+    with pytest.raises(lcb.LcError) as e:
+        lcb.lc_check_config(c)
+    assert e.value.status == lcb.LC_ERR_SHAPE
+    assert lcb.lc_workspace_bytes(c, 0, 0) == 0 and lcb.lc_cache_entry_bytes(c) == 0
+
+
+def test_bad_dtype_and_null():
+    c = lcb.make_config(synth.CONFIGS["tiny"])
+    c.dtype = 7
+    with pytest.raises(lcb.LcError) as e:
+        lcb.lc_check_config(c)
+    assert e.value.status == lcb.LC_ERR_ARG
+    assert lcb.lib().lc_check_config(None) == lcb.LC_ERR_ARG
+    assert "NULL" in lcb.lc_last_error()
+
+
+def test_footprint_model_scales_with_chunk_not_with_frames():
+    cfg = synth.CONFIGS["animatediff"]
+    c = lcb.make_config(cfg)
+    full = lcb.lc_workspace_bytes(c, 0, 0)
+    sizes = [lcb.lc_workspace_bytes(c, fc, 0) for fc in (16, 8, 4, 2, 1)]
+    assert all(a > b for a, b in zip([full] + sizes, sizes))
+    # persistent part: skip feature + dev_slots cache entries (+ small statistics scratch)
+    es = 2
+    persistent = cfg.N * cfg.T * cfg.C * es + 2 * lcb.lc_cache_entry_bytes(c)
+    chunk1 = 4 * cfg.C * cfg.T * es  # one frame of (normalised copy + q,k,v)
+    assert sizes[-1] - persistent < chunk1 + 16e6
+    # chunk scratch is linear in the frame chunk
+    assert abs((sizes[1] - sizes[2]) - 4 * chunk1) < 1e6
+    # negative chunk
+    assert lcb.lc_workspace_bytes(c, -1, 0) == 0
+    # clamping: a chunk above the axis length equals unchunked
+    assert lcb.lc_workspace_bytes(c, 1000, 0) == full
+    # no score matrix is ever materialised: the stress instance stays far below 64 GB even unchunked
+    s = lcb.make_config(synth.CONFIGS["stress"], host_slots=10)
+    assert lcb.lc_workspace_bytes(s, 0, 0) < 4e9
+
+
+def test_token_chunk_bounds_the_temporal_pass():
+    cfg = synth.CONFIGS["svdxt"]
+    c = lcb.make_config(cfg)
+    a = lcb.lc_workspace_bytes(c, 5, 2304)
+    b = lcb.lc_workspace_bytes(c, 5, 0)
+    assert a > 0 and b > 0
+    # 50 frames x 2304 positions = 115200 rows > 5 x 9216 = 46080 rows: the token chunk dominates
+    assert a > b
