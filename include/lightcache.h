@@ -180,13 +180,18 @@ lc_status lc_reset_stats(lc_ctx* ctx);
 
 /* mask: bit k set = bracket every launch of kernel family k (LC_K_*) with events on the compute
  * stream. lc_get_profile() synchronises, sums the brackets into out and clears them. At most
- * 16384 brackets are kept between two lc_get_profile calls; further launches are not timed. */
+ * 4096 brackets are kept between two lc_get_profile calls; further launches are not timed. */
 lc_status lc_set_profiling(lc_ctx* ctx, uint32_t mask);
 lc_status lc_get_profile(lc_ctx* ctx, lc_profile* out /* [host] */);
 
 /* ---- single operators (the same kernels the steps launch; used by the parity tests and the
  *      benchmark). Activations are in the library's internal channels-last layout
- *      [rows, channels] with rows = frame-major pixels; all pointers [device], cfg dtype.
+ *      [rows, channels] with rows = frame-major pixels; all pointers [device].
+ *      Element types: tensors of the residual stream (the outputs of conv_in, of the RESi / UP /
+ *      DOWN convolutions and of proj, every `res` argument, the inputs of group_norm and conv_out
+ *      and concat_norm's `skip`) are always float: with bf16 storage the stream that every block
+ *      adds into is kept in fp32 and only MFMA operands are rounded. All other tensors (normalised
+ *      activations, qkv, attention outputs, cache entries, x, eps) have the cfg dtype.
  *      Each call enqueues on the compute stream. `frames` counts frames of H x W pixels
  *      (H/2 x W/2 where stated). -------------------------------------------------------------- */
 
@@ -195,16 +200,17 @@ typedef enum {
   LC_L_SATTN = 8, LC_L_TATTN = 9, LC_L_DRES = 10, LC_L_UP = 11, LC_L_OUT = 12, LC_L_DOWN = 13
 } lc_layer;
 
-/* y = [SiLU](GroupNorm(x)) with the scale/shift of `layer`; channels = that layer's input width
- * (C, or C_deep at H/2 x W/2 for LC_L_DRES). */
+/* y (cfg dtype) = [SiLU](GroupNorm(x (float))) with the scale/shift of `layer`; channels = that
+ * layer's input width (C, or C_deep at H/2 x W/2 for LC_L_DRES). */
 lc_status lc_op_group_norm(lc_ctx* ctx, int layer, const void* x, void* y, int frames, int silu);
 /* y = [res +] conv3x3(x) + bias of `layer` (LC_L_RESi, LC_L_DRES at H/2 x W/2, LC_L_UP with
- * C + C_deep input channels, LC_L_DOWN stride 2: x at H x W -> y at H/2 x W/2). res may be NULL
- * or equal to y. */
+ * C + C_deep input channels, LC_L_DOWN stride 2: x at H x W -> y at H/2 x W/2). res (float) may be
+ * NULL or equal to y. x is cfg dtype except for LC_L_DOWN (float: it reads the skip feature); y is
+ * float except for LC_L_DRES (cfg dtype: it writes a cache entry). */
 lc_status lc_op_conv3x3(lc_ctx* ctx, int layer, const void* x, const void* res, void* y, int frames);
 /* qkv[rows, 3C] = x[rows, C] [Wq;Wk;Wv]^T of LC_L_SATTN / LC_L_TATTN. */
 lc_status lc_op_qkv(lc_ctx* ctx, int layer, const void* x, void* qkv, int64_t rows);
-/* y[rows, C] = res + a[rows, C] Wo^T + bo of LC_L_SATTN / LC_L_TATTN. res may equal y. */
+/* y[rows, C] (float) = res (float) + a[rows, C] Wo^T + bo of LC_L_SATTN / LC_L_TATTN. res may equal y. */
 lc_status lc_op_proj(lc_ctx* ctx, int layer, const void* a, const void* res, void* y, int64_t rows);
 /* Spatial attention core: per frame and head, softmax(QK^T/sqrt(d))V over the H*W tokens of the
  * frame, for query tokens [q0, q1). qkv [frames*H*W, 3C] -> out [frames*H*W, C]. */
@@ -212,12 +218,12 @@ lc_status lc_op_spatial_attention(lc_ctx* ctx, const void* qkv, void* out, int f
 /* Temporal attention core: qkv [(B*F) * positions, 3C] (frame-major) -> out [(B*F)*positions, C];
  * per batch element, position and head attention over the F frames. */
 lc_status lc_op_temporal_attention(lc_ctx* ctx, const void* qkv, void* out, int positions);
-/* h[frames*H*W, C] = conv_in(x[frames, C_lat, H, W]). */
+/* h[frames*H*W, C] (float) = conv_in(x[frames, C_lat, H, W]). */
 lc_status lc_op_conv_in(lc_ctx* ctx, const void* x, void* h, int frames);
-/* catn[frames*H*W, C + C_deep] = SiLU(GN_up(Concat(skip, up2(deep)))) ([FC]); deep is
+/* catn[frames*H*W, C + C_deep] = SiLU(GN_up(Concat(skip (float), up2(deep)))) ([FC]); deep is
  * [frames*(H/2)*(W/2), C_deep] channels-last. */
 lc_status lc_op_concat_norm(lc_ctx* ctx, const void* skip, const void* deep, void* catn, int frames);
-/* eps[frames, C_lat, H, W] = conv_out(SiLU(GN_out(u))), u [frames*H*W, C]. */
+/* eps[frames, C_lat, H, W] = conv_out(SiLU(GN_out(u))), u (float) [frames*H*W, C]. */
 lc_status lc_op_conv_out(lc_ctx* ctx, const void* u, void* eps, int frames);
 
 #ifdef __cplusplus

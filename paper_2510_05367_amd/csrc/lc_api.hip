@@ -123,7 +123,7 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   else p.tc = (int)T;
   p.qc = token_chunk > 0 ? (int)std::min<int64_t>(token_chunk, T) : (int)T;
   size_t off = 0;
-  p.off_h = off; off += align_up((size_t)(N * T * g.C) * es);
+  p.off_h = off; off += align_up((size_t)(N * T * g.C) * 4);  // the skip / residual stream is fp32
   p.slot_bytes = align_up((size_t)(N * (T / 4) * g.C_deep) * es);
   p.off_slots = off; off += p.slot_bytes * g.dev_slots;
   // partH also serves the half-resolution GroupNorm of the deep stand-in
@@ -134,10 +134,10 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   p.off_shift = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
   const int64_t pc = (int64_t)p.fc * T;   // pixels of a frame chunk
   const int64_t rt = N * p.tc;            // rows of a temporal pass
-  int64_t elems = 4 * g.C * std::max(pc, rt);                       // tn + qkv
-  elems = std::max(elems, pc * (2 * (int64_t)g.C + g.C_deep));      // catn + u
-  elems = std::max(elems, 2 * (pc / 4) * (int64_t)g.C_deep);        // deep stand-in: d0 + dn
-  p.ws_bytes = align_up((size_t)elems * es) + kAlign;
+  size_t wsb = (size_t)(4 * g.C * std::max(pc, rt)) * es;                                   // tn + qkv
+  wsb = std::max(wsb, (size_t)(pc * ((int64_t)g.C + g.C_deep)) * es + (size_t)(pc * g.C) * 4);  // catn + u (fp32)
+  wsb = std::max(wsb, (size_t)((pc / 4) * (int64_t)g.C_deep) * (4 + es));                     // deep stand-in: d0 (fp32) + dn
+  p.ws_bytes = align_up(wsb) + kAlign;
   p.off_ws = off; off += p.ws_bytes;
   p.total = off;
   return p;
@@ -178,27 +178,29 @@ RowMap dense_map() { return RowMap{0, 0, 1 << 30}; }
 // `frames` entries of the scale/shift scratch).
 lc_status gn_scale_shift(lc_ctx* c, const void* x, int frames, int rows_per_frame, int C, const GnW& w) {
   const lc_config& g = c->cfg;
-  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, x, partH(c), frames, rows_per_frame, C));
+  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, x, partH(c), frames, rows_per_frame, C));
   LC_LAUNCH(c, LC_K_GN_FINAL,
             launch_gn_finalize(c->cs, partH(c), C, stat_splits(rows_per_frame), rows_per_frame, 1.f, nullptr, 0, 0,
                                0, 0.f, w.gamma, w.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), frames));
   return LC_OK;
 }
 
+// x is an fp32 residual-stream tensor; y gets the operand type of the configuration.
 lc_status gn_full(lc_ctx* c, const void* x, int frames, int rows_per_frame, int C, const GnW& w, void* y, int silu) {
   lc_status s = gn_scale_shift(c, x, frames, rows_per_frame, C, w);
   if (s != LC_OK) return s;
   RowMap m{0, 0, rows_per_frame};
   m.seg_stride = rows_per_frame;  // dense frames: segment f starts at f * rows_per_frame
-  LC_LAUNCH(c, LC_K_GN_APPLY, launch_gn_apply(c->cs, c->cfg.dtype, x, m, y, (int64_t)frames * rows_per_frame, C,
+  LC_LAUNCH(c, LC_K_GN_APPLY, launch_gn_apply(c->cs, kF32, c->cfg.dtype, x, m, y, (int64_t)frames * rows_per_frame, C,
                                               scale_p(c), shift_p(c), silu));
   return LC_OK;
 }
 
 ConvDesc conv_desc(const lc_config& g, const ConvW& w, int Cin, int Cout, int frames, int H, int W, int stride,
-                   const void* x, const void* res, void* y) {
+                   const void* x, const void* res, void* y, int x_f32, int y_f32) {
   ConvDesc d;
   memset(&d, 0, sizeof d);
+  d.x_f32 = x_f32; d.y_f32 = y_f32;
   d.dt = g.dtype; d.taps = 9; d.stride = stride; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
   d.w = w.w; d.bias = w.b; d.frames = frames; d.H = H; d.W = W; d.x = x; d.res = res; d.y = y;
   d.out_map = dense_map();
@@ -206,9 +208,10 @@ ConvDesc conv_desc(const lc_config& g, const ConvW& w, int Cin, int Cout, int fr
 }
 
 ConvDesc linear_desc(const lc_config& g, const void* w, const float* bias, int Cin, int Cout, int64_t rows,
-                     RowMap out_map, const void* x, const void* res, void* y) {
+                     RowMap out_map, const void* x, const void* res, void* y, int y_f32) {
   ConvDesc d;
   memset(&d, 0, sizeof d);
+  d.y_f32 = y_f32;
   d.dt = g.dtype; d.taps = 1; d.stride = 1; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
   d.w = w; d.bias = bias; d.rows = rows; d.out_map = out_map; d.x = x; d.res = res; d.y = y;
   return d;
@@ -227,7 +230,7 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
   for (int n0 = 0; n0 < N; n0 += p.fc) {
     const int nf = std::min(p.fc, N - n0);
     const int64_t pc = (int64_t)nf * T;
-    char* hc = h + (size_t)n0 * T * C * es;
+    char* hc = h + (size_t)n0 * T * C * 4;
     char* tn = ws;
     char* qkv = ws + (size_t)pc * C * es;
     LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, (const char*)x + (size_t)n0 * g.C_lat * T * es, hc, nf,
@@ -235,17 +238,17 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     for (int i = 0; i < g.n_res; ++i) {
       lc_status s = gn_full(c, hc, nf, T, C, w.res_gn[i], tn, 1);
       if (s != LC_OK) return s;
-      LC_LAUNCH(c, LC_K_CONV_RES, launch_conv(c->cs, conv_desc(g, w.res[i], C, C, nf, g.H, g.W, 1, tn, hc, hc)));
+      LC_LAUNCH(c, LC_K_CONV_RES, launch_conv(c->cs, conv_desc(g, w.res[i], C, C, nf, g.H, g.W, 1, tn, hc, hc, 0, 1)));
     }
     lc_status s = gn_full(c, hc, nf, T, C, w.sattn.gn, tn, 0);
     if (s != LC_OK) return s;
     LC_LAUNCH(c, LC_K_QKV,
-              launch_conv(c->cs, linear_desc(g, w.sattn.wqkv, nullptr, C, 3 * C, pc, dense_map(), tn, nullptr, qkv)));
+              launch_conv(c->cs, linear_desc(g, w.sattn.wqkv, nullptr, C, 3 * C, pc, dense_map(), tn, nullptr, qkv, 0)));
     for (int q0 = 0; q0 < T; q0 += p.qc)
       LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, tn, nf, T, g.heads, g.head_dim, q0,
                                                         std::min(q0 + p.qc, T)));
     LC_LAUNCH(c, LC_K_PROJ,
-              launch_conv(c->cs, linear_desc(g, w.sattn.wo, w.sattn.bo, C, C, pc, dense_map(), tn, hc, hc)));
+              launch_conv(c->cs, linear_desc(g, w.sattn.wo, w.sattn.bo, C, C, pc, dense_map(), tn, hc, hc, 1)));
   }
 
   // ---- temporal block: per-frame statistics over whole frames, then per position chunk
@@ -258,11 +261,11 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       RowMap m{p0, T, np};
       char* tn = ws;
       char* qkv = ws + (size_t)rows * C * es;
-      LC_LAUNCH(c, LC_K_GN_APPLY, launch_gn_apply(c->cs, g.dtype, h, m, tn, rows, C, scale_p(c), shift_p(c), 0));
+      LC_LAUNCH(c, LC_K_GN_APPLY, launch_gn_apply(c->cs, kF32, g.dtype, h, m, tn, rows, C, scale_p(c), shift_p(c), 0));
       LC_LAUNCH(c, LC_K_QKV,
-                launch_conv(c->cs, linear_desc(g, w.tattn.wqkv, nullptr, C, 3 * C, rows, dense_map(), tn, nullptr, qkv)));
+                launch_conv(c->cs, linear_desc(g, w.tattn.wqkv, nullptr, C, 3 * C, rows, dense_map(), tn, nullptr, qkv, 0)));
       LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, tn, g.B, g.F, np, g.heads, g.head_dim));
-      LC_LAUNCH(c, LC_K_PROJ, launch_conv(c->cs, linear_desc(g, w.tattn.wo, w.tattn.bo, C, C, rows, m, tn, h, h)));
+      LC_LAUNCH(c, LC_K_PROJ, launch_conv(c->cs, linear_desc(g, w.tattn.wo, w.tattn.bo, C, C, rows, m, tn, h, h, 1)));
     }
   }
 
@@ -275,14 +278,14 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     for (int n0 = 0; n0 < N; n0 += p.fc) {
       const int nf = std::min(p.fc, N - n0);
       const int64_t pq = (int64_t)nf * (T / 4);
-      char* hc = h + (size_t)n0 * T * C * es;
-      char* d0 = ws;
-      char* dn = ws + (size_t)pq * Cd * es;
+      char* hc = h + (size_t)n0 * T * C * 4;
+      char* d0 = ws;  // fp32
+      char* dn = ws + (size_t)pq * Cd * 4;
       char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
-      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, conv_desc(g, w.down, C, Cd, nf, g.H, g.W, 2, hc, nullptr, d0)));
+      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, conv_desc(g, w.down, C, Cd, nf, g.H, g.W, 2, hc, nullptr, d0, 1, 1)));
       lc_status s = gn_full(c, d0, nf, T / 4, Cd, w.dres_gn, dn, 1);
       if (s != LC_OK) return s;
-      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, conv_desc(g, w.dres, Cd, Cd, nf, g.H / 2, g.W / 2, 1, dn, d0, dc)));
+      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, conv_desc(g, w.dres, Cd, Cd, nf, g.H / 2, g.W / 2, 1, dn, d0, dc, 0, 0)));
     }
     LC_HIP(c, hipEventRecord(c->ev_produced[slot], c->cs));
     c->dev_filled[slot] = 1;
@@ -295,22 +298,22 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
   for (int n0 = 0; n0 < N; n0 += p.fc) {
     const int nf = std::min(p.fc, N - n0);
     const int64_t pc = (int64_t)nf * T;
-    char* hc = h + (size_t)n0 * T * C * es;
+    char* hc = h + (size_t)n0 * T * C * 4;
     char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
     char* catn = ws;
-    char* u = ws + (size_t)pc * (C + Cd) * es;
-    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, hc, partH(c), nf, T, C));
+    char* u = ws + align_up((size_t)pc * (C + Cd) * es);  // fp32
+    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, hc, partH(c), nf, T, C));
     LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, dc, partD(c), nf, T / 4, Cd));
     LC_LAUNCH(c, LC_K_GN_FINAL,
               launch_gn_finalize(c->cs, partH(c), C, stat_splits(T), T, 1.f, partD(c), Cd, stat_splits(T / 4), T / 4,
                                  4.f, w.up_gn.gamma, w.up_gn.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), nf));
     LC_LAUNCH(c, LC_K_CAT_APPLY,
               launch_concat_apply(c->cs, g.dtype, hc, dc, catn, nf, g.H, g.W, C, Cd, scale_p(c), shift_p(c)));
-    LC_LAUNCH(c, LC_K_CONV_UP, launch_conv(c->cs, conv_desc(g, w.up, C + Cd, C, nf, g.H, g.W, 1, catn, nullptr, u)));
+    LC_LAUNCH(c, LC_K_CONV_UP, launch_conv(c->cs, conv_desc(g, w.up, C + Cd, C, nf, g.H, g.W, 1, catn, nullptr, u, 0, 1)));
     lc_status s = gn_full(c, u, nf, T, C, w.out_gn, catn, 1);
     if (s != LC_OK) return s;
     ConvDesc d = conv_desc(g, w.out, C, 16, nf, g.H, g.W, 1, catn, nullptr,
-                           (char*)eps + (size_t)n0 * g.C_lat * T * es);
+                           (char*)eps + (size_t)n0 * g.C_lat * T * es, 0, 0);
     d.Cout_store = g.C_lat;
     d.planar_out = 1;
     LC_LAUNCH(c, LC_K_CONV_OUT, launch_conv(c->cs, d));
@@ -773,10 +776,10 @@ lc_status lc_op_conv3x3(lc_ctx* c, int layer, const void* x, const void* res, vo
   if (!x || !y) return fail(c, LC_ERR_ARG, "NULL tensor");
   const lc_config& g = c->cfg;
   ConvDesc d;
-  if (layer >= LC_L_RES0 && layer < LC_L_RES0 + g.n_res) d = conv_desc(g, c->pw.res[layer], g.C, g.C, frames, g.H, g.W, 1, x, res, y);
-  else if (layer == LC_L_DRES) d = conv_desc(g, c->pw.dres, g.C_deep, g.C_deep, frames, g.H / 2, g.W / 2, 1, x, res, y);
-  else if (layer == LC_L_UP) d = conv_desc(g, c->pw.up, g.C + g.C_deep, g.C, frames, g.H, g.W, 1, x, res, y);
-  else if (layer == LC_L_DOWN) d = conv_desc(g, c->pw.down, g.C, g.C_deep, frames, g.H, g.W, 2, x, res, y);
+  if (layer >= LC_L_RES0 && layer < LC_L_RES0 + g.n_res) d = conv_desc(g, c->pw.res[layer], g.C, g.C, frames, g.H, g.W, 1, x, res, y, 0, 1);
+  else if (layer == LC_L_DRES) d = conv_desc(g, c->pw.dres, g.C_deep, g.C_deep, frames, g.H / 2, g.W / 2, 1, x, res, y, 0, 0);
+  else if (layer == LC_L_UP) d = conv_desc(g, c->pw.up, g.C + g.C_deep, g.C, frames, g.H, g.W, 1, x, res, y, 0, 1);
+  else if (layer == LC_L_DOWN) d = conv_desc(g, c->pw.down, g.C, g.C_deep, frames, g.H, g.W, 2, x, res, y, 1, 1);
   else return fail(c, LC_ERR_ARG, "layer %d is not a 3x3 convolution", layer);
   const int kind = layer == LC_L_UP ? LC_K_CONV_UP : (layer == LC_L_DOWN || layer == LC_L_DRES) ? LC_K_DEEP : LC_K_CONV_RES;
   LC_LAUNCH(c, kind, launch_conv(c->cs, d));
@@ -789,7 +792,7 @@ lc_status lc_op_qkv(lc_ctx* c, int layer, const void* x, void* qkv, int64_t rows
   if (!x || !qkv || rows <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
   if (layer != LC_L_SATTN && layer != LC_L_TATTN) return fail(c, LC_ERR_ARG, "layer %d is not an attention block", layer);
   const AttnW& a = layer == LC_L_SATTN ? c->pw.sattn : c->pw.tattn;
-  LC_LAUNCH(c, LC_K_QKV, launch_conv(c->cs, linear_desc(c->cfg, a.wqkv, nullptr, c->cfg.C, 3 * c->cfg.C, rows, dense_map(), x, nullptr, qkv)));
+  LC_LAUNCH(c, LC_K_QKV, launch_conv(c->cs, linear_desc(c->cfg, a.wqkv, nullptr, c->cfg.C, 3 * c->cfg.C, rows, dense_map(), x, nullptr, qkv, 0)));
   return LC_OK;
 }
 
@@ -799,7 +802,7 @@ lc_status lc_op_proj(lc_ctx* c, int layer, const void* a_in, const void* res, vo
   if (!a_in || !y || rows <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
   if (layer != LC_L_SATTN && layer != LC_L_TATTN) return fail(c, LC_ERR_ARG, "layer %d is not an attention block", layer);
   const AttnW& a = layer == LC_L_SATTN ? c->pw.sattn : c->pw.tattn;
-  LC_LAUNCH(c, LC_K_PROJ, launch_conv(c->cs, linear_desc(c->cfg, a.wo, a.bo, c->cfg.C, c->cfg.C, rows, dense_map(), a_in, res, y)));
+  LC_LAUNCH(c, LC_K_PROJ, launch_conv(c->cs, linear_desc(c->cfg, a.wo, a.bo, c->cfg.C, c->cfg.C, rows, dense_map(), a_in, res, y, 1)));
   return LC_OK;
 }
 
@@ -837,7 +840,7 @@ lc_status lc_op_concat_norm(lc_ctx* c, const void* skip, const void* deep, void*
   if (!skip || !deep || !catn) return fail(c, LC_ERR_ARG, "NULL tensor");
   const lc_config& g = c->cfg;
   const int T = g.H * g.W, C = g.C, Cd = g.C_deep;
-  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, skip, partH(c), frames, T, C));
+  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, skip, partH(c), frames, T, C));
   LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, deep, partD(c), frames, T / 4, Cd));
   LC_LAUNCH(c, LC_K_GN_FINAL,
             launch_gn_finalize(c->cs, partH(c), C, stat_splits(T), T, 1.f, partD(c), Cd, stat_splits(T / 4), T / 4, 4.f,
@@ -858,7 +861,7 @@ lc_status lc_op_conv_out(lc_ctx* c, const void* u, void* eps, int frames) {
   char* un = ws_ptr(c);
   s = gn_full(c, u, frames, T, g.C, c->pw.out_gn, un, 1);
   if (s != LC_OK) return s;
-  ConvDesc d = conv_desc(g, c->pw.out, g.C, 16, frames, g.H, g.W, 1, un, nullptr, eps);
+  ConvDesc d = conv_desc(g, c->pw.out, g.C, 16, frames, g.H, g.W, 1, un, nullptr, eps, 0, 0);
   d.Cout_store = g.C_lat;
   d.planar_out = 1;
   LC_LAUNCH(c, LC_K_CONV_OUT, launch_conv(c->cs, d));

@@ -48,6 +48,41 @@ template <class T> __device__ __forceinline__ Vec16<T> zero16() {
   return z;
 }
 
+// N consecutive elements as floats, moved in 16-byte packets (N * sizeof(T) is a multiple of 16).
+template <class T, int N> __device__ __forceinline__ void load_f(const T* p, float (&v)[N]) {
+  constexpr int PN = Vec16<T>::N;
+  static_assert(N % PN == 0, "whole packets");
+#pragma unroll
+  for (int k = 0; k < N / PN; ++k) {
+    Vec16<T> t = load16(p + k * PN);
+#pragma unroll
+    for (int e = 0; e < PN; ++e) v[k * PN + e] = t.get(e);
+  }
+}
+template <class T, int N> __device__ __forceinline__ void store_f(T* p, const float (&v)[N]) {
+  constexpr int PN = Vec16<T>::N;
+  static_assert(N % PN == 0, "whole packets");
+#pragma unroll
+  for (int k = 0; k < N / PN; ++k) {
+    Vec16<T> t;
+#pragma unroll
+    for (int e = 0; e < PN; ++e) t.set(e, v[k * PN + e]);
+    store16(p + k * PN, t);
+  }
+}
+// One 16-byte packet of MFMA operand type T gathered from memory of type XT (same type: a plain
+// load; float memory feeding bf16 operands: two loads and a round-to-nearest-even conversion).
+template <class XT, class T> __device__ __forceinline__ Vec16<T> load_packet(const XT* p) {
+  float v[Vec16<T>::N];
+  load_f<XT, Vec16<T>::N>(p, v);
+  Vec16<T> o;
+#pragma unroll
+  for (int e = 0; e < Vec16<T>::N; ++e) o.set(e, v[e]);
+  return o;
+}
+template <> __device__ __forceinline__ Vec16<bf16_t> load_packet<bf16_t, bf16_t>(const bf16_t* p) { return load16(p); }
+template <> __device__ __forceinline__ Vec16<float> load_packet<float, float>(const float* p) { return load16(p); }
+
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
 // ---------------------------------------------------------------------------------------

@@ -31,7 +31,9 @@ constexpr int kLdsRow = 144;    // LDS row stride in bytes
 template <int BCO, int BPX>
 constexpr int conv_lds_bytes() { return 2 * (BCO + BPX) * kLdsRow; }
 
-template <class T, int TAPS, int STRIDE, int WCO, int WPX, int CO_T, int PX_T, bool PLANAR>
+// T: MFMA operand type (type of w and of the LDS tiles); XT: type of x in memory (T, or float that is
+// rounded to T while staged); OT: type of y. A residual, when given, is always fp32.
+template <class T, class XT, class OT, int TAPS, int STRIDE, int WCO, int WPX, int CO_T, int PX_T, bool PLANAR>
 __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a) {
   constexpr int VEC = Vec16<T>::N;
   constexpr int BKC = kRowBytes / (int)sizeof(T);  // K elements per step
@@ -49,7 +51,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int wco = wid / WPX, wpx = wid % WPX;
   const int co0 = blockIdx.y * BCO;
-  const T* __restrict__ X = (const T*)a.x;
+  const XT* __restrict__ X = (const XT*)a.x;
   const T* __restrict__ Wt = (const T*)a.w;
 
   // ---- which pixels this workgroup owns
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a) {
       } else {
         off = (row0 + lrow + 32 * i) * a.Cin + kofs;
       }
-      xv[i] = ok ? load16(X + off) : zero16<T>();
+      xv[i] = ok ? load_packet<XT, T>(X + off) : zero16<T>();
     }
 #pragma unroll
     for (int i = 0; i < WP; ++i) {
@@ -151,8 +153,8 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a) {
   }
 
   // ---- epilogue: lane holds channels co + 0..3 of pixel (tile j, column fr)
-  T* Y = (T*)a.y;
-  const T* R = (const T*)a.res;  // may alias Y (in-place residual)
+  OT* Y = (OT*)a.y;
+  const float* R = (const float*)a.res;  // may alias Y (in-place residual)
 #pragma unroll
   for (int j = 0; j < PX_T; ++j) {
     const int p = wpx * PX_T * 16 + j * 16 + fr;
@@ -177,7 +179,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a) {
         for (int r = 0; r < 4; ++r) {
           if (co + r < a.Cout_store) {
             float v = acc[i][j][r] + (a.bias ? a.bias[co + r] : 0.f);
-            Y[(((int64_t)frame * a.Cout_store + co + r) * a.Ho + oy) * a.Wo + ox] = from_f32<T>(v);
+            Y[(((int64_t)frame * a.Cout_store + co + r) * a.Ho + oy) * a.Wo + ox] = from_f32<OT>(v);
           }
         }
       } else {
@@ -186,22 +188,17 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = acc[i][j][r] + (a.bias ? a.bias[co + r] : 0.f);
         const int64_t o = orow * a.Cout_store + co;
-        if (sizeof(T) == 2) {
-          if (R) {
-            bf16x4 rv = *reinterpret_cast<const bf16x4*>((const bf16_t*)R + o);
+        if (R) {
+          f32x4 rv = *reinterpret_cast<const f32x4*>(R + o);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] += static_cast<float>(rv[r]);
-          }
+          for (int r = 0; r < 4; ++r) v[r] += rv[r];
+        }
+        if constexpr (sizeof(OT) == 2) {
           bf16x4 ov;
 #pragma unroll
           for (int r = 0; r < 4; ++r) ov[r] = static_cast<bf16_t>(v[r]);
           *reinterpret_cast<bf16x4*>((bf16_t*)Y + o) = ov;
         } else {
-          if (R) {
-            f32x4 rv = *reinterpret_cast<const f32x4*>((const float*)R + o);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] += rv[r];
-          }
           *reinterpret_cast<f32x4*>((float*)Y + o) = f32x4{v[0], v[1], v[2], v[3]};
         }
       }
@@ -209,11 +206,11 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a) {
   }
 }
 
-template <class T, int TAPS, int STRIDE, int WCO, int WPX, int CO_T, int PX_T, bool PLANAR>
+template <class T, class XT, class OT, int TAPS, int STRIDE, int WCO, int WPX, int CO_T, int PX_T, bool PLANAR>
 static hipError_t run(hipStream_t s, const ConvDesc& d) {
   constexpr int BCO = WCO * CO_T * 16, BPX = WPX * PX_T * 16;
   constexpr int lds = conv_lds_bytes<BCO, BPX>();
-  auto kern = conv_kernel<T, TAPS, STRIDE, WCO, WPX, CO_T, PX_T, PLANAR>;
+  auto kern = conv_kernel<T, XT, OT, TAPS, STRIDE, WCO, WPX, CO_T, PX_T, PLANAR>;
   static bool attr_done = false;  // per instantiation
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -239,29 +236,37 @@ static hipError_t run(hipStream_t s, const ConvDesc& d) {
   return hipGetLastError();
 }
 
-template <class T>
-static hipError_t dispatch(hipStream_t s, const ConvDesc& d) {
-  const int esz = (int)sizeof(T);
-  if (d.Cin % (kRowBytes / esz) != 0) return hipErrorInvalidValue;
-  if (d.planar_out) {
-    if (d.taps != 9 || d.stride != 1 || d.Cout != 16 || d.res) return hipErrorInvalidValue;
-    return run<T, 9, 1, 1, 4, 1, 2, true>(s, d);
-  }
-  if (d.Cout_store != d.Cout || d.Cout % 4) return hipErrorInvalidValue;
+template <class T, class XT, class OT>
+static hipError_t dispatch_shape(hipStream_t s, const ConvDesc& d) {
   const bool wide = d.Cout % 160 == 0;
   if (!wide && d.Cout % 64 != 0) return hipErrorInvalidValue;
   if (d.taps == 9 && d.stride == 1)
-    return wide ? run<T, 9, 1, 2, 2, 5, 4, false>(s, d) : run<T, 9, 1, 2, 2, 2, 4, false>(s, d);
+    return wide ? run<T, XT, OT, 9, 1, 2, 2, 5, 4, false>(s, d) : run<T, XT, OT, 9, 1, 2, 2, 2, 4, false>(s, d);
   if (d.taps == 9 && d.stride == 2)
-    return wide ? run<T, 9, 2, 2, 2, 5, 4, false>(s, d) : run<T, 9, 2, 2, 2, 2, 4, false>(s, d);
+    return wide ? run<T, XT, OT, 9, 2, 2, 2, 5, 4, false>(s, d) : run<T, XT, OT, 9, 2, 2, 2, 2, 4, false>(s, d);
   if (d.taps == 1)
-    return wide ? run<T, 1, 1, 2, 2, 5, 4, false>(s, d) : run<T, 1, 1, 2, 2, 2, 4, false>(s, d);
+    return wide ? run<T, XT, OT, 1, 1, 2, 2, 5, 4, false>(s, d) : run<T, XT, OT, 1, 1, 2, 2, 2, 4, false>(s, d);
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_conv(hipStream_t s, const ConvDesc& d) {
   if (d.taps == 9 && (d.H % d.stride || d.W % d.stride)) return hipErrorInvalidValue;
-  return d.dt == kBF16 ? dispatch<bf16_t>(s, d) : dispatch<float>(s, d);
+  const int esz = (int)dtype_size(d.dt);
+  if (d.Cin % (kRowBytes / esz) != 0) return hipErrorInvalidValue;
+  if (d.planar_out) {
+    if (d.taps != 9 || d.stride != 1 || d.Cout != 16 || d.res || d.x_f32 || d.y_f32) return hipErrorInvalidValue;
+    return d.dt == kBF16 ? run<bf16_t, bf16_t, bf16_t, 9, 1, 1, 4, 1, 2, true>(s, d)
+                         : run<float, float, float, 9, 1, 1, 4, 1, 2, true>(s, d);
+  }
+  if (d.Cout_store != d.Cout || d.Cout % 4) return hipErrorInvalidValue;
+  if (d.dt == kF32) return dispatch_shape<float, float, float>(s, d);
+  if (d.x_f32) {
+    if (!d.y_f32 || d.taps != 9 || d.stride != 2) return hipErrorInvalidValue;  // only the down conv reads fp32
+    return d.Cout % 160 == 0 ? run<bf16_t, float, float, 9, 2, 2, 2, 5, 4, false>(s, d)
+                             : run<bf16_t, float, float, 9, 2, 2, 2, 2, 4, false>(s, d);
+  }
+  if (d.taps == 9 && d.stride == 2) return hipErrorInvalidValue;
+  return d.y_f32 ? dispatch_shape<bf16_t, bf16_t, float>(s, d) : dispatch_shape<bf16_t, bf16_t, bf16_t>(s, d);
 }
 
 }  // namespace lc

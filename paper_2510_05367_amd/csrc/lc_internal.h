@@ -27,16 +27,20 @@ hipError_t launch_gn_finalize(hipStream_t s, const float* partA, int CA, int spl
                               const float* gamma, const float* beta, int groups, float eps,
                               float* scale, float* shift, int frames);
 // y[r][c] = act(x[map(r)][c] * scale[f][c] + shift[f][c]),  f = r / map.rows_per_seg.
-hipError_t launch_gn_apply(hipStream_t s, int dt, const void* x, RowMap map, void* y, int64_t rows, int C,
+// x has element type xdt, y element type ydt (fp32 -> fp32, fp32 -> bf16 or bf16 -> bf16).
+hipError_t launch_gn_apply(hipStream_t s, int xdt, int ydt, const void* x, RowMap map, void* y, int64_t rows, int C,
                            const float* scale, const float* shift, int silu);
-// catn[r][0:C] from skip[r], catn[r][C:C+Cd] from deep[(frame, y/2, x/2)], normalised + SiLU.
+// catn[r][0:C] from skip[r] (always fp32: the residual stream), catn[r][C:C+Cd] from
+// deep[(frame, y/2, x/2)] (element type dt, like catn), normalised + SiLU.
 hipError_t launch_concat_apply(hipStream_t s, int dt, const void* skip, const void* deep, void* catn,
                                int frames, int H, int W, int C, int Cd, const float* scale,
                                const float* shift);
 
 // ---- implicit-GEMM convolution / linear layers (MFMA) ---------------------------------------
 struct ConvDesc {
-  int dt;
+  int dt;      // MFMA operand type = type of w (and of x unless x_f32)
+  int x_f32;   // 1: x is fp32 in memory and is rounded to dt while it is staged
+  int y_f32;   // 1: y is stored as fp32 (residual streams); res, when given, is always fp32
   int taps;    // 9 (3x3, zero padding 1) or 1 (per-row linear layer)
   int stride;  // 1 or 2 (taps == 9 only)
   int Cin, Cout;  // Cout here is the padded width of `w` rows, a multiple of the cout tile
@@ -65,7 +69,7 @@ hipError_t launch_temporal_attention(hipStream_t s, int dt, const void* qkv, voi
                                      int heads, int d);
 
 // ---- small kernels -------------------------------------------------------------------------
-// h[frames*H*W][C] = conv3x3(x[frames][Cl][H][W]); w_packed float [Cl*9][C], bias float [C].
+// h[frames*H*W][C] (fp32) = conv3x3(x[frames][Cl][H][W] of type dt); w_packed float [Cl*9][C], bias float [C].
 hipError_t launch_conv_in(hipStream_t s, int dt, const void* x, void* h, int frames, int H, int W, int Cl, int C,
                           const float* w_packed, const float* bias);
 // planar [frames][C][HW] <-> channels-last [frames][HW][C]

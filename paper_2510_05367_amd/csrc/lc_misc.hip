@@ -5,13 +5,13 @@
 namespace lc {
 
 // ---------------------------------------------------------------------------------------------
-// conv_in: 3x3, zero padding, C_lat (<= 16) input channels. One thread = one pixel x one 16-byte
-// packet of output channels; the packed weights [C_lat*9][C] are read through the vector cache.
+// conv_in: 3x3, zero padding, C_lat (<= 16) input channels, fp32 output. One thread = one pixel x 8
+// output channels; the packed weights [C_lat*9][C] are read through the vector cache.
 template <class T>
-__global__ __launch_bounds__(256) void conv_in_kernel(const T* __restrict__ x, T* __restrict__ h, int frames, int H,
+__global__ __launch_bounds__(256) void conv_in_kernel(const T* __restrict__ x, float* __restrict__ h, int frames, int H,
                                                       int W, int Cl, int C, const float* __restrict__ wp,
                                                       const float* __restrict__ bias) {
-  constexpr int VEC = Vec16<T>::N;
+  constexpr int VEC = 8;
   const int cv = C / VEC;
   const int64_t total = (int64_t)frames * H * W * cv;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -41,20 +41,16 @@ __global__ __launch_bounds__(256) void conv_in_kernel(const T* __restrict__ x, T
       }
     }
   }
-  Vec16<T> o;
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) o.set(e, acc[e]);
-  store16(h + pix * C + c0, o);
+  store_f<float, VEC>(h + pix * C + c0, acc);
 }
 
 hipError_t launch_conv_in(hipStream_t s, int dt, const void* x, void* h, int frames, int H, int W, int Cl, int C,
                           const float* w_packed, const float* bias) {
   if (frames <= 0) return hipSuccess;
-  const int vec = dt == kBF16 ? 8 : 4;
-  const int64_t total = (int64_t)frames * H * W * (C / vec);
+  const int64_t total = (int64_t)frames * H * W * (C / 8);
   const unsigned blocks = (unsigned)((total + 255) / 256);
   if (dt == kBF16)
-    conv_in_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)x, (bf16_t*)h, frames, H, W, Cl, C, w_packed, bias);
+    conv_in_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)x, (float*)h, frames, H, W, Cl, C, w_packed, bias);
   else
     conv_in_kernel<float><<<blocks, 256, 0, s>>>((const float*)x, (float*)h, frames, H, W, Cl, C, w_packed, bias);
   return hipGetLastError();

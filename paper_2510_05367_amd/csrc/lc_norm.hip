@@ -140,11 +140,11 @@ hipError_t launch_gn_finalize(hipStream_t s, const float* partA, int CA, int spl
 }
 
 // ---------------------------------------------------------------------------------------------
-template <class T, bool SILU>
-__global__ __launch_bounds__(256) void gn_apply_kernel(const T* __restrict__ x, RowMap map, T* __restrict__ y,
+template <class XT, class YT, bool SILU>
+__global__ __launch_bounds__(256) void gn_apply_kernel(const XT* __restrict__ x, RowMap map, YT* __restrict__ y,
                                                        int64_t rows, int C, const float* __restrict__ scale,
                                                        const float* __restrict__ shift) {
-  constexpr int VEC = Vec16<T>::N;
+  constexpr int VEC = sizeof(XT) == 4 && sizeof(YT) == 4 ? 4 : 8;  // channels per thread
   const int cv = C / VEC;
   const int64_t total = rows * cv;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -152,41 +152,45 @@ __global__ __launch_bounds__(256) void gn_apply_kernel(const T* __restrict__ x, 
   const int64_t r = i / cv;
   const int c0 = (int)(i - r * cv) * VEC;
   const int64_t f = r / map.rows_per_seg;
-  Vec16<T> v = load16(x + map(r) * C + c0);
-  const float* a = scale + f * C + c0;
-  const float* b = shift + f * C + c0;
-  Vec16<T> o;
+  float v[VEC], a[VEC], b[VEC];
+  load_f<XT, VEC>(x + map(r) * C + c0, v);
+  load_f<float, VEC>(scale + f * C + c0, a);
+  load_f<float, VEC>(shift + f * C + c0, b);
 #pragma unroll
   for (int k = 0; k < VEC; ++k) {
-    float t = fmaf(v.get(k), a[k], b[k]);
-    o.set(k, SILU ? silu_f(t) : t);
+    const float t = fmaf(v[k], a[k], b[k]);
+    v[k] = SILU ? silu_f(t) : t;
   }
-  store16(y + r * C + c0, o);
+  store_f<YT, VEC>(y + r * C + c0, v);
 }
 
-hipError_t launch_gn_apply(hipStream_t s, int dt, const void* x, RowMap map, void* y, int64_t rows, int C,
+hipError_t launch_gn_apply(hipStream_t s, int xdt, int ydt, const void* x, RowMap map, void* y, int64_t rows, int C,
                            const float* scale, const float* shift, int silu) {
   if (rows <= 0) return hipSuccess;
-  const int vec = dt == kBF16 ? 8 : 4;
+  const int vec = (xdt == kF32 && ydt == kF32) ? 4 : 8;
   const int64_t total = rows * (C / vec);
   const unsigned blocks = (unsigned)((total + 255) / 256);
-#define LC_GO(T, S) gn_apply_kernel<T, S><<<blocks, 256, 0, s>>>((const T*)x, map, (T*)y, rows, C, scale, shift)
-  if (dt == kBF16) {
-    if (silu) LC_GO(bf16_t, true); else LC_GO(bf16_t, false);
-  } else {
-    if (silu) LC_GO(float, true); else LC_GO(float, false);
-  }
+#define LC_GO(XT, YT, S) \
+  gn_apply_kernel<XT, YT, S><<<blocks, 256, 0, s>>>((const XT*)x, map, (YT*)y, rows, C, scale, shift)
+#define LC_GO2(XT, YT) do { if (silu) LC_GO(XT, YT, true); else LC_GO(XT, YT, false); } while (0)
+  if (xdt == kF32 && ydt == kF32) LC_GO2(float, float);
+  else if (xdt == kF32 && ydt == kBF16) LC_GO2(float, bf16_t);
+  else if (xdt == kBF16 && ydt == kBF16) LC_GO2(bf16_t, bf16_t);
+  else return hipErrorInvalidValue;
+#undef LC_GO2
 #undef LC_GO
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
-template <class T>
-__global__ __launch_bounds__(256) void concat_apply_kernel(const T* __restrict__ skip, const T* __restrict__ deep,
+// ST: type of the skip feature (the fp32 residual stream), T: type of the cached deep feature and
+// of the normalised output.
+template <class ST, class T>
+__global__ __launch_bounds__(256) void concat_apply_kernel(const ST* __restrict__ skip, const T* __restrict__ deep,
                                                            T* __restrict__ catn, int frames, int H, int W, int C,
                                                            int Cd, const float* __restrict__ scale,
                                                            const float* __restrict__ shift) {
-  constexpr int VEC = Vec16<T>::N;
+  constexpr int VEC = sizeof(T) == 4 ? 4 : 8;
   const int Ct = C + Cd;
   const int cv = Ct / VEC;
   const int64_t total = (int64_t)frames * H * W * cv;
@@ -197,20 +201,19 @@ __global__ __launch_bounds__(256) void concat_apply_kernel(const T* __restrict__
   const int hw = H * W;
   const int f = (int)(r / hw);
   const int p = (int)(r - (int64_t)f * hw);
-  Vec16<T> v;
+  float v[VEC], a[VEC], b[VEC];
   if (c0 < C) {
-    v = load16(skip + r * C + c0);
+    load_f<ST, VEC>(skip + r * C + c0, v);
   } else {
     const int yy = p / W, xx = p - yy * W;
     const int64_t dr = ((int64_t)f * (H / 2) + (yy >> 1)) * (W / 2) + (xx >> 1);
-    v = load16(deep + dr * Cd + (c0 - C));
+    load_f<T, VEC>(deep + dr * Cd + (c0 - C), v);
   }
-  const float* a = scale + (int64_t)f * Ct + c0;
-  const float* b = shift + (int64_t)f * Ct + c0;
-  Vec16<T> o;
+  load_f<float, VEC>(scale + (int64_t)f * Ct + c0, a);
+  load_f<float, VEC>(shift + (int64_t)f * Ct + c0, b);
 #pragma unroll
-  for (int k = 0; k < VEC; ++k) o.set(k, silu_f(fmaf(v.get(k), a[k], b[k])));
-  store16(catn + r * Ct + c0, o);
+  for (int k = 0; k < VEC; ++k) v[k] = silu_f(fmaf(v[k], a[k], b[k]));
+  store_f<T, VEC>(catn + r * Ct + c0, v);
 }
 
 hipError_t launch_concat_apply(hipStream_t s, int dt, const void* skip, const void* deep, void* catn, int frames,
@@ -220,11 +223,11 @@ hipError_t launch_concat_apply(hipStream_t s, int dt, const void* skip, const vo
   const int64_t total = (int64_t)frames * H * W * ((C + Cd) / vec);
   const unsigned blocks = (unsigned)((total + 255) / 256);
   if (dt == kBF16)
-    concat_apply_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)skip, (const bf16_t*)deep, (bf16_t*)catn,
-                                                       frames, H, W, C, Cd, scale, shift);
+    concat_apply_kernel<float, bf16_t><<<blocks, 256, 0, s>>>((const float*)skip, (const bf16_t*)deep, (bf16_t*)catn,
+                                                              frames, H, W, C, Cd, scale, shift);
   else
-    concat_apply_kernel<float><<<blocks, 256, 0, s>>>((const float*)skip, (const float*)deep, (float*)catn,
-                                                      frames, H, W, C, Cd, scale, shift);
+    concat_apply_kernel<float, float><<<blocks, 256, 0, s>>>((const float*)skip, (const float*)deep, (float*)catn,
+                                                             frames, H, W, C, Cd, scale, shift);
   return hipGetLastError();
 }
 

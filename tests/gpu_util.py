@@ -56,3 +56,12 @@ def dev(stage, a):
 
 def host(t):
     return t.float().cpu().numpy().astype(np.float64)
+
+
+def dev32(stage, a):
+    """numpy -> float32 device tensor (tensors of the fp32 residual stream)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(stage.device)
+
+
+def empty32(stage, *shape):
+    return torch.empty(*shape, dtype=torch.float32, device=stage.device)

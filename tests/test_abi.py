@@ -71,9 +71,9 @@ def test_footprint_model_scales_with_chunk_not_with_frames():
     full = lcb.lc_workspace_bytes(c, 0, 0)
     sizes = [lcb.lc_workspace_bytes(c, fc, 0) for fc in (16, 8, 4, 2, 1)]
     assert all(a > b for a, b in zip([full] + sizes, sizes))
-    # persistent part: skip feature + dev_slots cache entries (+ small statistics scratch)
+    # persistent part: fp32 skip feature + dev_slots cache entries (+ small statistics scratch)
     es = 2
-    persistent = cfg.N * cfg.T * cfg.C * es + 2 * lcb.lc_cache_entry_bytes(c)
+    persistent = cfg.N * cfg.T * cfg.C * 4 + 2 * lcb.lc_cache_entry_bytes(c)
     chunk1 = 4 * cfg.C * cfg.T * es  # one frame of (normalised copy + q,k,v)
     assert sizes[-1] - persistent < chunk1 + 16e6
     # chunk scratch is linear in the frame chunk
