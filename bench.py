@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the cache-hit denoising step on one MI355X.
+
+A "step" is one pass of the whole hot path (conv_in, residual blocks, spatial and temporal
+attention blocks, fetch of the cached deep feature, skip-concat, up conv, conv_out) over one batch
+of seeded synthetic input shaped like the AnimateDiff workload (batch 2 x 16 frames of 4 x 64 x 64
+latents, 320 channels, 8 heads of 40, frame chunk 4), with every input already resident in HBM.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # dense MFMA peaks of MI355X, TFLOP/s
+PEAK_HBM_GBS = 8000.0
+
+
+def family_flops(cfg):
+    """Algorithmic FLOPs per cached step of each MFMA kernel family."""
+    P, C, Cd = cfg.N * cfg.T, cfg.C, cfg.C_deep
+    return {
+        "conv_res": cfg.n_res * 2.0 * 9 * C * C * P,
+        "conv_up": 2.0 * 9 * (C + Cd) * C * P,
+        "qkv": 2 * 6.0 * C * C * P,
+        "proj": 2 * 2.0 * C * C * P,
+        "sattn": 4.0 * cfg.T * cfg.T * cfg.head_dim * cfg.heads * cfg.N,
+        "tattn": 4.0 * cfg.F * cfg.F * cfg.head_dim * cfg.heads * cfg.B * cfg.T,
+        "conv_in": 2.0 * 9 * cfg.C_lat * C * P,
+        "conv_out": 2.0 * 9 * cfg.C_lat * C * P,
+    }
+
+
+def family_bytes(cfg):
+    """Algorithmic HBM bytes per cached step of each bandwidth kernel family (one read + one write
+    of what the operator must touch; fp32 residual stream = 4 bytes, operands = element size)."""
+    P, C, Cd = cfg.N * cfg.T, cfg.C, cfg.C_deep
+    es = 2 if cfg.dtype == "bf16" else 4
+    n_norm = cfg.n_res + 3  # residual blocks, two attention pre-norms, conv_out's norm
+    return {
+        "gn_stats": (n_norm + 1) * P * C * 4 + (P // 4) * Cd * es,   # reads only (+ concat: skip and deep)
+        "gn_apply": n_norm * P * C * (4 + es),
+        "cat_apply": P * C * 4 + (P // 4) * Cd * es + P * (C + Cd) * es,
+        "conv_in": P * cfg.C_lat * es + P * C * 4,
+        "conv_out": P * C * es + P * cfg.C_lat * es,
+        "tattn": 4 * P * C * es,
+    }
+
+
+def cpu_baseline(cfg, w, budget_frames=1):
+    """The float64 oracle, as it stands, on a bounded sample: a cached step over `budget_frames`
+    frames (batch 1) of the same per-frame shape."""
+    import numpy as np
+    from oracle import lightcache_oracle as lo
+    from paper_2510_05367_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    small = cfg.with_(B=1, F=budget_frames)
+    x = synth.make_latents(small, 1)
+    deep = synth.make_deep(small, 2)
+    orc = lo.Oracle(small, {k: v.astype(np.float64) for k, v in w.items()})
+    orc.cache_write(0, deep)
+    t0 = time.time()
+    orc.cached_step(x, 0)
+    dt = time.time() - t0
+    return {"value": small.cached_step_flops() / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"one cached step of the float64 numpy oracle over {budget_frames} frames (batch 1) of the "
+                      f"same {cfg.H}x{cfg.W}x{cfg.C} per-frame shape ({small.cached_step_flops() / 1e9:.1f} GFLOP)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="animatediff", choices=["tiny", "animatediff", "svdxt", "stress"])
+    ap.add_argument("--frame-chunk", type=int, default=None)
+    ap.add_argument("--token-chunk", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-breakdown", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_2510_05367_amd import binding as lcb
+    from paper_2510_05367_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("no GPU visible: the HIP path cannot run and there is no CPU fallback")
+    if not os.path.exists(lcb.LIB_PATH):
+        from paper_2510_05367_amd import build as lcbuild
+        lcbuild.build_library()
+
+    cfg = synth.CONFIGS[args.workload]
+    fc = cfg.frame_chunk if args.frame_chunk is None else args.frame_chunk
+    tc = cfg.token_chunk if args.token_chunk is None else args.token_chunk
+    w = synth.make_weights(cfg, 0)
+    torch.cuda.reset_peak_memory_stats()
+    stage = lcb.Stage(cfg, w, host_slots=2, dev_slots=2, frame_chunk=fc, token_chunk=tc)
+    x = stage.to_device(synth.make_latents(cfg, 1))
+    eps = stage.empty(*x.shape)
+    stage.cache_write(0, stage.to_device(synth.make_deep(cfg, 2)))
+    stage.sync()
+    K, W = args.steps, args.warmup
+    dom = "conv_up"
+
+    for _ in range(W):
+        stage.cached_step(x, eps, 0)
+    stage.sync()
+
+    # ---- timed region: K cached steps, the dominant kernel bracketed by events on its own stream
+    lcb.lc_set_profiling(stage.ctx, 1 << lcb.LC_K[dom])
+    lcb.lc_get_profile(stage.ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        stage.cached_step(x, eps, 0)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = lcb.lc_get_profile(stage.ctx)
+    lcb.lc_set_profiling(stage.ctx, 0)
+    ms = (t1 - t0) * 1e3 / K
+    flops = cfg.cached_step_flops()
+    tflops = flops / (ms * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[cfg.dtype]
+    fam_fl = family_flops(cfg)
+    d = prof[dom]
+    dom_ms = d["ms"] / max(d["launches"], 1)
+    dom_flops = fam_fl[dom] * K / max(d["launches"], 1)
+    achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "traffic": None,
+                "avg_launch_ms": round(dom_ms, 5), "launches_per_step": d["launches"] // K,
+                "flops_per_launch": dom_flops}
+
+    # ---- per-family breakdown (a separate profiled pass; brackets add small gaps)
+    breakdown = None
+    if not args.no_breakdown:
+        lcb.lc_set_profiling(stage.ctx, (1 << len(lcb.KERNEL_FAMILIES)) - 1)
+        nb = min(K, 5)
+        for _ in range(nb):
+            stage.cached_step(x, eps, 0)
+        pf = lcb.lc_get_profile(stage.ctx)
+        lcb.lc_set_profiling(stage.ctx, 0)
+        fam_by = family_bytes(cfg)
+        breakdown = {}
+        for name, v in pf.items():
+            if v["launches"] == 0:
+                continue
+            e = {"ms_per_step": round(v["ms"] / nb, 4), "launches_per_step": v["launches"] // nb}
+            if name in fam_fl and name not in ("conv_in", "conv_out", "tattn"):
+                e["tflops"] = round(fam_fl[name] / (v["ms"] / nb * 1e-3) / 1e12, 1)
+                e["frac_mfma_peak"] = round(e["tflops"] / peak, 4)
+            if name in fam_by:
+                e["gbs"] = round(fam_by[name] / (v["ms"] / nb * 1e-3) / 1e9, 1)
+                e["frac_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+            breakdown[name] = e
+
+    # ---- asynchronous swapping: copy alone, step alone (above), step with a prefetch in flight
+    stage.swap_out(0, 0)
+    stage.sync()
+    lcb.lc_reset_stats(stage.ctx)
+    for _ in range(5):
+        stage.swap_in(0, 1)
+    st = lcb.lc_get_stats(stage.ctx)
+    copy_ms = st.ms_in / 5
+    entry = lcb.lc_cache_entry_bytes(stage.ccfg)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        stage.swap_in(0, (i + 1) % 2)      # prefetch for the next step into the other buffer
+        stage.cached_step(x, eps, i % 2)
+    torch.cuda.synchronize()
+    ms_swap = (time.perf_counter() - t0) * 1e3 / K
+    overlap = 1.0 - max(0.0, ms_swap - ms) / copy_ms if copy_ms > 0 else None
+    swap = {"entry_mb": round(entry / 1e6, 1), "h2d_ms": round(copy_ms, 4),
+            "h2d_gbs": round(entry / (copy_ms * 1e-3) / 1e9, 1) if copy_ms > 0 else None,
+            "step_ms_with_prefetch": round(ms_swap, 4),
+            "overlap_frac": None if overlap is None else round(min(1.0, max(0.0, overlap)), 4)}
+
+    stats = lcb.lc_get_stats(stage.ctx)
+    peak_alloc = torch.cuda.max_memory_allocated() + stats.weight_bytes
+    floor = cfg.N * cfg.T * cfg.C * 4 + 2 * entry + stats.weight_bytes + 2 * x.numel() * x.element_size()
+
+    out = {
+        "metric": "shallow-branch TFLOP/s of one cached step (cached-step ms, MFMA util, peak HBM GB alongside)",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: cached step, B={cfg.B} F={cfg.F} latent {cfg.C_lat}x{cfg.H}x{cfg.W}, "
+                               f"C={cfg.C}, C_deep={cfg.C_deep}, {cfg.heads} heads x {cfg.head_dim}, n_res={cfg.n_res}",
+                   "frame_chunk": fc, "token_chunk": tc, "gflop_per_step": round(flops / 1e9, 1)},
+        "cached_step_ms": round(ms, 4), "mfma_util_frac": round(tflops / peak, 4),
+        "peak_hbm_gb": round(peak_alloc / 1e9, 4), "hbm_floor_gb": round(floor / 1e9, 4),
+        "workspace_gb": round(stats.workspace_bytes / 1e9, 4),
+        "roofline": roofline, "swap": swap,
+    }
+    if breakdown is not None:
+        out["breakdown"] = breakdown
+    stage.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
