@@ -187,43 +187,45 @@ lc_status lc_get_profile(lc_ctx* ctx, lc_profile* out /* [host] */);
 /* ---- single operators (the same kernels the steps launch; used by the parity tests and the
  *      benchmark). Activations are in the library's internal channels-last layout
  *      [rows, channels] with rows = frame-major pixels; all pointers [device].
- *      Element types: tensors of the residual stream (the outputs of conv_in, of the RESi / UP /
- *      DOWN convolutions and of proj, every `res` argument, the inputs of group_norm and conv_out
- *      and concat_norm's `skip`) are always float: with bf16 storage the stream that every block
- *      adds into is kept in fp32 and only MFMA operands are rounded. All other tensors (normalised
- *      activations, qkv, attention outputs, cache entries, x, eps) have the cfg dtype.
- *      Each call enqueues on the compute stream. `frames` counts frames of H x W pixels
- *      (H/2 x W/2 where stated). -------------------------------------------------------------- */
+ *      Element types: tensors of the residual stream (h, u, d0 below: what every block adds into)
+ *      are always float: with bf16 storage that stream is kept in fp32 and only MFMA operands are
+ *      rounded. Operand tensors (qkv, attention outputs, cache entries) and the public x / eps
+ *      have the cfg dtype. GroupNorm (+ SiLU), the 2x upsampling and the skip-concat are applied
+ *      inside the loaders of the kernels that consume them, so they appear here only as part of
+ *      the operator they feed. Each call enqueues on the compute stream. `frames` counts frames of
+ *      H x W pixels (H/2 x W/2 where stated) and is at most B*F. ------------------------------- */
 
 typedef enum {
   LC_L_RES0 = 0, /* .. LC_L_RES0 + n_res - 1 */
-  LC_L_SATTN = 8, LC_L_TATTN = 9, LC_L_DRES = 10, LC_L_UP = 11, LC_L_OUT = 12, LC_L_DOWN = 13
+  LC_L_SATTN = 8, LC_L_TATTN = 9, LC_L_DRES = 10
 } lc_layer;
 
-/* y (cfg dtype) = [SiLU](GroupNorm(x (float))) with the scale/shift of `layer`; channels = that
- * layer's input width (C, or C_deep at H/2 x W/2 for LC_L_DRES). */
-lc_status lc_op_group_norm(lc_ctx* ctx, int layer, const void* x, void* y, int frames, int silu);
-/* y = [res +] conv3x3(x) + bias of `layer` (LC_L_RESi, LC_L_DRES at H/2 x W/2, LC_L_UP with
- * C + C_deep input channels, LC_L_DOWN stride 2: x at H x W -> y at H/2 x W/2). res (float) may be
- * NULL or equal to y. x is cfg dtype except for LC_L_DOWN (float: it reads the skip feature); y is
- * float except for LC_L_DRES (cfg dtype: it writes a cache entry). */
-lc_status lc_op_conv3x3(lc_ctx* ctx, int layer, const void* x, const void* res, void* y, int frames);
-/* qkv[rows, 3C] = x[rows, C] [Wq;Wk;Wv]^T of LC_L_SATTN / LC_L_TATTN. */
-lc_status lc_op_qkv(lc_ctx* ctx, int layer, const void* x, void* qkv, int64_t rows);
-/* y[rows, C] (float) = res (float) + a[rows, C] Wo^T + bo of LC_L_SATTN / LC_L_TATTN. res may equal y. */
-lc_status lc_op_proj(lc_ctx* ctx, int layer, const void* a, const void* res, void* y, int64_t rows);
+/* h[frames*H*W, C] (float) = conv_in(x[frames, C_lat, H, W]). */
+lc_status lc_op_conv_in(lc_ctx* ctx, const void* x, void* h, int frames);
+/* Residual block body, y = x + conv3x3(SiLU(GroupNorm(x))), x float, y != x.
+ * LC_L_RESi: [frames*H*W, C], y float. LC_L_DRES: [frames*(H/2)*(W/2), C_deep], y cfg dtype (it
+ * writes a cache entry). */
+lc_status lc_op_res_block(lc_ctx* ctx, int layer, const void* x, void* y, int frames);
+/* qkv[frames*H*W, 3C] (cfg dtype) = GroupNorm(x)[rows, C] [Wq;Wk;Wv]^T of LC_L_SATTN / LC_L_TATTN,
+ * x float, statistics per frame. */
+lc_status lc_op_qkv(lc_ctx* ctx, int layer, const void* x, void* qkv, int frames);
 /* Spatial attention core: per frame and head, softmax(QK^T/sqrt(d))V over the H*W tokens of the
- * frame, for query tokens [q0, q1). qkv [frames*H*W, 3C] -> out [frames*H*W, C]. */
+ * frame, for query tokens [q0, q1). qkv [frames*H*W, 3C] -> out [frames*H*W, C]; rows of other
+ * queries are not written. */
 lc_status lc_op_spatial_attention(lc_ctx* ctx, const void* qkv, void* out, int frames, int q0, int q1);
 /* Temporal attention core: qkv [(B*F) * positions, 3C] (frame-major) -> out [(B*F)*positions, C];
  * per batch element, position and head attention over the F frames. */
 lc_status lc_op_temporal_attention(lc_ctx* ctx, const void* qkv, void* out, int positions);
-/* h[frames*H*W, C] (float) = conv_in(x[frames, C_lat, H, W]). */
-lc_status lc_op_conv_in(lc_ctx* ctx, const void* x, void* h, int frames);
-/* catn[frames*H*W, C + C_deep] = SiLU(GN_up(Concat(skip (float), up2(deep)))) ([FC]); deep is
- * [frames*(H/2)*(W/2), C_deep] channels-last. */
-lc_status lc_op_concat_norm(lc_ctx* ctx, const void* skip, const void* deep, void* catn, int frames);
-/* eps[frames, C_lat, H, W] = conv_out(SiLU(GN_out(u))), u (float) [frames*H*W, C]. */
+/* y[rows, C] (float) = res (float) + a[rows, C] Wo^T + bo of LC_L_SATTN / LC_L_TATTN. res may be
+ * NULL or equal y. */
+lc_status lc_op_proj(lc_ctx* ctx, int layer, const void* a, const void* res, void* y, int64_t rows);
+/* d0[frames*(H/2)*(W/2), C_deep] (float) = stride-2 conv3x3 of x[frames*H*W, C] (float): the first
+ * half of the deep stand-in of the normal step. */
+lc_status lc_op_down_conv(lc_ctx* ctx, const void* x, void* d0, int frames);
+/* u[frames*H*W, C] (float) = conv3x3(SiLU(GroupNorm(Concat(skip, up2(deep))))) ([FC]); skip float
+ * [frames*H*W, C], deep cfg dtype [frames*(H/2)*(W/2), C_deep] (a cache entry, channels-last). */
+lc_status lc_op_up_conv(lc_ctx* ctx, const void* skip, const void* deep, void* u, int frames);
+/* eps[frames, C_lat, H, W] (cfg dtype) = conv_out(SiLU(GroupNorm(u))), u float [frames*H*W, C]. */
 lc_status lc_op_conv_out(lc_ctx* ctx, const void* u, void* eps, int frames);
 
 #ifdef __cplusplus

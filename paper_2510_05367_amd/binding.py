@@ -23,7 +23,7 @@ LC_MAX_RES = 4
 KERNEL_FAMILIES = ["conv_in", "gn_stats", "gn_final", "gn_apply", "conv_res", "qkv", "sattn", "tattn",
                    "proj", "cat_apply", "conv_up", "conv_out", "deep"]
 LC_K = {n: i for i, n in enumerate(KERNEL_FAMILIES)}
-LC_L_RES0, LC_L_SATTN, LC_L_TATTN, LC_L_DRES, LC_L_UP, LC_L_OUT, LC_L_DOWN = 0, 8, 9, 10, 11, 12, 13
+LC_L_RES0, LC_L_SATTN, LC_L_TATTN, LC_L_DRES = 0, 8, 9, 10
 STATUS_NAMES = ["LC_OK", "LC_ERR_ARG", "LC_ERR_SHAPE", "LC_ERR_STATE", "LC_ERR_NOMEM", "LC_ERR_HIP"]
 
 
@@ -89,14 +89,14 @@ PROTOTYPES = {
     "lc_reset_stats": (_I, [_P]),
     "lc_set_profiling": (_I, [_P, C.c_uint32]),
     "lc_get_profile": (_I, [_P, C.POINTER(lc_profile)]),
-    "lc_op_group_norm": (_I, [_P, _I, _P, _P, _I, _I]),
-    "lc_op_conv3x3": (_I, [_P, _I, _P, _P, _P, _I]),
-    "lc_op_qkv": (_I, [_P, _I, _P, _P, _I64]),
-    "lc_op_proj": (_I, [_P, _I, _P, _P, _P, _I64]),
+    "lc_op_conv_in": (_I, [_P, _P, _P, _I]),
+    "lc_op_res_block": (_I, [_P, _I, _P, _P, _I]),
+    "lc_op_qkv": (_I, [_P, _I, _P, _P, _I]),
     "lc_op_spatial_attention": (_I, [_P, _P, _P, _I, _I, _I]),
     "lc_op_temporal_attention": (_I, [_P, _P, _P, _I]),
-    "lc_op_conv_in": (_I, [_P, _P, _P, _I]),
-    "lc_op_concat_norm": (_I, [_P, _P, _P, _P, _I]),
+    "lc_op_proj": (_I, [_P, _I, _P, _P, _P, _I64]),
+    "lc_op_down_conv": (_I, [_P, _P, _P, _I]),
+    "lc_op_up_conv": (_I, [_P, _P, _P, _P, _I]),
     "lc_op_conv_out": (_I, [_P, _P, _P, _I]),
 }
 
@@ -230,20 +230,16 @@ def lc_get_profile(ctx) -> Dict[str, Dict[str, float]]:
     return {n: {"ms": p.ms[i], "launches": int(p.launches[i])} for i, n in enumerate(KERNEL_FAMILIES)}
 
 
-def lc_op_group_norm(ctx, layer, x_ptr, y_ptr, frames, silu) -> None:
-    _check(lib().lc_op_group_norm(ctx, layer, x_ptr, y_ptr, frames, int(silu)), ctx)
+def lc_op_conv_in(ctx, x_ptr, h_ptr, frames) -> None:
+    _check(lib().lc_op_conv_in(ctx, x_ptr, h_ptr, frames), ctx)
 
 
-def lc_op_conv3x3(ctx, layer, x_ptr, res_ptr, y_ptr, frames) -> None:
-    _check(lib().lc_op_conv3x3(ctx, layer, x_ptr, res_ptr, y_ptr, frames), ctx)
+def lc_op_res_block(ctx, layer, x_ptr, y_ptr, frames) -> None:
+    _check(lib().lc_op_res_block(ctx, layer, x_ptr, y_ptr, frames), ctx)
 
 
-def lc_op_qkv(ctx, layer, x_ptr, qkv_ptr, rows) -> None:
-    _check(lib().lc_op_qkv(ctx, layer, x_ptr, qkv_ptr, rows), ctx)
-
-
-def lc_op_proj(ctx, layer, a_ptr, res_ptr, y_ptr, rows) -> None:
-    _check(lib().lc_op_proj(ctx, layer, a_ptr, res_ptr, y_ptr, rows), ctx)
+def lc_op_qkv(ctx, layer, x_ptr, qkv_ptr, frames) -> None:
+    _check(lib().lc_op_qkv(ctx, layer, x_ptr, qkv_ptr, frames), ctx)
 
 
 def lc_op_spatial_attention(ctx, qkv_ptr, out_ptr, frames, q0, q1) -> None:
@@ -254,12 +250,16 @@ def lc_op_temporal_attention(ctx, qkv_ptr, out_ptr, positions) -> None:
     _check(lib().lc_op_temporal_attention(ctx, qkv_ptr, out_ptr, positions), ctx)
 
 
-def lc_op_conv_in(ctx, x_ptr, h_ptr, frames) -> None:
-    _check(lib().lc_op_conv_in(ctx, x_ptr, h_ptr, frames), ctx)
+def lc_op_proj(ctx, layer, a_ptr, res_ptr, y_ptr, rows) -> None:
+    _check(lib().lc_op_proj(ctx, layer, a_ptr, res_ptr, y_ptr, rows), ctx)
 
 
-def lc_op_concat_norm(ctx, skip_ptr, deep_ptr, catn_ptr, frames) -> None:
-    _check(lib().lc_op_concat_norm(ctx, skip_ptr, deep_ptr, catn_ptr, frames), ctx)
+def lc_op_down_conv(ctx, x_ptr, d0_ptr, frames) -> None:
+    _check(lib().lc_op_down_conv(ctx, x_ptr, d0_ptr, frames), ctx)
+
+
+def lc_op_up_conv(ctx, skip_ptr, deep_ptr, u_ptr, frames) -> None:
+    _check(lib().lc_op_up_conv(ctx, skip_ptr, deep_ptr, u_ptr, frames), ctx)
 
 
 def lc_op_conv_out(ctx, u_ptr, eps_ptr, frames) -> None:

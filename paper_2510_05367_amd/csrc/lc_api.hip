@@ -99,7 +99,7 @@ lc_status check_cfg(lc_ctx* c, const lc_config* g) {
   if (g->C > 1024 || g->C_deep > 1024) return fail(c, LC_ERR_SHAPE, "C and C_deep must be <= 1024");
   if (g->C % g->groups || g->C_deep % g->groups || (g->C + g->C_deep) % g->groups)
     return fail(c, LC_ERR_SHAPE, "C, C_deep and C + C_deep must be divisible by groups");
-  if (g->groups > 256) return fail(c, LC_ERR_SHAPE, "groups must be <= 256");
+  if ((g->C + g->C_deep) / g->groups > 512) return fail(c, LC_ERR_SHAPE, "at most 512 channels per group");
   if (g->heads * g->head_dim != g->C) return fail(c, LC_ERR_SHAPE, "heads * head_dim must equal C");
   const int d = g->head_dim;
   if (!(d == 8 || d == 16 || d == 32 || d == 40 || d == 64))
@@ -134,9 +134,11 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   p.off_shift = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
   const int64_t pc = (int64_t)p.fc * T;   // pixels of a frame chunk
   const int64_t rt = N * p.tc;            // rows of a temporal pass
-  size_t wsb = (size_t)(4 * g.C * std::max(pc, rt)) * es;                                   // tn + qkv
-  wsb = std::max(wsb, (size_t)(pc * ((int64_t)g.C + g.C_deep)) * es + (size_t)(pc * g.C) * 4);  // catn + u (fp32)
-  wsb = std::max(wsb, (size_t)((pc / 4) * (int64_t)g.C_deep) * (4 + es));                     // deep stand-in: d0 (fp32) + dn
+  // frame-chunk pass: ping-pong copy of the fp32 stream + q,k,v + attention output
+  size_t wsb = (size_t)(pc * g.C) * 4 + (size_t)(4 * g.C * pc) * es;
+  wsb = std::max(wsb, (size_t)(4 * g.C * rt) * es);                 // temporal pass: q,k,v + attention output
+  wsb = std::max(wsb, (size_t)((pc / 4) * (int64_t)g.C_deep) * 4);  // deep stand-in: fp32 d0
+  wsb += 2 * kAlign;
   p.ws_bytes = align_up(wsb) + kAlign;
   p.off_ws = off; off += p.ws_bytes;
   p.total = off;
@@ -185,36 +187,70 @@ lc_status gn_scale_shift(lc_ctx* c, const void* x, int frames, int rows_per_fram
   return LC_OK;
 }
 
-// x is an fp32 residual-stream tensor; y gets the operand type of the configuration.
-lc_status gn_full(lc_ctx* c, const void* x, int frames, int rows_per_frame, int C, const GnW& w, void* y, int silu) {
-  lc_status s = gn_scale_shift(c, x, frames, rows_per_frame, C, w);
+ConvDesc down_desc(const lc_config& g, const ConvW& w, int frames, const void* x, void* y) {
+  ConvDesc d;
+  memset(&d, 0, sizeof d);
+  d.dt = g.dtype; d.x_f32 = 1; d.y_f32 = 1; d.taps = 9; d.stride = 2; d.Cin = g.C; d.Cout = g.C_deep;
+  d.Cout_store = g.C_deep; d.w = w.w; d.bias = w.b; d.frames = frames; d.H = g.H; d.W = g.W;
+  d.x = x; d.res = nullptr; d.y = y; d.out_map = dense_map();
+  return d;
+}
+
+// 3x3 stride-1 convolution whose loader applies scale/shift (+ SiLU) to the fp32 tensor x.
+FusedDesc fconv_desc(lc_ctx* c, const ConvW& w, int Cin, int Cout, int frames, int H, int W, const void* x,
+                     const void* res, void* y, int y_f32) {
+  FusedDesc d;
+  memset(&d, 0, sizeof d);
+  d.dt = c->cfg.dtype; d.y_f32 = y_f32; d.taps = 9; d.src = 2; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
+  d.w = w.w; d.bias = w.b; d.frames = frames; d.H = H; d.W = W; d.x = x; d.scale = scale_p(c); d.shift = shift_p(c);
+  d.res = res; d.y = y; d.in_map = dense_map(); d.out_map = dense_map();
+  return d;
+}
+
+FusedDesc flinear_desc(lc_ctx* c, const void* w, const float* bias, int Cin, int Cout, int64_t rows, int src,
+                       RowMap in_map, RowMap out_map, const void* x, const void* res, void* y, int y_f32) {
+  FusedDesc d;
+  memset(&d, 0, sizeof d);
+  d.dt = c->cfg.dtype; d.y_f32 = y_f32; d.taps = 1; d.src = src; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
+  d.w = w; d.bias = bias; d.rows = rows; d.in_map = in_map; d.out_map = out_map; d.x = x;
+  d.scale = scale_p(c); d.shift = shift_p(c); d.res = res; d.y = y;
+  return d;
+}
+
+// residual block body: y = x + conv3x3(SiLU(GN(x))); x fp32 [frames][H*W][Cn]; y must not alias x
+lc_status res_block(lc_ctx* c, const GnW& gn, const ConvW& cw, int Cn, int frames, int H, int W, const void* x,
+                    void* y, int y_f32, int kind) {
+  lc_status s = gn_scale_shift(c, x, frames, H * W, Cn, gn);
   if (s != LC_OK) return s;
-  RowMap m{0, 0, rows_per_frame};
-  m.seg_stride = rows_per_frame;  // dense frames: segment f starts at f * rows_per_frame
-  LC_LAUNCH(c, LC_K_GN_APPLY, launch_gn_apply(c->cs, kF32, c->cfg.dtype, x, m, y, (int64_t)frames * rows_per_frame, C,
-                                              scale_p(c), shift_p(c), silu));
+  LC_LAUNCH(c, kind, launch_fused(c->cs, fconv_desc(c, cw, Cn, Cn, frames, H, W, x, x, y, y_f32)));
   return LC_OK;
 }
 
-ConvDesc conv_desc(const lc_config& g, const ConvW& w, int Cin, int Cout, int frames, int H, int W, int stride,
-                   const void* x, const void* res, void* y, int x_f32, int y_f32) {
-  ConvDesc d;
-  memset(&d, 0, sizeof d);
-  d.x_f32 = x_f32; d.y_f32 = y_f32;
-  d.dt = g.dtype; d.taps = 9; d.stride = stride; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
-  d.w = w.w; d.bias = w.b; d.frames = frames; d.H = H; d.W = W; d.x = x; d.res = res; d.y = y;
-  d.out_map = dense_map();
-  return d;
+// u = conv3x3(SiLU(GN(Concat(skip, up2(deep)))))
+lc_status up_conv(lc_ctx* c, const void* skip, const void* deep, void* u, int frames) {
+  const lc_config& g = c->cfg;
+  const int T = g.H * g.W, C = g.C, Cd = g.C_deep;
+  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, skip, partH(c), frames, T, C));
+  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, deep, partD(c), frames, T / 4, Cd));
+  LC_LAUNCH(c, LC_K_GN_FINAL,
+            launch_gn_finalize(c->cs, partH(c), C, stat_splits(T), T, 1.f, partD(c), Cd, stat_splits(T / 4), T / 4, 4.f,
+                               c->pw.up_gn.gamma, c->pw.up_gn.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), frames));
+  FusedDesc d = fconv_desc(c, c->pw.up, C + Cd, C, frames, g.H, g.W, skip, nullptr, u, 1);
+  d.src = 3; d.x2 = deep; d.Cs = C;
+  LC_LAUNCH(c, LC_K_CONV_UP, launch_fused(c->cs, d));
+  return LC_OK;
 }
 
-ConvDesc linear_desc(const lc_config& g, const void* w, const float* bias, int Cin, int Cout, int64_t rows,
-                     RowMap out_map, const void* x, const void* res, void* y, int y_f32) {
-  ConvDesc d;
-  memset(&d, 0, sizeof d);
-  d.y_f32 = y_f32;
-  d.dt = g.dtype; d.taps = 1; d.stride = 1; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
-  d.w = w; d.bias = bias; d.rows = rows; d.out_map = out_map; d.x = x; d.res = res; d.y = y;
-  return d;
+// eps = conv_out(SiLU(GN(u))), planar output of the operand type
+lc_status conv_out(lc_ctx* c, const void* u, void* eps, int frames) {
+  const lc_config& g = c->cfg;
+  lc_status s = gn_scale_shift(c, u, frames, g.H * g.W, g.C, c->pw.out_gn);
+  if (s != LC_OK) return s;
+  FusedDesc d = fconv_desc(c, c->pw.out, g.C, 32, frames, g.H, g.W, u, nullptr, eps, 0);
+  d.Cout_store = g.C_lat;
+  d.planar_out = 1;
+  LC_LAUNCH(c, LC_K_CONV_OUT, launch_fused(c->cs, d));
+  return LC_OK;
 }
 
 lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
@@ -231,24 +267,30 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     const int nf = std::min(p.fc, N - n0);
     const int64_t pc = (int64_t)nf * T;
     char* hc = h + (size_t)n0 * T * C * 4;
-    char* tn = ws;
-    char* qkv = ws + (size_t)pc * C * es;
-    LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, (const char*)x + (size_t)n0 * g.C_lat * T * es, hc, nf,
+    char* hb = ws;                                           // fp32 ping-pong partner of hc
+    char* qkv = ws + align_up((size_t)pc * C * 4);
+    char* ao = qkv + align_up((size_t)pc * 3 * C * es);
+    // a 3x3 convolution cannot run in place (its halo reads rows other workgroups write), so the
+    // residual blocks alternate between hc and hb; start so that the last one lands in hc
+    char* cur = (g.n_res % 2 == 0) ? hc : hb;
+    LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, (const char*)x + (size_t)n0 * g.C_lat * T * es, cur, nf,
                                               g.H, g.W, g.C_lat, C, w.cin_w, w.cin_b));
     for (int i = 0; i < g.n_res; ++i) {
-      lc_status s = gn_full(c, hc, nf, T, C, w.res_gn[i], tn, 1);
+      char* nxt = cur == hc ? hb : hc;
+      lc_status s = res_block(c, w.res_gn[i], w.res[i], C, nf, g.H, g.W, cur, nxt, 1, LC_K_CONV_RES);
       if (s != LC_OK) return s;
-      LC_LAUNCH(c, LC_K_CONV_RES, launch_conv(c->cs, conv_desc(g, w.res[i], C, C, nf, g.H, g.W, 1, tn, hc, hc, 0, 1)));
+      cur = nxt;
     }
-    lc_status s = gn_full(c, hc, nf, T, C, w.sattn.gn, tn, 0);
+    lc_status s = gn_scale_shift(c, hc, nf, T, C, w.sattn.gn);
     if (s != LC_OK) return s;
-    LC_LAUNCH(c, LC_K_QKV,
-              launch_conv(c->cs, linear_desc(g, w.sattn.wqkv, nullptr, C, 3 * C, pc, dense_map(), tn, nullptr, qkv, 0)));
+    RowMap fm{0, T, T};  // dense rows; frame of row r = r / T
+    LC_LAUNCH(c, LC_K_QKV, launch_fused(c->cs, flinear_desc(c, w.sattn.wqkv, nullptr, C, 3 * C, pc, 1, fm, dense_map(),
+                                                            hc, nullptr, qkv, 0)));
     for (int q0 = 0; q0 < T; q0 += p.qc)
-      LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, tn, nf, T, g.heads, g.head_dim, q0,
+      LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, ao, nf, T, g.heads, g.head_dim, q0,
                                                         std::min(q0 + p.qc, T)));
-    LC_LAUNCH(c, LC_K_PROJ,
-              launch_conv(c->cs, linear_desc(g, w.sattn.wo, w.sattn.bo, C, C, pc, dense_map(), tn, hc, hc, 1)));
+    LC_LAUNCH(c, LC_K_PROJ, launch_fused(c->cs, flinear_desc(c, w.sattn.wo, w.sattn.bo, C, C, pc, 0, dense_map(),
+                                                             dense_map(), ao, hc, hc, 1)));
   }
 
   // ---- temporal block: per-frame statistics over whole frames, then per position chunk
@@ -258,14 +300,14 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     for (int p0 = 0; p0 < T; p0 += p.tc) {
       const int np = std::min(p.tc, T - p0);
       const int64_t rows = (int64_t)N * np;
-      RowMap m{p0, T, np};
-      char* tn = ws;
-      char* qkv = ws + (size_t)rows * C * es;
-      LC_LAUNCH(c, LC_K_GN_APPLY, launch_gn_apply(c->cs, kF32, g.dtype, h, m, tn, rows, C, scale_p(c), shift_p(c), 0));
-      LC_LAUNCH(c, LC_K_QKV,
-                launch_conv(c->cs, linear_desc(g, w.tattn.wqkv, nullptr, C, 3 * C, rows, dense_map(), tn, nullptr, qkv, 0)));
-      LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, tn, g.B, g.F, np, g.heads, g.head_dim));
-      LC_LAUNCH(c, LC_K_PROJ, launch_conv(c->cs, linear_desc(g, w.tattn.wo, w.tattn.bo, C, C, rows, m, tn, h, h, 1)));
+      RowMap m{p0, T, np};  // dense row r = (frame r / np, position p0 + r % np)
+      char* qkv = ws;
+      char* ao = ws + align_up((size_t)rows * 3 * C * es);
+      LC_LAUNCH(c, LC_K_QKV, launch_fused(c->cs, flinear_desc(c, w.tattn.wqkv, nullptr, C, 3 * C, rows, 1, m, dense_map(),
+                                                              h, nullptr, qkv, 0)));
+      LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
+      LC_LAUNCH(c, LC_K_PROJ, launch_fused(c->cs, flinear_desc(c, w.tattn.wo, w.tattn.bo, C, C, rows, 0, dense_map(), m,
+                                                               ao, h, h, 1)));
     }
   }
 
@@ -277,15 +319,12 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     c->in_pending[slot] = 0;
     for (int n0 = 0; n0 < N; n0 += p.fc) {
       const int nf = std::min(p.fc, N - n0);
-      const int64_t pq = (int64_t)nf * (T / 4);
       char* hc = h + (size_t)n0 * T * C * 4;
       char* d0 = ws;  // fp32
-      char* dn = ws + (size_t)pq * Cd * 4;
       char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
-      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, conv_desc(g, w.down, C, Cd, nf, g.H, g.W, 2, hc, nullptr, d0, 1, 1)));
-      lc_status s = gn_full(c, d0, nf, T / 4, Cd, w.dres_gn, dn, 1);
+      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, down_desc(g, w.down, nf, hc, d0)));
+      lc_status s = res_block(c, w.dres_gn, w.dres, Cd, nf, g.H / 2, g.W / 2, d0, dc, 0, LC_K_DEEP);
       if (s != LC_OK) return s;
-      LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, conv_desc(g, w.dres, Cd, Cd, nf, g.H / 2, g.W / 2, 1, dn, d0, dc, 0, 0)));
     }
     LC_HIP(c, hipEventRecord(c->ev_produced[slot], c->cs));
     c->dev_filled[slot] = 1;
@@ -297,26 +336,13 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
   // ---- shallow up branch U_m on Concat(skip, up2(deep)), per frame chunk
   for (int n0 = 0; n0 < N; n0 += p.fc) {
     const int nf = std::min(p.fc, N - n0);
-    const int64_t pc = (int64_t)nf * T;
     char* hc = h + (size_t)n0 * T * C * 4;
     char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
-    char* catn = ws;
-    char* u = ws + align_up((size_t)pc * (C + Cd) * es);  // fp32
-    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, hc, partH(c), nf, T, C));
-    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, dc, partD(c), nf, T / 4, Cd));
-    LC_LAUNCH(c, LC_K_GN_FINAL,
-              launch_gn_finalize(c->cs, partH(c), C, stat_splits(T), T, 1.f, partD(c), Cd, stat_splits(T / 4), T / 4,
-                                 4.f, w.up_gn.gamma, w.up_gn.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), nf));
-    LC_LAUNCH(c, LC_K_CAT_APPLY,
-              launch_concat_apply(c->cs, g.dtype, hc, dc, catn, nf, g.H, g.W, C, Cd, scale_p(c), shift_p(c)));
-    LC_LAUNCH(c, LC_K_CONV_UP, launch_conv(c->cs, conv_desc(g, w.up, C + Cd, C, nf, g.H, g.W, 1, catn, nullptr, u, 0, 1)));
-    lc_status s = gn_full(c, u, nf, T, C, w.out_gn, catn, 1);
+    char* u = ws;  // fp32
+    lc_status s = up_conv(c, hc, dc, u, nf);
     if (s != LC_OK) return s;
-    ConvDesc d = conv_desc(g, w.out, C, 16, nf, g.H, g.W, 1, catn, nullptr,
-                           (char*)eps + (size_t)n0 * g.C_lat * T * es, 0, 0);
-    d.Cout_store = g.C_lat;
-    d.planar_out = 1;
-    LC_LAUNCH(c, LC_K_CONV_OUT, launch_conv(c->cs, d));
+    s = conv_out(c, u, (char*)eps + (size_t)n0 * g.C_lat * T * es, nf);
+    if (s != LC_OK) return s;
   }
   LC_HIP(c, hipEventRecord(c->ev_consumed[slot], c->cs));
   return LC_OK;
@@ -337,20 +363,6 @@ lc_status op_checks(lc_ctx* c, int frames) {
   if (!c->arena) return fail(c, LC_ERR_STATE, "workspace not set");
   if (frames <= 0 || frames > c->cfg.B * c->cfg.F) return fail(c, LC_ERR_ARG, "frames out of range");
   return LC_OK;
-}
-
-bool layer_gn(lc_ctx* c, int layer, GnW* gn, int* Cn, int* rows_div) {
-  const lc_config& g = c->cfg;
-  *rows_div = 1;
-  *Cn = g.C;
-  if (layer >= LC_L_RES0 && layer < LC_L_RES0 + g.n_res) { *gn = c->pw.res_gn[layer]; return true; }
-  switch (layer) {
-    case LC_L_SATTN: *gn = c->pw.sattn.gn; return true;
-    case LC_L_TATTN: *gn = c->pw.tattn.gn; return true;
-    case LC_L_OUT: *gn = c->pw.out_gn; return true;
-    case LC_L_DRES: *gn = c->pw.dres_gn; *Cn = g.C_deep; *rows_div = 4; return true;
-    default: return false;
-  }
 }
 
 }  // namespace
@@ -484,7 +496,7 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
   const size_t o_up_g = take((size_t)(C + Cd) * 4), o_up_b = take((size_t)(C + Cd) * 4);
   const size_t o_up_w = take((size_t)C * 9 * (C + Cd) * es), o_up_bias = take((size_t)C * 4);
   const size_t o_out_g = take((size_t)C * 4), o_out_b = take((size_t)C * 4);
-  const size_t o_out_w = take((size_t)16 * 9 * C * es), o_out_bias = take((size_t)16 * 4);
+  const size_t o_out_w = take((size_t)32 * 9 * C * es), o_out_bias = take((size_t)32 * 4);
 
   LC_HIP(c, hipStreamSynchronize(c->cs));
   if (c->wblob) { LC_HIP(c, hipFree(c->wblob)); c->wblob = nullptr; c->have_weights = false; }
@@ -529,7 +541,7 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
   p.up_gn = GnW{(float*)(b + o_up_g), (float*)(b + o_up_b)};
   p.up = ConvW{b + o_up_w, (float*)(b + o_up_bias)};
   F32(w->out.gn_g, o_out_g, C, C); F32(w->out.gn_b, o_out_b, C, C);
-  CW(w->out.w, o_out_w, Cl, C, 9, 16); F32(w->out.b, o_out_bias, Cl, 16);
+  CW(w->out.w, o_out_w, Cl, C, 9, 32); F32(w->out.b, o_out_bias, Cl, 32);
   p.out_gn = GnW{(float*)(b + o_out_g), (float*)(b + o_out_b)};
   p.out = ConvW{b + o_out_w, (float*)(b + o_out_bias)};
 #undef F32
@@ -761,38 +773,46 @@ lc_status lc_get_profile(lc_ctx* c, lc_profile* out) {
 
 // ---- single operators -------------------------------------------------------------------------
 
-lc_status lc_op_group_norm(lc_ctx* c, int layer, const void* x, void* y, int frames, int silu) {
+lc_status lc_op_res_block(lc_ctx* c, int layer, const void* x, void* y, int frames) {
   lc_status s = op_checks(c, frames);
   if (s != LC_OK) return s;
-  if (!x || !y) return fail(c, LC_ERR_ARG, "NULL tensor");
-  GnW gn; int Cn, div;
-  if (!layer_gn(c, layer, &gn, &Cn, &div)) return fail(c, LC_ERR_ARG, "layer %d has no plain GroupNorm", layer);
-  return gn_full(c, x, frames, c->cfg.H * c->cfg.W / div, Cn, gn, y, silu);
+  if (!x || !y || x == y) return fail(c, LC_ERR_ARG, "x and y must be distinct non-NULL tensors");
+  const lc_config& g = c->cfg;
+  if (layer >= LC_L_RES0 && layer < LC_L_RES0 + g.n_res)
+    return res_block(c, c->pw.res_gn[layer], c->pw.res[layer], g.C, frames, g.H, g.W, x, y, 1, LC_K_CONV_RES);
+  if (layer == LC_L_DRES)
+    return res_block(c, c->pw.dres_gn, c->pw.dres, g.C_deep, frames, g.H / 2, g.W / 2, x, y, 0, LC_K_DEEP);
+  return fail(c, LC_ERR_ARG, "layer %d is not a residual block", layer);
 }
 
-lc_status lc_op_conv3x3(lc_ctx* c, int layer, const void* x, const void* res, void* y, int frames) {
+lc_status lc_op_up_conv(lc_ctx* c, const void* skip, const void* deep, void* u, int frames) {
+  lc_status s = op_checks(c, frames);
+  if (s != LC_OK) return s;
+  if (!skip || !deep || !u) return fail(c, LC_ERR_ARG, "NULL tensor");
+  return up_conv(c, skip, deep, u, frames);
+}
+
+lc_status lc_op_down_conv(lc_ctx* c, const void* x, void* y, int frames) {
   lc_status s = op_checks(c, frames);
   if (s != LC_OK) return s;
   if (!x || !y) return fail(c, LC_ERR_ARG, "NULL tensor");
-  const lc_config& g = c->cfg;
-  ConvDesc d;
-  if (layer >= LC_L_RES0 && layer < LC_L_RES0 + g.n_res) d = conv_desc(g, c->pw.res[layer], g.C, g.C, frames, g.H, g.W, 1, x, res, y, 0, 1);
-  else if (layer == LC_L_DRES) d = conv_desc(g, c->pw.dres, g.C_deep, g.C_deep, frames, g.H / 2, g.W / 2, 1, x, res, y, 0, 0);
-  else if (layer == LC_L_UP) d = conv_desc(g, c->pw.up, g.C + g.C_deep, g.C, frames, g.H, g.W, 1, x, res, y, 0, 1);
-  else if (layer == LC_L_DOWN) d = conv_desc(g, c->pw.down, g.C, g.C_deep, frames, g.H, g.W, 2, x, res, y, 1, 1);
-  else return fail(c, LC_ERR_ARG, "layer %d is not a 3x3 convolution", layer);
-  const int kind = layer == LC_L_UP ? LC_K_CONV_UP : (layer == LC_L_DOWN || layer == LC_L_DRES) ? LC_K_DEEP : LC_K_CONV_RES;
-  LC_LAUNCH(c, kind, launch_conv(c->cs, d));
+  LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, down_desc(c->cfg, c->pw.down, frames, x, y)));
   return LC_OK;
 }
 
-lc_status lc_op_qkv(lc_ctx* c, int layer, const void* x, void* qkv, int64_t rows) {
-  lc_status s = op_checks(c, 1);
+lc_status lc_op_qkv(lc_ctx* c, int layer, const void* x, void* qkv, int frames) {
+  lc_status s = op_checks(c, frames);
   if (s != LC_OK) return s;
-  if (!x || !qkv || rows <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
+  if (!x || !qkv) return fail(c, LC_ERR_ARG, "NULL tensor");
   if (layer != LC_L_SATTN && layer != LC_L_TATTN) return fail(c, LC_ERR_ARG, "layer %d is not an attention block", layer);
+  const lc_config& g = c->cfg;
   const AttnW& a = layer == LC_L_SATTN ? c->pw.sattn : c->pw.tattn;
-  LC_LAUNCH(c, LC_K_QKV, launch_conv(c->cs, linear_desc(c->cfg, a.wqkv, nullptr, c->cfg.C, 3 * c->cfg.C, rows, dense_map(), x, nullptr, qkv, 0)));
+  const int T = g.H * g.W;
+  s = gn_scale_shift(c, x, frames, T, g.C, a.gn);
+  if (s != LC_OK) return s;
+  RowMap fm{0, T, T};
+  LC_LAUNCH(c, LC_K_QKV, launch_fused(c->cs, flinear_desc(c, a.wqkv, nullptr, g.C, 3 * g.C, (int64_t)frames * T, 1, fm,
+                                                          dense_map(), x, nullptr, qkv, 0)));
   return LC_OK;
 }
 
@@ -802,7 +822,8 @@ lc_status lc_op_proj(lc_ctx* c, int layer, const void* a_in, const void* res, vo
   if (!a_in || !y || rows <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
   if (layer != LC_L_SATTN && layer != LC_L_TATTN) return fail(c, LC_ERR_ARG, "layer %d is not an attention block", layer);
   const AttnW& a = layer == LC_L_SATTN ? c->pw.sattn : c->pw.tattn;
-  LC_LAUNCH(c, LC_K_PROJ, launch_conv(c->cs, linear_desc(c->cfg, a.wo, a.bo, c->cfg.C, c->cfg.C, rows, dense_map(), a_in, res, y, 1)));
+  LC_LAUNCH(c, LC_K_PROJ, launch_fused(c->cs, flinear_desc(c, a.wo, a.bo, c->cfg.C, c->cfg.C, rows, 0, dense_map(),
+                                                           dense_map(), a_in, res, y, 1)));
   return LC_OK;
 }
 
@@ -834,38 +855,11 @@ lc_status lc_op_conv_in(lc_ctx* c, const void* x, void* h, int frames) {
   return LC_OK;
 }
 
-lc_status lc_op_concat_norm(lc_ctx* c, const void* skip, const void* deep, void* catn, int frames) {
-  lc_status s = op_checks(c, frames);
-  if (s != LC_OK) return s;
-  if (!skip || !deep || !catn) return fail(c, LC_ERR_ARG, "NULL tensor");
-  const lc_config& g = c->cfg;
-  const int T = g.H * g.W, C = g.C, Cd = g.C_deep;
-  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, skip, partH(c), frames, T, C));
-  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, deep, partD(c), frames, T / 4, Cd));
-  LC_LAUNCH(c, LC_K_GN_FINAL,
-            launch_gn_finalize(c->cs, partH(c), C, stat_splits(T), T, 1.f, partD(c), Cd, stat_splits(T / 4), T / 4, 4.f,
-                               c->pw.up_gn.gamma, c->pw.up_gn.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), frames));
-  LC_LAUNCH(c, LC_K_CAT_APPLY, launch_concat_apply(c->cs, g.dtype, skip, deep, catn, frames, g.H, g.W, C, Cd, scale_p(c), shift_p(c)));
-  return LC_OK;
-}
-
 lc_status lc_op_conv_out(lc_ctx* c, const void* u, void* eps, int frames) {
   lc_status s = op_checks(c, frames);
   if (s != LC_OK) return s;
   if (!u || !eps) return fail(c, LC_ERR_ARG, "NULL tensor");
-  const lc_config& g = c->cfg;
-  const int T = g.H * g.W;
-  // normalised copy goes to the chunk scratch; it must hold frames * T * C elements
-  if ((size_t)frames * T * g.C * dtype_size(g.dtype) > c->plan.ws_bytes)
-    return fail(c, LC_ERR_NOMEM, "chunk scratch too small for %d frames", frames);
-  char* un = ws_ptr(c);
-  s = gn_full(c, u, frames, T, g.C, c->pw.out_gn, un, 1);
-  if (s != LC_OK) return s;
-  ConvDesc d = conv_desc(g, c->pw.out, g.C, 16, frames, g.H, g.W, 1, un, nullptr, eps, 0, 0);
-  d.Cout_store = g.C_lat;
-  d.planar_out = 1;
-  LC_LAUNCH(c, LC_K_CONV_OUT, launch_conv(c->cs, d));
-  return LC_OK;
+  return conv_out(c, u, eps, frames);
 }
 
 }  // extern "C"

@@ -14,33 +14,6 @@
 
 namespace lc {
 
-// ---------------------------------------------------------------------------------------------
-// 32x32 MFMA tiles. D[32x32] += A[32xK] B[Kx32]; lane l: A row l%32, B column l%32;
-// D: column l%32, rows 8*(r/4) + 4*(l/32) + r%4 for r = 0..15.
-// bf16: K = 16 per instruction, the lane's k-slots are 8*(l/32)..+7. fp32: K = 2, k-slot l/32.
-// ---------------------------------------------------------------------------------------------
-template <class T> struct Mma32;
-template <> struct Mma32<bf16_t> {
-  static constexpr int K = 16;   // contraction elements per instruction
-  static constexpr int LK = 8;   // contiguous elements one lane supplies
-  typedef bf16x8 Frag;
-  static __device__ __forceinline__ Frag load(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
-  static __device__ __forceinline__ Frag zero() { Frag f; for (int i = 0; i < 8; ++i) f[i] = (bf16_t)0.f; return f; }
-  static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x16& d) {
-    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, d, 0, 0, 0);
-  }
-};
-template <> struct Mma32<float> {
-  static constexpr int K = 2;
-  static constexpr int LK = 1;
-  typedef float Frag;
-  static __device__ __forceinline__ Frag load(const float* p) { return *p; }
-  static __device__ __forceinline__ Frag zero() { return 0.f; }
-  static __device__ __forceinline__ void mma(const Frag& a, const Frag& b, f32x16& d) {
-    d = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, d, 0, 0, 0);
-  }
-};
-
 constexpr int kKeys = 64;  // keys per LDS stage
 
 // Column of key `k` (0..63) inside a V^T row in LDS. For bf16 the four 4-key blocks of every 16

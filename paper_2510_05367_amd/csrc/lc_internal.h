@@ -26,16 +26,6 @@ hipError_t launch_gn_finalize(hipStream_t s, const float* partA, int CA, int spl
                               const float* partB, int CB, int splitsB, int rowsB, float wB,
                               const float* gamma, const float* beta, int groups, float eps,
                               float* scale, float* shift, int frames);
-// y[r][c] = act(x[map(r)][c] * scale[f][c] + shift[f][c]),  f = r / map.rows_per_seg.
-// x has element type xdt, y element type ydt (fp32 -> fp32, fp32 -> bf16 or bf16 -> bf16).
-hipError_t launch_gn_apply(hipStream_t s, int xdt, int ydt, const void* x, RowMap map, void* y, int64_t rows, int C,
-                           const float* scale, const float* shift, int silu);
-// catn[r][0:C] from skip[r] (always fp32: the residual stream), catn[r][C:C+Cd] from
-// deep[(frame, y/2, x/2)] (element type dt, like catn), normalised + SiLU.
-hipError_t launch_concat_apply(hipStream_t s, int dt, const void* skip, const void* deep, void* catn,
-                               int frames, int H, int W, int C, int Cd, const float* scale,
-                               const float* shift);
-
 // ---- implicit-GEMM convolution / linear layers (MFMA) ---------------------------------------
 struct ConvDesc {
   int dt;      // MFMA operand type = type of w (and of x unless x_f32)
@@ -59,6 +49,32 @@ struct ConvDesc {
   int planar_out;
 };
 hipError_t launch_conv(hipStream_t s, const ConvDesc& d);
+
+// ---- fused-loader 3x3 stride-1 convolutions and linear layers (32x32 MFMA tiles) -------------
+struct FusedDesc {
+  int dt;        // MFMA operand type (type of w and of the LDS tiles)
+  int y_f32;     // 1: y is an fp32 stream tensor; 0: y has the operand type
+  int taps;      // 9: 3x3 conv over [frames][H][W][Cin]; 1: linear layer over rows
+  int src;       // 0: x has the operand type, used as is
+                 // 1: x is fp32, x * scale[f][c] + shift[f][c] (GroupNorm apply)
+                 // 2: the same followed by SiLU
+                 // 3: channels [0,Cs) from the fp32 skip x, [Cs,Cin) from x2 (operand type, half
+                 //    resolution, nearest 2x upsampled), then as 2
+  int Cin, Cs, Cout, Cout_store;
+  const void* w;       // [Cout][taps*Cin]
+  const float* bias;   // [Cout] or nullptr
+  int frames, H, W;    // taps == 9
+  int64_t rows;        // taps == 1: x row of dense row r is in_map(r), y / res row is out_map(r);
+  RowMap in_map, out_map;  //        scale/shift frame of row r is r / in_map.rows_per_seg
+  const void* x;
+  const void* x2;
+  const float* scale;  // [frames][Cin]
+  const float* shift;
+  const void* res;     // fp32, indexed like y; nullptr if none; may equal y only when taps == 1
+  void* y;
+  int planar_out;      // 1: y is [frame][Cout_store][H][W] of the operand type (Cout = 32, zero-padded w)
+};
+hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
 
 // ---- attention cores -----------------------------------------------------------------------
 // qkv [frames*T][3C] -> out [frames*T][C]; queries [q0,q1) of every frame.

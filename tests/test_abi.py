@@ -74,8 +74,8 @@ def test_footprint_model_scales_with_chunk_not_with_frames():
     # persistent part: fp32 skip feature + dev_slots cache entries (+ small statistics scratch)
     es = 2
     persistent = cfg.N * cfg.T * cfg.C * 4 + 2 * lcb.lc_cache_entry_bytes(c)
-    # one frame of scratch: max(normalised copy + q,k,v ; normalised concat + fp32 up-conv output)
-    chunk1 = cfg.T * max(4 * cfg.C * es, (cfg.C + cfg.C_deep) * es + 4 * cfg.C)
+    # one frame of scratch: fp32 ping-pong copy of the stream + q,k,v + attention output
+    chunk1 = cfg.T * (4 * cfg.C + 4 * cfg.C * es)
     assert sizes[-1] - persistent < chunk1 + 16e6
     # chunk scratch is linear in the frame chunk
     assert abs((sizes[1] - sizes[2]) - 4 * chunk1) < 1e6

@@ -37,82 +37,74 @@ def act(cfg, shape, seed, scale=1.0):
     return synth.make_activation(shape, seed, cfg.dtype, scale)
 
 
-def test_group_norm(st):
+def test_res_block(st):
     stage, cfg, w = st
     N, C, H, W = cfg.N, cfg.C, cfg.H, cfg.W
-    x = act(cfg, (N, C, H, W), 21, 1.5) + (0.5 if cfg.dtype == "f32" else 0.0)
-    if cfg.dtype == "bf16":
-        x = synth.round_to_bf16(x)
+    x = act(cfg, (N, C, H, W), 21, 1.5) + np.float32(0.5)
     xd = dev32(stage, planar_to_rows(x))
-    for layer, pre, silu in [(lcb.LC_L_RES0, "res0", True), (lcb.LC_L_SATTN, "sattn", False), (lcb.LC_L_OUT, "out", True)]:
-        y = stage.empty(*xd.shape)
-        lcb.lc_op_group_norm(stage.ctx, layer, xd.data_ptr(), y.data_ptr(), N, silu)
+    for i in range(cfg.n_res):
+        pre = f"res{i}"
+        y = empty32(stage, *xd.shape)
+        lcb.lc_op_res_block(stage.ctx, lcb.LC_L_RES0 + i, xd.data_ptr(), y.data_ptr(), N)
         stage.sync()
-        ref = lo.group_norm(x.astype(np.float64), w[pre + ".gn_g"], w[pre + ".gn_b"], cfg.groups, cfg.gn_eps)
-        if silu:
-            ref = lo.silu(ref)
-        check(f"group_norm[{pre}]", rows_to_planar(host(y), N, C, H, W), ref, cfg.dtype)
-    # half-resolution, C_deep channels
-    Cd = cfg.C_deep
-    z = act(cfg, (N, Cd, H // 2, W // 2), 22)
+        x64 = x.astype(np.float64)
+        g = lo.silu(lo.group_norm(x64, w[pre + ".gn_g"], w[pre + ".gn_b"], cfg.groups, cfg.gn_eps))
+        ref = x64 + lo.conv3x3(g, w[pre + ".w"], w[pre + ".b"])
+        check(f"res_block[{pre}]", rows_to_planar(host(y), N, C, H, W), ref, cfg.dtype, abs_scale=4.0)
+    # fewer frames than the stage holds
+    y = empty32(stage, *xd.shape)
+    y.fill_(7.0)
+    lcb.lc_op_res_block(stage.ctx, lcb.LC_L_RES0, xd.data_ptr(), y.data_ptr(), 1)
+    stage.sync()
+    x64 = x[:1].astype(np.float64)
+    g = lo.silu(lo.group_norm(x64, w["res0.gn_g"], w["res0.gn_b"], cfg.groups, cfg.gn_eps))
+    check("res_block 1 frame", rows_to_planar(host(y[:H * W]), 1, C, H, W),
+          x64 + lo.conv3x3(g, w["res0.w"], w["res0.b"]), cfg.dtype, abs_scale=4.0)
+    assert bool((y[H * W:] == 7.0).all())
+
+
+def test_deep_stand_in(st):
+    stage, cfg, w = st
+    N, C, Cd, H, W = cfg.N, cfg.C, cfg.C_deep, cfg.H, cfg.W
+    x = act(cfg, (N, C, H, W), 23, 1.2)
+    xd = dev32(stage, planar_to_rows(x))
+    d0 = empty32(stage, N * (H // 2) * (W // 2), Cd)
+    lcb.lc_op_down_conv(stage.ctx, xd.data_ptr(), d0.data_ptr(), N)
+    stage.sync()
+    ref0 = lo.conv3x3(x.astype(np.float64), w["down.w"], w["down.b"], stride=2)
+    check("down_conv", rows_to_planar(host(d0), N, Cd, H // 2, W // 2), ref0, cfg.dtype, abs_scale=4.0)
+    # residual block at C_deep on an independent input; output has the cache-entry type
+    z = act(cfg, (N, Cd, H // 2, W // 2), 24, 1.5)
     zd = dev32(stage, planar_to_rows(z))
     y = stage.empty(*zd.shape)
-    lcb.lc_op_group_norm(stage.ctx, lcb.LC_L_DRES, zd.data_ptr(), y.data_ptr(), N, True)
+    lcb.lc_op_res_block(stage.ctx, lcb.LC_L_DRES, zd.data_ptr(), y.data_ptr(), N)
     stage.sync()
-    ref = lo.silu(lo.group_norm(z.astype(np.float64), w["dres.gn_g"], w["dres.gn_b"], cfg.groups, cfg.gn_eps))
-    check("group_norm[dres]", rows_to_planar(host(y), N, Cd, H // 2, W // 2), ref, cfg.dtype)
-
-
-@pytest.mark.parametrize("layer,pre", [(lcb.LC_L_RES0, "res0"), (lcb.LC_L_UP, "up"), (lcb.LC_L_DRES, "dres"),
-                                       (lcb.LC_L_DOWN, "down")])
-def test_conv3x3(st, layer, pre):
-    stage, cfg, w = st
-    N, H, W = cfg.N, cfg.H, cfg.W
-    Cout, Cin = w[pre + ".w"].shape[:2]
-    stride = 2 if pre == "down" else 1
-    if pre == "dres":
-        H, W = H // 2, W // 2
-    x = act(cfg, (N, Cin, H, W), 31)
-    Ho, Wo = H // stride, W // stride
-    res = act(cfg, (N, Cout, Ho, Wo), 32)
-    # element types: see the operator section of lightcache.h
-    xd = (dev32 if pre == "down" else dev)(stage, planar_to_rows(x))
-    rd = dev32(stage, planar_to_rows(res))
-    ref = lo.conv3x3(x.astype(np.float64), w[pre + ".w"], w[pre + ".b"], stride)
-    y = (stage.empty if pre == "dres" else lambda *s_: empty32(stage, *s_))(N * Ho * Wo, Cout)
-    rout = y.clone() if pre == "dres" else rd
-    lcb.lc_op_conv3x3(stage.ctx, layer, xd.data_ptr(), None, y.data_ptr(), N)
-    stage.sync()
-    check(f"conv3x3[{pre}]", rows_to_planar(host(y), N, Cout, Ho, Wo), ref, cfg.dtype, abs_scale=4.0)
-    # with a residual, written in place over it
-    lcb.lc_op_conv3x3(stage.ctx, layer, xd.data_ptr(), rd.data_ptr(), rout.data_ptr(), N)
-    stage.sync()
-    check(f"conv3x3[{pre}]+res", rows_to_planar(host(rout), N, Cout, Ho, Wo), ref + res.astype(np.float64), cfg.dtype,
-          abs_scale=4.0)
-    # fewer frames than the stage holds
-    lcb.lc_op_conv3x3(stage.ctx, layer, xd.data_ptr(), None, y.data_ptr(), 1)
-    stage.sync()
-    check(f"conv3x3[{pre}] 1 frame", rows_to_planar(host(y[:Ho * Wo]), 1, Cout, Ho, Wo), ref[:1], cfg.dtype, abs_scale=4.0)
+    z64 = z.astype(np.float64)
+    g = lo.silu(lo.group_norm(z64, w["dres.gn_g"], w["dres.gn_b"], cfg.groups, cfg.gn_eps))
+    check("res_block[dres]", rows_to_planar(host(y), N, Cd, H // 2, W // 2),
+          z64 + lo.conv3x3(g, w["dres.w"], w["dres.b"]), cfg.dtype, abs_scale=4.0)
 
 
 @pytest.mark.parametrize("layer,pre", [(lcb.LC_L_SATTN, "sattn"), (lcb.LC_L_TATTN, "tattn")])
 def test_qkv_and_proj(st, layer, pre):
     stage, cfg, w = st
-    C = cfg.C
-    rows = 333  # not a multiple of the 128-row tile
-    x = act(cfg, (rows, C), 41)
-    xd = dev(stage, x)
+    N, C, H, W = cfg.N, cfg.C, cfg.H, cfg.W
+    x = act(cfg, (N, C, H, W), 41, 1.4) - np.float32(0.3)
+    xd = dev32(stage, planar_to_rows(x))
+    rows = N * H * W
     qkv = stage.empty(rows, 3 * C)
-    lcb.lc_op_qkv(stage.ctx, layer, xd.data_ptr(), qkv.data_ptr(), rows)
+    lcb.lc_op_qkv(stage.ctx, layer, xd.data_ptr(), qkv.data_ptr(), N)
     stage.sync()
-    x64 = x.astype(np.float64)
-    ref = np.concatenate([x64 @ w[pre + ".wq"].T, x64 @ w[pre + ".wk"].T, x64 @ w[pre + ".wv"].T], axis=1)
+    g = planar_to_rows(lo.group_norm(x.astype(np.float64), w[pre + ".gn_g"], w[pre + ".gn_b"], cfg.groups, cfg.gn_eps))
+    ref = np.concatenate([g @ w[pre + ".wq"].T, g @ w[pre + ".wk"].T, g @ w[pre + ".wv"].T], axis=1)
     check(f"qkv[{pre}]", host(qkv), ref, cfg.dtype)
+    rows = 333  # not a multiple of the 128-row tile
+    a_in = act(cfg, (rows, C), 43)
     res = act(cfg, (rows, C), 42)
-    rd = dev32(stage, res)
-    lcb.lc_op_proj(stage.ctx, layer, xd.data_ptr(), rd.data_ptr(), rd.data_ptr(), rows)
+    ad, rd = dev(stage, a_in), dev32(stage, res)
+    lcb.lc_op_proj(stage.ctx, layer, ad.data_ptr(), rd.data_ptr(), rd.data_ptr(), rows)
     stage.sync()
-    ref = res.astype(np.float64) + x64 @ w[pre + ".wo"].T + w[pre + ".bo"]
+    ref = res.astype(np.float64) + a_in.astype(np.float64) @ w[pre + ".wo"].T + w[pre + ".bo"]
     check(f"proj[{pre}]", host(rd), ref, cfg.dtype)
 
 
@@ -188,7 +180,7 @@ def test_conv_in(st):
     check("conv_in", rows_to_planar(host(h), N, cfg.C, H, W), ref, cfg.dtype)
 
 
-def test_concat_norm(st):
+def test_up_conv(st):
     stage, cfg, w = st
     N, H, W, C, Cd = cfg.N, cfg.H, cfg.W, cfg.C, cfg.C_deep
     s = act(cfg, (N, C, H, W), 81, 1.3)
@@ -196,12 +188,13 @@ def test_concat_norm(st):
     if cfg.dtype == "bf16":
         d = synth.round_to_bf16(d)
     sd, dd = dev32(stage, planar_to_rows(s)), dev(stage, planar_to_rows(d))
-    catn = stage.empty(N * H * W, C + Cd)
-    lcb.lc_op_concat_norm(stage.ctx, sd.data_ptr(), dd.data_ptr(), catn.data_ptr(), N)
+    u = empty32(stage, N * H * W, C)
+    lcb.lc_op_up_conv(stage.ctx, sd.data_ptr(), dd.data_ptr(), u.data_ptr(), N)
     stage.sync()
     cat = np.concatenate([s.astype(np.float64), lo.up2(d.astype(np.float64))], axis=1)
-    ref = lo.silu(lo.group_norm(cat, w["up.gn_g"], w["up.gn_b"], cfg.groups, cfg.gn_eps))
-    check("concat_norm", rows_to_planar(host(catn), N, C + Cd, H, W), ref, cfg.dtype)
+    g = lo.silu(lo.group_norm(cat, w["up.gn_g"], w["up.gn_b"], cfg.groups, cfg.gn_eps))
+    ref = lo.conv3x3(g, w["up.w"], w["up.b"])
+    check("up_conv", rows_to_planar(host(u), N, C, H, W), ref, cfg.dtype, abs_scale=4.0)
 
 
 def test_conv_out(st):
