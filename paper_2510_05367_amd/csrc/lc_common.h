@@ -84,6 +84,10 @@ template <> __device__ __forceinline__ Vec16<bf16_t> load_packet<bf16_t, bf16_t>
 template <> __device__ __forceinline__ Vec16<float> load_packet<float, float>(const float* p) { return load16(p); }
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
+// x * sigmoid(x) with the hardware exp2 / reciprocal approximations (about 1 ulp each)
+__device__ __forceinline__ float silu_fast(float x) {
+  return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
 
 // ---------------------------------------------------------------------------------------
 // MFMA 16x16 tiles, D[16x16] += A[16xK] * B[Kx16], one wavefront.

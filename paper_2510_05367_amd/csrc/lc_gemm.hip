@@ -2,9 +2,11 @@
 // and the per-row linear layers of the stage.
 //
 // Product (transposed): D[cout][pixel] = sum_k W[cout][k] X[pixel][k], k = tap * Cin + ci.
-// One workgroup = 4 wavefronts = BCO output channels x 128 pixels; every wavefront owns all BCO
-// channels of 32 pixels (CO_T accumulator tiles of 32x32), so the weight fragments it reads from
-// LDS are used once per 32-pixel fragment and the pixel fragment once per CO_T weight fragments.
+// One workgroup = 4 wavefronts = BCO output channels x 128 pixels. The LDS read port, not the MFMA
+// pipe, is the scarce resource at this tile size, so the wavefronts do not split the tile four ways:
+// each takes all BCO channels of 64 pixels (CO_T x 2 accumulator tiles of 32x32, every weight
+// fragment feeds two MFMAs) over one HALF of the K elements of every step, and the two halves are
+// added through LDS once, before the epilogue.
 //
 // What is fused into the loader of X (it is staged through registers anyway):
 //   * GroupNorm apply (+ SiLU): x is the fp32 residual stream; the per-frame, per-channel
@@ -15,11 +17,10 @@
 //     paragraph): channel slabs below C_skip are read from the fp32 skip feature, the others from
 //     the cached deep feature at (y/2, x/2). Neither the concatenated nor the normalised tensor is
 //     ever written to memory.
-// A convolution stages, per 64-byte.. 128-byte channel slab, the 10 x 18 halo of its 8 x 16 pixel
-// tile once and walks the 9 taps over it by shifting LDS addresses; the weights of a (slab, tap)
-// step are streamed through a second LDS tile. Weight loads are issued two steps ahead, the next
-// slab's halo is fetched and activated one 16-byte packet per thread per tap while the MFMAs of
-// the current slab run.
+// A convolution stages, per 128-byte channel slab, the 10 x 18 halo of its 8 x 16 pixel tile once
+// and walks the 9 taps over it by shifting LDS addresses; the weights of a (slab, tap) step are
+// streamed through a second LDS tile one step ahead, and the next slab's halo is fetched and
+// activated one 16-byte packet per thread per tap while the MFMAs of the current slab run.
 #include "lc_internal.h"
 
 namespace lc {
@@ -29,6 +30,7 @@ namespace {
 constexpr int kRow = 128;     // K bytes per LDS row per step
 constexpr int kLds = 144;     // LDS row stride (bytes): 16-byte reads of 16 consecutive rows hit 64 distinct banks
 constexpr int kHaloW = 18, kHaloH = 10, kHalo = kHaloW * kHaloH;
+constexpr int kHaloRows = 192;  // LDS rows of a halo tile: 180 used, padded to 6 rounds of 32 rows
 
 struct GemmArgs {
   const void* x;        // PLAIN: T [rows][Cin]; NORM: float [..][Cin]; CAT: float skip [..][Cs]
@@ -57,18 +59,22 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   constexpr int VEC = Vec16<T>::N;               // operand elements per 16-byte LDS packet
   constexpr int BKC = kRow / (int)sizeof(T);     // K elements per step
   constexpr int BCO = CO_T * 32;
-  constexpr int XROWS = TAPS == 9 ? kHalo : 128;
+  constexpr int XROWS = TAPS == 9 ? kHaloRows : 128;
   constexpr int WP = (BCO * 8 + 255) / 256;      // weight packets per thread per step
-  constexpr int XR = TAPS == 9 ? (kHalo * 8 + 255) / 256 : 4;  // x packets per thread per slab
-  constexpr int KI = kRow / (M::K * (int)sizeof(T));           // MFMA k-steps per LDS row
+  constexpr int XR = XROWS / 32;                 // x packets per thread per slab
+  constexpr int KI = kRow / (M::K * (int)sizeof(T));  // MFMA k-steps per LDS row
+  constexpr int LKB = M::LK * (int)sizeof(T), KB = M::K * (int)sizeof(T);
   constexpr bool NORM = SRC != 0;
   constexpr bool SILU = SRC >= 2;
+  static_assert(KI % 2 == 0, "the k-steps of a row are split between two wavefronts");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   auto w_lds = [&](int b) { return smem + b * (BCO + XROWS) * kLds; };
   auto x_lds = [&](int b) { return smem + b * (BCO + XROWS) * kLds + BCO * kLds; };
 
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int lp = lane & 31, hh = lane >> 5;
+  // wavefront = (pixel half, K half): 64 pixels x all BCO channels over half of every K row
+  const int pxh = wid & 1, kh = wid >> 1;
   const int co0 = blockIdx.y * BCO;
   const T* __restrict__ Wt = (const T*)a.w;
 
@@ -85,56 +91,58 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   }
   const int kp = tid & 7, lrow = tid >> 3;  // this thread moves packet kp of rows lrow + 32 * i
 
-  // ---------------- weights: registers two steps ahead of the MFMAs ----------------
-  Vec16<T> wreg[2][WP];
-  auto issue_w = [&](int step, Vec16<T> (&dst)[WP]) {
+  // ---------------- weights of the next step: global -> registers -> LDS ----------------
+  Vec16<T> wreg[WP];
+  auto issue_w = [&](int step) {
     const int slab = step / TAPS, tap = step - slab * TAPS;
     const int kofs = tap * a.Cin + slab * BKC + kp * VEC;
 #pragma unroll
     for (int i = 0; i < WP; ++i) {
-      const int r = lrow + 32 * i;
-      if (BCO % 32 == 0 || r < BCO) dst[i] = load16(Wt + (int64_t)(co0 + r) * a.ldw + kofs);
+      const int r = min(lrow + 32 * i, BCO - 1);
+      wreg[i] = load16(Wt + (int64_t)(co0 + r) * a.ldw + kofs);
     }
   };
-  auto store_w = [&](int buf, const Vec16<T> (&src)[WP]) {
+  auto store_w = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < WP; ++i) {
       const int r = lrow + 32 * i;
-      if (BCO % 32 == 0 || r < BCO) *reinterpret_cast<Vec16<T>*>(w_lds(buf) + r * kLds + kp * 16) = src[i];
+      if (BCO % 32 == 0 || r < BCO) *reinterpret_cast<Vec16<T>*>(w_lds(buf) + r * kLds + kp * 16) = wreg[i];
     }
   };
 
-  // ---------------- x packets: fetch raw, then activate + round + store ----------------
-  struct XRaw { float v[VEC]; bool ok; };
+  // ---------------- x packets: fetch raw (branch-free, clamped addresses), then activate + round + store ----
+  // raw bits as loaded (converted only when consumed, so that no wait follows the load)
+  struct XRaw { f32x4 q[2]; bool ok; };  // q[0] alone = one operand-type packet; q[0..1] = 8 floats (q[0] = 4 floats if T is float)
   struct Affine { float sc[VEC], sh[VEC]; };
-  // conv: packet round r of slab -> halo pixel (tid + 256 r) / 8; linear: row lrow + 32 r of the tile
+  // conv: round r of a slab -> halo row lrow + 32 r (rows >= 180 are padding, loaded from clamped
+  // addresses and never read); linear: row lrow + 32 r of the tile
+  auto load_raw = [&](const float* p, XRaw& o) {  // VEC floats
+    o.q[0] = *reinterpret_cast<const f32x4*>(p);
+    if (VEC == 8) o.q[1] = *reinterpret_cast<const f32x4*>(p + 4);
+  };
   auto fetch_x = [&](int slab, int r, XRaw& o) {
     const int c0 = slab * BKC + kp * VEC;
-    o.ok = false;
     if (TAPS == 9) {
-      const int q = tid + 256 * r;
-      const int hp = q >> 3;
-      if (hp >= kHalo) return;
+      const int hp = lrow + 32 * r;
       const int hy = hp / kHaloW, hx = hp - hy * kHaloW;
       const int iy = ty0 + hy - 1, ix = tx0 + hx - 1;
-      if (iy < 0 || iy >= a.H || ix < 0 || ix >= a.W) return;
-      o.ok = true;
-      if (SRC == 3 && c0 >= a.Cs) {
-        const int64_t dr = ((int64_t)frame * (a.H >> 1) + (iy >> 1)) * (a.W >> 1) + (ix >> 1);
-        load_f<T, VEC>((const T*)a.x2 + dr * (a.Cin - a.Cs) + (c0 - a.Cs), o.v);
+      o.ok = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+      const int cy = min(max(iy, 0), a.H - 1), cx = min(max(ix, 0), a.W - 1);
+      if (SRC == 3 && slab * BKC >= a.Cs) {  // uniform: a slab lies on one side of Cs
+        const int64_t dr = ((int64_t)frame * (a.H >> 1) + (cy >> 1)) * (a.W >> 1) + (cx >> 1);
+        o.q[0] = *reinterpret_cast<const f32x4*>((const T*)a.x2 + dr * (a.Cin - a.Cs) + (c0 - a.Cs));
       } else if (NORM) {
         const int ldx = SRC == 3 ? a.Cs : a.Cin;
-        load_f<float, VEC>((const float*)a.x + (((int64_t)frame * a.H + iy) * a.W + ix) * ldx + c0, o.v);
+        load_raw((const float*)a.x + (((int64_t)frame * a.H + cy) * a.W + cx) * ldx + c0, o);
       } else {
-        load_f<T, VEC>((const T*)a.x + (((int64_t)frame * a.H + iy) * a.W + ix) * a.Cin + c0, o.v);
+        o.q[0] = *reinterpret_cast<const f32x4*>((const T*)a.x + (((int64_t)frame * a.H + cy) * a.W + cx) * a.Cin + c0);
       }
     } else {
       const int64_t rr = row0 + lrow + 32 * r;
-      if (rr >= a.rows) return;
-      o.ok = true;
-      const int64_t sr = a.in_map(rr);
-      if (NORM) load_f<float, VEC>((const float*)a.x + sr * a.Cin + c0, o.v);
-      else load_f<T, VEC>((const T*)a.x + sr * a.Cin + c0, o.v);
+      o.ok = rr < a.rows;
+      const int64_t sr = a.in_map(o.ok ? rr : a.rows - 1);
+      if (NORM) load_raw((const float*)a.x + sr * a.Cin + c0, o);
+      else o.q[0] = *reinterpret_cast<const f32x4*>((const T*)a.x + sr * a.Cin + c0);
     }
   };
   // scale/shift of the channels this thread moves: conv = one set per slab (fixed frame); linear =
@@ -148,50 +156,62 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   };
   auto row_frame = [&](int r) -> int64_t {
     const int64_t rr = row0 + lrow + 32 * r;
-    return (rr < a.rows ? rr : 0) / a.in_map.rows_per_seg;
+    return (rr < a.rows ? rr : a.rows - 1) / a.in_map.rows_per_seg;
   };
-  auto finish_x = [&](int buf, int r, const XRaw& o, const Affine& af) {
-    int lr;
-    if (TAPS == 9) {
-      lr = (tid + 256 * r) >> 3;
-      if (lr >= kHalo) return;
-    } else {
-      lr = lrow + 32 * r;
-    }
+  auto finish_x = [&](int slab, int buf, int r, const XRaw& o, const Affine& af) {
+    const bool from_t = !NORM || (SRC == 3 && slab * BKC >= a.Cs);  // uniform
     Vec16<T> pk;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
-      float t = o.v[e];
+      float t;
+      if (from_t) {
+        if constexpr (sizeof(T) == 2) {  // element e of the bf16 packet held in q[0]
+          typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+          const uint32_t wd = __builtin_bit_cast(u32x4, o.q[0])[e >> 1];
+          t = __builtin_bit_cast(float, (e & 1) ? (wd & 0xffff0000u) : (wd << 16));
+        } else {
+          t = o.q[0][e];
+        }
+      } else {
+        t = o.q[e >> 2][e & 3];
+      }
       if (NORM) {
         t = fmaf(t, af.sc[e], af.sh[e]);
-        if (SILU) t = silu_f(t);
+        if (SILU) t = silu_fast(t);
       }
       pk.set(e, o.ok ? t : 0.f);
     }
-    *reinterpret_cast<Vec16<T>*>(x_lds(buf) + lr * kLds + kp * 16) = pk;
+    *reinterpret_cast<Vec16<T>*>(x_lds(buf) + (lrow + 32 * r) * kLds + kp * 16) = pk;
   };
 
-  f32x16 acc[CO_T];
+  f32x16 acc[CO_T][2];
 #pragma unroll
   for (int i = 0; i < CO_T; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // pixel of this lane inside the tile and its LDS row for tap (0,0)
-  const int p = wid * 32 + lp;
-  const int xrow0 = TAPS == 9 ? (p >> 4) * kHaloW + (p & 15) : p;
+  // the two pixels of this lane inside the tile and their LDS rows for tap (0,0)
+  const int p0 = pxh * 64 + lp, p1 = p0 + 32;
+  const int xr0 = TAPS == 9 ? (p0 >> 4) * kHaloW + (p0 & 15) : p0;
+  const int xr1 = TAPS == 9 ? (p1 >> 4) * kHaloW + (p1 & 15) : p1;
 
   auto compute = [&](int wbuf, int xbuf, int tap) {
-    const int xrow = TAPS == 9 ? xrow0 + (tap / 3) * kHaloW + (tap % 3) : xrow0;
-    const unsigned char* xl = x_lds(xbuf) + xrow * kLds + hh * (M::LK * (int)sizeof(T));
-    const unsigned char* wl = w_lds(wbuf) + lp * kLds + hh * (M::LK * (int)sizeof(T));
+    const int sh = TAPS == 9 ? (tap / 3) * kHaloW + (tap % 3) : 0;
+    const unsigned char* xb = x_lds(xbuf) + hh * LKB + kh * (KI / 2) * KB;
+    const unsigned char* xl0 = xb + (xr0 + sh) * kLds;
+    const unsigned char* xl1 = xb + (xr1 + sh) * kLds;
+    const unsigned char* wl = w_lds(wbuf) + lp * kLds + hh * LKB + kh * (KI / 2) * KB;
 #pragma unroll
-    for (int kk = 0; kk < KI; ++kk) {
-      const typename M::Frag xf = M::load((const T*)(xl + kk * M::K * (int)sizeof(T)));
+    for (int kk = 0; kk < KI / 2; ++kk) {
+      const typename M::Frag xf0 = M::load((const T*)(xl0 + kk * KB));
+      const typename M::Frag xf1 = M::load((const T*)(xl1 + kk * KB));
 #pragma unroll
       for (int i = 0; i < CO_T; ++i) {
-        const typename M::Frag wf = M::load((const T*)(wl + i * 32 * kLds + kk * M::K * (int)sizeof(T)));
-        M::mma(wf, xf, acc[i]);
+        const typename M::Frag wf = M::load((const T*)(wl + i * 32 * kLds + kk * KB));
+        M::mma(wf, xf0, acc[i][0]);
+        M::mma(wf, xf1, acc[i][1]);
       }
     }
   };
@@ -200,16 +220,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   const int nsteps = TAPS * nslab;
 
   // ---------------- prologue ----------------
-  issue_w(0, wreg[0]);
-  if (nsteps > 1) issue_w(1, wreg[1]);
   Affine aff[TAPS == 9 ? 1 : XR];
   XRaw xin[TAPS == 9 ? 1 : XR];
+  issue_w(0);
   if (TAPS == 9) {
     load_affine(0, frame, aff[0]);
 #pragma unroll
     for (int r = 0; r < XR; ++r) {
       fetch_x(0, r, xin[0]);
-      finish_x(0, r, xin[0], aff[0]);
+      finish_x(0, 0, r, xin[0], aff[0]);
     }
   } else {
 #pragma unroll
@@ -218,91 +237,129 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
       load_affine(0, row_frame(r), aff[r]);
     }
 #pragma unroll
-    for (int r = 0; r < XR; ++r) finish_x(0, r, xin[r], aff[r]);
+    for (int r = 0; r < XR; ++r) finish_x(0, 0, r, xin[r], aff[r]);
   }
-  store_w(0, wreg[0]);
+  store_w(0);
   __syncthreads();
 
-  // ---------------- main loop, unrolled by two so that the register sets are static ----------------
-  auto step = [&](int s, Vec16<T> (&w_free)[WP], Vec16<T> (&w_next)[WP]) {
-    const int slab = s / TAPS, tap = s - slab * TAPS;
-    if (s + 2 < nsteps) issue_w(s + 2, w_free);
-    if (TAPS == 9) {
-      // next slab's halo, one packet round per tap: finish round tap-1, fetch round tap
-      if (slab + 1 < nslab) {
-        if (tap >= 1 && tap <= XR) finish_x((slab + 1) & 1, tap - 1, xin[0], aff[0]);
-        if (tap == 0) load_affine(slab + 1, frame, aff[0]);
-        if (tap < XR) fetch_x(slab + 1, tap, xin[0]);
+  // ---------------- main loop ----------------
+  // Every global load of a step is issued before the MFMAs of the step and consumed after them, in
+  // issue order, so each wait is for "everything outstanding" and costs nothing extra.
+  // The scheduling barriers pin that order: left alone, the compiler sinks the loads below the MFMAs.
+  if (TAPS == 9) {
+    for (int slab = 0; slab < nslab; ++slab) {
+      const bool more = slab + 1 < nslab;
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int s = slab * 9 + tap;
+        const bool last = !more && tap == 8;
+        // next slab's halo, one packet round per tap: finish round tap-1, fetch round tap
+        if (more && tap >= 1 && tap <= XR) finish_x(slab + 1, (slab + 1) & 1, tap - 1, xin[0], aff[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) {
+          if (tap == 0) load_affine(slab + 1, frame, aff[0]);
+          if (tap < XR) fetch_x(slab + 1, tap, xin[0]);
+        }
+        if (!last) issue_w(s + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(s & 1, slab & 1, tap);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!last) store_w((s + 1) & 1);
+        __syncthreads();
       }
-      compute(s & 1, slab & 1, tap);
-    } else {
-      if (s + 1 < nsteps) {
+    }
+  } else {
+    for (int s = 0; s < nsteps; ++s) {
+      const bool more = s + 1 < nsteps;
+      if (more) {
 #pragma unroll
         for (int r = 0; r < XR; ++r) {
           fetch_x(s + 1, r, xin[r]);
           load_affine(s + 1, row_frame(r), aff[r]);
         }
+        issue_w(s + 1);
       }
+      __builtin_amdgcn_sched_barrier(0);
       compute(s & 1, s & 1, 0);
-      if (s + 1 < nsteps) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) {
 #pragma unroll
-        for (int r = 0; r < XR; ++r) finish_x((s + 1) & 1, r, xin[r], aff[r]);
+        for (int r = 0; r < XR; ++r) finish_x(s + 1, (s + 1) & 1, r, xin[r], aff[r]);
+        store_w((s + 1) & 1);
       }
+      __syncthreads();
     }
-    if (s + 1 < nsteps) store_w((s + 1) & 1, w_next);
-    __syncthreads();
-  };
-  for (int s = 0; s < nsteps; s += 2) {
-    step(s, wreg[0], wreg[1]);
-    if (s + 1 < nsteps) step(s + 1, wreg[1], wreg[0]);
   }
 
-  // ---------------- epilogue: lane holds, for pixel p, channels co0 + 32 i + 8 g + 4 hh + {0..3} ----------------
-  OT* Y = (OT*)a.y;
-  const float* R = a.res;  // may alias Y (in-place residual)
-  int64_t orow;
-  int oy = 0, ox = 0;
-  bool ok;
-  if (TAPS == 9) {
-    oy = ty0 + (p >> 4);
-    ox = tx0 + (p & 15);
-    ok = oy < a.H && ox < a.W;
-    orow = ((int64_t)frame * a.H + oy) * a.W + ox;
-  } else {
-    ok = row0 + p < a.rows;
-    orow = ok ? a.out_map(row0 + p) : 0;
+  // ---------------- fold the two K halves: the upper half hands its tiles over through LDS ----------------
+  float* red = reinterpret_cast<float*>(smem) + pxh * (CO_T * 2 * 16 * 64);
+  if (kh == 1) {
+#pragma unroll
+    for (int i = 0; i < CO_T; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[((i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
   }
-  if (!ok) return;
+  __syncthreads();
+  if (kh == 1) return;
 #pragma unroll
-  for (int i = 0; i < CO_T; ++i) {
+  for (int i = 0; i < CO_T; ++i)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int co = co0 + i * 32 + g * 8 + hh * 4;
-      if (PLANAR) {
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (co + e < a.Cout_store) {
-            const float v = acc[i][g * 4 + e] + (a.bias ? a.bias[co + e] : 0.f);
-            Y[(((int64_t)frame * a.Cout_store + co + e) * a.H + oy) * a.W + ox] = from_f32<OT>(v);
+      for (int r = 0; r < 16; ++r) acc[i][j][r] += red[((i * 2 + j) * 16 + r) * 64 + lane];
+
+  // ---------------- epilogue: lane holds, for pixel p_j, channels co0 + 32 i + 8 g + 4 hh + {0..3} ----------------
+  OT* Y = (OT*)a.y;
+  const float* R = a.res;  // may alias Y (in-place residual of a linear layer)
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int p = j == 0 ? p0 : p1;
+    int64_t orow;
+    int oy = 0, ox = 0;
+    bool ok;
+    if (TAPS == 9) {
+      oy = ty0 + (p >> 4);
+      ox = tx0 + (p & 15);
+      ok = oy < a.H && ox < a.W;
+      orow = ((int64_t)frame * a.H + oy) * a.W + ox;
+    } else {
+      ok = row0 + p < a.rows;
+      orow = ok ? a.out_map(row0 + p) : 0;
+    }
+    if (!ok) continue;
+#pragma unroll
+    for (int i = 0; i < CO_T; ++i) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int co = co0 + i * 32 + g * 8 + hh * 4;
+        if (PLANAR) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (co + e < a.Cout_store) {
+              const float v = acc[i][j][g * 4 + e] + (a.bias ? a.bias[co + e] : 0.f);
+              Y[(((int64_t)frame * a.Cout_store + co + e) * a.H + oy) * a.W + ox] = from_f32<OT>(v);
+            }
           }
-        }
-      } else {
-        float v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][g * 4 + e] + (a.bias ? a.bias[co + e] : 0.f);
-        const int64_t o = orow * a.Cout_store + co;
-        if (R) {
-          const f32x4 rv = *reinterpret_cast<const f32x4*>(R + o);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += rv[e];
-        }
-        if constexpr (sizeof(OT) == 2) {
-          bf16x4 ov;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16_t>(v[e]);
-          *reinterpret_cast<bf16x4*>((bf16_t*)Y + o) = ov;
         } else {
-          *reinterpret_cast<f32x4*>((float*)Y + o) = f32x4{v[0], v[1], v[2], v[3]};
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + (a.bias ? a.bias[co + e] : 0.f);
+          const int64_t o = orow * a.Cout_store + co;
+          if (R) {
+            const f32x4 rv = *reinterpret_cast<const f32x4*>(R + o);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += rv[e];
+          }
+          if constexpr (sizeof(OT) == 2) {
+            bf16x4 ov;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16_t>(v[e]);
+            *reinterpret_cast<bf16x4*>((bf16_t*)Y + o) = ov;
+          } else {
+            *reinterpret_cast<f32x4*>((float*)Y + o) = f32x4{v[0], v[1], v[2], v[3]};
+          }
         }
       }
     }
@@ -312,8 +369,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
 template <class T, class OT, int TAPS, int CO_T, int SRC, bool PLANAR>
 static hipError_t run_gemm(hipStream_t s, const FusedDesc& d) {
   constexpr int BCO = CO_T * 32;
-  constexpr int XROWS = TAPS == 9 ? kHalo : 128;
+  constexpr int XROWS = TAPS == 9 ? kHaloRows : 128;
   constexpr int lds = gemm_lds_bytes<BCO, XROWS>();
+  static_assert(lds >= 2 * CO_T * 2 * 16 * 64 * 4, "the K-half hand-over reuses the operand tiles");
   auto kern = gemm_kernel<T, OT, TAPS, CO_T, SRC, PLANAR>;
   static bool attr_done = false;  // per instantiation
   if (!attr_done) {
