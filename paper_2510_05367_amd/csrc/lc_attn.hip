@@ -37,8 +37,12 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
   constexpr int KROW = DP * (int)sizeof(T) + 16;    // LDS row stride of the K tile, bytes
   constexpr int VROW = kKeys * (int)sizeof(T) + 16; // LDS row stride of the V^T tile, bytes
   constexpr int PSTEPS = 32 / M::K;                 // P^T V instructions per 32-key sub-tile
-  __shared__ __attribute__((aligned(16))) unsigned char k_lds[kKeys * KROW];
-  __shared__ __attribute__((aligned(16))) unsigned char v_lds[DM * 32 * VROW];
+  constexpr int KT = kKeys / 32;                    // 32-key sub-tiles per stage
+  constexpr int KBYTES = kKeys * KROW, VBYTES = DM * 32 * VROW;
+  constexpr int PK = D / VEC;                       // 16-byte packets per K / V row
+  constexpr int NP = (kKeys * PK + 255) / 256;      // K (and V) packets per thread per stage
+  __shared__ __attribute__((aligned(16))) unsigned char k_lds[2][KBYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char v_lds[2][VBYTES];
 
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int lq = lane & 31, hh = lane >> 5;
@@ -47,9 +51,36 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
   const T* __restrict__ base = qkv + (int64_t)frame * T_tok * ld + head * D;
   const int qblk = q0 + blockIdx.x * (4 * NQT * 32) + wid * (NQT * 32);
 
-  // zero the V^T rows beyond D once (they feed unused rows of O^T)
-  for (int i = tid; i < DM * 32 * VROW / 4; i += 256) reinterpret_cast<uint32_t*>(v_lds)[i] = 0u;
-  for (int i = tid; i < kKeys * KROW / 4; i += 256) reinterpret_cast<uint32_t*>(k_lds)[i] = 0u;
+  // zero both buffers once: K columns beyond D and V^T rows beyond D feed padded MFMA lanes
+  for (int i = tid; i < 2 * KBYTES / 4; i += 256) reinterpret_cast<uint32_t*>(&k_lds[0][0])[i] = 0u;
+  for (int i = tid; i < 2 * VBYTES / 4; i += 256) reinterpret_cast<uint32_t*>(&v_lds[0][0])[i] = 0u;
+
+  // ---- staging: this thread moves packets i = tid + 256 j of a stage (key i / PK, packet i % PK)
+  Vec16<T> kreg[NP], vreg[NP];
+  auto fetch_kv = [&](int k0) {
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int i = tid + 256 * j;
+      const int key = min(i / PK, kKeys - 1), pk = i % PK;
+      const int gk = min(k0 + key, T_tok - 1);  // clamped: keys beyond the sequence are masked later
+      kreg[j] = load16(base + (int64_t)gk * ld + C + pk * VEC);
+      vreg[j] = load16(base + (int64_t)gk * ld + 2 * C + pk * VEC);
+    }
+  };
+  auto stash_kv = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int i = tid + 256 * j;
+      if (i < kKeys * PK) {
+        const int key = i / PK, pk = i % PK;
+        *reinterpret_cast<Vec16<T>*>(&k_lds[buf][key * KROW + pk * 16]) = kreg[j];
+        const int col = vcol<T>(key);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          *reinterpret_cast<T*>(&v_lds[buf][(pk * VEC + e) * VROW + col * (int)sizeof(T)]) = vreg[j].v[e];
+      }
+    }
+  };
 
   // ---- Q fragments (B operand of S^T = K Q^T): lane holds query lq, k-slots M::LK*hh + M::K*kk
   typename M::Frag qf[NQT][KSTEPS];
@@ -63,7 +94,7 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
     }
   }
   f32x16 o[NQT][DM];
-  float m_run[NQT], l_run[NQT];
+  float m_run[NQT], l_run[NQT];  // running max (raw score units) and per-lane partial sum
 #pragma unroll
   for (int t = 0; t < NQT; ++t) {
     m_run[t] = -INFINITY;
@@ -73,95 +104,102 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[t][mt][r] = 0.f;
   }
+  fetch_kv(0);
+  __syncthreads();  // zero fill done
+  stash_kv(0);
   __syncthreads();
 
-  constexpr int PK = D / VEC;  // 16-byte packets per K / V row
-  for (int k0 = 0; k0 < T_tok; k0 += kKeys) {
-    // ---- stage 64 keys: K rows as they are, V transposed
-    for (int i = tid; i < kKeys * PK; i += 256) {
-      const int key = i / PK, pk = i - key * PK;
-      const int gk = k0 + key;
-      Vec16<T> kv = zero16<T>(), vv = zero16<T>();
-      if (gk < T_tok) {
-        kv = load16(base + (int64_t)gk * ld + C + pk * VEC);
-        vv = load16(base + (int64_t)gk * ld + 2 * C + pk * VEC);
-      }
-      *reinterpret_cast<Vec16<T>*>(k_lds + key * KROW + pk * 16) = kv;
-      const int col = vcol<T>(key);
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-        *reinterpret_cast<T*>(v_lds + (pk * VEC + e) * VROW + col * (int)sizeof(T)) = vv.v[e];
-    }
-    __syncthreads();
+  const int nstage = (T_tok + kKeys - 1) / kKeys;
+  for (int st_i = 0; st_i < nstage; ++st_i) {
+    const int k0 = st_i * kKeys, buf = st_i & 1;
+    const bool tail = k0 + kKeys > T_tok;  // uniform: some keys of this stage lie beyond the sequence
+    if (st_i + 1 < nstage) fetch_kv(k0 + kKeys);
 
+    // ---- S^T sub-tiles [32 keys][32 queries]
+    f32x16 sc[NQT][KT];
 #pragma unroll
-    for (int kt = 0; kt < kKeys / 32; ++kt) {
-      if (k0 + kt * 32 >= T_tok) break;  // uniform: whole sub-tile beyond the sequence
-      // ---- S^T sub-tile [32 keys][32 queries] per query tile
+    for (int kt = 0; kt < KT; ++kt) {
       typename M::Frag kf[KSTEPS];
 #pragma unroll
       for (int kk = 0; kk < KSTEPS; ++kk)
-        kf[kk] = M::load(reinterpret_cast<const T*>(k_lds + (kt * 32 + lq) * KROW) + kk * M::K + hh * M::LK);
-      typename M::Frag pf[NQT][PSTEPS];
+        kf[kk] = M::load(reinterpret_cast<const T*>(&k_lds[buf][(kt * 32 + lq) * KROW]) + kk * M::K + hh * M::LK);
 #pragma unroll
       for (int t = 0; t < NQT; ++t) {
-        f32x16 s;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        for (int r = 0; r < 16; ++r) sc[t][kt][r] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) M::mma(kf[kk], qf[t][kk], s);
-        // lane holds keys  k0 + kt*32 + 8*(r/4) + 4*hh + r%4  of query lq
-        float mx = -INFINITY;
+        for (int kk = 0; kk < KSTEPS; ++kk) M::mma(kf[kk], qf[t][kk], sc[t][kt]);
+      }
+    }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = k0 + kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-          s[r] = key < T_tok ? s[r] * scale_log2e : -INFINITY;
-          mx = fmaxf(mx, s[r]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    for (int t = 0; t < NQT; ++t) {
+      // lane holds keys  k0 + kt*32 + 8*(r/4) + 4*hh + r%4  of query lq
+      if (tail) {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (k0 + kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3) >= T_tok) sc[t][kt][r] = -INFINITY;
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[t][kt][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // a stage always holds at least one valid key: finite
+      // rescale only when some query of the wavefront saw a new maximum (exp2(0) = 1 exactly, so the
+      // result does not depend on whether the branch is taken for the other lanes)
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[t]) != 0) {
         const float m_new = fmaxf(m_run[t], mx);
-        const float alpha = exp2f(m_run[t] - m_new);  // m_new is finite: the sub-tile has a valid key
+        const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2e);
         m_run[t] = m_new;
-        float ps = 0.f;
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = exp2f(s[r] - m_new);
-          ps += p[r];
-        }
-        l_run[t] = l_run[t] * alpha + ps;
+        l_run[t] *= alpha;
 #pragma unroll
         for (int mt = 0; mt < DM; ++mt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[t][mt][r] *= alpha;
-        // pack P^T: instruction step ps_ takes registers [LK*ps_ .. ) of this lane
+      }
+      const float mc = m_run[t] * scale_log2e;
+      typename M::Frag pf[KT][PSTEPS];
+      float ps = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt) {
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[r] = __builtin_amdgcn_exp2f(fmaf(sc[t][kt][r], scale_log2e, -mc));
+          ps += p[r];
+        }
         if constexpr (sizeof(T) == 2) {
 #pragma unroll
           for (int st = 0; st < PSTEPS; ++st)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[t][st][e] = static_cast<bf16_t>(p[st * 8 + e]);
+            for (int e = 0; e < 8; ++e) pf[kt][st][e] = static_cast<bf16_t>(p[st * 8 + e]);
         } else {
 #pragma unroll
-          for (int st = 0; st < PSTEPS; ++st) pf[t][st] = p[st];
+          for (int st = 0; st < PSTEPS; ++st) pf[kt][st] = p[st];
         }
       }
-      // ---- O^T += V^T P^T. Step st contracts, in lane half hh, the keys of registers
+      l_run[t] += ps;
+      // ---- O^T += V^T P^T. Step st of sub-tile kt contracts, in lane half hh, the keys of registers
       //      [LK*st, LK*st + LK): bf16 -> keys 16*st + 4*hh + {0..3} and 16*st + 8 + 4*hh + {0..3}
-      //      (contiguous after the vcol permutation, at column 16*st + 8*hh); fp32 -> the single
-      //      key 8*(st/4) + 4*hh + st%4.
+      //      (contiguous after the vcol permutation, at column 16*st + 8*hh); fp32 -> the single key
+      //      8*(st/4) + 4*hh + st%4.
 #pragma unroll
-      for (int st = 0; st < PSTEPS; ++st) {
-        int col;
-        if constexpr (sizeof(T) == 2) col = kt * 32 + 16 * st + 8 * hh;
-        else col = kt * 32 + 8 * (st >> 2) + 4 * hh + (st & 3);
+      for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-        for (int mt = 0; mt < DM; ++mt) {
-          typename M::Frag vf = M::load(reinterpret_cast<const T*>(v_lds + (mt * 32 + lq) * VROW) + col);
+        for (int st = 0; st < PSTEPS; ++st) {
+          int col;
+          if constexpr (sizeof(T) == 2) col = kt * 32 + 16 * st + 8 * hh;
+          else col = kt * 32 + 8 * (st >> 2) + 4 * hh + (st & 3);
 #pragma unroll
-          for (int t = 0; t < NQT; ++t) M::mma(vf, pf[t][st], o[t][mt]);
+          for (int mt = 0; mt < DM; ++mt) {
+            const typename M::Frag vf = M::load(reinterpret_cast<const T*>(&v_lds[buf][(mt * 32 + lq) * VROW]) + col);
+            M::mma(vf, pf[kt][st], o[t][mt]);
+          }
         }
-      }
     }
+    if (st_i + 1 < nstage) stash_kv(buf ^ 1);
     __syncthreads();
   }
 
