@@ -135,10 +135,11 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   const int64_t pc = (int64_t)p.fc * T;   // pixels of a frame chunk
   const int64_t rt = N * p.tc;            // rows of a temporal pass
   // frame-chunk pass: ping-pong copy of the fp32 stream + q,k,v + attention output
-  size_t wsb = (size_t)(pc * g.C) * 4 + (size_t)(4 * g.C * pc) * es;
+  const int64_t Tp = attn_tp((int)T);  // V^T rows of the spatial kernel are padded to 64 tokens
+  size_t wsb = (size_t)(pc * g.C) * 4 + (size_t)(3 * g.C * pc + (int64_t)p.fc * g.C * Tp) * es;
   wsb = std::max(wsb, (size_t)(4 * g.C * rt) * es);                 // temporal pass: q,k,v + attention output
   wsb = std::max(wsb, (size_t)((pc / 4) * (int64_t)g.C_deep) * 4);  // deep stand-in: fp32 d0
-  wsb += 2 * kAlign;
+  wsb += 4 * kAlign;
   p.ws_bytes = align_up(wsb) + kAlign;
   p.off_ws = off; off += p.ws_bytes;
   p.total = off;
@@ -268,8 +269,10 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     const int64_t pc = (int64_t)nf * T;
     char* hc = h + (size_t)n0 * T * C * 4;
     char* hb = ws;                                           // fp32 ping-pong partner of hc
-    char* qkv = ws + align_up((size_t)pc * C * 4);
-    char* ao = qkv + align_up((size_t)pc * 3 * C * es);
+    const int Tp = attn_tp(T);
+    char* qk = ws + align_up((size_t)pc * C * 4);                 // q,k rows [pc][2C]
+    char* vt = qk + align_up((size_t)pc * 2 * C * es);            // V^T [nf][C][Tp]
+    char* ao = vt + align_up((size_t)nf * C * Tp * es);
     // a 3x3 convolution cannot run in place (its halo reads rows other workgroups write), so the
     // residual blocks alternate between hc and hb; start so that the last one lands in hc
     char* cur = (g.n_res % 2 == 0) ? hc : hb;
@@ -284,11 +287,16 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     lc_status s = gn_scale_shift(c, hc, nf, T, C, w.sattn.gn);
     if (s != LC_OK) return s;
     RowMap fm{0, T, T};  // dense rows; frame of row r = r / T
-    LC_LAUNCH(c, LC_K_QKV, launch_fused(c->cs, flinear_desc(c, w.sattn.wqkv, nullptr, C, 3 * C, pc, 1, fm, dense_map(),
-                                                            hc, nullptr, qkv, 0)));
+    {
+      // q and k as rows, v transposed straight from the GEMM epilogue into the layout the attention
+      // kernel stages (no scattered transposition later)
+      FusedDesc d = flinear_desc(c, w.sattn.wqkv, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
+      d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
+      LC_LAUNCH(c, LC_K_QKV, launch_fused(c->cs, d));
+    }
     for (int q0 = 0; q0 < T; q0 += p.qc)
-      LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, ao, nf, T, g.heads, g.head_dim, q0,
-                                                        std::min(q0 + p.qc, T)));
+      LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
+                                                        g.head_dim, q0, std::min(q0 + p.qc, T)));
     LC_LAUNCH(c, LC_K_PROJ, launch_fused(c->cs, flinear_desc(c, w.sattn.wo, w.sattn.bo, C, C, pc, 0, dense_map(),
                                                              dense_map(), ao, hc, hc, 1)));
   }
@@ -832,8 +840,17 @@ lc_status lc_op_spatial_attention(lc_ctx* c, const void* qkv, void* out, int fra
   if (s != LC_OK) return s;
   if (!qkv || !out) return fail(c, LC_ERR_ARG, "NULL tensor");
   const lc_config& g = c->cfg;
-  if (q0 < 0 || q1 > g.H * g.W || q0 >= q1) return fail(c, LC_ERR_ARG, "query range out of bounds");
-  LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, out, frames, g.H * g.W, g.heads, g.head_dim, q0, q1));
+  const int T = g.H * g.W, Tp = attn_tp(T);
+  if (q0 < 0 || q1 > T || q0 >= q1) return fail(c, LC_ERR_ARG, "query range out of bounds");
+  const size_t es = dtype_size(g.dtype);
+  if ((size_t)frames * g.C * Tp * es > c->plan.ws_bytes)
+    return fail(c, LC_ERR_NOMEM, "chunk scratch too small for %d frames", frames);
+  // the kernel wants V transposed (the steps get that layout straight from the q,k,v GEMM)
+  char* vt = ws_ptr(c);
+  LC_LAUNCH(c, LC_K_SATTN, launch_make_vt(c->cs, g.dtype, (const char*)qkv + (size_t)2 * g.C * es, 3 * g.C, vt, frames, T,
+                                          Tp, g.C));
+  LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * g.C, vt, Tp, out, frames, T, g.heads,
+                                                    g.head_dim, q0, q1));
   return LC_OK;
 }
 

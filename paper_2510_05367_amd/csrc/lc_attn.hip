@@ -16,19 +16,16 @@ namespace lc {
 
 constexpr int kKeys = 64;  // keys per LDS stage
 
-// Column of key `k` (0..63) inside a V^T row in LDS. For bf16 the four 4-key blocks of every 16
-// keys are stored in the order 0,2,1,3 so that the 8 keys one lane contracts in one instruction
-// (see below) are 16 contiguous bytes.
-template <class T> __device__ __forceinline__ int vcol(int k);
-template <> __device__ __forceinline__ int vcol<float>(int k) { return k; }
-template <> __device__ __forceinline__ int vcol<bf16_t>(int k) {
-  const int b = (k >> 2) & 3;
-  return (k & ~15) | ((b & 1) << 3) | ((b >> 1) << 2) | (k & 3);
-}
+// qk: rows [frame*T + token] of stride ldq holding q at column 0 and k at column C (per head: + head*D).
+// vt: V transposed and block-permuted, [frame][C][Tp] with token t of a row at column vcol(t), Tp a
+// multiple of 64 (columns beyond T are never trusted: they are zeroed while staging).
+// the permutation is an involution on the 4-key blocks (it swaps blocks 1 and 2)
+template <class T> __device__ __forceinline__ int vcol_inv(int c) { return vcol<T>(c); }
 
 template <class T, int D, int NQT>
-__global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__ qkv, T* __restrict__ out, int T_tok,
-                                                           int C, int q0, int q1, float scale_log2e) {
+__global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restrict__ qk, int ldq,
+                                                           const T* __restrict__ vt, int Tp, T* __restrict__ out,
+                                                           int T_tok, int C, int q0, int q1, float scale_log2e) {
   typedef Mma32<T> M;
   constexpr int VEC = Vec16<T>::N;
   constexpr int DP = (D + M::K - 1) / M::K * M::K;  // contraction length of Q K^T, padded
@@ -47,16 +44,20 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int lq = lane & 31, hh = lane >> 5;
   const int head = blockIdx.y, frame = blockIdx.z;
-  const int ld = 3 * C;
-  const T* __restrict__ base = qkv + (int64_t)frame * T_tok * ld + head * D;
+  const int ld = ldq;
+  const T* __restrict__ base = qk + (int64_t)frame * T_tok * ld + head * D;
+  const T* __restrict__ vbase = vt + ((int64_t)frame * C + head * D) * Tp;
   const int qblk = q0 + blockIdx.x * (4 * NQT * 32) + wid * (NQT * 32);
 
   // zero both buffers once: K columns beyond D and V^T rows beyond D feed padded MFMA lanes
   for (int i = tid; i < 2 * KBYTES / 4; i += 256) reinterpret_cast<uint32_t*>(&k_lds[0][0])[i] = 0u;
   for (int i = tid; i < 2 * VBYTES / 4; i += 256) reinterpret_cast<uint32_t*>(&v_lds[0][0])[i] = 0u;
 
-  // ---- staging: this thread moves packets i = tid + 256 j of a stage (key i / PK, packet i % PK)
-  Vec16<T> kreg[NP], vreg[NP];
+  // ---- staging: K packet i = tid + 256 j of a stage is (key i / PK, packet i % PK); V^T packet i is
+  //      (dim i / VPK, packet i % VPK) and is already in LDS order
+  constexpr int VPK = kKeys / VEC;              // 16-byte packets per V^T row of a stage
+  constexpr int NPV = (D * VPK + 255) / 256;
+  Vec16<T> kreg[NP], vreg[NPV];
   auto fetch_kv = [&](int k0) {
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
@@ -64,20 +65,33 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
       const int key = min(i / PK, kKeys - 1), pk = i % PK;
       const int gk = min(k0 + key, T_tok - 1);  // clamped: keys beyond the sequence are masked later
       kreg[j] = load16(base + (int64_t)gk * ld + C + pk * VEC);
-      vreg[j] = load16(base + (int64_t)gk * ld + 2 * C + pk * VEC);
+    }
+#pragma unroll
+    for (int j = 0; j < NPV; ++j) {
+      const int i = tid + 256 * j;
+      const int dim = min(i / VPK, D - 1), pk = i % VPK;
+      vreg[j] = load16(vbase + (int64_t)dim * Tp + k0 + pk * VEC);
     }
   };
-  auto stash_kv = [&](int buf) {
+  auto stash_kv = [&](int buf, int k0) {
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
       const int i = tid + 256 * j;
-      if (i < kKeys * PK) {
-        const int key = i / PK, pk = i % PK;
-        *reinterpret_cast<Vec16<T>*>(&k_lds[buf][key * KROW + pk * 16]) = kreg[j];
-        const int col = vcol<T>(key);
+      if (i < kKeys * PK) *reinterpret_cast<Vec16<T>*>(&k_lds[buf][(i / PK) * KROW + (i % PK) * 16]) = kreg[j];
+    }
+    const bool tail = k0 + kKeys > T_tok;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e)
-          *reinterpret_cast<T*>(&v_lds[buf][(pk * VEC + e) * VROW + col * (int)sizeof(T)]) = vreg[j].v[e];
+    for (int j = 0; j < NPV; ++j) {
+      const int i = tid + 256 * j;
+      if (i < D * VPK) {
+        const int dim = i / VPK, pk = i % VPK;
+        Vec16<T> v = vreg[j];
+        if (tail) {  // column c of the stage holds the token whose vcol is c; zero what lies beyond T
+#pragma unroll
+          for (int e = 0; e < VEC; ++e)
+            if (k0 + vcol_inv<T>(pk * VEC + e) >= T_tok) v.set(e, 0.f);
+        }
+        *reinterpret_cast<Vec16<T>*>(&v_lds[buf][dim * VROW + pk * 16]) = v;
       }
     }
   };
@@ -106,7 +120,7 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
   }
   fetch_kv(0);
   __syncthreads();  // zero fill done
-  stash_kv(0);
+  stash_kv(0, 0);
   __syncthreads();
 
   const int nstage = (T_tok + kKeys - 1) / kKeys;
@@ -199,7 +213,7 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
           }
         }
     }
-    if (st_i + 1 < nstage) stash_kv(buf ^ 1);
+    if (st_i + 1 < nstage) stash_kv(buf ^ 1, k0 + kKeys);
     __syncthreads();
   }
 
@@ -225,12 +239,12 @@ __global__ __launch_bounds__(256) void spatial_attn_kernel(const T* __restrict__
 }
 
 template <class T, int NQT>
-static hipError_t spatial_dispatch(hipStream_t s, const T* qkv, T* out, int frames, int T_tok, int heads, int d,
-                                   int q0, int q1) {
+static hipError_t spatial_dispatch(hipStream_t s, const T* qk, int ldq, const T* vt, int Tp, T* out, int frames,
+                                   int T_tok, int heads, int d, int q0, int q1) {
   const int C = heads * d;
   const float sl = 1.4426950408889634f / sqrtf((float)d);
   dim3 grid((q1 - q0 + 4 * NQT * 32 - 1) / (4 * NQT * 32), heads, frames);
-#define LC_GO(D) spatial_attn_kernel<T, D, NQT><<<grid, 256, 0, s>>>(qkv, out, T_tok, C, q0, q1, sl)
+#define LC_GO(D) spatial_attn_kernel<T, D, NQT><<<grid, 256, 0, s>>>(qk, ldq, vt, Tp, out, T_tok, C, q0, q1, sl)
   switch (d) {
     case 8: LC_GO(8); break;
     case 16: LC_GO(16); break;
@@ -243,11 +257,38 @@ static hipError_t spatial_dispatch(hipStream_t s, const T* qkv, T* out, int fram
   return hipGetLastError();
 }
 
-hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qkv, void* out, int frames, int T,
-                                    int heads, int d, int q0, int q1) {
+hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
+                                    int frames, int T, int heads, int d, int q0, int q1) {
   if (frames <= 0 || q1 <= q0) return hipSuccess;
-  if (dt == kBF16) return spatial_dispatch<bf16_t, 2>(s, (const bf16_t*)qkv, (bf16_t*)out, frames, T, heads, d, q0, q1);
-  return spatial_dispatch<float, 1>(s, (const float*)qkv, (float*)out, frames, T, heads, d, q0, q1);
+  if (Tp % kKeys != 0 || Tp < T) return hipErrorInvalidValue;
+  if (dt == kBF16)
+    return spatial_dispatch<bf16_t, 2>(s, (const bf16_t*)qk, ldq, (const bf16_t*)vt, Tp, (bf16_t*)out, frames, T, heads,
+                                       d, q0, q1);
+  return spatial_dispatch<float, 1>(s, (const float*)qk, ldq, (const float*)vt, Tp, (float*)out, frames, T, heads, d,
+                                    q0, q1);
+}
+
+// V^T in the layout the spatial kernel stages: vt[frame][c][vcol(t)] = v[frame*T + t][c] (v rows of stride ldv)
+template <class T>
+__global__ __launch_bounds__(256) void make_vt_kernel(const T* __restrict__ v, int ldv, T* __restrict__ vt, int T_tok,
+                                                      int Tp, int C) {
+  __shared__ T tile[32][33];
+  const int f = blockIdx.z, t0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int k = ty; k < 32; k += 8)
+    if (t0 + k < T_tok && c0 + tx < C) tile[k][tx] = v[((int64_t)f * T_tok + t0 + k) * ldv + c0 + tx];
+  __syncthreads();
+  for (int k = ty; k < 32; k += 8) {
+    const int t = t0 + tx;
+    if (c0 + k < C && t < T_tok) vt[((int64_t)f * C + c0 + k) * Tp + (t & ~63) + vcol<T>(t & 63)] = tile[tx][k];
+  }
+}
+hipError_t launch_make_vt(hipStream_t s, int dt, const void* v, int ldv, void* vt, int frames, int T, int Tp, int C) {
+  if (frames <= 0) return hipSuccess;
+  dim3 grid((T + 31) / 32, (C + 31) / 32, frames);
+  if (dt == kBF16) make_vt_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t*)v, ldv, (bf16_t*)vt, T, Tp, C);
+  else make_vt_kernel<float><<<grid, 256, 0, s>>>((const float*)v, ldv, (float*)vt, T, Tp, C);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------

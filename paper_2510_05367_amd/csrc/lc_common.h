@@ -165,6 +165,16 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Column of key `k` (0..63) inside a V^T row in LDS. For bf16 the four 4-key blocks of every 16
+// keys are stored in the order 0,2,1,3 so that the 8 keys one lane contracts in one instruction
+// (see below) are 16 contiguous bytes.
+template <class T> __device__ __forceinline__ int vcol(int k);
+template <> __device__ __forceinline__ int vcol<float>(int k) { return k; }
+template <> __device__ __forceinline__ int vcol<bf16_t>(int k) {
+  const int b = (k >> 2) & 3;
+  return (k & ~15) | ((b & 1) << 3) | ((b >> 1) << 2) | (k & 3);
+}
+
 // Source-row mapping of a dense block of `rows` rows onto a larger row-major matrix:
 // dense row r lives at source row  base + (r / rows_per_seg) * seg_stride + (r % rows_per_seg).
 // A frame chunk is one segment; a token chunk takes `rows_per_seg` positions out of every frame.

@@ -41,7 +41,9 @@ struct GemmArgs {
   const float* bias;
   const float* res;     // fp32, indexed like y (may alias y)
   void* y;
-  int Cin, Cs, Cout_store, ldw;
+  int Cin, Cs, Cout, Cout_store, ldw;
+  void* yt;             // linear only: channels >= yt_from go, transposed, to the V^T layout of spatial attention
+  int yt_from, yt_T, yt_Tp;
   int frames, H, W, tiles_x, tiles_y;
   int64_t rows;
   RowMap in_map, out_map;
@@ -346,6 +348,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + (a.bias ? a.bias[co + e] : 0.f);
+          if (TAPS == 1 && a.yt && co >= a.yt_from) {  // uniform over the workgroup
+            const int64_t rr = row0 + p;
+            const int64_t f = rr / a.yt_T;
+            const int t = (int)(rr - f * a.yt_T);
+            OT* dst = (OT*)a.yt + (f * (a.Cout - a.yt_from) + (co - a.yt_from)) * a.yt_Tp + (t & ~63) + vcol<OT>(t & 63);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[(int64_t)e * a.yt_Tp] = from_f32<OT>(v[e]);
+            continue;
+          }
           const int64_t o = orow * a.Cout_store + co;
           if (R) {
             const f32x4 rv = *reinterpret_cast<const f32x4*>(R + o);
@@ -382,7 +393,8 @@ static hipError_t run_gemm(hipStream_t s, const FusedDesc& d) {
   GemmArgs a;
   a.x = d.x; a.x2 = d.x2; a.scale = d.scale; a.shift = d.shift; a.w = d.w; a.bias = d.bias;
   a.res = (const float*)d.res; a.y = d.y;
-  a.Cin = d.Cin; a.Cs = d.Cs; a.Cout_store = d.Cout_store; a.ldw = d.taps * d.Cin;
+  a.Cin = d.Cin; a.Cs = d.Cs; a.Cout = d.Cout; a.Cout_store = d.yt ? d.yt_from : d.Cout_store; a.ldw = d.taps * d.Cin;
+  a.yt = d.yt; a.yt_from = d.yt_from; a.yt_T = d.yt_T; a.yt_Tp = d.yt_Tp;
   a.frames = d.frames; a.H = d.H; a.W = d.W;
   a.tiles_x = (d.W + 15) / 16; a.tiles_y = (d.H + 7) / 8;
   a.rows = d.rows; a.in_map = d.in_map; a.out_map = d.out_map;
@@ -427,6 +439,9 @@ static hipError_t by_kind(hipStream_t s, const FusedDesc& d) {
 }
 
 hipError_t launch_fused(hipStream_t s, const FusedDesc& d) {
+  if (d.yt && (d.taps != 1 || d.y_f32 || d.res || d.yt_from % 32 || d.yt_from <= 0 || d.yt_from >= d.Cout ||
+               d.yt_Tp % 64 || d.yt_Tp < d.yt_T || d.out_map.rows_per_seg < d.rows))
+    return hipErrorInvalidValue;
   const int esz = (int)dtype_size(d.dt);
   if (d.Cin % (kRow / esz) != 0) return hipErrorInvalidValue;
   if (d.src == 3 && (d.Cs % (kRow / esz) != 0 || d.Cs <= 0 || d.Cs >= d.Cin || (d.H | d.W) & 1)) return hipErrorInvalidValue;

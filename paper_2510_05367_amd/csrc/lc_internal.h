@@ -73,13 +73,23 @@ struct FusedDesc {
   const void* res;     // fp32, indexed like y; nullptr if none; may equal y only when taps == 1
   void* y;
   int planar_out;      // 1: y is [frame][Cout_store][H][W] of the operand type (Cout = 32, zero-padded w)
+  // taps == 1 only: output channels >= yt_from are not stored in y (whose rows then have yt_from
+  // channels) but transposed into yt[frame][Cout - yt_from][yt_Tp] at column (t & ~63) + vcol(t & 63),
+  // frame = r / yt_T, t = r % yt_T (the V^T layout of the spatial attention kernel). yt == nullptr: off.
+  void* yt;
+  int yt_from, yt_T, yt_Tp;
 };
 hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
 
 // ---- attention cores -----------------------------------------------------------------------
-// qkv [frames*T][3C] -> out [frames*T][C]; queries [q0,q1) of every frame.
-hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qkv, void* out, int frames, int T,
-                                    int heads, int d, int q0, int q1);
+// Spatial attention core. qk: rows [frames*T] of stride ldq with q at column 0 and k at column C;
+// vt: V transposed [frames][C][Tp], token t at column (t & ~63) + vcol(t & 63), Tp a multiple of 64;
+// out [frames*T][C]; queries [q0,q1) of every frame.
+inline int attn_tp(int T) { return (T + 63) / 64 * 64; }
+hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
+                                    int frames, int T, int heads, int d, int q0, int q1);
+// vt from plain value rows v[frames*T][C] of stride ldv
+hipError_t launch_make_vt(hipStream_t s, int dt, const void* v, int ldv, void* vt, int frames, int T, int Tp, int C);
 // qkv [(B*F)*P][3C] frame-major -> out same rows x C; attention over the F frames.
 hipError_t launch_temporal_attention(hipStream_t s, int dt, const void* qkv, void* out, int B, int F, int P,
                                      int heads, int d);
