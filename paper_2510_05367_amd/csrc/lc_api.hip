@@ -292,12 +292,12 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       // kernel stages (no scattered transposition later)
       FusedDesc d = flinear_desc(c, w.sattn.wqkv, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
       d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
-      LC_LAUNCH(c, LC_K_QKV, launch_fused(c->cs, d));
+      LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, d));
     }
     for (int q0 = 0; q0 < T; q0 += p.qc)
       LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
                                                         g.head_dim, q0, std::min(q0 + p.qc, T)));
-    LC_LAUNCH(c, LC_K_PROJ, launch_fused(c->cs, flinear_desc(c, w.sattn.wo, w.sattn.bo, C, C, pc, 0, dense_map(),
+    LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, w.sattn.wo, w.sattn.bo, C, C, pc, 0, dense_map(),
                                                              dense_map(), ao, hc, hc, 1)));
   }
 
@@ -311,10 +311,10 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       RowMap m{p0, T, np};  // dense row r = (frame r / np, position p0 + r % np)
       char* qkv = ws;
       char* ao = ws + align_up((size_t)rows * 3 * C * es);
-      LC_LAUNCH(c, LC_K_QKV, launch_fused(c->cs, flinear_desc(c, w.tattn.wqkv, nullptr, C, 3 * C, rows, 1, m, dense_map(),
+      LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, flinear_desc(c, w.tattn.wqkv, nullptr, C, 3 * C, rows, 1, m, dense_map(),
                                                               h, nullptr, qkv, 0)));
       LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
-      LC_LAUNCH(c, LC_K_PROJ, launch_fused(c->cs, flinear_desc(c, w.tattn.wo, w.tattn.bo, C, C, rows, 0, dense_map(), m,
+      LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, w.tattn.wo, w.tattn.bo, C, C, rows, 0, dense_map(), m,
                                                                ao, h, h, 1)));
     }
   }
@@ -819,7 +819,7 @@ lc_status lc_op_qkv(lc_ctx* c, int layer, const void* x, void* qkv, int frames) 
   s = gn_scale_shift(c, x, frames, T, g.C, a.gn);
   if (s != LC_OK) return s;
   RowMap fm{0, T, T};
-  LC_LAUNCH(c, LC_K_QKV, launch_fused(c->cs, flinear_desc(c, a.wqkv, nullptr, g.C, 3 * g.C, (int64_t)frames * T, 1, fm,
+  LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, flinear_desc(c, a.wqkv, nullptr, g.C, 3 * g.C, (int64_t)frames * T, 1, fm,
                                                           dense_map(), x, nullptr, qkv, 0)));
   return LC_OK;
 }
@@ -830,7 +830,7 @@ lc_status lc_op_proj(lc_ctx* c, int layer, const void* a_in, const void* res, vo
   if (!a_in || !y || rows <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
   if (layer != LC_L_SATTN && layer != LC_L_TATTN) return fail(c, LC_ERR_ARG, "layer %d is not an attention block", layer);
   const AttnW& a = layer == LC_L_SATTN ? c->pw.sattn : c->pw.tattn;
-  LC_LAUNCH(c, LC_K_PROJ, launch_fused(c->cs, flinear_desc(c, a.wo, a.bo, c->cfg.C, c->cfg.C, rows, 0, dense_map(),
+  LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, a.wo, a.bo, c->cfg.C, c->cfg.C, rows, 0, dense_map(),
                                                            dense_map(), a_in, res, y, 1)));
   return LC_OK;
 }

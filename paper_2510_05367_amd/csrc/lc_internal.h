@@ -80,6 +80,12 @@ struct FusedDesc {
   int yt_from, yt_T, yt_Tp;
 };
 hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
+// taps == 1 with the whole activation tile resident in LDS; hipErrorNotSupported if it does not fit
+hipError_t launch_linear(hipStream_t s, const FusedDesc& d);
+inline hipError_t launch_linear_any(hipStream_t s, const FusedDesc& d) {
+  const hipError_t e = launch_linear(s, d);
+  return e == hipErrorNotSupported ? launch_fused(s, d) : e;
+}
 
 // ---- attention cores -----------------------------------------------------------------------
 // Spatial attention core. qk: rows [frames*T] of stride ldq with q at column 0 and k at column C;
