@@ -21,6 +21,8 @@
 // and walks the 9 taps over it by shifting LDS addresses; the weights of a (slab, tap) step are
 // streamed through a second LDS tile one step ahead, and the next slab's halo is fetched and
 // activated one 16-byte packet per thread per tap while the MFMAs of the current slab run.
+#include <type_traits>
+
 #include "lc_internal.h"
 
 namespace lc {
@@ -94,8 +96,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   const int kp = tid & 7, lrow = tid >> 3;  // this thread moves packet kp of rows lrow + 32 * i
 
   // ---------------- weights of the next step: global -> registers -> LDS ----------------
-  Vec16<T> wreg[WP];
-  auto issue_w = [&](int step) {
+  constexpr int NW = TAPS == 9 ? 3 : 1;  // conv: three sets in rotation, loads run two steps ahead
+  Vec16<T> wregs[NW][WP];
+  auto issue_w = [&](int step, Vec16<T> (&wreg)[WP]) {
     const int slab = step / TAPS, tap = step - slab * TAPS;
     const int kofs = tap * a.Cin + slab * BKC + kp * VEC;
 #pragma unroll
@@ -104,7 +107,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
       wreg[i] = load16(Wt + (int64_t)(co0 + r) * a.ldw + kofs);
     }
   };
-  auto store_w = [&](int buf) {
+  auto store_w = [&](int buf, const Vec16<T> (&wreg)[WP]) {
 #pragma unroll
     for (int i = 0; i < WP; ++i) {
       const int r = lrow + 32 * i;
@@ -122,7 +125,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
     o.q[0] = *reinterpret_cast<const f32x4*>(p);
     if (VEC == 8) o.q[1] = *reinterpret_cast<const f32x4*>(p + 4);
   };
-  auto fetch_x = [&](int slab, int r, XRaw& o) {
+  // `deep_c`: compile-time flag, the slab lies in the cached deep feature (SRC == 3 only)
+  auto fetch_x = [&](int slab, int r, XRaw& o, auto deep_c) {
+    constexpr bool DEEP = decltype(deep_c)::value;
     const int c0 = slab * BKC + kp * VEC;
     if (TAPS == 9) {
       const int hp = lrow + 32 * r;
@@ -130,7 +135,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
       const int iy = ty0 + hy - 1, ix = tx0 + hx - 1;
       o.ok = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
       const int cy = min(max(iy, 0), a.H - 1), cx = min(max(ix, 0), a.W - 1);
-      if (SRC == 3 && slab * BKC >= a.Cs) {  // uniform: a slab lies on one side of Cs
+      if (SRC == 3 && DEEP) {
         const int64_t dr = ((int64_t)frame * (a.H >> 1) + (cy >> 1)) * (a.W >> 1) + (cx >> 1);
         o.q[0] = *reinterpret_cast<const f32x4*>((const T*)a.x2 + dr * (a.Cin - a.Cs) + (c0 - a.Cs));
       } else if (NORM) {
@@ -160,8 +165,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
     const int64_t rr = row0 + lrow + 32 * r;
     return (rr < a.rows ? rr : a.rows - 1) / a.in_map.rows_per_seg;
   };
-  auto finish_x = [&](int slab, int buf, int r, const XRaw& o, const Affine& af) {
-    const bool from_t = !NORM || (SRC == 3 && slab * BKC >= a.Cs);  // uniform
+  auto finish_x = [&](int buf, int r, const XRaw& o, const Affine& af, auto deep_c) {
+    constexpr bool from_t = !NORM || (SRC == 3 && decltype(deep_c)::value);
     Vec16<T> pk;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
@@ -222,72 +227,83 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   const int nsteps = TAPS * nslab;
 
   // ---------------- prologue ----------------
+  constexpr int NXS = TAPS == 9 ? 3 : XR;  // conv: three halo packets in flight
+  const std::false_type no_c{};
+  const std::true_type yes_c{};
   Affine aff[TAPS == 9 ? 1 : XR];
-  XRaw xin[TAPS == 9 ? 1 : XR];
-  issue_w(0);
+  XRaw xin[XR];
+  issue_w(0, wregs[0]);
   if (TAPS == 9) {
+    if (nsteps > 1) issue_w(1, wregs[1]);
     load_affine(0, frame, aff[0]);
 #pragma unroll
-    for (int r = 0; r < XR; ++r) {
-      fetch_x(0, r, xin[0]);
-      finish_x(0, 0, r, xin[0], aff[0]);
-    }
+    for (int r = 0; r < XR; ++r) fetch_x(0, r, xin[r], no_c);  // slab 0 is never in the deep part
+#pragma unroll
+    for (int r = 0; r < XR; ++r) finish_x(0, r, xin[r], aff[0], no_c);
   } else {
 #pragma unroll
     for (int r = 0; r < XR; ++r) {
-      fetch_x(0, r, xin[r]);
+      fetch_x(0, r, xin[r], no_c);
       load_affine(0, row_frame(r), aff[r]);
     }
 #pragma unroll
-    for (int r = 0; r < XR; ++r) finish_x(0, 0, r, xin[r], aff[r]);
+    for (int r = 0; r < XR; ++r) finish_x(0, r, xin[r], aff[r], no_c);
   }
-  store_w(0);
+  store_w(0, wregs[0]);
   __syncthreads();
 
   // ---------------- main loop ----------------
-  // Every global load of a step is issued before the MFMAs of the step and consumed after them, in
-  // issue order, so each wait is for "everything outstanding" and costs nothing extra.
-  // The scheduling barriers pin that order: left alone, the compiler sinks the loads below the MFMAs.
+  // conv: per step (= one tap of one 64-channel slab) a thread issues at most one halo packet of the
+  // NEXT slab (rounds 0..5 at taps 0..5, activated and stored three taps later) and the weights of
+  // step s+2; it stores the weights of step s+1 (fetched during step s-1) after its MFMAs. The
+  // number of loads per tap is fixed at compile time - the loop is split by where the next slab
+  // comes from (skip feature, deep feature, none) instead of branching - so every wait is an exact
+  // count of younger loads and global latency has two to three steps to hide in. The scheduling
+  // barriers pin the order: left alone, the compiler sinks the loads below the MFMAs.
   if (TAPS == 9) {
-    for (int slab = 0; slab < nslab; ++slab) {
-      const bool more = slab + 1 < nslab;
+    auto slab_body = [&](int slab, auto more_c, auto deep_c) {
+      constexpr bool MORE = decltype(more_c)::value;
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap) {
         const int s = slab * 9 + tap;
-        const bool last = !more && tap == 8;
-        // next slab's halo, one packet round per tap: finish round tap-1, fetch round tap
-        if (more && tap >= 1 && tap <= XR) finish_x(slab + 1, (slab + 1) & 1, tap - 1, xin[0], aff[0]);
+        if (MORE && tap >= 3 && tap - 3 < XR) finish_x((slab + 1) & 1, tap - 3, xin[(tap - 3) % NXS], aff[0], deep_c);
         __builtin_amdgcn_sched_barrier(0);
-        if (more) {
+        if (MORE) {
           if (tap == 0) load_affine(slab + 1, frame, aff[0]);
-          if (tap < XR) fetch_x(slab + 1, tap, xin[0]);
+          if (tap < XR) fetch_x(slab + 1, tap, xin[tap % NXS], deep_c);
         }
-        if (!last) issue_w(s + 1);
+        if (MORE || tap + 2 < 9) issue_w(s + 2, wregs[(tap + 2) % 3]);
         __builtin_amdgcn_sched_barrier(0);
         compute(s & 1, slab & 1, tap);
         __builtin_amdgcn_sched_barrier(0);
-        if (!last) store_w((s + 1) & 1);
+        if (MORE || tap + 1 < 9) store_w((s + 1) & 1, wregs[(tap + 1) % 3]);
         __syncthreads();
       }
-    }
+    };
+    const int nskip = SRC == 3 ? a.Cs / BKC : nslab;  // slabs read from x; the rest from x2
+    int slab = 0;
+    for (; slab + 1 < nskip; ++slab) slab_body(slab, yes_c, no_c);
+    if (SRC == 3)
+      for (; slab + 1 < nslab; ++slab) slab_body(slab, yes_c, yes_c);
+    slab_body(nslab - 1, no_c, no_c);
   } else {
     for (int s = 0; s < nsteps; ++s) {
       const bool more = s + 1 < nsteps;
       if (more) {
 #pragma unroll
         for (int r = 0; r < XR; ++r) {
-          fetch_x(s + 1, r, xin[r]);
+          fetch_x(s + 1, r, xin[r], no_c);
           load_affine(s + 1, row_frame(r), aff[r]);
         }
-        issue_w(s + 1);
+        issue_w(s + 1, wregs[0]);
       }
       __builtin_amdgcn_sched_barrier(0);
       compute(s & 1, s & 1, 0);
       __builtin_amdgcn_sched_barrier(0);
       if (more) {
 #pragma unroll
-        for (int r = 0; r < XR; ++r) finish_x(s + 1, (s + 1) & 1, r, xin[r], aff[r]);
-        store_w((s + 1) & 1);
+        for (int r = 0; r < XR; ++r) finish_x((s + 1) & 1, r, xin[r], aff[r], no_c);
+        store_w((s + 1) & 1, wregs[0]);
       }
       __syncthreads();
     }
