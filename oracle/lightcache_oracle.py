@@ -111,9 +111,9 @@ def attention(xq: np.ndarray, xkv: np.ndarray, wq, wk, wv, wo, bo, heads: int) -
     C = xq.shape[-1]
     d = C // heads
     assert heads * d == C
-    q = xq @ wq.T
-    k = xkv @ wk.T
-    v = xkv @ wv.T
+    q = _project(xq, wq)
+    k = _project(xkv, wk)
+    v = _project(xkv, wv)
     o = np.empty_like(q)
     scale = 1.0 / math.sqrt(d)
     for hd in range(heads):
@@ -121,7 +121,14 @@ def attention(xq: np.ndarray, xkv: np.ndarray, wq, wk, wv, wo, bo, heads: int) -
         qh, kh, vh = (np.ascontiguousarray(t[..., sl]) for t in (q, k, v))
         s = (qh @ np.swapaxes(kh, -1, -2)) * q.dtype.type(scale)
         o[..., sl] = softmax_rows(s) @ vh
-    return o @ wo.T + bo
+    return _project(o, wo) + bo
+
+
+def _project(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """x W^T over the last axis. All leading axes are flattened into one row axis first, so a stack
+    of many short sequences (temporal attention: one per spatial position) is one matrix product."""
+    y = x.reshape(-1, x.shape[-1]) @ np.ascontiguousarray(w.T)
+    return y.reshape(x.shape[:-1] + (w.shape[0],))
 
 
 def up2(z: np.ndarray) -> np.ndarray:
