@@ -299,7 +299,11 @@ class Stage:
     # -- memory helpers
     def to_device(self, a):
         t = self.torch.from_numpy(a).to(self.device)
-        return t.to(self.tdtype).contiguous()
+        t = t.to(self.tdtype).contiguous()
+        # torch converted on ITS current stream; the library runs on `self.compute`, which does not
+        # wait for that stream by itself
+        self.torch.cuda.current_stream(self.device).synchronize()
+        return t
 
     def empty(self, *shape):
         return self.torch.empty(*shape, dtype=self.tdtype, device=self.device)

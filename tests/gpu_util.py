@@ -46,7 +46,11 @@ def rows_to_planar(r, N, C, H, W):
 
 def make_stage(cfg, seed=0, sharp=1.0, **kw):
     w = synth.make_weights(cfg, seed, sharp=sharp)
-    return lcb.Stage(cfg, w, **kw), w
+    stage = lcb.Stage(cfg, w, **kw)
+    # torch work the tests issue between library calls (fill_, clone, copies) must be ordered with the
+    # library's kernels: make the stage's compute stream torch's current stream
+    torch.cuda.set_stream(stage.compute)
+    return stage, w
 
 
 def dev(stage, a):
