@@ -30,7 +30,7 @@ struct Plan {
 
 struct GnW { float *gamma, *beta; };
 struct ConvW { void* w; float* b; };
-struct AttnW { GnW gn; void* wqkv; void* wo; float* bo; };
+struct AttnW { GnW gn; void* wqkv; void* wo; float* bo; void* wqkv_f; void* wo_f; };  // *_f: fragment order
 struct Packed {
   float* cin_w; float* cin_b;
   GnW res_gn[LC_MAX_RES]; ConvW res[LC_MAX_RES];
@@ -208,12 +208,12 @@ FusedDesc fconv_desc(lc_ctx* c, const ConvW& w, int Cin, int Cout, int frames, i
   return d;
 }
 
-FusedDesc flinear_desc(lc_ctx* c, const void* w, const float* bias, int Cin, int Cout, int64_t rows, int src,
+FusedDesc flinear_desc(lc_ctx* c, const void* w, const void* w_frag, const float* bias, int Cin, int Cout, int64_t rows, int src,
                        RowMap in_map, RowMap out_map, const void* x, const void* res, void* y, int y_f32) {
   FusedDesc d;
   memset(&d, 0, sizeof d);
   d.dt = c->cfg.dtype; d.y_f32 = y_f32; d.taps = 1; d.src = src; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
-  d.w = w; d.bias = bias; d.rows = rows; d.in_map = in_map; d.out_map = out_map; d.x = x;
+  d.w = w; d.w_frag = w_frag; d.bias = bias; d.rows = rows; d.in_map = in_map; d.out_map = out_map; d.x = x;
   d.scale = scale_p(c); d.shift = shift_p(c); d.res = res; d.y = y;
   return d;
 }
@@ -290,14 +290,14 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     {
       // q and k as rows, v transposed straight from the GEMM epilogue into the layout the attention
       // kernel stages (no scattered transposition later)
-      FusedDesc d = flinear_desc(c, w.sattn.wqkv, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
+      FusedDesc d = flinear_desc(c, w.sattn.wqkv, w.sattn.wqkv_f, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
       d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
       LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, d));
     }
     for (int q0 = 0; q0 < T; q0 += p.qc)
       LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
                                                         g.head_dim, q0, std::min(q0 + p.qc, T)));
-    LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, w.sattn.wo, w.sattn.bo, C, C, pc, 0, dense_map(),
+    LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, w.sattn.wo, w.sattn.wo_f, w.sattn.bo, C, C, pc, 0, dense_map(),
                                                              dense_map(), ao, hc, hc, 1)));
   }
 
@@ -311,10 +311,10 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       RowMap m{p0, T, np};  // dense row r = (frame r / np, position p0 + r % np)
       char* qkv = ws;
       char* ao = ws + align_up((size_t)rows * 3 * C * es);
-      LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, flinear_desc(c, w.tattn.wqkv, nullptr, C, 3 * C, rows, 1, m, dense_map(),
+      LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, flinear_desc(c, w.tattn.wqkv, w.tattn.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(),
                                                               h, nullptr, qkv, 0)));
       LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
-      LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, w.tattn.wo, w.tattn.bo, C, C, rows, 0, dense_map(), m,
+      LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, w.tattn.wo, w.tattn.wo_f, w.tattn.bo, C, C, rows, 0, dense_map(), m,
                                                                ao, h, h, 1)));
     }
   }
@@ -493,10 +493,11 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
     o_res_g[i] = take((size_t)C * 4); o_res_b[i] = take((size_t)C * 4);
     o_res_w[i] = take((size_t)C * 9 * C * es); o_res_bias[i] = take((size_t)C * 4);
   }
-  size_t o_at[2][5];
+  size_t o_at[2][7];
   for (int k = 0; k < 2; ++k) {
     o_at[k][0] = take((size_t)C * 4); o_at[k][1] = take((size_t)C * 4);
     o_at[k][2] = take((size_t)3 * C * C * es); o_at[k][3] = take((size_t)C * C * es); o_at[k][4] = take((size_t)C * 4);
+    o_at[k][5] = take((size_t)3 * C * C * es); o_at[k][6] = take((size_t)C * C * es);
   }
   const size_t o_down_w = take((size_t)Cd * 9 * C * es), o_down_b = take((size_t)Cd * 4);
   const size_t o_dres_g = take((size_t)Cd * 4), o_dres_b = take((size_t)Cd * 4);
@@ -535,8 +536,10 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
     LC_HIP(c, launch_copy_rows(s, dt, aw[k]->wv, b + o_at[k][2] + (size_t)2 * C * C * es, (int64_t)C * C));
     LC_HIP(c, launch_copy_rows(s, dt, aw[k]->wo, b + o_at[k][3], (int64_t)C * C));
     F32(aw[k]->bo, o_at[k][4], C, C);
+    LC_HIP(c, launch_pack_lin_w(s, dt, b + o_at[k][2], b + o_at[k][5], 3 * C, C));
+    LC_HIP(c, launch_pack_lin_w(s, dt, b + o_at[k][3], b + o_at[k][6], C, C));
     *ap[k] = AttnW{GnW{(float*)(b + o_at[k][0]), (float*)(b + o_at[k][1])}, b + o_at[k][2], b + o_at[k][3],
-                   (float*)(b + o_at[k][4])};
+                   (float*)(b + o_at[k][4]), b + o_at[k][5], b + o_at[k][6]};
   }
   CW(w->down_w, o_down_w, Cd, C, 9, Cd); F32(w->down_b, o_down_b, Cd, Cd);
   p.down = ConvW{b + o_down_w, (float*)(b + o_down_b)};
@@ -819,7 +822,7 @@ lc_status lc_op_qkv(lc_ctx* c, int layer, const void* x, void* qkv, int frames) 
   s = gn_scale_shift(c, x, frames, T, g.C, a.gn);
   if (s != LC_OK) return s;
   RowMap fm{0, T, T};
-  LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, flinear_desc(c, a.wqkv, nullptr, g.C, 3 * g.C, (int64_t)frames * T, 1, fm,
+  LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, flinear_desc(c, a.wqkv, a.wqkv_f, nullptr, g.C, 3 * g.C, (int64_t)frames * T, 1, fm,
                                                           dense_map(), x, nullptr, qkv, 0)));
   return LC_OK;
 }
@@ -830,7 +833,7 @@ lc_status lc_op_proj(lc_ctx* c, int layer, const void* a_in, const void* res, vo
   if (!a_in || !y || rows <= 0) return fail(c, LC_ERR_ARG, "bad tensor argument");
   if (layer != LC_L_SATTN && layer != LC_L_TATTN) return fail(c, LC_ERR_ARG, "layer %d is not an attention block", layer);
   const AttnW& a = layer == LC_L_SATTN ? c->pw.sattn : c->pw.tattn;
-  LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, a.wo, a.bo, c->cfg.C, c->cfg.C, rows, 0, dense_map(),
+  LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, a.wo, a.wo_f, a.bo, c->cfg.C, c->cfg.C, rows, 0, dense_map(),
                                                            dense_map(), a_in, res, y, 1)));
   return LC_OK;
 }

@@ -62,6 +62,7 @@ struct FusedDesc {
                  //    resolution, nearest 2x upsampled), then as 2
   int Cin, Cs, Cout, Cout_store;
   const void* w;       // [Cout][taps*Cin]
+  const void* w_frag;  // taps == 1: the same matrix in MFMA fragment order (launch_pack_lin_w), or nullptr
   const float* bias;   // [Cout] or nullptr
   int frames, H, W;    // taps == 9
   int64_t rows;        // taps == 1: x row of dense row r is in_map(r), y / res row is out_map(r);
@@ -80,7 +81,7 @@ struct FusedDesc {
   int yt_from, yt_T, yt_Tp;
 };
 hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
-// taps == 1 with the whole activation tile resident in LDS; hipErrorNotSupported if it does not fit
+// taps == 1 with the weights resident in registers (needs w_frag); hipErrorNotSupported for shapes it does not cover
 hipError_t launch_linear(hipStream_t s, const FusedDesc& d);
 inline hipError_t launch_linear_any(hipStream_t s, const FusedDesc& d) {
   const hipError_t e = launch_linear(s, d);
@@ -111,6 +112,8 @@ hipError_t launch_cl_to_planar(hipStream_t s, int dt, const void* src, void* dst
 hipError_t launch_pack_conv_w(hipStream_t s, int dt, const void* w, void* packed, int Cout, int Cin, int taps,
                               int Cout_padded);  // [Cout][Cin][taps] -> [Cout_padded][taps][Cin]
 hipError_t launch_pack_conv_in_w(hipStream_t s, int dt, const void* w, float* packed, int C, int Cl);
+// w[Cout][Cin] -> MFMA fragment order for launch_linear
+hipError_t launch_pack_lin_w(hipStream_t s, int dt, const void* w, void* out, int Cout, int Cin);
 hipError_t launch_to_f32(hipStream_t s, int dt, const void* src, float* dst, int n, int n_padded);
 hipError_t launch_copy_rows(hipStream_t s, int dt, const void* src, void* dst, int64_t elems);
 

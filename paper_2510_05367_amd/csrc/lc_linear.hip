@@ -1,214 +1,344 @@
-// Per-row linear layers (q,k,v and output projections of the attention blocks) on 32x32 MFMA tiles.
+// Per-row linear layers (q,k,v and output projections of the attention blocks) on 32x32 MFMA tiles,
+// weights stationary.
 //
-// K is only C (320) here, so a workgroup keeps its whole activation tile resident: 128 rows x Cin are
-// fetched once (through the row map of a temporal pass if any), GroupNorm'ed on the way in when the
-// source is the fp32 residual stream, rounded to the operand type and parked in LDS. The workgroup
-// then walks `nct` output-channel tiles of BCO = 32 * CO_T channels, streaming the weights of a
-// (tile, 64-byte..128-byte K slab) step through a double-buffered LDS tile one step ahead. Each
-// wavefront owns 32 rows x BCO channels (no K split: nothing to fold), and writes its tile out when
-// the last slab of the tile is done: bias, fp32 residual, row map, or - for the value third of the
-// spatial q,k,v - transposed into the V^T layout the spatial attention kernel stages.
+// K is only C here (320), so the weights a wavefront needs - up to 96 output channels x Cin - fit
+// in its registers as MFMA fragments (3 x Cin/16 packets of 16 bytes for bf16; one wavefront per
+// SIMD, so it may use the whole register file). A workgroup of four wavefronts covers a column of
+// up to 12 32-channel tiles, split 3,3,2,2 for the 10 tiles of 320 channels, and walks a range of
+// 32-row activation tiles: the tile is fetched one step ahead with coalesced 16/32-byte loads,
+// GroupNorm'ed on the way in when the source is the fp32 residual stream, rounded to the operand
+// type and parked in a double-buffered LDS tile that all wavefronts read. LDS traffic is one
+// fragment per two or three MFMAs.
+//
+// Epilogue: the accumulator layout (a lane owns one row and 4-channel pieces of it) would store
+// 8..16-byte pieces scattered over 32 rows; instead the wavefront turns each 32 x 32 tile through a
+// private LDS patch and stores 16 bytes per lane with 64..128 contiguous bytes per row, adding the
+// bias and the fp32 residual (prefetched in the same layout before the MFMAs). The value third of
+// the spatial q,k,v goes straight from the accumulators into the V^T layout of the spatial
+// attention kernel (consecutive lanes = consecutive tokens there).
 #include "lc_internal.h"
+
+#include <type_traits>
 
 namespace lc {
 
 namespace {
 
-constexpr int kRowL = 128;  // K bytes per weight row per step
-constexpr int kLdsL = 144;  // LDS row stride of the weight tile
-
 struct LinArgs {
   const void* x;
   const float* scale;
   const float* shift;
-  const void* w;  // T [Cout][Cin]
+  const void* wf;  // fragment-major weights, see pack_lin_w_kernel
   const float* bias;
   const float* res;
   void* y;
   void* yt;
-  int Cin, Cout, ldy, nct;
+  int Cout, ldy, tc, tiles_per_wg;  // tc: 32-channel tiles per workgroup column
   int yt_from, yt_T, yt_Tp;
-  int64_t rows;
+  int rows;
   RowMap in_map, out_map;
 };
+
+constexpr int kRows = 32;        // rows of one activation tile
+constexpr int kTileMax = 3;      // 32-channel tiles one wavefront can own
+constexpr int kLinMinTiles = 2;  // fewest activation tiles a workgroup takes on (it loads its weights once)
+
+// Segment / offset of dense row row0 + r for a segment length rps, with the division of the
+// (wave-uniform) tile origin done once: seg0 = row0 / rps, rem0 = row0 % rps.
+struct TileOrigin {
+  int seg0, rem0;
+};
+__device__ __forceinline__ TileOrigin tile_origin(int row0, int rps) {
+  const int q = row0 / rps;
+  return TileOrigin{q, row0 - q * rps};
+}
+__device__ __forceinline__ void locate(const TileOrigin& o, int rps, int r, int& seg, int& rem) {
+  const unsigned x = (unsigned)(o.rem0 + r);
+  const unsigned dq = x / (unsigned)rps;
+  seg = o.seg0 + (int)dq;
+  rem = (int)(x - dq * (unsigned)rps);
+}
+__device__ __forceinline__ int64_t mapped(const RowMap& m, int seg, int rem) {
+  return m.base + (int64_t)seg * m.seg_stride + rem;
+}
 
 }  // namespace
 
 // SRC: 0 = x has the operand type; 1 = x is fp32 and gets scale/shift (GroupNorm apply)
-template <class T, class OT, int CO_T, int SRC>
+template <class T, class OT, int CIN, int SRC>
 __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
   typedef Mma32<T> M;
   constexpr int VEC = Vec16<T>::N;
-  constexpr int BKC = kRowL / (int)sizeof(T);
-  constexpr int BCO = CO_T * 32;
-  constexpr int WP = (BCO * 8 + 255) / 256;
-  constexpr int KI = kRowL / (M::K * (int)sizeof(T));
-  constexpr int LKB = M::LK * (int)sizeof(T), KB = M::K * (int)sizeof(T);
-  constexpr int XB = 4;  // x packets in flight per thread while the tile is staged
+  constexpr int ES = (int)sizeof(T);
+  constexpr int KT = CIN / M::K;                 // MFMA k-steps over the whole contraction
+  constexpr int XS = CIN * ES + 16;              // LDS row stride of the activation tile, bytes
+  constexpr int TS = 32 * (int)sizeof(OT) + 16;  // LDS row stride of the output patch, bytes
+  constexpr int PPR = CIN / VEC;                 // operand packets per row
+  constexpr int RPR = 256 / PPR;                 // rows one round of the staging threads covers
+  constexpr int XP = (kRows + RPR - 1) / RPR;    // rounds = packets per thread
+  constexpr int RAWN = (SRC == 1 && VEC == 8) ? 2 : 1;  // 16-byte loads per packet
+  constexpr int OV = 16 / (int)sizeof(OT);       // output elements per 16-byte store
+  constexpr int LPR = 32 / OV;                   // lanes per output row of a 32-channel tile
+  constexpr int RPI = 64 / LPR;                  // rows per store instruction
+  constexpr int NK = kRows / RPI;                // 16-byte stores per lane per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int xs = a.Cin * (int)sizeof(T) + 16;  // x row stride: rows start 16 bytes apart modulo 128
-  unsigned char* const x_lds = smem;
-  auto w_lds = [&](int b) { return smem + 128 * xs + b * BCO * kLdsL; };
+  auto x_lds = [&](int b) { return smem + b * kRows * XS; };
 
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int lp = lane & 31, hh = lane >> 5;
-  const int64_t row0 = (int64_t)blockIdx.x * 128;
-  const int ct0 = blockIdx.y * a.nct;
-  const T* __restrict__ Wt = (const T*)a.w;
-  const int kp = tid & 7, lrow = tid >> 3;
-  const int nslab = a.Cin / BKC;
-  const int nsteps = a.nct * nslab;
+  unsigned char* const t_lds = smem + 2 * kRows * XS + wid * kRows * TS;
+  const int ntiles = (a.rows + kRows - 1) / kRows;
+  const int t0 = blockIdx.x * a.tiles_per_wg;
+  const int t1 = min(ntiles, t0 + a.tiles_per_wg);
+  if (t0 >= t1) return;
+  // this wavefront's share of the column's tiles
+  const int nt = a.tc / 4 + (wid < a.tc % 4 ? 1 : 0);
+  const int tile0 = blockIdx.y * a.tc + wid * (a.tc / 4) + min(wid, a.tc % 4);
+  const int co_w = tile0 * 32;
 
-  Vec16<T> wreg[WP];
-  auto issue_w = [&](int step) {
-    const int ct = step / nslab, slab = step - ct * nslab;
-    const int kofs = slab * BKC + kp * VEC;
-#pragma unroll
-    for (int i = 0; i < WP; ++i) {
-      const int r = min(lrow + 32 * i, BCO - 1);
-      wreg[i] = load16(Wt + (int64_t)((ct0 + ct) * BCO + r) * a.Cin + kofs);
-    }
-  };
-  auto store_w = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < WP; ++i) {
-      const int r = lrow + 32 * i;
-      if (BCO % 32 == 0 || r < BCO) *reinterpret_cast<Vec16<T>*>(w_lds(buf) + r * kLdsL + kp * 16) = wreg[i];
-    }
-  };
-  issue_w(0);
-
-  // ---- stage the activation tile: packet q = tid + 256 j is (row q / ppr, packet q % ppr)
+  // ---- resident weights: fragment kt of tile i
+  typename M::Frag wf[kTileMax][KT];
   {
-    const int ppr = a.Cin / VEC;
-    const int total = 128 * ppr;
-    for (int q0 = 0; q0 < total; q0 += 256 * XB) {
-      f32x4 raw[XB][2];
-      float sc[XB][VEC], sh[XB][VEC];
-      bool ok[XB];
+    const typename M::Frag* W = (const typename M::Frag*)a.wf + ((int64_t)tile0 * KT) * 64 + lane;
+    if (nt > 0) {
 #pragma unroll
-      for (int j = 0; j < XB; ++j) {
-        const int q = min(q0 + tid + 256 * j, total - 1);
-        const int r = q / ppr, c0 = (q - r * ppr) * VEC;
-        const int64_t rr = row0 + r;
-        ok[j] = rr < a.rows;
-        const int64_t rc = ok[j] ? rr : a.rows - 1;
-        const int64_t sr = a.in_map(rc);
-        if (SRC == 1) {
-          const float* px = (const float*)a.x + sr * a.Cin + c0;
-          raw[j][0] = *reinterpret_cast<const f32x4*>(px);
-          if (VEC == 8) raw[j][1] = *reinterpret_cast<const f32x4*>(px + 4);
-          const int64_t f = rc / a.in_map.rows_per_seg;
-          load_f<float, VEC>(a.scale + f * a.Cin + c0, sc[j]);
-          load_f<float, VEC>(a.shift + f * a.Cin + c0, sh[j]);
-        } else {
-          raw[j][0] = *reinterpret_cast<const f32x4*>((const T*)a.x + sr * a.Cin + c0);
-        }
-      }
+      for (int i = 0; i < kTileMax; ++i) {
+        const int ic = i < nt ? i : 0;  // tiles this wavefront does not own: a harmless repeat, never used
 #pragma unroll
-      for (int j = 0; j < XB; ++j) {
-        const int q = q0 + tid + 256 * j;
-        if (q < total) {
-          const int r = q / ppr, pk = q - r * ppr;
-          Vec16<T> out;
-          if (SRC == 1) {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) out.set(e, ok[j] ? fmaf(raw[j][e >> 2][e & 3], sc[j][e], sh[j][e]) : 0.f);
-          } else {
-            out = __builtin_bit_cast(Vec16<T>, raw[j][0]);
-            if (!ok[j]) out = zero16<T>();
-          }
-          *reinterpret_cast<Vec16<T>*>(x_lds + r * xs + pk * 16) = out;
-        }
+        for (int kt = 0; kt < KT; ++kt) wf[i][kt] = W[(ic * KT + kt) * 64];
       }
     }
   }
-  store_w(0);
-  __syncthreads();
 
-  f32x16 acc[CO_T];
+  // ---- activation staging: a thread keeps packet column `col` and rows rg, rg + RPR, ...
+  const int col = tid % PPR, rg = tid / PPR;
+  const bool stager = rg < RPR;
+  const int c0 = col * VEC;
+  f32x4 raw[XP][RAWN];
+  float sc[VEC], sh[VEC];  // dead unless SRC == 1
+  int fcur = -1;
+  auto fetch_x = [&](int t) {
+    const int row0 = t * kRows;
+    const TileOrigin o = tile_origin(row0, a.in_map.rows_per_seg);
+    const int rmax = a.rows - 1 - row0;
 #pragma unroll
-  for (int i = 0; i < CO_T; ++i)
+    for (int j = 0; j < XP; ++j) {
+      const int r = min(min(rg + RPR * j, kRows - 1), rmax);  // clamped: always a valid row
+      int seg, rem;
+      locate(o, a.in_map.rows_per_seg, r, seg, rem);
+      const int64_t sr = mapped(a.in_map, seg, rem);
+      if (SRC == 1) {
+        const float* px = (const float*)a.x + sr * CIN + c0;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        for (int q = 0; q < RAWN; ++q) raw[j][q] = *reinterpret_cast<const f32x4*>(px + 4 * q);
+      } else {
+        raw[j][0] = *reinterpret_cast<const f32x4*>((const T*)a.x + sr * CIN + c0);
+      }
+    }
+  };
+  auto finish_x = [&](int buf, int t) {
+    const int row0 = t * kRows;
+    const TileOrigin o = tile_origin(row0, a.in_map.rows_per_seg);
+    const int rmax = a.rows - 1 - row0;
+#pragma unroll
+    for (int j = 0; j < XP; ++j) {
+      const int r = rg + RPR * j;
+      if (stager && r < kRows) {
+        const bool ok = r <= rmax;
+        Vec16<T> out;
+        if constexpr (SRC == 1) {
+          int f, rem;
+          locate(o, a.in_map.rows_per_seg, min(r, rmax), f, rem);
+          if (f != fcur) {
+            fcur = f;
+            load_f<float, VEC>(a.scale + (int64_t)f * CIN + c0, sc);
+            load_f<float, VEC>(a.shift + (int64_t)f * CIN + c0, sh);
+          }
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) out.set(e, ok ? fmaf(raw[j][(e >> 2) % RAWN][e & 3], sc[e], sh[e]) : 0.f);
+        } else {
+          out = __builtin_bit_cast(Vec16<T>, raw[j][0]);
+          if (!ok) out = zero16<T>();
+        }
+        *reinterpret_cast<Vec16<T>*>(x_lds(buf) + r * XS + col * 16) = out;
+      }
+    }
+  };
 
-  const int p = wid * 32 + lp;  // this lane's row of the tile
-  const bool row_ok = row0 + p < a.rows;
-  const int64_t orow = row_ok ? a.out_map(row0 + p) : 0;
+  // ---- output side: lane -> (rows orow_l + RPI k, 16-byte piece ocol) of a tile's patch
+  const int ocol = lane % LPR, orow_l = lane / LPR;
+  float bias_l[kTileMax][OV];  // fp32 output only; the bf16 path reads its bias when it stores
+  if constexpr (sizeof(OT) == 4) {
+#pragma unroll
+    for (int i = 0; i < kTileMax; ++i)
+#pragma unroll
+      for (int e = 0; e < OV; ++e) bias_l[i][e] = 0.f;
+    if (a.bias && nt > 0) {
+#pragma unroll
+      for (int i = 0; i < kTileMax; ++i)
+        load_f<float, OV>(a.bias + co_w + (i < nt ? i : 0) * 32 + ocol * OV, bias_l[i]);
+    }
+  }
   OT* Y = (OT*)a.y;
   const float* R = a.res;  // may alias Y
 
-  for (int s = 0; s < nsteps; ++s) {
-    const int ct = s / nslab, slab = s - ct * nslab;
-    const bool more = s + 1 < nsteps;
-    if (more) issue_w(s + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    {
-      const unsigned char* xl = x_lds + p * xs + slab * kRowL + hh * LKB;
-      const unsigned char* wl = w_lds(s & 1) + lp * kLdsL + hh * LKB;
+  fetch_x(t0);
+  finish_x(0, t0);
+  __syncthreads();
+
+  for (int t = t0; t < t1; ++t) {
+    const int buf = (t - t0) & 1;
+    const bool more = t + 1 < t1;
+    const int row0 = t * kRows;
+    fetch_x(more ? t + 1 : t);  // the last step repeats its own tile: no branch around the loads
+    // rows of the output patch this lane stores, and the residual it adds there
+    const TileOrigin oo = tile_origin(row0, a.out_map.rows_per_seg);
+    int64_t orow[NK];
 #pragma unroll
-      for (int kk = 0; kk < KI; ++kk) {
-        const typename M::Frag xf = M::load((const T*)(xl + kk * KB));
+    for (int k = 0; k < NK; ++k) {
+      int seg, rem;
+      locate(oo, a.out_map.rows_per_seg, min(orow_l + RPI * k, a.rows - 1 - row0), seg, rem);
+      orow[k] = mapped(a.out_map, seg, rem) * a.ldy + co_w + ocol * OV;
+    }
+    f32x4 rres[kTileMax][NK];
+    if constexpr (sizeof(OT) == 4) {
+      if (R && nt > 0) {
 #pragma unroll
-        for (int i = 0; i < CO_T; ++i) {
-          const typename M::Frag wf = M::load((const T*)(wl + i * 32 * kLdsL + kk * KB));
-          M::mma(wf, xf, acc[i]);
-        }
+        for (int i = 0; i < kTileMax; ++i)
+#pragma unroll
+          for (int k = 0; k < NK; ++k)
+            rres[i][k] = *reinterpret_cast<const f32x4*>(R + orow[k] + (i < nt ? i : 0) * 32);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (more) store_w((s + 1) & 1);
-    if (slab == nslab - 1) {
-      // ---- tile done: lane holds, for row p, channels co0 + 32 i + 8 g + 4 hh + {0..3}
-      const int co0 = (ct0 + ct) * BCO;
-      if (row_ok) {
+    f32x16 acc[kTileMax];
 #pragma unroll
-        for (int i = 0; i < CO_T; ++i)
+    for (int i = 0; i < kTileMax; ++i)
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int co = co0 + i * 32 + g * 8 + hh * 4;
-            float v[4];
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    const unsigned char* xl = x_lds(buf) + lp * XS + hh * M::LK * ES;
+    auto compute = [&](auto ntc) {
+      constexpr int N = decltype(ntc)::value;
+      constexpr int AHEAD = 3;  // activation fragments requested ahead of their use
+      typename M::Frag xf[AHEAD + 1];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = acc[i][g * 4 + e] + (a.bias ? a.bias[co + e] : 0.f);
-            if (a.yt && co >= a.yt_from) {  // uniform over the workgroup
-              const int64_t rr = row0 + p;
-              const int64_t f = rr / a.yt_T;
-              const int t = (int)(rr - f * a.yt_T);
-              OT* dst = (OT*)a.yt + (f * (a.Cout - a.yt_from) + (co - a.yt_from)) * a.yt_Tp + (t & ~63) +
-                        vcol<OT>(t & 63);
+      for (int kt = 0; kt < AHEAD && kt < KT; ++kt) xf[kt] = M::load((const T*)(xl + kt * M::K * ES));
 #pragma unroll
-              for (int e = 0; e < 4; ++e) dst[(int64_t)e * a.yt_Tp] = from_f32<OT>(v[e]);
-            } else {
-              const int64_t o = orow * a.ldy + co;
-              if (R) {
-                const f32x4 rv = *reinterpret_cast<const f32x4*>(R + o);
+      for (int kt = 0; kt < KT; ++kt) {
+        if (kt + AHEAD < KT) xf[(kt + AHEAD) % (AHEAD + 1)] = M::load((const T*)(xl + (kt + AHEAD) * M::K * ES));
+        __builtin_amdgcn_sched_barrier(0);  // keep the request ahead of the MFMAs it must overlap with
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] += rv[e];
-              }
-              if constexpr (sizeof(OT) == 2) {
-                bf16x4 ov;
+        for (int i = 0; i < N; ++i) M::mma(wf[i][kt], xf[kt % (AHEAD + 1)], acc[i]);
+      }
+    };
+    if (nt == 3) compute(std::integral_constant<int, 3>{});
+    else if (nt == 2) compute(std::integral_constant<int, 2>{});
+    else if (nt == 1) compute(std::integral_constant<int, 1>{});
+    __builtin_amdgcn_sched_barrier(0);
+    // next tile into LDS before this tile's stores go out: waiting for its loads must not wait for them
+    if (more) finish_x(buf ^ 1, t + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- lane holds, for row lp of the tile, channels co + 8 g + 4 hh + {0..3} of each of its tiles
 #pragma unroll
-                for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16_t>(v[e]);
-                *reinterpret_cast<bf16x4*>((bf16_t*)Y + o) = ov;
-              } else {
-                *reinterpret_cast<f32x4*>((float*)Y + o) = f32x4{v[0], v[1], v[2], v[3]};
-              }
-            }
-          }
+    for (int i = 0; i < kTileMax; ++i) {
+      if (i >= nt) break;
+      const int co = co_w + i * 32;
+      if (a.yt && co >= a.yt_from) {
+        if (row0 + lp < a.rows) {
+          const TileOrigin ov = tile_origin(row0, a.yt_T);
+          int f, tk;
+          locate(ov, a.yt_T, lp, f, tk);
+          OT* dst = (OT*)a.yt + ((int64_t)f * (a.Cout - a.yt_from) + (co - a.yt_from)) * a.yt_Tp + (tk & ~63) +
+                    vcol<OT>(tk & 63);
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[(int64_t)(g * 8 + hh * 4 + e) * a.yt_Tp] = from_f32<OT>(acc[i][g * 4 + e]);
+        }
+        continue;
       }
 #pragma unroll
-      for (int i = 0; i < CO_T; ++i)
+      for (int g = 0; g < 4; ++g) {
+        unsigned char* p = t_lds + lp * TS + (g * 8 + hh * 4) * (int)sizeof(OT);
+        if constexpr (sizeof(OT) == 2) {
+          bf16x4 ov;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+          for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16_t>(acc[i][g * 4 + e]);
+          *reinterpret_cast<bf16x4*>(p) = ov;
+        } else {
+          *reinterpret_cast<f32x4*>(p) = f32x4{acc[i][g * 4], acc[i][g * 4 + 1], acc[i][g * 4 + 2], acc[i][g * 4 + 3]};
+        }
+      }
+      // the patch is private to this wavefront, whose LDS operations complete in order
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int k = 0; k < NK; ++k) {
+        const int r = orow_l + RPI * k;
+        const Vec16<OT> pv = *reinterpret_cast<const Vec16<OT>*>(t_lds + r * TS + ocol * 16);
+        if (row0 + r < a.rows) {
+          const int64_t o = orow[k] + i * 32;
+          if constexpr (sizeof(OT) == 4) {
+            f32x4 v = pv.v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += bias_l[i][e];
+            if (R) v += rres[i][k];
+            *reinterpret_cast<f32x4*>((float*)Y + o) = v;
+          } else {
+            Vec16<OT> ov = pv;
+            if (a.bias) {
+              float bv[OV];
+              load_f<float, OV>(a.bias + co + ocol * OV, bv);
+#pragma unroll
+              for (int e = 0; e < OV; ++e) ov.set(e, pv.get(e) + bv[e]);
+            }
+            store16((OT*)Y + o, ov);
+          }
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
   }
 }
 
-template <class T, class OT, int CO_T, int SRC>
-static hipError_t run_lin(hipStream_t s, const FusedDesc& d, int lds) {
-  constexpr int BCO = CO_T * 32;
-  auto kern = lin_kernel<T, OT, CO_T, SRC>;
+// Fragment-major copy of a row-major weight matrix w[Cout][Cin] for lin_kernel: fragment (tile, kt)
+// holds, for lane l, the M::LK consecutive k values  kt * M::K + (l / 32) * M::LK ...  of output
+// channel 32 * tile + l % 32; fragments are stored [tile][kt][lane].
+template <class T>
+__global__ void pack_lin_w_kernel(const T* __restrict__ w, T* __restrict__ out, int Cout, int Cin) {
+  typedef Mma32<T> M;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // output element
+  if (i >= (int64_t)Cout * Cin) return;
+  const int e = (int)(i % M::LK);
+  int64_t q = i / M::LK;
+  const int lane = (int)(q % 64);
+  q /= 64;
+  const int KT = Cin / M::K;
+  const int kt = (int)(q % KT), tile = (int)(q / KT);
+  out[i] = w[(int64_t)(tile * 32 + (lane & 31)) * Cin + kt * M::K + (lane >> 5) * M::LK + e];
+}
+hipError_t launch_pack_lin_w(hipStream_t s, int dt, const void* w, void* out, int Cout, int Cin) {
+  if (Cout % 32 != 0 || Cin % 16 != 0) return hipErrorInvalidValue;
+  const int64_t n = (int64_t)Cout * Cin;
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (dt == kBF16) pack_lin_w_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)w, (bf16_t*)out, Cout, Cin);
+  else pack_lin_w_kernel<float><<<blocks, 256, 0, s>>>((const float*)w, (float*)out, Cout, Cin);
+  return hipGetLastError();
+}
+
+template <class T, class OT, int CIN, int SRC>
+static hipError_t run_lin(hipStream_t s, const FusedDesc& d) {
+  // workgroup columns: as few as keep a column within 4 wavefronts x kTileMax tiles
+  const int tiles = d.Cout / 32;
+  int cols = (tiles + 4 * kTileMax - 1) / (4 * kTileMax);
+  while (tiles % cols) ++cols;
+  const int tc = tiles / cols;
+  if (d.yt && d.yt_from % 32) return hipErrorInvalidValue;
+  const int lds = 2 * kRows * (CIN * (int)sizeof(T) + 16) + 4 * kRows * (32 * (int)sizeof(OT) + 16);
+  auto kern = lin_kernel<T, OT, CIN, SRC>;
   static int attr_bytes = 0;  // per instantiation
   if (lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -216,45 +346,49 @@ static hipError_t run_lin(hipStream_t s, const FusedDesc& d, int lds) {
     attr_bytes = lds;
   }
   LinArgs a;
-  a.x = d.x; a.scale = d.scale; a.shift = d.shift; a.w = d.w; a.bias = d.bias; a.res = (const float*)d.res; a.y = d.y;
-  a.yt = d.yt; a.Cin = d.Cin; a.Cout = d.Cout; a.ldy = d.yt ? d.yt_from : d.Cout;
-  a.yt_from = d.yt_from; a.yt_T = d.yt_T; a.yt_Tp = d.yt_Tp; a.rows = d.rows; a.in_map = d.in_map; a.out_map = d.out_map;
-  // output-channel tiles per workgroup: as many as possible while the grid still covers the chip
-  const int tiles = d.Cout / BCO;
-  const int64_t row_blocks = (d.rows + 127) / 128;
-  int nct = tiles;
-  while (nct > 1 && (tiles % nct != 0 || row_blocks * (tiles / nct) < 256)) --nct;
-  a.nct = nct;
-  dim3 grid((unsigned)row_blocks, tiles / nct);
+  a.x = d.x; a.scale = d.scale; a.shift = d.shift; a.wf = d.w_frag; a.bias = d.bias; a.res = (const float*)d.res; a.y = d.y;
+  a.yt = d.yt; a.Cout = d.Cout; a.ldy = d.yt ? d.yt_from : d.Cout; a.tc = tc;
+  a.yt_from = d.yt_from; a.yt_T = d.yt_T; a.yt_Tp = d.yt_Tp; a.rows = (int)d.rows; a.in_map = d.in_map; a.out_map = d.out_map;
+  // one workgroup per compute unit (its registers hold the weights), each with a contiguous range of tiles
+  const int ntiles = ((int)d.rows + kRows - 1) / kRows;
+  const int gx_max = 256 / cols > 1 ? 256 / cols : 1;
+  int tpw = (ntiles + gx_max - 1) / gx_max;
+  if (tpw < kLinMinTiles) tpw = kLinMinTiles;
+  a.tiles_per_wg = tpw;
+  dim3 grid((unsigned)((ntiles + tpw - 1) / tpw), cols);
   kern<<<grid, 256, lds, s>>>(a);
   return hipGetLastError();
 }
 
-// Returns hipErrorNotSupported when the resident activation tile does not fit in LDS (the caller
+// Returns hipErrorNotSupported for shapes whose weights do not fit the register budget (the caller
 // then uses the streaming kernel).
 hipError_t launch_linear(hipStream_t s, const FusedDesc& d) {
   if (d.taps != 1 || d.rows <= 0) return d.rows <= 0 ? hipSuccess : hipErrorInvalidValue;
-  const int es = (int)dtype_size(d.dt);
-  if (d.Cin % (kRowL / es) != 0 || d.Cout_store != d.Cout) return hipErrorInvalidValue;
-  const bool wide = d.Cout % 160 == 0;
-  if (!wide && d.Cout % 64 != 0) return hipErrorInvalidValue;
-  const int bco = wide ? 160 : 64;
-  const int lds = 128 * (d.Cin * es + 16) + 2 * bco * kLdsL;
-  if (lds > 150 * 1024) return hipErrorNotSupported;
-  if (d.yt && (d.y_f32 || d.res || d.yt_from % bco || d.yt_from <= 0 || d.yt_from >= d.Cout || d.yt_Tp % 64 ||
-               d.yt_Tp < d.yt_T || d.out_map.rows_per_seg < d.rows))
+  if (!d.w_frag || d.Cout % 32 != 0 || d.Cout_store != d.Cout || d.rows > (int64_t)1 << 30) return hipErrorNotSupported;
+  const bool y32 = d.y_f32 || d.dt != kBF16;
+  if (d.res && !y32) return hipErrorNotSupported;
+  if (d.yt && (d.y_f32 || d.res || d.yt_from <= 0 || d.yt_from >= d.Cout || d.yt_Tp % 64 || d.yt_Tp < d.yt_T ||
+               d.out_map.rows_per_seg < d.rows))
     return hipErrorInvalidValue;
-  const bool y32 = d.y_f32 || es == 4;
-#define LC_GO(T, OT, SRC) (wide ? run_lin<T, OT, 5, SRC>(s, d, lds) : run_lin<T, OT, 2, SRC>(s, d, lds))
+#define LC_GO(T, OT, SRC)                                                      \
+  switch (d.Cin) {                                                             \
+    case 64: return run_lin<T, OT, 64, SRC>(s, d);                             \
+    case 128: return run_lin<T, OT, 128, SRC>(s, d);                           \
+    case 320:                                                                  \
+      if (sizeof(T) == 2) return run_lin<T, OT, sizeof(T) == 2 ? 320 : 64, SRC>(s, d); \
+      break;                                                                   \
+    default: break;                                                            \
+  }                                                                            \
+  return hipErrorNotSupported
   if (d.dt == kBF16) {
-    if (d.src == 1 && !y32) return LC_GO(bf16_t, bf16_t, 1);
-    if (d.src == 0 && y32) return LC_GO(bf16_t, float, 0);
+    if (d.src == 1 && !y32) { LC_GO(bf16_t, bf16_t, 1); }
+    if (d.src == 0 && y32) { LC_GO(bf16_t, float, 0); }
   } else {
-    if (d.src == 1) return LC_GO(float, float, 1);
-    if (d.src == 0) return LC_GO(float, float, 0);
+    if (d.src == 1) { LC_GO(float, float, 1); }
+    if (d.src == 0) { LC_GO(float, float, 0); }
   }
 #undef LC_GO
-  return hipErrorInvalidValue;
+  return hipErrorNotSupported;
 }
 
 }  // namespace lc
