@@ -51,8 +51,27 @@ struct GemmArgs {
   RowMap in_map, out_map;
 };
 
-template <int BCO, int XROWS>
-constexpr int gemm_lds_bytes() { return 2 * (BCO + XROWS) * kLds; }
+// conv (TAPS == 9): three weight tiles of BCO x 128 bytes, written by LDS-direct loads (no padding:
+// a wavefront's 64 x 16 bytes land contiguously; bank conflicts are avoided by a swizzle instead),
+// then two padded halo tiles. Linear (TAPS == 1): two {weight tile, activation tile} pairs, all padded.
+template <int BCO, int XROWS, int TAPS>
+constexpr int gemm_lds_bytes() {
+  return TAPS == 9 ? 3 * BCO * kRow + 2 * XROWS * kLds : 2 * (BCO + XROWS) * kLds;
+}
+
+// s_waitcnt immediate: at most `vm` vector-memory operations and no LDS operation outstanding
+constexpr int waitcnt_imm(int vm) { return (vm & 15) | (7 << 4) | (0 << 8) | ((vm >> 4) << 14); }
+// Workgroup barrier that leaves the youngest `VM` vector-memory loads in flight. __syncthreads()
+// would wait for all of them: it cannot know that the outstanding LDS-direct loads write a tile
+// nobody reads before a later barrier.
+template <int VM>
+__device__ __forceinline__ void barrier_keep() {
+  static_assert(VM >= 0 && VM < 64, "vmcnt has six bits");
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(VM));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 }  // namespace
 
@@ -72,8 +91,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   constexpr bool SILU = SRC >= 2;
   static_assert(KI % 2 == 0, "the k-steps of a row are split between two wavefronts");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  auto w_lds = [&](int b) { return smem + b * (BCO + XROWS) * kLds; };
-  auto x_lds = [&](int b) { return smem + b * (BCO + XROWS) * kLds + BCO * kLds; };
+  auto w_lds = [&](int b) { return TAPS == 9 ? smem + b * BCO * kRow : smem + b * (BCO + XROWS) * kLds; };
+  auto x_lds = [&](int b) {
+    return TAPS == 9 ? smem + 3 * BCO * kRow + b * XROWS * kLds : smem + b * (BCO + XROWS) * kLds + BCO * kLds;
+  };
 
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int lp = lane & 31, hh = lane >> 5;
@@ -95,8 +116,28 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   }
   const int kp = tid & 7, lrow = tid >> 3;  // this thread moves packet kp of rows lrow + 32 * i
 
-  // ---------------- weights of the next step: global -> registers -> LDS ----------------
-  constexpr int NW = TAPS == 9 ? 3 : 1;  // conv: three sets in rotation, loads run two steps ahead
+  // ---------------- weights of a later step ----------------
+  // conv: global -> LDS directly, two steps ahead, into the tile that was read one step ago. A
+  // wavefront instruction moves 8 rows x 128 bytes; the 16-byte packet c of row r is parked in slot
+  // c ^ ((r >> 1) & 7) of that row, which makes the MFMA fragment reads (32 consecutive rows, one
+  // slot) conflict-free without padding. linear: global -> registers -> padded LDS tile, one step ahead.
+  static_assert(TAPS != 9 || (BCO * 8) % 256 == 0, "whole wavefront instructions");
+  auto dma_w = [&](int step, int buf) {
+    const int slab = step / TAPS, tap = step - slab * TAPS;
+#pragma unroll
+    for (int i = 0; i < WP; ++i) {
+      const int grp = i * 4 + wid;  // 8 rows
+      const int r = grp * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      const T* src = Wt + (int64_t)(co0 + r) * a.ldw + tap * a.Cin + slab * BKC + c * VEC;
+#ifdef __HIP_DEVICE_COMPILE__  // the host pass only needs the kernel's stub; it does not know this builtin
+      __builtin_amdgcn_global_load_lds(src, w_lds(buf) + grp * 1024, 16, 0, 0);
+#else
+      (void)src;
+#endif
+    }
+  };
+  constexpr int NW = 1;
   Vec16<T> wregs[NW][WP];
   auto issue_w = [&](int step, Vec16<T> (&wreg)[WP]) {
     const int slab = step / TAPS, tap = step - slab * TAPS;
@@ -209,14 +250,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
     const unsigned char* xb = x_lds(xbuf) + hh * LKB + kh * (KI / 2) * KB;
     const unsigned char* xl0 = xb + (xr0 + sh) * kLds;
     const unsigned char* xl1 = xb + (xr1 + sh) * kLds;
-    const unsigned char* wl = w_lds(wbuf) + lp * kLds + hh * LKB + kh * (KI / 2) * KB;
+    const int wstride = TAPS == 9 ? kRow : kLds;
+    const unsigned char* wl = w_lds(wbuf) + lp * wstride;
+    const int wkey = TAPS == 9 ? (lp >> 1) & 7 : 0;  // slot swizzle of this lane's rows (32 i does not change it)
 #pragma unroll
     for (int kk = 0; kk < KI / 2; ++kk) {
       const typename M::Frag xf0 = M::load((const T*)(xl0 + kk * KB));
       const typename M::Frag xf1 = M::load((const T*)(xl1 + kk * KB));
+      const int wb = hh * LKB + (kh * (KI / 2) + kk) * KB;  // byte of the fragment inside the row
+      const int wofs = (((wb >> 4) ^ wkey) << 4) | (wb & 15);
 #pragma unroll
       for (int i = 0; i < CO_T; ++i) {
-        const typename M::Frag wf = M::load((const T*)(wl + i * 32 * kLds + kk * KB));
+        const typename M::Frag wf = M::load((const T*)(wl + i * 32 * wstride + wofs));
         M::mma(wf, xf0, acc[i][0]);
         M::mma(wf, xf1, acc[i][1]);
       }
@@ -227,20 +272,24 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   const int nsteps = TAPS * nslab;
 
   // ---------------- prologue ----------------
-  constexpr int NXS = TAPS == 9 ? 3 : XR;  // conv: three halo packets in flight
+  // conv: a halo packet is requested at tap r and consumed at the end of tap r + 3, after that tap's
+  // own request has been issued: four register sets in rotation
+  constexpr int NXS = TAPS == 9 ? 4 : XR;
   const std::false_type no_c{};
   const std::true_type yes_c{};
   Affine aff[TAPS == 9 ? 1 : XR];
   XRaw xin[XR];
-  issue_w(0, wregs[0]);
   if (TAPS == 9) {
-    if (nsteps > 1) issue_w(1, wregs[1]);
+    dma_w(0, 0);
+    dma_w(1, 1);  // nsteps >= 9
     load_affine(0, frame, aff[0]);
 #pragma unroll
     for (int r = 0; r < XR; ++r) fetch_x(0, r, xin[r], no_c);  // slab 0 is never in the deep part
 #pragma unroll
     for (int r = 0; r < XR; ++r) finish_x(0, r, xin[r], aff[0], no_c);
+    barrier_keep<WP>();  // the weights of step 0 have landed, those of step 1 may still be on their way
   } else {
+    issue_w(0, wregs[0]);
 #pragma unroll
     for (int r = 0; r < XR; ++r) {
       fetch_x(0, r, xin[r], no_c);
@@ -248,13 +297,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
     }
 #pragma unroll
     for (int r = 0; r < XR; ++r) finish_x(0, r, xin[r], aff[r], no_c);
+    store_w(0, wregs[0]);
+    __syncthreads();
   }
-  store_w(0, wregs[0]);
-  __syncthreads();
 
   // ---------------- main loop ----------------
   // conv: per step (= one tap of one 64-channel slab) a thread issues at most one halo packet of the
-  // NEXT slab (rounds 0..5 at taps 0..5, activated and stored three taps later) and the weights of
+  // NEXT slab (rounds 0..5 at taps 0..5, activated and stored three taps later, interleaved with the
+  // MFMAs of that tap) and the weights of
   // step s+2; it stores the weights of step s+1 (fetched during step s-1) after its MFMAs. The
   // number of loads per tap is fixed at compile time - the loop is split by where the next slab
   // comes from (skip feature, deep feature, none) instead of branching - so every wait is an exact
@@ -266,18 +316,37 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap) {
         const int s = slab * 9 + tap;
-        if (MORE && tap >= 3 && tap - 3 < XR) finish_x((slab + 1) & 1, tap - 3, xin[(tap - 3) % NXS], aff[0], deep_c);
         __builtin_amdgcn_sched_barrier(0);
         if (MORE) {
           if (tap == 0) load_affine(slab + 1, frame, aff[0]);
           if (tap < XR) fetch_x(slab + 1, tap, xin[tap % NXS], deep_c);
         }
-        if (MORE || tap + 2 < 9) issue_w(s + 2, wregs[(tap + 2) % 3]);
         __builtin_amdgcn_sched_barrier(0);
-        compute(s & 1, slab & 1, tap);
+        constexpr bool WMORE = MORE;  // taps 7, 8 of the last slab have no step s + 2
+        if (WMORE || tap + 2 < 9) dma_w(s + 2, (s + 2) % 3);
         __builtin_amdgcn_sched_barrier(0);
-        if (MORE || tap + 1 < 9) store_w((s + 1) & 1, wregs[(tap + 1) % 3]);
-        __syncthreads();
+        compute(s % 3, slab & 1, tap);
+        if (MORE && tap >= 3 && tap - 3 < XR) finish_x((slab + 1) & 1, tap - 3, xin[(tap - 3) % NXS], aff[0], deep_c);
+        // the activation arithmetic of the next slab's packet rides between the MFMAs: one MFMA,
+        // one fragment read, a handful of vector instructions, and again
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+        for (int q = 0; q < (KI / 2) * CO_T * 2; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // Before the barrier the weights of step s + 1 must have landed. They were the last loads of
+        // the previous tap; younger than them are exactly this tap's loads, whose number is fixed at
+        // compile time: scale/shift at tap 0, one halo packet at taps 0..5, the weights of step s + 2.
+        constexpr bool DEEPC = decltype(deep_c)::value;
+        constexpr int n_aff = !NORM ? 0 : 2 * (VEC / 4);
+        constexpr int n_pkt = (SRC == 3 && DEEPC) || !NORM ? 1 : VEC / 4;
+        if (tap == 0) barrier_keep<(MORE ? n_aff + n_pkt : 0) + WP>();
+        else if (tap < XR) barrier_keep<(MORE ? n_pkt : 0) + WP>();
+        else if (WMORE || tap + 2 < 9) barrier_keep<WP>();
+        else barrier_keep<0>();
       }
     };
     const int nskip = SRC == 3 ? a.Cs / BKC : nslab;  // slabs read from x; the rest from x2
@@ -307,6 +376,90 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
       }
       __syncthreads();
     }
+  }
+
+  if constexpr (TAPS == 9 && !PLANAR) {
+    // ---------------- conv: fold the two K halves and write out, both wavefronts of a pixel half at work ----------------
+    // The wavefront (pxh, kh) keeps the 32-pixel tiles j = kh, hands the others to its partner through LDS,
+    // then turns each finished 32 x 32 tile through a private LDS patch so that a lane stores 16 bytes
+    // of one pixel row and eight lanes cover its 128 contiguous bytes (the accumulator layout would
+    // store 16-byte pieces of 32 different rows per instruction). Bias and residual are added in that
+    // layout; the residual is requested before the hand-over so its latency hides behind it.
+    constexpr int kTile = 16 * 64;  // floats of one accumulator tile
+    float* give = reinterpret_cast<float*>(smem) + (pxh * 2 + kh) * (CO_T * kTile);
+    const float* take = reinterpret_cast<const float*>(smem) + (pxh * 2 + (kh ^ 1)) * (CO_T * kTile);
+    float* patch = reinterpret_cast<float*>(smem + 4 * CO_T * kTile * 4) + wid * (32 * 36);
+    static_assert(gemm_lds_bytes<BCO, XROWS, TAPS>() >= 4 * CO_T * kTile * 4 + 4 * 32 * 36 * 4, "hand-over area + patches");
+    const int prow = lane >> 3, pcol = (lane & 7) * 4;  // patch read-back: rows prow + 8 k, channels pcol..pcol+3
+    int64_t obase[4];
+    bool okk[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int p = pxh * 64 + kh * 32 + prow + 8 * k;
+      const int oy = ty0 + (p >> 4), ox = tx0 + (p & 15);
+      okk[k] = oy < a.H && ox < a.W;
+      obase[k] = okk[k] ? (((int64_t)frame * a.H + oy) * a.W + ox) * a.Cout_store + co0 + pcol : 0;
+    }
+    const float* R = a.res;
+    f32x4 rres[CO_T][4];
+    f32x4 bias_l[CO_T];
+#pragma unroll
+    for (int i = 0; i < CO_T; ++i) {
+      bias_l[i] = a.bias ? *reinterpret_cast<const f32x4*>(a.bias + co0 + i * 32 + pcol) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        rres[i][k] = (R && okk[k]) ? *reinterpret_cast<const f32x4*>(R + obase[k] + i * 32) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    auto hand_over = [&](auto jc) {  // jc: the tile column this wavefront gives away
+      constexpr int J = decltype(jc)::value;
+#pragma unroll
+      for (int i = 0; i < CO_T; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) give[(i * 16 + r) * 64 + lane] = acc[i][J][r];
+    };
+    if (kh == 0) hand_over(std::integral_constant<int, 1>{});
+    else hand_over(std::integral_constant<int, 0>{});
+    __syncthreads();
+    OT* Y = (OT*)a.y;
+    auto finish = [&](auto jc) {  // jc: the tile column this wavefront keeps
+      constexpr int J = decltype(jc)::value;
+#pragma unroll
+      for (int i = 0; i < CO_T; ++i) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][J][g * 4 + e] + take[(i * 16 + g * 4 + e) * 64 + lane];
+          *reinterpret_cast<f32x4*>(patch + lp * 36 + g * 8 + hh * 4) = v;
+        }
+        // the patch is private to this wavefront, whose LDS operations complete in order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          f32x4 v = *reinterpret_cast<const f32x4*>(patch + (prow + 8 * k) * 36 + pcol);
+          v += bias_l[i];
+          v += rres[i][k];
+          if (okk[k]) {
+            const int64_t o = obase[k] + i * 32;
+            if constexpr (sizeof(OT) == 2) {
+              bf16x4 ov;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16_t>(v[e]);
+              *reinterpret_cast<bf16x4*>((bf16_t*)Y + o) = ov;
+            } else {
+              *reinterpret_cast<f32x4*>((float*)Y + o) = v;
+            }
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+    };
+    if (kh == 0) finish(std::integral_constant<int, 0>{});
+    else finish(std::integral_constant<int, 1>{});
+    return;
   }
 
   // ---------------- fold the two K halves: the upper half hands its tiles over through LDS ----------------
@@ -397,7 +550,7 @@ template <class T, class OT, int TAPS, int CO_T, int SRC, bool PLANAR>
 static hipError_t run_gemm(hipStream_t s, const FusedDesc& d) {
   constexpr int BCO = CO_T * 32;
   constexpr int XROWS = TAPS == 9 ? kHaloRows : 128;
-  constexpr int lds = gemm_lds_bytes<BCO, XROWS>();
+  constexpr int lds = gemm_lds_bytes<BCO, XROWS, TAPS>();
   static_assert(lds >= 2 * CO_T * 2 * 16 * 64 * 4, "the K-half hand-over reuses the operand tiles");
   auto kern = gemm_kernel<T, OT, TAPS, CO_T, SRC, PLANAR>;
   static bool attr_done = false;  // per instantiation
