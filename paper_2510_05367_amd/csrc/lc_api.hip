@@ -33,6 +33,7 @@ struct ConvW { void* w; float* b; };
 struct AttnW { GnW gn; void* wqkv; void* wo; float* bo; void* wqkv_f; void* wo_f; };  // *_f: fragment order
 struct Packed {
   float* cin_w; float* cin_b;
+  void* cin_wf;  // conv_in as a linear layer on gathered neighbourhoods: [C][64] in fragment order, or nullptr
   GnW res_gn[LC_MAX_RES]; ConvW res[LC_MAX_RES];
   AttnW sattn, tattn;
   ConvW down; GnW dres_gn; ConvW dres;
@@ -218,6 +219,21 @@ FusedDesc flinear_desc(lc_ctx* c, const void* w, const void* w_frag, const float
   return d;
 }
 
+// h = conv3x3(x): x planar [frames][C_lat][H][W] of the operand type, h fp32 rows
+hipError_t conv_in_launch(lc_ctx* c, const void* x, void* h, int frames) {
+  const lc_config& g = c->cfg;
+  if (c->pw.cin_wf) {
+    FusedDesc d;
+    memset(&d, 0, sizeof d);
+    d.dt = g.dtype; d.y_f32 = 1; d.taps = 1; d.src = 2; d.Cin = 64; d.Cs = g.C_lat; d.Cout = g.C; d.Cout_store = g.C;
+    d.w_frag = c->pw.cin_wf; d.bias = c->pw.cin_b; d.frames = frames; d.H = g.H; d.W = g.W;
+    d.rows = (int64_t)frames * g.H * g.W; d.in_map = dense_map(); d.out_map = dense_map(); d.x = x; d.y = h;
+    const hipError_t e = launch_linear(c->cs, d);
+    if (e != hipErrorNotSupported) return e;
+  }
+  return launch_conv_in(c->cs, g.dtype, x, h, frames, g.H, g.W, g.C_lat, g.C, c->pw.cin_w, c->pw.cin_b);
+}
+
 // residual block body: y = x + conv3x3(SiLU(GN(x))); x fp32 [frames][H*W][Cn]; y must not alias x
 lc_status res_block(lc_ctx* c, const GnW& gn, const ConvW& cw, int Cn, int frames, int H, int W, const void* x,
                     void* y, int y_f32, int kind) {
@@ -276,8 +292,7 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     // a 3x3 convolution cannot run in place (its halo reads rows other workgroups write), so the
     // residual blocks alternate between hc and hb; start so that the last one lands in hc
     char* cur = (g.n_res % 2 == 0) ? hc : hb;
-    LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, (const char*)x + (size_t)n0 * g.C_lat * T * es, cur, nf,
-                                              g.H, g.W, g.C_lat, C, w.cin_w, w.cin_b));
+    LC_LAUNCH(c, LC_K_CONV_IN, conv_in_launch(c, (const char*)x + (size_t)n0 * g.C_lat * T * es, cur, nf));
     for (int i = 0; i < g.n_res; ++i) {
       char* nxt = cur == hc ? hb : hc;
       lc_status s = res_block(c, w.res_gn[i], w.res[i], C, nf, g.H, g.W, cur, nxt, 1, LC_K_CONV_RES);
@@ -488,6 +503,7 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   const size_t o_cin_w = take((size_t)Cl * 9 * C * 4), o_cin_b = take((size_t)C * 4);
+  const size_t o_cin_wp = take((size_t)C * 64 * es), o_cin_wf = take((size_t)C * 64 * es);
   size_t o_res_g[LC_MAX_RES], o_res_b[LC_MAX_RES], o_res_w[LC_MAX_RES], o_res_bias[LC_MAX_RES];
   for (int i = 0; i < g.n_res; ++i) {
     o_res_g[i] = take((size_t)C * 4); o_res_b[i] = take((size_t)C * 4);
@@ -520,6 +536,12 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
   LC_HIP(c, launch_pack_conv_in_w(s, dt, w->conv_in_w, (float*)(b + o_cin_w), C, Cl));
   F32(w->conv_in_b, o_cin_b, C, C);
   p.cin_w = (float*)(b + o_cin_w); p.cin_b = (float*)(b + o_cin_b);
+  p.cin_wf = nullptr;
+  if (Cl * 9 <= 64) {  // [C][Cl][3][3] is already [C][Cl*9]: pad the rows to 64, then fragment order
+    LC_HIP(c, launch_pad_rows(s, dt, w->conv_in_w, b + o_cin_wp, C, Cl * 9, 64));
+    LC_HIP(c, launch_pack_lin_w(s, dt, b + o_cin_wp, b + o_cin_wf, C, 64));
+    p.cin_wf = b + o_cin_wf;
+  }
   for (int i = 0; i < g.n_res; ++i) {
     F32(w->res[i].gn_g, o_res_g[i], C, C); F32(w->res[i].gn_b, o_res_b[i], C, C);
     CW(w->res[i].w, o_res_w[i], C, C, 9, C); F32(w->res[i].b, o_res_bias[i], C, C);
@@ -871,7 +893,7 @@ lc_status lc_op_conv_in(lc_ctx* c, const void* x, void* h, int frames) {
   if (s != LC_OK) return s;
   if (!x || !h) return fail(c, LC_ERR_ARG, "NULL tensor");
   const lc_config& g = c->cfg;
-  LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, x, h, frames, g.H, g.W, g.C_lat, g.C, c->pw.cin_w, c->pw.cin_b));
+  LC_LAUNCH(c, LC_K_CONV_IN, conv_in_launch(c, x, h, frames));
   return LC_OK;
 }
 

@@ -292,11 +292,97 @@ hipError_t launch_make_vt(hipStream_t s, int dt, const void* v, int ldv, void* v
 }
 
 // ---------------------------------------------------------------------------------------------
-// Temporal attention: thread = (batch b, position p, query frame f, head h), h fastest so that
-// neighbouring lanes read neighbouring head slices of the same row.
+// Temporal attention over the F frames of one spatial position. A workgroup takes `np` consecutive
+// positions of one batch element and brings the q,k,v rows of all F frames at those positions into
+// LDS once, with LDS-direct loads (F x np rows of 3C elements; the rows of one frame are contiguous
+// in memory). Then thread = (position, query frame f, head h), h fastest: per key frame every lane of
+// a wavefront reads the same row and neighbouring lanes neighbouring head slices of it, so the LDS
+// reads are broadcasts or conflict-free, where the same loop over global memory had every thread
+// pull all F key and value rows through the vector cache again.
 // ---------------------------------------------------------------------------------------------
 template <class T, int D>
-__global__ __launch_bounds__(256) void temporal_attn_kernel(const T* __restrict__ qkv, T* __restrict__ out, int B,
+__global__ __launch_bounds__(256) void temporal_attn_kernel(const T* __restrict__ qkv, T* __restrict__ out, int F,
+                                                            int P, int heads, int np, float scale_log2e) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int PK = D / VEC;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int C = heads * D, ld = 3 * C;
+  const int tid = threadIdx.x, wid = tid >> 6;
+  const int b = blockIdx.y, p0 = blockIdx.x * np;
+  const int npv = min(np, P - p0);  // positions of this workgroup that exist
+  // LDS image [f][np][ld], filled 16 bytes per lane: packet q = (frame, position, packet of the row)
+  const int ppr = ld / VEC;         // packets per row
+  const int total = F * np * ppr;
+  for (int q0 = 0; q0 < total; q0 += 256) {
+    const int q = min(q0 + tid, total - 1);
+    const int row = q / ppr, pk = q - row * ppr;
+    const int f = row / np, pos = min(row - f * np, npv - 1);  // positions beyond the end: a copy nobody reads
+    const T* src = qkv + ((int64_t)(b * F + f) * P + p0 + pos) * ld + pk * VEC;
+#ifdef __HIP_DEVICE_COMPILE__  // the host pass only needs the kernel's stub; it does not know this builtin
+    __builtin_amdgcn_global_load_lds(src, smem + (q0 + wid * 64) * 16, 16, 0, 0);
+#else
+    (void)src;
+#endif
+  }
+  __builtin_amdgcn_s_waitcnt(0);  // every counter at zero: the rows have landed
+  __syncthreads();
+
+  const T* rows = reinterpret_cast<const T*>(smem);
+  const int items = npv * F * heads;
+  for (int item = tid; item < items; item += 256) {
+    const int h = item % heads;
+    const int f = (item / heads) % F;
+    const int pos = item / (heads * F);
+    const T* qrow = rows + (int64_t)(f * np + pos) * ld + h * D;
+    float q[D];
+#pragma unroll
+    for (int k = 0; k < PK; ++k) {
+      Vec16<T> v = load16(qrow + k * VEC);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) q[k * VEC + e] = v.get(e) * scale_log2e;
+    }
+    float acc[D];
+#pragma unroll
+    for (int e = 0; e < D; ++e) acc[e] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    for (int g = 0; g < F; ++g) {
+      const T* krow = rows + (int64_t)(g * np + pos) * ld + C + h * D;
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < PK; ++k) {
+        Vec16<T> v = load16(krow + k * VEC);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s = fmaf(q[k * VEC + e], v.get(e), s);
+      }
+      const float m_new = fmaxf(m, s);
+      const float alpha = exp2f(m - m_new);
+      const float pe = exp2f(s - m_new);
+      m = m_new;
+      l = l * alpha + pe;
+      const T* vrow = krow + C;
+#pragma unroll
+      for (int k = 0; k < PK; ++k) {
+        Vec16<T> v = load16(vrow + k * VEC);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[k * VEC + e] = fmaf(acc[k * VEC + e], alpha, pe * v.get(e));
+      }
+    }
+    const float inv = 1.f / l;
+    T* orow = out + ((int64_t)(b * F + f) * P + p0 + pos) * C + h * D;
+#pragma unroll
+    for (int k = 0; k < PK; ++k) {
+      Vec16<T> v;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v.set(e, acc[k * VEC + e] * inv);
+      store16(orow + k * VEC, v);
+    }
+  }
+}
+
+// The same computation straight from global memory, for frame counts whose rows do not fit in LDS:
+// thread = (batch b, position p, query frame f, head h), h fastest.
+template <class T, int D>
+__global__ __launch_bounds__(256) void temporal_attn_global_kernel(const T* __restrict__ qkv, T* __restrict__ out, int B,
                                                             int F, int P, int heads, float scale_log2e) {
   constexpr int VEC = Vec16<T>::N;
   constexpr int PK = D / VEC;
@@ -356,22 +442,43 @@ __global__ __launch_bounds__(256) void temporal_attn_kernel(const T* __restrict_
   }
 }
 
+template <class T, int D>
+static hipError_t temporal_run(hipStream_t s, const T* qkv, T* out, int B, int F, int P, int heads, float sl) {
+  const int64_t pos_bytes = (int64_t)F * 3 * heads * D * (int64_t)sizeof(T);  // LDS for one position
+  if (pos_bytes + 4096 > 150 * 1024) {
+    const int64_t total = (int64_t)B * P * F * heads;
+    temporal_attn_global_kernel<T, D><<<(unsigned)((total + 255) / 256), 256, 0, s>>>(qkv, out, B, F, P, heads, sl);
+    return hipGetLastError();
+  }
+  // positions per workgroup: two workgroups per compute unit if possible, at most 16 positions
+  int np = (int)(64 * 1024 / pos_bytes);
+  np = np < 1 ? 1 : (np > 16 ? 16 : np);
+  if (np > P) np = P;
+  const int64_t packets = (int64_t)F * np * (3 * heads * D / Vec16<T>::N);
+  const int lds = (int)((packets + 255) / 256 * 256 * 16);  // whole rounds of 256 lanes land in LDS
+  auto kern = temporal_attn_kernel<T, D>;
+  static int attr_bytes = 0;  // per instantiation
+  if (lds > attr_bytes) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_bytes = lds;
+  }
+  dim3 grid((unsigned)((P + np - 1) / np), (unsigned)B);
+  kern<<<grid, 256, lds, s>>>(qkv, out, F, P, heads, np, sl);
+  return hipGetLastError();
+}
+
 template <class T>
 static hipError_t temporal_dispatch(hipStream_t s, const T* qkv, T* out, int B, int F, int P, int heads, int d) {
-  const int64_t total = (int64_t)B * P * F * heads;
-  const unsigned blocks = (unsigned)((total + 255) / 256);
   const float sl = 1.4426950408889634f / sqrtf((float)d);
-#define LC_GO(D) temporal_attn_kernel<T, D><<<blocks, 256, 0, s>>>(qkv, out, B, F, P, heads, sl)
   switch (d) {
-    case 8: LC_GO(8); break;
-    case 16: LC_GO(16); break;
-    case 32: LC_GO(32); break;
-    case 40: LC_GO(40); break;
-    case 64: LC_GO(64); break;
+    case 8: return temporal_run<T, 8>(s, qkv, out, B, F, P, heads, sl);
+    case 16: return temporal_run<T, 16>(s, qkv, out, B, F, P, heads, sl);
+    case 32: return temporal_run<T, 32>(s, qkv, out, B, F, P, heads, sl);
+    case 40: return temporal_run<T, 40>(s, qkv, out, B, F, P, heads, sl);
+    case 64: return temporal_run<T, 64>(s, qkv, out, B, F, P, heads, sl);
     default: return hipErrorInvalidValue;
   }
-#undef LC_GO
-  return hipGetLastError();
 }
 
 hipError_t launch_temporal_attention(hipStream_t s, int dt, const void* qkv, void* out, int B, int F, int P,

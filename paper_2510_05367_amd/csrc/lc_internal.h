@@ -57,7 +57,9 @@ struct FusedDesc {
   int taps;      // 9: 3x3 conv over [frames][H][W][Cin]; 1: linear layer over rows
   int src;       // 0: x has the operand type, used as is
                  // 1: x is fp32, x * scale[f][c] + shift[f][c] (GroupNorm apply)
-                 // 2: the same followed by SiLU
+                 // 2: the same followed by SiLU (taps == 9); taps == 1: x is a planar image
+                 //    [frames][Cs][H][W] of the operand type and row r gathers the 3x3 neighbourhood of
+                 //    pixel r, k = channel * 9 + tap (a first convolution as a linear layer; Cin = 64 >= 9 Cs)
                  // 3: channels [0,Cs) from the fp32 skip x, [Cs,Cin) from x2 (operand type, half
                  //    resolution, nearest 2x upsampled), then as 2
   int Cin, Cs, Cout, Cout_store;
@@ -114,6 +116,8 @@ hipError_t launch_pack_conv_w(hipStream_t s, int dt, const void* w, void* packed
 hipError_t launch_pack_conv_in_w(hipStream_t s, int dt, const void* w, float* packed, int C, int Cl);
 // w[Cout][Cin] -> MFMA fragment order for launch_linear
 hipError_t launch_pack_lin_w(hipStream_t s, int dt, const void* w, void* out, int Cout, int Cin);
+// w[Cout][Cin] -> out[Cout][Cin_padded] with zero columns appended
+hipError_t launch_pad_rows(hipStream_t s, int dt, const void* w, void* out, int Cout, int Cin, int Cin_padded);
 hipError_t launch_to_f32(hipStream_t s, int dt, const void* src, float* dst, int n, int n_padded);
 hipError_t launch_copy_rows(hipStream_t s, int dt, const void* src, void* dst, int64_t elems);
 

@@ -36,6 +36,7 @@ struct LinArgs {
   int Cout, ldy, tc, tiles_per_wg;  // tc: 32-channel tiles per workgroup column
   int yt_from, yt_T, yt_Tp;
   int rows;
+  int im_H, im_W, im_Cl;  // SRC == 2: x is planar [frames][im_Cl][im_H][im_W]
   RowMap in_map, out_map;
 };
 
@@ -64,7 +65,9 @@ __device__ __forceinline__ int64_t mapped(const RowMap& m, int seg, int rem) {
 
 }  // namespace
 
-// SRC: 0 = x has the operand type; 1 = x is fp32 and gets scale/shift (GroupNorm apply)
+// SRC: 0 = x has the operand type; 1 = x is fp32 and gets scale/shift (GroupNorm apply); 2 = row r is
+// the 3x3 neighbourhood (zero padded) of pixel r of a planar image, k = channel * 9 + tap, zeros beyond
+// 9 * im_Cl: a first convolution with few input channels as a linear layer on gathered rows
 template <class T, class OT, int CIN, int SRC>
 __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
   typedef Mma32<T> M;
@@ -115,12 +118,37 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
   const bool stager = rg < RPR;
   const int c0 = col * VEC;
   f32x4 raw[XP][RAWN];
+  T graw[SRC == 2 ? XP : 1][VEC];  // SRC == 2: gathered neighbourhood values and which of them exist
+  unsigned gmask[SRC == 2 ? XP : 1];
   float sc[VEC], sh[VEC];  // dead unless SRC == 1
   int fcur = -1;
   auto fetch_x = [&](int t) {
     const int row0 = t * kRows;
-    const TileOrigin o = tile_origin(row0, a.in_map.rows_per_seg);
     const int rmax = a.rows - 1 - row0;
+    if constexpr (SRC == 2) {
+      const int hw = a.im_H * a.im_W;
+#pragma unroll
+      for (int j = 0; j < XP; ++j) {
+        const int row = row0 + min(min(rg + RPR * j, kRows - 1), rmax);
+        const int f = row / hw, p = row - f * hw;
+        const int yy = p / a.im_W, xx = p - yy * a.im_W;
+        const T* img = (const T*)a.x + (int64_t)f * a.im_Cl * hw;
+        unsigned m = 0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const int k = c0 + e;
+          const int cl = k / 9, tap = k - cl * 9;
+          const int iy = yy + tap / 3 - 1, ix = xx + tap % 3 - 1;
+          const bool ok = cl < a.im_Cl && iy >= 0 && iy < a.im_H && ix >= 0 && ix < a.im_W;
+          m |= ok ? 1u << e : 0u;
+          // clamped: always a valid element
+          graw[j][e] = img[(int64_t)min(cl, a.im_Cl - 1) * hw + min(max(iy, 0), a.im_H - 1) * a.im_W + min(max(ix, 0), a.im_W - 1)];
+        }
+        gmask[j] = m;
+      }
+      return;
+    }
+    const TileOrigin o = tile_origin(row0, a.in_map.rows_per_seg);
 #pragma unroll
     for (int j = 0; j < XP; ++j) {
       const int r = min(min(rg + RPR * j, kRows - 1), rmax);  // clamped: always a valid row
@@ -156,6 +184,9 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
           }
 #pragma unroll
           for (int e = 0; e < VEC; ++e) out.set(e, ok ? fmaf(raw[j][(e >> 2) % RAWN][e & 3], sc[e], sh[e]) : 0.f);
+        } else if constexpr (SRC == 2) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) out.set(e, (ok && (gmask[j] >> e & 1u)) ? to_f32(graw[j][e]) : 0.f);
         } else {
           out = __builtin_bit_cast(Vec16<T>, raw[j][0]);
           if (!ok) out = zero16<T>();
@@ -329,6 +360,24 @@ hipError_t launch_pack_lin_w(hipStream_t s, int dt, const void* w, void* out, in
   return hipGetLastError();
 }
 
+// w[Cout][Cin] -> out[Cout][Cin_padded], zero columns beyond Cin
+template <class T>
+__global__ void pad_rows_kernel(const T* __restrict__ w, T* __restrict__ out, int Cout, int Cin, int Cin_padded) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)Cout * Cin_padded) return;
+  const int k = (int)(i % Cin_padded);
+  const int64_t co = i / Cin_padded;
+  out[i] = k < Cin ? w[co * Cin + k] : from_f32<T>(0.f);
+}
+hipError_t launch_pad_rows(hipStream_t s, int dt, const void* w, void* out, int Cout, int Cin, int Cin_padded) {
+  const int64_t n = (int64_t)Cout * Cin_padded;
+  if (n <= 0 || Cin > Cin_padded) return hipErrorInvalidValue;
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (dt == kBF16) pad_rows_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)w, (bf16_t*)out, Cout, Cin, Cin_padded);
+  else pad_rows_kernel<float><<<blocks, 256, 0, s>>>((const float*)w, (float*)out, Cout, Cin, Cin_padded);
+  return hipGetLastError();
+}
+
 template <class T, class OT, int CIN, int SRC>
 static hipError_t run_lin(hipStream_t s, const FusedDesc& d) {
   // workgroup columns: as few as keep a column within 4 wavefronts x kTileMax tiles
@@ -349,6 +398,7 @@ static hipError_t run_lin(hipStream_t s, const FusedDesc& d) {
   a.x = d.x; a.scale = d.scale; a.shift = d.shift; a.wf = d.w_frag; a.bias = d.bias; a.res = (const float*)d.res; a.y = d.y;
   a.yt = d.yt; a.Cout = d.Cout; a.ldy = d.yt ? d.yt_from : d.Cout; a.tc = tc;
   a.yt_from = d.yt_from; a.yt_T = d.yt_T; a.yt_Tp = d.yt_Tp; a.rows = (int)d.rows; a.in_map = d.in_map; a.out_map = d.out_map;
+  a.im_H = d.H; a.im_W = d.W; a.im_Cl = d.Cs;
   // one workgroup per compute unit (its registers hold the weights), each with a contiguous range of tiles
   const int ntiles = ((int)d.rows + kRows - 1) / kRows;
   const int gx_max = 256 / cols > 1 ? 256 / cols : 1;
@@ -380,6 +430,12 @@ hipError_t launch_linear(hipStream_t s, const FusedDesc& d) {
     default: break;                                                            \
   }                                                                            \
   return hipErrorNotSupported
+  if (d.src == 2) {  // gathered 3x3 neighbourhoods of a planar image
+    if (!y32 || d.res || d.yt || d.Cin != 64 || d.Cs <= 0 || d.Cs * 9 > 64 || d.H <= 0 || d.W <= 0 ||
+        d.rows != (int64_t)d.frames * d.H * d.W)
+      return hipErrorNotSupported;
+    return d.dt == kBF16 ? run_lin<bf16_t, float, 64, 2>(s, d) : run_lin<float, float, 64, 2>(s, d);
+  }
   if (d.dt == kBF16) {
     if (d.src == 1 && !y32) { LC_GO(bf16_t, bf16_t, 1); }
     if (d.src == 0 && y32) { LC_GO(bf16_t, float, 0); }
