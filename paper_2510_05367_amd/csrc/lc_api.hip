@@ -25,7 +25,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   int fc, tc, qc;  // effective frame chunk, temporal position chunk, spatial query chunk
-  size_t off_h, off_slots, slot_bytes, off_partH, off_partD, off_scale, off_shift, off_ws, ws_bytes, total;
+  size_t off_h, off_slots, slot_bytes, off_partH, off_partT, off_partU, off_partD, partD_bytes, off_scale, off_shift, off_ws,
+      ws_bytes, total;
 };
 
 struct GnW { float *gamma, *beta; };
@@ -61,6 +62,7 @@ struct lc_ctx {
   std::vector<char> host_filled, dev_filled;
   std::vector<hipEvent_t> ev_produced, ev_consumed, ev_in_done, ev_rd_done, ev_out_done;
   std::vector<char> in_pending;
+  std::vector<char> deep_stat_valid;  // partD of the slot matches its contents
   // stats
   lc_stats st;
   std::vector<EvPair> copy_pool, copy_pending;
@@ -127,10 +129,21 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   p.off_h = off; off += align_up((size_t)(N * T * g.C) * 4);  // the skip / residual stream is fp32
   p.slot_bytes = align_up((size_t)(N * (T / 4) * g.C_deep) * es);
   p.off_slots = off; off += p.slot_bytes * g.dev_slots;
-  // partH also serves the half-resolution GroupNorm of the deep stand-in
-  const size_t ph = std::max((size_t)stat_splits((int)T) * g.C, (size_t)stat_splits((int)(T / 4)) * g.C_deep);
+  // GroupNorm partial sums [frame][split][channel][2]. The kernels that produce a normalised tensor
+  // also write its partials, with their own split geometry (32-row tiles of the linear kernels,
+  // 32-pixel quarter tiles of the 3x3 kernels); the stand-alone statistics kernel uses 64-row splits.
+  // partH: the tensor at hand inside a frame chunk (also the half-resolution one of the deep stand-in);
+  // partT / partU: input of the temporal block / skip input of the up block, written chunk by chunk
+  // for all frames; partD: the cached deep feature, one region per device slot (kept while the slot
+  // does not change) plus one for the single-operator entry points.
+  size_t sp = std::max((size_t)stat_splits((int)T), (size_t)conv_stat_splits(g.H, g.W));
+  if (T % 32 == 0) sp = std::max(sp, (size_t)(T / 32));
+  const size_t ph = std::max(sp * g.C, (size_t)stat_splits((int)(T / 4)) * g.C_deep);
   p.off_partH = off; off += align_up((size_t)N * ph * 2 * sizeof(float));
-  p.off_partD = off; off += align_up((size_t)N * stat_splits((int)(T / 4)) * g.C_deep * 2 * sizeof(float));
+  p.off_partT = off; off += align_up((size_t)N * sp * g.C * 2 * sizeof(float));
+  p.off_partU = off; off += align_up((size_t)N * sp * g.C * 2 * sizeof(float));
+  p.partD_bytes = align_up((size_t)N * stat_splits((int)(T / 4)) * g.C_deep * 2 * sizeof(float));
+  p.off_partD = off; off += p.partD_bytes * (g.dev_slots + 1);
   p.off_scale = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
   p.off_shift = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
   const int64_t pc = (int64_t)p.fc * T;   // pixels of a frame chunk
@@ -171,21 +184,54 @@ struct Prof {
 inline char* slot_ptr(lc_ctx* c, int s) { return c->arena + c->plan.off_slots + c->plan.slot_bytes * s; }
 inline char* h_ptr(lc_ctx* c) { return c->arena + c->plan.off_h; }
 inline float* partH(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partH); }
-inline float* partD(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partD); }
+inline float* partT(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partT); }
+inline float* partU(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partU); }
+// statistics of the deep feature in device slot `s`; s == dev_slots: scratch of the single-operator calls
+inline float* partD(lc_ctx* c, int s) { return (float*)(c->arena + c->plan.off_partD + c->plan.partD_bytes * s); }
 inline float* scale_p(lc_ctx* c) { return (float*)(c->arena + c->plan.off_scale); }
 inline float* shift_p(lc_ctx* c) { return (float*)(c->arena + c->plan.off_shift); }
 inline char* ws_ptr(lc_ctx* c) { return c->arena + c->plan.off_ws; }
 
 RowMap dense_map() { return RowMap{0, 0, 1 << 30}; }
 
-// GroupNorm statistics of `frames` contiguous frames of [rows_per_frame, C] -> scale/shift (first
-// `frames` entries of the scale/shift scratch).
-lc_status gn_scale_shift(lc_ctx* c, const void* x, int frames, int rows_per_frame, int C, const GnW& w) {
+// Per-channel partial sums of the frames at hand, [frame][splits][C][2]; part == nullptr: none yet.
+struct StatRef {
+  const float* part;
+  int splits;
+};
+
+// scale/shift (first `frames` entries of the scale/shift scratch) from partial sums
+lc_status gn_from_stats(lc_ctx* c, StatRef st, int frames, int rows_per_frame, int C, const GnW& w) {
   const lc_config& g = c->cfg;
-  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, x, partH(c), frames, rows_per_frame, C));
   LC_LAUNCH(c, LC_K_GN_FINAL,
-            launch_gn_finalize(c->cs, partH(c), C, stat_splits(rows_per_frame), rows_per_frame, 1.f, nullptr, 0, 0,
-                               0, 0.f, w.gamma, w.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), frames));
+            launch_gn_finalize(c->cs, st.part, C, st.splits, rows_per_frame, 1.f, nullptr, 0, 0, 0, 0.f, w.gamma, w.beta,
+                               g.groups, g.gn_eps, scale_p(c), shift_p(c), frames));
+  return LC_OK;
+}
+
+// GroupNorm statistics of `frames` contiguous frames of fp32 [rows_per_frame, C] -> scale/shift; `st`
+// holds the partial sums if the kernel that wrote x produced them, else they are computed here.
+lc_status gn_scale_shift(lc_ctx* c, const void* x, int frames, int rows_per_frame, int C, const GnW& w,
+                         StatRef st = StatRef{nullptr, 0}) {
+  if (!st.part) {
+    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, x, partH(c), frames, rows_per_frame, C));
+    st = StatRef{partH(c), stat_splits(rows_per_frame)};
+  }
+  return gn_from_stats(c, st, frames, rows_per_frame, C, w);
+}
+
+// A linear layer through the weight-stationary kernel, which can also write the statistics of its
+// output (d.stat); shapes it does not cover go to the streaming kernel, which cannot. *wrote tells.
+lc_status linear(lc_ctx* c, int kind, FusedDesc d, bool* wrote_stats) {
+  hipError_t e;
+  { Prof pr_(c, kind); e = launch_linear(c->cs, d); }
+  if (wrote_stats) *wrote_stats = e == hipSuccess && d.stat != nullptr;
+  if (e == hipErrorNotSupported) {
+    d.stat = nullptr;
+    Prof pr_(c, kind);
+    e = launch_fused(c->cs, d);
+  }
+  if (e != hipSuccess) return fail(c, LC_ERR_HIP, "linear layer: %s", hipGetErrorString(e));
   return LC_OK;
 }
 
@@ -219,49 +265,84 @@ FusedDesc flinear_desc(lc_ctx* c, const void* w, const void* w_frag, const float
   return d;
 }
 
-// h = conv3x3(x): x planar [frames][C_lat][H][W] of the operand type, h fp32 rows
-hipError_t conv_in_launch(lc_ctx* c, const void* x, void* h, int frames) {
+// h = conv3x3(x): x planar [frames][C_lat][H][W] of the operand type, h fp32 rows. With `stat` the
+// partial sums of h are written too ([frame][T/32][C][2]; T must be a multiple of 32); *wrote tells
+// whether the kernel that ran could do that.
+lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat, bool* wrote_stats) {
   const lc_config& g = c->cfg;
+  const int T = g.H * g.W;
+  if (wrote_stats) *wrote_stats = false;
   if (c->pw.cin_wf) {
     FusedDesc d;
     memset(&d, 0, sizeof d);
     d.dt = g.dtype; d.y_f32 = 1; d.taps = 1; d.src = 2; d.Cin = 64; d.Cs = g.C_lat; d.Cout = g.C; d.Cout_store = g.C;
     d.w_frag = c->pw.cin_wf; d.bias = c->pw.cin_b; d.frames = frames; d.H = g.H; d.W = g.W;
-    d.rows = (int64_t)frames * g.H * g.W; d.in_map = dense_map(); d.out_map = dense_map(); d.x = x; d.y = h;
-    const hipError_t e = launch_linear(c->cs, d);
-    if (e != hipErrorNotSupported) return e;
+    d.rows = (int64_t)frames * T; d.in_map = dense_map(); d.out_map = dense_map(); d.x = x; d.y = h;
+    if (stat && T % 32 == 0) { d.stat = stat; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
+    hipError_t e;
+    { Prof pr_(c, LC_K_CONV_IN); e = launch_linear(c->cs, d); }
+    if (e == hipSuccess) {
+      if (wrote_stats) *wrote_stats = d.stat != nullptr;
+      return LC_OK;
+    }
+    if (e != hipErrorNotSupported) return fail(c, LC_ERR_HIP, "conv_in: %s", hipGetErrorString(e));
   }
-  return launch_conv_in(c->cs, g.dtype, x, h, frames, g.H, g.W, g.C_lat, g.C, c->pw.cin_w, c->pw.cin_b);
-}
-
-// residual block body: y = x + conv3x3(SiLU(GN(x))); x fp32 [frames][H*W][Cn]; y must not alias x
-lc_status res_block(lc_ctx* c, const GnW& gn, const ConvW& cw, int Cn, int frames, int H, int W, const void* x,
-                    void* y, int y_f32, int kind) {
-  lc_status s = gn_scale_shift(c, x, frames, H * W, Cn, gn);
-  if (s != LC_OK) return s;
-  LC_LAUNCH(c, kind, launch_fused(c->cs, fconv_desc(c, cw, Cn, Cn, frames, H, W, x, x, y, y_f32)));
+  LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, x, h, frames, g.H, g.W, g.C_lat, g.C, c->pw.cin_w, c->pw.cin_b));
   return LC_OK;
 }
 
-// u = conv3x3(SiLU(GN(Concat(skip, up2(deep)))))
-lc_status up_conv(lc_ctx* c, const void* skip, const void* deep, void* u, int frames) {
+// residual block body: y = x + conv3x3(SiLU(GN(x))); x fp32 [frames][H*W][Cn]; y must not alias x.
+// `in`: partial sums of x if its producer wrote them. `out` (fp32 y only): receives the partial sums of y.
+lc_status res_block(lc_ctx* c, const GnW& gn, const ConvW& cw, int Cn, int frames, int H, int W, const void* x,
+                    void* y, int y_f32, int kind, StatRef in = StatRef{nullptr, 0}, StatRef* out = nullptr) {
+  lc_status s = gn_scale_shift(c, x, frames, H * W, Cn, gn, in);
+  if (s != LC_OK) return s;
+  FusedDesc d = fconv_desc(c, cw, Cn, Cn, frames, H, W, x, x, y, y_f32);
+  if (out && (y_f32 || c->cfg.dtype == kF32)) {
+    d.stat = partH(c);  // the partials of x have been folded into scale/shift by now
+    d.stat_splits = conv_stat_splits(H, W);
+    *out = StatRef{d.stat, d.stat_splits};
+  } else if (out) {
+    *out = StatRef{nullptr, 0};
+  }
+  LC_LAUNCH(c, kind, launch_fused(c->cs, d));
+  return LC_OK;
+}
+
+// u = conv3x3(SiLU(GN(Concat(skip, up2(deep))))). `skip_st`: partial sums of the skip feature if its
+// producer wrote them; `deep_part`: those of the deep feature ([frame][stat_splits(T/4)][Cd][2]) if
+// already known, else they are computed into the scratch region; `out` receives those of u.
+lc_status up_conv(lc_ctx* c, const void* skip, const void* deep, void* u, int frames, StatRef skip_st = StatRef{nullptr, 0},
+                  const float* deep_part = nullptr, StatRef* out = nullptr) {
   const lc_config& g = c->cfg;
   const int T = g.H * g.W, C = g.C, Cd = g.C_deep;
-  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, skip, partH(c), frames, T, C));
-  LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, deep, partD(c), frames, T / 4, Cd));
+  if (!skip_st.part) {
+    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, skip, partH(c), frames, T, C));
+    skip_st = StatRef{partH(c), stat_splits(T)};
+  }
+  if (!deep_part) {
+    float* pd = partD(c, g.dev_slots);
+    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, deep, pd, frames, T / 4, Cd));
+    deep_part = pd;
+  }
   LC_LAUNCH(c, LC_K_GN_FINAL,
-            launch_gn_finalize(c->cs, partH(c), C, stat_splits(T), T, 1.f, partD(c), Cd, stat_splits(T / 4), T / 4, 4.f,
+            launch_gn_finalize(c->cs, skip_st.part, C, skip_st.splits, T, 1.f, deep_part, Cd, stat_splits(T / 4), T / 4, 4.f,
                                c->pw.up_gn.gamma, c->pw.up_gn.beta, g.groups, g.gn_eps, scale_p(c), shift_p(c), frames));
   FusedDesc d = fconv_desc(c, c->pw.up, C + Cd, C, frames, g.H, g.W, skip, nullptr, u, 1);
   d.src = 3; d.x2 = deep; d.Cs = C;
+  if (out) {
+    d.stat = partH(c);
+    d.stat_splits = conv_stat_splits(g.H, g.W);
+    *out = StatRef{d.stat, d.stat_splits};
+  }
   LC_LAUNCH(c, LC_K_CONV_UP, launch_fused(c->cs, d));
   return LC_OK;
 }
 
 // eps = conv_out(SiLU(GN(u))), planar output of the operand type
-lc_status conv_out(lc_ctx* c, const void* u, void* eps, int frames) {
+lc_status conv_out(lc_ctx* c, const void* u, void* eps, int frames, StatRef u_st = StatRef{nullptr, 0}) {
   const lc_config& g = c->cfg;
-  lc_status s = gn_scale_shift(c, u, frames, g.H * g.W, g.C, c->pw.out_gn);
+  lc_status s = gn_scale_shift(c, u, frames, g.H * g.W, g.C, c->pw.out_gn, u_st);
   if (s != LC_OK) return s;
   FusedDesc d = fconv_desc(c, c->pw.out, g.C, 32, frames, g.H, g.W, u, nullptr, eps, 0);
   d.Cout_store = g.C_lat;
@@ -280,6 +361,7 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
   const Packed& w = c->pw;
 
   // ---- shallow down branch D_m, per frame chunk
+  bool tstat = T % 32 == 0;  // the 32-row tiles of the projection kernels stay inside a frame
   for (int n0 = 0; n0 < N; n0 += p.fc) {
     const int nf = std::min(p.fc, N - n0);
     const int64_t pc = (int64_t)nf * T;
@@ -292,14 +374,22 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     // a 3x3 convolution cannot run in place (its halo reads rows other workgroups write), so the
     // residual blocks alternate between hc and hb; start so that the last one lands in hc
     char* cur = (g.n_res % 2 == 0) ? hc : hb;
-    LC_LAUNCH(c, LC_K_CONV_IN, conv_in_launch(c, (const char*)x + (size_t)n0 * g.C_lat * T * es, cur, nf));
+    // every kernel below that writes the fp32 stream also writes the partial sums of what it wrote,
+    // for the GroupNorm that reads it next (where its tiles fit the frame; else they are computed apart)
+    StatRef st{nullptr, 0};
+    {
+      bool wrote = false;
+      lc_status s = conv_in_run(c, (const char*)x + (size_t)n0 * g.C_lat * T * es, cur, nf, partH(c), &wrote);
+      if (s != LC_OK) return s;
+      if (wrote) st = StatRef{partH(c), T / 32};
+    }
     for (int i = 0; i < g.n_res; ++i) {
       char* nxt = cur == hc ? hb : hc;
-      lc_status s = res_block(c, w.res_gn[i], w.res[i], C, nf, g.H, g.W, cur, nxt, 1, LC_K_CONV_RES);
+      lc_status s = res_block(c, w.res_gn[i], w.res[i], C, nf, g.H, g.W, cur, nxt, 1, LC_K_CONV_RES, st, &st);
       if (s != LC_OK) return s;
       cur = nxt;
     }
-    lc_status s = gn_scale_shift(c, hc, nf, T, C, w.sattn.gn);
+    lc_status s = gn_scale_shift(c, hc, nf, T, C, w.sattn.gn, st);
     if (s != LC_OK) return s;
     RowMap fm{0, T, T};  // dense rows; frame of row r = r / T
     {
@@ -307,18 +397,28 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       // kernel stages (no scattered transposition later)
       FusedDesc d = flinear_desc(c, w.sattn.wqkv, w.sattn.wqkv_f, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
       d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
-      LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, d));
+      s = linear(c, LC_K_QKV, d, nullptr);
+      if (s != LC_OK) return s;
     }
     for (int q0 = 0; q0 < T; q0 += p.qc)
       LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
                                                         g.head_dim, q0, std::min(q0 + p.qc, T)));
-    LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, w.sattn.wo, w.sattn.wo_f, w.sattn.bo, C, C, pc, 0, dense_map(),
-                                                             dense_map(), ao, hc, hc, 1)));
+    {
+      // the output projection closes the spatial block; its partial sums are those of the temporal
+      // block's input, collected for all frames in partT
+      FusedDesc d = flinear_desc(c, w.sattn.wo, w.sattn.wo_f, w.sattn.bo, C, C, pc, 0, dense_map(), dense_map(), ao, hc, hc, 1);
+      if (tstat) { d.stat = partT(c) + (size_t)n0 * (T / 32) * C * 2; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
+      bool wrote = false;
+      s = linear(c, LC_K_PROJ, d, &wrote);
+      if (s != LC_OK) return s;
+      tstat = tstat && wrote;
+    }
   }
 
   // ---- temporal block: per-frame statistics over whole frames, then per position chunk
+  bool ustat = T % 32 == 0 && p.tc % 32 == 0;  // the 32-row tiles of a position chunk stay inside a frame and a split
   {
-    lc_status s = gn_scale_shift(c, h, N, T, C, w.tattn.gn);
+    lc_status s = gn_scale_shift(c, h, N, T, C, w.tattn.gn, tstat ? StatRef{partT(c), T / 32} : StatRef{nullptr, 0});
     if (s != LC_OK) return s;
     for (int p0 = 0; p0 < T; p0 += p.tc) {
       const int np = std::min(p.tc, T - p0);
@@ -326,11 +426,17 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       RowMap m{p0, T, np};  // dense row r = (frame r / np, position p0 + r % np)
       char* qkv = ws;
       char* ao = ws + align_up((size_t)rows * 3 * C * es);
-      LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, flinear_desc(c, w.tattn.wqkv, w.tattn.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(),
-                                                              h, nullptr, qkv, 0)));
+      s = linear(c, LC_K_QKV, flinear_desc(c, w.tattn.wqkv, w.tattn.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(), h, nullptr, qkv, 0),
+                 nullptr);
+      if (s != LC_OK) return s;
       LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
-      LC_LAUNCH(c, LC_K_PROJ, launch_linear_any(c->cs, flinear_desc(c, w.tattn.wo, w.tattn.wo_f, w.tattn.bo, C, C, rows, 0, dense_map(), m,
-                                                               ao, h, h, 1)));
+      // this projection finishes the skip feature: its partial sums, for the up block, go to partU
+      FusedDesc d = flinear_desc(c, w.tattn.wo, w.tattn.wo_f, w.tattn.bo, C, C, rows, 0, dense_map(), m, ao, h, h, 1);
+      if (ustat) { d.stat = partU(c); d.stat_splits = T / 32; d.stat_rps = np; d.stat_off = p0; }
+      bool wrote = false;
+      s = linear(c, LC_K_PROJ, d, &wrote);
+      if (s != LC_OK) return s;
+      ustat = ustat && wrote;
     }
   }
 
@@ -351,9 +457,16 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     }
     LC_HIP(c, hipEventRecord(c->ev_produced[slot], c->cs));
     c->dev_filled[slot] = 1;
+    c->deep_stat_valid[slot] = 0;
   } else if (c->in_pending[slot]) {
     LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
     c->in_pending[slot] = 0;
+  }
+
+  // statistics of the cached deep feature: once per content of the slot, all frames in one launch
+  if (!c->deep_stat_valid[slot]) {
+    LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, g.dtype, deep, partD(c, slot), N, T / 4, Cd));
+    c->deep_stat_valid[slot] = 1;
   }
 
   // ---- shallow up branch U_m on Concat(skip, up2(deep)), per frame chunk
@@ -362,9 +475,11 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     char* hc = h + (size_t)n0 * T * C * 4;
     char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
     char* u = ws;  // fp32
-    lc_status s = up_conv(c, hc, dc, u, nf);
+    StatRef ust{nullptr, 0};
+    lc_status s = up_conv(c, hc, dc, u, nf, ustat ? StatRef{partU(c) + (size_t)n0 * (T / 32) * C * 2, T / 32} : StatRef{nullptr, 0},
+                          partD(c, slot) + (size_t)n0 * stat_splits(T / 4) * Cd * 2, &ust);
     if (s != LC_OK) return s;
-    s = conv_out(c, u, (char*)eps + (size_t)n0 * g.C_lat * T * es, nf);
+    s = conv_out(c, u, (char*)eps + (size_t)n0 * g.C_lat * T * es, nf, ust);
     if (s != LC_OK) return s;
   }
   LC_HIP(c, hipEventRecord(c->ev_consumed[slot], c->cs));
@@ -444,6 +559,7 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
   c->host_filled.assign(cfg->host_slots, 0);
   c->dev_filled.assign(cfg->dev_slots, 0);
   c->in_pending.assign(cfg->dev_slots, 0);
+  c->deep_stat_valid.assign(cfg->dev_slots, 0);
   auto mk = [&](std::vector<hipEvent_t>& v, int n, unsigned flags) -> hipError_t {
     for (int i = 0; i < n; ++i) {
       hipEvent_t e;
@@ -597,6 +713,7 @@ lc_status lc_set_workspace(lc_ctx* c, void* arena, size_t bytes) {
   c->arena_bytes = bytes;
   std::fill(c->dev_filled.begin(), c->dev_filled.end(), 0);
   std::fill(c->in_pending.begin(), c->in_pending.end(), 0);
+  std::fill(c->deep_stat_valid.begin(), c->deep_stat_valid.end(), 0);
   c->st.workspace_bytes = c->plan.total;
   return LC_OK;
 }
@@ -612,6 +729,7 @@ lc_status lc_set_chunk(lc_ctx* c, int frame_chunk, int token_chunk) {
   c->frame_chunk = frame_chunk;
   c->token_chunk = token_chunk;
   c->plan = np;
+  std::fill(c->deep_stat_valid.begin(), c->deep_stat_valid.end(), 0);  // their region moves with the plan
   c->st.workspace_bytes = np.total;
   return LC_OK;
 }
@@ -681,6 +799,7 @@ lc_status lc_swap_in(lc_ctx* c, int host_slot, int dev_slot) {
   LC_HIP(c, hipEventRecord(c->ev_in_done[dev_slot], c->ss));
   c->in_pending[dev_slot] = 1;
   c->dev_filled[dev_slot] = 1;
+  c->deep_stat_valid[dev_slot] = 0;
   c->st.swaps_in++;
   c->st.bytes_in += (int64_t)bytes;
   return LC_OK;
@@ -705,6 +824,7 @@ lc_status lc_cache_write(lc_ctx* c, int dev_slot, const void* deep) {
   LC_HIP(c, launch_planar_to_cl(c->cs, g.dtype, deep, slot_ptr(c, dev_slot), g.B * g.F, g.C_deep, (g.H / 2) * (g.W / 2)));
   LC_HIP(c, hipEventRecord(c->ev_produced[dev_slot], c->cs));
   c->dev_filled[dev_slot] = 1;
+  c->deep_stat_valid[dev_slot] = 0;
   return LC_OK;
 }
 
@@ -893,7 +1013,7 @@ lc_status lc_op_conv_in(lc_ctx* c, const void* x, void* h, int frames) {
   if (s != LC_OK) return s;
   if (!x || !h) return fail(c, LC_ERR_ARG, "NULL tensor");
   const lc_config& g = c->cfg;
-  LC_LAUNCH(c, LC_K_CONV_IN, conv_in_launch(c, x, h, frames));
+  return conv_in_run(c, x, h, frames, nullptr, nullptr);
   return LC_OK;
 }
 

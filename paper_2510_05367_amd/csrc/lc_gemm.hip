@@ -49,6 +49,8 @@ struct GemmArgs {
   int frames, H, W, tiles_x, tiles_y;
   int64_t rows;
   RowMap in_map, out_map;
+  float* stat;          // conv, fp32 output: per-channel statistics of the output (see FusedDesc), or nullptr
+  int stat_splits;
 };
 
 // conv (TAPS == 9): three weight tiles of BCO x 128 bytes, written by LDS-direct loads (no padding:
@@ -436,6 +438,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        float ssum[4] = {0.f, 0.f, 0.f, 0.f}, ssq[4] = {0.f, 0.f, 0.f, 0.f};  // statistics of this lane's pixels
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           f32x4 v = *reinterpret_cast<const f32x4*>(patch + (prow + 8 * k) * 36 + pcol);
@@ -450,6 +453,31 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
               *reinterpret_cast<bf16x4*>((bf16_t*)Y + o) = ov;
             } else {
               *reinterpret_cast<f32x4*>((float*)Y + o) = v;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                ssum[e] += v[e];
+                ssq[e] = fmaf(v[e], v[e], ssq[e]);
+              }
+            }
+          }
+        }
+        if constexpr (sizeof(OT) == 4) {
+          if (a.stat) {
+            // fold the eight lanes that hold the same channels, in a fixed order; the first writes.
+            // One split = the 32 pixels of this wavefront (those inside the image).
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+#pragma unroll
+              for (int m = 8; m < 64; m <<= 1) {
+                ssum[e] += __shfl_xor(ssum[e], m, 64);
+                ssq[e] += __shfl_xor(ssq[e], m, 64);
+              }
+            }
+            if (prow == 0) {
+              const int split = ((blockIdx.x % (a.tiles_x * a.tiles_y)) * 2 + pxh) * 2 + kh;
+              float* sp = a.stat + (((int64_t)frame * a.stat_splits + split) * a.Cout_store + co0 + i * 32 + pcol) * 2;
+              *reinterpret_cast<f32x4*>(sp) = f32x4{ssum[0], ssq[0], ssum[1], ssq[1]};
+              *reinterpret_cast<f32x4*>(sp + 4) = f32x4{ssum[2], ssq[2], ssum[3], ssq[3]};
             }
           }
         }
@@ -567,6 +595,7 @@ static hipError_t run_gemm(hipStream_t s, const FusedDesc& d) {
   a.frames = d.frames; a.H = d.H; a.W = d.W;
   a.tiles_x = (d.W + 15) / 16; a.tiles_y = (d.H + 7) / 8;
   a.rows = d.rows; a.in_map = d.in_map; a.out_map = d.out_map;
+  a.stat = d.stat; a.stat_splits = d.stat_splits;
   dim3 grid;
   if (TAPS == 9) {
     if (d.frames <= 0) return hipSuccess;
@@ -612,6 +641,8 @@ hipError_t launch_fused(hipStream_t s, const FusedDesc& d) {
                d.yt_Tp % 64 || d.yt_Tp < d.yt_T || d.out_map.rows_per_seg < d.rows))
     return hipErrorInvalidValue;
   const int esz = (int)dtype_size(d.dt);
+  if (d.stat && (d.taps != 9 || d.planar_out || !(d.y_f32 || esz == 4) || d.stat_splits != conv_stat_splits(d.H, d.W)))
+    return hipErrorInvalidValue;
   if (d.Cin % (kRow / esz) != 0) return hipErrorInvalidValue;
   if (d.src == 3 && (d.Cs % (kRow / esz) != 0 || d.Cs <= 0 || d.Cs >= d.Cin || (d.H | d.W) & 1)) return hipErrorInvalidValue;
   return d.dt == kBF16 ? by_kind<bf16_t>(s, d) : by_kind<float>(s, d);

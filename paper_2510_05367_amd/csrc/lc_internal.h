@@ -81,7 +81,17 @@ struct FusedDesc {
   // frame = r / yt_T, t = r % yt_T (the V^T layout of the spatial attention kernel). yt == nullptr: off.
   void* yt;
   int yt_from, yt_T, yt_Tp;
+  // Optional (fp32 output only): per-channel sum and sum of squares of the stored output, for the
+  // GroupNorm that reads it next, so that no separate pass over the tensor is needed.
+  // stat[frame][split][Cout][2]; nullptr = off. taps == 9: `frame` counts from the first frame of the
+  // launch and a split is one 32-pixel quarter of a workgroup tile (stat_splits = 4 * tiles per frame).
+  // taps == 1: dense row r belongs to frame r / stat_rps and split (stat_off + r % stat_rps) / 32;
+  // stat_rps and stat_off must be multiples of 32.
+  float* stat;
+  int stat_splits, stat_rps, stat_off;
 };
+// splits per frame of the statistics a 3x3 launch writes
+inline int conv_stat_splits(int H, int W) { return 4 * ((W + 15) / 16) * ((H + 7) / 8); }
 hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
 // taps == 1 with the weights resident in registers (needs w_frag); hipErrorNotSupported for shapes it does not cover
 hipError_t launch_linear(hipStream_t s, const FusedDesc& d);

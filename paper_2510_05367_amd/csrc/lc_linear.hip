@@ -37,6 +37,8 @@ struct LinArgs {
   int yt_from, yt_T, yt_Tp;
   int rows;
   int im_H, im_W, im_Cl;  // SRC == 2: x is planar [frames][im_Cl][im_H][im_W]
+  float* stat;            // per-channel statistics of the output (see FusedDesc), or nullptr
+  int stat_splits, stat_rps, stat_off;
   RowMap in_map, out_map;
 };
 
@@ -304,6 +306,7 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      float ssum[4] = {0.f, 0.f, 0.f, 0.f}, ssq[4] = {0.f, 0.f, 0.f, 0.f};  // statistics of this lane's rows
 #pragma unroll
       for (int k = 0; k < NK; ++k) {
         const int r = orow_l + RPI * k;
@@ -316,6 +319,11 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
             for (int e = 0; e < 4; ++e) v[e] += bias_l[i][e];
             if (R) v += rres[i][k];
             *reinterpret_cast<f32x4*>((float*)Y + o) = v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              ssum[e] += v[e];
+              ssq[e] = fmaf(v[e], v[e], ssq[e]);
+            }
           } else {
             Vec16<OT> ov = pv;
             if (a.bias) {
@@ -325,6 +333,27 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
               for (int e = 0; e < OV; ++e) ov.set(e, pv.get(e) + bv[e]);
             }
             store16((OT*)Y + o, ov);
+          }
+        }
+      }
+      if constexpr (sizeof(OT) == 4) {
+        if (a.stat) {
+          // the 32 rows of the tile lie in one frame and one split: fold the lanes that hold the same
+          // channels (they differ in lane / LPR), in a fixed order, and let the first of them write
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+#pragma unroll
+            for (int m = LPR; m < 64; m <<= 1) {
+              ssum[e] += __shfl_xor(ssum[e], m, 64);
+              ssq[e] += __shfl_xor(ssq[e], m, 64);
+            }
+          }
+          if (orow_l == 0) {
+            const int fr = row0 / a.stat_rps;
+            const int split = (a.stat_off + (row0 - fr * a.stat_rps)) >> 5;
+            float* sp = a.stat + (((int64_t)fr * a.stat_splits + split) * a.Cout + co + ocol * OV) * 2;
+            *reinterpret_cast<f32x4*>(sp) = f32x4{ssum[0], ssq[0], ssum[1], ssq[1]};
+            *reinterpret_cast<f32x4*>(sp + 4) = f32x4{ssum[2], ssq[2], ssum[3], ssq[3]};
           }
         }
       }
@@ -399,6 +428,7 @@ static hipError_t run_lin(hipStream_t s, const FusedDesc& d) {
   a.yt = d.yt; a.Cout = d.Cout; a.ldy = d.yt ? d.yt_from : d.Cout; a.tc = tc;
   a.yt_from = d.yt_from; a.yt_T = d.yt_T; a.yt_Tp = d.yt_Tp; a.rows = (int)d.rows; a.in_map = d.in_map; a.out_map = d.out_map;
   a.im_H = d.H; a.im_W = d.W; a.im_Cl = d.Cs;
+  a.stat = d.stat; a.stat_splits = d.stat_splits; a.stat_rps = d.stat_rps; a.stat_off = d.stat_off;
   // one workgroup per compute unit (its registers hold the weights), each with a contiguous range of tiles
   const int ntiles = ((int)d.rows + kRows - 1) / kRows;
   const int gx_max = 256 / cols > 1 ? 256 / cols : 1;
@@ -417,6 +447,9 @@ hipError_t launch_linear(hipStream_t s, const FusedDesc& d) {
   if (!d.w_frag || d.Cout % 32 != 0 || d.Cout_store != d.Cout || d.rows > (int64_t)1 << 30) return hipErrorNotSupported;
   const bool y32 = d.y_f32 || d.dt != kBF16;
   if (d.res && !y32) return hipErrorNotSupported;
+  if (d.stat && (!y32 || d.yt || d.stat_rps <= 0 || d.stat_rps % 32 || d.stat_off % 32 || d.rows % d.stat_rps ||
+                 (d.stat_off + d.stat_rps) / 32 > d.stat_splits))
+    return hipErrorInvalidValue;
   if (d.yt && (d.y_f32 || d.res || d.yt_from <= 0 || d.yt_from >= d.Cout || d.yt_Tp % 64 || d.yt_Tp < d.yt_T ||
                d.out_map.rows_per_seg < d.rows))
     return hipErrorInvalidValue;
