@@ -69,63 +69,63 @@ hipError_t launch_gn_stats(hipStream_t s, int dt, const void* x, float* partial,
 }
 
 // ---------------------------------------------------------------------------------------------
-// One workgroup folds the partial sums of `gpb` whole groups of one frame: 64 channel lanes x 4
-// split lanes, so that the loads over the splits are independent and few per thread.
-constexpr int kFinalCh = 512;  // channels one workgroup can own
-
+// One workgroup folds the partial sums of one group of one frame. The group's (split, channel) cells
+// are dealt to the 256 threads in a fixed pattern, each thread adds its cells in double precision in
+// a fixed order, and the 256 partial results are folded by a fixed tree: the result does not depend
+// on scheduling. The tensor may be the concatenation of two sources (A then B along the channels)
+// with different row counts per frame; `w` weighs a source's rows (the 2x-upsampled deep feature
+// counts each of its pixels four times).
 __global__ __launch_bounds__(256) void gn_finalize_kernel(const float* __restrict__ partA, int CA, int splitsA,
                                                           int rowsA, float wA, const float* __restrict__ partB,
                                                           int CB, int splitsB, int rowsB, float wB,
                                                           const float* __restrict__ gamma,
-                                                          const float* __restrict__ beta, int groups, int gpb,
-                                                          float eps, float* __restrict__ scale,
-                                                          float* __restrict__ shift) {
-  __shared__ double csum[4][kFinalCh], csq[4][kFinalCh];
-  __shared__ float gmean[kFinalCh], grstd[kFinalCh];
-  const int f = blockIdx.y, tid = threadIdx.x;
+                                                          const float* __restrict__ beta, int groups, float eps,
+                                                          float* __restrict__ scale, float* __restrict__ shift) {
+  __shared__ double rs[256], rq[256];
+  __shared__ float s_mean, s_rstd;
+  const int g = blockIdx.x, f = blockIdx.y, tid = threadIdx.x;
   const int Ct = CA + CB, cg = Ct / groups;
-  const int g0 = blockIdx.x * gpb, g1 = min(g0 + gpb, groups);
-  const int c_lo = g0 * cg, nch = (g1 - g0) * cg;
-  const int cl = tid & 63, sl = tid >> 6;
-  for (int j = cl; j < nch; j += 64) {
-    const int c = c_lo + j;
-    const bool inA = c < CA;
-    const int Cs = inA ? CA : CB, splits = inA ? splitsA : splitsB;
-    const float* p = (inA ? partA + ((int64_t)f * splitsA * CA + c) * 2
-                          : partB + ((int64_t)f * splitsB * CB + (c - CA)) * 2);
-    double ss = 0.0, qq = 0.0;
-#pragma unroll 8
-    for (int k = sl; k < splits; k += 4) {
-      const float2 v = *reinterpret_cast<const float2*>(p + (int64_t)k * Cs * 2);
-      ss += (double)v.x;
-      qq += (double)v.y;
-    }
-    csum[sl][j] = ss;
-    csq[sl][j] = qq;
+  const int c_lo = g * cg;
+  // channels of the group that lie in A / in B
+  const int nA = max(0, min(c_lo + cg, CA) - c_lo), nB = cg - nA;
+  const int cellsA = nA * splitsA, cellsB = nB * splitsB;
+  double ss = 0.0, qq = 0.0;
+  for (int i = tid; i < cellsA; i += 256) {
+    const int k = i / nA, c = c_lo + (i - k * nA);
+    const float2 v = *reinterpret_cast<const float2*>(partA + (((int64_t)f * splitsA + k) * CA + c) * 2);
+    ss += (double)wA * (double)v.x;
+    qq += (double)wA * (double)v.y;
   }
+  for (int i = tid; i < cellsB; i += 256) {
+    const int k = i / nB, c = max(c_lo, CA) - CA + (i - k * nB);
+    const float2 v = *reinterpret_cast<const float2*>(partB + (((int64_t)f * splitsB + k) * CB + c) * 2);
+    ss += (double)wB * (double)v.x;
+    qq += (double)wB * (double)v.y;
+  }
+  rs[tid] = ss;
+  rq[tid] = qq;
   __syncthreads();
-  for (int g = tid; g < g1 - g0; g += 256) {
-    double ss = 0.0, qq = 0.0, cnt = 0.0;
-    for (int j = g * cg; j < (g + 1) * cg; ++j) {
-      const bool inA = c_lo + j < CA;
-      const double w = inA ? (double)wA : (double)wB;
-      // fixed order: split lanes 0..3, then channels
-      ss += w * (((csum[0][j] + csum[1][j]) + csum[2][j]) + csum[3][j]);
-      qq += w * (((csq[0][j] + csq[1][j]) + csq[2][j]) + csq[3][j]);
-      cnt += inA ? (double)rowsA * wA : (double)rowsB * wB;
+  for (int m = 128; m > 0; m >>= 1) {
+    if (tid < m) {
+      rs[tid] += rs[tid + m];
+      rq[tid] += rq[tid + m];
     }
-    const double mean = ss / cnt;
-    double var = qq / cnt - mean * mean;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const double cnt = (double)nA * rowsA * wA + (double)nB * rowsB * wB;
+    const double mean = rs[0] / cnt;
+    double var = rq[0] / cnt - mean * mean;
     if (var < 0.0) var = 0.0;
-    gmean[g] = (float)mean;
-    grstd[g] = (float)(1.0 / sqrt(var + (double)eps));
+    s_mean = (float)mean;
+    s_rstd = (float)(1.0 / sqrt(var + (double)eps));
   }
   __syncthreads();
-  for (int j = tid; j < nch; j += 256) {
-    const int c = c_lo + j, g = j / cg;
-    const float a = grstd[g] * gamma[c];
+  for (int j = tid; j < cg; j += 256) {
+    const int c = c_lo + j;
+    const float a = s_rstd * gamma[c];
     scale[(int64_t)f * Ct + c] = a;
-    shift[(int64_t)f * Ct + c] = fmaf(-gmean[g], a, beta[c]);
+    shift[(int64_t)f * Ct + c] = fmaf(-s_mean, a, beta[c]);
   }
 }
 
@@ -134,13 +134,10 @@ hipError_t launch_gn_finalize(hipStream_t s, const float* partA, int CA, int spl
                               const float* gamma, const float* beta, int groups, float eps, float* scale,
                               float* shift, int frames) {
   if (frames <= 0) return hipSuccess;
-  const int cg = (CA + CB) / groups;
-  if (cg > kFinalCh) return hipErrorInvalidValue;
-  int gpb = 64 / cg;  // about 64 channels per workgroup
-  if (gpb < 1) gpb = 1;
-  dim3 grid((groups + gpb - 1) / gpb, frames);
+  if (groups <= 0 || (CA + CB) % groups) return hipErrorInvalidValue;
+  dim3 grid(groups, frames);
   gn_finalize_kernel<<<grid, 256, 0, s>>>(partA, CA, splitsA, rowsA, wA, partB, CB, splitsB, rowsB, wB, gamma, beta,
-                                          groups, gpb, eps, scale, shift);
+                                          groups, eps, scale, shift);
   return hipGetLastError();
 }
 
