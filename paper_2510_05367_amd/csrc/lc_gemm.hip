@@ -53,12 +53,14 @@ struct GemmArgs {
   int stat_splits;
 };
 
-// conv (TAPS == 9): three weight tiles of BCO x 128 bytes, written by LDS-direct loads (no padding:
+constexpr int kWBuf = 3;  // conv: weight tiles in LDS; the loads run kWBuf - 1 steps ahead of their use
+
+// conv (TAPS == 9): kWBuf weight tiles of BCO x 128 bytes, written by LDS-direct loads (no padding:
 // a wavefront's 64 x 16 bytes land contiguously; bank conflicts are avoided by a swizzle instead),
 // then two padded halo tiles. Linear (TAPS == 1): two {weight tile, activation tile} pairs, all padded.
 template <int BCO, int XROWS, int TAPS>
 constexpr int gemm_lds_bytes() {
-  return TAPS == 9 ? 3 * BCO * kRow + 2 * XROWS * kLds : 2 * (BCO + XROWS) * kLds;
+  return TAPS == 9 ? kWBuf * BCO * kRow + 2 * XROWS * kLds : 2 * (BCO + XROWS) * kLds;
 }
 
 // s_waitcnt immediate: at most `vm` vector-memory operations and no LDS operation outstanding
@@ -66,6 +68,19 @@ constexpr int waitcnt_imm(int vm) { return (vm & 15) | (7 << 4) | (0 << 8) | ((v
 // Workgroup barrier that leaves the youngest `VM` vector-memory loads in flight. __syncthreads()
 // would wait for all of them: it cannot know that the outstanding LDS-direct loads write a tile
 // nobody reads before a later barrier.
+// vector-memory loads issued in tap t of a conv slab body (see the main loop): scale/shift at tap 0 and a
+// halo packet at taps < xr if a next slab follows (`more`), then the weights of step s + ah if there is one.
+// t < 0 is tap 8 of the slab before, which was not the last one: weights only.
+constexpr int conv_tap_loads(int t, bool more, int n_aff, int n_pkt, int xr, int wp, int ah) {
+  if (t < 0) return wp;
+  return (more ? (t == 0 ? n_aff : 0) + (t < xr ? n_pkt : 0) : 0) + ((more || t + ah < 9) ? wp : 0);
+}
+// loads younger than the weights of step s + 1 at the end of tap `tap`: those of the last ah - 1 taps
+constexpr int conv_tap_keep(int tap, bool more, int n_aff, int n_pkt, int xr, int wp, int ah) {
+  int n = 0;
+  for (int j = 0; j < ah - 1; ++j) n += conv_tap_loads(tap - j, more, n_aff, n_pkt, xr, wp, ah);
+  return n;
+}
 template <int VM>
 __device__ __forceinline__ void barrier_keep() {
   static_assert(VM >= 0 && VM < 64, "vmcnt has six bits");
@@ -95,7 +110,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   auto w_lds = [&](int b) { return TAPS == 9 ? smem + b * BCO * kRow : smem + b * (BCO + XROWS) * kLds; };
   auto x_lds = [&](int b) {
-    return TAPS == 9 ? smem + 3 * BCO * kRow + b * XROWS * kLds : smem + b * (BCO + XROWS) * kLds + BCO * kLds;
+    return TAPS == 9 ? smem + kWBuf * BCO * kRow + b * XROWS * kLds : smem + b * (BCO + XROWS) * kLds + BCO * kLds;
   };
 
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
@@ -282,14 +297,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   Affine aff[TAPS == 9 ? 1 : XR];
   XRaw xin[XR];
   if (TAPS == 9) {
-    dma_w(0, 0);
-    dma_w(1, 1);  // nsteps >= 9
+#pragma unroll
+    for (int j = 0; j < kWBuf - 1; ++j) dma_w(j, j);  // nsteps >= 9 > kWBuf
     load_affine(0, frame, aff[0]);
 #pragma unroll
     for (int r = 0; r < XR; ++r) fetch_x(0, r, xin[r], no_c);  // slab 0 is never in the deep part
 #pragma unroll
     for (int r = 0; r < XR; ++r) finish_x(0, r, xin[r], aff[0], no_c);
-    barrier_keep<WP>();  // the weights of step 0 have landed, those of step 1 may still be on their way
+    barrier_keep<(kWBuf - 2) * WP>();  // the weights of step 0 have landed, the later ones may still be on their way
   } else {
     issue_w(0, wregs[0]);
 #pragma unroll
@@ -324,10 +339,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
           if (tap < XR) fetch_x(slab + 1, tap, xin[tap % NXS], deep_c);
         }
         __builtin_amdgcn_sched_barrier(0);
-        constexpr bool WMORE = MORE;  // taps 7, 8 of the last slab have no step s + 2
-        if (WMORE || tap + 2 < 9) dma_w(s + 2, (s + 2) % 3);
+        constexpr int AH = kWBuf - 1;  // the last slab has no step s + AH for its last AH taps
+        if (MORE || tap + AH < 9) dma_w(s + AH, (s + AH) % kWBuf);
         __builtin_amdgcn_sched_barrier(0);
-        compute(s % 3, slab & 1, tap);
+        compute(s % kWBuf, slab & 1, tap);
         if (MORE && tap >= 3 && tap - 3 < XR) finish_x((slab + 1) & 1, tap - 3, xin[(tap - 3) % NXS], aff[0], deep_c);
         // the activation arithmetic of the next slab's packet rides between the MFMAs: one MFMA,
         // one fragment read, a handful of vector instructions, and again
@@ -340,15 +355,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
         }
         __builtin_amdgcn_sched_barrier(0);
         // Before the barrier the weights of step s + 1 must have landed. They were the last loads of
-        // the previous tap; younger than them are exactly this tap's loads, whose number is fixed at
-        // compile time: scale/shift at tap 0, one halo packet at taps 0..5, the weights of step s + 2.
+        // tap s + 1 - AH; younger than them are exactly the loads of the AH - 1 taps since, whose
+        // number is fixed at compile time: per tap the scale/shift (tap 0) and halo packet (taps
+        // 0..5) of the next slab, then the weights of a later step.
         constexpr bool DEEPC = decltype(deep_c)::value;
         constexpr int n_aff = !NORM ? 0 : 2 * (VEC / 4);
         constexpr int n_pkt = (SRC == 3 && DEEPC) || !NORM ? 1 : VEC / 4;
-        if (tap == 0) barrier_keep<(MORE ? n_aff + n_pkt : 0) + WP>();
-        else if (tap < XR) barrier_keep<(MORE ? n_pkt : 0) + WP>();
-        else if (WMORE || tap + 2 < 9) barrier_keep<WP>();
-        else barrier_keep<0>();
+#define LC_KEEP(TAP) \
+  case TAP: barrier_keep<conv_tap_keep(TAP, MORE, n_aff, n_pkt, XR, WP, AH)>(); break;
+        switch (tap) {  // `tap` is a constant once the loop is unrolled
+          LC_KEEP(0) LC_KEEP(1) LC_KEEP(2) LC_KEEP(3) LC_KEEP(4) LC_KEEP(5) LC_KEEP(6) LC_KEEP(7) LC_KEEP(8)
+        }
+#undef LC_KEEP
       }
     };
     const int nskip = SRC == 3 ? a.Cs / BKC : nslab;  // slabs read from x; the rest from x2

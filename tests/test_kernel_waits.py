@@ -1,8 +1,10 @@
 """The conv kernel's workgroup barriers leave a counted number of vector-memory loads in flight
-(the weights of step s + 2 and the halo packet requested in the same tap) and rely on the loads
-issued in a tap being exactly those the source spells out. This test compiles the kernel file to
-gfx950 assembly and checks, for every 3x3 instantiation and every barrier interval of its main loop,
-that the count in the wait before the barrier equals the loads the compiler actually emitted."""
+(weights of later steps, which go to LDS directly, and the halo packets of the next slab) and rely on
+the loads issued in a tap being exactly those the source spells out. The weights of step s + 1 are the
+last loads of an earlier tap; before the barrier that ends tap s they must have landed, so the wait
+may leave at most the loads of the taps since then outstanding. This test compiles the kernel file to
+gfx950 assembly and checks that, for every 3x3 instantiation and every barrier interval of its main
+loop, against the loads the compiler actually emitted."""
 import re
 import subprocess
 from pathlib import Path
@@ -32,12 +34,17 @@ def test_barrier_waits_match_emitted_loads(gemm_asm):
         parts = body.split("s_barrier")[:-1]
         assert len(parts) >= 1 + 2 * 9  # prologue + at least two slab bodies of nine taps
         nloop = (len(parts) - 1) // 9 * 9  # what follows the main loop (the hand-over of the K halves) is not counted
-        for k, part in enumerate(parts[1:1 + nloop], start=1):
-            dma = len(re.findall(r"global_load_lds_dwordx4", part))
-            loads = len(re.findall(r"global_load_dword", part))
-            waits = [int(v) for v in re.findall(r"s_waitcnt vmcnt\((\d+)\)", part)]
-            assert len(waits) == 1, (name, k, waits)  # the explicit one before the barrier, nothing earlier
-            # either everything must have landed, or exactly this interval's loads may stay in flight
-            assert waits[0] in (0, dma + loads), (name, k, dma, loads, waits)
-            if dma == 0:
-                assert waits[0] == 0, (name, k)
+        issued, waits = [], []
+        for part in parts:
+            issued.append(len(re.findall(r"global_load_lds_dwordx4", part)) + len(re.findall(r"global_load_dword", part)))
+            waits.append([int(v) for v in re.findall(r"s_waitcnt vmcnt\((\d+)\)", part)])
+        # the weight loads run kWBuf - 1 steps ahead: those of step s + 1 are kWBuf - 3 taps old at the end of tap s
+        ahead = int(re.search(r"constexpr int kWBuf = (\d+);", (CSRC / "lc_gemm.hip").read_text()).group(1)) - 1
+        exact = 0
+        for k in range(1, nloop + 1):
+            assert len(waits[k]) == 1, (name, k, waits[k])  # the explicit one before the barrier, nothing earlier
+            younger = sum(issued[max(k - (ahead - 2), 0):k + 1])
+            assert waits[k][0] <= younger, (name, k, issued[k - 1:k + 1], waits[k])
+            exact += waits[k][0] == younger
+        # and it does not wait for more than it must, except where the loop runs out of steps
+        assert exact >= nloop - 5, (name, exact, nloop)
