@@ -53,6 +53,7 @@ struct GemmArgs {
   int stat_splits;
 };
 
+constexpr int FA = 3;  // weight fragments requested from LDS ahead of the MFMAs that use them
 constexpr int kWBuf = 3;  // conv: weight tiles in LDS; the loads run kWBuf - 1 steps ahead of their use
 
 // conv (TAPS == 9): kWBuf weight tiles of BCO x 128 bytes, written by LDS-direct loads (no padding:
@@ -223,30 +224,38 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
     const int64_t rr = row0 + lrow + 32 * r;
     return (rr < a.rows ? rr : a.rows - 1) / a.in_map.rows_per_seg;
   };
-  auto finish_x = [&](int buf, int r, const XRaw& o, const Affine& af, auto deep_c) {
+  // one element of a packet: activation arithmetic only
+  auto finish_elem = [&](int e, const XRaw& o, const Affine& af, auto deep_c, float (&vals)[VEC]) {
     constexpr bool from_t = !NORM || (SRC == 3 && decltype(deep_c)::value);
+    float t;
+    if (from_t) {
+      if constexpr (sizeof(T) == 2) {  // element e of the bf16 packet held in q[0]
+        typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+        const uint32_t wd = __builtin_bit_cast(u32x4, o.q[0])[e >> 1];
+        t = __builtin_bit_cast(float, (e & 1) ? (wd & 0xffff0000u) : (wd << 16));
+      } else {
+        t = o.q[0][e];
+      }
+    } else {
+      t = o.q[e >> 2][e & 3];
+    }
+    if (NORM) {
+      t = fmaf(t, af.sc[e], af.sh[e]);
+      if (SILU) t = silu_fast(t);
+    }
+    vals[e] = o.ok ? t : 0.f;
+  };
+  auto finish_store = [&](int buf, int r, const float (&vals)[VEC]) {
     Vec16<T> pk;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      float t;
-      if (from_t) {
-        if constexpr (sizeof(T) == 2) {  // element e of the bf16 packet held in q[0]
-          typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-          const uint32_t wd = __builtin_bit_cast(u32x4, o.q[0])[e >> 1];
-          t = __builtin_bit_cast(float, (e & 1) ? (wd & 0xffff0000u) : (wd << 16));
-        } else {
-          t = o.q[0][e];
-        }
-      } else {
-        t = o.q[e >> 2][e & 3];
-      }
-      if (NORM) {
-        t = fmaf(t, af.sc[e], af.sh[e]);
-        if (SILU) t = silu_fast(t);
-      }
-      pk.set(e, o.ok ? t : 0.f);
-    }
+    for (int e = 0; e < VEC; ++e) pk.set(e, vals[e]);
     *reinterpret_cast<Vec16<T>*>(x_lds(buf) + (lrow + 32 * r) * kLds + kp * 16) = pk;
+  };
+  auto finish_x = [&](int buf, int r, const XRaw& o, const Affine& af, auto deep_c) {
+    float vals[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) finish_elem(e, o, af, deep_c, vals);
+    finish_store(buf, r, vals);
   };
 
   f32x16 acc[CO_T][2];
@@ -262,7 +271,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   const int xr0 = TAPS == 9 ? (p0 >> 4) * kHaloW + (p0 & 15) : p0;
   const int xr1 = TAPS == 9 ? (p1 >> 4) * kHaloW + (p1 & 15) : p1;
 
-  auto compute = [&](int wbuf, int xbuf, int tap) {
+  // One tap. All activation fragments first, then the weight fragments in a ring that runs FA reads
+  // ahead of the MFMAs using them (one wavefront per SIMD: nothing else hides the LDS latency).
+  // `side(idx)` is vector work to run in the shadow of MFMA pair idx; the scheduling barriers pin
+  // this order.
+  constexpr int NF = (KI / 2) * CO_T;  // weight fragments of a tap for this wavefront
+  auto compute = [&](int wbuf, int xbuf, int tap, auto side) {
     const int sh = TAPS == 9 ? (tap / 3) * kHaloW + (tap % 3) : 0;
     const unsigned char* xb = x_lds(xbuf) + hh * LKB + kh * (KI / 2) * KB;
     const unsigned char* xl0 = xb + (xr0 + sh) * kLds;
@@ -270,18 +284,33 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
     const int wstride = TAPS == 9 ? kRow : kLds;
     const unsigned char* wl = w_lds(wbuf) + lp * wstride;
     const int wkey = TAPS == 9 ? (lp >> 1) & 7 : 0;  // slot swizzle of this lane's rows (32 i does not change it)
-#pragma unroll
-    for (int kk = 0; kk < KI / 2; ++kk) {
-      const typename M::Frag xf0 = M::load((const T*)(xl0 + kk * KB));
-      const typename M::Frag xf1 = M::load((const T*)(xl1 + kk * KB));
+    auto wload = [&](int idx) {
+      const int kk = idx / CO_T, i = idx - kk * CO_T;
       const int wb = hh * LKB + (kh * (KI / 2) + kk) * KB;  // byte of the fragment inside the row
       const int wofs = (((wb >> 4) ^ wkey) << 4) | (wb & 15);
+      return M::load((const T*)(wl + i * 32 * wstride + wofs));
+    };
+    typename M::Frag xf[KI / 2][2];
+    typename M::Frag wf[FA + 1];
+    xf[0][0] = M::load((const T*)(xl0));
+    xf[0][1] = M::load((const T*)(xl1));
 #pragma unroll
-      for (int i = 0; i < CO_T; ++i) {
-        const typename M::Frag wf = M::load((const T*)(wl + i * 32 * wstride + wofs));
-        M::mma(wf, xf0, acc[i][0]);
-        M::mma(wf, xf1, acc[i][1]);
-      }
+    for (int idx = 0; idx < FA && idx < NF; ++idx) wf[idx] = wload(idx);
+#pragma unroll
+    for (int kk = 1; kk < KI / 2; ++kk) {
+      xf[kk][0] = M::load((const T*)(xl0 + kk * KB));
+      xf[kk][1] = M::load((const T*)(xl1 + kk * KB));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int idx = 0; idx < NF; ++idx) {
+      if (idx + FA < NF) wf[(idx + FA) % (FA + 1)] = wload(idx + FA);
+      __builtin_amdgcn_sched_barrier(0);
+      const int kk = idx / CO_T, i = idx - kk * CO_T;
+      M::mma(wf[idx % (FA + 1)], xf[kk][0], acc[i][0]);
+      M::mma(wf[idx % (FA + 1)], xf[kk][1], acc[i][1]);
+      side(idx);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -342,17 +371,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
         constexpr int AH = kWBuf - 1;  // the last slab has no step s + AH for its last AH taps
         if (MORE || tap + AH < 9) dma_w(s + AH, (s + AH) % kWBuf);
         __builtin_amdgcn_sched_barrier(0);
-        compute(s % kWBuf, slab & 1, tap);
-        if (MORE && tap >= 3 && tap - 3 < XR) finish_x((slab + 1) & 1, tap - 3, xin[(tap - 3) % NXS], aff[0], deep_c);
-        // the activation arithmetic of the next slab's packet rides between the MFMAs: one MFMA,
-        // one fragment read, a handful of vector instructions, and again
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        // the activation arithmetic of the halo packet requested three taps ago rides in the shadow
+        // of the MFMAs, a few elements per MFMA pair; the packet is stored after the last pair
+        float xv[VEC];
+        constexpr int PER = (VEC + NF - 1) / NF;
+        compute(s % kWBuf, slab & 1, tap, [&](int idx) {
+          if (MORE && tap >= 3 && tap - 3 < XR) {
 #pragma unroll
-        for (int q = 0; q < (KI / 2) * CO_T * 2; ++q) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
-        }
+            for (int e = idx * PER; e < (idx + 1) * PER && e < VEC; ++e)
+              finish_elem(e, xin[(tap - 3) % NXS], aff[0], deep_c, xv);
+            if (idx == NF - 1) finish_store((slab + 1) & 1, tap - 3, xv);
+          }
+        });
         __builtin_amdgcn_sched_barrier(0);
         // Before the barrier the weights of step s + 1 must have landed. They were the last loads of
         // tap s + 1 - AH; younger than them are exactly the loads of the AH - 1 taps since, whose
@@ -387,7 +417,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
         issue_w(s + 1, wregs[0]);
       }
       __builtin_amdgcn_sched_barrier(0);
-      compute(s & 1, s & 1, 0);
+      compute(s & 1, s & 1, 0, [](int) {});
       __builtin_amdgcn_sched_barrier(0);
       if (more) {
 #pragma unroll
