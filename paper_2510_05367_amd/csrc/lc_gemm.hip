@@ -140,20 +140,21 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   // c ^ ((r >> 1) & 7) of that row, which makes the MFMA fragment reads (32 consecutive rows, one
   // slot) conflict-free without padding. linear: global -> registers -> padded LDS tile, one step ahead.
   static_assert(TAPS != 9 || (BCO * 8) % 256 == 0, "whole wavefront instructions");
-  auto dma_w = [&](int step, int buf) {
+  auto dma_w_one = [&](int step, int buf, int i) {  // instruction i of the WP that move one tile
     const int slab = step / TAPS, tap = step - slab * TAPS;
-#pragma unroll
-    for (int i = 0; i < WP; ++i) {
-      const int grp = i * 4 + wid;  // 8 rows
-      const int r = grp * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ ((r >> 1) & 7);
-      const T* src = Wt + (int64_t)(co0 + r) * a.ldw + tap * a.Cin + slab * BKC + c * VEC;
+    const int grp = i * 4 + wid;  // 8 rows
+    const int r = grp * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    const T* src = Wt + (int64_t)(co0 + r) * a.ldw + tap * a.Cin + slab * BKC + c * VEC;
 #ifdef __HIP_DEVICE_COMPILE__  // the host pass only needs the kernel's stub; it does not know this builtin
-      __builtin_amdgcn_global_load_lds(src, w_lds(buf) + grp * 1024, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(src, w_lds(buf) + grp * 1024, 16, 0, 0);
 #else
-      (void)src;
+    (void)src;
 #endif
-    }
+  };
+  auto dma_w = [&](int step, int buf) {
+#pragma unroll
+    for (int i = 0; i < WP; ++i) dma_w_one(step, buf, i);
   };
   constexpr int NW = 1;
   Vec16<T> wregs[NW][WP];
@@ -369,13 +370,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
         }
         __builtin_amdgcn_sched_barrier(0);
         constexpr int AH = kWBuf - 1;  // the last slab has no step s + AH for its last AH taps
-        if (MORE || tap + AH < 9) dma_w(s + AH, (s + AH) % kWBuf);
-        __builtin_amdgcn_sched_barrier(0);
         // the activation arithmetic of the halo packet requested three taps ago rides in the shadow
         // of the MFMAs, a few elements per MFMA pair; the packet is stored after the last pair
         float xv[VEC];
         constexpr int PER = (VEC + NF - 1) / NF;
         compute(s % kWBuf, slab & 1, tap, [&](int idx) {
+          // the weights of step s + AH are requested one instruction per MFMA pair: issued in a
+          // burst at the head of the tap they hold the MFMAs up
+          if ((MORE || tap + AH < 9) && idx < WP) dma_w_one(s + AH, (s + AH) % kWBuf, idx);
           if (MORE && tap >= 3 && tap - 3 < XR) {
 #pragma unroll
             for (int e = idx * PER; e < (idx + 1) * PER && e < VEC; ++e)
