@@ -52,6 +52,15 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
   // zero both buffers once: K columns beyond D and V^T rows beyond D feed padded MFMA lanes
   for (int i = tid; i < 2 * KBYTES / 4; i += 256) reinterpret_cast<uint32_t*>(&k_lds[0][0])[i] = 0u;
   for (int i = tid; i < 2 * VBYTES / 4; i += 256) reinterpret_cast<uint32_t*>(&v_lds[0][0])[i] = 0u;
+  // Softmax denominators for free: when d leaves a spare row in the 32-row tiles of V^T (d = 40:
+  // rows 40..63 are padding), row D is set to ones, so O^T[D][q] accumulates the sum over keys of
+  // exactly the (rounded) probabilities that multiply V, and is rescaled with the rest of O^T.
+  constexpr bool ROWSUM = D % 32 != 0;
+  if (ROWSUM) {
+    __syncthreads();
+    for (int i = tid; i < 2 * kKeys; i += 256)
+      reinterpret_cast<T*>(&v_lds[i / kKeys][D * VROW])[i % kKeys] = from_f32<T>(1.f);
+  }
 
   // ---- staging: K packet i = tid + 256 j of a stage is (key i / PK, packet i % PK); V^T packet i is
   //      (dim i / VPK, packet i % VPK) and is already in LDS order
@@ -167,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
         const float m_new = fmaxf(m_run[t], mx);
         const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2e);
         m_run[t] = m_new;
-        l_run[t] *= alpha;
+        if (!ROWSUM) l_run[t] *= alpha;
 #pragma unroll
         for (int mt = 0; mt < DM; ++mt)
 #pragma unroll
@@ -182,7 +191,7 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           p[r] = __builtin_amdgcn_exp2f(fmaf(sc[t][kt][r], scale_log2e, -mc));
-          ps += p[r];
+          if (!ROWSUM) ps += p[r];
         }
         if constexpr (sizeof(T) == 2) {
 #pragma unroll
@@ -194,7 +203,7 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
           for (int st = 0; st < PSTEPS; ++st) pf[kt][st] = p[st];
         }
       }
-      l_run[t] += ps;
+      if (!ROWSUM) l_run[t] += ps;
       // ---- O^T += V^T P^T. Step st of sub-tile kt contracts, in lane half hh, the keys of registers
       //      [LK*st, LK*st + LK): bf16 -> keys 16*st + 4*hh + {0..3} and 16*st + 8 + 4*hh + {0..3}
       //      (contiguous after the vcol permutation, at column 16*st + 8*hh); fp32 -> the single key
@@ -221,7 +230,13 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
 #pragma unroll
   for (int t = 0; t < NQT; ++t) {
     const int q = qblk + t * 32 + lq;
-    const float l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
+    float l;
+    if (ROWSUM) {  // O^T[D][q] sits in register r of the lanes of half hsel
+      constexpr int rem = D % 32, hsel = (rem % 8) / 4, r = (rem / 8) * 4 + rem % 4;
+      l = __shfl(o[t][D / 32][r], lq + 32 * hsel, 64);
+    } else {
+      l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
+    }
     const float inv = 1.f / l;
     if (q >= q1) continue;
     T* orow = out + ((int64_t)frame * T_tok + q) * C + head * D;
