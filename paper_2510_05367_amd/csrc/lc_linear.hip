@@ -151,6 +151,24 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
       return;
     }
     const TileOrigin o = tile_origin(row0, a.in_map.rows_per_seg);
+    if (o.rem0 + kRows <= a.in_map.rows_per_seg) {
+      // the usual case: the tile lies inside one segment, its rows are consecutive in memory. One
+      // (wave-uniform) base and 32-bit offsets: no per-lane division, no 64-bit arithmetic.
+      const int64_t sr0 = mapped(a.in_map, o.seg0, o.rem0);
+#pragma unroll
+      for (int j = 0; j < XP; ++j) {
+        const int r = min(min(rg + RPR * j, kRows - 1), rmax);  // clamped: always a valid row
+        const int ofs = r * CIN + c0;
+        if (SRC == 1) {
+          const float* px = (const float*)a.x + sr0 * CIN + ofs;
+#pragma unroll
+          for (int q = 0; q < RAWN; ++q) raw[j][q] = *reinterpret_cast<const f32x4*>(px + 4 * q);
+        } else {
+          raw[j][0] = *reinterpret_cast<const f32x4*>((const T*)a.x + sr0 * CIN + ofs);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < XP; ++j) {
       const int r = min(min(rg + RPR * j, kRows - 1), rmax);  // clamped: always a valid row
@@ -169,6 +187,7 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
   auto finish_x = [&](int buf, int t) {
     const int row0 = t * kRows;
     const TileOrigin o = tile_origin(row0, a.in_map.rows_per_seg);
+    const bool one_seg = o.rem0 + kRows <= a.in_map.rows_per_seg;
     const int rmax = a.rows - 1 - row0;
 #pragma unroll
     for (int j = 0; j < XP; ++j) {
@@ -177,9 +196,9 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
         const bool ok = r <= rmax;
         Vec16<T> out;
         if constexpr (SRC == 1) {
-          int f, rem;
-          locate(o, a.in_map.rows_per_seg, min(r, rmax), f, rem);
-          if (f != fcur) {
+          int f = o.seg0, rem;
+          if (!one_seg) locate(o, a.in_map.rows_per_seg, min(r, rmax), f, rem);
+          if (f != fcur) {  // one segment: the same for every lane, at most once per tile
             fcur = f;
             load_f<float, VEC>(a.scale + (int64_t)f * CIN + c0, sc);
             load_f<float, VEC>(a.shift + (int64_t)f * CIN + c0, sh);
@@ -229,9 +248,14 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
     int64_t orow[NK];
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
-      int seg, rem;
-      locate(oo, a.out_map.rows_per_seg, min(orow_l + RPI * k, a.rows - 1 - row0), seg, rem);
-      orow[k] = mapped(a.out_map, seg, rem) * a.ldy + co_w + ocol * OV;
+      const int rr = min(orow_l + RPI * k, a.rows - 1 - row0);
+      if (oo.rem0 + kRows <= a.out_map.rows_per_seg) {  // the tile lies inside one segment (uniform)
+        orow[k] = (mapped(a.out_map, oo.seg0, oo.rem0) + rr) * a.ldy + co_w + ocol * OV;
+      } else {
+        int seg, rem;
+        locate(oo, a.out_map.rows_per_seg, rr, seg, rem);
+        orow[k] = mapped(a.out_map, seg, rem) * a.ldy + co_w + ocol * OV;
+      }
     }
     f32x4 rres[kTileMax][NK];
     if constexpr (sizeof(OT) == 4) {
