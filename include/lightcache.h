@@ -207,12 +207,15 @@ lc_status lc_op_conv_in(lc_ctx* ctx, const void* x, void* h, int frames);
  * writes a cache entry). */
 lc_status lc_op_res_block(lc_ctx* ctx, int layer, const void* x, void* y, int frames);
 /* qkv[frames*H*W, 3C] (cfg dtype) = GroupNorm(x)[rows, C] [Wq;Wk;Wv]^T of LC_L_SATTN / LC_L_TATTN,
- * x float, statistics per frame. */
+ * x float, statistics per frame. For LC_L_SATTN the q third is stored multiplied by
+ * log2(e)/sqrt(head_dim), scaled before it is rounded: the form lc_op_spatial_attention takes with
+ * q_prescaled = 1 and the steps use between the two kernels. */
 lc_status lc_op_qkv(lc_ctx* ctx, int layer, const void* x, void* qkv, int frames);
 /* Spatial attention core: per frame and head, softmax(QK^T/sqrt(d))V over the H*W tokens of the
  * frame, for query tokens [q0, q1). qkv [frames*H*W, 3C] -> out [frames*H*W, C]; rows of other
- * queries are not written. */
-lc_status lc_op_spatial_attention(lc_ctx* ctx, const void* qkv, void* out, int frames, int q0, int q1);
+ * queries are not written. q_prescaled: 0 = the q third holds Q; 1 = it holds Q*log2(e)/sqrt(d). */
+lc_status lc_op_spatial_attention(lc_ctx* ctx, const void* qkv, void* out, int frames, int q0, int q1,
+                                  int q_prescaled);
 /* Temporal attention core: qkv [(B*F) * positions, 3C] (frame-major) -> out [(B*F)*positions, C];
  * per batch element, position and head attention over the F frames. */
 lc_status lc_op_temporal_attention(lc_ctx* ctx, const void* qkv, void* out, int positions);

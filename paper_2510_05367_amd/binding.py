@@ -92,7 +92,7 @@ PROTOTYPES = {
     "lc_op_conv_in": (_I, [_P, _P, _P, _I]),
     "lc_op_res_block": (_I, [_P, _I, _P, _P, _I]),
     "lc_op_qkv": (_I, [_P, _I, _P, _P, _I]),
-    "lc_op_spatial_attention": (_I, [_P, _P, _P, _I, _I, _I]),
+    "lc_op_spatial_attention": (_I, [_P, _P, _P, _I, _I, _I, _I]),
     "lc_op_temporal_attention": (_I, [_P, _P, _P, _I]),
     "lc_op_proj": (_I, [_P, _I, _P, _P, _P, _I64]),
     "lc_op_down_conv": (_I, [_P, _P, _P, _I]),
@@ -242,8 +242,8 @@ def lc_op_qkv(ctx, layer, x_ptr, qkv_ptr, frames) -> None:
     _check(lib().lc_op_qkv(ctx, layer, x_ptr, qkv_ptr, frames), ctx)
 
 
-def lc_op_spatial_attention(ctx, qkv_ptr, out_ptr, frames, q0, q1) -> None:
-    _check(lib().lc_op_spatial_attention(ctx, qkv_ptr, out_ptr, frames, q0, q1), ctx)
+def lc_op_spatial_attention(ctx, qkv_ptr, out_ptr, frames, q0, q1, q_prescaled=0) -> None:
+    _check(lib().lc_op_spatial_attention(ctx, qkv_ptr, out_ptr, frames, q0, q1, q_prescaled), ctx)
 
 
 def lc_op_temporal_attention(ctx, qkv_ptr, out_ptr, positions) -> None:

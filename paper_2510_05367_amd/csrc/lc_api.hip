@@ -397,12 +397,13 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       // kernel stages (no scattered transposition later)
       FusedDesc d = flinear_desc(c, w.sattn.wqkv, w.sattn.wqkv_f, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
       d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
+      d.q_scale = attn_q_scale(g.head_dim); d.q_cols = C;  // the softmax scale rides on q, applied before rounding
       s = linear(c, LC_K_QKV, d, nullptr);
       if (s != LC_OK) return s;
     }
     for (int q0 = 0; q0 < T; q0 += p.qc)
       LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
-                                                        g.head_dim, q0, std::min(q0 + p.qc, T)));
+                                                        g.head_dim, q0, std::min(q0 + p.qc, T), 1));
     {
       // the output projection closes the spatial block; its partial sums are those of the temporal
       // block's input, collected for all frames in partT
@@ -964,8 +965,9 @@ lc_status lc_op_qkv(lc_ctx* c, int layer, const void* x, void* qkv, int frames) 
   s = gn_scale_shift(c, x, frames, T, g.C, a.gn);
   if (s != LC_OK) return s;
   RowMap fm{0, T, T};
-  LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, flinear_desc(c, a.wqkv, a.wqkv_f, nullptr, g.C, 3 * g.C, (int64_t)frames * T, 1, fm,
-                                                          dense_map(), x, nullptr, qkv, 0)));
+  FusedDesc d = flinear_desc(c, a.wqkv, a.wqkv_f, nullptr, g.C, 3 * g.C, (int64_t)frames * T, 1, fm, dense_map(), x, nullptr, qkv, 0);
+  if (layer == LC_L_SATTN) { d.q_scale = attn_q_scale(g.head_dim); d.q_cols = g.C; }
+  LC_LAUNCH(c, LC_K_QKV, launch_linear_any(c->cs, d));
   return LC_OK;
 }
 
@@ -980,7 +982,7 @@ lc_status lc_op_proj(lc_ctx* c, int layer, const void* a_in, const void* res, vo
   return LC_OK;
 }
 
-lc_status lc_op_spatial_attention(lc_ctx* c, const void* qkv, void* out, int frames, int q0, int q1) {
+lc_status lc_op_spatial_attention(lc_ctx* c, const void* qkv, void* out, int frames, int q0, int q1, int q_prescaled) {
   lc_status s = op_checks(c, frames);
   if (s != LC_OK) return s;
   if (!qkv || !out) return fail(c, LC_ERR_ARG, "NULL tensor");
@@ -995,7 +997,7 @@ lc_status lc_op_spatial_attention(lc_ctx* c, const void* qkv, void* out, int fra
   LC_LAUNCH(c, LC_K_SATTN, launch_make_vt(c->cs, g.dtype, (const char*)qkv + (size_t)2 * g.C * es, 3 * g.C, vt, frames, T,
                                           Tp, g.C));
   LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * g.C, vt, Tp, out, frames, T, g.heads,
-                                                    g.head_dim, q0, q1));
+                                                    g.head_dim, q0, q1, q_prescaled != 0));
   return LC_OK;
 }
 

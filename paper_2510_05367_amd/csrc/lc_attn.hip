@@ -22,7 +22,9 @@ constexpr int kKeys = 64;  // keys per LDS stage
 // the permutation is an involution on the 4-key blocks (it swaps blocks 1 and 2)
 template <class T> __device__ __forceinline__ int vcol_inv(int c) { return vcol<T>(c); }
 
-template <class T, int D, int NQT>
+// PRE: the q columns already hold q * log2(e) / sqrt(d) (the q,k,v projection scales them before it
+// rounds them); `scale_log2e` is then 1.
+template <class T, int D, int NQT, bool PRE>
 __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restrict__ qk, int ldq,
                                                            const T* __restrict__ vt, int Tp, T* __restrict__ out,
                                                            int T_tok, int C, int q0, int q1, float scale_log2e) {
@@ -56,10 +58,21 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
   // rows 40..63 are padding), row D is set to ones, so O^T[D][q] accumulates the sum over keys of
   // exactly the (rounded) probabilities that multiply V, and is rescaled with the rest of O^T.
   constexpr bool ROWSUM = D % 32 != 0;
+  // Softmax exponents for free as well: when the padded contraction of K Q^T has a spare slot (d = 40
+  // contracts 48) and the queries come multiplied by scale * log2(e), slot D of every key is 1 and
+  // slot D of a query holds minus its running maximum (in the operand type, in log2 units). The
+  // MFMA then delivers  s * scale * log2(e) - m  directly and the probability is exp2 of that: no
+  // per-score multiply-add. Any rounding of m cancels, since the same m enters the probabilities,
+  // the denominator (ones row above) and the rescaling of O^T.
+  constexpr bool FOLD = PRE && sizeof(T) == 2 && DP > D && ROWSUM;
+  constexpr int KX = D / M::K, HX = (D % M::K) / M::LK, EX = (D % M::K) % M::LK;  // where slot D lives
   if (ROWSUM) {
     __syncthreads();
     for (int i = tid; i < 2 * kKeys; i += 256)
       reinterpret_cast<T*>(&v_lds[i / kKeys][D * VROW])[i % kKeys] = from_f32<T>(1.f);
+    if (FOLD)
+      for (int i = tid; i < 2 * kKeys; i += 256)
+        reinterpret_cast<T*>(&k_lds[i / kKeys][(i % kKeys) * KROW])[D] = from_f32<T>(1.f);
   }
 
   // ---- staging: K packet i = tid + 256 j of a stage is (key i / PK, packet i % PK); V^T packet i is
@@ -114,13 +127,18 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
     for (int kk = 0; kk < KSTEPS; ++kk) {
       const int e = kk * M::K + hh * M::LK;
       qf[t][kk] = (q < q1 && e < D) ? M::load(base + (int64_t)q * ld + e) : M::zero();
+      if constexpr (FOLD) {  // slots >= D must be zero: slot D will carry the running maximum
+#pragma unroll
+        for (int j = 0; j < M::LK; ++j)
+          if (e + j >= D) qf[t][kk][j] = (bf16_t)0.f;
+      }
     }
   }
   f32x16 o[NQT][DM];
   float m_run[NQT], l_run[NQT];  // running max (raw score units) and per-lane partial sum
 #pragma unroll
   for (int t = 0; t < NQT; ++t) {
-    m_run[t] = -INFINITY;
+    m_run[t] = FOLD ? 0.f : -INFINITY;  // FOLD: log2 units, as held in slot D of the query
     l_run[t] = 0.f;
 #pragma unroll
     for (int mt = 0; mt < DM; ++mt)
@@ -172,7 +190,26 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // a stage always holds at least one valid key: finite
       // rescale only when some query of the wavefront saw a new maximum (exp2(0) = 1 exactly, so the
       // result does not depend on whether the branch is taken for the other lanes)
-      if (__builtin_amdgcn_ballot_w64(mx > m_run[t]) != 0) {
+      if constexpr (FOLD) {
+        // sc already is s * scale * log2(e) - m_run: a new maximum shows as a positive score
+        const bool first = st_i == 0;  // the first stage sets the offset, which may be negative
+        if (first || __builtin_amdgcn_ballot_w64(mx > 0.f) != 0) {
+          float m_new = m_run[t] + (first ? mx : fmaxf(mx, 0.f));
+          m_new = static_cast<float>(static_cast<bf16_t>(m_new));  // as slot D will hold it
+          const float delta = m_new - m_run[t];
+          const float alpha = __builtin_amdgcn_exp2f(-delta);
+          m_run[t] = m_new;
+#pragma unroll
+          for (int mt = 0; mt < DM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[t][mt][r] *= alpha;
+#pragma unroll
+          for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc[t][kt][r] -= delta;
+          if (hh == HX) qf[t][KX][EX] = static_cast<bf16_t>(-m_new);
+        }
+      } else if (__builtin_amdgcn_ballot_w64(mx > m_run[t]) != 0) {
         const float m_new = fmaxf(m_run[t], mx);
         const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2e);
         m_run[t] = m_new;
@@ -190,7 +227,7 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
         float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          p[r] = __builtin_amdgcn_exp2f(fmaf(sc[t][kt][r], scale_log2e, -mc));
+          p[r] = FOLD ? __builtin_amdgcn_exp2f(sc[t][kt][r]) : __builtin_amdgcn_exp2f(fmaf(sc[t][kt][r], scale_log2e, -mc));
           if (!ROWSUM) ps += p[r];
         }
         if constexpr (sizeof(T) == 2) {
@@ -253,13 +290,13 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
   }
 }
 
-template <class T, int NQT>
+template <class T, int NQT, bool PRE>
 static hipError_t spatial_dispatch(hipStream_t s, const T* qk, int ldq, const T* vt, int Tp, T* out, int frames,
                                    int T_tok, int heads, int d, int q0, int q1) {
   const int C = heads * d;
-  const float sl = 1.4426950408889634f / sqrtf((float)d);
+  const float sl = PRE ? 1.f : 1.4426950408889634f / sqrtf((float)d);
   dim3 grid((q1 - q0 + 4 * NQT * 32 - 1) / (4 * NQT * 32), heads, frames);
-#define LC_GO(D) spatial_attn_kernel<T, D, NQT><<<grid, 256, 0, s>>>(qk, ldq, vt, Tp, out, T_tok, C, q0, q1, sl)
+#define LC_GO(D) spatial_attn_kernel<T, D, NQT, PRE><<<grid, 256, 0, s>>>(qk, ldq, vt, Tp, out, T_tok, C, q0, q1, sl)
   switch (d) {
     case 8: LC_GO(8); break;
     case 16: LC_GO(16); break;
@@ -273,14 +310,14 @@ static hipError_t spatial_dispatch(hipStream_t s, const T* qk, int ldq, const T*
 }
 
 hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
-                                    int frames, int T, int heads, int d, int q0, int q1) {
+                                    int frames, int T, int heads, int d, int q0, int q1, int q_prescaled) {
   if (frames <= 0 || q1 <= q0) return hipSuccess;
   if (Tp % kKeys != 0 || Tp < T) return hipErrorInvalidValue;
+#define LC_ARGS(TT) s, (const TT*)qk, ldq, (const TT*)vt, Tp, (TT*)out, frames, T, heads, d, q0, q1
   if (dt == kBF16)
-    return spatial_dispatch<bf16_t, 2>(s, (const bf16_t*)qk, ldq, (const bf16_t*)vt, Tp, (bf16_t*)out, frames, T, heads,
-                                       d, q0, q1);
-  return spatial_dispatch<float, 1>(s, (const float*)qk, ldq, (const float*)vt, Tp, (float*)out, frames, T, heads, d,
-                                    q0, q1);
+    return q_prescaled ? spatial_dispatch<bf16_t, 2, true>(LC_ARGS(bf16_t)) : spatial_dispatch<bf16_t, 2, false>(LC_ARGS(bf16_t));
+  return q_prescaled ? spatial_dispatch<float, 1, true>(LC_ARGS(float)) : spatial_dispatch<float, 1, false>(LC_ARGS(float));
+#undef LC_ARGS
 }
 
 // V^T in the layout the spatial kernel stages: vt[frame][c][vcol(t)] = v[frame*T + t][c] (v rows of stride ldv)

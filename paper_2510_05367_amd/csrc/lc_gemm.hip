@@ -51,6 +51,8 @@ struct GemmArgs {
   RowMap in_map, out_map;
   float* stat;          // conv, fp32 output: per-channel statistics of the output (see FusedDesc), or nullptr
   int stat_splits;
+  float q_scale;        // linear: output channels below q_cols are multiplied by this before rounding
+  int q_cols;
 };
 
 constexpr int FA = 3;  // weight fragments requested from LDS ahead of the MFMAs that use them
@@ -595,6 +597,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + (a.bias ? a.bias[co + e] : 0.f);
+          if (TAPS == 1 && co < a.q_cols) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] *= a.q_scale;
+          }
           if (TAPS == 1 && a.yt && co >= a.yt_from) {  // uniform over the workgroup
             const int64_t rr = row0 + p;
             const int64_t f = rr / a.yt_T;
@@ -646,6 +652,7 @@ static hipError_t run_gemm(hipStream_t s, const FusedDesc& d) {
   a.tiles_x = (d.W + 15) / 16; a.tiles_y = (d.H + 7) / 8;
   a.rows = d.rows; a.in_map = d.in_map; a.out_map = d.out_map;
   a.stat = d.stat; a.stat_splits = d.stat_splits;
+  a.q_scale = d.q_scale; a.q_cols = d.q_cols;
   dim3 grid;
   if (TAPS == 9) {
     if (d.frames <= 0) return hipSuccess;
@@ -691,6 +698,7 @@ hipError_t launch_fused(hipStream_t s, const FusedDesc& d) {
                d.yt_Tp % 64 || d.yt_Tp < d.yt_T || d.out_map.rows_per_seg < d.rows))
     return hipErrorInvalidValue;
   const int esz = (int)dtype_size(d.dt);
+  if (d.q_cols && (d.taps != 1 || d.q_cols % 4 || d.q_cols > d.Cout || d.bias || d.res)) return hipErrorInvalidValue;
   if (d.stat && (d.taps != 9 || d.planar_out || !(d.y_f32 || esz == 4) || d.stat_splits != conv_stat_splits(d.H, d.W)))
     return hipErrorInvalidValue;
   if (d.Cin % (kRow / esz) != 0) return hipErrorInvalidValue;

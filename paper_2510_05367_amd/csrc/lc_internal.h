@@ -1,6 +1,7 @@
 // Host-side declarations of the kernel launchers (one per kernel family). Every launcher only
 // enqueues on `s`; none allocates. Activations are channels-last [rows, channels].
 #pragma once
+#include <math.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -89,7 +90,12 @@ struct FusedDesc {
   // stat_rps and stat_off must be multiples of 32.
   float* stat;
   int stat_splits, stat_rps, stat_off;
+  // taps == 1, optional: output channels [0, q_cols) are multiplied by q_scale before they are rounded
+  // and stored (the softmax scale of spatial attention folded into q). q_cols == 0: off; a multiple of 32.
+  float q_scale;
+  int q_cols;
 };
+inline float attn_q_scale(int head_dim) { return 1.4426950408889634f / sqrtf((float)head_dim); }
 // splits per frame of the statistics a 3x3 launch writes
 inline int conv_stat_splits(int H, int W) { return 4 * ((W + 15) / 16) * ((H + 7) / 8); }
 hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
@@ -103,10 +109,11 @@ inline hipError_t launch_linear_any(hipStream_t s, const FusedDesc& d) {
 // ---- attention cores -----------------------------------------------------------------------
 // Spatial attention core. qk: rows [frames*T] of stride ldq with q at column 0 and k at column C;
 // vt: V transposed [frames][C][Tp], token t at column (t & ~63) + vcol(t & 63), Tp a multiple of 64;
-// out [frames*T][C]; queries [q0,q1) of every frame.
+// out [frames*T][C]; queries [q0,q1) of every frame. q_prescaled: the q columns hold q * log2(e) / sqrt(d)
+// (FusedDesc::q_scale of the projection that wrote them) instead of q.
 inline int attn_tp(int T) { return (T + 63) / 64 * 64; }
 hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
-                                    int frames, int T, int heads, int d, int q0, int q1);
+                                    int frames, int T, int heads, int d, int q0, int q1, int q_prescaled);
 // vt from plain value rows v[frames*T][C] of stride ldv
 hipError_t launch_make_vt(hipStream_t s, int dt, const void* v, int ldv, void* vt, int frames, int T, int Tp, int C);
 // qkv [(B*F)*P][3C] frame-major -> out same rows x C; attention over the F frames.

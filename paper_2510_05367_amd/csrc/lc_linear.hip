@@ -39,6 +39,8 @@ struct LinArgs {
   int im_H, im_W, im_Cl;  // SRC == 2: x is planar [frames][im_Cl][im_H][im_W]
   float* stat;            // per-channel statistics of the output (see FusedDesc), or nullptr
   int stat_splits, stat_rps, stat_off;
+  float q_scale;          // output channels below q_cols are multiplied by this before rounding
+  int q_cols;
   RowMap in_map, out_map;
 };
 
@@ -314,16 +316,17 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
         }
         continue;
       }
+      const float osc = co < a.q_cols ? a.q_scale : 1.f;  // uniform per tile
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         unsigned char* p = t_lds + lp * TS + (g * 8 + hh * 4) * (int)sizeof(OT);
         if constexpr (sizeof(OT) == 2) {
           bf16x4 ov;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16_t>(acc[i][g * 4 + e]);
+          for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16_t>(acc[i][g * 4 + e] * osc);
           *reinterpret_cast<bf16x4*>(p) = ov;
         } else {
-          *reinterpret_cast<f32x4*>(p) = f32x4{acc[i][g * 4], acc[i][g * 4 + 1], acc[i][g * 4 + 2], acc[i][g * 4 + 3]};
+          *reinterpret_cast<f32x4*>(p) = f32x4{acc[i][g * 4] * osc, acc[i][g * 4 + 1] * osc, acc[i][g * 4 + 2] * osc, acc[i][g * 4 + 3] * osc};
         }
       }
       // the patch is private to this wavefront, whose LDS operations complete in order
@@ -453,6 +456,7 @@ static hipError_t run_lin(hipStream_t s, const FusedDesc& d) {
   a.yt_from = d.yt_from; a.yt_T = d.yt_T; a.yt_Tp = d.yt_Tp; a.rows = (int)d.rows; a.in_map = d.in_map; a.out_map = d.out_map;
   a.im_H = d.H; a.im_W = d.W; a.im_Cl = d.Cs;
   a.stat = d.stat; a.stat_splits = d.stat_splits; a.stat_rps = d.stat_rps; a.stat_off = d.stat_off;
+  a.q_scale = d.q_scale; a.q_cols = d.q_cols;
   // one workgroup per compute unit (its registers hold the weights), each with a contiguous range of tiles
   const int ntiles = ((int)d.rows + kRows - 1) / kRows;
   const int gx_max = 256 / cols > 1 ? 256 / cols : 1;
@@ -471,6 +475,8 @@ hipError_t launch_linear(hipStream_t s, const FusedDesc& d) {
   if (!d.w_frag || d.Cout % 32 != 0 || d.Cout_store != d.Cout || d.rows > (int64_t)1 << 30) return hipErrorNotSupported;
   const bool y32 = d.y_f32 || d.dt != kBF16;
   if (d.res && !y32) return hipErrorNotSupported;
+  if (d.q_cols && (d.q_cols % 32 || d.q_cols > d.Cout || d.bias || d.res || (d.yt && d.q_cols > d.yt_from)))
+    return hipErrorInvalidValue;
   if (d.stat && (!y32 || d.yt || d.stat_rps <= 0 || d.stat_rps % 32 || d.stat_off % 32 || d.rows % d.stat_rps ||
                  (d.stat_off + d.stat_rps) / 32 > d.stat_splits))
     return hipErrorInvalidValue;

@@ -157,14 +157,18 @@ def test_spatial_attention_all_frames_sampled_queries(big):
     N, T, C = cfg.N, cfg.T, cfg.C
     qkv = synth.make_activation((N * T, 3 * C), 51, cfg.dtype)
     qkv[:, :2 * C] *= np.float32(1.5)
+    # as in the steps: the q third holds q * log2(e)/sqrt(d); its stored (rounded) value defines q
+    qs = np.float32(np.log2(np.e) / np.sqrt(cfg.head_dim))
+    qkv[:, :C] *= qs
     if cfg.dtype == "bf16":
         qkv = synth.round_to_bf16(qkv)
     qd = dev(stage, qkv)
+    qkv[:, :C] /= qs  # (float32 division of the stored values: close enough to exact for the tolerance)
     out = stage.empty(N * T, C)
     # query windows as the step cuts them: the stage's token chunk (whole frame if 0)
     tc = cfg.token_chunk if cfg.token_chunk else T
     for q0 in range(0, T, tc):
-        lcb.lc_op_spatial_attention(stage.ctx, qd.data_ptr(), out.data_ptr(), N, q0, min(T, q0 + tc))
+        lcb.lc_op_spatial_attention(stage.ctx, qd.data_ptr(), out.data_ptr(), N, q0, min(T, q0 + tc), 1)
     stage.sync()
     rng = np.random.default_rng(7)
     a = qkv.reshape(N, T, 3 * C)
@@ -210,7 +214,8 @@ def test_qkv_and_proj_all_frames(big):
     for f in sample_frames(cfg, 5):
         g = planar_to_rows(lo.group_norm(x[f:f + 1].astype(np.float64), w["sattn.gn_g"], w["sattn.gn_b"], cfg.groups,
                                          cfg.gn_eps))
-        ref = np.concatenate([g @ w["sattn.wq"].T, g @ w["sattn.wk"].T, g @ w["sattn.wv"].T], axis=1)
+        qs = np.log2(np.e) / np.sqrt(cfg.head_dim)  # the spatial q is stored with the softmax scale applied
+        ref = np.concatenate([(g @ w["sattn.wq"].T) * qs, g @ w["sattn.wk"].T, g @ w["sattn.wv"].T], axis=1)
         check(f"qkv frame {f}", host(qkv[f * T:(f + 1) * T]), ref, cfg.dtype)
         sl = slice(f * T, (f + 1) * T)
         ref = xr[sl].astype(np.float64) + a_in[sl].astype(np.float64) @ w["sattn.wo"].T + w["sattn.bo"]

@@ -96,7 +96,9 @@ def test_qkv_and_proj(st, layer, pre):
     lcb.lc_op_qkv(stage.ctx, layer, xd.data_ptr(), qkv.data_ptr(), N)
     stage.sync()
     g = planar_to_rows(lo.group_norm(x.astype(np.float64), w[pre + ".gn_g"], w[pre + ".gn_b"], cfg.groups, cfg.gn_eps))
-    ref = np.concatenate([g @ w[pre + ".wq"].T, g @ w[pre + ".wk"].T, g @ w[pre + ".wv"].T], axis=1)
+    # the spatial block's q is stored multiplied by the softmax scale in base 2 (applied before rounding)
+    qs = np.log2(np.e) / np.sqrt(cfg.head_dim) if pre == "sattn" else 1.0
+    ref = np.concatenate([(g @ w[pre + ".wq"].T) * qs, g @ w[pre + ".wk"].T, g @ w[pre + ".wv"].T], axis=1)
     check(f"qkv[{pre}]", host(qkv), ref, cfg.dtype)
     rows = 333  # not a multiple of the 128-row tile
     a_in = act(cfg, (rows, C), 43)
@@ -122,27 +124,36 @@ def oracle_attention_core(q, k, v, heads):
     return out
 
 
+@pytest.mark.parametrize("prescaled", [0, 1])
 @pytest.mark.parametrize("logit_scale", [1.0, 6.0])
-def test_spatial_attention_core(st, logit_scale):
+def test_spatial_attention_core(st, logit_scale, prescaled):
     stage, cfg, w = st
     N, T, C = cfg.N, cfg.T, cfg.C
     qkv = act(cfg, (N * T, 3 * C), 51)
     qkv[:, :2 * C] *= np.float32(np.sqrt(logit_scale))  # logit std ~ logit_scale * sqrt(d)/sqrt(d)
     if cfg.dtype == "bf16":
         qkv = synth.round_to_bf16(qkv)
+    # prescaled: the kernel is handed q' = q * log2(e)/sqrt(d); whatever q' holds (after rounding to
+    # the storage type) defines the queries the oracle attends with, q = q' / that factor
+    qs = np.log2(np.e) / np.sqrt(cfg.head_dim)
+    a = qkv.astype(np.float64).reshape(N, T, 3 * C)
+    if prescaled:
+        qp = (qkv[:, :C].astype(np.float64) * qs).astype(np.float32)
+        qkv[:, :C] = synth.round_to_bf16(qp) if cfg.dtype == "bf16" else qp
+        a = qkv.astype(np.float64).reshape(N, T, 3 * C)
+        a[..., :C] /= qs
     qd = dev(stage, qkv)
     out = stage.empty(N * T, C)
     out.zero_()
     q0, q1 = 0, T
-    lcb.lc_op_spatial_attention(stage.ctx, qd.data_ptr(), out.data_ptr(), N, q0, q1)
+    lcb.lc_op_spatial_attention(stage.ctx, qd.data_ptr(), out.data_ptr(), N, q0, q1, prescaled)
     stage.sync()
-    a = qkv.astype(np.float64).reshape(N, T, 3 * C)
     ref = oracle_attention_core(a[..., :C], a[..., C:2 * C], a[..., 2 * C:], cfg.heads).reshape(N * T, C)
-    check(f"spatial core x{logit_scale}", host(out), ref, cfg.dtype)
+    check(f"spatial core x{logit_scale} prescaled={prescaled}", host(out), ref, cfg.dtype)
     # a ragged query window must only write its own rows and reproduce them bit for bit
     out2 = stage.empty(N * T, C)
     out2.fill_(7.0)
-    lcb.lc_op_spatial_attention(stage.ctx, qd.data_ptr(), out2.data_ptr(), N, 37, 101)
+    lcb.lc_op_spatial_attention(stage.ctx, qd.data_ptr(), out2.data_ptr(), N, 37, 101, prescaled)
     stage.sync()
     o1 = out.view(N, T, C)
     o2 = out2.view(N, T, C)
