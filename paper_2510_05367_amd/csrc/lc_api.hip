@@ -124,6 +124,9 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   if (token_chunk > 0) p.tc = (int)std::min<int64_t>(token_chunk, T);
   else if (p.fc < N) p.tc = (int)(((int64_t)p.fc * T + N - 1) / N);
   else p.tc = (int)T;
+  // position chunks of the temporal block in whole 32-row tiles where the frame allows it (the
+  // weight-stationary linear kernel works on such tiles)
+  if (T % 32 == 0) p.tc = (int)std::min<int64_t>(T, ((int64_t)p.tc + 31) / 32 * 32);
   p.qc = token_chunk > 0 ? (int)std::min<int64_t>(token_chunk, T) : (int)T;
   size_t off = 0;
   p.off_h = off; off += align_up((size_t)(N * T * g.C) * 4);  // the skip / residual stream is fp32
@@ -222,9 +225,12 @@ lc_status gn_scale_shift(lc_ctx* c, const void* x, int frames, int rows_per_fram
 
 // A linear layer through the weight-stationary kernel, which can also write the statistics of its
 // output (d.stat); shapes it does not cover go to the streaming kernel, which cannot. *wrote tells.
-lc_status linear(lc_ctx* c, int kind, FusedDesc d, bool* wrote_stats) {
-  hipError_t e;
-  { Prof pr_(c, kind); e = launch_linear(c->cs, d); }
+// The choice between the two must not depend on how the stage is chunked (a chunked step reproduces
+// the unchunked one bit for bit, and the two kernels round differently): `tiled` says that the stage's
+// geometry suits the weight-stationary kernel for every chunking (frames of a multiple of 32 positions).
+lc_status linear(lc_ctx* c, int kind, FusedDesc d, bool* wrote_stats, bool tiled) {
+  hipError_t e = hipErrorNotSupported;
+  if (tiled) { Prof pr_(c, kind); e = launch_linear(c->cs, d); }
   if (wrote_stats) *wrote_stats = e == hipSuccess && d.stat != nullptr;
   if (e == hipErrorNotSupported) {
     d.stat = nullptr;
@@ -272,7 +278,7 @@ lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat
   const lc_config& g = c->cfg;
   const int T = g.H * g.W;
   if (wrote_stats) *wrote_stats = false;
-  if (c->pw.cin_wf) {
+  if (c->pw.cin_wf && T % 32 == 0) {  // (the same kernel for every chunking: see linear())
     FusedDesc d;
     memset(&d, 0, sizeof d);
     d.dt = g.dtype; d.y_f32 = 1; d.taps = 1; d.src = 2; d.Cin = 64; d.Cs = g.C_lat; d.Cout = g.C; d.Cout_store = g.C;
@@ -361,7 +367,8 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
   const Packed& w = c->pw;
 
   // ---- shallow down branch D_m, per frame chunk
-  bool tstat = T % 32 == 0;  // the 32-row tiles of the projection kernels stay inside a frame
+  const bool tiled = T % 32 == 0;  // whole 32-row tiles in every frame and position chunk: see linear()
+  bool tstat = tiled;              // the 32-row tiles of the projection kernels stay inside a frame
   for (int n0 = 0; n0 < N; n0 += p.fc) {
     const int nf = std::min(p.fc, N - n0);
     const int64_t pc = (int64_t)nf * T;
@@ -398,7 +405,7 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       FusedDesc d = flinear_desc(c, w.sattn.wqkv, w.sattn.wqkv_f, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
       d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
       d.q_scale = attn_q_scale(g.head_dim); d.q_cols = C;  // the softmax scale rides on q, applied before rounding
-      s = linear(c, LC_K_QKV, d, nullptr);
+      s = linear(c, LC_K_QKV, d, nullptr, tiled);
       if (s != LC_OK) return s;
     }
     for (int q0 = 0; q0 < T; q0 += p.qc)
@@ -410,7 +417,7 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       FusedDesc d = flinear_desc(c, w.sattn.wo, w.sattn.wo_f, w.sattn.bo, C, C, pc, 0, dense_map(), dense_map(), ao, hc, hc, 1);
       if (tstat) { d.stat = partT(c) + (size_t)n0 * (T / 32) * C * 2; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
       bool wrote = false;
-      s = linear(c, LC_K_PROJ, d, &wrote);
+      s = linear(c, LC_K_PROJ, d, &wrote, tiled);
       if (s != LC_OK) return s;
       tstat = tstat && wrote;
     }
@@ -428,14 +435,14 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       char* qkv = ws;
       char* ao = ws + align_up((size_t)rows * 3 * C * es);
       s = linear(c, LC_K_QKV, flinear_desc(c, w.tattn.wqkv, w.tattn.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(), h, nullptr, qkv, 0),
-                 nullptr);
+                 nullptr, tiled);
       if (s != LC_OK) return s;
       LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
       // this projection finishes the skip feature: its partial sums, for the up block, go to partU
       FusedDesc d = flinear_desc(c, w.tattn.wo, w.tattn.wo_f, w.tattn.bo, C, C, rows, 0, dense_map(), m, ao, h, h, 1);
       if (ustat) { d.stat = partU(c); d.stat_splits = T / 32; d.stat_rps = np; d.stat_off = p0; }
       bool wrote = false;
-      s = linear(c, LC_K_PROJ, d, &wrote);
+      s = linear(c, LC_K_PROJ, d, &wrote, tiled);
       if (s != LC_OK) return s;
       ustat = ustat && wrote;
     }

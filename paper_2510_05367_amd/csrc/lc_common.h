@@ -187,4 +187,19 @@ struct RowMap {
   }
 };
 
+// s_waitcnt immediate: at most `vm` vector-memory operations and no LDS operation outstanding
+constexpr int waitcnt_imm(int vm) { return (vm & 15) | (7 << 4) | (0 << 8) | ((vm >> 4) << 14); }
+// Workgroup barrier that orders LDS traffic only and leaves the youngest `VM` vector-memory
+// operations in flight (63: all of them). __syncthreads() would wait for every outstanding global
+// load and store: it cannot know that LDS-direct loads still on their way write a tile nobody reads
+// before a later barrier, or that nobody in the workgroup reads back what the stores write.
+template <int VM>
+__device__ __forceinline__ void barrier_keep() {
+  static_assert(VM >= 0 && VM < 64, "vmcnt has six bits");
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(VM));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 }  // namespace lc

@@ -66,11 +66,6 @@ constexpr int gemm_lds_bytes() {
   return TAPS == 9 ? kWBuf * BCO * kRow + 2 * XROWS * kLds : 2 * (BCO + XROWS) * kLds;
 }
 
-// s_waitcnt immediate: at most `vm` vector-memory operations and no LDS operation outstanding
-constexpr int waitcnt_imm(int vm) { return (vm & 15) | (7 << 4) | (0 << 8) | ((vm >> 4) << 14); }
-// Workgroup barrier that leaves the youngest `VM` vector-memory loads in flight. __syncthreads()
-// would wait for all of them: it cannot know that the outstanding LDS-direct loads write a tile
-// nobody reads before a later barrier.
 // vector-memory loads issued in tap t of a conv slab body (see the main loop): scale/shift at tap 0 and a
 // halo packet at taps < xr if a next slab follows (`more`), then the weights of step s + ah if there is one.
 // t < 0 is tap 8 of the slab before, which was not the last one: weights only.
@@ -84,15 +79,6 @@ constexpr int conv_tap_keep(int tap, bool more, int n_aff, int n_pkt, int xr, in
   for (int j = 0; j < ah - 1; ++j) n += conv_tap_loads(tap - j, more, n_aff, n_pkt, xr, wp, ah);
   return n;
 }
-template <int VM>
-__device__ __forceinline__ void barrier_keep() {
-  static_assert(VM >= 0 && VM < 64, "vmcnt has six bits");
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(VM));
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-}
-
 }  // namespace
 
 // SRC: 0 plain operand-type rows, 1 fp32 rows with scale/shift, 2 the same + SiLU, 3 concat (+ SiLU)
