@@ -103,7 +103,8 @@ size_t lc_cache_entry_bytes(const lc_config* cfg);
 
 /* Footprint model: arena bytes lc_set_workspace() needs for the given chunk setting (persistent
  * skip feature + dev_slots cache entries + chunk-sized scratch). frame_chunk / token_chunk as in
- * lc_set_chunk(). Returns 0 if cfg is invalid or a chunk is negative. */
+ * lc_set_chunk(); with a chunk set, the chunk scratch is counted twice (see lc_set_lanes()).
+ * Returns 0 if cfg is invalid or a chunk is negative. */
 size_t lc_workspace_bytes(const lc_config* cfg, int frame_chunk, int token_chunk);
 
 /* Message of the most recent error on this ctx (ctx == NULL: of the calling thread's last
@@ -138,6 +139,17 @@ lc_status lc_set_workspace(lc_ctx* ctx, void* arena, size_t bytes);
  * (as many rows as a frame chunk). Chunking never changes results (each output is reduced in the
  * same order). LC_ERR_NOMEM if a workspace is set and is too small for the new setting. */
 lc_status lc_set_chunk(lc_ctx* ctx, int frame_chunk, int token_chunk);
+
+/* Chunk overlap. The chunks of a step ([CHK]) depend on each other only where the method joins
+ * them (before temporal attention, before the up branch, at the end), so a chunked step issues
+ * alternate chunks on two streams - the compute stream and one of the library's own, forked from
+ * and joined back into the compute stream inside every step, so the caller still orders work
+ * against the compute stream alone - each with its own chunk scratch (lc_workspace_bytes counts the
+ * second copy whenever a chunk is set). lanes = 1 keeps everything on the compute stream; 2 is the
+ * default. Results are identical bit for bit. While per-kernel profiling is on (lc_set_profiling)
+ * steps run on one lane, so that a timed kernel has the device to itself. LC_ERR_ARG unless
+ * lanes is 1 or 2. */
+lc_status lc_set_lanes(lc_ctx* ctx, int lanes);
 
 /* Normal step ([AS]: the steps t = 0, n, 2n, ...): shallow down branch, deep stand-in, shallow
  * up branch on Concat(skip, deep) ([FC]); the deep feature is left in device slot dev_slot.

@@ -76,6 +76,7 @@ PROTOTYPES = {
     "lc_load_weights": (_I, [_P, C.POINTER(lc_weights)]),
     "lc_set_workspace": (_I, [_P, _P, C.c_size_t]),
     "lc_set_chunk": (_I, [_P, _I, _I]),
+    "lc_set_lanes": (_I, [_P, _I]),
     "lc_full_step": (_I, [_P, _P, _P, _I]),
     "lc_cached_step": (_I, [_P, _P, _P, _I]),
     "lc_swap_out": (_I, [_P, _I, _I]),
@@ -168,6 +169,10 @@ def lc_set_workspace(ctx, arena_ptr: int, nbytes: int) -> None:
 
 def lc_set_chunk(ctx, frame_chunk: int, token_chunk: int) -> None:
     _check(lib().lc_set_chunk(ctx, frame_chunk, token_chunk), ctx)
+
+
+def lc_set_lanes(ctx, lanes: int) -> None:
+    _check(lib().lc_set_lanes(ctx, lanes), ctx)
 
 
 def lc_full_step(ctx, x_ptr: int, eps_ptr: int, dev_slot: int) -> None:
@@ -334,6 +339,9 @@ class Stage:
     def set_chunk(self, frame_chunk: int, token_chunk: int) -> None:
         self._ensure_arena(frame_chunk, token_chunk)
         lc_set_chunk(self.ctx, frame_chunk, token_chunk)
+
+    def set_lanes(self, lanes: int) -> None:
+        lc_set_lanes(self.ctx, lanes)
 
     def full_step(self, x, eps, dev_slot: int = 0):
         lc_full_step(self.ctx, x.data_ptr(), eps.data_ptr(), dev_slot)

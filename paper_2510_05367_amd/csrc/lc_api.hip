@@ -27,6 +27,7 @@ struct Plan {
   int fc, tc, qc;  // effective frame chunk, temporal position chunk, spatial query chunk
   size_t off_h, off_slots, slot_bytes, off_partH, off_partT, off_partU, off_partD, partD_bytes, off_scale, off_shift, off_ws,
       ws_bytes, total;
+  size_t lane_off, lane_stride;  // [lane_off, lane_off + lane_stride): the scratch one lane works in (see use_lane)
 };
 
 struct GnW { float *gamma, *beta; };
@@ -47,7 +48,12 @@ struct EvPair { hipEvent_t a, b; int kind; int64_t bytes; };
 
 struct lc_ctx {
   lc_config cfg;
-  hipStream_t cs, ss;
+  hipStream_t cs, ss;            // cs: the stream kernels are issued on right now (see use_lane)
+  hipStream_t cs_main, cs_aux;   // the caller's compute stream; the library's own second one
+  hipEvent_t ev_fork, ev_join;
+  int lanes;                     // 1 or 2: streams a chunked step spreads its chunks over
+  int lane;                      // the lane in use: selects cs and the per-lane scratch
+  bool forked;
   int device;
   int frame_chunk, token_chunk;
   Plan plan;
@@ -142,11 +148,14 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   size_t sp = std::max((size_t)stat_splits((int)T), (size_t)conv_stat_splits(g.H, g.W));
   if (T % 32 == 0) sp = std::max(sp, (size_t)(T / 32));
   const size_t ph = std::max(sp * g.C, (size_t)stat_splits((int)(T / 4)) * g.C_deep);
-  p.off_partH = off; off += align_up((size_t)N * ph * 2 * sizeof(float));
   p.off_partT = off; off += align_up((size_t)N * sp * g.C * 2 * sizeof(float));
   p.off_partU = off; off += align_up((size_t)N * sp * g.C * 2 * sizeof(float));
   p.partD_bytes = align_up((size_t)N * stat_splits((int)(T / 4)) * g.C_deep * 2 * sizeof(float));
   p.off_partD = off; off += p.partD_bytes * (g.dev_slots + 1);
+  // what a chunk works in - partH, scale / shift, the chunk scratch - exists once per lane: a chunked
+  // step runs alternate chunks on two streams
+  p.lane_off = off;
+  p.off_partH = off; off += align_up((size_t)N * ph * 2 * sizeof(float));
   p.off_scale = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
   p.off_shift = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
   const int64_t pc = (int64_t)p.fc * T;   // pixels of a frame chunk
@@ -159,6 +168,8 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   wsb += 4 * kAlign;
   p.ws_bytes = align_up(wsb) + kAlign;
   p.off_ws = off; off += p.ws_bytes;
+  p.lane_stride = off - p.lane_off;
+  if (p.fc < N || p.tc < T) off += p.lane_stride;  // the second lane's copy
   p.total = off;
   return p;
 }
@@ -186,16 +197,44 @@ struct Prof {
 
 inline char* slot_ptr(lc_ctx* c, int s) { return c->arena + c->plan.off_slots + c->plan.slot_bytes * s; }
 inline char* h_ptr(lc_ctx* c) { return c->arena + c->plan.off_h; }
-inline float* partH(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partH); }
+inline size_t lane_base(lc_ctx* c) { return c->lane * c->plan.lane_stride; }
+inline float* partH(lc_ctx* c) { return (float*)(c->arena + lane_base(c) + c->plan.off_partH); }
 inline float* partT(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partT); }
 inline float* partU(lc_ctx* c) { return (float*)(c->arena + c->plan.off_partU); }
 // statistics of the deep feature in device slot `s`; s == dev_slots: scratch of the single-operator calls
 inline float* partD(lc_ctx* c, int s) { return (float*)(c->arena + c->plan.off_partD + c->plan.partD_bytes * s); }
-inline float* scale_p(lc_ctx* c) { return (float*)(c->arena + c->plan.off_scale); }
-inline float* shift_p(lc_ctx* c) { return (float*)(c->arena + c->plan.off_shift); }
-inline char* ws_ptr(lc_ctx* c) { return c->arena + c->plan.off_ws; }
+inline float* scale_p(lc_ctx* c) { return (float*)(c->arena + lane_base(c) + c->plan.off_scale); }
+inline float* shift_p(lc_ctx* c) { return (float*)(c->arena + lane_base(c) + c->plan.off_shift); }
+inline char* ws_ptr(lc_ctx* c) { return c->arena + lane_base(c) + c->plan.off_ws; }
 
 RowMap dense_map() { return RowMap{0, 0, 1 << 30}; }
+
+// Two lanes. The chunks of a step depend on each other only at three points (before the temporal
+// block, before the up branch, at the end), and nearly every kernel wants the whole device for a short
+// time: run back to back on one stream, each pays its ramp-up and its tail, and the small ones
+// (statistics, finalisation) leave most of the device idle. So alternate chunks go to two streams, each
+// with its own scratch, and the device fills one chunk's gaps with the other's kernels. The results do
+// not depend on it: the same kernels see the same data.
+void use_lane(lc_ctx* c, int l) {
+  c->lane = l;
+  c->cs = l ? c->cs_aux : c->cs_main;
+}
+// lanes for a loop of n chunks; with per-kernel timing on, one (a bracketed kernel must run alone)
+int loop_lanes(lc_ctx* c, int n) { return (c->lanes > 1 && n > 1 && c->prof_mask == 0 && c->plan.total > c->plan.lane_off + c->plan.lane_stride) ? 2 : 1; }
+lc_status fork_lanes(lc_ctx* c) {
+  LC_HIP(c, hipEventRecord(c->ev_fork, c->cs_main));
+  LC_HIP(c, hipStreamWaitEvent(c->cs_aux, c->ev_fork, 0));
+  c->forked = true;
+  return LC_OK;
+}
+lc_status join_lanes(lc_ctx* c) {
+  use_lane(c, 0);
+  if (!c->forked) return LC_OK;
+  c->forked = false;
+  LC_HIP(c, hipEventRecord(c->ev_join, c->cs_aux));
+  LC_HIP(c, hipStreamWaitEvent(c->cs_main, c->ev_join, 0));
+  return LC_OK;
+}
 
 // Per-channel partial sums of the frames at hand, [frame][splits][C][2]; part == nullptr: none yet.
 struct StatRef {
@@ -357,19 +396,22 @@ lc_status conv_out(lc_ctx* c, const void* u, void* eps, int frames, StatRef u_st
   return LC_OK;
 }
 
-lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
+lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
   const lc_config& g = c->cfg;
   const Plan& p = c->plan;
   const int N = g.B * g.F, T = g.H * g.W, C = g.C, Cd = g.C_deep;
   const size_t es = dtype_size(g.dtype);
   char* h = h_ptr(c);
-  char* ws = ws_ptr(c);
   const Packed& w = c->pw;
+  const int frame_lanes = loop_lanes(c, (N + p.fc - 1) / p.fc);
 
   // ---- shallow down branch D_m, per frame chunk
   const bool tiled = T % 32 == 0;  // whole 32-row tiles in every frame and position chunk: see linear()
   bool tstat = tiled;              // the 32-row tiles of the projection kernels stay inside a frame
-  for (int n0 = 0; n0 < N; n0 += p.fc) {
+  if (frame_lanes == 2) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
+  for (int n0 = 0, ci = 0; n0 < N; n0 += p.fc, ++ci) {
+    use_lane(c, frame_lanes == 2 ? ci & 1 : 0);
+    char* ws = ws_ptr(c);
     const int nf = std::min(p.fc, N - n0);
     const int64_t pc = (int64_t)nf * T;
     char* hc = h + (size_t)n0 * T * C * 4;
@@ -422,20 +464,30 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       tstat = tstat && wrote;
     }
   }
+  {
+    lc_status s = join_lanes(c);
+    if (s != LC_OK) return s;
+  }
 
   // ---- temporal block: per-frame statistics over whole frames, then per position chunk
   bool ustat = T % 32 == 0 && p.tc % 32 == 0;  // the 32-row tiles of a position chunk stay inside a frame and a split
   {
     lc_status s = gn_scale_shift(c, h, N, T, C, w.tattn.gn, tstat ? StatRef{partT(c), T / 32} : StatRef{nullptr, 0});
     if (s != LC_OK) return s;
-    for (int p0 = 0; p0 < T; p0 += p.tc) {
+    const float *sc0 = scale_p(c), *sh0 = shift_p(c);  // of all frames: every position chunk reads them, on either lane
+    const int pos_lanes = loop_lanes(c, (T + p.tc - 1) / p.tc);
+    if (pos_lanes == 2 && (s = fork_lanes(c)) != LC_OK) return s;
+    for (int p0 = 0, ci = 0; p0 < T; p0 += p.tc, ++ci) {
+      use_lane(c, pos_lanes == 2 ? ci & 1 : 0);
+      char* ws = ws_ptr(c);
       const int np = std::min(p.tc, T - p0);
       const int64_t rows = (int64_t)N * np;
       RowMap m{p0, T, np};  // dense row r = (frame r / np, position p0 + r % np)
       char* qkv = ws;
       char* ao = ws + align_up((size_t)rows * 3 * C * es);
-      s = linear(c, LC_K_QKV, flinear_desc(c, w.tattn.wqkv, w.tattn.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(), h, nullptr, qkv, 0),
-                 nullptr, tiled);
+      FusedDesc dq = flinear_desc(c, w.tattn.wqkv, w.tattn.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(), h, nullptr, qkv, 0);
+      dq.scale = sc0; dq.shift = sh0;
+      s = linear(c, LC_K_QKV, dq, nullptr, tiled);
       if (s != LC_OK) return s;
       LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
       // this projection finishes the skip feature: its partial sums, for the up block, go to partU
@@ -446,6 +498,7 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
       if (s != LC_OK) return s;
       ustat = ustat && wrote;
     }
+    if ((s = join_lanes(c)) != LC_OK) return s;
   }
 
   char* deep = slot_ptr(c, slot);
@@ -454,13 +507,19 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_rd_done[slot], 0));
     LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
     c->in_pending[slot] = 0;
-    for (int n0 = 0; n0 < N; n0 += p.fc) {
+    if (frame_lanes == 2) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
+    for (int n0 = 0, ci = 0; n0 < N; n0 += p.fc, ++ci) {
+      use_lane(c, frame_lanes == 2 ? ci & 1 : 0);
       const int nf = std::min(p.fc, N - n0);
       char* hc = h + (size_t)n0 * T * C * 4;
-      char* d0 = ws;  // fp32
+      char* d0 = ws_ptr(c);  // fp32
       char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
       LC_LAUNCH(c, LC_K_DEEP, launch_conv(c->cs, down_desc(g, w.down, nf, hc, d0)));
       lc_status s = res_block(c, w.dres_gn, w.dres, Cd, nf, g.H / 2, g.W / 2, d0, dc, 0, LC_K_DEEP);
+      if (s != LC_OK) return s;
+    }
+    {
+      lc_status s = join_lanes(c);
       if (s != LC_OK) return s;
     }
     LC_HIP(c, hipEventRecord(c->ev_produced[slot], c->cs));
@@ -478,11 +537,13 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
   }
 
   // ---- shallow up branch U_m on Concat(skip, up2(deep)), per frame chunk
-  for (int n0 = 0; n0 < N; n0 += p.fc) {
+  if (frame_lanes == 2) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
+  for (int n0 = 0, ci = 0; n0 < N; n0 += p.fc, ++ci) {
+    use_lane(c, frame_lanes == 2 ? ci & 1 : 0);
     const int nf = std::min(p.fc, N - n0);
     char* hc = h + (size_t)n0 * T * C * 4;
     char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
-    char* u = ws;  // fp32
+    char* u = ws_ptr(c);  // fp32
     StatRef ust{nullptr, 0};
     lc_status s = up_conv(c, hc, dc, u, nf, ustat ? StatRef{partU(c) + (size_t)n0 * (T / 32) * C * 2, T / 32} : StatRef{nullptr, 0},
                           partD(c, slot) + (size_t)n0 * stat_splits(T / 4) * Cd * 2, &ust);
@@ -490,8 +551,22 @@ lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
     s = conv_out(c, u, (char*)eps + (size_t)n0 * g.C_lat * T * es, nf, ust);
     if (s != LC_OK) return s;
   }
+  {
+    lc_status s = join_lanes(c);
+    if (s != LC_OK) return s;
+  }
   LC_HIP(c, hipEventRecord(c->ev_consumed[slot], c->cs));
   return LC_OK;
+}
+
+lc_status run_step(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
+  const lc_status s = run_step_lanes(c, x, eps, slot, full);
+  if (s != LC_OK) {  // leave the streams joined and the first lane selected whatever happened
+    const std::string keep = c->err;
+    (void)join_lanes(c);
+    c->err = keep;
+  }
+  return s;
 }
 
 lc_status step_checks(lc_ctx* c, const void* x, void* eps, int slot) {
@@ -542,8 +617,10 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
   lc_ctx* c = new (std::nothrow) lc_ctx();
   if (!c) return fail(nullptr, LC_ERR_NOMEM, "out of host memory");
   c->cfg = *cfg;
-  c->cs = (hipStream_t)compute_stream;
+  c->cs = c->cs_main = (hipStream_t)compute_stream;
   c->ss = (hipStream_t)side_stream;
+  c->cs_aux = nullptr; c->ev_fork = c->ev_join = nullptr;
+  c->lanes = 2; c->lane = 0; c->forked = false;
   c->device = dev;
   c->frame_chunk = c->token_chunk = 0;
   c->plan = make_plan(c->cfg, 0, 0);
@@ -578,6 +655,11 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
     return hipSuccess;
   };
   hipError_t e;
+  // the second lane: a stream of the library's own (default priority; it never syncs with the legacy stream)
+  if ((e = hipStreamCreateWithFlags(&c->cs_aux, hipStreamNonBlocking)) != hipSuccess) return bail(LC_ERR_HIP, "hipStreamCreate", e);
+  if ((e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming)) != hipSuccess ||
+      (e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming)) != hipSuccess)
+    return bail(LC_ERR_HIP, "hipEventCreate", e);
   if ((e = mk(c->ev_produced, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
       (e = mk(c->ev_consumed, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
       (e = mk(c->ev_in_done, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
@@ -597,8 +679,11 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
 
 lc_status lc_destroy(lc_ctx* c) {
   if (!c) return LC_OK;
-  (void)hipStreamSynchronize(c->cs);
+  (void)hipStreamSynchronize(c->cs_main);
   (void)hipStreamSynchronize(c->ss);
+  if (c->cs_aux) { (void)hipStreamSynchronize(c->cs_aux); (void)hipStreamDestroy(c->cs_aux); }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   for (void* p : c->host) (void)hipHostFree(p);
   for (auto* v : {&c->ev_produced, &c->ev_consumed, &c->ev_in_done, &c->ev_rd_done, &c->ev_out_done})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
@@ -723,6 +808,13 @@ lc_status lc_set_workspace(lc_ctx* c, void* arena, size_t bytes) {
   std::fill(c->in_pending.begin(), c->in_pending.end(), 0);
   std::fill(c->deep_stat_valid.begin(), c->deep_stat_valid.end(), 0);
   c->st.workspace_bytes = c->plan.total;
+  return LC_OK;
+}
+
+lc_status lc_set_lanes(lc_ctx* c, int lanes) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (lanes != 1 && lanes != 2) return fail(c, LC_ERR_ARG, "lanes must be 1 or 2");
+  c->lanes = lanes;
   return LC_OK;
 }
 

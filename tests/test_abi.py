@@ -69,7 +69,8 @@ def test_footprint_model_scales_with_chunk_not_with_frames():
     cfg = synth.CONFIGS["animatediff"]
     c = lcb.make_config(cfg)
     full = lcb.lc_workspace_bytes(c, 0, 0)
-    sizes = [lcb.lc_workspace_bytes(c, fc, 0) for fc in (16, 8, 4, 2, 1)]
+    # a chunked step keeps two chunks in flight (one per lane), so halving the axis saves nothing yet
+    sizes = [lcb.lc_workspace_bytes(c, fc, 0) for fc in (8, 4, 2, 1)]
     assert all(a > b for a, b in zip([full] + sizes, sizes))
     # persistent part: fp32 skip feature + dev_slots cache entries + GroupNorm partial sums (three tensors
     # of [N][T/32][C][2] floats written by the kernels that produce the normalised tensors, and the
@@ -78,9 +79,9 @@ def test_footprint_model_scales_with_chunk_not_with_frames():
     persistent = cfg.N * cfg.T * cfg.C * 4 + 2 * lcb.lc_cache_entry_bytes(c) + 3 * cfg.N * (cfg.T // 32) * cfg.C * 8
     # one frame of scratch: fp32 ping-pong copy of the stream + q,k,v + attention output
     chunk1 = cfg.T * (4 * cfg.C + 4 * cfg.C * es)
-    assert sizes[-1] - persistent < chunk1 + 16e6
-    # chunk scratch is linear in the frame chunk
-    assert abs((sizes[1] - sizes[2]) - 4 * chunk1) < 1e6
+    assert sizes[-1] - persistent < 2 * chunk1 + 32e6
+    # chunk scratch is linear in the frame chunk (fc = 8 -> 4, two lanes each)
+    assert abs((sizes[0] - sizes[1]) - 2 * 4 * chunk1) < 1e6
     # negative chunk
     assert lcb.lc_workspace_bytes(c, -1, 0) == 0
     # clamping: a chunk above the axis length equals unchunked

@@ -81,6 +81,19 @@ def test_chunked_equals_unchunked_bitwise(cfg):
             assert torch.equal(a, ref_full), (fc, tc)
             assert torch.equal(b, ref_cached), (fc, tc)
             assert stage.dev_entry_bytes(1) == deep_ref, (fc, tc)
+        # the chunks above ran on two lanes (alternate chunks on two streams); on one lane: the same bits
+        stage.set_lanes(1)
+        for fc, tc in [(2, 0), (3, 64)]:
+            print(f"[chunk] {cfg.name} ({fc},{tc}) one lane", flush=True)
+            stage.set_chunk(fc, tc)
+            a, b = stage.empty(*x.shape), stage.empty(*x.shape)
+            stage.full_step(x, a, 1)
+            stage.cached_step(x, b, 1)
+            stage.sync()
+            assert torch.equal(a, ref_full), (fc, tc)
+            assert torch.equal(b, ref_cached), (fc, tc)
+        with pytest.raises(lcb.LcError):
+            stage.set_lanes(3)
     finally:
         stage.close()
 
