@@ -389,6 +389,15 @@ lc_status conv_out(lc_ctx* c, const void* u, void* eps, int frames, StatRef u_st
   const lc_config& g = c->cfg;
   lc_status s = gn_scale_shift(c, u, frames, g.H * g.W, g.C, c->pw.out_gn, u_st);
   if (s != LC_OK) return s;
+  // the tile kernel where the stage's geometry allows it (a property of the stage, not of the chunk)
+  hipError_t e;
+  {
+    Prof pr_(c, LC_K_CONV_OUT);
+    e = launch_conv_out_tile(c->cs, g.dtype, u, scale_p(c), shift_p(c), c->pw.out.w, c->pw.out.b, eps, frames, g.H, g.W, g.C,
+                             g.C_lat);
+  }
+  if (e == hipSuccess) return LC_OK;
+  if (e != hipErrorNotSupported) return fail(c, LC_ERR_HIP, "conv_out: %s", hipGetErrorString(e));
   FusedDesc d = fconv_desc(c, c->pw.out, g.C, 32, frames, g.H, g.W, u, nullptr, eps, 0);
   d.Cout_store = g.C_lat;
   d.planar_out = 1;

@@ -269,4 +269,132 @@ hipError_t launch_conv(hipStream_t s, const ConvDesc& d) {
   return d.y_f32 ? dispatch_shape<bf16_t, bf16_t, float>(s, d) : dispatch_shape<bf16_t, bf16_t, bf16_t>(s, d);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Last convolution of the stage: eps = conv3x3_{C -> C_lat}(SiLU(GN(u))) + bias, C_lat <= 16 output
+// channels, planar output. One pass over u bounds it (C * 4 bytes read per pixel against
+// 2 * 9 * C * C_lat FLOP): what costs time is the activation (two transcendentals per element) and
+// getting every compute unit to pull its share of u early. So:
+//   - a workgroup owns a 4 x 16 pixel tile of one frame (256 tiles for four 64 x 64 frames) and all C
+//     channels of its 6 x 18 halo: every thread requests all its 32-byte pieces of the halo at once,
+//     then normalises, activates and rounds them as they land and parks them in LDS, pixel-major;
+//   - the contraction over K = 9 * C runs on 16 x 16 x 32 MFMAs with the (zero padded) output channels
+//     as rows and 16 pixels of an image row as columns; the wavefronts split K (the weights of a
+//     wavefront's share sit in its registers as A fragments, fetched while the halo is on its way),
+//     each covers the four image rows of the tile;
+//   - the wavefronts' partial sums meet in LDS and are added in a fixed order.
+// NT threads: with 512 two wavefronts share a SIMD, and one's transcendentals overlap the other's loads.
+template <int C, int NT>
+__global__ __launch_bounds__(NT) void conv_out_tile_kernel(const float* __restrict__ u, const float* __restrict__ scale,
+                                                           const float* __restrict__ shift, const bf16_t* __restrict__ w,
+                                                           const float* __restrict__ bias, bf16_t* __restrict__ out, int H,
+                                                           int W, int C_lat) {
+  typedef Mma16<bf16_t> M;
+  constexpr int XS = C * 2 + 16;                 // LDS bytes per halo pixel (padded: 16 pixels hit 64 banks)
+  constexpr int HW_ = 18, HP = 6 * HW_;          // halo width, halo pixels
+  constexpr int PPR = C / 8;                     // 16-byte bf16 packets per pixel
+  constexpr int GRP = NT / PPR;                  // pixels staged per round
+  constexpr int RND = (HP + GRP - 1) / GRP;      // rounds
+  constexpr int CB = C / 32;                     // k-steps per tap
+  constexpr int NKS = 9 * CB;                    // k-steps
+  constexpr int NW = NT / 64;                    // wavefronts
+  constexpr int KSW = (NKS + NW - 1) / NW;       // k-steps per wavefront
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* const red = reinterpret_cast<float*>(smem + HP * XS);  // [wave][row 4][channel 16][x 16]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int x0 = blockIdx.x * 16, y0 = blockIdx.y * 4, frame = blockIdx.z;
+
+  // ---- staging: thread = (packet column, pixel group); its halo pixels are grp, grp + GRP, ...
+  const int col = tid % PPR, grp = tid / PPR;
+  const int c0 = col * 8;
+  f32x4 raw[RND][2];
+  const float* uf = u + (int64_t)frame * H * W * C + c0;
+#pragma unroll
+  for (int j = 0; j < RND; ++j) {
+    const int hp = min(grp + GRP * j, HP - 1);
+    const int iy = min(max(y0 + hp / HW_ - 1, 0), H - 1), ix = min(max(x0 + hp % HW_ - 1, 0), W - 1);  // clamped: valid
+    const float* px = uf + ((int64_t)iy * W + ix) * C;
+    raw[j][0] = *reinterpret_cast<const f32x4*>(px);
+    raw[j][1] = *reinterpret_cast<const f32x4*>(px + 4);
+  }
+  float sc[8], sh[8];
+  load_f<float, 8>(scale + (int64_t)frame * C + c0, sc);
+  load_f<float, 8>(shift + (int64_t)frame * C + c0, sh);
+  // ---- this wavefront's weights: k-step ks = wid + NW j is (tap ks / CB, channels 32 (ks % CB) ..)
+  typename M::Frag af[KSW];
+  {
+    const int co = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < KSW; ++j) {
+      const int ks = min(wid + NW * j, NKS - 1);  // beyond the end: a repeat, never used
+      af[j] = M::load(w + ((int64_t)co * 9 + ks / CB) * C + (ks % CB) * 32, g);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < RND; ++j) {
+    const int hp = grp + GRP * j;
+    const int iy = y0 + hp / HW_ - 1, ix = x0 + hp % HW_ - 1;
+    const bool inside = iy >= 0 && iy < H && ix >= 0 && ix < W;  // the padding is zero after the activation
+    Vec16<bf16_t> o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o.set(e, inside ? silu_fast(fmaf(raw[j][e >> 2][e & 3], sc[e], sh[e])) : 0.f);
+    if (grp < GRP && hp < HP) *reinterpret_cast<Vec16<bf16_t>*>(smem + hp * XS + col * 16) = o;
+  }
+  __syncthreads();
+
+  // ---- contraction: D[channel][pixel x] for the four image rows of the tile
+  f32x4 acc[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const unsigned char* bl = smem + (lane & 15) * XS + (lane >> 4) * 16;
+#pragma unroll
+  for (int j = 0; j < KSW; ++j) {
+    const int ks = wid + NW * j;
+    if (ks < NKS) {  // uniform over the wavefront
+      const int tap = ks / CB, cb = ks - tap * CB;
+      const int dy = tap / 3, dx = tap - dy * 3;
+      const unsigned char* b0 = bl + (dy * HW_ + dx) * XS + cb * 64;
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        const typename M::Frag bf = *reinterpret_cast<const typename M::Frag*>(b0 + n * HW_ * XS);
+        M::mma(af[j], bf, acc[n]);
+      }
+    }
+  }
+  // lane holds channels 4 (lane / 16) + r of pixel x = lane % 16
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[((wid * 4 + n) * 16 + 4 * (lane >> 4) + r) * 16 + (lane & 15)] = acc[n][r];
+  __syncthreads();
+  for (int i = tid; i < 4 * C_lat * 16; i += NT) {
+    const int x = i & 15, co = (i >> 4) % C_lat, n = i / (16 * C_lat);
+    float v = red[(n * 16 + co) * 16 + x];
+#pragma unroll
+    for (int q = 1; q < NW; ++q) v += red[((q * 4 + n) * 16 + co) * 16 + x];  // fixed order
+    v += bias[co];
+    out[(((int64_t)frame * C_lat + co) * H + y0 + n) * W + x0 + x] = static_cast<bf16_t>(v);
+  }
+}
+
+// Returns hipErrorNotSupported for shapes it does not cover (the caller then uses the general kernel).
+hipError_t launch_conv_out_tile(hipStream_t s, int dt, const void* u, const float* scale, const float* shift, const void* w,
+                                const float* bias, void* out, int frames, int H, int W, int C, int C_lat) {
+  if (dt != kBF16 || C != 320 || W % 16 || H % 4 || C_lat < 1 || C_lat > 16) return hipErrorNotSupported;
+  if (frames <= 0) return hipSuccess;
+  constexpr int NT = 512;
+  const int lds = (6 * 18) * (320 * 2 + 16) + (NT / 64) * 4 * 16 * 16 * 4;
+  auto kern = conv_out_tile_kernel<320, NT>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid((unsigned)(W / 16), (unsigned)(H / 4), (unsigned)frames);
+  kern<<<grid, NT, lds, s>>>((const float*)u, scale, shift, (const bf16_t*)w, bias, (bf16_t*)out, H, W, C_lat);
+  return hipGetLastError();
+}
+
 }  // namespace lc

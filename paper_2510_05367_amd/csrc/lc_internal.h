@@ -50,6 +50,11 @@ struct ConvDesc {
   int planar_out;
 };
 hipError_t launch_conv(hipStream_t s, const ConvDesc& d);
+// eps = conv3x3_{C -> C_lat}(SiLU(u * scale + shift)) + bias: u fp32 rows [frames][H*W][C], scale / shift
+// [frames][C], w [32][9][C] (rows beyond C_lat zero), eps planar [frames][C_lat][H][W]. bf16 stages with
+// C = 320, W % 16 == 0, H % 4 == 0 only: otherwise hipErrorNotSupported (use the general kernel).
+hipError_t launch_conv_out_tile(hipStream_t s, int dt, const void* u, const float* scale, const float* shift, const void* w,
+                                const float* bias, void* out, int frames, int H, int W, int C, int C_lat);
 
 // ---- fused-loader 3x3 stride-1 convolutions and linear layers (32x32 MFMA tiles) -------------
 struct FusedDesc {
