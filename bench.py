@@ -224,7 +224,10 @@ def main():
         for i in range(n):
             stage.cached_step(x, eps, i % 2)
             stage.swap_in(0, (i + 1) % 2)  # prefetch for the next step into the other buffer
-    prefetched_steps(max(2, W))            # untimed, like the warm-up of the plain steps
+    # untimed, like the warm-up of the plain steps, but longer: the first time the host runs many steps with
+    # copies ahead of the device, a few lc_swap_in calls block for milliseconds inside the runtime (seen at
+    # iterations 9-15 of the first such loop, never again afterwards)
+    prefetched_steps(max(W, 24))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     prefetched_steps(K)

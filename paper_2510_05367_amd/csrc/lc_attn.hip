@@ -176,11 +176,15 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
     for (int t = 0; t < NQT; ++t) {
       // lane holds keys  k0 + kt*32 + 8*(r/4) + 4*hh + r%4  of query lq
       if (tail) {
+        // (the key indices are built from a value the compiler cannot see through: left alone it hoists
+        // these 64 additions out of the branch and every stage pays for them)
+        int kb = k0 + 4 * hh;
+        asm volatile("" : "+v"(kb));
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            if (k0 + kt * 32 + 8 * (r >> 2) + 4 * hh + (r & 3) >= T_tok) sc[t][kt][r] = -INFINITY;
+            if (kb + kt * 32 + 8 * (r >> 2) + (r & 3) >= T_tok) sc[t][kt][r] = -INFINITY;
       }
       float mx = -INFINITY;
 #pragma unroll
