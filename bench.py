@@ -68,6 +68,10 @@ def family_bytes(cfg):
         "conv_in": P * cfg.C_lat * es + P * C * 4,
         "conv_out": P * C * es + P * cfg.C_lat * es,
         "tattn": 4 * P * C * es,
+        # the projections are near the machine balance (193 FLOP per byte): both rooflines are reported.
+        # q,k,v: fp32 stream in, three operand tensors out; output projection: operand in, fp32 residual in and out
+        "qkv": 2 * (P * C * 4 + 3 * P * C * es),
+        "proj": 2 * (P * C * es + 2 * P * C * 4),
     }
 
 

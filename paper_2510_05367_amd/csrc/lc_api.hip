@@ -43,14 +43,15 @@ struct Packed {
 };
 
 struct EvPair { hipEvent_t a, b; int kind; int64_t bytes; };
+constexpr int kMaxLanes = 2;  // streams a chunked step can spread its chunks over (a third one measured no gain)
 
 }  // namespace
 
 struct lc_ctx {
   lc_config cfg;
   hipStream_t cs, ss;            // cs: the stream kernels are issued on right now (see use_lane)
-  hipStream_t cs_main, cs_aux;   // the caller's compute stream; the library's own second one
-  hipEvent_t ev_fork, ev_join;
+  hipStream_t cs_main, cs_aux[kMaxLanes - 1];  // the caller's compute stream; the library's own further ones
+  hipEvent_t ev_fork, ev_join[kMaxLanes - 1];
   int lanes;                     // 1 or 2: streams a chunked step spreads its chunks over
   int lane;                      // the lane in use: selects cs and the per-lane scratch
   bool forked;
@@ -169,7 +170,7 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   p.ws_bytes = align_up(wsb) + kAlign;
   p.off_ws = off; off += p.ws_bytes;
   p.lane_stride = off - p.lane_off;
-  if (p.fc < N || p.tc < T) off += p.lane_stride;  // the second lane's copy
+  if (p.fc < N || p.tc < T) off += (kMaxLanes - 1) * p.lane_stride;  // the other lanes' copies
   p.total = off;
   return p;
 }
@@ -217,13 +218,16 @@ RowMap dense_map() { return RowMap{0, 0, 1 << 30}; }
 // not depend on it: the same kernels see the same data.
 void use_lane(lc_ctx* c, int l) {
   c->lane = l;
-  c->cs = l ? c->cs_aux : c->cs_main;
+  c->cs = l ? c->cs_aux[l - 1] : c->cs_main;
 }
 // lanes for a loop of n chunks; with per-kernel timing on, one (a bracketed kernel must run alone)
-int loop_lanes(lc_ctx* c, int n) { return (c->lanes > 1 && n > 1 && c->prof_mask == 0 && c->plan.total > c->plan.lane_off + c->plan.lane_stride) ? 2 : 1; }
+int loop_lanes(lc_ctx* c, int n) {
+  const bool can = c->prof_mask == 0 && c->plan.total > c->plan.lane_off + c->plan.lane_stride;
+  return can ? std::max(1, std::min(c->lanes, n)) : 1;
+}
 lc_status fork_lanes(lc_ctx* c) {
   LC_HIP(c, hipEventRecord(c->ev_fork, c->cs_main));
-  LC_HIP(c, hipStreamWaitEvent(c->cs_aux, c->ev_fork, 0));
+  for (int i = 0; i + 1 < c->lanes; ++i) LC_HIP(c, hipStreamWaitEvent(c->cs_aux[i], c->ev_fork, 0));
   c->forked = true;
   return LC_OK;
 }
@@ -231,8 +235,10 @@ lc_status join_lanes(lc_ctx* c) {
   use_lane(c, 0);
   if (!c->forked) return LC_OK;
   c->forked = false;
-  LC_HIP(c, hipEventRecord(c->ev_join, c->cs_aux));
-  LC_HIP(c, hipStreamWaitEvent(c->cs_main, c->ev_join, 0));
+  for (int i = 0; i + 1 < kMaxLanes; ++i) {  // (a lane that got no work joins at once)
+    LC_HIP(c, hipEventRecord(c->ev_join[i], c->cs_aux[i]));
+    LC_HIP(c, hipStreamWaitEvent(c->cs_main, c->ev_join[i], 0));
+  }
   return LC_OK;
 }
 
@@ -417,9 +423,9 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
   // ---- shallow down branch D_m, per frame chunk
   const bool tiled = T % 32 == 0;  // whole 32-row tiles in every frame and position chunk: see linear()
   bool tstat = tiled;              // the 32-row tiles of the projection kernels stay inside a frame
-  if (frame_lanes == 2) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
+  if (frame_lanes > 1) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
   for (int n0 = 0, ci = 0; n0 < N; n0 += p.fc, ++ci) {
-    use_lane(c, frame_lanes == 2 ? ci & 1 : 0);
+    use_lane(c, ci % frame_lanes);
     char* ws = ws_ptr(c);
     const int nf = std::min(p.fc, N - n0);
     const int64_t pc = (int64_t)nf * T;
@@ -485,9 +491,9 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
     if (s != LC_OK) return s;
     const float *sc0 = scale_p(c), *sh0 = shift_p(c);  // of all frames: every position chunk reads them, on either lane
     const int pos_lanes = loop_lanes(c, (T + p.tc - 1) / p.tc);
-    if (pos_lanes == 2 && (s = fork_lanes(c)) != LC_OK) return s;
+    if (pos_lanes > 1 && (s = fork_lanes(c)) != LC_OK) return s;
     for (int p0 = 0, ci = 0; p0 < T; p0 += p.tc, ++ci) {
-      use_lane(c, pos_lanes == 2 ? ci & 1 : 0);
+      use_lane(c, ci % pos_lanes);
       char* ws = ws_ptr(c);
       const int np = std::min(p.tc, T - p0);
       const int64_t rows = (int64_t)N * np;
@@ -516,9 +522,9 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
     LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_rd_done[slot], 0));
     LC_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
     c->in_pending[slot] = 0;
-    if (frame_lanes == 2) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
+    if (frame_lanes > 1) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
     for (int n0 = 0, ci = 0; n0 < N; n0 += p.fc, ++ci) {
-      use_lane(c, frame_lanes == 2 ? ci & 1 : 0);
+      use_lane(c, ci % frame_lanes);
       const int nf = std::min(p.fc, N - n0);
       char* hc = h + (size_t)n0 * T * C * 4;
       char* d0 = ws_ptr(c);  // fp32
@@ -546,9 +552,9 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
   }
 
   // ---- shallow up branch U_m on Concat(skip, up2(deep)), per frame chunk
-  if (frame_lanes == 2) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
+  if (frame_lanes > 1) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
   for (int n0 = 0, ci = 0; n0 < N; n0 += p.fc, ++ci) {
-    use_lane(c, frame_lanes == 2 ? ci & 1 : 0);
+    use_lane(c, ci % frame_lanes);
     const int nf = std::min(p.fc, N - n0);
     char* hc = h + (size_t)n0 * T * C * 4;
     char* dc = deep + (size_t)n0 * (T / 4) * Cd * es;
@@ -628,7 +634,8 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
   c->cfg = *cfg;
   c->cs = c->cs_main = (hipStream_t)compute_stream;
   c->ss = (hipStream_t)side_stream;
-  c->cs_aux = nullptr; c->ev_fork = c->ev_join = nullptr;
+  for (int i = 0; i + 1 < kMaxLanes; ++i) { c->cs_aux[i] = nullptr; c->ev_join[i] = nullptr; }
+  c->ev_fork = nullptr;
   c->lanes = 2; c->lane = 0; c->forked = false;
   c->device = dev;
   c->frame_chunk = c->token_chunk = 0;
@@ -665,10 +672,11 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
   };
   hipError_t e;
   // the second lane: a stream of the library's own (default priority; it never syncs with the legacy stream)
-  if ((e = hipStreamCreateWithFlags(&c->cs_aux, hipStreamNonBlocking)) != hipSuccess) return bail(LC_ERR_HIP, "hipStreamCreate", e);
-  if ((e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming)) != hipSuccess ||
-      (e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming)) != hipSuccess)
-    return bail(LC_ERR_HIP, "hipEventCreate", e);
+  for (int i = 0; i + 1 < kMaxLanes; ++i) {
+    if ((e = hipStreamCreateWithFlags(&c->cs_aux[i], hipStreamNonBlocking)) != hipSuccess) return bail(LC_ERR_HIP, "hipStreamCreate", e);
+    if ((e = hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming)) != hipSuccess) return bail(LC_ERR_HIP, "hipEventCreate", e);
+  }
+  if ((e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming)) != hipSuccess) return bail(LC_ERR_HIP, "hipEventCreate", e);
   if ((e = mk(c->ev_produced, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
       (e = mk(c->ev_consumed, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
       (e = mk(c->ev_in_done, cfg->dev_slots, hipEventDisableTiming)) != hipSuccess ||
@@ -690,9 +698,11 @@ lc_status lc_destroy(lc_ctx* c) {
   if (!c) return LC_OK;
   (void)hipStreamSynchronize(c->cs_main);
   (void)hipStreamSynchronize(c->ss);
-  if (c->cs_aux) { (void)hipStreamSynchronize(c->cs_aux); (void)hipStreamDestroy(c->cs_aux); }
+  for (int i = 0; i + 1 < kMaxLanes; ++i) {
+    if (c->cs_aux[i]) { (void)hipStreamSynchronize(c->cs_aux[i]); (void)hipStreamDestroy(c->cs_aux[i]); }
+    if (c->ev_join[i]) (void)hipEventDestroy(c->ev_join[i]);
+  }
   if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   for (void* p : c->host) (void)hipHostFree(p);
   for (auto* v : {&c->ev_produced, &c->ev_consumed, &c->ev_in_done, &c->ev_rd_done, &c->ev_out_done})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
@@ -822,7 +832,7 @@ lc_status lc_set_workspace(lc_ctx* c, void* arena, size_t bytes) {
 
 lc_status lc_set_lanes(lc_ctx* c, int lanes) {
   if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
-  if (lanes != 1 && lanes != 2) return fail(c, LC_ERR_ARG, "lanes must be 1 or 2");
+  if (lanes < 1 || lanes > kMaxLanes) return fail(c, LC_ERR_ARG, "lanes must be in [1, %d]", kMaxLanes);
   c->lanes = lanes;
   return LC_OK;
 }
