@@ -1,0 +1,465 @@
+// 3x3 stride-1 convolution of the bf16 stages with the wavefronts of a workgroup specialised
+// (gfx950): four wavefronts only contract (LDS fragment reads and 32x32x16 MFMAs), four only load
+// (global memory -> activation arithmetic -> LDS). Both kinds sit on every SIMD, so the vector
+// arithmetic of the loader (GroupNorm apply, SiLU, rounding: two transcendentals per element) and
+// every global-memory latency run beside the MFMAs of the other wavefront instead of inside one
+// instruction stream, which a single wavefront per SIMD executes one part after the other.
+//
+// Product, tiles and LDS layout are those of the general kernel in lc_gemm.hip: transposed product
+// D[cout][pixel] = sum_k W[cout][k] X[pixel][k], k = tap * Cin + ci; a workgroup owns 160 output
+// channels x 128 pixels (an 8 x 16 tile of one frame); contracting wavefront (pxh, kh) takes all 160
+// channels of 64 pixels over half of the K elements of every (64-channel slab, tap) step, and the two
+// halves are added through LDS before the epilogue. The loader fuses GroupNorm apply + SiLU and, for
+// the up block, the 2x nearest upsampling and the skip-concat U_m = Concat(D_m, up2(U_{m+1}))
+// ("Feature Calculation" paragraph): neither the normalised nor the concatenated tensor exists in
+// memory. The same accumulation order as the general kernel: results agree bit for bit.
+#include <type_traits>
+
+#include "lc_internal.h"
+
+namespace lc {
+
+namespace {
+
+constexpr int kwRow = 128;      // K bytes per LDS row per step (64 bf16 channels)
+constexpr int kwLds = 144;      // row stride of the halo tiles: 16-byte reads of 8 consecutive rows cover all banks
+constexpr int kwHaloW = 18;     // halo of an 8 x 16 pixel tile: 10 x 18
+constexpr int kwHaloRows = 192; // 180 used, padded to 6 rounds of 32 rows
+constexpr int kwBuf = 4;        // weight tiles in LDS; the loads run kwBuf - 1 steps ahead of their use
+constexpr int kwAhead = kwBuf - 1;
+constexpr int kwLead = 2;       // at the barrier that ends step s the weights of step s + kwLead have landed: the
+                                // contracting wavefronts request the first fragments of step s + 1 before that barrier
+constexpr int kwFA = 4;         // weight fragments requested from LDS ahead of the MFMAs that use them (ring of kwFA + 1)
+constexpr int kwFin = 2;        // a halo packet requested at tap r is activated and stored at tap r + kwFin
+constexpr int kwXR = kwHaloRows / 32;  // halo packets per loader thread per slab
+
+struct WsArgs {
+  const float* x;       // fp32 rows [frames][H][W][ldx]; ldx = Cin (plain) or Cs (concat)
+  const bf16_t* x2;     // concat: cached deep feature [frames][H/2][W/2][Cin - Cs]
+  const float* scale;   // [frames][Cin]
+  const float* shift;
+  const bf16_t* w;      // [Cout][9 * Cin]
+  const float* bias;    // [Cout] or nullptr
+  const float* res;     // fp32, indexed like y, or nullptr
+  float* y;             // fp32 [frames][H][W][Cout]
+  int Cin, Cs, Cout, ldw;
+  int H, W, tiles_x, tiles_y;
+  float* stat;          // per-channel sums of the output per 32-pixel split, or nullptr
+  int stat_splits;
+};
+
+template <int CO_T>
+constexpr int ws_lds_bytes() { return kwBuf * CO_T * 32 * kwRow + 2 * kwHaloRows * kwLds; }
+
+// vector-memory loads a loader thread issues in tap t of a slab: scale/shift at tap 0 and a halo
+// packet at taps < kwXR when a next slab follows (`more`), then the weights of step s + kwAhead if
+// there is one. t < 0 is a late tap of the slab before (weights only).
+constexpr int ws_tap_loads(int t, bool more, int n_pkt, int wp) {
+  if (t < 0) return wp;
+  return (more && t == 0 ? 4 + kwXR * n_pkt : 0) + ((more || t + kwAhead < 9) ? wp : 0);
+}
+// loads younger than the weights of step s + kwLead at the end of tap `tap`: those of the last kwAhead - kwLead taps
+constexpr int ws_tap_keep(int tap, bool more, int n_pkt, int wp) {
+  int n = 0;
+  for (int j = 0; j < kwAhead - kwLead; ++j) n += ws_tap_loads(tap - j, more, n_pkt, wp);
+  return n;
+}
+
+}  // namespace
+
+// CAT: channel slabs at and above Cs come from the half-resolution deep feature x2
+template <int CO_T, bool CAT>
+__global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
+  typedef Mma32<bf16_t> M;
+  constexpr int BCO = CO_T * 32;
+  constexpr int WP = BCO * 8 / 256;  // weight DMA instructions per loader thread per step
+  constexpr int KI = 4;              // MFMA k-steps per 64-channel row
+  constexpr int KB = 32;             // bytes of one k-step in a row
+  static_assert((BCO * 8) % 256 == 0, "whole wavefront instructions");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  auto w_lds = [&](int b) { return smem + b * BCO * kwRow; };
+  auto x_lds = [&](int b) { return smem + kwBuf * BCO * kwRow + b * kwHaloRows * kwLds; };
+
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int co0 = blockIdx.y * BCO;
+  int frame, ty0, tx0;
+  {
+    int t = blockIdx.x;
+    tx0 = (t % a.tiles_x) * 16;
+    t /= a.tiles_x;
+    ty0 = (t % a.tiles_y) * 8;
+    frame = t / a.tiles_y;
+  }
+  const int nslab = a.Cin / 64;
+
+  if (wid >= 4) {
+    // =========================== loader wavefronts ===========================
+    const int lt = tid - 256, lw = wid - 4;
+    const int kp = lt & 7, lrow = lt >> 3;  // this thread moves 16-byte packet kp of halo rows lrow + 32 r
+    // halo rows of this thread: source pixel (clamped; out-of-image taps become zero after the activation)
+    int pix[kwXR], dpix[kwXR];
+    unsigned okmask = 0;
+#pragma unroll
+    for (int r = 0; r < kwXR; ++r) {
+      const int hp = lrow + 32 * r;
+      const int hy = hp / kwHaloW, hx = hp - hy * kwHaloW;
+      const int iy = ty0 + hy - 1, ix = tx0 + hx - 1;
+      if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) okmask |= 1u << r;
+      const int cy = min(max(iy, 0), a.H - 1), cx = min(max(ix, 0), a.W - 1);
+      pix[r] = (frame * a.H + cy) * a.W + cx;
+      dpix[r] = CAT ? (frame * (a.H >> 1) + (cy >> 1)) * (a.W >> 1) + (cx >> 1) : 0;
+    }
+    const int ldx = CAT ? a.Cs : a.Cin;
+    const float* __restrict__ xbase = a.x + kp * 8;
+    const bf16_t* __restrict__ dbase = CAT ? a.x2 + kp * 8 - a.Cs : nullptr;  // indexed with the concat channel
+    const int ldd = a.Cin - a.Cs;
+    const float* __restrict__ scb = a.scale + (int64_t)frame * a.Cin + kp * 8;
+    const float* __restrict__ shb = a.shift + (int64_t)frame * a.Cin + kp * 8;
+    // weights: global -> LDS directly. A wavefront instruction moves 8 rows x 128 bytes; packet c of row r
+    // is parked in slot c ^ ((r >> 1) & 7) of that row (conflict-free fragment reads without padding).
+    // Instruction i covers rows (4 i + lw) * 8 ..+7; the slot key does not depend on i.
+    const int l8 = lane >> 3;
+    const int wr0 = lw * 8 + l8;
+    const int wc = (lane & 7) ^ ((wr0 >> 1) & 7);
+    const bf16_t* __restrict__ wsrc = a.w + (int64_t)(co0 + wr0) * a.ldw + wc * 8;
+    auto dma_w = [&](int step, int buf) {
+      const int slab = step / 9, tap = step - slab * 9;
+      const bf16_t* src = wsrc + tap * a.Cin + slab * 64;
+#pragma unroll
+      for (int i = 0; i < WP; ++i) {
+#ifdef __HIP_DEVICE_COMPILE__  // the host pass only needs the kernel's stub; it does not know this builtin
+        __builtin_amdgcn_global_load_lds(src + (int64_t)i * 32 * a.ldw, w_lds(buf) + (i * 4 + lw) * 1024, 16, 0, 0);
+#else
+        (void)src;
+#endif
+      }
+    };
+    struct XRaw { f32x4 q[2]; };
+    struct Affine { f32x4 sc[2], sh[2]; };
+    auto load_affine = [&](int slab, Affine& af) {
+      af.sc[0] = *reinterpret_cast<const f32x4*>(scb + slab * 64);
+      af.sc[1] = *reinterpret_cast<const f32x4*>(scb + slab * 64 + 4);
+      af.sh[0] = *reinterpret_cast<const f32x4*>(shb + slab * 64);
+      af.sh[1] = *reinterpret_cast<const f32x4*>(shb + slab * 64 + 4);
+    };
+    auto fetch_x = [&](int slab, int r, XRaw& o, auto deep_c) {
+      if constexpr (decltype(deep_c)::value) {
+        o.q[0] = *reinterpret_cast<const f32x4*>(dbase + (int64_t)dpix[r] * ldd + slab * 64);
+      } else {
+        const float* p = xbase + (int64_t)pix[r] * ldx + slab * 64;
+        o.q[0] = *reinterpret_cast<const f32x4*>(p);
+        o.q[1] = *reinterpret_cast<const f32x4*>(p + 4);
+      }
+    };
+    auto finish_x = [&](int buf, int r, const XRaw& o, const Affine& af, auto deep_c) {
+      const bool ok = (okmask >> r) & 1u;
+      bf16x8 pk;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float t;
+        if constexpr (decltype(deep_c)::value) {
+          typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+          const uint32_t wd = __builtin_bit_cast(u32x4, o.q[0])[e >> 1];
+          t = __builtin_bit_cast(float, (e & 1) ? (wd & 0xffff0000u) : (wd << 16));
+        } else {
+          t = o.q[e >> 2][e & 3];
+        }
+        t = fmaf(t, af.sc[e >> 2][e & 3], af.sh[e >> 2][e & 3]);
+        t = silu_fast(t);
+        pk[e] = static_cast<bf16_t>(ok ? t : 0.f);
+      }
+      *reinterpret_cast<bf16x8*>(x_lds(buf) + (lrow + 32 * r) * kwLds + kp * 16) = pk;
+    };
+
+    const std::false_type no_c{};
+    const std::true_type yes_c{};
+    Affine aff;
+    XRaw xin[kwXR];  // the packets of the next slab are all requested at tap 0; packet r is consumed at tap r + kwFin
+    // ---- prologue: weights of the first steps, halo of slab 0 (never in the deep part)
+#pragma unroll
+    for (int j = 0; j < kwAhead; ++j) dma_w(j, j);
+    load_affine(0, aff);
+    {
+      XRaw x0[kwXR];
+#pragma unroll
+      for (int r = 0; r < kwXR; ++r) fetch_x(0, r, x0[r], no_c);
+#pragma unroll
+      for (int r = 0; r < kwXR; ++r) finish_x(0, r, x0[r], aff, no_c);
+    }
+    barrier_keep<(kwAhead - kwLead) * WP>();  // the weights of the first kwLead steps have landed, later ones may be on their way
+
+    // ---- main loop. The number of loads per tap is fixed at compile time (the loop is split by where
+    // the next slab comes from instead of branching), so the wait before each barrier is an exact count
+    // of younger loads: the weights of step s + 1 must have landed, nothing else is waited for.
+    auto slab_body = [&](int slab, auto more_c, auto deep_c) {
+      constexpr bool MORE = decltype(more_c)::value;
+      constexpr bool DEEPC = decltype(deep_c)::value;
+      constexpr int n_pkt = DEEPC ? 1 : 2;
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int s = slab * 9 + tap;
+        __builtin_amdgcn_sched_barrier(0);
+        if (MORE) {
+          if (tap == 0) load_affine(slab + 1, aff);
+          if (tap == 0) {
+#pragma unroll
+            for (int r = 0; r < kwXR; ++r) fetch_x(slab + 1, r, xin[r], deep_c);
+          }
+        }
+        if (MORE || tap + kwAhead < 9) dma_w(s + kwAhead, (s + kwAhead) % kwBuf);
+        __builtin_amdgcn_sched_barrier(0);
+        if (MORE && tap >= kwFin && tap - kwFin < kwXR)
+          finish_x((slab + 1) & 1, tap - kwFin, xin[tap - kwFin], aff, deep_c);
+        __builtin_amdgcn_sched_barrier(0);
+#define LC_KEEP(TAP) \
+  case TAP: barrier_keep<ws_tap_keep(TAP, MORE, n_pkt, WP)>(); break;
+        switch (tap) {  // `tap` is a constant once the loop is unrolled
+          LC_KEEP(0) LC_KEEP(1) LC_KEEP(2) LC_KEEP(3) LC_KEEP(4) LC_KEEP(5) LC_KEEP(6) LC_KEEP(7) LC_KEEP(8)
+        }
+#undef LC_KEEP
+      }
+    };
+    static_assert(kwXR - 1 + kwFin < 8, "the halo of the next slab is complete one barrier before the slab ends");
+    const int nskip = CAT ? a.Cs / 64 : nslab;  // slabs read from x; the rest from x2
+    int slab = 0;
+    for (; slab + 1 < nskip; ++slab) slab_body(slab, yes_c, no_c);
+    if (CAT)
+      for (; slab + 1 < nslab; ++slab) slab_body(slab, yes_c, yes_c);
+    slab_body(nslab - 1, no_c, no_c);
+    __syncthreads();  // the hand-over barrier of the contracting wavefronts
+    return;
+  }
+
+  // =========================== contracting wavefronts ===========================
+  const int lp = lane & 31, hh = lane >> 5;
+  const int pxh = wid & 1, kh = wid >> 1;  // 64 pixels x all BCO channels over half of every K row
+  f32x16 acc[CO_T][2];
+#pragma unroll
+  for (int i = 0; i < CO_T; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // the two pixels of this lane inside the tile and their halo rows for tap (0,0)
+  const int p0 = pxh * 64 + lp, p1 = p0 + 32;
+  const int xr0 = (p0 >> 4) * kwHaloW + (p0 & 15);
+  const int xr1 = (p1 >> 4) * kwHaloW + (p1 & 15);
+  const int xoff0 = xr0 * kwLds + hh * 16 + kh * (KI / 2) * KB;
+  const int xoff1 = xr1 * kwLds + hh * 16 + kh * (KI / 2) * KB;
+  const int wkey = (lp >> 1) & 7;  // slot swizzle of this lane's weight rows (32 i does not change it)
+  int wofs[KI / 2];
+#pragma unroll
+  for (int kk = 0; kk < KI / 2; ++kk) {
+    const int wb = hh * 16 + (kh * (KI / 2) + kk) * KB;
+    wofs[kk] = lp * kwRow + ((((wb >> 4) ^ wkey) << 4) | (wb & 15));
+  }
+  constexpr int NF = (KI / 2) * CO_T;  // weight fragments of a tap for this wavefront
+  static_assert(NF % (kwFA + 1) == 0, "a fragment's place in the ring does not depend on the tap");
+  // The fragment stream runs ahead of the MFMAs across the taps: while the pairs of step s are issued
+  // the wavefront requests the activation fragments of step s + 1 and, in its last kwFA pairs, the
+  // first weight fragments of step s + 1 (both are complete in LDS one barrier earlier), so that the
+  // MFMAs of the next step start right behind the barrier instead of an LDS round trip later.
+  M::Frag xf[KI / 2][2], xn[KI / 2][2];
+  M::Frag wf[kwFA + 1];
+  auto x_ptr = [&](int xbuf, int tap, int j) {
+    const int sh = (tap / 3) * kwHaloW + (tap % 3);
+    return x_lds(xbuf) + (j ? xoff1 : xoff0) + sh * kwLds;
+  };
+  auto wload = [&](const unsigned char* wl, int idx) {
+    const int kk = idx / CO_T, i = idx - kk * CO_T;
+    return M::load((const bf16_t*)(wl + i * 32 * kwRow + wofs[kk]));
+  };
+  // one step: `wl` / `wl_next` the weight tiles of this and the next step, `xbuf_next` / `tap_next` where the
+  // next step reads its activations
+  auto compute = [&](const unsigned char* wl, const unsigned char* wl_next, int xbuf_next, int tap_next) {
+    const unsigned char* xn0 = x_ptr(xbuf_next, tap_next, 0);
+    const unsigned char* xn1 = x_ptr(xbuf_next, tap_next, 1);
+#pragma unroll
+    for (int idx = 0; idx < NF; ++idx) {
+      const int nxt = idx + kwFA;
+      wf[nxt % (kwFA + 1)] = nxt < NF ? wload(wl, nxt) : wload(wl_next, nxt - NF);
+      // the activation fragments of the next step, one request per pair from the second pair on
+      if (idx >= 1 && idx - 1 < KI) {
+        const int q = idx - 1, kk = q >> 1, j = q & 1;
+        xn[kk][j] = M::load((const bf16_t*)((j ? xn1 : xn0) + kk * KB));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      const int kk = idx / CO_T, i = idx - kk * CO_T;
+      M::mma(wf[idx % (kwFA + 1)], xf[kk][0], acc[i][0]);
+      M::mma(wf[idx % (kwFA + 1)], xf[kk][1], acc[i][1]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int kk = 0; kk < KI / 2; ++kk) {
+      xf[kk][0] = xn[kk][0];
+      xf[kk][1] = xn[kk][1];
+    }
+  };
+  // a barrier that does not wait for this wavefront's LDS reads: those in flight are the requests for
+  // the next step, whose tiles nobody writes before a later barrier
+  auto step_barrier = [&]() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  barrier_keep<63>();  // prologue: halo of slab 0 and the weights of the first kwLead steps are in LDS
+#pragma unroll
+  for (int kk = 0; kk < KI / 2; ++kk) {
+    xf[kk][0] = M::load((const bf16_t*)(x_ptr(0, 0, 0) + kk * KB));
+    xf[kk][1] = M::load((const bf16_t*)(x_ptr(0, 0, 1) + kk * KB));
+  }
+#pragma unroll
+  for (int idx = 0; idx < kwFA; ++idx) wf[idx] = wload(w_lds(0), idx);
+  int wb = 0;  // weight tile of the current step
+  for (int slab = 0; slab < nslab; ++slab) {
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const int wb_next = wb + 1 == kwBuf ? 0 : wb + 1;
+      // (behind the last step the requests read tiles that hold nothing new: in bounds, never used)
+      compute(w_lds(wb), w_lds(wb_next), tap < 8 ? (slab & 1) : ((slab + 1) & 1), tap < 8 ? tap + 1 : 0);
+      wb = wb_next;
+      step_barrier();
+    }
+  }
+  asm volatile("" :: "v"(xf[0][0]), "v"(wf[0]));  // (the requests behind the last step have no other reader)
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(63));      // no LDS read of this wavefront is in flight when the tiles are reused
+
+  // ---------------- fold the two K halves and write out ----------------
+  // The wavefront (pxh, kh) keeps the 32-pixel tiles j = kh, hands the others to its partner through LDS,
+  // then turns each finished 32 x 32 tile through a private LDS patch so that a lane stores 16 bytes
+  // of one pixel row and eight lanes cover its 128 contiguous bytes (the accumulator layout would
+  // store 16-byte pieces of 32 different rows per instruction). Bias and residual are added in that
+  // layout; the residual is requested before the barrier of the hand-over so its latency hides behind it.
+  constexpr int kTile = 16 * 64;  // floats of one accumulator tile
+  float* give = reinterpret_cast<float*>(smem) + (pxh * 2 + kh) * (CO_T * kTile);
+  const float* take = reinterpret_cast<const float*>(smem) + (pxh * 2 + (kh ^ 1)) * (CO_T * kTile);
+  float* patch = reinterpret_cast<float*>(smem + 4 * CO_T * kTile * 4) + wid * (32 * 36);
+  static_assert(ws_lds_bytes<CO_T>() >= 4 * CO_T * kTile * 4 + 4 * 32 * 36 * 4, "hand-over area + patches");
+  const int prow = lane >> 3, pcol = (lane & 7) * 4;  // patch read-back: rows prow + 8 k, channels pcol..pcol+3
+  auto hand_over = [&](auto jc) {  // jc: the tile column this wavefront gives away
+    constexpr int J = decltype(jc)::value;
+#pragma unroll
+    for (int i = 0; i < CO_T; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) give[(i * 16 + r) * 64 + lane] = acc[i][J][r];
+  };
+  if (kh == 0) hand_over(std::integral_constant<int, 1>{});
+  else hand_over(std::integral_constant<int, 0>{});
+  int64_t obase[4];
+  bool okk[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int p = pxh * 64 + kh * 32 + prow + 8 * k;
+    const int oy = ty0 + (p >> 4), ox = tx0 + (p & 15);
+    okk[k] = oy < a.H && ox < a.W;
+    obase[k] = okk[k] ? (((int64_t)frame * a.H + oy) * a.W + ox) * a.Cout + co0 + pcol : 0;
+  }
+  const float* R = a.res;
+  // residual and bias of one 32-channel tile, requested one tile ahead of its use
+  struct Side { f32x4 r[4]; f32x4 b; };
+  auto load_side = [&](int i, Side& sd) {
+    sd.b = a.bias ? *reinterpret_cast<const f32x4*>(a.bias + co0 + i * 32 + pcol) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      sd.r[k] = (R && okk[k]) ? *reinterpret_cast<const f32x4*>(R + obase[k] + i * 32) : f32x4{0.f, 0.f, 0.f, 0.f};
+  };
+  Side side[2];
+  load_side(0, side[0]);
+  __syncthreads();
+  float* Y = a.y;
+  auto finish = [&](auto jc) {  // jc: the tile column this wavefront keeps
+    constexpr int J = decltype(jc)::value;
+#pragma unroll
+    for (int i = 0; i < CO_T; ++i) {
+      if (i + 1 < CO_T) load_side(i + 1, side[(i + 1) & 1]);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][J][g * 4 + e] + take[(i * 16 + g * 4 + e) * 64 + lane];
+        *reinterpret_cast<f32x4*>(patch + lp * 36 + g * 8 + hh * 4) = v;
+      }
+      // the patch is private to this wavefront, whose LDS operations complete in order
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      float ssum[4] = {0.f, 0.f, 0.f, 0.f}, ssq[4] = {0.f, 0.f, 0.f, 0.f};  // statistics of this lane's pixels
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        f32x4 v = *reinterpret_cast<const f32x4*>(patch + (prow + 8 * k) * 36 + pcol);
+        v += side[i & 1].b;
+        v += side[i & 1].r[k];
+        if (okk[k]) {
+          *reinterpret_cast<f32x4*>(Y + obase[k] + i * 32) = v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            ssum[e] += v[e];
+            ssq[e] = fmaf(v[e], v[e], ssq[e]);
+          }
+        }
+      }
+      if (a.stat) {
+        // fold the eight lanes that hold the same channels, in a fixed order; the first writes.
+        // One split = the 32 pixels of this wavefront (those inside the image).
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+#pragma unroll
+          for (int m = 8; m < 64; m <<= 1) {
+            ssum[e] += __shfl_xor(ssum[e], m, 64);
+            ssq[e] += __shfl_xor(ssq[e], m, 64);
+          }
+        }
+        if (prow == 0) {
+          const int split = ((blockIdx.x % (a.tiles_x * a.tiles_y)) * 2 + pxh) * 2 + kh;
+          float* sp = a.stat + (((int64_t)frame * a.stat_splits + split) * a.Cout + co0 + i * 32 + pcol) * 2;
+          *reinterpret_cast<f32x4*>(sp) = f32x4{ssum[0], ssq[0], ssum[1], ssq[1]};
+          *reinterpret_cast<f32x4*>(sp + 4) = f32x4{ssum[2], ssq[2], ssum[3], ssq[3]};
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+  };
+  if (kh == 0) finish(std::integral_constant<int, 0>{});
+  else finish(std::integral_constant<int, 1>{});
+}
+
+template <int CO_T, bool CAT>
+static hipError_t run_ws(hipStream_t s, const FusedDesc& d) {
+  constexpr int lds = ws_lds_bytes<CO_T>();
+  auto kern = conv_ws_kernel<CO_T, CAT>;
+  static bool attr_done = false;  // per instantiation
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  WsArgs a;
+  a.x = (const float*)d.x; a.x2 = (const bf16_t*)d.x2; a.scale = d.scale; a.shift = d.shift;
+  a.w = (const bf16_t*)d.w; a.bias = d.bias; a.res = (const float*)d.res; a.y = (float*)d.y;
+  a.Cin = d.Cin; a.Cs = d.Cs; a.Cout = d.Cout; a.ldw = 9 * d.Cin;
+  a.H = d.H; a.W = d.W; a.tiles_x = (d.W + 15) / 16; a.tiles_y = (d.H + 7) / 8;
+  a.stat = d.stat; a.stat_splits = d.stat_splits;
+  dim3 grid((unsigned)(a.tiles_x * a.tiles_y * d.frames), d.Cout / (CO_T * 32));
+  kern<<<grid, 512, lds, s>>>(a);
+  return hipGetLastError();
+}
+
+// The 3x3 convolutions of a bf16 stage whose widths suit the kernel above (a property of the stage,
+// never of how it is chunked); hipErrorNotSupported otherwise.
+hipError_t launch_conv_ws(hipStream_t s, const FusedDesc& d) {
+  if (d.dt != kBF16 || d.taps != 9 || !d.y_f32 || d.planar_out || d.yt || d.q_cols) return hipErrorNotSupported;
+  if (d.src != 2 && d.src != 3) return hipErrorNotSupported;
+  if (d.Cout % 160 != 0 || d.Cout_store != d.Cout || d.Cin % 64 != 0) return hipErrorNotSupported;
+  if (d.src == 3 && (d.Cs % 64 != 0 || d.Cs <= 0 || d.Cs >= d.Cin || ((d.H | d.W) & 1))) return hipErrorNotSupported;
+  if (d.stat && d.stat_splits != conv_stat_splits(d.H, d.W)) return hipErrorInvalidValue;
+  // 32-bit pixel and byte-offset arithmetic in the loader
+  if ((int64_t)d.frames * d.H * d.W * (int64_t)d.Cin * 4 >= (int64_t)1 << 40 || (int64_t)d.frames * d.H * d.W >= (int64_t)1 << 30)
+    return hipErrorNotSupported;
+  if (d.frames <= 0) return hipSuccess;
+  return d.src == 3 ? run_ws<5, true>(s, d) : run_ws<5, false>(s, d);
+}
+
+}  // namespace lc

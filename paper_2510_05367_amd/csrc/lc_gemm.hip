@@ -689,6 +689,10 @@ hipError_t launch_fused(hipStream_t s, const FusedDesc& d) {
     return hipErrorInvalidValue;
   if (d.Cin % (kRow / esz) != 0) return hipErrorInvalidValue;
   if (d.src == 3 && (d.Cs % (kRow / esz) != 0 || d.Cs <= 0 || d.Cs >= d.Cin || (d.H | d.W) & 1)) return hipErrorInvalidValue;
+  if (d.taps == 9) {  // the kernel with specialised wavefronts where the stage's widths suit it
+    const hipError_t e = launch_conv_ws(s, d);
+    if (e != hipErrorNotSupported) return e;
+  }
   return d.dt == kBF16 ? by_kind<bf16_t>(s, d) : by_kind<float>(s, d);
 }
 

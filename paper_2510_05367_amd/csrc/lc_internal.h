@@ -104,6 +104,9 @@ inline float attn_q_scale(int head_dim) { return 1.4426950408889634f / sqrtf((fl
 // splits per frame of the statistics a 3x3 launch writes
 inline int conv_stat_splits(int H, int W) { return 4 * ((W + 15) / 16) * ((H + 7) / 8); }
 hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
+// taps == 9 of a bf16 stage with specialised wavefronts (lc_convws.hip): the same results as the general
+// kernel bit for bit; hipErrorNotSupported for shapes it does not cover. launch_fused tries it first.
+hipError_t launch_conv_ws(hipStream_t s, const FusedDesc& d);
 // taps == 1 with the weights resident in registers (needs w_frag); hipErrorNotSupported for shapes it does not cover
 hipError_t launch_linear(hipStream_t s, const FusedDesc& d);
 inline hipError_t launch_linear_any(hipStream_t s, const FusedDesc& d) {
