@@ -241,8 +241,10 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // the two pixels of this lane inside the tile and their halo rows for tap (0,0)
-  const int p0 = pxh * 64 + lp, p1 = p0 + 32;
+  // the two pixels of this lane inside the tile and their halo rows for tap (0,0). Tile column 0 of the
+  // accumulators is the one this wavefront finishes after the K halves are folded, column 1 the one its
+  // partner (pxh, kh ^ 1) finishes: which 32 pixels that is depends on kh, the code that follows does not.
+  const int p0 = pxh * 64 + kh * 32 + lp, p1 = pxh * 64 + (kh ^ 1) * 32 + lp;
   const int xr0 = (p0 >> 4) * kwHaloW + (p0 & 15);
   const int xr1 = (p1 >> 4) * kwHaloW + (p1 & 15);
   const int xoff0 = xr0 * kwLds + hh * 16 + kh * (KI / 2) * KB;
@@ -327,7 +329,7 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(63));      // no LDS read of this wavefront is in flight when the tiles are reused
 
   // ---------------- fold the two K halves and write out ----------------
-  // The wavefront (pxh, kh) keeps the 32-pixel tiles j = kh, hands the others to its partner through LDS,
+  // The wavefront (pxh, kh) keeps its tile column 0 (pixels kh * 32 ..+31 of its 64), hands column 1 to its partner through LDS,
   // then turns each finished 32 x 32 tile through a private LDS patch so that a lane stores 16 bytes
   // of one pixel row and eight lanes cover its 128 contiguous bytes (the accumulator layout would
   // store 16-byte pieces of 32 different rows per instruction). Bias and residual are added in that
@@ -338,15 +340,10 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
   float* patch = reinterpret_cast<float*>(smem + 4 * CO_T * kTile * 4) + wid * (32 * 36);
   static_assert(ws_lds_bytes<CO_T>() >= 4 * CO_T * kTile * 4 + 4 * 32 * 36 * 4, "hand-over area + patches");
   const int prow = lane >> 3, pcol = (lane & 7) * 4;  // patch read-back: rows prow + 8 k, channels pcol..pcol+3
-  auto hand_over = [&](auto jc) {  // jc: the tile column this wavefront gives away
-    constexpr int J = decltype(jc)::value;
 #pragma unroll
-    for (int i = 0; i < CO_T; ++i)
+  for (int i = 0; i < CO_T; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) give[(i * 16 + r) * 64 + lane] = acc[i][J][r];
-  };
-  if (kh == 0) hand_over(std::integral_constant<int, 1>{});
-  else hand_over(std::integral_constant<int, 0>{});
+    for (int r = 0; r < 16; ++r) give[(i * 16 + r) * 64 + lane] = acc[i][1][r];
   int64_t obase[4];
   bool okk[4];
 #pragma unroll
@@ -357,7 +354,7 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
     obase[k] = okk[k] ? (((int64_t)frame * a.H + oy) * a.W + ox) * a.Cout + co0 + pcol : 0;
   }
   const float* R = a.res;
-  // residual and bias of one 32-channel tile, requested one tile ahead of its use
+  // residual and bias of one 32-channel tile
   struct Side { f32x4 r[4]; f32x4 b; };
   auto load_side = [&](int i, Side& sd) {
     sd.b = a.bias ? *reinterpret_cast<const f32x4*>(a.bias + co0 + i * 32 + pcol) : f32x4{0.f, 0.f, 0.f, 0.f};
@@ -365,20 +362,22 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
     for (int k = 0; k < 4; ++k)
       sd.r[k] = (R && okk[k]) ? *reinterpret_cast<const f32x4*>(R + obase[k] + i * 32) : f32x4{0.f, 0.f, 0.f, 0.f};
   };
-  Side side[2];
-  load_side(0, side[0]);
+  // all tiles at once: the given-away half of the accumulators is dead by now, so the registers are there,
+  // and one memory latency (hidden behind the hand-over barrier) is paid instead of one per tile
+  asm volatile("" ::: "memory");  // (the requests stay below the hand-over: above it they would not fit)
+  Side side[CO_T];
+#pragma unroll
+  for (int i = 0; i < CO_T; ++i) load_side(i, side[i]);
   __syncthreads();
   float* Y = a.y;
-  auto finish = [&](auto jc) {  // jc: the tile column this wavefront keeps
-    constexpr int J = decltype(jc)::value;
+  {
 #pragma unroll
     for (int i = 0; i < CO_T; ++i) {
-      if (i + 1 < CO_T) load_side(i + 1, side[(i + 1) & 1]);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][J][g * 4 + e] + take[(i * 16 + g * 4 + e) * 64 + lane];
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][0][g * 4 + e] + take[(i * 16 + g * 4 + e) * 64 + lane];
         *reinterpret_cast<f32x4*>(patch + lp * 36 + g * 8 + hh * 4) = v;
       }
       // the patch is private to this wavefront, whose LDS operations complete in order
@@ -389,8 +388,8 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         f32x4 v = *reinterpret_cast<const f32x4*>(patch + (prow + 8 * k) * 36 + pcol);
-        v += side[i & 1].b;
-        v += side[i & 1].r[k];
+        v += side[i].b;
+        v += side[i].r[k];
         if (okk[k]) {
           *reinterpret_cast<f32x4*>(Y + obase[k] + i * 32) = v;
 #pragma unroll
@@ -421,9 +420,7 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
     }
-  };
-  if (kh == 0) finish(std::integral_constant<int, 0>{});
-  else finish(std::integral_constant<int, 1>{});
+  }
 }
 
 template <int CO_T, bool CAT>
