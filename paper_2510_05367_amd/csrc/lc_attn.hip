@@ -45,11 +45,26 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
 
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int lq = lane & 31, hh = lane >> 5;
-  const int head = blockIdx.y, frame = blockIdx.z;
+  // Workgroups are handed to the eight XCDs round robin in launch order, and each XCD has an L2 of its
+  // own. All query blocks of one (frame, head) stream the same keys and values, so they are mapped to one
+  // XCD (problem p on XCD p % 8): its L2 then fetches that K / V once instead of every XCD fetching all of
+  // them. Needs the number of problems to be a multiple of eight; otherwise the plain mapping.
+  int qb = blockIdx.x, head = blockIdx.y, frame = blockIdx.z;
+  {
+    const int nqb = gridDim.x, heads = gridDim.y, nprob = gridDim.y * gridDim.z;
+    if (nprob % 8 == 0) {
+      const int lin = blockIdx.x + nqb * (blockIdx.y + heads * blockIdx.z);
+      const int xcd = lin & 7, slot = lin >> 3;
+      const int prob = xcd + 8 * (slot / nqb);
+      qb = slot % nqb;
+      head = prob % heads;
+      frame = prob / heads;
+    }
+  }
   const int ld = ldq;
   const T* __restrict__ base = qk + (int64_t)frame * T_tok * ld + head * D;
   const T* __restrict__ vbase = vt + ((int64_t)frame * C + head * D) * Tp;
-  const int qblk = q0 + blockIdx.x * (4 * NQT * 32) + wid * (NQT * 32);
+  const int qblk = q0 + qb * (4 * NQT * 32) + wid * (NQT * 32);
 
   // zero both buffers once: K columns beyond D and V^T rows beyond D feed padded MFMA lanes
   for (int i = tid; i < 2 * KBYTES / 4; i += 256) reinterpret_cast<uint32_t*>(&k_lds[0][0])[i] = 0u;
