@@ -25,7 +25,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   int fc, tc, qc;  // effective frame chunk, temporal position chunk, spatial query chunk
-  size_t off_h, off_slots, slot_bytes, off_partH, off_partT, off_partU, off_partD, partD_bytes, off_scale, off_shift, off_ws,
+  size_t off_h, off_slots, slot_bytes, off_partH, off_partT, off_partU, off_partD, partD_bytes, off_scale, off_shift, off_scale_cat,
+      off_shift_cat, off_ws,
       ws_bytes, total;
   size_t lane_off, lane_stride;  // [lane_off, lane_off + lane_stride): the scratch one lane works in (see use_lane)
 };
@@ -153,6 +154,10 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   p.off_partU = off; off += align_up((size_t)N * sp * g.C * 2 * sizeof(float));
   p.partD_bytes = align_up((size_t)N * stat_splits((int)(T / 4)) * g.C_deep * 2 * sizeof(float));
   p.off_partD = off; off += p.partD_bytes * (g.dev_slots + 1);
+  // scale / shift of the concatenated tensor of the up block for all frames: once the skip feature is
+  // complete one launch folds them, instead of one launch at the head of every frame chunk
+  p.off_scale_cat = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
+  p.off_shift_cat = off; off += align_up((size_t)N * (g.C + g.C_deep) * sizeof(float));
   // what a chunk works in - partH, scale / shift, the chunk scratch - exists once per lane: a chunked
   // step runs alternate chunks on two streams
   p.lane_off = off;
@@ -363,10 +368,23 @@ lc_status res_block(lc_ctx* c, const GnW& gn, const ConvW& cw, int Cn, int frame
 // u = conv3x3(SiLU(GN(Concat(skip, up2(deep))))). `skip_st`: partial sums of the skip feature if its
 // producer wrote them; `deep_part`: those of the deep feature ([frame][stat_splits(T/4)][Cd][2]) if
 // already known, else they are computed into the scratch region; `out` receives those of u.
+// `sc`, `sh`: scale / shift of these frames if already folded (then the partial sums are not looked at).
 lc_status up_conv(lc_ctx* c, const void* skip, const void* deep, void* u, int frames, StatRef skip_st = StatRef{nullptr, 0},
-                  const float* deep_part = nullptr, StatRef* out = nullptr) {
+                  const float* deep_part = nullptr, StatRef* out = nullptr, const float* sc = nullptr,
+                  const float* sh = nullptr) {
   const lc_config& g = c->cfg;
   const int T = g.H * g.W, C = g.C, Cd = g.C_deep;
+  if (sc && sh) {
+    FusedDesc d = fconv_desc(c, c->pw.up, C + Cd, C, frames, g.H, g.W, skip, nullptr, u, 1);
+    d.src = 3; d.x2 = deep; d.Cs = C; d.scale = sc; d.shift = sh;
+    if (out) {
+      d.stat = partH(c);
+      d.stat_splits = conv_stat_splits(g.H, g.W);
+      *out = StatRef{d.stat, d.stat_splits};
+    }
+    LC_LAUNCH(c, LC_K_CONV_UP, launch_fused(c->cs, d));
+    return LC_OK;
+  }
   if (!skip_st.part) {
     LC_LAUNCH(c, LC_K_GN_STATS, launch_gn_stats(c->cs, kF32, skip, partH(c), frames, T, C));
     skip_st = StatRef{partH(c), stat_splits(T)};
@@ -552,6 +570,16 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
   }
 
   // ---- shallow up branch U_m on Concat(skip, up2(deep)), per frame chunk
+  // with the partial sums of the whole skip feature at hand, its GroupNorm is folded for all frames at once
+  float* sc_cat = nullptr;
+  float* sh_cat = nullptr;
+  if (ustat) {
+    sc_cat = (float*)(c->arena + p.off_scale_cat);
+    sh_cat = (float*)(c->arena + p.off_shift_cat);
+    LC_LAUNCH(c, LC_K_GN_FINAL,
+              launch_gn_finalize(c->cs, partU(c), C, T / 32, T, 1.f, partD(c, slot), Cd, stat_splits(T / 4), T / 4, 4.f,
+                                 w.up_gn.gamma, w.up_gn.beta, g.groups, g.gn_eps, sc_cat, sh_cat, N));
+  }
   if (frame_lanes > 1) { lc_status s = fork_lanes(c); if (s != LC_OK) return s; }
   for (int n0 = 0, ci = 0; n0 < N; n0 += p.fc, ++ci) {
     use_lane(c, ci % frame_lanes);
@@ -561,7 +589,8 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
     char* u = ws_ptr(c);  // fp32
     StatRef ust{nullptr, 0};
     lc_status s = up_conv(c, hc, dc, u, nf, ustat ? StatRef{partU(c) + (size_t)n0 * (T / 32) * C * 2, T / 32} : StatRef{nullptr, 0},
-                          partD(c, slot) + (size_t)n0 * stat_splits(T / 4) * Cd * 2, &ust);
+                          partD(c, slot) + (size_t)n0 * stat_splits(T / 4) * Cd * 2, &ust,
+                          sc_cat ? sc_cat + (size_t)n0 * (C + Cd) : nullptr, sh_cat ? sh_cat + (size_t)n0 * (C + Cd) : nullptr);
     if (s != LC_OK) return s;
     s = conv_out(c, u, (char*)eps + (size_t)n0 * g.C_lat * T * es, nf, ust);
     if (s != LC_OK) return s;
