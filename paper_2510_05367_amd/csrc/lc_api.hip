@@ -32,7 +32,7 @@ struct Plan {
 };
 
 struct GnW { float *gamma, *beta; };
-struct ConvW { void* w; float* b; };
+struct ConvW { void* w; float* b; void* wt; };  // wt: tile order for the specialised conv kernel, or nullptr
 struct AttnW { GnW gn; void* wqkv; void* wo; float* bo; void* wqkv_f; void* wo_f; };  // *_f: fragment order
 struct Packed {
   float* cin_w; float* cin_b;
@@ -306,7 +306,7 @@ FusedDesc fconv_desc(lc_ctx* c, const ConvW& w, int Cin, int Cout, int frames, i
   FusedDesc d;
   memset(&d, 0, sizeof d);
   d.dt = c->cfg.dtype; d.y_f32 = y_f32; d.taps = 9; d.src = 2; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
-  d.w = w.w; d.bias = w.b; d.frames = frames; d.H = H; d.W = W; d.x = x; d.scale = scale_p(c); d.shift = shift_p(c);
+  d.w = w.w; d.w_tiles = w.wt; d.bias = w.b; d.frames = frames; d.H = H; d.W = W; d.x = x; d.scale = scale_p(c); d.shift = shift_p(c);
   d.res = res; d.y = y; d.in_map = dense_map(); d.out_map = dense_map();
   return d;
 }
@@ -766,6 +766,13 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
     o_res_g[i] = take((size_t)C * 4); o_res_b[i] = take((size_t)C * 4);
     o_res_w[i] = take((size_t)C * 9 * C * es); o_res_bias[i] = take((size_t)C * 4);
   }
+  // a second copy of the big 3x3 weights in the tile order the specialised-wavefront kernel streams
+  const bool tiles = dt == kBF16 && C % 160 == 0 && C % 64 == 0 && (C + Cd) % 64 == 0;
+  size_t o_res_wt[LC_MAX_RES] = {0}, o_up_wt = 0;
+  if (tiles) {
+    for (int i = 0; i < g.n_res; ++i) o_res_wt[i] = take((size_t)C * 9 * C * es);
+    o_up_wt = take((size_t)C * 9 * (C + Cd) * es);
+  }
   size_t o_at[2][7];
   for (int k = 0; k < 2; ++k) {
     o_at[k][0] = take((size_t)C * 4); o_at[k][1] = take((size_t)C * 4);
@@ -803,7 +810,11 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
     F32(w->res[i].gn_g, o_res_g[i], C, C); F32(w->res[i].gn_b, o_res_b[i], C, C);
     CW(w->res[i].w, o_res_w[i], C, C, 9, C); F32(w->res[i].b, o_res_bias[i], C, C);
     p.res_gn[i] = GnW{(float*)(b + o_res_g[i]), (float*)(b + o_res_b[i])};
-    p.res[i] = ConvW{b + o_res_w[i], (float*)(b + o_res_bias[i])};
+    p.res[i] = ConvW{b + o_res_w[i], (float*)(b + o_res_bias[i]), nullptr};
+    if (tiles) {
+      LC_HIP(c, launch_pack_conv_w_tiles(s, dt, b + o_res_w[i], b + o_res_wt[i], C, C));
+      p.res[i].wt = b + o_res_wt[i];
+    }
   }
   const lc_attn_w* aw[2] = {&w->sattn, &w->tattn};
   AttnW* ap[2] = {&p.sattn, &p.tattn};
@@ -821,19 +832,23 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
                    (float*)(b + o_at[k][4]), b + o_at[k][5], b + o_at[k][6]};
   }
   CW(w->down_w, o_down_w, Cd, C, 9, Cd); F32(w->down_b, o_down_b, Cd, Cd);
-  p.down = ConvW{b + o_down_w, (float*)(b + o_down_b)};
+  p.down = ConvW{b + o_down_w, (float*)(b + o_down_b), nullptr};
   F32(w->dres.gn_g, o_dres_g, Cd, Cd); F32(w->dres.gn_b, o_dres_b, Cd, Cd);
   CW(w->dres.w, o_dres_w, Cd, Cd, 9, Cd); F32(w->dres.b, o_dres_bias, Cd, Cd);
   p.dres_gn = GnW{(float*)(b + o_dres_g), (float*)(b + o_dres_b)};
-  p.dres = ConvW{b + o_dres_w, (float*)(b + o_dres_bias)};
+  p.dres = ConvW{b + o_dres_w, (float*)(b + o_dres_bias), nullptr};
   F32(w->up.gn_g, o_up_g, C + Cd, C + Cd); F32(w->up.gn_b, o_up_b, C + Cd, C + Cd);
   CW(w->up.w, o_up_w, C, C + Cd, 9, C); F32(w->up.b, o_up_bias, C, C);
   p.up_gn = GnW{(float*)(b + o_up_g), (float*)(b + o_up_b)};
-  p.up = ConvW{b + o_up_w, (float*)(b + o_up_bias)};
+  p.up = ConvW{b + o_up_w, (float*)(b + o_up_bias), nullptr};
+  if (tiles) {
+    LC_HIP(c, launch_pack_conv_w_tiles(s, dt, b + o_up_w, b + o_up_wt, C, C + Cd));
+    p.up.wt = b + o_up_wt;
+  }
   F32(w->out.gn_g, o_out_g, C, C); F32(w->out.gn_b, o_out_b, C, C);
   CW(w->out.w, o_out_w, Cl, C, 9, 32); F32(w->out.b, o_out_bias, Cl, 32);
   p.out_gn = GnW{(float*)(b + o_out_g), (float*)(b + o_out_b)};
-  p.out = ConvW{b + o_out_w, (float*)(b + o_out_bias)};
+  p.out = ConvW{b + o_out_w, (float*)(b + o_out_bias), nullptr};
 #undef F32
 #undef CW
   LC_HIP(c, hipStreamSynchronize(s));

@@ -38,11 +38,11 @@ struct WsArgs {
   const bf16_t* x2;     // concat: cached deep feature [frames][H/2][W/2][Cin - Cs]
   const float* scale;   // [frames][Cin]
   const float* shift;
-  const bf16_t* w;      // [Cout][9 * Cin]
+  const bf16_t* w;      // tiles [Cout / 160][9 * Cin / 64][160][64]: one step's block is contiguous
   const float* bias;    // [Cout] or nullptr
   const float* res;     // fp32, indexed like y, or nullptr
   float* y;             // fp32 [frames][H][W][Cout]
-  int Cin, Cs, Cout, ldw;
+  int Cin, Cs, Cout;
   int H, W, tiles_x, tiles_y;
   float* stat;          // per-channel sums of the output per 32-pixel split, or nullptr
   int stat_splits;
@@ -51,17 +51,14 @@ struct WsArgs {
 template <int CO_T>
 constexpr int ws_lds_bytes() { return kwBuf * CO_T * 32 * kwRow + 2 * kwHaloRows * kwLds; }
 
-// vector-memory loads a loader thread issues in tap t of a slab: scale/shift at tap 0 and a halo
-// packet at taps < kwXR when a next slab follows (`more`), then the weights of step s + kwAhead if
-// there is one. t < 0 is a late tap of the slab before (weights only).
-constexpr int ws_tap_loads(int t, bool more, int n_pkt, int wp) {
-  if (t < 0) return wp;
-  return (more && t == 0 ? 4 + kwXR * n_pkt : 0) + ((more || t + kwAhead < 9) ? wp : 0);
-}
-// loads younger than the weights of step s + kwLead at the end of tap `tap`: those of the last kwAhead - kwLead taps
-constexpr int ws_tap_keep(int tap, bool more, int n_pkt, int wp) {
+// weight requests a contracting wavefront has issued in the last kwAhead - kwLead steps, seen from the end of
+// tap `tap`: wp per step, none in the steps of the last slab whose tile would lie behind the end
+constexpr int ws_younger(int tap, bool last, int wp) {
   int n = 0;
-  for (int j = 0; j < kwAhead - kwLead; ++j) n += ws_tap_loads(tap - j, more, n_pkt, wp);
+  for (int j = 0; j < kwAhead - kwLead; ++j) {
+    const int t = tap - j;
+    n += (!last || t < 0 || t + kwAhead < 9) ? wp : 0;
+  }
   return n;
 }
 
@@ -72,7 +69,7 @@ template <int CO_T, bool CAT>
 __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
   typedef Mma32<bf16_t> M;
   constexpr int BCO = CO_T * 32;
-  constexpr int WP = BCO * 8 / 256;  // weight DMA instructions per loader thread per step
+  constexpr int WP = BCO * 8 / 256;  // weight DMA instructions per contracting wavefront per step
   constexpr int KI = 4;              // MFMA k-steps per 64-channel row
   constexpr int KB = 32;             // bytes of one k-step in a row
   static_assert((BCO * 8) % 256 == 0, "whole wavefront instructions");
@@ -94,7 +91,7 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
 
   if (wid >= 4) {
     // =========================== loader wavefronts ===========================
-    const int lt = tid - 256, lw = wid - 4;
+    const int lt = tid - 256;
     const int kp = lt & 7, lrow = lt >> 3;  // this thread moves 16-byte packet kp of halo rows lrow + 32 r
     // halo rows of this thread: source pixel (clamped; out-of-image taps become zero after the activation)
     int pix[kwXR], dpix[kwXR];
@@ -115,25 +112,6 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
     const int ldd = a.Cin - a.Cs;
     const float* __restrict__ scb = a.scale + (int64_t)frame * a.Cin + kp * 8;
     const float* __restrict__ shb = a.shift + (int64_t)frame * a.Cin + kp * 8;
-    // weights: global -> LDS directly. A wavefront instruction moves 8 rows x 128 bytes; packet c of row r
-    // is parked in slot c ^ ((r >> 1) & 7) of that row (conflict-free fragment reads without padding).
-    // Instruction i covers rows (4 i + lw) * 8 ..+7; the slot key does not depend on i.
-    const int l8 = lane >> 3;
-    const int wr0 = lw * 8 + l8;
-    const int wc = (lane & 7) ^ ((wr0 >> 1) & 7);
-    const bf16_t* __restrict__ wsrc = a.w + (int64_t)(co0 + wr0) * a.ldw + wc * 8;
-    auto dma_w = [&](int step, int buf) {
-      const int slab = step / 9, tap = step - slab * 9;
-      const bf16_t* src = wsrc + tap * a.Cin + slab * 64;
-#pragma unroll
-      for (int i = 0; i < WP; ++i) {
-#ifdef __HIP_DEVICE_COMPILE__  // the host pass only needs the kernel's stub; it does not know this builtin
-        __builtin_amdgcn_global_load_lds(src + (int64_t)i * 32 * a.ldw, w_lds(buf) + (i * 4 + lw) * 1024, 16, 0, 0);
-#else
-        (void)src;
-#endif
-      }
-    };
     struct XRaw { f32x4 q[2]; };
     struct Affine { f32x4 sc[2], sh[2]; };
     auto load_affine = [&](int slab, Affine& af) {
@@ -175,9 +153,7 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
     const std::true_type yes_c{};
     Affine aff;
     XRaw xin[kwXR];  // the packets of the next slab are all requested at tap 0; packet r is consumed at tap r + kwFin
-    // ---- prologue: weights of the first steps, halo of slab 0 (never in the deep part)
-#pragma unroll
-    for (int j = 0; j < kwAhead; ++j) dma_w(j, j);
+    // ---- prologue: halo of slab 0 (never in the deep part)
     load_affine(0, aff);
     {
       XRaw x0[kwXR];
@@ -186,19 +162,15 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
 #pragma unroll
       for (int r = 0; r < kwXR; ++r) finish_x(0, r, x0[r], aff, no_c);
     }
-    barrier_keep<(kwAhead - kwLead) * WP>();  // the weights of the first kwLead steps have landed, later ones may be on their way
+    barrier_keep<63>();
 
-    // ---- main loop. The number of loads per tap is fixed at compile time (the loop is split by where
-    // the next slab comes from instead of branching), so the wait before each barrier is an exact count
-    // of younger loads: the weights of step s + 1 must have landed, nothing else is waited for.
+    // ---- main loop: the packets of the next slab are requested at its first tap and finished one per tap
+    // from tap kwFin on, so that the tile is complete one barrier before the slab ends. The waits for the
+    // packets are the compiler's; the barriers only order the LDS stores.
     auto slab_body = [&](int slab, auto more_c, auto deep_c) {
       constexpr bool MORE = decltype(more_c)::value;
-      constexpr bool DEEPC = decltype(deep_c)::value;
-      constexpr int n_pkt = DEEPC ? 1 : 2;
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap) {
-        const int s = slab * 9 + tap;
-        __builtin_amdgcn_sched_barrier(0);
         if (MORE) {
           if (tap == 0) load_affine(slab + 1, aff);
           if (tap == 0) {
@@ -206,17 +178,9 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
             for (int r = 0; r < kwXR; ++r) fetch_x(slab + 1, r, xin[r], deep_c);
           }
         }
-        if (MORE || tap + kwAhead < 9) dma_w(s + kwAhead, (s + kwAhead) % kwBuf);
-        __builtin_amdgcn_sched_barrier(0);
         if (MORE && tap >= kwFin && tap - kwFin < kwXR)
           finish_x((slab + 1) & 1, tap - kwFin, xin[tap - kwFin], aff, deep_c);
-        __builtin_amdgcn_sched_barrier(0);
-#define LC_KEEP(TAP) \
-  case TAP: barrier_keep<ws_tap_keep(TAP, MORE, n_pkt, WP)>(); break;
-        switch (tap) {  // `tap` is a constant once the loop is unrolled
-          LC_KEEP(0) LC_KEEP(1) LC_KEEP(2) LC_KEEP(3) LC_KEEP(4) LC_KEEP(5) LC_KEEP(6) LC_KEEP(7) LC_KEEP(8)
-        }
-#undef LC_KEEP
+        barrier_keep<63>();
       }
     };
     static_assert(kwXR - 1 + kwFin < 8, "the halo of the next slab is complete one barrier before the slab ends");
@@ -256,6 +220,29 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
     const int wb = hh * 16 + (kh * (KI / 2) + kk) * KB;
     wofs[kk] = lp * kwRow + ((((wb >> 4) ^ wkey) << 4) | (wb & 15));
   }
+  // weights: global -> LDS directly, kwAhead steps ahead, requested by the contracting wavefronts themselves
+  // (their stream has room between the MFMAs, and the loaders then never wait for memory on the
+  // contracting wavefronts' behalf). A wavefront instruction moves 8 rows x 128 bytes; packet c of row r is
+  // parked in slot c ^ ((r >> 1) & 7) of that row (conflict-free fragment reads without padding).
+  // Instruction i covers rows (4 i + wid) * 8 ..+7 (1 KB of contiguous memory in the tile order of the
+  // weights); the slot key does not depend on i.
+  const int l8 = lane >> 3;
+  const int wr0 = wid * 8 + l8;
+  const int wc = (lane & 7) ^ ((wr0 >> 1) & 7);
+  const bf16_t* __restrict__ wsrc = a.w + ((int64_t)blockIdx.y * (9 * nslab) * BCO + wr0) * 64 + wc * 8;
+  auto dma_w_one = [&](const bf16_t* src, unsigned char* tile, int i) {  // instruction i of the WP that move one tile
+#ifdef __HIP_DEVICE_COMPILE__  // the host pass only needs the kernel's stub; it does not know this builtin
+    __builtin_amdgcn_global_load_lds(src + i * 32 * 64, tile + (i * 4 + wid) * 1024, 16, 0, 0);
+#else
+    (void)src; (void)tile;
+#endif
+  };
+  auto w_src = [&](int step) { return wsrc + (int64_t)step * (BCO * 64); };
+  // at most `VM` vector-memory operations outstanding; LDS reads are not waited for
+  auto wait_vm = [&](auto vm_c) {
+    constexpr int VM = decltype(vm_c)::value;
+    __builtin_amdgcn_s_waitcnt((VM & 15) | (7 << 4) | (15 << 8) | ((VM >> 4) << 14));
+  };
   constexpr int NF = (KI / 2) * CO_T;  // weight fragments of a tap for this wavefront
   static_assert(NF % (kwFA + 1) == 0, "a fragment's place in the ring does not depend on the tap");
   // The fragment stream runs ahead of the MFMAs across the taps: while the pairs of step s are issued
@@ -274,7 +261,9 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
   };
   // one step: `wl` / `wl_next` the weight tiles of this and the next step, `xbuf_next` / `tap_next` where the
   // next step reads its activations
-  auto compute = [&](const unsigned char* wl, const unsigned char* wl_next, int xbuf_next, int tap_next) {
+  // `dma_c`: the weights of step s + kwAhead exist and are requested, one instruction behind each of the first MFMA pairs
+  auto compute = [&](const unsigned char* wl, const unsigned char* wl_next, int xbuf_next, int tap_next, auto dma_c,
+                     const bf16_t* dsrc, unsigned char* dtile) {
     const unsigned char* xn0 = x_ptr(xbuf_next, tap_next, 0);
     const unsigned char* xn1 = x_ptr(xbuf_next, tap_next, 1);
 #pragma unroll
@@ -290,6 +279,9 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
       const int kk = idx / CO_T, i = idx - kk * CO_T;
       M::mma(wf[idx % (kwFA + 1)], xf[kk][0], acc[i][0]);
       M::mma(wf[idx % (kwFA + 1)], xf[kk][1], acc[i][1]);
+      if constexpr (decltype(dma_c)::value) {
+        if (idx < WP) dma_w_one(dsrc, dtile, idx);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
@@ -300,13 +292,21 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
   };
   // a barrier that does not wait for this wavefront's LDS reads: those in flight are the requests for
   // the next step, whose tiles nobody writes before a later barrier
-  auto step_barrier = [&]() {
+  // Before it the weights of step s + kwLead must have landed: they were requested kwAhead - kwLead steps
+  // ago, younger are the requests of the steps since (`VM` of them: this wavefront issues nothing else).
+  auto step_barrier = [&](auto vm_c) {
     asm volatile("" ::: "memory");
+    wait_vm(vm_c);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
+  static_assert(NF >= WP, "one request behind each of the first MFMA pairs");
 
-  barrier_keep<63>();  // prologue: halo of slab 0 and the weights of the first kwLead steps are in LDS
+#pragma unroll
+  for (int j = 0; j < kwAhead; ++j)  // nsteps >= 9 > kwAhead
+#pragma unroll
+    for (int i = 0; i < WP; ++i) dma_w_one(w_src(j), w_lds(j), i);
+  barrier_keep<(kwAhead - kwLead) * WP>();  // prologue: halo of slab 0 and the weights of the first kwLead steps are in LDS
 #pragma unroll
   for (int kk = 0; kk < KI / 2; ++kk) {
     xf[kk][0] = M::load((const bf16_t*)(x_ptr(0, 0, 0) + kk * KB));
@@ -314,17 +314,36 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
   }
 #pragma unroll
   for (int idx = 0; idx < kwFA; ++idx) wf[idx] = wload(w_lds(0), idx);
-  int wb = 0;  // weight tile of the current step
-  for (int slab = 0; slab < nslab; ++slab) {
+  int wb = 0;                  // weight tile of the current step
+  int wd = kwAhead % kwBuf;    // weight tile the requests of the current step go to
+  const std::true_type dma_yes{};
+  const std::false_type dma_no{};
+  auto slab_steps = [&](int slab, auto last_c) {
+    constexpr bool LAST = decltype(last_c)::value;
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
       const int wb_next = wb + 1 == kwBuf ? 0 : wb + 1;
-      // (behind the last step the requests read tiles that hold nothing new: in bounds, never used)
-      compute(w_lds(wb), w_lds(wb_next), tap < 8 ? (slab & 1) : ((slab + 1) & 1), tap < 8 ? tap + 1 : 0);
+      const int xb_next = tap < 8 ? (slab & 1) : ((slab + 1) & 1), tap_next = tap < 8 ? tap + 1 : 0;
+      // (behind the last step the fragment requests read tiles that hold nothing new: in bounds, never used)
+      if (!LAST || tap + kwAhead < 9) {
+        compute(w_lds(wb), w_lds(wb_next), xb_next, tap_next, dma_yes, w_src(slab * 9 + tap + kwAhead), w_lds(wd));
+        wd = wd + 1 == kwBuf ? 0 : wd + 1;
+      } else {
+        compute(w_lds(wb), w_lds(wb_next), xb_next, tap_next, dma_no, nullptr, nullptr);
+      }
+      // requests of the last kwAhead - kwLead steps (a step before this slab always issued; in the last slab
+      // the steps whose tile would lie behind the end issue none)
+      switch (tap) {  // `tap` is a constant once the loop is unrolled
+#define LC_VM(TAP) \
+  case TAP: step_barrier(std::integral_constant<int, ws_younger(TAP, LAST, WP)>{}); break;
+        LC_VM(0) LC_VM(1) LC_VM(2) LC_VM(3) LC_VM(4) LC_VM(5) LC_VM(6) LC_VM(7) LC_VM(8)
+#undef LC_VM
+      }
       wb = wb_next;
-      step_barrier();
     }
-  }
+  };
+  for (int slab = 0; slab + 1 < nslab; ++slab) slab_steps(slab, std::false_type{});
+  slab_steps(nslab - 1, std::true_type{});
   asm volatile("" :: "v"(xf[0][0]), "v"(wf[0]));  // (the requests behind the last step have no other reader)
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(63));      // no LDS read of this wavefront is in flight when the tiles are reused
 
@@ -435,8 +454,8 @@ static hipError_t run_ws(hipStream_t s, const FusedDesc& d) {
   }
   WsArgs a;
   a.x = (const float*)d.x; a.x2 = (const bf16_t*)d.x2; a.scale = d.scale; a.shift = d.shift;
-  a.w = (const bf16_t*)d.w; a.bias = d.bias; a.res = (const float*)d.res; a.y = (float*)d.y;
-  a.Cin = d.Cin; a.Cs = d.Cs; a.Cout = d.Cout; a.ldw = 9 * d.Cin;
+  a.w = (const bf16_t*)d.w_tiles; a.bias = d.bias; a.res = (const float*)d.res; a.y = (float*)d.y;
+  a.Cin = d.Cin; a.Cs = d.Cs; a.Cout = d.Cout;
   a.H = d.H; a.W = d.W; a.tiles_x = (d.W + 15) / 16; a.tiles_y = (d.H + 7) / 8;
   a.stat = d.stat; a.stat_splits = d.stat_splits;
   dim3 grid((unsigned)(a.tiles_x * a.tiles_y * d.frames), d.Cout / (CO_T * 32));
@@ -447,7 +466,7 @@ static hipError_t run_ws(hipStream_t s, const FusedDesc& d) {
 // The 3x3 convolutions of a bf16 stage whose widths suit the kernel above (a property of the stage,
 // never of how it is chunked); hipErrorNotSupported otherwise.
 hipError_t launch_conv_ws(hipStream_t s, const FusedDesc& d) {
-  if (d.dt != kBF16 || d.taps != 9 || !d.y_f32 || d.planar_out || d.yt || d.q_cols) return hipErrorNotSupported;
+  if (d.dt != kBF16 || d.taps != 9 || !d.y_f32 || d.planar_out || d.yt || d.q_cols || !d.w_tiles) return hipErrorNotSupported;
   if (d.src != 2 && d.src != 3) return hipErrorNotSupported;
   if (d.Cout % 160 != 0 || d.Cout_store != d.Cout || d.Cin % 64 != 0) return hipErrorNotSupported;
   if (d.src == 3 && (d.Cs % 64 != 0 || d.Cs <= 0 || d.Cs >= d.Cin || ((d.H | d.W) & 1))) return hipErrorNotSupported;

@@ -70,6 +70,8 @@ struct FusedDesc {
                  //    resolution, nearest 2x upsampled), then as 2
   int Cin, Cs, Cout, Cout_store;
   const void* w;       // [Cout][taps*Cin]
+  const void* w_tiles; // taps == 9, optional: the same weights in the order of launch_pack_conv_w_tiles (what the
+                       // specialised-wavefront kernel reads; without it the general kernel runs)
   const void* w_frag;  // taps == 1: the same matrix in MFMA fragment order (launch_pack_lin_w), or nullptr
   const float* bias;   // [Cout] or nullptr
   int frames, H, W;    // taps == 9
@@ -139,6 +141,8 @@ hipError_t launch_cl_to_planar(hipStream_t s, int dt, const void* src, void* dst
 hipError_t launch_pack_conv_w(hipStream_t s, int dt, const void* w, void* packed, int Cout, int Cin, int taps,
                               int Cout_padded);  // [Cout][Cin][taps] -> [Cout_padded][taps][Cin]
 hipError_t launch_pack_conv_in_w(hipStream_t s, int dt, const void* w, float* packed, int C, int Cl);
+// packed [Cout][9*Cin] -> tiles [Cout/160][9*Cin/64][160][64] (bf16; Cout % 160 == 0, Cin % 64 == 0)
+hipError_t launch_pack_conv_w_tiles(hipStream_t s, int dt, const void* w, void* tiles, int Cout, int Cin);
 // w[Cout][Cin] -> MFMA fragment order for launch_linear
 hipError_t launch_pack_lin_w(hipStream_t s, int dt, const void* w, void* out, int Cout, int Cin);
 // w[Cout][Cin] -> out[Cout][Cin_padded] with zero columns appended

@@ -110,6 +110,28 @@ hipError_t launch_pack_conv_w(hipStream_t s, int dt, const void* w, void* packed
   return hipGetLastError();
 }
 
+// [Cout][9 * Cin] (tap-major rows, as launch_pack_conv_w writes them) -> tiles[Cout / 160][step][160][64],
+// step = slab * 9 + tap: the 160 x 64 block a workgroup of the specialised-wavefront conv kernel moves to LDS
+// in one step is then 20 KB of contiguous memory instead of 160 pieces of 128 bytes a whole row apart.
+__global__ void pack_conv_w_tiles_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ tiles, int Cout, int Cin) {
+  const int64_t total = (int64_t)Cout * 9 * Cin;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int nsteps = 9 * (Cin / 64);
+  const int c = (int)(i % 64);
+  const int r = (int)((i / 64) % 160);
+  const int step = (int)((i / (64 * 160)) % nsteps);
+  const int cb = (int)(i / ((int64_t)64 * 160 * nsteps));
+  const int slab = step / 9, tap = step - slab * 9;
+  tiles[i] = w[(int64_t)(cb * 160 + r) * (9 * Cin) + tap * Cin + slab * 64 + c];
+}
+hipError_t launch_pack_conv_w_tiles(hipStream_t s, int dt, const void* w, void* tiles, int Cout, int Cin) {
+  if (dt != kBF16 || Cout % 160 != 0 || Cin % 64 != 0) return hipErrorInvalidValue;
+  const int64_t total = (int64_t)Cout * 9 * Cin;
+  pack_conv_w_tiles_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const bf16_t*)w, (bf16_t*)tiles, Cout, Cin);
+  return hipGetLastError();
+}
+
 template <class T>
 __global__ void pack_conv_in_w_kernel(const T* __restrict__ w, float* __restrict__ packed, int C, int Cl) {
   const int total = C * Cl * 9;

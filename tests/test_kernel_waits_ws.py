@@ -1,10 +1,11 @@
-"""The loader wavefronts of the specialised-wavefront conv kernel (lc_convws.hip) end every tap with a
-wait that leaves a counted number of vector-memory loads in flight: the weights of step s + kwLead must
-have landed, and they were the last loads of tap s + kwLead - kwAhead, so the wait may leave at most the
-loads of the taps since then outstanding. A count that is too large would let the contracting wavefronts
-read a weight tile that is still on its way. This test compiles the kernel to gfx950 assembly and checks
-every such wait against the loads the compiler actually emitted, and that the contracting wavefronts'
-main loop touches no global memory, spills nothing and waits for no LDS read before its barriers."""
+"""The contracting wavefronts of the specialised-wavefront conv kernel (lc_convws.hip) request the weight
+tiles themselves (global -> LDS directly, kwAhead steps ahead) and end every step with a wait that leaves
+a counted number of those requests in flight: the weights of step s + kwLead must have landed, and they
+were requested kwAhead - kwLead steps ago, so the wait may leave at most the requests of the steps since
+then outstanding. A count that is too large would let a wavefront read a weight tile that is still on its
+way. This test compiles the kernel to gfx950 assembly and checks every such wait against the loads the
+compiler actually emitted, that the contracting loop issues no other global-memory operation, spills
+nothing and waits for no LDS read before its barriers."""
 import re
 import subprocess
 from pathlib import Path
@@ -48,41 +49,27 @@ def test_no_spills_and_two_waves_per_simd(ws_asm):
         assert int(m.group(1)) <= 256  # eight wavefronts per workgroup: two per SIMD
 
 
-def test_loader_waits_match_emitted_loads(ws_asm):
-    span = const("kwBuf") - 1 - const("kwLead")  # taps whose loads are younger than the awaited weights, the current one included
-    assert span >= 1
-    for name, body in kernels(ws_asm):
-        parts = body.split("s_barrier")[:-1]
-        checked = exact = 0
-        run = []  # loads of the loader taps that precede this one in the text without interruption
-        for part in parts:
-            lines = [l for l in part.rstrip().splitlines() if l.strip() and not l.strip().startswith(";")]
-            waits = [int(v) for v in re.findall(r"s_waitcnt vmcnt\((\d+)\)", part)]
-            # a tap of a loader main loop ends with its explicit wait, right before the barrier
-            if "v_mfma" in part or not lines or "s_waitcnt vmcnt" not in lines[-1]:
-                run = []
-                continue
-            run.append(n_loads(part))
-            if len(run) < span:
-                continue  # its predecessors are in another block: not checked here
-            younger = sum(run[-span:])
-            # never more loads left outstanding than were issued after the awaited weights
-            assert waits[-1] <= younger, (name, waits[-1], run[-span:])
-            exact += waits[-1] == younger
-            checked += 1
-        assert checked >= 16, (name, checked)
-        # and it does not wait for more than it must (the prologue's wait is the exception)
-        assert exact >= checked - 2, (name, exact, checked)
-
-
-def test_contracting_loop_is_lds_and_mfma_only(ws_asm):
+def test_step_waits_match_emitted_requests(ws_asm):
+    assert const("kwBuf") - 1 - const("kwLead") == 1  # requests younger than the awaited weights: those of the current step
+    per_step = 160 * 8 // 256  # instructions per contracting wavefront per step
     for name, body in kernels(ws_asm):
         parts = body.split("s_barrier")
-        loop = [p for p in parts if p.count("v_mfma") >= 20]
-        assert len(loop) >= 9, name  # nine taps of the unrolled slab
-        for p in loop:
-            assert n_loads(p) == 0 and "global_store" not in p, name
-            # the barrier that ends a tap is not preceded by a wait for all LDS reads: the requests for the
-            # next step stay in flight across it
-            last = [l for l in p.rstrip().splitlines() if l.strip() and not l.strip().startswith(";")][-1]
-            assert "lgkmcnt(0)" not in last, (name, last)
+        steps = [p for p in parts if p.count("v_mfma") >= 20]
+        assert len(steps) >= 18, name  # nine unrolled taps of the main loop and of the last slab
+        seen = set()
+        for p in steps:
+            lines = [l for l in p.rstrip().splitlines() if l.strip() and not l.strip().startswith(";")]
+            dma = len(re.findall(r"\bglobal_load_lds_dwordx4\b", p))
+            assert n_loads(p) == dma and "global_store" not in p, name  # weight requests only
+            # the barrier that ends a step is preceded by the explicit wait for the weights, and by no wait for
+            # all LDS reads: the fragment requests for the next step stay in flight across it
+            m = re.fullmatch(r"\s*s_waitcnt vmcnt\((\d+)\)\s*", lines[-1])
+            assert m, (name, lines[-1])
+            wait = int(m.group(1))
+            assert wait <= dma, (name, wait, dma)  # never more left outstanding than were issued after the awaited weights
+            seen.add((wait, dma))
+        assert seen == {(per_step, per_step), (0, 0)}, (name, seen)
+        # the prologue: kwAhead steps requested, the last kwAhead - kwLead may stay in flight
+        pro = next(p for p in parts if len(re.findall(r"\bglobal_load_lds_dwordx4\b", p)) == (const("kwBuf") - 1) * per_step)
+        waits = [int(v) for v in re.findall(r"s_waitcnt vmcnt\((\d+)\)", pro)]
+        assert waits and waits[-1] <= (const("kwBuf") - 1 - const("kwLead")) * per_step, (name, waits)
