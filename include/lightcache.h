@@ -151,6 +151,14 @@ lc_status lc_set_chunk(lc_ctx* ctx, int frame_chunk, int token_chunk);
  * lanes is 1 or 2. */
 lc_status lc_set_lanes(lc_ctx* ctx, int lanes);
 
+/* Kernel choice of the 3x3 convolutions of the shallow branch (residual blocks, up conv; the operations of
+ * [FC] and of the residual blocks are the same either way). A bf16 stage whose widths allow it
+ * (C % 160 == 0) runs them in a kernel whose wavefronts are specialised (loaders / contracting); general = 1
+ * forces the general kernel, which every other stage uses anyway. The two accumulate the same products in
+ * the same order: results are identical bit for bit (this switch exists so that a test can say so).
+ * Default 0. LC_ERR_ARG unless general is 0 or 1. */
+lc_status lc_set_conv_general(lc_ctx* ctx, int general);
+
 /* Normal step ([AS]: the steps t = 0, n, 2n, ...): shallow down branch, deep stand-in, shallow
  * up branch on Concat(skip, deep) ([FC]); the deep feature is left in device slot dev_slot.
  * x [device, B,F,C_lat,H,W] -> eps [device, same shape]. Both must stay valid until the compute

@@ -77,6 +77,7 @@ PROTOTYPES = {
     "lc_set_workspace": (_I, [_P, _P, C.c_size_t]),
     "lc_set_chunk": (_I, [_P, _I, _I]),
     "lc_set_lanes": (_I, [_P, _I]),
+    "lc_set_conv_general": (_I, [_P, _I]),
     "lc_full_step": (_I, [_P, _P, _P, _I]),
     "lc_cached_step": (_I, [_P, _P, _P, _I]),
     "lc_swap_out": (_I, [_P, _I, _I]),
@@ -173,6 +174,10 @@ def lc_set_chunk(ctx, frame_chunk: int, token_chunk: int) -> None:
 
 def lc_set_lanes(ctx, lanes: int) -> None:
     _check(lib().lc_set_lanes(ctx, lanes), ctx)
+
+
+def lc_set_conv_general(ctx, general: int) -> None:
+    _check(lib().lc_set_conv_general(ctx, general), ctx)
 
 
 def lc_full_step(ctx, x_ptr: int, eps_ptr: int, dev_slot: int) -> None:
@@ -342,6 +347,9 @@ class Stage:
 
     def set_lanes(self, lanes: int) -> None:
         lc_set_lanes(self.ctx, lanes)
+
+    def set_conv_general(self, general: bool) -> None:
+        lc_set_conv_general(self.ctx, 1 if general else 0)
 
     def full_step(self, x, eps, dev_slot: int = 0):
         lc_full_step(self.ctx, x.data_ptr(), eps.data_ptr(), dev_slot)

@@ -54,6 +54,7 @@ struct lc_ctx {
   hipStream_t cs_main, cs_aux[kMaxLanes - 1];  // the caller's compute stream; the library's own further ones
   hipEvent_t ev_fork, ev_join[kMaxLanes - 1];
   int lanes;                     // 1 or 2: streams a chunked step spreads its chunks over
+  bool conv_general;             // lc_set_conv_general: the specialised-wavefront conv kernel is not used
   int lane;                      // the lane in use: selects cs and the per-lane scratch
   bool forked;
   int device;
@@ -306,7 +307,7 @@ FusedDesc fconv_desc(lc_ctx* c, const ConvW& w, int Cin, int Cout, int frames, i
   FusedDesc d;
   memset(&d, 0, sizeof d);
   d.dt = c->cfg.dtype; d.y_f32 = y_f32; d.taps = 9; d.src = 2; d.Cin = Cin; d.Cout = Cout; d.Cout_store = Cout;
-  d.w = w.w; d.w_tiles = w.wt; d.bias = w.b; d.frames = frames; d.H = H; d.W = W; d.x = x; d.scale = scale_p(c); d.shift = shift_p(c);
+  d.w = w.w; d.w_tiles = c->conv_general ? nullptr : w.wt; d.bias = w.b; d.frames = frames; d.H = H; d.W = W; d.x = x; d.scale = scale_p(c); d.shift = shift_p(c);
   d.res = res; d.y = y; d.in_map = dense_map(); d.out_map = dense_map();
   return d;
 }
@@ -665,7 +666,7 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
   c->ss = (hipStream_t)side_stream;
   for (int i = 0; i + 1 < kMaxLanes; ++i) { c->cs_aux[i] = nullptr; c->ev_join[i] = nullptr; }
   c->ev_fork = nullptr;
-  c->lanes = 2; c->lane = 0; c->forked = false;
+  c->lanes = 2; c->lane = 0; c->forked = false; c->conv_general = false;
   c->device = dev;
   c->frame_chunk = c->token_chunk = 0;
   c->plan = make_plan(c->cfg, 0, 0);
@@ -878,6 +879,13 @@ lc_status lc_set_lanes(lc_ctx* c, int lanes) {
   if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
   if (lanes < 1 || lanes > kMaxLanes) return fail(c, LC_ERR_ARG, "lanes must be in [1, %d]", kMaxLanes);
   c->lanes = lanes;
+  return LC_OK;
+}
+
+lc_status lc_set_conv_general(lc_ctx* c, int general) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (general != 0 && general != 1) return fail(c, LC_ERR_ARG, "general must be 0 or 1");
+  c->conv_general = general != 0;
   return LC_OK;
 }
 

@@ -219,3 +219,35 @@ def test_conv_out(st):
     g = lo.silu(lo.group_norm(u.astype(np.float64), w["out.gn_g"], w["out.gn_b"], cfg.groups, cfg.gn_eps))
     ref = lo.conv3x3(g, w["out.w"], w["out.b"])
     check("conv_out", host(eps), ref, cfg.dtype)
+
+
+def test_specialised_conv_equals_general_bitwise(st):
+    """The 3x3 convolutions of a bf16 stage with C % 160 == 0 run in the kernel with specialised wavefronts;
+    it accumulates the same products in the same order as the general kernel, so the two must agree bit for
+    bit (output and the GroupNorm partial sums it writes, seen through the next operator)."""
+    stage, cfg, w = st
+    N, C, Cd, H, W = cfg.N, cfg.C, cfg.C_deep, cfg.H, cfg.W
+    x = act(cfg, (N, C, H, W), 131, 1.5) + np.float32(0.25)
+    d = act(cfg, (N, Cd, H // 2, W // 2), 132, 0.7)
+    if cfg.dtype == "bf16":
+        d = synth.round_to_bf16(d)
+    xd, dd = dev32(stage, planar_to_rows(x)), dev(stage, planar_to_rows(d))
+    outs = []
+    for general in (0, 1):
+        lcb.lc_set_conv_general(stage.ctx, general)
+        y = empty32(stage, *xd.shape)
+        u = empty32(stage, N * H * W, C)
+        lcb.lc_op_res_block(stage.ctx, lcb.LC_L_RES0, xd.data_ptr(), y.data_ptr(), N)
+        lcb.lc_op_up_conv(stage.ctx, xd.data_ptr(), dd.data_ptr(), u.data_ptr(), N)
+        # a whole cached step as well: its GroupNorms read the partial sums the convolutions write
+        lat = synth.make_latents(cfg, 133)
+        eps = stage.empty(*lat.shape)
+        stage.cache_write(0, dev(stage, synth.make_deep(cfg, 134)))
+        stage.cached_step(dev(stage, lat), eps, 0)
+        stage.sync()
+        outs.append((y.clone(), u.clone(), eps.clone()))
+    lcb.lc_set_conv_general(stage.ctx, 0)
+    for a, b, name in zip(outs[0], outs[1], ("res_block", "up_conv", "cached_step")):
+        assert torch.equal(a, b), name
+    with pytest.raises(lcb.LcError):
+        lcb.lc_set_conv_general(stage.ctx, 2)
