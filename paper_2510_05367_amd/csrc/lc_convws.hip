@@ -1,9 +1,12 @@
 // 3x3 stride-1 convolution of the bf16 stages with the wavefronts of a workgroup specialised
-// (gfx950): four wavefronts only contract (LDS fragment reads and 32x32x16 MFMAs), four only load
-// (global memory -> activation arithmetic -> LDS). Both kinds sit on every SIMD, so the vector
-// arithmetic of the loader (GroupNorm apply, SiLU, rounding: two transcendentals per element) and
-// every global-memory latency run beside the MFMAs of the other wavefront instead of inside one
-// instruction stream, which a single wavefront per SIMD executes one part after the other.
+// (gfx950). Four wavefronts contract: their stream is LDS fragment reads, 32x32x16 MFMAs and the
+// requests that bring the weight tiles of later steps from global memory straight into LDS. Four
+// build the activations: global memory -> GroupNorm apply, SiLU, rounding (two transcendentals per
+// element) -> halo tile in LDS. One of each kind sits on every SIMD. The contracting stream never
+// waits for activation arithmetic or for the latency of an activation load, and the fragment reads of
+// the next step are requested before the barrier that ends the current one, so its MFMAs follow each
+// other across the steps; a single wavefront per SIMD that does everything executes these parts one
+// after the other.
 //
 // Product, tiles and LDS layout are those of the general kernel in lc_gemm.hip: transposed product
 // D[cout][pixel] = sum_k W[cout][k] X[pixel][k], k = tap * Cin + ci; a workgroup owns 160 output
@@ -31,7 +34,7 @@ constexpr int kwLead = 2;       // at the barrier that ends step s the weights o
                                 // contracting wavefronts request the first fragments of step s + 1 before that barrier
 constexpr int kwFA = 4;         // weight fragments requested from LDS ahead of the MFMAs that use them (ring of kwFA + 1)
 constexpr int kwFin = 2;        // a halo packet requested at tap r is activated and stored at tap r + kwFin
-constexpr int kwXR = kwHaloRows / 32;  // halo packets per loader thread per slab
+constexpr int kwXR = kwHaloRows / 32;  // halo packets per activation-building thread per slab
 
 struct WsArgs {
   const float* x;       // fp32 rows [frames][H][W][ldx]; ldx = Cin (plain) or Cs (concat)
