@@ -206,7 +206,9 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
       for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[t][kt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // a stage always holds at least one valid key: finite
+      // mx: over this lane's 16 keys of the query. The other half of the query's keys sits in lane l ^ 32; the
+      // exchange (a trip through LDS) is only made inside the rare branch below: whether ANY lane of the
+      // wavefront exceeds the margin is the same question asked of the per-lane and of the per-query maxima.
       // The offset m subtracted in the exponent need not be the exact running maximum: any m gives the same
       // softmax as long as exp2 stays in range, because the same m enters the probabilities, the denominator
       // and the rescaling. So m is raised (and O^T, l rescaled) only when some query of the wavefront sees a
@@ -219,6 +221,7 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
         // sc already is s * scale * log2(e) - m_run: a score above the offset shows as a positive one
         const bool first = st_i == 0;  // the first stage sets the offset, which may be negative
         if (first || __builtin_amdgcn_ballot_w64(mx > kLazy) != 0) {
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // a stage always holds at least one valid key: finite
           // (each query decides for itself: what the other lanes of the wavefront do must not show in its bits,
           // or the result would depend on which queries share a wavefront, i.e. on the query window)
           float m_new = m_run[t] + ((first || mx > kLazy) ? mx : 0.f);
@@ -236,7 +239,9 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
             for (int r = 0; r < 16; ++r) sc[t][kt][r] -= delta;
           if (hh == HX) qf[t][KX][EX] = static_cast<bf16_t>(-m_new);
         }
-      } else if (const bool up = st_i == 0 || (mx - m_run[t]) * scale_log2e > kLazy; __builtin_amdgcn_ballot_w64(up) != 0) {
+      } else if (st_i == 0 || __builtin_amdgcn_ballot_w64((mx - m_run[t]) * scale_log2e > kLazy) != 0) {
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const bool up = st_i == 0 || (mx - m_run[t]) * scale_log2e > kLazy;
         const float m_new = up ? fmaxf(m_run[t], mx) : m_run[t];
         const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_new) * scale_log2e);
         m_run[t] = m_new;
