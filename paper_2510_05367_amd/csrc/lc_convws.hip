@@ -80,7 +80,8 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
   auto w_lds = [&](int b) { return smem + b * BCO * kwRow; };
   auto x_lds = [&](int b) { return smem + kwBuf * BCO * kwRow + b * kwHaloRows * kwLds; };
 
-  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  // (the wavefront index as a scalar: what is derived from it - roles, LDS targets of the weight requests - stays scalar)
+  const int tid = threadIdx.x, lane = tid & 63, wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int co0 = blockIdx.y * BCO;
   int frame, ty0, tx0;
   {
