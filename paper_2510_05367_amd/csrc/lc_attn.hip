@@ -12,6 +12,8 @@
 // one thread owns one (position, head, query frame) and streams the F keys / values.
 #include "lc_internal.h"
 
+#include <type_traits>
+
 namespace lc {
 
 constexpr int kKeys = 64;  // keys per LDS stage
@@ -463,6 +465,98 @@ __global__ __launch_bounds__(256) void temporal_attn_kernel(const T* __restrict_
   }
 }
 
+// The bf16 case with F <= 16 frames on the matrix cores: the score tile of one (position, head) fits one
+// 16 x 16 MFMA tile, so a wavefront takes (position, head) pairs whole instead of a thread taking one query
+// (frames beyond F: rows read again from frame F - 1, masked as keys, not stored as queries).
+//   S^T[key][query] = K Q^T      16 x 16 x 32 MFMAs over d (packets beyond d are zeros); the lane ends up with
+//                                keys 4 (lane / 16) .. + 3 of query lane % 16
+//   softmax over the keys        in the lane and across the four lane groups (two shuffles), exact (all 16 keys at once)
+//   O^T[d][query] = V^T P^T      16 x 16 x 16 MFMAs, one per 16 channels: the accumulator layout of S^T is the
+//                                operand layout of P^T as it stands; V^T is read from the staged rows two bytes
+//                                at a time (the four keys of a lane sit in four rows)
+// and stores 8 bytes (4 channels of one query frame) per lane. The staging is the one of the kernel above.
+// The vector kernel spends 3200 instructions per wavefront on 4 such pairs; this one about 100 on one.
+template <int D>
+__global__ __launch_bounds__(256) void temporal_attn_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+                                                                 int F, int P, int heads, int np, float scale_log2e) {
+  static_assert(D % 8 == 0, "whole 16-byte packets per head");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int C = heads * D, ld = 3 * C;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int b = blockIdx.y, p0 = blockIdx.x * np;
+  const int npv = min(np, P - p0);
+  const int ppr = ld / 8;
+  const int total = F * np * ppr;
+  for (int q0 = 0; q0 < total; q0 += 256) {
+    const int q = min(q0 + tid, total - 1);
+    const int row = q / ppr, pk = q - row * ppr;
+    const int f = row / np, pos = min(row - f * np, npv - 1);  // positions beyond the end: a copy nobody reads
+    const bf16_t* src = qkv + ((int64_t)(b * F + f) * P + p0 + pos) * ld + pk * 8;
+#ifdef __HIP_DEVICE_COMPILE__
+    __builtin_amdgcn_global_load_lds(src, smem + (q0 + wid * 64) * 16, 16, 0, 0);
+#else
+    (void)src;
+#endif
+  }
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  const bf16_t* rows = reinterpret_cast<const bf16_t*>(smem);
+  const int i16 = lane & 15, g = lane >> 4;
+  const int tasks = npv * heads;
+  for (int task = wid; task < tasks; task += 4) {  // uniform over the wavefront
+    const int h = task % heads, pos = task / heads;
+    const bf16_t* qrow = rows + (min(i16, F - 1) * np + pos) * ld + h * D;  // frame i16: as query (B operand) and, + C, as key (A)
+    f32x4 st = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int sl = 0; sl < (D + 31) / 32; ++sl) {
+      const int d0 = sl * 32 + 8 * g;
+      bf16x8 ka, qb;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ka[e] = qb[e] = (bf16_t)0.f;
+      if (d0 < D) {
+        ka = *reinterpret_cast<const bf16x8*>(qrow + C + d0);
+        qb = *reinterpret_cast<const bf16x8*>(qrow + d0);
+      }
+      st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb, st, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (4 * g + r >= F) st[r] = -INFINITY;  // no such key (key 0 always exists: the maximum is finite)
+    float mx = fmaxf(fmaxf(st[0], st[1]), fmaxf(st[2], st[3]));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float pe[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) pe[r] = exp2f((st[r] - mx) * scale_log2e);
+    float l = (pe[0] + pe[1]) + (pe[2] + pe[3]);
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.f / l;
+    bf16x4 pb;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) pb[r] = static_cast<bf16_t>(pe[r]);
+    const bf16_t* vbase = rows + pos * ld + 2 * C + h * D;  // + key * np * ld
+    bf16_t* obase = out + ((int64_t)(b * F + i16) * P + p0 + pos) * C + h * D;
+#pragma unroll
+    for (int t = 0; t < (D + 15) / 16; ++t) {
+      const int dv = min(t * 16 + i16, D - 1);  // channels beyond the head: a copy, computed and dropped
+      bf16x4 va;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) va[r] = vbase[min(4 * g + r, F - 1) * np * ld + dv];  // (weight 0 beyond F)
+      const f32x4 o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+      const int dd = t * 16 + 4 * g;  // this lane's four channels of query frame i16
+      if (dd < D && i16 < F) {
+        bf16x4 ov;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ov[r] = static_cast<bf16_t>(o[r] * inv);
+        *reinterpret_cast<bf16x4*>(obase + dd) = ov;
+      }
+    }
+  }
+}
+
 // The same computation straight from global memory, for frame counts whose rows do not fit in LDS:
 // thread = (batch b, position p, query frame f, head h), h fastest.
 template <class T, int D>
@@ -535,11 +629,25 @@ static hipError_t temporal_run(hipStream_t s, const T* qkv, T* out, int B, int F
     return hipGetLastError();
   }
   // positions per workgroup: two workgroups per compute unit if possible, at most 16 positions
-  int np = (int)(64 * 1024 / pos_bytes);
+  int np = (int)(32 * 1024 / pos_bytes);
   np = np < 1 ? 1 : (np > 16 ? 16 : np);
   if (np > P) np = P;
   const int64_t packets = (int64_t)F * np * (3 * heads * D / Vec16<T>::N);
   const int lds = (int)((packets + 255) / 256 * 256 * 16);  // whole rounds of 256 lanes land in LDS
+  if constexpr (std::is_same<T, bf16_t>::value && D % 8 == 0) {
+    if (F >= 8 && F <= 16) {  // (below 8 frames the vector kernel has less to do than a padded tile)
+      auto mk = temporal_attn_mfma_kernel<D>;
+      static int mk_attr_bytes = 0;  // per instantiation
+      if (lds > mk_attr_bytes) {
+        hipError_t e = hipFuncSetAttribute((const void*)mk, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        mk_attr_bytes = lds;
+      }
+      dim3 grid((unsigned)((P + np - 1) / np), (unsigned)B);
+      mk<<<grid, 256, lds, s>>>(qkv, out, F, P, heads, np, sl);
+      return hipGetLastError();
+    }
+  }
   auto kern = temporal_attn_kernel<T, D>;
   static int attr_bytes = 0;  // per instantiation
   if (lds > attr_bytes) {

@@ -251,3 +251,34 @@ def test_specialised_conv_equals_general_bitwise(st):
         assert torch.equal(a, b), name
     with pytest.raises(lcb.LcError):
         lcb.lc_set_conv_general(stage.ctx, 2)
+
+
+@pytest.mark.parametrize("heads,head_dim,B", [(8, 40, 2), (5, 64, 1), (8, 8, 1), (4, 16, 1), (2, 32, 2)])
+@pytest.mark.parametrize("logit_scale", [1.0, 8.0])
+@pytest.mark.parametrize("F", [16, 11, 8])
+def test_temporal_attention_on_matrix_cores(heads, head_dim, B, logit_scale, F):
+    """bf16 stages with 8 <= F <= 16 run the temporal attention on 16 x 16 MFMA tiles (one tile = the scores of
+    one position and head, padded beyond F); every head size the library accepts, position counts that leave a
+    ragged last workgroup, unit and sharp logits. Against the definition in float64."""
+    C = heads * head_dim
+    if C % 64:
+        pytest.skip("C must be a multiple of 64")
+    cfg = synth.StageConfig(f"t{F}_{heads}x{head_dim}", B=B, F=F, H=4, W=4, C_lat=4, C=C, C_deep=64, groups=8, n_res=1,
+                            heads=heads, head_dim=head_dim, dtype="bf16")
+    stage, _ = make_stage(cfg, seed=5)
+    try:
+        for P in (37, 1, 64):
+            qkv = act(cfg, (B * F * P, 3 * C), 61 + P)
+            qkv[:, :2 * C] *= np.float32(np.sqrt(logit_scale) * 1.4)
+            qkv = synth.round_to_bf16(qkv)
+            qd = dev(stage, qkv)
+            out = stage.empty(B * F * P, C)
+            out.fill_(7.0)
+            lcb.lc_op_temporal_attention(stage.ctx, qd.data_ptr(), out.data_ptr(), P)
+            stage.sync()
+            a = qkv.astype(np.float64).reshape(B, F, P, 3 * C).transpose(0, 2, 1, 3)  # [B, P, F, 3C]
+            ref = oracle_attention_core(a[..., :C], a[..., C:2 * C], a[..., 2 * C:], heads)
+            ref = ref.transpose(0, 2, 1, 3).reshape(B * F * P, C)
+            check(f"temporal core F={F} {heads}x{head_dim} P={P} x{logit_scale}", host(out), ref, cfg.dtype)
+    finally:
+        stage.close()
