@@ -537,9 +537,12 @@ static hipError_t run_lin_r(hipStream_t s, const FusedDesc& d, int cols, int tc)
   a.im_H = d.H; a.im_W = d.W; a.im_Cl = d.Cs;
   a.stat = d.stat; a.stat_splits = d.stat_splits; a.stat_rps = d.stat_rps; a.stat_off = d.stat_off;
   a.q_scale = d.q_scale; a.q_cols = d.q_cols;
-  // one workgroup per compute unit (its registers hold the weights), each with a contiguous range of tiles
+  // one workgroup per compute unit (its registers hold the weights), each with a contiguous range of tiles.
+  // The gathering instantiation with one tile per wavefront has few weights and little LDS: three of its
+  // workgroups share a compute unit, and one's gather latency hides behind the others' stores.
+  constexpr int kPerCu = (SRC == 2 && NTM == 1) ? 3 : 1;
   const int ntiles = (int)d.rows / kRows;
-  const int gx_max = 256 / cols > 1 ? 256 / cols : 1;
+  const int gx_max = 256 * kPerCu / cols > 1 ? 256 * kPerCu / cols : 1;
   int tpw = (ntiles + gx_max - 1) / gx_max;
   if (tpw < kLinMinTiles) tpw = kLinMinTiles;
   a.tiles_per_wg = tpw;
@@ -563,7 +566,8 @@ static hipError_t run_lin(hipStream_t s, const FusedDesc& d) {
   // well inside the 256 architectural registers, at most kTileMax. Workgroup columns: as few as keep a
   // column within 4 wavefronts x that many tiles; the last column may be narrower.
   constexpr int kt_regs = CIN / Mma32<T>::K * (int)sizeof(typename Mma32<T>::Frag) / 4;
-  constexpr int ntm_max = 160 / kt_regs < 1 ? 1 : (160 / kt_regs > kTileMax ? kTileMax : 160 / kt_regs);
+  // (the gathering instantiation: one tile, so that several workgroups fit a compute unit - see run_lin_r)
+  constexpr int ntm_max = SRC == 2 ? 1 : 160 / kt_regs < 1 ? 1 : (160 / kt_regs > kTileMax ? kTileMax : 160 / kt_regs);
   const int tiles = d.Cout / 32;
   const int cols = (tiles + 4 * ntm_max - 1) / (4 * ntm_max);
   const int tc = (tiles + cols - 1) / cols;
