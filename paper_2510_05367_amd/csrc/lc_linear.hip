@@ -540,7 +540,7 @@ static hipError_t run_lin_r(hipStream_t s, const FusedDesc& d, int cols, int tc)
   // one workgroup per compute unit (its registers hold the weights), each with a contiguous range of tiles.
   // The gathering instantiation with one tile per wavefront has few weights and little LDS: three of its
   // workgroups share a compute unit, and one's gather latency hides behind the others' stores.
-  constexpr int kPerCu = (SRC == 2 && NTM == 1) ? 3 : 1;
+  constexpr int kPerCu = (SRC == 2 && NTM == 1) ? 3 : (SRC == 0 && CIN == 320 && NTM == 1) ? 2 : 1;
   const int ntiles = (int)d.rows / kRows;
   const int gx_max = 256 * kPerCu / cols > 1 ? 256 * kPerCu / cols : 1;
   int tpw = (ntiles + gx_max - 1) / gx_max;
@@ -567,7 +567,7 @@ static hipError_t run_lin(hipStream_t s, const FusedDesc& d) {
   // column within 4 wavefronts x that many tiles; the last column may be narrower.
   constexpr int kt_regs = CIN / Mma32<T>::K * (int)sizeof(typename Mma32<T>::Frag) / 4;
   // (the gathering instantiation: one tile, so that several workgroups fit a compute unit - see run_lin_r)
-  constexpr int ntm_max = SRC == 2 ? 1 : 160 / kt_regs < 1 ? 1 : (160 / kt_regs > kTileMax ? kTileMax : 160 / kt_regs);
+  constexpr int ntm_max = (SRC == 2 || (SRC == 0 && CIN == 320)) ? 1 : 160 / kt_regs < 1 ? 1 : (160 / kt_regs > kTileMax ? kTileMax : 160 / kt_regs);
   const int tiles = d.Cout / 32;
   const int cols = (tiles + 4 * ntm_max - 1) / (4 * ntm_max);
   const int tc = (tiles + cols - 1) / cols;
