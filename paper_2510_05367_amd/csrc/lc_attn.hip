@@ -8,8 +8,9 @@
 // in-lane plus a single cross-lane exchange, and the exponentials, packed to the storage type,
 // are directly the B operand of O^T[dim][query] += V^T[dim][key] P^T[key][query].
 //
-// Temporal attention (tokens = the F frames of one position) is bandwidth-bound: F is 8..32, so
-// one thread owns one (position, head, query frame) and streams the F keys / values.
+// Temporal attention (tokens = the F frames of one position) is bandwidth-bound: F is 8..32. bf16 stages
+// with 8..16 frames put the 16 x 16 scores of a (position, head) on one MFMA tile; otherwise one thread
+// owns one (position, head, query frame) and streams the F keys / values.
 #include "lc_internal.h"
 
 #include <type_traits>

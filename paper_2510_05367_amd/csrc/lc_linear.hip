@@ -3,7 +3,9 @@
 //
 // K is only C here (320), so the weights a wavefront needs - up to 96 output channels x Cin - fit
 // in its registers as MFMA fragments (3 x Cin/16 packets of 16 bytes for bf16; one wavefront per
-// SIMD, so it may use the whole register file). A workgroup of four wavefronts covers a column of
+// SIMD, so it may use the whole register file; the output projections and the gathering conv_in keep
+// one tile per wavefront instead, so that two or three workgroups fit a compute unit and overlap
+// each other's latencies). A workgroup of four wavefronts covers a column of
 // up to 12 32-channel tiles, split 3,3,2,2 for the 10 tiles of 320 channels, and walks a range of
 // 32-row activation tiles: the tile is fetched one step ahead with coalesced 16/32-byte loads,
 // GroupNorm'ed on the way in when the source is the fp32 residual stream, rounded to the operand
