@@ -75,7 +75,10 @@ hipError_t launch_gn_stats(hipStream_t s, int dt, const void* x, float* partial,
 // on scheduling. The tensor may be the concatenation of two sources (A then B along the channels)
 // with different row counts per frame; `w` weighs a source's rows (the 2x-upsampled deep feature
 // counts each of its pixels four times).
-__global__ __launch_bounds__(256) void gn_finalize_kernel(const float* __restrict__ partA, int CA, int splitsA,
+// At most 32 vector registers: the 3x3 convolution kernel leaves that many free on every SIMD (two
+// wavefronts of 240), so when a step runs its chunks on two streams this kernel starts beside the other
+// stream's convolution instead of waiting for a compute unit to drain.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(32))) void gn_finalize_kernel(const float* __restrict__ partA, int CA, int splitsA,
                                                           int rowsA, float wA, const float* __restrict__ partB,
                                                           int CB, int splitsB, int rowsB, float wB,
                                                           const float* __restrict__ gamma,
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(256) void gn_finalize_kernel(const float* __restric
   // cells i = tid, tid + 256, ... in batches of kBatch: all loads of a batch are requested before the first
   // is added (one at a time, every cell paid a trip to L2: that was most of this kernel's time); the order
   // of the additions is the same either way
-  constexpr int kBatch = 8;
+  constexpr int kBatch = 3;
   auto fold = [&](const float* part, int C, int splits, int n, int c_first, int cells, float w) {
     for (int i0 = tid; i0 < cells; i0 += 256 * kBatch) {
       float2 v[kBatch];
