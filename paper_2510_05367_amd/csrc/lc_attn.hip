@@ -9,7 +9,7 @@
 // are directly the B operand of O^T[dim][query] += V^T[dim][key] P^T[key][query].
 //
 // Temporal attention (tokens = the F frames of one position) is bandwidth-bound: F is 8..32. bf16 stages
-// with 8..16 frames put the 16 x 16 scores of a (position, head) on one MFMA tile; otherwise one thread
+// with 8..32 frames put the scores of a (position, head) on one 16 x 16 or 32 x 32 MFMA tile; otherwise one thread
 // owns one (position, head, query frame) and streams the F keys / values.
 #include "lc_internal.h"
 
@@ -558,6 +558,106 @@ __global__ __launch_bounds__(256) void temporal_attn_mfma_kernel(const bf16_t* _
   }
 }
 
+// The same for 17 <= F <= 32 frames on 32 x 32 MFMA tiles. The lane ends up with 16 keys of query lane % 32:
+// keys 8 (r / 4) + 4 (lane / 32) + r % 4, r = 0..15. The contraction of O^T = V^T P^T runs over the keys in two slabs
+// of 16 whose order inside a slab is free as long as both operands use the same one: slot j of lane group hh in
+// slab u stands for key 16 u + 8 (j / 4) + 4 hh + j % 4, which is where accumulator r = 8 u + j already sits.
+template <int D>
+__global__ __launch_bounds__(256) void temporal_attn_mfma32_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+                                                                   int F, int P, int heads, int np, float scale_log2e) {
+  static_assert(D % 8 == 0, "whole 16-byte packets per head");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int C = heads * D, ld = 3 * C;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int b = blockIdx.y, p0 = blockIdx.x * np;
+  const int npv = min(np, P - p0);
+  const int ppr = ld / 8;
+  const int total = F * np * ppr;
+  for (int q0 = 0; q0 < total; q0 += 256) {
+    const int q = min(q0 + tid, total - 1);
+    const int row = q / ppr, pk = q - row * ppr;
+    const int f = row / np, pos = min(row - f * np, npv - 1);  // positions beyond the end: a copy nobody reads
+    const bf16_t* src = qkv + ((int64_t)(b * F + f) * P + p0 + pos) * ld + pk * 8;
+#ifdef __HIP_DEVICE_COMPILE__
+    __builtin_amdgcn_global_load_lds(src, smem + (q0 + wid * 64) * 16, 16, 0, 0);
+#else
+    (void)src;
+#endif
+  }
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  const bf16_t* rows = reinterpret_cast<const bf16_t*>(smem);
+  const int i32 = lane & 31, hh = lane >> 5;
+  const int tasks = npv * heads;
+  for (int task = wid; task < tasks; task += 4) {  // uniform over the wavefront
+    const int h = task % heads, pos = task / heads;
+    const bf16_t* qrow = rows + (min(i32, F - 1) * np + pos) * ld + h * D;  // frame i32: as query (B operand) and, + C, as key (A)
+    f32x16 st;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) st[r] = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < (D + 15) / 16; ++sl) {
+      const int d0 = sl * 16 + 8 * hh;
+      bf16x8 ka, qb;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ka[e] = qb[e] = (bf16_t)0.f;
+      if (d0 < D) {
+        ka = *reinterpret_cast<const bf16x8*>(qrow + C + d0);
+        qb = *reinterpret_cast<const bf16x8*>(qrow + d0);
+      }
+      st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb, st, 0, 0, 0);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      if (8 * (r >> 2) + 4 * hh + (r & 3) >= F) st[r] = -INFINITY;  // no such key (key 0 always exists: the maximum is finite)
+      mx = fmaxf(mx, st[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float l = 0.f;
+    bf16x8 pb[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pe = exp2f((st[r] - mx) * scale_log2e);
+      l += pe;
+      pb[r >> 3][r & 7] = static_cast<bf16_t>(pe);
+    }
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.f / l;
+    const bf16_t* vbase = rows + pos * ld + 2 * C + h * D;  // + key * np * ld
+    bf16_t* obase = out + ((int64_t)(b * F + i32) * P + p0 + pos) * C + h * D;
+#pragma unroll
+    for (int t = 0; t < (D + 31) / 32; ++t) {
+      const int dv = min(t * 32 + i32, D - 1);  // channels beyond the head: a copy, computed and dropped
+      f32x16 o;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[r] = 0.f;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        bf16x8 va;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int key = 16 * u + 8 * (j >> 2) + 4 * hh + (j & 3);
+          va[j] = vbase[min(key, F - 1) * np * ld + dv];  // (weight 0 beyond F)
+        }
+        o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[u], o, 0, 0, 0);
+      }
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int dd = t * 32 + 8 * g4 + 4 * hh;  // this lane's channels dd .. dd + 3 of query frame i32
+        if (dd < D && i32 < F) {
+          bf16x4 ov;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ov[r] = static_cast<bf16_t>(o[4 * g4 + r] * inv);
+          *reinterpret_cast<bf16x4*>(obase + dd) = ov;
+        }
+      }
+    }
+  }
+}
+
 // The same computation straight from global memory, for frame counts whose rows do not fit in LDS:
 // thread = (batch b, position p, query frame f, head h), h fastest.
 template <class T, int D>
@@ -643,6 +743,18 @@ static hipError_t temporal_run(hipStream_t s, const T* qkv, T* out, int B, int F
         hipError_t e = hipFuncSetAttribute((const void*)mk, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         mk_attr_bytes = lds;
+      }
+      dim3 grid((unsigned)((P + np - 1) / np), (unsigned)B);
+      mk<<<grid, 256, lds, s>>>(qkv, out, F, P, heads, np, sl);
+      return hipGetLastError();
+    }
+    if (F > 16 && F <= 32) {
+      auto mk = temporal_attn_mfma32_kernel<D>;
+      static int mk32_attr_bytes = 0;  // per instantiation
+      if (lds > mk32_attr_bytes) {
+        hipError_t e = hipFuncSetAttribute((const void*)mk, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        mk32_attr_bytes = lds;
       }
       dim3 grid((unsigned)((P + np - 1) / np), (unsigned)B);
       mk<<<grid, 256, lds, s>>>(qkv, out, F, P, heads, np, sl);

@@ -255,10 +255,10 @@ def test_specialised_conv_equals_general_bitwise(st):
 
 @pytest.mark.parametrize("heads,head_dim,B", [(8, 40, 2), (5, 64, 1), (8, 8, 1), (4, 16, 1), (2, 32, 2)])
 @pytest.mark.parametrize("logit_scale", [1.0, 8.0])
-@pytest.mark.parametrize("F", [16, 11, 8])
+@pytest.mark.parametrize("F", [16, 11, 8, 32, 25, 17])
 def test_temporal_attention_on_matrix_cores(heads, head_dim, B, logit_scale, F):
-    """bf16 stages with 8 <= F <= 16 run the temporal attention on 16 x 16 MFMA tiles (one tile = the scores of
-    one position and head, padded beyond F); every head size the library accepts, position counts that leave a
+    """bf16 stages with 8 <= F <= 32 run the temporal attention on 16 x 16 or 32 x 32 MFMA tiles (one tile = the
+    scores of one position and head, padded beyond F); every head size the library accepts, position counts that leave a
     ragged last workgroup, unit and sharp logits. Against the definition in float64."""
     C = heads * head_dim
     if C % 64:
