@@ -36,6 +36,7 @@ struct ConvW { void* w; float* b; void* wt; };  // wt: tile order for the specia
 struct AttnW { GnW gn; void* wqkv; void* wo; float* bo; void* wqkv_f; void* wo_f; };  // *_f: fragment order
 struct Packed {
   float* cin_w; float* cin_b;
+  void* cin_wp;  // conv_in weights as rows [C][64] of the operand type (k = plane * 9 + tap, zero padded), or nullptr
   void* cin_wf;  // conv_in as a linear layer on gathered neighbourhoods: [C][64] in fragment order, or nullptr
   GnW res_gn[LC_MAX_RES]; ConvW res[LC_MAX_RES];
   AttnW sattn, tattn;
@@ -329,6 +330,15 @@ lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat
   const lc_config& g = c->cfg;
   const int T = g.H * g.W;
   if (wrote_stats) *wrote_stats = false;
+  if (c->pw.cin_wp) {  // (a property of the stage's geometry: the same kernel for every chunking)
+    hipError_t e;
+    { Prof pr_(c, LC_K_CONV_IN); e = launch_conv_in_tile(c->cs, g.dtype, x, c->pw.cin_wp, c->pw.cin_b, (float*)h, stat, frames, g.H, g.W, g.C_lat, g.C); }
+    if (e == hipSuccess) {
+      if (wrote_stats) *wrote_stats = stat != nullptr;
+      return LC_OK;
+    }
+    if (e != hipErrorNotSupported) return fail(c, LC_ERR_HIP, "conv_in: %s", hipGetErrorString(e));
+  }
   if (c->pw.cin_wf && T % 32 == 0) {  // (the same kernel for every chunking: see linear())
     FusedDesc d;
     memset(&d, 0, sizeof d);
@@ -801,11 +811,11 @@ lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
   LC_HIP(c, launch_pack_conv_in_w(s, dt, w->conv_in_w, (float*)(b + o_cin_w), C, Cl));
   F32(w->conv_in_b, o_cin_b, C, C);
   p.cin_w = (float*)(b + o_cin_w); p.cin_b = (float*)(b + o_cin_b);
-  p.cin_wf = nullptr;
+  p.cin_wf = nullptr; p.cin_wp = nullptr;
   if (Cl * 9 <= 64) {  // [C][Cl][3][3] is already [C][Cl*9]: pad the rows to 64, then fragment order
     LC_HIP(c, launch_pad_rows(s, dt, w->conv_in_w, b + o_cin_wp, C, Cl * 9, 64));
     LC_HIP(c, launch_pack_lin_w(s, dt, b + o_cin_wp, b + o_cin_wf, C, 64));
-    p.cin_wf = b + o_cin_wf;
+    p.cin_wf = b + o_cin_wf; p.cin_wp = b + o_cin_wp;
   }
   for (int i = 0; i < g.n_res; ++i) {
     F32(w->res[i].gn_g, o_res_g[i], C, C); F32(w->res[i].gn_b, o_res_b[i], C, C);

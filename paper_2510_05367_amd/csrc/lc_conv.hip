@@ -378,6 +378,99 @@ __global__ __launch_bounds__(NT) void conv_out_tile_kernel(const float* __restri
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// First convolution of the stage for bf16: h = conv3x3_{C_lat -> C}(x) + bias, planar latents in, fp32 rows out,
+// with the per-channel sums of every 32 output rows for the GroupNorm that follows. The contraction is only
+// K = 9 * C_lat (36) long: what costs time is writing C * 4 bytes per pixel, so the kernel is built around many
+// small workgroups that overlap each other's phases. A workgroup owns 32 consecutive pixels of an image row
+// (one statistics split) and all C channels: its 3 x 34 halo of the C_lat planes goes to LDS; the product is
+// D[pixel][channel] on 32 x 32 x 16 MFMAs, the A operand (k = channel * 9 + tap, zeros beyond 9 * C_lat)
+// gathered from the halo two bytes at a time, the B operand read straight from the weights padded to rows
+// of 64; in D a lane holds one channel of 16 pixels, so 32 lanes store 128 contiguous bytes of a pixel's
+// row and the sums over the pixels are 16 additions in the lane and one across its two halves. The four
+// wavefronts split the 32-channel tiles (w, w + 4, w + 8, ...).
+template <int KS, int NTM>
+__global__ __launch_bounds__(256) void conv_in_tile_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wp,
+                                                           const float* __restrict__ bias, float* __restrict__ y,
+                                                           float* __restrict__ stat, int H, int W, int Cl, int C) {
+  __shared__ bf16_t halo[8][3][40];  // [plane][row][34 used]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int segs = W / 32;
+  const int yy = blockIdx.x / segs, x0 = (blockIdx.x - yy * segs) * 32, frame = blockIdx.y;
+  const bf16_t* img = x + (int64_t)frame * Cl * H * W;
+  for (int i = tid; i < Cl * 3 * 34; i += 256) {
+    const int xx = i % 34, dy = (i / 34) % 3, cl = i / (3 * 34);
+    const int iy = yy + dy - 1, ix = x0 + xx - 1;
+    const bool ok = iy >= 0 && iy < H && ix >= 0 && ix < W;
+    const bf16_t v = img[((int64_t)cl * H + min(max(iy, 0), H - 1)) * W + min(max(ix, 0), W - 1)];  // clamped: valid
+    halo[cl][dy][xx] = ok ? v : (bf16_t)0.f;
+  }
+  const int l32 = lane & 31, hh = lane >> 5;
+  const int tiles = C / 32;
+  // this wavefront's weights (tile slots beyond its share: the last tile again, never used)
+  bf16x8 bw[NTM][KS];
+#pragma unroll
+  for (int i = 0; i < NTM; ++i) {
+    const int t = min(wid + 4 * i, tiles - 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) bw[i][ks] = *reinterpret_cast<const bf16x8*>(wp + (int64_t)(t * 32 + l32) * 64 + 16 * ks + 8 * hh);
+  }
+  __syncthreads();
+  bf16x8 af[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int k = 16 * ks + 8 * hh + j;
+      const int cl = k / 9, tap = k - cl * 9;
+      const int dy = tap / 3, dx = tap - dy * 3;
+      af[ks][j] = k < 9 * Cl ? halo[cl][dy][l32 + dx] : (bf16_t)0.f;  // (cl < Cl <= 8 whenever it is read)
+    }
+  const int split = (yy * W + x0) >> 5, splits = (H * W) >> 5;
+  float* yrow = y + ((int64_t)frame * H * W + (int64_t)yy * W + x0) * C;
+#pragma unroll
+  for (int i = 0; i < NTM; ++i) {
+    const int t = wid + 4 * i;
+    if (t < tiles) {  // uniform over the wavefront
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks], bw[i][ks], acc, 0, 0, 0);
+      const int ch = t * 32 + l32;
+      const float bv = bias[ch];
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float v = acc[r] + bv;
+        const int px = 8 * (r >> 2) + 4 * hh + (r & 3);
+        yrow[(int64_t)px * C + ch] = v;
+        s1 += v;
+        s2 = fmaf(v, v, s2);
+      }
+      s1 += __shfl_xor(s1, 32, 64);
+      s2 += __shfl_xor(s2, 32, 64);
+      if (stat && hh == 0) {
+        float* sp = stat + (((int64_t)frame * splits + split) * C + ch) * 2;
+        sp[0] = s1;
+        sp[1] = s2;
+      }
+    }
+  }
+}
+
+// Returns hipErrorNotSupported for shapes it does not cover. wp: the weights as rows [C][64] of the operand type,
+// k = plane * 9 + tap, zeros beyond 9 * C_lat. stat: [frame][H * W / 32][C][2] or nullptr.
+hipError_t launch_conv_in_tile(hipStream_t s, int dt, const void* x, const void* wp, const float* bias, float* y, float* stat,
+                               int frames, int H, int W, int Cl, int C) {
+  if (dt != kBF16 || !wp || W % 32 || C % 32 || Cl < 1 || 9 * Cl > 48 || C / 32 > 12) return hipErrorNotSupported;
+  if (frames <= 0) return hipSuccess;
+  dim3 grid((unsigned)(H * (W / 32)), (unsigned)frames);
+  conv_in_tile_kernel<3, 3><<<grid, 256, 0, s>>>((const bf16_t*)x, (const bf16_t*)wp, bias, y, stat, H, W, Cl, C);
+  return hipGetLastError();
+}
+
 // Returns hipErrorNotSupported for shapes it does not cover (the caller then uses the general kernel).
 hipError_t launch_conv_out_tile(hipStream_t s, int dt, const void* u, const float* scale, const float* shift, const void* w,
                                 const float* bias, void* out, int frames, int H, int W, int C, int C_lat) {

@@ -132,6 +132,10 @@ hipError_t launch_temporal_attention(hipStream_t s, int dt, const void* qkv, voi
 
 // ---- small kernels -------------------------------------------------------------------------
 // h[frames*H*W][C] (fp32) = conv3x3(x[frames][Cl][H][W] of type dt); w_packed float [Cl*9][C], bias float [C].
+// conv_in for bf16 stages whose image rows are whole 32-pixel segments, with the GroupNorm partial sums of its
+// output (lc_conv.hip); hipErrorNotSupported otherwise
+hipError_t launch_conv_in_tile(hipStream_t s, int dt, const void* x, const void* wp, const float* bias, float* y, float* stat,
+                               int frames, int H, int W, int Cl, int C);
 hipError_t launch_conv_in(hipStream_t s, int dt, const void* x, void* h, int frames, int H, int W, int Cl, int C,
                           const float* w_packed, const float* bias);
 // planar [frames][C][HW] <-> channels-last [frames][HW][C]

@@ -282,3 +282,29 @@ def test_temporal_attention_on_matrix_cores(heads, head_dim, B, logit_scale, F):
             check(f"temporal core F={F} {heads}x{head_dim} P={P} x{logit_scale}", host(out), ref, cfg.dtype)
     finally:
         stage.close()
+
+
+@pytest.mark.parametrize("C,heads,head_dim,C_lat,H,W", [(320, 8, 40, 4, 6, 64), (64, 1, 64, 4, 4, 32), (128, 2, 64, 5, 2, 96),
+                                                       (320, 5, 64, 2, 8, 32), (384, 6, 64, 1, 2, 32)])
+def test_conv_in_tile_kernel(C, heads, head_dim, C_lat, H, W):
+    """bf16 stages whose image rows are whole 32-pixel segments run conv_in in a kernel of its own (one workgroup
+    per segment, all channels): widths that leave wavefronts without a channel tile (C = 64) or give them three
+    (C = 320, 384), 1 to 5 latent planes, one and several segments per row; borders on all four sides."""
+    cfg = synth.StageConfig(f"cin_{C}_{C_lat}_{H}x{W}", B=1, F=2, H=H, W=W, C_lat=C_lat, C=C, C_deep=64, groups=32, n_res=1,
+                            heads=heads, head_dim=head_dim, dtype="bf16")
+    stage, w = make_stage(cfg, seed=9)
+    try:
+        N = cfg.N
+        x = act(cfg, (N, C_lat, H, W), 171, 1.3) - np.float32(0.2)
+        xd = dev(stage, x)
+        h = empty32(stage, N * H * W, C)
+        h.fill_(7.0)
+        lcb.lc_op_conv_in(stage.ctx, xd.data_ptr(), h.data_ptr(), 1)  # one frame of the two: the rest stays untouched
+        stage.sync()
+        assert bool((h[H * W:] == 7.0).all())
+        lcb.lc_op_conv_in(stage.ctx, xd.data_ptr(), h.data_ptr(), N)
+        stage.sync()
+        ref = lo.conv3x3(x.astype(np.float64), w["conv_in.w"].astype(np.float64), w["conv_in.b"].astype(np.float64))
+        check(f"conv_in tile {cfg.name}", rows_to_planar(host(h), N, C, H, W), ref, cfg.dtype)
+    finally:
+        stage.close()

@@ -21,6 +21,9 @@ RAG_BF16 = synth.StageConfig("rag_bf16", B=2, F=3, H=10, W=12, C_lat=4, C=320, C
                              heads=8, head_dim=40, dtype="bf16")
 RAG_BF16_D64 = synth.StageConfig("rag_bf16_d64", B=1, F=5, H=12, W=18, C_lat=4, C=320, C_deep=640, groups=32,
                                  n_res=2, heads=5, head_dim=64, dtype="bf16")
+# image rows of whole 32-pixel segments: conv_in runs in its tile kernel, every linear layer on whole 32-row tiles
+W32_BF16 = synth.StageConfig("w32_bf16", B=1, F=3, H=6, W=32, C_lat=4, C=320, C_deep=640, groups=32, n_res=1,
+                             heads=8, head_dim=40, dtype="bf16")
 
 
 def oracle_for(cfg, w, **kw):
@@ -30,6 +33,7 @@ def oracle_for(cfg, w, **kw):
 @pytest.mark.parametrize("cfg,sharp,fc,tc", [
     (TINY, 1.0, 2, 0), (TINY, 8.0, 0, 0), (RAG_F32, 1.0, 4, 50), (RAG_F32, 8.0, 0, 0),
     (RAG_BF16, 1.0, 4, 0), (RAG_BF16, 8.0, 0, 33), (RAG_BF16_D64, 1.0, 2, 100), (RAG_BF16_D64, 8.0, 0, 0),
+    (W32_BF16, 1.0, 2, 0), (W32_BF16, 8.0, 0, 64),
 ], ids=lambda v: getattr(v, "name", str(v)))
 def test_full_and_cached_step_match_oracle(cfg, sharp, fc, tc):
     print(f"\n[case] {cfg.name} sharp={sharp} chunk=({fc},{tc})", flush=True)
@@ -61,7 +65,7 @@ def test_full_and_cached_step_match_oracle(cfg, sharp, fc, tc):
         stage.close()
 
 
-@pytest.mark.parametrize("cfg", [RAG_F32, RAG_BF16], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [RAG_F32, RAG_BF16, W32_BF16], ids=lambda c: c.name)
 def test_chunked_equals_unchunked_bitwise(cfg):
     stage, w = make_stage(cfg, seed=0, sharp=4.0, frame_chunk=0, token_chunk=0)
     try:
