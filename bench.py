@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes of one launch of the dominant kernel (up-path conv3x3, animatediff, frame chunk 4) from the
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (fetch x 2.0, the factor a plain copy
 # of known size gave). Valid only for the kernel source the counters were taken with.
-DOM_TRAFFIC = {"sha256_16": "5c6cb34dbb075710", "workload": "animatediff", "frame_chunk": 4,
+DOM_TRAFFIC = {"sha256_16": "31bb2c43b18a8fdb", "workload": "animatediff", "frame_chunk": 4,
                "bytes_per_launch": 83.6e6 + 22.3e6}
 DOM_SOURCES = ("lc_convws.hip", "lc_common.h", "lc_internal.h")  # what the dominant kernel is compiled from
 
