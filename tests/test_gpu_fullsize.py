@@ -2,7 +2,8 @@
 stage in a test's time, so the full sizes are covered three ways:
   * whole steps at the full image size, channel widths, head layout and chunk sizes, with one
     chunk's worth of frames (every launch then has the shape the timed configuration uses),
-    compared element by element with the oracle;
+    compared element by element with the oracle; for the benchmark workload also with all 16 frames of
+    one batch element (four frame chunks on two lanes, the temporal block over 16 frames);
   * single operators over all B*F frames, compared with the oracle on sampled frames, sampled
     query tokens and sampled spatial positions (each of which the oracle can compute on its own);
   * the method's invariants on the whole stage at full size: chunked == unchunked bit for bit,
@@ -30,7 +31,10 @@ def w64_of(w):
 # ------------------------------------------------------------------------------------------
 # whole steps, one chunk of frames at the full image size
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("base,F,full_too", [(AD, 4, True), (SVD, 2, False)], ids=lambda v: getattr(v, "name", str(v)))
+# (AD, 16): one batch element with all 16 frames, frame chunk 4 on two lanes - every launch of the cached step as
+# bench.py times it, the 16-frame temporal attention on its MFMA tiles included; the oracle takes about 15 s for it
+@pytest.mark.parametrize("base,F,full_too", [(AD, 4, True), (SVD, 2, False), (AD, 16, False)],
+                         ids=lambda v: getattr(v, "name", str(v)))
 def test_step_one_chunk_full_image(base, F, full_too):
     cfg = base.with_(B=1, F=F)
     fc, tc = min(base.frame_chunk, F), base.token_chunk
