@@ -102,6 +102,25 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
     return e
 
 
+def attention_core(q: np.ndarray, k: np.ndarray, v: np.ndarray, heads: int) -> np.ndarray:
+    """Per head: softmax(Q_h K_h^T / sqrt(d)) V_h, heads merged again on the channel axis.
+
+    q [.., Lq, C]; k, v [.., L, C]; head h owns channels [h*d, (h+1)*d), d = C / heads. No mask, no
+    dropout. This is the part of the attention block between the q/k/v projections and the output
+    projection."""
+    C = q.shape[-1]
+    d = C // heads
+    assert heads * d == C and k.shape[-1] == C and v.shape[-1] == C
+    o = np.empty(q.shape, dtype=q.dtype)
+    scale = 1.0 / math.sqrt(d)
+    for hd in range(heads):
+        sl = slice(hd * d, (hd + 1) * d)
+        qh, kh, vh = (np.ascontiguousarray(t[..., sl]) for t in (q, k, v))
+        s = (qh @ np.swapaxes(kh, -1, -2)) * q.dtype.type(scale)
+        o[..., sl] = softmax_rows(s) @ vh
+    return o
+
+
 def attention(xq: np.ndarray, xkv: np.ndarray, wq, wk, wv, wo, bo, heads: int) -> np.ndarray:
     """Multi-head self-attention of query rows xq [.., Lq, C] against rows xkv [.., L, C].
 
@@ -109,18 +128,8 @@ def attention(xq: np.ndarray, xkv: np.ndarray, wq, wk, wv, wo, bo, heads: int) -
     Y = O Wo^T + bo. (xq is xkv itself, or a slice of its rows when queries are chunked.)
     """
     C = xq.shape[-1]
-    d = C // heads
-    assert heads * d == C
-    q = _project(xq, wq)
-    k = _project(xkv, wk)
-    v = _project(xkv, wv)
-    o = np.empty_like(q)
-    scale = 1.0 / math.sqrt(d)
-    for hd in range(heads):
-        sl = slice(hd * d, (hd + 1) * d)
-        qh, kh, vh = (np.ascontiguousarray(t[..., sl]) for t in (q, k, v))
-        s = (qh @ np.swapaxes(kh, -1, -2)) * q.dtype.type(scale)
-        o[..., sl] = softmax_rows(s) @ vh
+    assert C % heads == 0
+    o = attention_core(_project(xq, wq), _project(xkv, wk), _project(xkv, wv), heads)
     return _project(o, wo) + bo
 
 

@@ -72,6 +72,23 @@ def attn_rows(X, wq, wk, wv, wo, bo, heads):
     return [[bo[o] + sum(wo[o][c] * O[i][c] for c in range(C)) for o in range(C)] for i in range(L)]
 
 
+def attn_core(Q, K, V, heads):
+    """Q: Lq rows, K and V: L rows, of C floats each -> Lq rows of C floats: per head, every query's
+    scores against all keys divided by sqrt(d), softmax over the keys, weighted sum of the values."""
+    Lq, L, C = len(Q), len(K), len(Q[0])
+    d = C // heads
+    O = zeros(Lq, C)
+    for hd in range(heads):
+        for i in range(Lq):
+            s = [sum(Q[i][hd * d + k] * K[j][hd * d + k] for k in range(d)) / math.sqrt(d) for j in range(L)]
+            m = max(s)
+            e = [math.exp(v - m) for v in s]
+            z = sum(e)
+            for k in range(d):
+                O[i][hd * d + k] = sum(e[j] * V[j][hd * d + k] for j in range(L)) / z
+    return O
+
+
 def stage(cfg, w, x, deep_in=None):
     """x: nested list [N][C_lat][H][W]. Returns (eps, deep). If deep_in is given it is used
     (cached step) instead of running the deep branch (full step)."""

@@ -168,6 +168,46 @@ def test_attention_matches_brute_force():
     assert np.max(np.abs(y - yb)) < 1e-12
 
 
+def test_attention_core_matches_brute_force():
+    # distinct q, k, v with fewer queries than keys (a query chunk), three heads
+    C, Lq, L, heads = 6, 3, 7, 3
+    q, k, v = rnd(Lq, C) * 2.0, rnd(L, C) * 2.0, rnd(L, C)
+    o = lo.attention_core(q, k, v, heads)
+    ob = np.array(brute.attn_core(q.tolist(), k.tolist(), v.tolist(), heads))
+    assert o.shape == (Lq, C)
+    assert np.max(np.abs(o - ob)) < 1e-13
+
+
+def test_attention_core_batched_matches_torch_sdpa_and_closed_forms():
+    C, Lq, L, heads = 16, 4, 9, 4
+    d = C // heads
+    q, k, v = rnd(2, 3, Lq, C), rnd(2, 3, L, C), rnd(2, 3, L, C)
+    o = lo.attention_core(q, k, v, heads)
+    split = lambda t: torch.from_numpy(t).reshape(2, 3, t.shape[2], heads, d).transpose(2, 3)
+    ot = TF.scaled_dot_product_attention(split(q), split(k), split(v)).transpose(2, 3).reshape(2, 3, Lq, C).numpy()
+    assert np.max(np.abs(o - ot)) < 1e-13
+    # zero queries: every key weighs the same, the output is the mean of the values
+    assert np.allclose(lo.attention_core(np.zeros_like(q), k, v, heads), v.mean(axis=2, keepdims=True).repeat(Lq, 2), atol=1e-14)
+    # one key: the softmax is 1 and the output is that value whatever the scores are
+    assert np.allclose(lo.attention_core(q, k[:, :, :1], v[:, :, :1], heads), v[:, :, :1].repeat(Lq, 2), atol=0)
+    # two keys, one head of size 4, q.k = 4 and 0: weights e^{4/2} : 1 (the 1/sqrt(d) scale)
+    qq = np.array([[1.0, 1.0, 1.0, 1.0]]); kk = np.array([[1.0, 1.0, 1.0, 1.0], [0.0, 0.0, 0.0, 0.0]])
+    vv = np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0]])
+    w0 = math.exp(2.0) / (math.exp(2.0) + 1.0)
+    assert np.allclose(lo.attention_core(qq, kk, vv, 1), [[w0, 1 - w0, 0, 0]], atol=1e-15)
+    # transposed-operand mistake (scores of k against q) would change a non-square case
+    assert o.shape == q.shape
+
+
+def test_attention_is_projections_around_the_core():
+    C, L, heads = 8, 6, 2
+    X = rnd(L, C)
+    wq, wk, wv, wo, bo = _attn_weights(C)
+    y = lo.attention(X[1:4], X, wq, wk, wv, wo, bo, heads)
+    o = np.array(brute.attn_core((X[1:4] @ wq.T).tolist(), (X @ wk.T).tolist(), (X @ wv.T).tolist(), heads))
+    assert np.max(np.abs(y - (o @ wo.T + bo))) < 1e-13
+
+
 def test_attention_matches_torch_sdpa():
     C, L, heads = 16, 9, 4
     X = rnd(3, L, C)
