@@ -19,6 +19,13 @@
  *     to lc_create) and return; lc_sync() drains both. Ordering between a step and a swap that
  *     touch the same device slot is enforced inside the library with events.
  *   - After lc_set_workspace() no call allocates or frees device memory.
+ *   - Lifetime of arguments: a [device] tensor passed to a step, an operator, lc_cache_write or
+ *     lc_cache_read is read or written by work that is only enqueued when the call returns. It must stay
+ *     valid, and must not be handed to other work on another stream, until lc_sync() has returned or an event
+ *     recorded on the compute stream after the call has completed. With a caching allocator this means:
+ *     allocate such tensors on the compute stream or keep a reference until then.
+ *   - lc_cache_peek / lc_cache_dev_peek return raw pointers with no ordering against a swap or step in
+ *     flight: call lc_sync() first.
  */
 #ifndef LIGHTCACHE_H
 #define LIGHTCACHE_H
@@ -79,7 +86,9 @@ typedef struct lc_weights {
 typedef struct lc_stats {
   int64_t full_steps, cached_steps, swaps_out, swaps_in;
   int64_t bytes_out, bytes_in;      /* bytes moved device->host / host->device */
-  double ms_out, ms_in;             /* summed copy durations (completed copies only) */
+  double ms_out, ms_in;             /* summed copy durations (completed, timed copies only) */
+  int64_t timed_out, timed_in;      /* copies ms_out / ms_in cover (a copy issued while all 256 timing event
+                                       pairs were still in flight is counted in swaps_* but not timed) */
   size_t workspace_bytes;           /* arena bytes in use for the current chunk setting */
   size_t weight_bytes;              /* device bytes of the packed private weight copies */
   size_t host_bank_bytes;           /* pinned host bytes */
@@ -91,7 +100,11 @@ enum {
   LC_K_SATTN, LC_K_TATTN, LC_K_PROJ, LC_K_CAT_APPLY, LC_K_CONV_UP, LC_K_CONV_OUT, LC_K_DEEP,
   LC_K_COUNT
 };
-typedef struct lc_profile { double ms[LC_K_COUNT]; int64_t launches[LC_K_COUNT]; } lc_profile;
+typedef struct lc_profile {
+  double ms[LC_K_COUNT];
+  int64_t launches[LC_K_COUNT];
+  int64_t dropped; /* launches of bracketed families that ran untimed because the bracket pool was full */
+} lc_profile;
 
 /* ---- host-only helpers (no GPU needed) ------------------------------------------------- */
 
@@ -118,8 +131,14 @@ const char* lc_last_error(const lc_ctx* ctx);
  * outlive the ctx. Allocates the pinned host bank (host_slots entries). */
 lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_stream, lc_ctx** out);
 
-/* Drains both streams and frees everything the library owns. NULL is a no-op. */
+/* Drains both streams and frees everything the library owns. NULL is a no-op. A pointer that lc_create did
+ * not return, or that has been destroyed before, is not dereferenced: LC_ERR_ARG. */
 lc_status lc_destroy(lc_ctx* ctx);
+
+/* Test hook for the error path of lc_create: the nth pinned allocation (1-based) that lc_create calls on this
+ * host thread make from now on fails as if the host were out of memory, once (0 = off). lc_create then
+ * returns LC_ERR_NOMEM and leaves nothing allocated. */
+lc_status lc_test_fail_host_alloc(int nth);
 
 /* Packs the weights into private device copies (allocates; synchronises the compute stream). */
 lc_status lc_load_weights(lc_ctx* ctx, const lc_weights* w /* [host] struct of [device] ptrs */);
@@ -200,7 +219,8 @@ lc_status lc_reset_stats(lc_ctx* ctx);
 
 /* mask: bit k set = bracket every launch of kernel family k (LC_K_*) with events on the compute
  * stream. lc_get_profile() synchronises, sums the brackets into out and clears them. At most
- * 4096 brackets are kept between two lc_get_profile calls; further launches are not timed. */
+ * 4096 brackets are kept between two lc_get_profile calls; further launches are not timed and are
+ * counted in lc_profile.dropped. */
 lc_status lc_set_profiling(lc_ctx* ctx, uint32_t mask);
 lc_status lc_get_profile(lc_ctx* ctx, lc_profile* out /* [host] */);
 
@@ -231,6 +251,13 @@ lc_status lc_op_res_block(lc_ctx* ctx, int layer, const void* x, void* y, int fr
  * log2(e)/sqrt(head_dim), scaled before it is rounded: the form lc_op_spatial_attention takes with
  * q_prescaled = 1 and the steps use between the two kernels. */
 lc_status lc_op_qkv(lc_ctx* ctx, int layer, const void* x, void* qkv, int frames);
+/* Whole attention blocks, in place on the float rows h (the sequence of launches a step issues, on the chunk
+ * scratch): h += proj(Attn(qkv(GroupNorm(h)))). Spatial: `frames` frames [frames*H*W, C], at most the frame
+ * chunk (LC_ERR_NOMEM beyond), queries in token chunks; the V third of q,k,v goes from the projection's
+ * epilogue straight into the transposed layout the attention kernel stages. Temporal: all B*F frames
+ * [B*F*H*W, C], in position chunks. */
+lc_status lc_op_spatial_block(lc_ctx* ctx, void* h, int frames);
+lc_status lc_op_temporal_block(lc_ctx* ctx, void* h);
 /* Spatial attention core: per frame and head, softmax(QK^T/sqrt(d))V over the H*W tokens of the
  * frame, for query tokens [q0, q1). qkv [frames*H*W, 3C] -> out [frames*H*W, C]; rows of other
  * queries are not written. q_prescaled: 0 = the q third holds Q; 1 = it holds Q*log2(e)/sqrt(d). */

@@ -56,12 +56,14 @@ class lc_weights(C.Structure):
 class lc_stats(C.Structure):
     _fields_ = [("full_steps", C.c_int64), ("cached_steps", C.c_int64), ("swaps_out", C.c_int64),
                 ("swaps_in", C.c_int64), ("bytes_out", C.c_int64), ("bytes_in", C.c_int64),
-                ("ms_out", C.c_double), ("ms_in", C.c_double), ("workspace_bytes", C.c_size_t),
+                ("ms_out", C.c_double), ("ms_in", C.c_double), ("timed_out", C.c_int64), ("timed_in", C.c_int64),
+                ("workspace_bytes", C.c_size_t),
                 ("weight_bytes", C.c_size_t), ("host_bank_bytes", C.c_size_t)]
 
 
 class lc_profile(C.Structure):
-    _fields_ = [("ms", C.c_double * len(KERNEL_FAMILIES)), ("launches", C.c_int64 * len(KERNEL_FAMILIES))]
+    _fields_ = [("ms", C.c_double * len(KERNEL_FAMILIES)), ("launches", C.c_int64 * len(KERNEL_FAMILIES)),
+                ("dropped", C.c_int64)]
 
 
 # name -> (restype, argtypes). Every symbol include/lightcache.h declares is listed here.
@@ -80,6 +82,9 @@ PROTOTYPES = {
     "lc_set_conv_general": (_I, [_P, _I]),
     "lc_full_step": (_I, [_P, _P, _P, _I]),
     "lc_cached_step": (_I, [_P, _P, _P, _I]),
+    "lc_test_fail_host_alloc": (_I, [_I]),
+    "lc_op_spatial_block": (_I, [_P, _P, _I]),
+    "lc_op_temporal_block": (_I, [_P, _P]),
     "lc_swap_out": (_I, [_P, _I, _I]),
     "lc_swap_in": (_I, [_P, _I, _I]),
     "lc_sync": (_I, [_P]),
@@ -188,6 +193,10 @@ def lc_cached_step(ctx, x_ptr: int, eps_ptr: int, dev_slot: int) -> None:
     _check(lib().lc_cached_step(ctx, x_ptr, eps_ptr, dev_slot), ctx)
 
 
+def lc_test_fail_host_alloc(nth: int) -> None:
+    _check(lib().lc_test_fail_host_alloc(nth), None)
+
+
 def lc_swap_out(ctx, dev_slot: int, host_slot: int) -> None:
     _check(lib().lc_swap_out(ctx, dev_slot, host_slot), ctx)
 
@@ -235,9 +244,12 @@ def lc_set_profiling(ctx, mask: int) -> None:
 
 
 def lc_get_profile(ctx) -> Dict[str, Dict[str, float]]:
+    """Per family {"ms", "launches"}; the key "dropped" holds lc_profile.dropped (an int)."""
     p = lc_profile()
     _check(lib().lc_get_profile(ctx, C.byref(p)), ctx)
-    return {n: {"ms": p.ms[i], "launches": int(p.launches[i])} for i, n in enumerate(KERNEL_FAMILIES)}
+    out = {n: {"ms": p.ms[i], "launches": int(p.launches[i])} for i, n in enumerate(KERNEL_FAMILIES)}
+    out["dropped"] = int(p.dropped)
+    return out
 
 
 def lc_op_conv_in(ctx, x_ptr, h_ptr, frames) -> None:
@@ -254,6 +266,14 @@ def lc_op_qkv(ctx, layer, x_ptr, qkv_ptr, frames) -> None:
 
 def lc_op_spatial_attention(ctx, qkv_ptr, out_ptr, frames, q0, q1, q_prescaled=0) -> None:
     _check(lib().lc_op_spatial_attention(ctx, qkv_ptr, out_ptr, frames, q0, q1, q_prescaled), ctx)
+
+
+def lc_op_spatial_block(ctx, h_ptr, frames) -> None:
+    _check(lib().lc_op_spatial_block(ctx, h_ptr, frames), ctx)
+
+
+def lc_op_temporal_block(ctx, h_ptr) -> None:
+    _check(lib().lc_op_temporal_block(ctx, h_ptr), ctx)
 
 
 def lc_op_temporal_attention(ctx, qkv_ptr, out_ptr, positions) -> None:
@@ -307,16 +327,18 @@ class Stage:
         self._ensure_arena(fc, tc)
 
     # -- memory helpers
+    # Tensors the library reads or writes are allocated, filled and converted on the compute stream: torch's
+    # caching allocator then hands a freed block only to later work of that same stream, so a temporary that
+    # the caller drops right after an (asynchronous) library call is not reused under a kernel that still
+    # reads it, and torch's own copies are ordered with the library's kernels.
     def to_device(self, a):
-        t = self.torch.from_numpy(a).to(self.device)
-        t = t.to(self.tdtype).contiguous()
-        # torch converted on ITS current stream; the library runs on `self.compute`, which does not
-        # wait for that stream by itself
-        self.torch.cuda.current_stream(self.device).synchronize()
-        return t
+        with self.torch.cuda.stream(self.compute):
+            t = self.torch.from_numpy(a).to(self.device)
+            return t.to(self.tdtype).contiguous()
 
     def empty(self, *shape):
-        return self.torch.empty(*shape, dtype=self.tdtype, device=self.device)
+        with self.torch.cuda.stream(self.compute):
+            return self.torch.empty(*shape, dtype=self.tdtype, device=self.device)
 
     def _ensure_arena(self, fc, tc):
         need = lc_workspace_bytes(self.ccfg, fc, tc)
@@ -367,6 +389,7 @@ class Stage:
         lc_cache_write(self.ctx, dev_slot, deep.data_ptr())
 
     def cache_read(self, dev_slot: int):
+        """The slot in public layout; lc_sync (or a wait on the compute stream) before it is read elsewhere."""
         c = self.cfg
         out = self.empty(c.N, c.C_deep, c.H // 2, c.W // 2)
         lc_cache_read(self.ctx, dev_slot, out.data_ptr())

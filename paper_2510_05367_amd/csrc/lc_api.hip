@@ -7,7 +7,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <set>
 #include <string>
 #include <vector>
 
@@ -19,6 +21,11 @@ using namespace lc;
 namespace {
 
 thread_local std::string g_err = "";
+thread_local int g_fail_host_alloc = 0;  // lc_test_fail_host_alloc: countdown to the pinned allocation that fails
+
+// contexts that lc_create has handed out and lc_destroy has not yet taken back
+std::mutex g_live_mu;
+std::set<const lc_ctx*> g_live;
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -80,6 +87,7 @@ struct lc_ctx {
   uint32_t prof_mask;
   std::vector<EvPair> prof_pool;
   size_t prof_used;
+  int64_t prof_dropped;  // launches that found the bracket pool empty since the last lc_get_profile
   std::string err;
 };
 
@@ -100,6 +108,8 @@ lc_status fail(lc_ctx* c, lc_status code, const char* fmt, ...) {
     hipError_t e_ = (expr);                                                                      \
     if (e_ != hipSuccess) return fail(c, LC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));   \
   } while (0)
+
+void destroy_ctx(lc_ctx* c);  // frees everything a (possibly half-built) context owns
 
 lc_status check_cfg(lc_ctx* c, const lc_config* g) {
   if (!g) return fail(c, LC_ERR_ARG, "config is NULL");
@@ -190,9 +200,14 @@ struct Prof {
         idx = c->prof_used++;
         c->prof_pool[idx].kind = k;
         on = hipEventRecord(c->prof_pool[idx].a, c->cs) == hipSuccess;
+        if (!on) { c->prof_used--; c->prof_dropped++; }
+      } else {
+        c->prof_dropped++;  // pool exhausted: the launch runs untimed and lc_get_profile says how many did
       }
     }
   }
+  // the launcher declined the shape and nothing ran: give the bracket back (it is the newest one)
+  void cancel() { if (on && idx + 1 == c->prof_used) { c->prof_used--; on = false; } }
   ~Prof() { if (on) (void)hipEventRecord(c->prof_pool[idx].b, c->cs); }
 };
 
@@ -282,7 +297,11 @@ lc_status gn_scale_shift(lc_ctx* c, const void* x, int frames, int rows_per_fram
 // geometry suits the weight-stationary kernel for every chunking (frames of a multiple of 32 positions).
 lc_status linear(lc_ctx* c, int kind, FusedDesc d, bool* wrote_stats, bool tiled) {
   hipError_t e = hipErrorNotSupported;
-  if (tiled) { Prof pr_(c, kind); e = launch_linear(c->cs, d); }
+  if (tiled) {
+    Prof pr_(c, kind);
+    e = launch_linear(c->cs, d);
+    if (e == hipErrorNotSupported) pr_.cancel();
+  }
   if (wrote_stats) *wrote_stats = e == hipSuccess && d.stat != nullptr;
   if (e == hipErrorNotSupported) {
     d.stat = nullptr;
@@ -332,7 +351,11 @@ lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat
   if (wrote_stats) *wrote_stats = false;
   if (c->pw.cin_wp) {  // (a property of the stage's geometry: the same kernel for every chunking)
     hipError_t e;
-    { Prof pr_(c, LC_K_CONV_IN); e = launch_conv_in_tile(c->cs, g.dtype, x, c->pw.cin_wp, c->pw.cin_b, (float*)h, stat, frames, g.H, g.W, g.C_lat, g.C); }
+    {
+      Prof pr_(c, LC_K_CONV_IN);
+      e = launch_conv_in_tile(c->cs, g.dtype, x, c->pw.cin_wp, c->pw.cin_b, (float*)h, stat, frames, g.H, g.W, g.C_lat, g.C);
+      if (e == hipErrorNotSupported) pr_.cancel();
+    }
     if (e == hipSuccess) {
       if (wrote_stats) *wrote_stats = stat != nullptr;
       return LC_OK;
@@ -347,7 +370,11 @@ lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat
     d.rows = (int64_t)frames * T; d.in_map = dense_map(); d.out_map = dense_map(); d.x = x; d.y = h;
     if (stat && T % 32 == 0) { d.stat = stat; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
     hipError_t e;
-    { Prof pr_(c, LC_K_CONV_IN); e = launch_linear(c->cs, d); }
+    {
+      Prof pr_(c, LC_K_CONV_IN);
+      e = launch_linear(c->cs, d);
+      if (e == hipErrorNotSupported) pr_.cancel();
+    }
     if (e == hipSuccess) {
       if (wrote_stats) *wrote_stats = d.stat != nullptr;
       return LC_OK;
@@ -430,6 +457,7 @@ lc_status conv_out(lc_ctx* c, const void* u, void* eps, int frames, StatRef u_st
     Prof pr_(c, LC_K_CONV_OUT);
     e = launch_conv_out_tile(c->cs, g.dtype, u, scale_p(c), shift_p(c), c->pw.out.w, c->pw.out.b, eps, frames, g.H, g.W, g.C,
                              g.C_lat);
+    if (e == hipErrorNotSupported) pr_.cancel();
   }
   if (e == hipSuccess) return LC_OK;
   if (e != hipErrorNotSupported) return fail(c, LC_ERR_HIP, "conv_out: %s", hipGetErrorString(e));
@@ -438,6 +466,83 @@ lc_status conv_out(lc_ctx* c, const void* u, void* eps, int frames, StatRef u_st
   d.planar_out = 1;
   LC_LAUNCH(c, LC_K_CONV_OUT, launch_fused(c->cs, d));
   return LC_OK;
+}
+
+// Spatial attention block of `nf` frames, in place on the fp32 rows hc [nf*T][C]:
+// hc += proj(Attn_spatial(qkv(GroupNorm(hc)))), queries in chunks of plan.qc tokens. `scr`: scratch for q,k rows,
+// V^T and the attention output of these frames. `st`: partial sums of hc if its producer wrote them. `stat_out`:
+// where the partial sums of the result go ([frame][T/32][C][2]) or nullptr; *wrote tells whether they were written.
+lc_status spatial_block(lc_ctx* c, char* hc, char* scr, int nf, StatRef st, float* stat_out, bool* wrote) {
+  const lc_config& g = c->cfg;
+  const int T = g.H * g.W, C = g.C;
+  const size_t es = dtype_size(g.dtype);
+  const int64_t pc = (int64_t)nf * T;
+  const bool tiled = T % 32 == 0;  // whole 32-row tiles in every frame: see linear()
+  const int Tp = attn_tp(T);
+  char* qk = scr;                                               // q,k rows [pc][2C]
+  char* vt = qk + align_up((size_t)pc * 2 * C * es);            // V^T [nf][C][Tp]
+  char* ao = vt + align_up((size_t)nf * C * Tp * es);
+  const AttnW& a = c->pw.sattn;
+  if (wrote) *wrote = false;
+  lc_status s = gn_scale_shift(c, hc, nf, T, C, a.gn, st);
+  if (s != LC_OK) return s;
+  RowMap fm{0, T, T};  // dense rows; frame of row r = r / T
+  {
+    // q and k as rows, v transposed straight from the GEMM epilogue into the layout the attention
+    // kernel stages (no scattered transposition later)
+    FusedDesc d = flinear_desc(c, a.wqkv, a.wqkv_f, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
+    d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
+    d.q_scale = attn_q_scale(g.head_dim); d.q_cols = C;  // the softmax scale rides on q, applied before rounding
+    s = linear(c, LC_K_QKV, d, nullptr, tiled);
+    if (s != LC_OK) return s;
+  }
+  for (int q0 = 0; q0 < T; q0 += c->plan.qc)
+    LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
+                                                      g.head_dim, q0, std::min(q0 + c->plan.qc, T), 1));
+  // the output projection closes the block; its partial sums are those of the next GroupNorm's input
+  FusedDesc d = flinear_desc(c, a.wo, a.wo_f, a.bo, C, C, pc, 0, dense_map(), dense_map(), ao, hc, hc, 1);
+  if (stat_out) { d.stat = stat_out; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
+  return linear(c, LC_K_PROJ, d, wrote, tiled);
+}
+
+// Temporal attention block over all N frames, in place on h [N*T][C] (fp32), per position chunk of plan.tc
+// positions on the lanes: h += proj(Attn_temporal(qkv(GroupNorm(h)))), statistics per whole frame. `tst`: partial
+// sums of h if its producers wrote them. *ustat: in, whether the partial sums of the result may go to partU;
+// out, whether they were written.
+lc_status temporal_block(lc_ctx* c, char* h, StatRef tst, bool* ustat) {
+  const lc_config& g = c->cfg;
+  const Plan& p = c->plan;
+  const int N = g.B * g.F, T = g.H * g.W, C = g.C;
+  const size_t es = dtype_size(g.dtype);
+  const bool tiled = T % 32 == 0;
+  const AttnW& a = c->pw.tattn;
+  lc_status s = gn_scale_shift(c, h, N, T, C, a.gn, tst);
+  if (s != LC_OK) return s;
+  const float *sc0 = scale_p(c), *sh0 = shift_p(c);  // of all frames: every position chunk reads them, on either lane
+  const int pos_lanes = loop_lanes(c, (T + p.tc - 1) / p.tc);
+  if (pos_lanes > 1 && (s = fork_lanes(c)) != LC_OK) return s;
+  for (int p0 = 0, ci = 0; p0 < T; p0 += p.tc, ++ci) {
+    use_lane(c, ci % pos_lanes);
+    char* ws = ws_ptr(c);
+    const int np = std::min(p.tc, T - p0);
+    const int64_t rows = (int64_t)N * np;
+    RowMap m{p0, T, np};  // dense row r = (frame r / np, position p0 + r % np)
+    char* qkv = ws;
+    char* ao = ws + align_up((size_t)rows * 3 * C * es);
+    FusedDesc dq = flinear_desc(c, a.wqkv, a.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(), h, nullptr, qkv, 0);
+    dq.scale = sc0; dq.shift = sh0;
+    s = linear(c, LC_K_QKV, dq, nullptr, tiled);
+    if (s != LC_OK) return s;
+    LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
+    // this projection finishes the skip feature: its partial sums, for the up block, go to partU
+    FusedDesc d = flinear_desc(c, a.wo, a.wo_f, a.bo, C, C, rows, 0, dense_map(), m, ao, h, h, 1);
+    if (*ustat) { d.stat = partU(c); d.stat_splits = T / 32; d.stat_rps = np; d.stat_off = p0; }
+    bool wrote = false;
+    s = linear(c, LC_K_PROJ, d, &wrote, tiled);
+    if (s != LC_OK) return s;
+    *ustat = *ustat && wrote;
+  }
+  return join_lanes(c);
 }
 
 lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool full) {
@@ -460,10 +565,6 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
     const int64_t pc = (int64_t)nf * T;
     char* hc = h + (size_t)n0 * T * C * 4;
     char* hb = ws;                                           // fp32 ping-pong partner of hc
-    const int Tp = attn_tp(T);
-    char* qk = ws + align_up((size_t)pc * C * 4);                 // q,k rows [pc][2C]
-    char* vt = qk + align_up((size_t)pc * 2 * C * es);            // V^T [nf][C][Tp]
-    char* ao = vt + align_up((size_t)nf * C * Tp * es);
     // a 3x3 convolution cannot run in place (its halo reads rows other workgroups write), so the
     // residual blocks alternate between hc and hb; start so that the last one lands in hc
     char* cur = (g.n_res % 2 == 0) ? hc : hb;
@@ -482,28 +583,10 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
       if (s != LC_OK) return s;
       cur = nxt;
     }
-    lc_status s = gn_scale_shift(c, hc, nf, T, C, w.sattn.gn, st);
-    if (s != LC_OK) return s;
-    RowMap fm{0, T, T};  // dense rows; frame of row r = r / T
     {
-      // q and k as rows, v transposed straight from the GEMM epilogue into the layout the attention
-      // kernel stages (no scattered transposition later)
-      FusedDesc d = flinear_desc(c, w.sattn.wqkv, w.sattn.wqkv_f, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
-      d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
-      d.q_scale = attn_q_scale(g.head_dim); d.q_cols = C;  // the softmax scale rides on q, applied before rounding
-      s = linear(c, LC_K_QKV, d, nullptr, tiled);
-      if (s != LC_OK) return s;
-    }
-    for (int q0 = 0; q0 < T; q0 += p.qc)
-      LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
-                                                        g.head_dim, q0, std::min(q0 + p.qc, T), 1));
-    {
-      // the output projection closes the spatial block; its partial sums are those of the temporal
-      // block's input, collected for all frames in partT
-      FusedDesc d = flinear_desc(c, w.sattn.wo, w.sattn.wo_f, w.sattn.bo, C, C, pc, 0, dense_map(), dense_map(), ao, hc, hc, 1);
-      if (tstat) { d.stat = partT(c) + (size_t)n0 * (T / 32) * C * 2; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
       bool wrote = false;
-      s = linear(c, LC_K_PROJ, d, &wrote, tiled);
+      lc_status s = spatial_block(c, hc, ws + align_up((size_t)pc * C * 4), nf, st,
+                                  tstat ? partT(c) + (size_t)n0 * (T / 32) * C * 2 : nullptr, &wrote);
       if (s != LC_OK) return s;
       tstat = tstat && wrote;
     }
@@ -516,33 +599,8 @@ lc_status run_step_lanes(lc_ctx* c, const void* x, void* eps, int slot, bool ful
   // ---- temporal block: per-frame statistics over whole frames, then per position chunk
   bool ustat = T % 32 == 0 && p.tc % 32 == 0;  // the 32-row tiles of a position chunk stay inside a frame and a split
   {
-    lc_status s = gn_scale_shift(c, h, N, T, C, w.tattn.gn, tstat ? StatRef{partT(c), T / 32} : StatRef{nullptr, 0});
+    lc_status s = temporal_block(c, h, tstat ? StatRef{partT(c), T / 32} : StatRef{nullptr, 0}, &ustat);
     if (s != LC_OK) return s;
-    const float *sc0 = scale_p(c), *sh0 = shift_p(c);  // of all frames: every position chunk reads them, on either lane
-    const int pos_lanes = loop_lanes(c, (T + p.tc - 1) / p.tc);
-    if (pos_lanes > 1 && (s = fork_lanes(c)) != LC_OK) return s;
-    for (int p0 = 0, ci = 0; p0 < T; p0 += p.tc, ++ci) {
-      use_lane(c, ci % pos_lanes);
-      char* ws = ws_ptr(c);
-      const int np = std::min(p.tc, T - p0);
-      const int64_t rows = (int64_t)N * np;
-      RowMap m{p0, T, np};  // dense row r = (frame r / np, position p0 + r % np)
-      char* qkv = ws;
-      char* ao = ws + align_up((size_t)rows * 3 * C * es);
-      FusedDesc dq = flinear_desc(c, w.tattn.wqkv, w.tattn.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(), h, nullptr, qkv, 0);
-      dq.scale = sc0; dq.shift = sh0;
-      s = linear(c, LC_K_QKV, dq, nullptr, tiled);
-      if (s != LC_OK) return s;
-      LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
-      // this projection finishes the skip feature: its partial sums, for the up block, go to partU
-      FusedDesc d = flinear_desc(c, w.tattn.wo, w.tattn.wo_f, w.tattn.bo, C, C, rows, 0, dense_map(), m, ao, h, h, 1);
-      if (ustat) { d.stat = partU(c); d.stat_splits = T / 32; d.stat_rps = np; d.stat_off = p0; }
-      bool wrote = false;
-      s = linear(c, LC_K_PROJ, d, &wrote, tiled);
-      if (s != LC_OK) return s;
-      ustat = ustat && wrote;
-    }
-    if ((s = join_lanes(c)) != LC_OK) return s;
   }
 
   char* deep = slot_ptr(c, slot);
@@ -684,17 +742,22 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
   c->have_weights = false; c->wblob = nullptr; c->wblob_bytes = 0;
   memset(&c->pw, 0, sizeof c->pw);
   memset(&c->st, 0, sizeof c->st);
-  c->prof_mask = 0; c->prof_used = 0;
+  c->prof_mask = 0; c->prof_used = 0; c->prof_dropped = 0;
   const size_t entry = lc_cache_entry_bytes(cfg);
   auto bail = [&](lc_status code, const char* what, hipError_t e) {
     g_err = std::string(what) + ": " + hipGetErrorString(e);
-    lc_destroy(c);
+    destroy_ctx(c);
     return code;
   };
   for (int i = 0; i < cfg->host_slots; ++i) {
     void* p = nullptr;
-    hipError_t e = hipHostMalloc(&p, entry, hipHostMallocDefault);
-    if (e != hipSuccess) return bail(LC_ERR_NOMEM, "hipHostMalloc (pinned cache bank)", e);
+    hipError_t e = hipErrorOutOfMemory;
+    const bool injected = g_fail_host_alloc > 0 && --g_fail_host_alloc == 0;
+    if (!injected) e = hipHostMalloc(&p, entry, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();  // the failure is reported through the status, not left for the next HIP call
+      return bail(LC_ERR_NOMEM, injected ? "pinned cache bank (injected failure)" : "hipHostMalloc (pinned cache bank)", e);
+    }
     c->host.push_back(p);
   }
   c->host_filled.assign(cfg->host_slots, 0);
@@ -730,12 +793,35 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
     c->copy_pool.push_back(pr);
   }
   c->st.host_bank_bytes = entry * cfg->host_slots;
+  {
+    std::lock_guard<std::mutex> lk(g_live_mu);
+    g_live.insert(c);
+  }
   *out = c;
   return LC_OK;
 }
 
 lc_status lc_destroy(lc_ctx* c) {
   if (!c) return LC_OK;
+  {
+    // a pointer lc_create did not hand out, or one that has been destroyed already, is not touched
+    std::lock_guard<std::mutex> lk(g_live_mu);
+    if (!g_live.erase(c)) return fail(nullptr, LC_ERR_ARG, "lc_destroy: unknown or already destroyed context");
+  }
+  destroy_ctx(c);
+  return LC_OK;
+}
+
+lc_status lc_test_fail_host_alloc(int nth) {
+  if (nth < 0) return fail(nullptr, LC_ERR_ARG, "nth must be >= 0");
+  g_fail_host_alloc = nth;
+  return LC_OK;
+}
+
+}  // extern "C"
+
+namespace {
+void destroy_ctx(lc_ctx* c) {
   (void)hipStreamSynchronize(c->cs_main);
   (void)hipStreamSynchronize(c->ss);
   for (int i = 0; i + 1 < kMaxLanes; ++i) {
@@ -750,8 +836,10 @@ lc_status lc_destroy(lc_ctx* c) {
     for (EvPair& pr : *v) { (void)hipEventDestroy(pr.a); (void)hipEventDestroy(pr.b); }
   if (c->wblob) (void)hipFree(c->wblob);
   delete c;
-  return LC_OK;
 }
+}  // namespace
+
+extern "C" {
 
 lc_status lc_load_weights(lc_ctx* c, const lc_weights* w) {
   if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
@@ -940,7 +1028,25 @@ static lc_status swap_common(lc_ctx* c, int dev_slot, int host_slot) {
   return LC_OK;
 }
 
+// folds the copies that have completed into the statistics and returns their event pairs to the pool
+static void harvest_copy_pairs(lc_ctx* c) {
+  size_t keep = 0;
+  for (size_t i = 0; i < c->copy_pending.size(); ++i) {
+    EvPair& pr = c->copy_pending[i];
+    float ms = 0.f;
+    if (hipEventQuery(pr.b) == hipSuccess && hipEventElapsedTime(&ms, pr.a, pr.b) == hipSuccess) {
+      (pr.kind == 0 ? c->st.ms_out : c->st.ms_in) += ms;
+      (pr.kind == 0 ? c->st.timed_out : c->st.timed_in)++;
+      c->copy_pool.push_back(pr);
+    } else {
+      c->copy_pending[keep++] = pr;
+    }
+  }
+  c->copy_pending.resize(keep);
+}
+
 static EvPair* take_copy_pair(lc_ctx* c) {
+  if (c->copy_pool.empty()) harvest_copy_pairs(c);
   if (c->copy_pool.empty()) return nullptr;
   c->copy_pending.push_back(c->copy_pool.back());
   c->copy_pool.pop_back();
@@ -1050,12 +1156,7 @@ lc_status lc_get_stats(lc_ctx* c, lc_stats* out) {
   if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
   if (!out) return fail(c, LC_ERR_ARG, "out is NULL");
   LC_HIP(c, hipStreamSynchronize(c->ss));
-  for (EvPair& pr : c->copy_pending) {
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, pr.a, pr.b) == hipSuccess) (pr.kind == 0 ? c->st.ms_out : c->st.ms_in) += ms;
-    c->copy_pool.push_back(pr);
-  }
-  c->copy_pending.clear();
+  harvest_copy_pairs(c);
   *out = c->st;
   return LC_OK;
 }
@@ -1101,11 +1202,37 @@ lc_status lc_get_profile(lc_ctx* c, lc_profile* out) {
     }
   }
   c->prof_used = 0;
+  pf.dropped = c->prof_dropped;
+  c->prof_dropped = 0;
   *out = pf;
   return LC_OK;
 }
 
 // ---- single operators -------------------------------------------------------------------------
+
+lc_status lc_op_spatial_block(lc_ctx* c, void* h, int frames) {
+  lc_status s = op_checks(c, frames);
+  if (s != LC_OK) return s;
+  if (!h) return fail(c, LC_ERR_ARG, "NULL tensor");
+  if (frames > c->plan.fc) return fail(c, LC_ERR_NOMEM, "the chunk scratch holds %d frames, not %d", c->plan.fc, frames);
+  // the scratch layout of a frame chunk inside a step: the fp32 ping-pong copy first, then what this block uses
+  const size_t skip = align_up((size_t)frames * c->cfg.H * c->cfg.W * c->cfg.C * 4);
+  return spatial_block(c, (char*)h, ws_ptr(c) + skip, frames, StatRef{nullptr, 0}, nullptr, nullptr);
+}
+
+lc_status lc_op_temporal_block(lc_ctx* c, void* h) {
+  lc_status s = op_checks(c, 1);
+  if (s != LC_OK) return s;
+  if (!h) return fail(c, LC_ERR_ARG, "NULL tensor");
+  bool ustat = false;
+  s = temporal_block(c, (char*)h, StatRef{nullptr, 0}, &ustat);
+  if (s != LC_OK) {  // leave the streams joined and the first lane selected whatever happened
+    const std::string keep = c->err;
+    (void)join_lanes(c);
+    c->err = keep;
+  }
+  return s;
+}
 
 lc_status lc_op_res_block(lc_ctx* c, int layer, const void* x, void* y, int frames) {
   lc_status s = op_checks(c, frames);
@@ -1194,9 +1321,7 @@ lc_status lc_op_conv_in(lc_ctx* c, const void* x, void* h, int frames) {
   lc_status s = op_checks(c, frames);
   if (s != LC_OK) return s;
   if (!x || !h) return fail(c, LC_ERR_ARG, "NULL tensor");
-  const lc_config& g = c->cfg;
   return conv_in_run(c, x, h, frames, nullptr, nullptr);
-  return LC_OK;
 }
 
 lc_status lc_op_conv_out(lc_ctx* c, const void* u, void* eps, int frames) {

@@ -8,8 +8,14 @@ from paper_2510_05367_amd import synth
 
 # Tolerances (HIP path vs float64 oracle on identical, already-rounded inputs):
 #   fp32 storage: rel-L2 <= 1e-4
-#   bf16 storage: rel-L2 <= 1e-2 and max-abs <= 2e-2 (on the step output eps, whose scale is O(1))
+#   bf16 storage: rel-L2 <= 1e-2 and max-abs <= 2e-2, on every tensor compared (operator outputs and eps).
+#   One exception, `cache_entry=True`: a deep feature written in bf16 (the cache entry of a normal step, the
+#   output of the residual block at C_deep). Its values reach |v| = 8..32 and a bf16 number has 8 significant
+#   bits, so storing the exact result already moves it by up to half an ulp <= 2^-8 |v| (0.031 at |v| = 8,
+#   0.0625 at 16), more than 2e-2. There the bound is taken element by element as 2e-2 + 2^-8 |ref|: the stated
+#   tolerance plus what the storage format alone forces. rel-L2 <= 1e-2 holds unchanged.
 TOL = {"f32": dict(rel=1e-4, abs=None), "bf16": dict(rel=1e-2, abs=2e-2)}
+BF16_HALF_ULP = 2.0 ** -8
 
 
 def rel_l2(a, b):
@@ -18,7 +24,7 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def check(name, got, ref, dtype, abs_scale=1.0):
+def check(name, got, ref, dtype, cache_entry=False):
     """got: torch tensor or array; ref: float64 array of the same shape."""
     g = got.float().cpu().numpy() if isinstance(got, torch.Tensor) else np.asarray(got)
     assert g.shape == ref.shape, (name, g.shape, ref.shape)
@@ -30,7 +36,8 @@ def check(name, got, ref, dtype, abs_scale=1.0):
     print(msg, flush=True)
     assert r <= tol["rel"], msg
     if tol["abs"] is not None:
-        assert m <= tol["abs"] * abs_scale, msg
+        bound = tol["abs"] + (BF16_HALF_ULP * np.abs(ref) if cache_entry else 0.0)
+        assert np.all(np.abs(g.astype(np.float64) - ref) <= bound), msg
     return r, m
 
 

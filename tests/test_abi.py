@@ -31,7 +31,27 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(lcb.lc_config) == 15 * 4
     assert ctypes.sizeof(lcb.lc_weights) == 8 * (2 + 4 * lcb.LC_MAX_RES + 7 + 7 + 2 + 4 + 4 + 4)
-    assert ctypes.sizeof(lcb.lc_profile) == 16 * len(lcb.KERNEL_FAMILIES)
+    assert ctypes.sizeof(lcb.lc_profile) == 16 * len(lcb.KERNEL_FAMILIES) + 8
+    assert ctypes.sizeof(lcb.lc_stats) == 8 * 13
+
+
+def test_destroy_rejects_pointers_it_did_not_hand_out():
+    # NULL is a no-op; any other pointer that lc_create never returned (or that was destroyed before) must be
+    # refused without being dereferenced
+    lcb.lc_destroy(None)
+    junk = ctypes.create_string_buffer(4096)
+    with pytest.raises(lcb.LcError) as e:
+        lcb.lc_destroy(ctypes.c_void_p(ctypes.addressof(junk)))
+    assert e.value.status == lcb.LC_ERR_ARG
+    assert "destroyed" in lcb.lc_last_error()
+    assert junk.raw == bytes(4096)
+
+
+def test_host_alloc_failure_hook_validates():
+    with pytest.raises(lcb.LcError) as e:
+        lcb.lc_test_fail_host_alloc(-1)
+    assert e.value.status == lcb.LC_ERR_ARG
+    lcb.lc_test_fail_host_alloc(0)
 
 
 @pytest.mark.parametrize("name", list(synth.CONFIGS))

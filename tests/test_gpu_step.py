@@ -48,7 +48,7 @@ def test_full_and_cached_step_match_oracle(cfg, sharp, fc, tc):
         stage.sync()
         ref = orc.full_step(x, 0)
         check("full_step eps", host(eps), ref, cfg.dtype)
-        check("full_step deep", host(stage.cache_read(0)), orc.dev[0], cfg.dtype, abs_scale=8.0)
+        check("full_step deep", host(stage.cache_read(0)), orc.dev[0], cfg.dtype, cache_entry=True)
         # cache step on a foreign deep feature in slot 1
         deep = synth.make_deep(cfg, 2)
         stage.cache_write(1, dev(stage, deep))
@@ -217,6 +217,56 @@ def test_state_machine_errors():
         assert e.value.status == lcb.LC_ERR_ARG
     finally:
         lcb.lc_destroy(ctx)
+
+
+def test_double_destroy_and_failed_pinned_allocation():
+    cfg = RAG_F32
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    ccfg = lcb.make_config(cfg, host_slots=3, dev_slots=2)
+    ctx = lcb.lc_create(ccfg, s1.cuda_stream, s2.cuda_stream)
+    lcb.lc_destroy(ctx)
+    with pytest.raises(lcb.LcError) as e:  # the second time the pointer is unknown: an error, not a crash
+        lcb.lc_destroy(ctx)
+    assert e.value.status == lcb.LC_ERR_ARG
+    # the second of three pinned allocations fails: LC_ERR_NOMEM, nothing left behind, the next create works
+    free0 = torch.cuda.mem_get_info()[0]
+    lcb.lc_test_fail_host_alloc(2)
+    with pytest.raises(lcb.LcError) as e:
+        lcb.lc_create(ccfg, s1.cuda_stream, s2.cuda_stream)
+    assert e.value.status == lcb.LC_ERR_NOMEM and "pinned" in str(e.value)
+    ctx = lcb.lc_create(ccfg, s1.cuda_stream, s2.cuda_stream)  # the hook fires once
+    lcb.lc_destroy(ctx)
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free0 - (8 << 20)
+
+
+def test_profile_reports_dropped_brackets_and_untimed_copies():
+    cfg = RAG_F32
+    stage, w = make_stage(cfg, seed=0, frame_chunk=1, host_slots=1)
+    try:
+        x = dev(stage, synth.make_latents(cfg, 1))
+        eps = stage.empty(*x.shape)
+        stage.full_step(x, eps, 0)
+        stage.swap_out(0, 0)
+        lcb.lc_set_profiling(stage.ctx, 1 << lcb.LC_K["gn_final"])
+        stage.cached_step(x, eps, 0)
+        per_step = lcb.lc_get_profile(stage.ctx)["gn_final"]["launches"]
+        assert per_step >= 6
+        n = 4096 // per_step + 10  # more finalize launches than the 4096 brackets
+        for i in range(n):
+            stage.cached_step(x, eps, 0)
+        prof = lcb.lc_get_profile(stage.ctx)
+        assert prof["gn_final"]["launches"] == 4096 and prof["dropped"] == per_step * n - 4096
+        assert lcb.lc_get_profile(stage.ctx)["dropped"] == 0
+        lcb.lc_set_profiling(stage.ctx, 0)
+        # more swaps than timing event pairs between two lc_get_stats: completed pairs are recycled on the way
+        lcb.lc_reset_stats(stage.ctx)
+        for i in range(600):
+            stage.swap_in(0, 1)
+        st = lcb.lc_get_stats(stage.ctx)
+        assert st.swaps_in == 600 and 256 <= st.timed_in <= 600 and st.ms_in > 0
+    finally:
+        stage.close()
 
 
 def test_profiling_brackets_count_launches():
