@@ -172,6 +172,7 @@ class Oracle:
         self.w = {k: np.asarray(v, dtype=self.dtype) for k, v in weights.items()}
         self.frame_chunk = 0
         self.token_chunk = 0
+        self.progress = None  # optional callable(str): told after every chunk of a step (long runs report where they are)
         self.dev: List[Optional[np.ndarray]] = [None] * dev_slots
         self.host: List[Optional[np.ndarray]] = [None] * host_slots
         c = cfg
@@ -196,6 +197,10 @@ class Oracle:
             # same number of (frame, position) rows per pass as a frame chunk has
             return -(-(self.frame_chunk * c.H * c.W) // (c.B * c.F))
         return 0
+
+    def _tick(self, what: str) -> None:
+        if self.progress is not None:
+            self.progress(what)
 
     # ---- blocks ---------------------------------------------------------------------
     def _gn(self, x, prefix):
@@ -245,7 +250,10 @@ class Oracle:
             for i in range(c.n_res):
                 t = self.res_block(t, f"res{i}")
             h[n0:n1] = self.spatial_block(t)
-        return self.temporal_block(h)
+            self._tick(f"shallow down: frames {n0}..{n1 - 1} of {N}")
+        h = self.temporal_block(h)
+        self._tick("temporal block")
+        return h
 
     def deep_branch(self, s):
         """Stand-in for everything below the shallow stage: stride-2 conv then one residual block."""
@@ -266,6 +274,7 @@ class Oracle:
             cat = np.concatenate([s[n0:n1], up2(deep[n0:n1])], axis=1)
             u = conv3x3(silu(self._gn(cat, "up")), self.w["up.w"], self.w["up.b"])
             eps[n0:n1] = conv3x3(silu(self._gn(u, "out")), self.w["out.w"], self.w["out.b"])
+            self._tick(f"shallow up: frames {n0}..{n1 - 1} of {N}")
         return eps
 
     # ---- steps ----------------------------------------------------------------------

@@ -47,6 +47,8 @@ def test_step_one_chunk_full_image(base, F, full_too):
     stage, w = make_stage(cfg, seed=0, frame_chunk=fc, token_chunk=tc)
     try:
         orc = lo.Oracle(cfg, w64_of(w))
+        orc.set_chunk(fc, tc)  # (the oracle's chunked loops give what its unchunked ones give: CPU tests)
+        orc.progress = lambda what: print(f"[oracle] {what}", flush=True)
         x = synth.make_latents(cfg, 1)
         xd = dev(stage, x)
         deep = synth.make_deep(cfg, 2)
