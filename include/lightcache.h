@@ -190,6 +190,24 @@ lc_status lc_full_step(lc_ctx* ctx, const void* x, void* eps, int dev_slot);
  * branch. */
 lc_status lc_cached_step(lc_ctx* ctx, const void* x, void* eps, int dev_slot);
 
+/* For callers that cannot allocate device memory and have none to hand over as a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc. The same cache step as lc_cached_step,
+ * with the library's own static device array (LC_STATIC_SCRATCH_BYTES per GPU, held from library load until the
+ * process ends) as its arena, so neither lc_set_workspace nor a filled device slot is needed, and the call
+ * itself allocates nothing (no hipMalloc / hipFree, no allocating library routine).
+ * x [device, B,F,C_lat,H,W] -> eps [device, same shape]; deep [device, N, C_deep, H/2, W/2], public layout as
+ * in lc_cache_write: the deep feature to concatenate ([FC]); it is copied into the scratch in the library's
+ * layout first. All three stay valid until the compute stream has been synchronised.
+ * LC_ERR_NOMEM if lc_workspace_bytes(cfg, current chunk setting) > LC_STATIC_SCRATCH_BYTES (a smaller chunk may
+ * fit; the AnimateDiff-sized stages do not). LC_ERR_STATE without weights. The context's own workspace,
+ * device slots and cache bank are not touched. Every call on a GPU shares that GPU's array, whichever context
+ * it comes from, and finds the last call's contents there (nothing in it needs clearing: every kernel writes
+ * what it later reads): calls are safe one after the other on one compute stream; calls that overlap on one
+ * GPU (two contexts on different streams, two host threads) race. */
+#define LC_STATIC_SCRATCH_BYTES (64u << 20)
+lc_status lc_cached_step_static(lc_ctx* ctx, const void* x, const void* deep, void* eps);
+size_t lc_static_scratch_bytes(void); /* LC_STATIC_SCRATCH_BYTES as the library was built */
+
 /* Asynchronous cache swapping ([AS]). Both enqueue one copy on the side stream and return.
  * swap_out: device slot -> host bank entry, after the work that produced the slot.
  * swap_in : host bank entry -> device slot, after the last enqueued step that reads the slot.

@@ -82,6 +82,8 @@ PROTOTYPES = {
     "lc_set_conv_general": (_I, [_P, _I]),
     "lc_full_step": (_I, [_P, _P, _P, _I]),
     "lc_cached_step": (_I, [_P, _P, _P, _I]),
+    "lc_cached_step_static": (_I, [_P, _P, _P, _P]),
+    "lc_static_scratch_bytes": (C.c_size_t, []),
     "lc_test_fail_host_alloc": (_I, [_I]),
     "lc_op_spatial_block": (_I, [_P, _P, _I]),
     "lc_op_temporal_block": (_I, [_P, _P]),
@@ -191,6 +193,14 @@ def lc_full_step(ctx, x_ptr: int, eps_ptr: int, dev_slot: int) -> None:
 
 def lc_cached_step(ctx, x_ptr: int, eps_ptr: int, dev_slot: int) -> None:
     _check(lib().lc_cached_step(ctx, x_ptr, eps_ptr, dev_slot), ctx)
+
+
+def lc_cached_step_static(ctx, x_ptr: int, deep_ptr: int, eps_ptr: int) -> None:
+    _check(lib().lc_cached_step_static(ctx, x_ptr, deep_ptr, eps_ptr), ctx)
+
+
+def lc_static_scratch_bytes() -> int:
+    return lib().lc_static_scratch_bytes()
 
 
 def lc_test_fail_host_alloc(nth: int) -> None:

@@ -18,6 +18,13 @@
 
 using namespace lc;
 
+// Scratch of lc_cached_step_static: one array per GPU the library is loaded on, held until the process ends.
+// Host code never uses this name as an address (it is only the host-side handle of the symbol): the device
+// address is looked up once per device in lc_create (static_scratch_ptr) and that pointer is what kernels,
+// and the arena plan, are given.
+constexpr size_t kStaticScratchBytes = (size_t)LC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local std::string g_err = "";
@@ -26,6 +33,9 @@ thread_local int g_fail_host_alloc = 0;  // lc_test_fail_host_alloc: countdown t
 // contexts that lc_create has handed out and lc_destroy has not yet taken back
 std::mutex g_live_mu;
 std::set<const lc_ctx*> g_live;
+
+constexpr int kMaxDevices = 64;
+void* g_static_ptr[kMaxDevices] = {nullptr};  // device address of g_static_scratch on each device (under g_live_mu)
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -88,10 +98,25 @@ struct lc_ctx {
   std::vector<EvPair> prof_pool;
   size_t prof_used;
   int64_t prof_dropped;  // launches that found the bracket pool empty since the last lc_get_profile
+  void* static_scratch;  // this device's static scratch (lc_cached_step_static)
   std::string err;
 };
 
 namespace {
+
+// Device address of this device's copy of the static scratch; looked up on first use, with `dev` current.
+hipError_t static_scratch_ptr(int dev, void** out) {
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_live_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess) return e;
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return hipSuccess;
+}
 
 lc_status fail(lc_ctx* c, lc_status code, const char* fmt, ...) {
   char buf[512];
@@ -749,6 +774,11 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
     destroy_ctx(c);
     return code;
   };
+  c->static_scratch = nullptr;
+  {
+    const hipError_t e = static_scratch_ptr(dev, &c->static_scratch);
+    if (e != hipSuccess) return bail(LC_ERR_HIP, "hipGetSymbolAddress (static scratch)", e);
+  }
   for (int i = 0; i < cfg->host_slots; ++i) {
     void* p = nullptr;
     hipError_t e = hipErrorOutOfMemory;
@@ -1207,6 +1237,35 @@ lc_status lc_get_profile(lc_ctx* c, lc_profile* out) {
   *out = pf;
   return LC_OK;
 }
+
+lc_status lc_cached_step_static(lc_ctx* c, const void* x, const void* deep, void* eps) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!x || !deep || !eps) return fail(c, LC_ERR_ARG, "x, deep and eps must not be NULL");
+  if (!c->have_weights) return fail(c, LC_ERR_STATE, "weights not loaded");
+  if (!c->static_scratch) return fail(c, LC_ERR_STATE, "static scratch not available on this device");
+  if (c->plan.total > kStaticScratchBytes)
+    return fail(c, LC_ERR_NOMEM,
+                "this stage needs %zu bytes of scratch with the current chunk setting; the static scratch of "
+                "lc_cached_step_static holds %zu: use a smaller chunk, or lc_set_workspace + lc_cached_step",
+                c->plan.total, kStaticScratchBytes);
+  const lc_config& g = c->cfg;
+  // the step runs as lc_cached_step does, with the static array as its arena and the deep feature in slot 0
+  // of that arena; the context's own arena, its slots and what it knows about them are put back afterwards
+  char* const arena0 = c->arena;
+  const char filled0 = c->dev_filled[0], pending0 = c->in_pending[0], statv0 = c->deep_stat_valid[0];
+  c->arena = (char*)c->static_scratch;
+  c->dev_filled[0] = 1; c->in_pending[0] = 0; c->deep_stat_valid[0] = 0;
+  lc_status s = LC_OK;
+  const hipError_t e = launch_planar_to_cl(c->cs, g.dtype, deep, slot_ptr(c, 0), g.B * g.F, g.C_deep, (g.H / 2) * (g.W / 2));
+  if (e != hipSuccess) s = fail(c, LC_ERR_HIP, "layout change of the deep feature: %s", hipGetErrorString(e));
+  if (s == LC_OK) s = run_step(c, x, eps, 0, false);
+  c->arena = arena0;
+  c->dev_filled[0] = filled0; c->in_pending[0] = pending0; c->deep_stat_valid[0] = statv0;
+  if (s == LC_OK) c->st.cached_steps++;
+  return s;
+}
+
+size_t lc_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 // ---- single operators -------------------------------------------------------------------------
 

@@ -33,6 +33,7 @@ def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(lcb.lc_weights) == 8 * (2 + 4 * lcb.LC_MAX_RES + 7 + 7 + 2 + 4 + 4 + 4)
     assert ctypes.sizeof(lcb.lc_profile) == 16 * len(lcb.KERNEL_FAMILIES) + 8
     assert ctypes.sizeof(lcb.lc_stats) == 8 * 13
+    assert lcb.lc_static_scratch_bytes() == 64 << 20
 
 
 def test_destroy_rejects_pointers_it_did_not_hand_out():
