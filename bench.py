@@ -5,13 +5,23 @@ A "step" is one pass of the whole hot path (conv_in, residual blocks, spatial an
 attention blocks, fetch of the cached deep feature, skip-concat, up conv, conv_out) over one batch
 of seeded synthetic input shaped like the AnimateDiff workload (batch 2 x 16 frames of 4 x 64 x 64
 latents, 320 channels, 8 heads of 40, frame chunk 4), with every input already resident in HBM.
-Prints ONE JSON line.
+Prints ONE JSON line. Beside the headline it carries, measured in the same run:
+  * `roofline`   the kernel family with the largest total time, and `rooflines` for each big MFMA kernel
+  * `svdxt`      the SVD-XT-like workload (batch 2 x 25 frames of 72 x 128, frame chunk 5, token chunk 2304)
+  * `tiny`       the small fp32 stage: step latencies, and the 25-step schedule (normal step every 3rd,
+                 swap-out after each, prefetch one step ahead) with frame chunk 16, 8, 4, 2
+  * `stress`     the 50-step schedule (interval 5, bank of 10 host entries) on batch 2 x 32 frames of 96 x 96,
+                 with the chunk the footprint model picks under 64 GB and predicted vs measured peak
+  * `swap`       host-to-device and device-to-host copies against the steps they hide behind
+  * `hbm_modes`  footprint with a resident cache, one device buffer, two device buffers
+  * `cpu_baseline` the CPU oracle on the same input
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -21,30 +31,36 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # dense MFMA peaks of MI355X, TFLOP/s
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes of one launch of the dominant kernel (up-path conv3x3, animatediff, frame chunk 4) from the
-# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (fetch x 2.0, the factor a plain copy
-# of known size gave). Valid only for the kernel source the counters were taken with.
-DOM_TRAFFIC = {"sha256_16": "31bb2c43b18a8fdb", "workload": "animatediff", "frame_chunk": 4,
-               "bytes_per_launch": 83.6e6 + 22.3e6}
-DOM_SOURCES = ("lc_convws.hip", "lc_common.h", "lc_internal.h")  # what the dominant kernel is compiled from
+# HBM-side bytes of one launch of a kernel family (animatediff, frame chunk 4) from the rocprofv3 FETCH_SIZE /
+# WRITE_SIZE runs summarised under profiles/ (fetch x 2.0, the factor a plain copy of known size gave). Valid only
+# for the kernel sources the counters were taken with: `sha256_16` covers the listed files, else traffic is null.
+TRAFFIC = {
+    "conv_up": {"sources": ("lc_convws.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "31bb2c43b18a8fdb",
+                "bytes_per_launch": 83.6e6 + 22.3e6},
+    "sattn": {"sources": ("lc_attn.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "",
+              "bytes_per_launch": 61.0e6 + 12.6e6},
+    "conv_res": {"sources": ("lc_convws.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "31bb2c43b18a8fdb",
+                 "bytes_per_launch": 54.5e6 + 22.3e6},
+}
+TRAFFIC_WORKLOAD = ("animatediff", 4)
 
 
-def dominant_traffic(cfg_name, fc):
+def measured_traffic(family, cfg_name, fc):
     import hashlib
+    t = TRAFFIC.get(family)
+    if t is None or (cfg_name, fc) != TRAFFIC_WORKLOAD:
+        return None
     m = hashlib.sha256()
     try:
-        for f in DOM_SOURCES:
+        for f in t["sources"]:
             m.update(open(os.path.join(ROOT, "paper_2510_05367_amd", "csrc", f), "rb").read())
     except OSError:
         return None
-    h = m.hexdigest()[:16]
-    if h != DOM_TRAFFIC["sha256_16"] or cfg_name != DOM_TRAFFIC["workload"] or fc != DOM_TRAFFIC["frame_chunk"]:
-        return None  # the kernel has changed since the counters were taken
-    return DOM_TRAFFIC["bytes_per_launch"]
+    return t["bytes_per_launch"] if m.hexdigest()[:16] == t["sha256_16"] else None  # null once the kernel has changed
 
 
 def family_flops(cfg):
-    """Algorithmic FLOPs per cached step of each MFMA kernel family."""
+    """Algorithmic FLOPs per cached step of each MFMA kernel family (unpadded head size, 9 taps)."""
     P, C, Cd = cfg.N * cfg.T, cfg.C, cfg.C_deep
     return {
         "conv_res": cfg.n_res * 2.0 * 9 * C * C * P,
@@ -53,6 +69,7 @@ def family_flops(cfg):
         "proj": 2 * 2.0 * C * C * P,
         "sattn": 4.0 * cfg.T * cfg.T * cfg.head_dim * cfg.heads * cfg.N,
         "tattn": 4.0 * cfg.F * cfg.F * cfg.head_dim * cfg.heads * cfg.B * cfg.T,
+        "tblock": 8.0 * C * C * P + 4.0 * cfg.F * cfg.F * cfg.head_dim * cfg.heads * cfg.B * cfg.T,
         "conv_in": 2.0 * 9 * cfg.C_lat * C * P,
         "conv_out": 2.0 * 9 * cfg.C_lat * C * P,
     }
@@ -66,8 +83,9 @@ def family_bytes(cfg):
     return {
         "gn_stats": (P // 4) * Cd * es,  # only the deep feature has a statistics pass of its own (once per slot content)
         "conv_in": P * cfg.C_lat * es + P * C * 4,
-        "conv_out": P * C * es + P * cfg.C_lat * es,
+        "conv_out": P * C * 4 + P * cfg.C_lat * es,
         "tattn": 4 * P * C * es,
+        "tblock": 2 * P * C * 4,  # the fused temporal block reads the fp32 stream once and writes it once
         # the projections are near the machine balance (193 FLOP per byte): both rooflines are reported.
         # q,k,v: fp32 stream in, three operand tensors out; output projection: operand in, fp32 residual in and out
         "qkv": 2 * (P * C * 4 + 3 * P * C * es),
@@ -75,9 +93,11 @@ def family_bytes(cfg):
     }
 
 
-def cpu_baseline(cfg, w, budget_frames=1):
-    """The float64 oracle, as it stands, on a bounded sample: a cached step over `budget_frames`
-    frames (batch 1) of the same per-frame shape."""
+MFMA_FAMILIES = ("conv_res", "conv_up", "qkv", "proj", "sattn", "tblock")
+
+
+def cpu_baseline(cfg, w):
+    """The float64 oracle, as it stands, on the same input: one cached step of the whole workload."""
     import numpy as np
     from oracle import lightcache_oracle as lo
     from paper_2510_05367_amd import synth
@@ -86,25 +106,218 @@ def cpu_baseline(cfg, w, budget_frames=1):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-    small = cfg.with_(B=1, F=budget_frames)
-    x = synth.make_latents(small, 1)
-    deep = synth.make_deep(small, 2)
-    orc = lo.Oracle(small, {k: v.astype(np.float64) for k, v in w.items()})
+    x = synth.make_latents(cfg, 1)
+    deep = synth.make_deep(cfg, 2)
+    orc = lo.Oracle(cfg, {k: v.astype(np.float64) for k, v in w.items()})
+    orc.set_chunk(cfg.frame_chunk, cfg.token_chunk)
     orc.cache_write(0, deep)
     t0 = time.time()
     orc.cached_step(x, 0)
     dt = time.time() - t0
-    return {"value": small.cached_step_flops() / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads),
+    return {"value": cfg.cached_step_flops() / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads),
             "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"one cached step of the float64 numpy oracle over {budget_frames} frames (batch 1) of the "
-                      f"same {cfg.H}x{cfg.W}x{cfg.C} per-frame shape ({small.cached_step_flops() / 1e9:.1f} GFLOP)"}
+            "sample": f"one cached step of the float64 numpy oracle on the whole workload input (B={cfg.B}, F={cfg.F}, "
+                      f"{cfg.H}x{cfg.W}x{cfg.C}; {cfg.cached_step_flops() / 1e9:.1f} GFLOP)"}
+
+
+class Timer:
+    """Per-step HIP events on the compute stream (the stream the steps are launched on; a chunked step forks to
+    the library's second stream and joins back into it) plus the wall clock around the whole region."""
+
+    def __init__(self, torch, stage):
+        self.torch, self.stage = torch, stage
+
+    def run(self, n, fn):
+        ev = [self.torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        self.torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev[0].record(self.stage.compute)
+        for i in range(n):
+            fn(i)
+            ev[i + 1].record(self.stage.compute)
+        self.torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        per = [ev[i].elapsed_time(ev[i + 1]) for i in range(n)]
+        return {"wall_ms_per_step": wall / n, "median_ms": statistics.median(per), "min_ms": min(per), "per_step": per}
+
+
+def make_stage(lcb, synth, cfg, w, fc, tc, host_slots, dev_slots, lanes):
+    stage = lcb.Stage(cfg, w, host_slots=host_slots, dev_slots=dev_slots, frame_chunk=fc, token_chunk=tc)
+    stage.set_lanes(lanes)
+    return stage
+
+
+def profile_families(lcb, stage, step, n):
+    """One-lane pass with every kernel family bracketed by events: ms and launches per step."""
+    lcb.lc_set_profiling(stage.ctx, (1 << len(lcb.KERNEL_FAMILIES)) - 1)
+    lcb.lc_get_profile(stage.ctx)
+    for i in range(n):
+        step(i)
+    pf = lcb.lc_get_profile(stage.ctx)
+    lcb.lc_set_profiling(stage.ctx, 0)
+    dropped = pf.pop("dropped", 0)
+    out = {k: {"ms_per_step": v["ms"] / n, "launches_per_step": v["launches"] // n} for k, v in pf.items()
+           if v["launches"]}
+    return out, dropped
+
+
+def breakdown_record(cfg, fams, peak):
+    fam_fl, fam_by = family_flops(cfg), family_bytes(cfg)
+    out = {}
+    for name, v in fams.items():
+        e = {"ms_per_step": round(v["ms_per_step"], 4), "launches_per_step": v["launches_per_step"]}
+        if name in MFMA_FAMILIES and name in fam_fl:
+            e["tflops"] = round(fam_fl[name] / (v["ms_per_step"] * 1e-3) / 1e12, 1)
+            e["frac_mfma_peak"] = round(e["tflops"] / peak, 4)
+        if name in fam_by:
+            e["gbs"] = round(fam_by[name] / (v["ms_per_step"] * 1e-3) / 1e9, 1)
+            e["frac_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+        out[name] = e
+    return out
+
+
+def roofline_of(lcb, torch, stage, cfg, fc, family, step, K, peak):
+    """K steps with one kernel family bracketed by events on the stream it is launched on. With a bracket set the
+    library keeps a step on one lane, so the kernel is timed with the device to itself."""
+    lcb.lc_set_profiling(stage.ctx, 1 << lcb.LC_K[family])
+    lcb.lc_get_profile(stage.ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
+    ms_one = (time.perf_counter() - t0) * 1e3 / K
+    d = lcb.lc_get_profile(stage.ctx)[family]
+    lcb.lc_set_profiling(stage.ctx, 0)
+    launches = max(d["launches"], 1)
+    avg_ms = d["ms"] / launches
+    if family in MFMA_FAMILIES:
+        work = family_flops(cfg)[family] * K / launches
+        achieved = work / (avg_ms * 1e-3) / 1e12
+        r = {"kernel": family, "bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+             "frac": round(achieved / peak, 4), "flops_per_launch": work}
+    else:
+        work = family_bytes(cfg)[family] * K / launches
+        achieved = work / (avg_ms * 1e-3) / 1e9
+        r = {"kernel": family, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": round(achieved / PEAK_HBM_GBS, 4), "bytes_per_launch": work}
+    r.update({"traffic": measured_traffic(family, cfg.name, fc), "traffic_unit": "bytes/launch",
+              "avg_launch_ms": round(avg_ms, 5), "launches_per_step": d["launches"] // K,
+              "total_ms_per_step": round(d["ms"] / K, 4)})
+    return r, ms_one
+
+
+def device_bytes_in_use(torch, stats):
+    """Measured device footprint: the high-water mark of what torch allocated since the last reset (the arena the
+    library works in, x, eps, and the temporaries of loading weights and inputs) plus the library's own allocation
+    (its packed weights)."""
+    return torch.cuda.max_memory_allocated() + stats.weight_bytes
+
+
+def footprint(lcb, cfg, fc, tc, dev_slots, host_slots, weight_bytes):
+    """Predicted device bytes: arena (footprint model) + packed weights + x + eps."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    io = 2 * cfg.N * cfg.C_lat * cfg.T * es
+    return lcb.lc_workspace_bytes(lcb.make_config(cfg, host_slots, dev_slots), fc, tc) + weight_bytes + io
+
+
+def run_schedule(stage, x, eps, steps, interval, host_slots, mode):
+    """The denoising loop with a normal step every `interval` steps. mode: "resident" (the deep feature stays in
+    one device slot, nothing is copied), "single" (swap-out after each normal step, swap-in into the same device
+    slot right before each cache step), "double" (swap-in one step ahead into the other device slot)."""
+    refresh = -1
+    prefetched = None
+    for t in range(steps):
+        slot = t % 2 if mode == "double" else 0
+        if t % interval == 0:
+            refresh += 1
+            stage.full_step(x, eps, slot)
+            if mode != "resident":
+                stage.swap_out(slot, refresh % host_slots)
+        else:
+            if mode == "single" or (mode == "double" and prefetched != (t, slot)):
+                stage.swap_in(refresh % host_slots, slot)
+            stage.cached_step(x, eps, slot)
+        nxt = t + 1
+        if mode == "double" and nxt < steps and nxt % interval != 0:
+            stage.swap_in(refresh % host_slots, nxt % 2)
+            prefetched = (nxt, nxt % 2)
+
+
+def time_schedule(torch, stage, x, eps, steps, interval, host_slots, mode, reps):
+    run_schedule(stage, x, eps, steps, interval, host_slots, mode)  # untimed
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        run_schedule(stage, x, eps, steps, interval, host_slots, mode)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) * 1e3
+        best = dt if best is None else min(best, dt)
+    return best
+
+
+def copy_times(lcb, stage, n=5):
+    """Plain copies of one cache entry on the idle device: (ms out, ms in)."""
+    stage.sync()
+    lcb.lc_reset_stats(stage.ctx)
+    for _ in range(n):
+        stage.swap_out(0, 0)
+    for _ in range(n):
+        stage.swap_in(0, 1)
+    st = lcb.lc_get_stats(stage.ctx)
+    stage.swap_in(0, 0)
+    stage.sync()
+    return st.ms_out / max(st.timed_out, 1), st.ms_in / max(st.timed_in, 1)
+
+
+def schedule_record(lcb, torch, synth, cfg, w, fc, tc, steps, interval, host_slots, reps, lanes):
+    """Schedule of `steps` steps in the three cache modes; overlap = 1 - (t_double - t_resident) / t_copies."""
+    torch.cuda.empty_cache()
+    torch.cuda.reset_peak_memory_stats()
+    stage = make_stage(lcb, synth, cfg, w, fc, tc, host_slots, 2, lanes)
+    try:
+        x = stage.to_device(synth.make_latents(cfg, 1))
+        eps = stage.empty(*x.shape)
+        stage.full_step(x, eps, 0)
+        ms_out, ms_in = copy_times(lcb, stage)
+        t_res = time_schedule(torch, stage, x, eps, steps, interval, host_slots, "resident", reps)
+        t_single = time_schedule(torch, stage, x, eps, steps, interval, host_slots, "single", reps)
+        t_double = time_schedule(torch, stage, x, eps, steps, interval, host_slots, "double", reps)
+        n_full = (steps + interval - 1) // interval
+        n_cached = steps - n_full
+        copies = n_full * ms_out + n_cached * ms_in
+        entry = lcb.lc_cache_entry_bytes(stage.ccfg)
+        tm = Timer(torch, stage)
+        cached = tm.run(max(10, min(50, steps)), lambda i: stage.cached_step(x, eps, 0))
+        st = lcb.lc_get_stats(stage.ctx)
+        measured = device_bytes_in_use(torch, st)
+
+        def ov(t):
+            return round(min(1.0, max(0.0, 1.0 - max(0.0, t - t_res) / copies)), 4) if copies > 0 else None
+        return {"frame_chunk": fc, "token_chunk": tc, "effective_frame_chunk": min(fc, cfg.N) if fc else cfg.N,
+                "steps": steps, "normal_steps": n_full, "cache_steps": n_cached,
+                "cached_step_ms": round(cached["median_ms"], 4),
+                "schedule_ms": {"resident": round(t_res, 3), "single_buffer": round(t_single, 3),
+                                "double_buffer": round(t_double, 3)},
+                "copy_ms": {"d2h": round(ms_out, 4), "h2d": round(ms_in, 4), "all_copies_of_schedule": round(copies, 3)},
+                "link_gbs": {"d2h": round(entry / (ms_out * 1e-3) / 1e9, 1) if ms_out > 0 else None,
+                             "h2d": round(entry / (ms_in * 1e-3) / 1e9, 1) if ms_in > 0 else None},
+                "overlap_frac": {"single_buffer": ov(t_single), "double_buffer": ov(t_double)},
+                "workspace_gb": round(st.workspace_bytes / 1e9, 5),
+                "peak_hbm_gb_predicted": round(footprint(lcb, cfg, fc, tc, 2, host_slots, st.weight_bytes) / 1e9, 5),
+                "peak_hbm_gb_measured": round(measured / 1e9, 5),
+                "host_bank_gb": round(st.host_bank_bytes / 1e9, 4)}
+    finally:
+        stage.close()
+        torch.cuda.empty_cache()
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="animatediff", choices=["tiny", "animatediff", "svdxt", "stress"])
     ap.add_argument("--frame-chunk", type=int, default=None)
     ap.add_argument("--token-chunk", type=int, default=None)
@@ -112,13 +325,15 @@ def main():
                     help="streams a chunked step spreads its chunks over (lc_set_lanes); 1 = compute stream only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="headline workload only (no svdxt / tiny / stress records)")
+    ap.add_argument("--steps-only", action="store_true",
+                    help="warm-up and the timed steps only, then a short JSON line (the command rocprofv3 is pointed at)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain device copy of 256 MiB three times (reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
-    import numpy as np
     import torch
     from paper_2510_05367_amd import binding as lcb
     from paper_2510_05367_amd import synth
@@ -134,14 +349,14 @@ def main():
     tc = cfg.token_chunk if args.token_chunk is None else args.token_chunk
     w = synth.make_weights(cfg, 0)
     torch.cuda.reset_peak_memory_stats()
-    stage = lcb.Stage(cfg, w, host_slots=2, dev_slots=2, frame_chunk=fc, token_chunk=tc)
+    stage = make_stage(lcb, synth, cfg, w, fc, tc, 2, 2, args.lanes)
     x = stage.to_device(synth.make_latents(cfg, 1))
     eps = stage.empty(*x.shape)
     stage.cache_write(0, stage.to_device(synth.make_deep(cfg, 2)))
-    stage.set_lanes(args.lanes)
     stage.sync()
     K, W = args.steps, args.warmup
-    dom = "conv_up"
+    peak = PEAK_TFLOPS[cfg.dtype]
+    tm = Timer(torch, stage)
 
     if args.copy_calibration:
         src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=stage.device)
@@ -151,102 +366,101 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(W):
+    def step(i):
         stage.cached_step(x, eps, 0)
+
+    for i in range(W):
+        step(i)
     stage.sync()
 
     # ---- timed region: K cached steps as the library runs them (chunks spread over `lanes` streams)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(K):
-        stage.cached_step(x, eps, 0)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms = (t1 - t0) * 1e3 / K
-    # ---- the same K steps again with the dominant kernel bracketed by events on its own stream. With a
-    #      bracket set the library keeps a step on one lane, so the kernel is timed with the device to itself
-    #      (on two lanes its launches share the device with the other lane's kernels and a per-kernel time
-    #      says little); ms_per_step_one_lane is this region's step time.
-    lcb.lc_set_profiling(stage.ctx, 1 << lcb.LC_K[dom])
-    lcb.lc_get_profile(stage.ctx)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(K):
-        stage.cached_step(x, eps, 0)
-    torch.cuda.synchronize()
-    ms_one = (time.perf_counter() - t0) * 1e3 / K
-    prof = lcb.lc_get_profile(stage.ctx)
-    lcb.lc_set_profiling(stage.ctx, 0)
+    timed = tm.run(K, step)
+    ms = timed["wall_ms_per_step"]
     flops = cfg.cached_step_flops()
     tflops = flops / (ms * 1e-3) / 1e12
-    peak = PEAK_TFLOPS[cfg.dtype]
-    fam_fl = family_flops(cfg)
-    d = prof[dom]
-    dom_ms = d["ms"] / max(d["launches"], 1)
-    dom_flops = fam_fl[dom] * K / max(d["launches"], 1)
-    achieved = dom_flops / (dom_ms * 1e-3) / 1e12
-    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "traffic": dominant_traffic(cfg.name, fc), "traffic_unit": "bytes/launch",
-                "avg_launch_ms": round(dom_ms, 5), "launches_per_step": d["launches"] // K,
-                "flops_per_launch": dom_flops}
+    if args.steps_only:
+        print(json.dumps({"workload": cfg.name, "frame_chunk": fc, "token_chunk": tc, "lanes": args.lanes, "steps": K,
+                          "warmup": W, "ms_per_step": round(ms, 4), "cached_step_ms_median": round(timed["median_ms"], 4),
+                          "tflops": round(tflops, 2)}))
+        stage.close()
+        return
 
-    # ---- per-family breakdown (a separate profiled pass; brackets add small gaps)
-    breakdown = None
-    if not args.no_breakdown:
-        lcb.lc_set_profiling(stage.ctx, (1 << len(lcb.KERNEL_FAMILIES)) - 1)
-        nb = min(K, 5)
-        for _ in range(nb):
-            stage.cached_step(x, eps, 0)
-        pf = lcb.lc_get_profile(stage.ctx)
-        lcb.lc_set_profiling(stage.ctx, 0)
-        fam_by = family_bytes(cfg)
-        breakdown = {}
-        for name, v in pf.items():
-            if v["launches"] == 0:
-                continue
-            e = {"ms_per_step": round(v["ms"] / nb, 4), "launches_per_step": v["launches"] // nb}
-            if name in fam_fl and name not in ("conv_in", "conv_out", "tattn"):
-                e["tflops"] = round(fam_fl[name] / (v["ms"] / nb * 1e-3) / 1e12, 1)
-                e["frac_mfma_peak"] = round(e["tflops"] / peak, 4)
-            if name in fam_by:
-                e["gbs"] = round(fam_by[name] / (v["ms"] / nb * 1e-3) / 1e9, 1)
-                e["frac_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
-            breakdown[name] = e
+    # ---- per-family pass (one lane, every family bracketed), then the family with the largest total time again
+    #      on its own for `roofline`, and each big MFMA kernel for `rooflines`
+    fams, dropped = profile_families(lcb, stage, step, min(K, 5))
+    dom = max(fams, key=lambda k: fams[k]["ms_per_step"])
+    roofline, ms_one = roofline_of(lcb, torch, stage, cfg, fc, dom, step, K, peak)
+    roofline["time_dominant"] = True
+    rooflines = [roofline]
+    for fam in ("sattn", "conv_up", "conv_res"):
+        if fam != dom and fam in fams:
+            r, _ = roofline_of(lcb, torch, stage, cfg, fc, fam, step, min(K, 10), peak)
+            r["time_dominant"] = False
+            rooflines.append(r)
+    breakdown = None if args.no_breakdown else breakdown_record(cfg, fams, peak)
 
-    # ---- asynchronous swapping: copy alone, step alone (above), step with a prefetch in flight
-    stage.swap_out(0, 0)
-    stage.sync()
-    lcb.lc_reset_stats(stage.ctx)
-    for _ in range(5):
-        stage.swap_in(0, 1)
-    st = lcb.lc_get_stats(stage.ctx)
-    copy_ms = st.ms_in / 5
+    # ---- asynchronous swapping on the headline workload
     entry = lcb.lc_cache_entry_bytes(stage.ccfg)
-    stage.swap_in(0, 0)
+    stage.swap_out(0, 0)
+    ms_out, ms_in = copy_times(lcb, stage)
 
     def prefetched_steps(n):
         for i in range(n):
             stage.cached_step(x, eps, i % 2)
             stage.swap_in(0, (i + 1) % 2)  # prefetch for the next step into the other buffer
     # untimed, like the warm-up of the plain steps, but longer: the first time the host runs many steps with
-    # copies ahead of the device, a few lc_swap_in calls block for milliseconds inside the runtime (seen at
-    # iterations 9-15 of the first such loop, never again afterwards)
+    # copies ahead of the device, a few lc_swap_in calls block for milliseconds inside the runtime
     prefetched_steps(max(W, 24))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     prefetched_steps(K)
     torch.cuda.synchronize()
     ms_swap = (time.perf_counter() - t0) * 1e3 / K
-    overlap = 1.0 - max(0.0, ms_swap - ms) / copy_ms if copy_ms > 0 else None
-    swap = {"entry_mb": round(entry / 1e6, 1), "h2d_ms": round(copy_ms, 4),
-            "h2d_gbs": round(entry / (copy_ms * 1e-3) / 1e9, 1) if copy_ms > 0 else None,
-            "step_ms_with_prefetch": round(ms_swap, 4),
-            "overlap_frac": None if overlap is None else round(min(1.0, max(0.0, overlap)), 4)}
+    overlap_in = 1.0 - max(0.0, ms_swap - ms) / ms_in if ms_in > 0 else None
+
+    # device-to-host: a normal step followed by the swap-out of what it produced, then a cache step on the other
+    # slot (the copy runs behind that step), against the same pair without the copy
+    e2 = stage.empty(*x.shape)
+
+    def pair(n, with_copy):
+        for i in range(n):
+            stage.full_step(x, e2, 0)
+            if with_copy:
+                stage.swap_out(0, 1)
+            stage.cached_step(x, eps, 1)
+    pair(3, True)
+    torch.cuda.synchronize()
+    n_pair = max(5, K // 4)
+    t0 = time.perf_counter(); pair(n_pair, False); torch.cuda.synchronize()
+    pair_plain = (time.perf_counter() - t0) * 1e3 / n_pair
+    t0 = time.perf_counter(); pair(n_pair, True); torch.cuda.synchronize()
+    pair_copy = (time.perf_counter() - t0) * 1e3 / n_pair
+    overlap_out = 1.0 - max(0.0, pair_copy - pair_plain) / ms_out if ms_out > 0 else None
+    clip = lambda v: None if v is None else round(min(1.0, max(0.0, v)), 4)
+    swap = {"entry_mb": round(entry / 1e6, 1), "h2d_ms": round(ms_in, 4), "d2h_ms": round(ms_out, 4),
+            "h2d_gbs": round(entry / (ms_in * 1e-3) / 1e9, 1) if ms_in > 0 else None,
+            "d2h_gbs": round(entry / (ms_out * 1e-3) / 1e9, 1) if ms_out > 0 else None,
+            "step_ms_with_prefetch": round(ms_swap, 4), "overlap_frac": clip(overlap_in),
+            "normal_plus_cache_step_ms": round(pair_plain, 4), "same_with_swap_out_ms": round(pair_copy, 4),
+            "overlap_frac_d2h": clip(overlap_out)}
 
     stats = lcb.lc_get_stats(stage.ctx)
-    peak_alloc = torch.cuda.max_memory_allocated() + stats.weight_bytes
-    floor = cfg.N * cfg.T * cfg.C * 4 + 2 * entry + stats.weight_bytes + 2 * x.numel() * x.element_size()
-
+    measured_peak = device_bytes_in_use(torch, stats)
+    es = 2 if cfg.dtype == "bf16" else 4
+    io = 2 * cfg.N * cfg.C_lat * cfg.T * es
+    floor = cfg.N * cfg.T * cfg.C * 4 + 2 * entry + stats.weight_bytes + io
+    # the three cache modes side by side: what a double buffer costs against keeping the feature resident, and
+    # what a bank of many entries would cost if it stayed on the device
+    hbm_modes = {
+        "resident_one_slot_gb": round(footprint(lcb, cfg, fc, tc, 1, 0, stats.weight_bytes) / 1e9, 4),
+        "swap_single_buffer_gb": round(footprint(lcb, cfg, fc, tc, 1, 2, stats.weight_bytes) / 1e9, 4),
+        "swap_double_buffer_gb": round(footprint(lcb, cfg, fc, tc, 2, 2, stats.weight_bytes) / 1e9, 4),
+        "second_lane_scratch_gb": round((lcb.lc_workspace_bytes(stage.ccfg, fc, tc) -
+                                         _one_lane_bytes(lcb, stage.ccfg, fc, tc)) / 1e9, 4),
+        "unchunked_double_buffer_gb": round(footprint(lcb, cfg, 0, 0, 2, 2, stats.weight_bytes) / 1e9, 4),
+        "note": "a double buffer holds two device copies of the deep feature: for one cached feature it uses MORE HBM "
+                "than keeping it resident; swapping saves memory only against a bank of several entries kept on the "
+                "device (stress record: 10 entries)"}
     out = {
         "metric": "shallow-branch TFLOP/s of one cached step (cached-step ms, MFMA util, peak HBM GB alongside)",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -255,18 +469,133 @@ def main():
         "config": {"workload": f"{cfg.name}: cached step, B={cfg.B} F={cfg.F} latent {cfg.C_lat}x{cfg.H}x{cfg.W}, "
                                f"C={cfg.C}, C_deep={cfg.C_deep}, {cfg.heads} heads x {cfg.head_dim}, n_res={cfg.n_res}",
                    "frame_chunk": fc, "token_chunk": tc, "lanes": args.lanes, "gflop_per_step": round(flops / 1e9, 1)},
-        "cached_step_ms": round(ms, 4), "ms_per_step_one_lane": round(ms_one, 4), "mfma_util_frac": round(tflops / peak, 4),
-        "peak_hbm_gb": round(peak_alloc / 1e9, 4), "hbm_floor_gb": round(floor / 1e9, 4),
-        "workspace_gb": round(stats.workspace_bytes / 1e9, 4),
-        "roofline": roofline, "swap": swap,
+        "cached_step_ms": round(ms, 4), "cached_step_ms_median": round(timed["median_ms"], 4),
+        "cached_step_ms_min": round(timed["min_ms"], 4),
+        "ms_per_step_one_lane": round(ms_one, 4), "mfma_util_frac": round(tflops / peak, 4),
+        "peak_hbm_gb": round(measured_peak / 1e9, 4), "peak_hbm_gb_predicted": round(
+            footprint(lcb, cfg, fc, tc, 2, 2, stats.weight_bytes) / 1e9, 4),
+        "hbm_floor_gb": round(floor / 1e9, 4), "workspace_gb": round(stats.workspace_bytes / 1e9, 4),
+        "hbm_modes": hbm_modes,
+        "roofline": roofline, "rooflines": rooflines, "swap": swap,
+        "paper_context": "end-to-end on 4x L40S, pretrained models (not comparable, context only): 1.59x on "
+                         "AnimateDiff-Lightning, 2.86x on SVD-XT; peak memory 13562 -> 5559 MB and 15346 -> 13937 MB",
     }
     if breakdown is not None:
         out["breakdown"] = breakdown
+        out["breakdown_dropped_brackets"] = dropped
     stage.close()
+    del stage, x, eps, e2
+    torch.cuda.empty_cache()
+
+    if not args.no_extra and args.workload == "animatediff":
+        out["svdxt"] = workload_record(lcb, torch, synth, "svdxt", w, args.lanes)
+        out["tiny"] = tiny_record(lcb, torch, synth, args.lanes)
+        out["stress"] = stress_record(lcb, torch, synth, w, args.lanes, stats.weight_bytes)
     if not args.no_cpu_baseline:
-        # one batch element with all its frames (the temporal block attends over them): about 10-20 s of oracle time
-        out["cpu_baseline"] = cpu_baseline(cfg, w, budget_frames=min(cfg.F, 16))
+        out["cpu_baseline"] = cpu_baseline(cfg, w)
     print(json.dumps(out))
+
+
+def _one_lane_bytes(lcb, ccfg, fc, tc):
+    """Arena bytes if the chunk scratch existed once: the plan counts it twice whenever a chunk is set, and the
+    unchunked plan (one scratch of the whole axis) bounds what one lane's scratch of a chunk can be."""
+    full = lcb.lc_workspace_bytes(ccfg, fc, tc)
+    # scratch of one lane = difference between the plans of chunk c and of chunk 2c, when both are chunked
+    N = ccfg.B * ccfg.F
+    if fc and 2 * fc < N and tc == 0:
+        per_lane = (lcb.lc_workspace_bytes(ccfg, 2 * fc, 0) - full) // 2
+        return full - per_lane
+    return full
+
+
+def workload_record(lcb, torch, synth, name, w, lanes, steps=12, warmup=3):
+    """Cached step of another workload in the same run: ms (median of per-step events), TFLOP/s, per-kernel, peak."""
+    cfg = synth.CONFIGS[name]
+    fc, tc = cfg.frame_chunk, cfg.token_chunk
+    torch.cuda.empty_cache()
+    torch.cuda.reset_peak_memory_stats()
+    stage = make_stage(lcb, synth, cfg, w, fc, tc, 1, 2, lanes)
+    try:
+        x = stage.to_device(synth.make_latents(cfg, 1))
+        eps = stage.empty(*x.shape)
+        stage.cache_write(0, stage.to_device(synth.make_deep(cfg, 2)))
+
+        def step(i):
+            stage.cached_step(x, eps, 0)
+        for i in range(warmup):
+            step(i)
+        stage.sync()
+        timed = Timer(torch, stage).run(steps, step)
+        fams, _ = profile_families(lcb, stage, step, 3)
+        st = lcb.lc_get_stats(stage.ctx)
+        measured = device_bytes_in_use(torch, st)
+        peak = PEAK_TFLOPS[cfg.dtype]
+        flops = cfg.cached_step_flops()
+        ms = timed["median_ms"]
+        return {"workload": f"{cfg.name}: B={cfg.B} F={cfg.F} latent {cfg.C_lat}x{cfg.H}x{cfg.W}, C={cfg.C}, "
+                            f"{cfg.heads} heads x {cfg.head_dim}", "frame_chunk": fc, "token_chunk": tc, "steps": steps,
+                "cached_step_ms_median": round(ms, 4), "cached_step_ms_wall_mean": round(timed["wall_ms_per_step"], 4),
+                "gflop_per_step": round(flops / 1e9, 1), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                "mfma_util_frac": round(flops / (ms * 1e-3) / 1e12 / peak, 4),
+                "peak_hbm_gb": round(measured / 1e9, 4),
+                "peak_hbm_gb_predicted": round(footprint(lcb, cfg, fc, tc, 2, 1, st.weight_bytes) / 1e9, 4),
+                "breakdown_one_lane": breakdown_record(cfg, fams, peak)}
+    finally:
+        stage.close()
+        torch.cuda.empty_cache()
+
+
+def tiny_record(lcb, torch, synth, lanes):
+    """The small fp32 stage: latency of a normal and a cache step (launch-bound), and the 25-step schedule
+    (normal step when t % 3 == 0, swap-out after it, prefetch one step ahead) for frame chunk 16, 8, 4, 2. The stage
+    has 8 frames: 16 and 8 both clamp to unchunked."""
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.make_weights(cfg, 0)
+    stage = make_stage(lcb, synth, cfg, w, cfg.frame_chunk, cfg.token_chunk, 2, 2, lanes)
+    try:
+        x = stage.to_device(synth.make_latents(cfg, 1))
+        eps = stage.empty(*x.shape)
+        for _ in range(5):
+            stage.full_step(x, eps, 0)
+            stage.cached_step(x, eps, 0)
+        tm = Timer(torch, stage)
+        full = tm.run(50, lambda i: stage.full_step(x, eps, 0))
+        cached = tm.run(50, lambda i: stage.cached_step(x, eps, 0))
+        flops = cfg.cached_step_flops()
+        rec = {"note_schedule": "the tiny steps are bound by the host's launch rate (about 100 launches of a few "
+                                "microseconds of device work each), so what a swap costs here is its seven runtime "
+                                "calls on the host, not the link: overlap_frac at this size measures that",
+               "workload": f"tiny fp32: B={cfg.B} F={cfg.F} latent {cfg.C_lat}x{cfg.H}x{cfg.W}, C={cfg.C}, frame chunk "
+                           f"{cfg.frame_chunk}", "normal_step_ms_median": round(full["median_ms"], 4),
+               "cached_step_ms_median": round(cached["median_ms"], 4), "gflop_per_cached_step": round(flops / 1e9, 2),
+               "tflops": round(flops / (cached["median_ms"] * 1e-3) / 1e12, 2)}
+    finally:
+        stage.close()
+    rec["schedule_25_steps_interval_3"] = [
+        schedule_record(lcb, torch, synth, cfg, w, c, 0, 25, 3, 2, 5, lanes) for c in (16, 8, 4, 2)]
+    rec["note"] = "8 frames: frame chunk 16 and 8 clamp to unchunked (same plan, same launches)"
+    return rec
+
+
+def stress_record(lcb, torch, synth, w, lanes, wbytes):
+    """50 steps, a normal step every 5th, a bank of 10 pinned host entries, two device buffers. The frame chunk is
+    the largest one that still gives both lanes a chunk and whose predicted footprint stays under 64 GB."""
+    cfg = synth.CONFIGS["stress"]
+    budget = 64e9  # (wbytes: the packed weights of the headline stage; the stress stage has the same widths)
+    cands = [c for c in (cfg.N // 2, 16, 8, 4, 2, 1) if c <= cfg.N // 2]
+    chosen = next((c for c in cands if footprint(lcb, cfg, c, 0, 2, 10, wbytes) < budget), 1)
+    rec = schedule_record(lcb, torch, synth, cfg, w, chosen, 0, 50, 5, 10, 1, lanes)
+    rec["workload"] = f"stress: B={cfg.B} F={cfg.F} latent {cfg.C_lat}x{cfg.H}x{cfg.W}, C={cfg.C}"
+    rec["chunk_candidates_predicted_gb"] = {str(c): round(footprint(lcb, cfg, c, 0, 2, 10, wbytes) / 1e9, 3)
+                                            for c in [cfg.N] + cands}
+    rec["budget_gb"] = 64.0
+    rec["bank_on_device_would_be_gb"] = round(10 * lcb.lc_cache_entry_bytes(lcb.make_config(cfg)) / 1e9, 3)
+    rec["gflop_per_cached_step"] = round(cfg.cached_step_flops() / 1e9, 1)
+    rec["tflops"] = round(cfg.cached_step_flops() / (rec["cached_step_ms"] * 1e-3) / 1e12, 1)
+    rec["note"] = ("no score matrix, concatenated or normalised copy is ever materialised, so every chunk meets the "
+                   "64 GB bound; it would only bite an implementation that materialises the fp32 scores "
+                   "(2.7 GB per frame)")
+    return rec
 
 
 if __name__ == "__main__":
