@@ -254,3 +254,62 @@ def test_invariants_whole_stage(cfg, chunks):
             assert stage.dev_entry_bytes(1) == deep_ref, (fc, tc)
     finally:
         stage.close()
+
+
+# ------------------------------------------------------------------------------------------
+# the stress schedule: 50 steps, a normal step every 5th, a bank of 10 host entries, two device buffers
+# ------------------------------------------------------------------------------------------
+def test_stress_schedule_bank_of_ten():
+    """The whole 50-step schedule at the stress shape (batch 2 x 32 frames of 96 x 96), free-running (x <- x - eps/50
+    on the device between steps). With swapping - each refresh swapped out to its own host entry, every cache step
+    reading a device buffer refilled one step ahead - every eps must equal, bit for bit, the eps of the same
+    schedule with the deep feature left resident in one device slot; each of the 10 host entries must hold the
+    bytes its normal step produced. (Values against the oracle at this shape: test_step_one_chunk_full_image.)"""
+    cfg = STRESS
+    steps, interval, bank = 50, 5, 10
+    stage, w = make_stage(cfg, seed=0, host_slots=bank, dev_slots=2)
+    try:
+        x0 = dev(stage, synth.make_latents(cfg, 1))
+
+        def run(swapping):
+            x = x0.clone()
+            outs, entries = [], []
+            eps = stage.empty(*x.shape)
+            refresh, prefetched = -1, None
+            for t in range(steps):
+                slot = t % 2 if swapping else 0
+                if t % interval == 0:
+                    refresh += 1
+                    stage.full_step(x, eps, slot)
+                    if swapping:
+                        stage.swap_out(slot, refresh)
+                    else:
+                        entries.append(stage.dev_entry_bytes(slot))
+                else:
+                    if swapping and prefetched != (t, slot):
+                        stage.swap_in(refresh, slot)
+                    stage.cached_step(x, eps, slot)
+                nxt = t + 1
+                if swapping and nxt < steps and nxt % interval != 0:
+                    stage.swap_in(refresh, nxt % 2)
+                    prefetched = (nxt, nxt % 2)
+                outs.append(eps.clone())
+                x = (x.float() - eps.float() / steps).to(x.dtype)  # (torch, on the compute stream)
+            stage.sync()
+            return outs, entries
+
+        print("[schedule] resident", flush=True)
+        ref, entries = run(False)
+        print("[schedule] swapping, bank of 10", flush=True)
+        got, _ = run(True)
+        for t in range(steps):
+            assert torch.equal(got[t], ref[t]), t
+        assert bool(torch.isfinite(ref[-1].float()).all())
+        for k in range(bank):
+            assert stage.host_entry_bytes(k) == entries[k], k
+        assert len({e[:4096] for e in entries}) == bank  # ten different features, not one written ten times
+        st = lcb.lc_get_stats(stage.ctx)
+        assert (st.full_steps, st.cached_steps, st.swaps_out, st.swaps_in) == (20, 80, 10, 40)
+        assert st.host_bank_bytes == bank * lcb.lc_cache_entry_bytes(stage.ccfg)
+    finally:
+        stage.close()
