@@ -120,6 +120,9 @@ size_t lc_cache_entry_bytes(const lc_config* cfg);
  * Returns 0 if cfg is invalid or a chunk is negative. */
 size_t lc_workspace_bytes(const lc_config* cfg, int frame_chunk, int token_chunk);
 
+/* The same with a spatial chunk (lc_set_spatial_chunk) of eta x omega blocks. 0 if the factors do not divide H, W. */
+size_t lc_workspace_bytes_spatial(const lc_config* cfg, int frame_chunk, int token_chunk, int eta, int omega);
+
 /* Message of the most recent error on this ctx (ctx == NULL: of the calling thread's last
  * ctx-less call). Never NULL; valid until the next call on the same ctx / thread. */
 const char* lc_last_error(const lc_ctx* ctx);
@@ -158,6 +161,20 @@ lc_status lc_set_workspace(lc_ctx* ctx, void* arena, size_t bytes);
  * (as many rows as a frame chunk). Chunking never changes results (each output is reduced in the
  * same order). LC_ERR_NOMEM if a workspace is set and is too small for the new setting. */
 lc_status lc_set_chunk(lc_ctx* ctx, int frame_chunk, int token_chunk);
+
+/* Spatial feature chunk ([CHK], eq. Chunk(F): F_i of size H/eta x W/omega). Every operator of the shallow branch
+ * then runs block by block over the eta x omega spatial blocks of each frame (inside the frame chunks above): the
+ * 3x3 convolutions and conv_in / conv_out compute a block's pixels with the one-pixel halo read from the
+ * neighbouring blocks of their input; GroupNorm statistics are split sums per block, folded once all blocks of the
+ * producing operator are done (two passes); the projections take a block's positions; spatial attention takes a
+ * block's queries against the keys and values of the whole frame; temporal attention takes a block's positions
+ * (the blocks replace token_chunk). Results are identical bit for bit to the unchunked step: a block is made of
+ * whole tiles of every kernel, which is what restricts the factors: eta must divide H with H/eta a multiple of 8,
+ * omega must divide W with W/omega a multiple of 32, eta * omega <= 64, C in {64, 128} or 320 with bf16, C_lat <= 7;
+ * otherwise LC_ERR_SHAPE. (1, 1) = off, the default. LC_ERR_ARG for factors below 1; LC_ERR_NOMEM if a workspace
+ * is set and is too small (the temporal pass then works on N * H/eta * W/omega rows: lc_workspace_bytes_spatial).
+ * The deep stand-in of the normal step is not chunked spatially. */
+lc_status lc_set_spatial_chunk(lc_ctx* ctx, int eta, int omega);
 
 /* Chunk overlap. The chunks of a step ([CHK]) depend on each other only where the method joins
  * them (before temporal attention, before the up branch, at the end), so a chunked step issues

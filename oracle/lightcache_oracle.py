@@ -28,6 +28,14 @@ What is computed (citations are to the paper's sections / equations):
   independent over (frames for per-frame operators, spatial positions for temporal
   attention, query tokens for spatial attention), so chunking is exact; the chunked
   variants below really loop over slices.
+* The same equation taken literally, F_i of size H/eta x W/omega (``set_spatial_chunk``):
+  every operator of the shallow branch loops over the eta x omega spatial blocks of a
+  frame. A 3x3 convolution computes a block from the block plus a one-pixel halo taken
+  from the neighbouring blocks (zeros beyond the image); GroupNorm is two passes over the
+  blocks (split sums of x and x^2 first, then the normalisation block by block); spatial
+  attention takes a block's tokens as queries against all tokens of the frame; temporal
+  attention takes a block's positions. The results are those of the unchunked operators
+  up to the rounding of the split sums.
 
 The operators inside the shallow blocks (the paper does not spell them out; these are
 the standard definitions):
@@ -77,6 +85,52 @@ def conv3x3(x: np.ndarray, w: np.ndarray, b: np.ndarray, stride: int = 1) -> np.
             patch = np.ascontiguousarray(patch).reshape(N, Cin, Ho * Wo)
             w_tap = np.ascontiguousarray(w[:, :, a, e])  # [Cout, Cin]
             y += np.matmul(w_tap[None], patch).reshape(N, Cout, Ho, Wo)
+    return y
+
+
+def conv3x3_block(x: np.ndarray, w: np.ndarray, b: np.ndarray, y0: int, y1: int, x0: int, x1: int) -> np.ndarray:
+    """Rows [y0, y1) x columns [x0, x1) of conv3x3(x, w, b) (stride 1), computed from that block of x and its
+    one-pixel halo only: the halo comes from the neighbouring blocks of x, zeros where it leaves the image."""
+    N, Cin, H, W = x.shape
+    Cout = w.shape[0]
+    bh, bw = y1 - y0, x1 - x0
+    assert 0 <= y0 < y1 <= H and 0 <= x0 < x1 <= W
+    patch = np.zeros((N, Cin, bh + 2, bw + 2), dtype=x.dtype)   # patch[i, j] = x[y0 - 1 + i, x0 - 1 + j]
+    ys0, ys1 = max(y0 - 1, 0), min(y1 + 1, H)
+    xs0, xs1 = max(x0 - 1, 0), min(x1 + 1, W)
+    patch[:, :, ys0 - (y0 - 1):ys1 - (y0 - 1), xs0 - (x0 - 1):xs1 - (x0 - 1)] = x[:, :, ys0:ys1, xs0:xs1]
+    y = np.empty((N, Cout, bh, bw), dtype=x.dtype)
+    y[...] = b[None, :, None, None]
+    for a in range(3):
+        for e in range(3):
+            tap = np.ascontiguousarray(patch[:, :, a:a + bh, e:e + bw]).reshape(N, Cin, bh * bw)
+            y += np.matmul(np.ascontiguousarray(w[:, :, a, e])[None], tap).reshape(N, Cout, bh, bw)
+    return y
+
+
+def group_norm_blocks(x: np.ndarray, gamma: np.ndarray, beta: np.ndarray, groups: int, eps: float, blocks) -> np.ndarray:
+    """GroupNorm in two passes over spatial blocks [(y0, y1, x0, x1), ...] that tile the image: pass 1 adds up, per
+    frame and group, the count, the sum and the sum of squares block by block (mean = S1 / n, biased variance =
+    S2 / n - mean^2); pass 2 normalises each block with those statistics."""
+    N, C, H, W = x.shape
+    cg = C // groups
+    assert C % groups == 0
+    n = 0
+    s1 = np.zeros((N, groups), dtype=x.dtype)
+    s2 = np.zeros((N, groups), dtype=x.dtype)
+    for (y0, y1, x0, x1) in blocks:
+        blk = x[:, :, y0:y1, x0:x1].reshape(N, groups, -1)
+        n += blk.shape[2]
+        s1 += blk.sum(axis=2)
+        s2 += (blk * blk).sum(axis=2)
+    assert n == cg * H * W, "the blocks must tile the image"
+    mu = s1 / n
+    rstd = 1.0 / np.sqrt(s2 / n - mu * mu + x.dtype.type(eps))
+    mu_c, rstd_c = np.repeat(mu, cg, axis=1), np.repeat(rstd, cg, axis=1)  # per channel
+    y = np.empty_like(x)
+    for (y0, y1, x0, x1) in blocks:
+        blk = (x[:, :, y0:y1, x0:x1] - mu_c[:, :, None, None]) * rstd_c[:, :, None, None]
+        y[:, :, y0:y1, x0:x1] = blk * gamma[None, :, None, None] + beta[None, :, None, None]
     return y
 
 
@@ -172,6 +226,8 @@ class Oracle:
         self.w = {k: np.asarray(v, dtype=self.dtype) for k, v in weights.items()}
         self.frame_chunk = 0
         self.token_chunk = 0
+        self.eta = 1    # spatial chunk: eta x omega blocks per frame (1, 1 = off)
+        self.omega = 1
         self.progress = None  # optional callable(str): told after every chunk of a step (long runs report where they are)
         self.dev: List[Optional[np.ndarray]] = [None] * dev_slots
         self.host: List[Optional[np.ndarray]] = [None] * host_slots
@@ -189,6 +245,31 @@ class Oracle:
             raise ValueError("chunk sizes must be >= 0")
         self.frame_chunk, self.token_chunk = frame_chunk, token_chunk
 
+    def set_spatial_chunk(self, eta: int, omega: int) -> None:
+        """Literal spatial feature chunk: every frame is processed in eta x omega blocks of H/eta x W/omega."""
+        c = self.cfg
+        if eta < 1 or omega < 1 or c.H % eta or c.W % omega or (c.H // eta) % 2 or (c.W // omega) % 2:
+            raise ValueError("eta must divide H and omega must divide W into blocks of even size")
+        self.eta, self.omega = eta, omega
+
+    def _spatial(self) -> bool:
+        return self.eta * self.omega > 1
+
+    def _blocks(self, H: int, W: int):
+        """(y0, y1, x0, x1) of the spatial blocks of an H x W map, row-major."""
+        bh, bw = H // self.eta, W // self.omega
+        return [(i * bh, (i + 1) * bh, j * bw, (j + 1) * bw) for i in range(self.eta) for j in range(self.omega)]
+
+    def _conv(self, x, w, b):
+        """conv3x3, block by block (each from its block and halo) under a spatial chunk."""
+        if not self._spatial():
+            return conv3x3(x, w, b)
+        N, _, H, W = x.shape
+        y = np.empty((N, w.shape[0], H, W), dtype=self.dtype)
+        for (y0, y1, x0, x1) in self._blocks(H, W):
+            y[:, :, y0:y1, x0:x1] = conv3x3_block(x, w, b, y0, y1, x0, x1)
+        return y
+
     def _token_chunk(self) -> int:
         c = self.cfg
         if self.token_chunk > 0:
@@ -204,11 +285,17 @@ class Oracle:
 
     # ---- blocks ---------------------------------------------------------------------
     def _gn(self, x, prefix):
-        return group_norm(x, self.w[prefix + ".gn_g"], self.w[prefix + ".gn_b"], self.cfg.groups, self.cfg.gn_eps)
+        g, b = self.w[prefix + ".gn_g"], self.w[prefix + ".gn_b"]
+        if self._spatial() and x.shape[2:] == (self.cfg.H, self.cfg.W):
+            return group_norm_blocks(x, g, b, self.cfg.groups, self.cfg.gn_eps, self._blocks(*x.shape[2:]))
+        return group_norm(x, g, b, self.cfg.groups, self.cfg.gn_eps)
 
     def res_block(self, h, prefix):
-        """h + conv3x3(SiLU(GN(h)))."""
-        return h + conv3x3(silu(self._gn(h, prefix)), self.w[prefix + ".w"], self.w[prefix + ".b"])
+        """h + conv3x3(SiLU(GN(h))). (The residual block of the deep stand-in, at half resolution, is never
+        chunked spatially.)"""
+        if h.shape[2:] != (self.cfg.H, self.cfg.W):
+            return h + conv3x3(silu(self._gn(h, prefix)), self.w[prefix + ".w"], self.w[prefix + ".b"])
+        return h + self._conv(silu(self._gn(h, prefix)), self.w[prefix + ".w"], self.w[prefix + ".b"])
 
     def _attn_w(self, prefix):
         w = self.w
@@ -221,6 +308,13 @@ class Oracle:
         out = h.copy()
         for n in range(N):
             X = g[n].reshape(C, H * W).T  # [T, C]
+            if self._spatial():
+                # queries = the tokens of one spatial block, keys and values = all tokens of the frame
+                for (y0, y1, x0, x1) in self._blocks(H, W):
+                    tok = (np.arange(y0, y1)[:, None] * W + np.arange(x0, x1)[None, :]).ravel()
+                    Y = attention(X[tok], X, *self._attn_w("sattn"), self.cfg.heads)
+                    out[n].reshape(C, H * W)[:, tok] += Y.T
+                continue
             for t0, t1 in _chunks(H * W, self._token_chunk()):
                 Y = attention(X[t0:t1], X, *self._attn_w("sattn"), self.cfg.heads)  # [tq, C]
                 out[n].reshape(C, H * W)[:, t0:t1] += Y.T
@@ -234,10 +328,15 @@ class Oracle:
         B, F = c.B, N // c.B
         g = self._gn(h, "tattn").reshape(B, F, C, H * W)
         out = h.copy().reshape(B, F, C, H * W)
-        for p0, p1 in _chunks(H * W, self._token_chunk()):
-            X = np.transpose(g[:, :, :, p0:p1], (0, 3, 1, 2))  # [B, positions, F, C]
+        if self._spatial():
+            pos_sets = [(np.arange(y0, y1)[:, None] * W + np.arange(x0, x1)[None, :]).ravel()
+                        for (y0, y1, x0, x1) in self._blocks(H, W)]  # the positions of one spatial block at a time
+        else:
+            pos_sets = [np.arange(p0, p1) for p0, p1 in _chunks(H * W, self._token_chunk())]
+        for pos in pos_sets:
+            X = np.transpose(g[:, :, :, pos], (0, 3, 1, 2))  # [B, positions, F, C]
             Y = attention(X, X, *self._attn_w("tattn"), c.heads)  # [B, positions, F, C]
-            out[:, :, :, p0:p1] += np.transpose(Y, (0, 2, 3, 1))
+            out[:, :, :, pos] += np.transpose(Y, (0, 2, 3, 1))
         return out.reshape(N, C, H, W)
 
     def shallow_down(self, x):
@@ -246,7 +345,7 @@ class Oracle:
         N = x.shape[0]
         h = np.empty((N, c.C, c.H, c.W), dtype=self.dtype)
         for n0, n1 in _chunks(N, self.frame_chunk):
-            t = conv3x3(x[n0:n1], self.w["conv_in.w"], self.w["conv_in.b"])
+            t = self._conv(x[n0:n1], self.w["conv_in.w"], self.w["conv_in.b"])
             for i in range(c.n_res):
                 t = self.res_block(t, f"res{i}")
             h[n0:n1] = self.spatial_block(t)
@@ -271,9 +370,17 @@ class Oracle:
         N = s.shape[0]
         eps = np.empty((N, c.C_lat, c.H, c.W), dtype=self.dtype)
         for n0, n1 in _chunks(N, self.frame_chunk):
-            cat = np.concatenate([s[n0:n1], up2(deep[n0:n1])], axis=1)
-            u = conv3x3(silu(self._gn(cat, "up")), self.w["up.w"], self.w["up.b"])
-            eps[n0:n1] = conv3x3(silu(self._gn(u, "out")), self.w["out.w"], self.w["out.b"])
+            if self._spatial():
+                # the concatenated map block by block: a block of the skip feature with the 2x upsampled block of
+                # the deep feature that lies under it
+                cat = np.empty((n1 - n0, c.C + c.C_deep, c.H, c.W), dtype=self.dtype)
+                for (y0, y1, x0, x1) in self._blocks(c.H, c.W):
+                    cat[:, :, y0:y1, x0:x1] = np.concatenate(
+                        [s[n0:n1, :, y0:y1, x0:x1], up2(deep[n0:n1, :, y0 // 2:y1 // 2, x0 // 2:x1 // 2])], axis=1)
+            else:
+                cat = np.concatenate([s[n0:n1], up2(deep[n0:n1])], axis=1)
+            u = self._conv(silu(self._gn(cat, "up")), self.w["up.w"], self.w["up.b"])
+            eps[n0:n1] = self._conv(silu(self._gn(u, "out")), self.w["out.w"], self.w["out.b"])
             self._tick(f"shallow up: frames {n0}..{n1 - 1} of {N}")
         return eps
 

@@ -78,6 +78,8 @@ PROTOTYPES = {
     "lc_load_weights": (_I, [_P, C.POINTER(lc_weights)]),
     "lc_set_workspace": (_I, [_P, _P, C.c_size_t]),
     "lc_set_chunk": (_I, [_P, _I, _I]),
+    "lc_set_spatial_chunk": (_I, [_P, _I, _I]),
+    "lc_workspace_bytes_spatial": (C.c_size_t, [C.POINTER(lc_config), _I, _I, _I, _I]),
     "lc_set_lanes": (_I, [_P, _I]),
     "lc_set_conv_general": (_I, [_P, _I]),
     "lc_full_step": (_I, [_P, _P, _P, _I]),
@@ -177,6 +179,14 @@ def lc_set_workspace(ctx, arena_ptr: int, nbytes: int) -> None:
 
 def lc_set_chunk(ctx, frame_chunk: int, token_chunk: int) -> None:
     _check(lib().lc_set_chunk(ctx, frame_chunk, token_chunk), ctx)
+
+
+def lc_set_spatial_chunk(ctx, eta: int, omega: int) -> None:
+    _check(lib().lc_set_spatial_chunk(ctx, eta, omega), ctx)
+
+
+def lc_workspace_bytes_spatial(cfg: lc_config, frame_chunk: int, token_chunk: int, eta: int, omega: int) -> int:
+    return lib().lc_workspace_bytes_spatial(C.byref(cfg), frame_chunk, token_chunk, eta, omega)
 
 
 def lc_set_lanes(ctx, lanes: int) -> None:
@@ -334,6 +344,7 @@ class Stage:
         self._wt = None  # the library keeps packed private copies
         lc_set_chunk(self.ctx, fc, tc)
         self.arena = None
+        self._fc, self._tc, self._eta, self._omega = fc, tc, 1, 1
         self._ensure_arena(fc, tc)
 
     # -- memory helpers
@@ -350,8 +361,10 @@ class Stage:
         with self.torch.cuda.stream(self.compute):
             return self.torch.empty(*shape, dtype=self.tdtype, device=self.device)
 
-    def _ensure_arena(self, fc, tc):
-        need = lc_workspace_bytes(self.ccfg, fc, tc)
+    def _ensure_arena(self, fc, tc, eta=None, omega=None):
+        eta = self._eta if eta is None else eta
+        omega = self._omega if omega is None else omega
+        need = lc_workspace_bytes_spatial(self.ccfg, fc, tc, eta, omega) or lc_workspace_bytes(self.ccfg, fc, tc)
         if self.arena is None or self.arena.numel() < need:
             lc_sync(self.ctx)
             self.arena = self.torch.empty(need, dtype=self.torch.uint8, device=self.device)
@@ -376,6 +389,12 @@ class Stage:
     def set_chunk(self, frame_chunk: int, token_chunk: int) -> None:
         self._ensure_arena(frame_chunk, token_chunk)
         lc_set_chunk(self.ctx, frame_chunk, token_chunk)
+        self._fc, self._tc = frame_chunk, token_chunk
+
+    def set_spatial_chunk(self, eta: int, omega: int) -> None:
+        self._ensure_arena(self._fc, self._tc, eta, omega)
+        lc_set_spatial_chunk(self.ctx, eta, omega)
+        self._eta, self._omega = eta, omega
 
     def set_lanes(self, lanes: int) -> None:
         lc_set_lanes(self.ctx, lanes)

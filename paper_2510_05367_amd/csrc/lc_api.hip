@@ -42,6 +42,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
   int fc, tc, qc;  // effective frame chunk, temporal position chunk, spatial query chunk
+  int blocks;      // spatial blocks per frame (1: no spatial chunk)
   size_t off_h, off_slots, slot_bytes, off_partH, off_partT, off_partU, off_partD, partD_bytes, off_scale, off_shift, off_scale_cat,
       off_shift_cat, off_ws,
       ws_bytes, total;
@@ -77,6 +78,7 @@ struct lc_ctx {
   bool forked;
   int device;
   int frame_chunk, token_chunk;
+  int sp_eta, sp_omega;          // spatial chunk factors of lc_set_spatial_chunk (1, 1 = off)
   Plan plan;
   char* arena;
   size_t arena_bytes;
@@ -161,7 +163,7 @@ lc_status check_cfg(lc_ctx* c, const lc_config* g) {
   return LC_OK;
 }
 
-Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
+Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk, int eta, int omega) {
   Plan p;
   const int64_t N = (int64_t)g.B * g.F, T = (int64_t)g.H * g.W;
   const size_t es = dtype_size(g.dtype);
@@ -173,6 +175,9 @@ Plan make_plan(const lc_config& g, int frame_chunk, int token_chunk) {
   // weight-stationary linear kernel works on such tiles)
   if (T % 32 == 0) p.tc = (int)std::min<int64_t>(T, ((int64_t)p.tc + 31) / 32 * 32);
   p.qc = token_chunk > 0 ? (int)std::min<int64_t>(token_chunk, T) : (int)T;
+  // with a spatial chunk the position chunks of the temporal block and the query chunks are its blocks
+  if (eta * omega > 1) p.tc = p.qc = (g.H / eta) * (g.W / omega);
+  p.blocks = eta * omega;
   size_t off = 0;
   p.off_h = off; off += align_up((size_t)(N * T * g.C) * 4);  // the skip / residual stream is fp32
   p.slot_bytes = align_up((size_t)(N * (T / 4) * g.C_deep) * es);
@@ -256,6 +261,29 @@ inline float* shift_p(lc_ctx* c) { return (float*)(c->arena + lane_base(c) + c->
 inline char* ws_ptr(lc_ctx* c) { return c->arena + lane_base(c) + c->plan.off_ws; }
 
 RowMap dense_map() { return RowMap{0, 0, 1 << 30}; }
+
+// The spatial blocks of a frame of H x W pixels under the current spatial chunk ("Feature chunk" section, eq.
+// Chunk(F): H/eta x W/omega), in row-major order; one entry {0,0,0,0} = the whole frame when no chunk is set.
+// `half`: blocks of the half-resolution grid (H, W are then already halved).
+struct Blocks {
+  int n;
+  Win w[64];
+};
+Blocks blocks_of(const lc_ctx* c, int H, int W) {
+  Blocks b;
+  if (c->sp_eta * c->sp_omega <= 1) { b.n = 1; b.w[0] = Win{0, 0, 0, 0}; return b; }
+  const int bh = H / c->sp_eta, bw = W / c->sp_omega;
+  b.n = 0;
+  for (int i = 0; i < c->sp_eta; ++i)
+    for (int j = 0; j < c->sp_omega; ++j) b.w[b.n++] = Win{j * bw, i * bh, bw, bh};
+  return b;
+}
+inline void set_conv_win(FusedDesc& d, Win w) { d.win_x0 = w.x0; d.win_y0 = w.y0; d.win_w = w.w; d.win_h = w.h; }
+// token-indexed launch (taps == 1) over the rows of whole frames of H x W pixels
+inline void set_row_win(FusedDesc& d, Win w, int H, int W, int in, int out) {
+  set_conv_win(d, w);
+  d.win_img_w = W; d.win_img_t = H; d.win_in = in; d.win_out = out;
+}
 
 // Two lanes. The chunks of a step depend on each other only at three points (before the temporal
 // block, before the up branch, at the end), and nearly every kernel wants the whole device for a short
@@ -370,7 +398,16 @@ FusedDesc flinear_desc(lc_ctx* c, const void* w, const void* w_frag, const float
 // h = conv3x3(x): x planar [frames][C_lat][H][W] of the operand type, h fp32 rows. With `stat` the
 // partial sums of h are written too ([frame][T/32][C][2]; T must be a multiple of 32); *wrote tells
 // whether the kernel that ran could do that.
+lc_status conv_in_block(lc_ctx* c, const void* x, void* h, int frames, float* stat, bool* wrote_stats, Win win);
 lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat, bool* wrote_stats) {
+  const Blocks bl = blocks_of(c, c->cfg.H, c->cfg.W);
+  for (int i = 0; i < bl.n; ++i) {  // (every block runs the same kernel: *wrote_stats is that of any of them)
+    const lc_status s = conv_in_block(c, x, h, frames, stat, wrote_stats, bl.w[i]);
+    if (s != LC_OK) return s;
+  }
+  return LC_OK;
+}
+lc_status conv_in_block(lc_ctx* c, const void* x, void* h, int frames, float* stat, bool* wrote_stats, Win win) {
   const lc_config& g = c->cfg;
   const int T = g.H * g.W;
   if (wrote_stats) *wrote_stats = false;
@@ -378,7 +415,7 @@ lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat
     hipError_t e;
     {
       Prof pr_(c, LC_K_CONV_IN);
-      e = launch_conv_in_tile(c->cs, g.dtype, x, c->pw.cin_wp, c->pw.cin_b, (float*)h, stat, frames, g.H, g.W, g.C_lat, g.C);
+      e = launch_conv_in_tile(c->cs, g.dtype, x, c->pw.cin_wp, c->pw.cin_b, (float*)h, stat, frames, g.H, g.W, g.C_lat, g.C, win);
       if (e == hipErrorNotSupported) pr_.cancel();
     }
     if (e == hipSuccess) {
@@ -394,6 +431,7 @@ lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat
     d.w_frag = c->pw.cin_wf; d.bias = c->pw.cin_b; d.frames = frames; d.H = g.H; d.W = g.W;
     d.rows = (int64_t)frames * T; d.in_map = dense_map(); d.out_map = dense_map(); d.x = x; d.y = h;
     if (stat && T % 32 == 0) { d.stat = stat; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
+    if (win.w) set_row_win(d, win, g.H, g.W, 1, 1);
     hipError_t e;
     {
       Prof pr_(c, LC_K_CONV_IN);
@@ -406,6 +444,7 @@ lc_status conv_in_run(lc_ctx* c, const void* x, void* h, int frames, float* stat
     }
     if (e != hipErrorNotSupported) return fail(c, LC_ERR_HIP, "conv_in: %s", hipGetErrorString(e));
   }
+  if (win.w) return fail(c, LC_ERR_SHAPE, "conv_in of this stage has no spatially chunked kernel");
   LC_LAUNCH(c, LC_K_CONV_IN, launch_conv_in(c->cs, g.dtype, x, h, frames, g.H, g.W, g.C_lat, g.C, c->pw.cin_w, c->pw.cin_b));
   return LC_OK;
 }
@@ -424,7 +463,12 @@ lc_status res_block(lc_ctx* c, const GnW& gn, const ConvW& cw, int Cn, int frame
   } else if (out) {
     *out = StatRef{nullptr, 0};
   }
-  LC_LAUNCH(c, kind, launch_fused(c->cs, d));
+  // (the residual block at C_deep of the normal step's stand-in runs on whole frames: it is not on the cache step)
+  const Blocks bl = kind == LC_K_DEEP ? Blocks{1, {Win{0, 0, 0, 0}}} : blocks_of(c, H, W);
+  for (int i = 0; i < bl.n; ++i) {
+    set_conv_win(d, bl.w[i]);
+    LC_LAUNCH(c, kind, launch_fused(c->cs, d));
+  }
   return LC_OK;
 }
 
@@ -445,7 +489,11 @@ lc_status up_conv(lc_ctx* c, const void* skip, const void* deep, void* u, int fr
       d.stat_splits = conv_stat_splits(g.H, g.W);
       *out = StatRef{d.stat, d.stat_splits};
     }
-    LC_LAUNCH(c, LC_K_CONV_UP, launch_fused(c->cs, d));
+    const Blocks bl = blocks_of(c, g.H, g.W);
+    for (int i = 0; i < bl.n; ++i) {
+      set_conv_win(d, bl.w[i]);
+      LC_LAUNCH(c, LC_K_CONV_UP, launch_fused(c->cs, d));
+    }
     return LC_OK;
   }
   if (!skip_st.part) {
@@ -467,7 +515,11 @@ lc_status up_conv(lc_ctx* c, const void* skip, const void* deep, void* u, int fr
     d.stat_splits = conv_stat_splits(g.H, g.W);
     *out = StatRef{d.stat, d.stat_splits};
   }
-  LC_LAUNCH(c, LC_K_CONV_UP, launch_fused(c->cs, d));
+  const Blocks bl = blocks_of(c, g.H, g.W);
+  for (int i = 0; i < bl.n; ++i) {
+    set_conv_win(d, bl.w[i]);
+    LC_LAUNCH(c, LC_K_CONV_UP, launch_fused(c->cs, d));
+  }
   return LC_OK;
 }
 
@@ -476,20 +528,24 @@ lc_status conv_out(lc_ctx* c, const void* u, void* eps, int frames, StatRef u_st
   const lc_config& g = c->cfg;
   lc_status s = gn_scale_shift(c, u, frames, g.H * g.W, g.C, c->pw.out_gn, u_st);
   if (s != LC_OK) return s;
-  // the tile kernel where the stage's geometry allows it (a property of the stage, not of the chunk)
-  hipError_t e;
-  {
-    Prof pr_(c, LC_K_CONV_OUT);
-    e = launch_conv_out_tile(c->cs, g.dtype, u, scale_p(c), shift_p(c), c->pw.out.w, c->pw.out.b, eps, frames, g.H, g.W, g.C,
-                             g.C_lat);
-    if (e == hipErrorNotSupported) pr_.cancel();
+  const Blocks bl = blocks_of(c, g.H, g.W);
+  for (int i = 0; i < bl.n; ++i) {
+    // the tile kernel where the stage's geometry allows it (a property of the stage, not of the chunk)
+    hipError_t e;
+    {
+      Prof pr_(c, LC_K_CONV_OUT);
+      e = launch_conv_out_tile(c->cs, g.dtype, u, scale_p(c), shift_p(c), c->pw.out.w, c->pw.out.b, eps, frames, g.H, g.W, g.C,
+                               g.C_lat, bl.w[i]);
+      if (e == hipErrorNotSupported) pr_.cancel();
+    }
+    if (e == hipSuccess) continue;
+    if (e != hipErrorNotSupported) return fail(c, LC_ERR_HIP, "conv_out: %s", hipGetErrorString(e));
+    FusedDesc d = fconv_desc(c, c->pw.out, g.C, 32, frames, g.H, g.W, u, nullptr, eps, 0);
+    d.Cout_store = g.C_lat;
+    d.planar_out = 1;
+    set_conv_win(d, bl.w[i]);
+    LC_LAUNCH(c, LC_K_CONV_OUT, launch_fused(c->cs, d));
   }
-  if (e == hipSuccess) return LC_OK;
-  if (e != hipErrorNotSupported) return fail(c, LC_ERR_HIP, "conv_out: %s", hipGetErrorString(e));
-  FusedDesc d = fconv_desc(c, c->pw.out, g.C, 32, frames, g.H, g.W, u, nullptr, eps, 0);
-  d.Cout_store = g.C_lat;
-  d.planar_out = 1;
-  LC_LAUNCH(c, LC_K_CONV_OUT, launch_fused(c->cs, d));
   return LC_OK;
 }
 
@@ -512,22 +568,43 @@ lc_status spatial_block(lc_ctx* c, char* hc, char* scr, int nf, StatRef st, floa
   lc_status s = gn_scale_shift(c, hc, nf, T, C, a.gn, st);
   if (s != LC_OK) return s;
   RowMap fm{0, T, T};  // dense rows; frame of row r = r / T
-  {
+  const Blocks bl = blocks_of(c, g.H, g.W);
+  // With a spatial chunk every operator below runs block by block; a block's queries attend to the keys and
+  // values of the whole frame, so the q,k,v projection of all blocks comes first.
+  for (int i = 0; i < bl.n; ++i) {
     // q and k as rows, v transposed straight from the GEMM epilogue into the layout the attention
     // kernel stages (no scattered transposition later)
     FusedDesc d = flinear_desc(c, a.wqkv, a.wqkv_f, nullptr, C, 3 * C, pc, 1, fm, dense_map(), hc, nullptr, qk, 0);
     d.yt = vt; d.yt_from = 2 * C; d.yt_T = T; d.yt_Tp = Tp;
     d.q_scale = attn_q_scale(g.head_dim); d.q_cols = C;  // the softmax scale rides on q, applied before rounding
+    if (bl.w[i].w) set_row_win(d, bl.w[i], g.H, g.W, 1, 1);
     s = linear(c, LC_K_QKV, d, nullptr, tiled);
     if (s != LC_OK) return s;
   }
-  for (int q0 = 0; q0 < T; q0 += c->plan.qc)
-    LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
-                                                      g.head_dim, q0, std::min(q0 + c->plan.qc, T), 1));
+  for (int i = 0; i < bl.n; ++i) {
+    const Win w = bl.w[i];
+    if (w.w) {
+      LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention_window(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads, g.head_dim,
+                                                               w.y0 * g.W + w.x0, w.w * w.h, w.w, g.W, 1));
+    } else {
+      for (int q0 = 0; q0 < T; q0 += c->plan.qc)
+        LC_LAUNCH(c, LC_K_SATTN, launch_spatial_attention(c->cs, g.dtype, qk, 2 * C, vt, Tp, ao, nf, T, g.heads,
+                                                          g.head_dim, q0, std::min(q0 + c->plan.qc, T), 1));
+    }
+  }
   // the output projection closes the block; its partial sums are those of the next GroupNorm's input
-  FusedDesc d = flinear_desc(c, a.wo, a.wo_f, a.bo, C, C, pc, 0, dense_map(), dense_map(), ao, hc, hc, 1);
-  if (stat_out) { d.stat = stat_out; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
-  return linear(c, LC_K_PROJ, d, wrote, tiled);
+  bool all = true;
+  for (int i = 0; i < bl.n; ++i) {
+    FusedDesc d = flinear_desc(c, a.wo, a.wo_f, a.bo, C, C, pc, 0, dense_map(), dense_map(), ao, hc, hc, 1);
+    if (stat_out) { d.stat = stat_out; d.stat_splits = T / 32; d.stat_rps = T; d.stat_off = 0; }
+    if (bl.w[i].w) set_row_win(d, bl.w[i], g.H, g.W, 1, 1);
+    bool wr = false;
+    s = linear(c, LC_K_PROJ, d, &wr, tiled);
+    if (s != LC_OK) return s;
+    all = all && wr;
+  }
+  if (wrote) *wrote = all;
+  return LC_OK;
 }
 
 // Temporal attention block over all N frames, in place on h [N*T][C] (fp32), per position chunk of plan.tc
@@ -544,24 +621,37 @@ lc_status temporal_block(lc_ctx* c, char* h, StatRef tst, bool* ustat) {
   lc_status s = gn_scale_shift(c, h, N, T, C, a.gn, tst);
   if (s != LC_OK) return s;
   const float *sc0 = scale_p(c), *sh0 = shift_p(c);  // of all frames: every position chunk reads them, on either lane
-  const int pos_lanes = loop_lanes(c, (T + p.tc - 1) / p.tc);
+  const Blocks bl = blocks_of(c, g.H, g.W);
+  const bool spatial = bl.w[0].w != 0;  // position chunks = the blocks of the spatial chunk
+  const int nchunks = spatial ? bl.n : (T + p.tc - 1) / p.tc;
+  const int pos_lanes = loop_lanes(c, nchunks);
   if (pos_lanes > 1 && (s = fork_lanes(c)) != LC_OK) return s;
-  for (int p0 = 0, ci = 0; p0 < T; p0 += p.tc, ++ci) {
+  for (int ci = 0; ci < nchunks; ++ci) {
     use_lane(c, ci % pos_lanes);
     char* ws = ws_ptr(c);
-    const int np = std::min(p.tc, T - p0);
+    const int p0 = spatial ? 0 : ci * p.tc;
+    const int np = spatial ? bl.w[ci].w * bl.w[ci].h : std::min(p.tc, T - p0);
     const int64_t rows = (int64_t)N * np;
-    RowMap m{p0, T, np};  // dense row r = (frame r / np, position p0 + r % np)
+    // dense row r of a pass = (frame r / np, the r % np-th position of the chunk)
+    RowMap m{p0, T, np};
+    RowMap whole{0, T, T};
     char* qkv = ws;
     char* ao = ws + align_up((size_t)rows * 3 * C * es);
-    FusedDesc dq = flinear_desc(c, a.wqkv, a.wqkv_f, nullptr, C, 3 * C, rows, 1, m, dense_map(), h, nullptr, qkv, 0);
+    FusedDesc dq = flinear_desc(c, a.wqkv, a.wqkv_f, nullptr, C, 3 * C, spatial ? (int64_t)N * T : rows, 1, spatial ? whole : m,
+                                dense_map(), h, nullptr, qkv, 0);
     dq.scale = sc0; dq.shift = sh0;
+    if (spatial) set_row_win(dq, bl.w[ci], g.H, g.W, 1, 0);
     s = linear(c, LC_K_QKV, dq, nullptr, tiled);
     if (s != LC_OK) return s;
     LC_LAUNCH(c, LC_K_TATTN, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, np, g.heads, g.head_dim));
     // this projection finishes the skip feature: its partial sums, for the up block, go to partU
-    FusedDesc d = flinear_desc(c, a.wo, a.wo_f, a.bo, C, C, rows, 0, dense_map(), m, ao, h, h, 1);
-    if (*ustat) { d.stat = partU(c); d.stat_splits = T / 32; d.stat_rps = np; d.stat_off = p0; }
+    FusedDesc d = flinear_desc(c, a.wo, a.wo_f, a.bo, C, C, spatial ? (int64_t)N * T : rows, 0, dense_map(), spatial ? whole : m,
+                               ao, h, h, 1);
+    if (*ustat) {
+      d.stat = partU(c); d.stat_splits = T / 32;
+      d.stat_rps = spatial ? T : np; d.stat_off = spatial ? 0 : p0;
+    }
+    if (spatial) set_row_win(d, bl.w[ci], g.H, g.W, 0, 1);
     bool wrote = false;
     s = linear(c, LC_K_PROJ, d, &wrote, tiled);
     if (s != LC_OK) return s;
@@ -741,7 +831,16 @@ size_t lc_cache_entry_bytes(const lc_config* cfg) {
 size_t lc_workspace_bytes(const lc_config* cfg, int frame_chunk, int token_chunk) {
   if (check_cfg(nullptr, cfg) != LC_OK) return 0;
   if (frame_chunk < 0 || token_chunk < 0) { g_err = "chunk sizes must be >= 0"; return 0; }
-  return make_plan(*cfg, frame_chunk, token_chunk).total;
+  return make_plan(*cfg, frame_chunk, token_chunk, 1, 1).total;
+}
+
+size_t lc_workspace_bytes_spatial(const lc_config* cfg, int frame_chunk, int token_chunk, int eta, int omega) {
+  if (check_cfg(nullptr, cfg) != LC_OK) return 0;
+  if (frame_chunk < 0 || token_chunk < 0 || eta < 1 || omega < 1 || cfg->H % eta || cfg->W % omega) {
+    g_err = "chunk sizes must be >= 0 and the spatial factors must divide H and W";
+    return 0;
+  }
+  return make_plan(*cfg, frame_chunk, token_chunk, eta, omega).total;
 }
 
 lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_stream, lc_ctx** out) {
@@ -762,7 +861,8 @@ lc_status lc_create(const lc_config* cfg, void* compute_stream, void* side_strea
   c->lanes = 2; c->lane = 0; c->forked = false; c->conv_general = false;
   c->device = dev;
   c->frame_chunk = c->token_chunk = 0;
-  c->plan = make_plan(c->cfg, 0, 0);
+  c->sp_eta = c->sp_omega = 1;
+  c->plan = make_plan(c->cfg, 0, 0, 1, 1);
   c->arena = nullptr; c->arena_bytes = 0;
   c->have_weights = false; c->wblob = nullptr; c->wblob_bytes = 0;
   memset(&c->pw, 0, sizeof c->pw);
@@ -1020,7 +1120,7 @@ lc_status lc_set_conv_general(lc_ctx* c, int general) {
 lc_status lc_set_chunk(lc_ctx* c, int frame_chunk, int token_chunk) {
   if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
   if (frame_chunk < 0 || token_chunk < 0) return fail(c, LC_ERR_ARG, "chunk sizes must be >= 0");
-  Plan np = make_plan(c->cfg, frame_chunk, token_chunk);
+  Plan np = make_plan(c->cfg, frame_chunk, token_chunk, c->sp_eta, c->sp_omega);
   if (c->arena && np.total > c->arena_bytes)
     return fail(c, LC_ERR_NOMEM, "chunk setting needs %zu bytes, workspace has %zu", np.total, c->arena_bytes);
   // the persistent regions (skip feature, cache slots) sit at chunk-independent offsets, so a
@@ -1029,6 +1129,32 @@ lc_status lc_set_chunk(lc_ctx* c, int frame_chunk, int token_chunk) {
   c->token_chunk = token_chunk;
   c->plan = np;
   std::fill(c->deep_stat_valid.begin(), c->deep_stat_valid.end(), 0);  // their region moves with the plan
+  c->st.workspace_bytes = np.total;
+  return LC_OK;
+}
+
+lc_status lc_set_spatial_chunk(lc_ctx* c, int eta, int omega) {
+  if (!c) return fail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (eta < 1 || omega < 1) return fail(c, LC_ERR_ARG, "eta and omega must be >= 1");
+  const lc_config& g = c->cfg;
+  if (eta * omega > 1) {
+    if (eta * omega > 64) return fail(c, LC_ERR_SHAPE, "at most 64 spatial blocks per frame");
+    if (g.H % eta || g.W % omega) return fail(c, LC_ERR_SHAPE, "eta must divide H and omega must divide W");
+    // a block is made of whole tiles of every kernel: 8 image rows (3x3 convolutions), 32 pixels of a row (the
+    // 32-row tiles of the projections, the row segments of conv_in)
+    if ((g.H / eta) % 8 || (g.W / omega) % 32)
+      return fail(c, LC_ERR_SHAPE, "a spatial block must be a multiple of 8 rows x 32 columns (got %d x %d)", g.H / eta, g.W / omega);
+    // the projections must have their weight-stationary kernel, conv_in its tile kernel or the gathering linear one
+    const bool lin_ok = g.C == 64 || g.C == 128 || (g.C == 320 && g.dtype == LC_BF16);
+    if (!lin_ok || g.C_lat * 9 > 64)
+      return fail(c, LC_ERR_SHAPE, "spatial chunking needs C in {64, 128} (or 320 with bf16) and C_lat <= 7");
+  }
+  Plan np = make_plan(g, c->frame_chunk, c->token_chunk, eta, omega);
+  if (c->arena && np.total > c->arena_bytes)
+    return fail(c, LC_ERR_NOMEM, "spatial chunk setting needs %zu bytes, workspace has %zu", np.total, c->arena_bytes);
+  c->sp_eta = eta; c->sp_omega = omega;
+  c->plan = np;
+  std::fill(c->deep_stat_valid.begin(), c->deep_stat_valid.end(), 0);
   c->st.workspace_bytes = np.total;
   return LC_OK;
 }

@@ -25,12 +25,15 @@ constexpr int kKeys = 64;  // keys per LDS stage
 // the permutation is an involution on the 4-key blocks (it swaps blocks 1 and 2)
 template <class T> __device__ __forceinline__ int vcol_inv(int c) { return vcol<T>(c); }
 
+// Queries: the launch takes nq of them, numbered densely; query number i is token q0 + (i / qw) * qstride + i % qw
+// (a window of rows of qw tokens out of image rows of qstride tokens; a plain range has qw >= nq).
 // PRE: the q columns already hold q * log2(e) / sqrt(d) (the q,k,v projection scales them before it
 // rounds them); `scale_log2e` is then 1.
 template <class T, int D, int NQT, bool PRE>
 __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restrict__ qk, int ldq,
                                                            const T* __restrict__ vt, int Tp, T* __restrict__ out,
-                                                           int T_tok, int C, int q0, int q1, float scale_log2e) {
+                                                           int T_tok, int C, int q0, int nq, int qw, int qstride,
+                                                           float scale_log2e) {
   typedef Mma32<T> M;
   constexpr int VEC = Vec16<T>::N;
   constexpr int DP = (D + M::K - 1) / M::K * M::K;  // contraction length of Q K^T, padded
@@ -67,7 +70,8 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
   const int ld = ldq;
   const T* __restrict__ base = qk + (int64_t)frame * T_tok * ld + head * D;
   const T* __restrict__ vbase = vt + ((int64_t)frame * C + head * D) * Tp;
-  const int qblk = q0 + qb * (4 * NQT * 32) + wid * (NQT * 32);
+  const int qblk = qb * (4 * NQT * 32) + wid * (NQT * 32);  // first query number of this wavefront
+  auto token_of = [&](int qi) { const int r = qi / qw; return q0 + r * qstride + (qi - r * qw); };
 
   // zero both buffers once: K columns beyond D and V^T rows beyond D feed padded MFMA lanes
   for (int i = tid; i < 2 * KBYTES / 4; i += 256) reinterpret_cast<uint32_t*>(&k_lds[0][0])[i] = 0u;
@@ -140,11 +144,12 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
   typename M::Frag qf[NQT][KSTEPS];
 #pragma unroll
   for (int t = 0; t < NQT; ++t) {
-    const int q = qblk + t * 32 + lq;
+    const int qi = qblk + t * 32 + lq;
+    const int q = token_of(qi);
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
       const int e = kk * M::K + hh * M::LK;
-      qf[t][kk] = (q < q1 && e < D) ? M::load(base + (int64_t)q * ld + e) : M::zero();
+      qf[t][kk] = (qi < nq && e < D) ? M::load(base + (int64_t)q * ld + e) : M::zero();
       if constexpr (FOLD) {  // slots >= D must be zero: slot D will carry the running maximum
 #pragma unroll
         for (int j = 0; j < M::LK; ++j)
@@ -301,7 +306,8 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
   // ---- normalise and store: lane holds O^T[dim = 32*mt + 8*(r/4) + 4*hh + r%4][query lq]
 #pragma unroll
   for (int t = 0; t < NQT; ++t) {
-    const int q = qblk + t * 32 + lq;
+    const int qi = qblk + t * 32 + lq;
+    const int q = token_of(qi);
     float l;
     if (ROWSUM) {  // O^T[D][q] sits in register r of the lanes of half hsel
       constexpr int rem = D % 32, hsel = (rem % 8) / 4, r = (rem / 8) * 4 + rem % 4;
@@ -310,7 +316,7 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
       l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
     }
     const float inv = 1.f / l;
-    if (q >= q1) continue;
+    if (qi >= nq) continue;
     T* orow = out + ((int64_t)frame * T_tok + q) * C + head * D;
 #pragma unroll
     for (int mt = 0; mt < DM; ++mt)
@@ -327,11 +333,11 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
 
 template <class T, int NQT, bool PRE>
 static hipError_t spatial_dispatch(hipStream_t s, const T* qk, int ldq, const T* vt, int Tp, T* out, int frames,
-                                   int T_tok, int heads, int d, int q0, int q1) {
+                                   int T_tok, int heads, int d, int q0, int nq, int qw, int qstride) {
   const int C = heads * d;
   const float sl = PRE ? 1.f : 1.4426950408889634f / sqrtf((float)d);
-  dim3 grid((q1 - q0 + 4 * NQT * 32 - 1) / (4 * NQT * 32), heads, frames);
-#define LC_GO(D) spatial_attn_kernel<T, D, NQT, PRE><<<grid, 256, 0, s>>>(qk, ldq, vt, Tp, out, T_tok, C, q0, q1, sl)
+  dim3 grid((nq + 4 * NQT * 32 - 1) / (4 * NQT * 32), heads, frames);
+#define LC_GO(D) spatial_attn_kernel<T, D, NQT, PRE><<<grid, 256, 0, s>>>(qk, ldq, vt, Tp, out, T_tok, C, q0, nq, qw, qstride, sl)
   switch (d) {
     case 8: LC_GO(8); break;
     case 16: LC_GO(16); break;
@@ -346,9 +352,21 @@ static hipError_t spatial_dispatch(hipStream_t s, const T* qk, int ldq, const T*
 
 hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
                                     int frames, int T, int heads, int d, int q0, int q1, int q_prescaled) {
-  if (frames <= 0 || q1 <= q0) return hipSuccess;
-  if (Tp % kKeys != 0 || Tp < T) return hipErrorInvalidValue;
-#define LC_ARGS(TT) s, (const TT*)qk, ldq, (const TT*)vt, Tp, (TT*)out, frames, T, heads, d, q0, q1
+  if (q1 <= q0) return hipSuccess;
+  return launch_spatial_attention_window(s, dt, qk, ldq, vt, Tp, out, frames, T, heads, d, q0, q1 - q0, q1 - q0, 0,
+                                         q_prescaled);
+}
+
+hipError_t launch_spatial_attention_window(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
+                                           int frames, int T, int heads, int d, int q0, int nq, int qw, int qstride,
+                                           int q_prescaled) {
+  if (frames <= 0 || nq <= 0) return hipSuccess;
+  if (Tp % kKeys != 0 || Tp < T || qw <= 0 || q0 < 0) return hipErrorInvalidValue;
+  {  // the last query must be a token of the frame
+    const int r = (nq - 1) / qw;
+    if ((int64_t)q0 + (int64_t)r * qstride + (nq - 1 - r * qw) >= T) return hipErrorInvalidValue;
+  }
+#define LC_ARGS(TT) s, (const TT*)qk, ldq, (const TT*)vt, Tp, (TT*)out, frames, T, heads, d, q0, nq, qw, qstride
   if (dt == kBF16)
     return q_prescaled ? spatial_dispatch<bf16_t, 2, true>(LC_ARGS(bf16_t)) : spatial_dispatch<bf16_t, 2, false>(LC_ARGS(bf16_t));
   return q_prescaled ? spatial_dispatch<float, 1, true>(LC_ARGS(float)) : spatial_dispatch<float, 1, false>(LC_ARGS(float));

@@ -287,7 +287,7 @@ template <int C, int NT>
 __global__ __launch_bounds__(NT) void conv_out_tile_kernel(const float* __restrict__ u, const float* __restrict__ scale,
                                                            const float* __restrict__ shift, const bf16_t* __restrict__ w,
                                                            const float* __restrict__ bias, bf16_t* __restrict__ out, int H,
-                                                           int W, int C_lat) {
+                                                           int W, int C_lat, int wx0, int wy0) {
   typedef Mma16<bf16_t> M;
   constexpr int XS = C * 2 + 16;                 // LDS bytes per halo pixel (padded: 16 pixels hit 64 banks)
   constexpr int HW_ = 18, HP = 6 * HW_;          // halo width, halo pixels
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(NT) void conv_out_tile_kernel(const float* __restri
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int x0 = blockIdx.x * 16, y0 = blockIdx.y * 4, frame = blockIdx.z;
+  const int x0 = wx0 + blockIdx.x * 16, y0 = wy0 + blockIdx.y * 4, frame = blockIdx.z;  // (wx0, wy0): origin of the window
 
   // ---- staging: thread = (packet column, pixel group); its halo pixels are grp, grp + GRP, ...
   const int col = tid % PPR, grp = tid / PPR;
@@ -392,12 +392,14 @@ __global__ __launch_bounds__(NT) void conv_out_tile_kernel(const float* __restri
 template <int KS, int NTM>
 __global__ __launch_bounds__(256) void conv_in_tile_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wp,
                                                            const float* __restrict__ bias, float* __restrict__ y,
-                                                           float* __restrict__ stat, int H, int W, int Cl, int C) {
+                                                           float* __restrict__ stat, int H, int W, int Cl, int C, int wx0,
+                                                           int wy0, int wsegs) {
   __shared__ bf16_t halo[8][3][40];  // [plane][row][34 used]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int segs = W / 32;
-  const int yy = blockIdx.x / segs, x0 = (blockIdx.x - yy * segs) * 32, frame = blockIdx.y;
+  // the window's rows and 32-pixel segments (wx0, wy0: its origin; wsegs: segments per row)
+  const int wr = blockIdx.x / wsegs;
+  const int yy = wy0 + wr, x0 = wx0 + (blockIdx.x - wr * wsegs) * 32, frame = blockIdx.y;
   const bf16_t* img = x + (int64_t)frame * Cl * H * W;
   for (int i = tid; i < Cl * 3 * 34; i += 256) {
     const int xx = i % 34, dy = (i / 34) % 3, cl = i / (3 * 34);
@@ -463,19 +465,27 @@ __global__ __launch_bounds__(256) void conv_in_tile_kernel(const bf16_t* __restr
 // Returns hipErrorNotSupported for shapes it does not cover. wp: the weights as rows [C][64] of the operand type,
 // k = plane * 9 + tap, zeros beyond 9 * C_lat. stat: [frame][H * W / 32][C][2] or nullptr.
 hipError_t launch_conv_in_tile(hipStream_t s, int dt, const void* x, const void* wp, const float* bias, float* y, float* stat,
-                               int frames, int H, int W, int Cl, int C) {
+                               int frames, int H, int W, int Cl, int C, Win win) {
   if (dt != kBF16 || !wp || W % 32 || C % 32 || Cl < 1 || 9 * Cl > 48 || C / 32 > 12) return hipErrorNotSupported;
   if (frames <= 0) return hipSuccess;
-  dim3 grid((unsigned)(H * (W / 32)), (unsigned)frames);
-  conv_in_tile_kernel<3, 3><<<grid, 256, 0, s>>>((const bf16_t*)x, (const bf16_t*)wp, bias, y, stat, H, W, Cl, C);
+  if (win.w == 0) win = Win{0, 0, W, H};
+  if (win.x0 < 0 || win.y0 < 0 || win.w <= 0 || win.h <= 0 || win.x0 + win.w > W || win.y0 + win.h > H || win.x0 % 32 || win.w % 32)
+    return hipErrorInvalidValue;
+  dim3 grid((unsigned)(win.h * (win.w / 32)), (unsigned)frames);
+  conv_in_tile_kernel<3, 3><<<grid, 256, 0, s>>>((const bf16_t*)x, (const bf16_t*)wp, bias, y, stat, H, W, Cl, C, win.x0, win.y0,
+                                                 win.w / 32);
   return hipGetLastError();
 }
 
 // Returns hipErrorNotSupported for shapes it does not cover (the caller then uses the general kernel).
 hipError_t launch_conv_out_tile(hipStream_t s, int dt, const void* u, const float* scale, const float* shift, const void* w,
-                                const float* bias, void* out, int frames, int H, int W, int C, int C_lat) {
+                                const float* bias, void* out, int frames, int H, int W, int C, int C_lat, Win win) {
   if (dt != kBF16 || C != 320 || W % 16 || H % 4 || C_lat < 1 || C_lat > 16) return hipErrorNotSupported;
   if (frames <= 0) return hipSuccess;
+  if (win.w == 0) win = Win{0, 0, W, H};
+  if (win.x0 < 0 || win.y0 < 0 || win.w <= 0 || win.h <= 0 || win.x0 + win.w > W || win.y0 + win.h > H || win.x0 % 16 ||
+      win.w % 16 || win.y0 % 4 || win.h % 4)
+    return hipErrorInvalidValue;
   constexpr int NT = 512;
   const int lds = (6 * 18) * (320 * 2 + 16) + (NT / 64) * 4 * 16 * 16 * 4;
   auto kern = conv_out_tile_kernel<320, NT>;
@@ -485,8 +495,8 @@ hipError_t launch_conv_out_tile(hipStream_t s, int dt, const void* u, const floa
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid((unsigned)(W / 16), (unsigned)(H / 4), (unsigned)frames);
-  kern<<<grid, NT, lds, s>>>((const float*)u, scale, shift, (const bf16_t*)w, bias, (bf16_t*)out, H, W, C_lat);
+  dim3 grid((unsigned)(win.w / 16), (unsigned)(win.h / 4), (unsigned)frames);
+  kern<<<grid, NT, lds, s>>>((const float*)u, scale, shift, (const bf16_t*)w, bias, (bf16_t*)out, H, W, C_lat, win.x0, win.y0);
   return hipGetLastError();
 }
 

@@ -47,6 +47,7 @@ struct WsArgs {
   float* y;             // fp32 [frames][H][W][Cout]
   int Cin, Cs, Cout;
   int H, W, tiles_x, tiles_y;
+  int win_tx0, win_ty0, win_tx, win_ty;  // the tiles a launch covers: origin and extent in tiles
   float* stat;          // per-channel sums of the output per 32-pixel split, or nullptr
   int stat_splits;
 };
@@ -85,11 +86,12 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
   const int co0 = blockIdx.y * BCO;
   int frame, ty0, tx0;
   {
+    // tiles of the window (the whole frame by default), counted in the frame's own tile grid
     int t = blockIdx.x;
-    tx0 = (t % a.tiles_x) * 16;
-    t /= a.tiles_x;
-    ty0 = (t % a.tiles_y) * 8;
-    frame = t / a.tiles_y;
+    tx0 = (a.win_tx0 + t % a.win_tx) * 16;
+    t /= a.win_tx;
+    ty0 = (a.win_ty0 + t % a.win_ty) * 8;
+    frame = t / a.win_ty;
   }
   const int nslab = a.Cin / 64;
 
@@ -434,7 +436,7 @@ __global__ __launch_bounds__(512) void conv_ws_kernel(WsArgs a) {
           }
         }
         if (prow == 0) {
-          const int split = ((blockIdx.x % (a.tiles_x * a.tiles_y)) * 2 + pxh) * 2 + kh;
+          const int split = (((ty0 >> 3) * a.tiles_x + (tx0 >> 4)) * 2 + pxh) * 2 + kh;
           float* sp = a.stat + (((int64_t)frame * a.stat_splits + split) * a.Cout + co0 + i * 32 + pcol) * 2;
           *reinterpret_cast<f32x4*>(sp) = f32x4{ssum[0], ssq[0], ssum[1], ssq[1]};
           *reinterpret_cast<f32x4*>(sp + 4) = f32x4{ssum[2], ssq[2], ssum[3], ssq[3]};
@@ -462,7 +464,8 @@ static hipError_t run_ws(hipStream_t s, const FusedDesc& d) {
   a.Cin = d.Cin; a.Cs = d.Cs; a.Cout = d.Cout;
   a.H = d.H; a.W = d.W; a.tiles_x = (d.W + 15) / 16; a.tiles_y = (d.H + 7) / 8;
   a.stat = d.stat; a.stat_splits = d.stat_splits;
-  dim3 grid((unsigned)(a.tiles_x * a.tiles_y * d.frames), d.Cout / (CO_T * 32));
+  if (!conv_window_tiles(d, &a.win_tx0, &a.win_ty0, &a.win_tx, &a.win_ty)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)(a.win_tx * a.win_ty * d.frames), d.Cout / (CO_T * 32));
   kern<<<grid, 512, lds, s>>>(a);
   return hipGetLastError();
 }

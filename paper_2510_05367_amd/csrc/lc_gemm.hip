@@ -47,6 +47,7 @@ struct GemmArgs {
   void* yt;             // linear only: channels >= yt_from go, transposed, to the V^T layout of spatial attention
   int yt_from, yt_T, yt_Tp;
   int frames, H, W, tiles_x, tiles_y;
+  int win_tx0, win_ty0, win_tx, win_ty;  // conv: the tiles a launch covers, origin and extent in tiles
   int64_t rows;
   RowMap in_map, out_map;
   float* stat;          // conv, fp32 output: per-channel statistics of the output (see FusedDesc), or nullptr
@@ -112,11 +113,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   int frame = 0, ty0 = 0, tx0 = 0;
   int64_t row0 = 0;
   if (TAPS == 9) {
+    // tiles of the window (the whole frame by default), counted in the frame's own tile grid
     int t = blockIdx.x;
-    tx0 = (t % a.tiles_x) * 16;
-    t /= a.tiles_x;
-    ty0 = (t % a.tiles_y) * 8;
-    frame = t / a.tiles_y;
+    tx0 = (a.win_tx0 + t % a.win_tx) * 16;
+    t /= a.win_tx;
+    ty0 = (a.win_ty0 + t % a.win_ty) * 8;
+    frame = t / a.win_ty;
   } else {
     row0 = (int64_t)blockIdx.x * 128;
   }
@@ -512,7 +514,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
               }
             }
             if (prow == 0) {
-              const int split = ((blockIdx.x % (a.tiles_x * a.tiles_y)) * 2 + pxh) * 2 + kh;
+              const int split = (((ty0 >> 3) * a.tiles_x + (tx0 >> 4)) * 2 + pxh) * 2 + kh;
               float* sp = a.stat + (((int64_t)frame * a.stat_splits + split) * a.Cout_store + co0 + i * 32 + pcol) * 2;
               *reinterpret_cast<f32x4*>(sp) = f32x4{ssum[0], ssq[0], ssum[1], ssq[1]};
               *reinterpret_cast<f32x4*>(sp + 4) = f32x4{ssum[2], ssq[2], ssum[3], ssq[3]};
@@ -640,9 +642,11 @@ static hipError_t run_gemm(hipStream_t s, const FusedDesc& d) {
   a.stat = d.stat; a.stat_splits = d.stat_splits;
   a.q_scale = d.q_scale; a.q_cols = d.q_cols;
   dim3 grid;
+  a.win_tx0 = a.win_ty0 = 0; a.win_tx = a.tiles_x; a.win_ty = a.tiles_y;
   if (TAPS == 9) {
     if (d.frames <= 0) return hipSuccess;
-    grid = dim3((unsigned)(a.tiles_x * a.tiles_y * d.frames), d.Cout / BCO);
+    if (!conv_window_tiles(d, &a.win_tx0, &a.win_ty0, &a.win_tx, &a.win_ty)) return hipErrorInvalidValue;
+    grid = dim3((unsigned)(a.win_tx * a.win_ty * d.frames), d.Cout / BCO);
   } else {
     if (d.rows <= 0) return hipSuccess;
     grid = dim3((unsigned)((d.rows + 127) / 128), d.Cout / BCO);
@@ -683,6 +687,7 @@ hipError_t launch_fused(hipStream_t s, const FusedDesc& d) {
   if (d.yt && (d.taps != 1 || d.y_f32 || d.res || d.yt_from % 32 || d.yt_from <= 0 || d.yt_from >= d.Cout ||
                d.yt_Tp % 64 || d.yt_Tp < d.yt_T || d.out_map.rows_per_seg < d.rows))
     return hipErrorInvalidValue;
+  if (d.taps == 1 && d.win_w) return hipErrorInvalidValue;  // the streaming linear kernel has no spatial window
   const int esz = (int)dtype_size(d.dt);
   if (d.q_cols && (d.taps != 1 || d.q_cols % 4 || d.q_cols > d.Cout || d.bias || d.res)) return hipErrorInvalidValue;
   if (d.stat && (d.taps != 9 || d.planar_out || !(d.y_f32 || esz == 4) || d.stat_splits != conv_stat_splits(d.H, d.W)))

@@ -27,6 +27,9 @@ hipError_t launch_gn_finalize(hipStream_t s, const float* partA, int CA, int spl
                               const float* partB, int CB, int splitsB, int rowsB, float wB,
                               const float* gamma, const float* beta, int groups, float eps,
                               float* scale, float* shift, int frames);
+// A spatial window of a frame, in pixels: the spatial block of a feature chunk. w == 0: the whole frame.
+struct Win { int x0, y0, w, h; };
+
 // ---- implicit-GEMM convolution / linear layers (MFMA) ---------------------------------------
 struct ConvDesc {
   int dt;      // MFMA operand type = type of w (and of x unless x_f32)
@@ -53,8 +56,9 @@ hipError_t launch_conv(hipStream_t s, const ConvDesc& d);
 // eps = conv3x3_{C -> C_lat}(SiLU(u * scale + shift)) + bias: u fp32 rows [frames][H*W][C], scale / shift
 // [frames][C], w [32][9][C] (rows beyond C_lat zero), eps planar [frames][C_lat][H][W]. bf16 stages with
 // C = 320, W % 16 == 0, H % 4 == 0 only: otherwise hipErrorNotSupported (use the general kernel).
+// win: the pixels to compute (win.w == 0: the whole frame); x0, w multiples of 16 and y0, h of 4.
 hipError_t launch_conv_out_tile(hipStream_t s, int dt, const void* u, const float* scale, const float* shift, const void* w,
-                                const float* bias, void* out, int frames, int H, int W, int C, int C_lat);
+                                const float* bias, void* out, int frames, int H, int W, int C, int C_lat, Win win);
 
 // ---- fused-loader 3x3 stride-1 convolutions and linear layers (32x32 MFMA tiles) -------------
 struct FusedDesc {
@@ -75,6 +79,18 @@ struct FusedDesc {
   const void* w_frag;  // taps == 1: the same matrix in MFMA fragment order (launch_pack_lin_w), or nullptr
   const float* bias;   // [Cout] or nullptr
   int frames, H, W;    // taps == 9
+  // Spatial window (the spatial block of a feature chunk): only the pixels [win_y0, win_y0 + win_h) x
+  // [win_x0, win_x0 + win_w) of every frame are computed, by the tiles they belong to in the whole frame (a
+  // window starts on a tile boundary and ends on one or at the frame's edge), with the halo read from the
+  // neighbouring blocks of x; every output, and the partial sums of the tiles, are what the whole-frame launch
+  // gives. win_w == 0: the whole frame.
+  //   taps == 9: in pixels of the H x W image (tiles of 16 x 8).
+  //   taps == 1: the dense rows of the launch are taken frame by frame as images of win_img_w pixels per row and
+  //   win_img_t rows per frame; the launch walks the 32-row tiles of the window only. win_in / win_out say
+  //   whether the input rows / the output rows (with residual, statistics and the V^T columns) are addressed by
+  //   the row's place in the whole frame (1) or by its running number inside the launch (0).
+  int win_x0, win_y0, win_w, win_h;
+  int win_img_w, win_img_t, win_in, win_out;
   int64_t rows;        // taps == 1: x row of dense row r is in_map(r), y / res row is out_map(r);
   RowMap in_map, out_map;  //        scale/shift frame of row r is r / in_map.rows_per_seg
   const void* x;
@@ -105,6 +121,18 @@ struct FusedDesc {
 inline float attn_q_scale(int head_dim) { return 1.4426950408889634f / sqrtf((float)head_dim); }
 // splits per frame of the statistics a 3x3 launch writes
 inline int conv_stat_splits(int H, int W) { return 4 * ((W + 15) / 16) * ((H + 7) / 8); }
+// The tiles (16 x 8 pixels) of a 3x3 launch's window: false if the window does not start on a tile boundary, or
+// ends neither on one nor at the frame's edge.
+inline bool conv_window_tiles(const FusedDesc& d, int* tx0, int* ty0, int* ntx, int* nty) {
+  const int tiles_x = (d.W + 15) / 16, tiles_y = (d.H + 7) / 8;
+  if (d.win_w == 0) { *tx0 = *ty0 = 0; *ntx = tiles_x; *nty = tiles_y; return true; }
+  const int x1 = d.win_x0 + d.win_w, y1 = d.win_y0 + d.win_h;
+  if (d.win_x0 < 0 || d.win_y0 < 0 || d.win_w <= 0 || d.win_h <= 0 || x1 > d.W || y1 > d.H) return false;
+  if (d.win_x0 % 16 || d.win_y0 % 8 || (x1 % 16 && x1 != d.W) || (y1 % 8 && y1 != d.H)) return false;
+  *tx0 = d.win_x0 / 16; *ty0 = d.win_y0 / 8;
+  *ntx = (x1 + 15) / 16 - *tx0; *nty = (y1 + 7) / 8 - *ty0;
+  return true;
+}
 hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
 // taps == 9 of a bf16 stage with specialised wavefronts (lc_convws.hip): the same results as the general
 // kernel bit for bit; hipErrorNotSupported for shapes it does not cover. launch_fused tries it first.
@@ -124,6 +152,11 @@ inline hipError_t launch_linear_any(hipStream_t s, const FusedDesc& d) {
 inline int attn_tp(int T) { return (T + 63) / 64 * 64; }
 hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
                                     int frames, int T, int heads, int d, int q0, int q1, int q_prescaled);
+// The same for a window of queries: nq queries, number i being token q0 + (i / qw) * qstride + i % qw (rows of qw
+// tokens out of image rows of qstride tokens). Each query's result does not depend on which others share its launch.
+hipError_t launch_spatial_attention_window(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
+                                           int frames, int T, int heads, int d, int q0, int nq, int qw, int qstride,
+                                           int q_prescaled);
 // vt from plain value rows v[frames*T][C] of stride ldv
 hipError_t launch_make_vt(hipStream_t s, int dt, const void* v, int ldv, void* vt, int frames, int T, int Tp, int C);
 // qkv [(B*F)*P][3C] frame-major -> out same rows x C; attention over the F frames.
@@ -134,8 +167,9 @@ hipError_t launch_temporal_attention(hipStream_t s, int dt, const void* qkv, voi
 // h[frames*H*W][C] (fp32) = conv3x3(x[frames][Cl][H][W] of type dt); w_packed float [Cl*9][C], bias float [C].
 // conv_in for bf16 stages whose image rows are whole 32-pixel segments, with the GroupNorm partial sums of its
 // output (lc_conv.hip); hipErrorNotSupported otherwise
+// win: the pixels to compute (win.w == 0: the whole frame); x0 and w multiples of 32.
 hipError_t launch_conv_in_tile(hipStream_t s, int dt, const void* x, const void* wp, const float* bias, float* y, float* stat,
-                               int frames, int H, int W, int Cl, int C);
+                               int frames, int H, int W, int Cl, int C, Win win);
 hipError_t launch_conv_in(hipStream_t s, int dt, const void* x, void* h, int frames, int H, int W, int Cl, int C,
                           const float* w_packed, const float* bias);
 // planar [frames][C][HW] <-> channels-last [frames][HW][C]

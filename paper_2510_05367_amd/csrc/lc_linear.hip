@@ -44,6 +44,12 @@ struct LinArgs {
   float q_scale;          // output channels below q_cols are multiplied by this before rounding
   int q_cols;
   RowMap in_map, out_map;
+  // Spatial window (win_bw == 0: off). The dense rows are frames of win_ft tiles, each frame an image whose rows
+  // are win_ftx tiles long; the launch walks only the tiles of a block of win_bh image rows x win_bw tiles that
+  // starts at tile win_t0 of every frame: tile j of the launch is tile full_of(j) of the dense rows. win_in /
+  // win_out: the input / the output side (y, residual, statistics, V^T) is addressed by the tile's place in the
+  // dense rows (1) or by its running number in the launch (0).
+  int win_bw, win_bh, win_t0, win_ftx, win_ft, win_in, win_out;
 };
 
 constexpr int kRows = 32;        // rows of one activation tile
@@ -133,6 +139,14 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
   const int t0 = blockIdx.x * a.tiles_per_wg;
   const int t1 = min(ntiles, t0 + a.tiles_per_wg);
   if (t0 >= t1) return;
+  auto full_of = [&](int j) {
+    const int q = j / a.win_bw, bx = j - q * a.win_bw;
+    const int f = q / a.win_bh, by = q - f * a.win_bh;
+    return f * a.win_ft + a.win_t0 + by * a.win_ftx + bx;
+  };
+  const bool win_in = a.win_bw != 0 && a.win_in != 0, win_out = a.win_bw != 0 && a.win_out != 0;
+  auto in_tile = [&](int j) { return win_in ? full_of(j) : j; };
+  auto out_tile = [&](int j) { return win_out ? full_of(j) : j; };
   // this wavefront's tiles: its share of the column's, topped up to NTM with repeats
   const int tcol = min(a.tc, a.Cout / 32 - (int)blockIdx.y * a.tc);  // the last column may be narrower
   const int nt = tcol / 4 + (wid < tcol % 4 ? 1 : 0);
@@ -178,7 +192,7 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
   // the tile being requested: its index and place in the source rows
   int tf = t0;
   TileWalk wi{0, 0};
-  if constexpr (SRC != 2) wi.start(t0 * kRows, a.in_map.rows_per_seg);
+  if constexpr (SRC != 2) wi.start(in_tile(t0) * kRows, a.in_map.rows_per_seg);
   const char* xbase = nullptr;
   auto set_xbase = [&]() {
     if constexpr (SRC != 2)
@@ -187,7 +201,10 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
   auto next_in_tile = [&]() {  // beyond the last tile of the range: that tile again
     if (tf < t1 - 1) {
       ++tf;
-      if constexpr (SRC != 2) wi.next(a.in_map.rows_per_seg);
+      if constexpr (SRC != 2) {
+        if (win_in) wi.start(full_of(tf) * kRows, a.in_map.rows_per_seg);  // (a window's tiles are not consecutive)
+        else wi.next(a.in_map.rows_per_seg);
+      }
     }
     set_xbase();
   };
@@ -195,7 +212,7 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
     constexpr int j = decltype(J)::value;
     if constexpr (SRC == 2) {
       const int hw = a.im_H * a.im_W;
-      const int row = tf * kRows + min(rg + RPR * j, kRows - 1);
+      const int row = in_tile(tf) * kRows + min(rg + RPR * j, kRows - 1);
       const int f = row / hw, p = row - f * hw;
       const int yy = p / a.im_W, xx = p - yy * a.im_W;
       const T* img = (const T*)a.x + (int64_t)f * a.im_Cl * hw;
@@ -260,9 +277,13 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
     }
   // wave-uniform bases of the tile being computed (c*) and of the one whose outputs wait in the patches (p*)
   TileWalk wo, wv{0, 0}, ws{0, 0};
-  wo.start(t0 * kRows, a.out_map.rows_per_seg);
-  if (a.yt) wv.start(t0 * kRows, a.yt_T);
-  if (F32OUT && a.stat) ws.start(t0 * kRows, a.stat_rps);
+  int to = t0;  // the tile whose bases c* hold
+  auto start_out = [&](int row0) {
+    wo.start(row0, a.out_map.rows_per_seg);
+    if (a.yt) wv.start(row0, a.yt_T);
+    if (F32OUT && a.stat) ws.start(row0, a.stat_rps);
+  };
+  start_out(out_tile(t0) * kRows);
   int64_t cy = 0, py = 0;      // byte offset of the tile's first row in y (and in the residual)
   char *cvt = nullptr, *pvt = nullptr;
   float *cst = nullptr, *pst = nullptr;
@@ -274,9 +295,14 @@ __global__ __launch_bounds__(256) void lin_kernel(LinArgs a) {
   };
   auto next_out_tile = [&]() {
     py = cy; pvt = cvt; pst = cst;
-    wo.next(a.out_map.rows_per_seg);
-    if (a.yt) wv.next(a.yt_T);
-    if (F32OUT && a.stat) ws.next(a.stat_rps);
+    ++to;
+    if (win_out) {
+      start_out(full_of(to) * kRows);
+    } else {
+      wo.next(a.out_map.rows_per_seg);
+      if (a.yt) wv.next(a.yt_T);
+      if (F32OUT && a.stat) ws.next(a.stat_rps);
+    }
     set_out_bases();
   };
   set_out_bases();
@@ -539,11 +565,18 @@ static hipError_t run_lin_r(hipStream_t s, const FusedDesc& d, int cols, int tc)
   a.im_H = d.H; a.im_W = d.W; a.im_Cl = d.Cs;
   a.stat = d.stat; a.stat_splits = d.stat_splits; a.stat_rps = d.stat_rps; a.stat_off = d.stat_off;
   a.q_scale = d.q_scale; a.q_cols = d.q_cols;
+  a.win_bw = a.win_bh = a.win_t0 = a.win_ftx = a.win_ft = a.win_in = a.win_out = 0;
+  int ntiles = (int)d.rows / kRows;
+  if (d.win_w) {  // (validated in launch_linear)
+    a.win_bw = d.win_w / kRows; a.win_bh = d.win_h; a.win_ftx = d.win_img_w / kRows; a.win_ft = a.win_ftx * d.win_img_t;
+    a.win_t0 = d.win_y0 * a.win_ftx + d.win_x0 / kRows; a.win_in = d.win_in; a.win_out = d.win_out;
+    ntiles = (int)(d.rows / ((int64_t)d.win_img_w * d.win_img_t)) * a.win_bh * a.win_bw;
+    a.rows = ntiles * kRows;
+  }
   // one workgroup per compute unit (its registers hold the weights), each with a contiguous range of tiles.
   // The gathering instantiation with one tile per wavefront has few weights and little LDS: three of its
   // workgroups share a compute unit, and one's gather latency hides behind the others' stores.
   constexpr int kPerCu = (SRC == 2 && NTM == 1) ? 3 : (SRC == 0 && CIN == 320 && NTM == 1) ? 2 : 1;
-  const int ntiles = (int)d.rows / kRows;
   const int gx_max = 256 * kPerCu / cols > 1 ? 256 * kPerCu / cols : 1;
   int tpw = (ntiles + gx_max - 1) / gx_max;
   if (tpw < kLinMinTiles) tpw = kLinMinTiles;
@@ -593,6 +626,14 @@ hipError_t launch_linear(hipStream_t s, const FusedDesc& d) {
   if (d.rows % kRows || (d.src != 2 && d.in_map.rows_per_seg % kRows) || d.out_map.rows_per_seg % kRows ||
       (d.yt && (d.yt_T % kRows || d.bias)))
     return hipErrorNotSupported;
+  if (d.win_w) {  // a window of whole 32-pixel segments of image rows, inside the frame; rows = whole frames
+    const int64_t fr = (int64_t)d.win_img_w * d.win_img_t;
+    if (d.win_img_w <= 0 || d.win_img_t <= 0 || d.win_img_w % kRows || d.win_x0 % kRows || d.win_w % kRows || d.win_x0 < 0 ||
+        d.win_y0 < 0 || d.win_w < 0 || d.win_h <= 0 || d.win_x0 + d.win_w > d.win_img_w || d.win_y0 + d.win_h > d.win_img_t ||
+        d.rows % fr)
+      return hipErrorInvalidValue;
+    if (!d.win_in && !d.win_out) return hipErrorInvalidValue;
+  }
   const bool y32 = d.y_f32 || d.dt != kBF16;
   if (d.res && !y32) return hipErrorNotSupported;
   if (d.q_cols && (d.q_cols % 32 || d.q_cols > d.Cout || d.bias || d.res || (d.yt && d.q_cols > d.yt_from)))

@@ -252,6 +252,19 @@ def test_invariants_whole_stage(cfg, chunks):
             assert torch.equal(a, e_full), (fc, tc)
             assert torch.equal(b, e_full), (fc, tc)
             assert stage.dev_entry_bytes(1) == deep_ref, (fc, tc)
+        # the literal spatial chunk, inside the workload's frame chunks: blocks of H/eta x W/omega
+        for eta, omega in {"animatediff": [(2, 2), (8, 1)], "svdxt": [(3, 4)], "stress": [(4, 3)]}[cfg.name]:
+            print(f"[spatial chunk] {eta} x {omega}", flush=True)
+            stage.set_chunk(cfg.frame_chunk, 0)
+            stage.set_spatial_chunk(eta, omega)
+            a, b = stage.empty(*x.shape), stage.empty(*x.shape)
+            stage.full_step(x, a, 1)
+            stage.cached_step(x, b, 1)
+            stage.sync()
+            assert torch.equal(a, e_full), (eta, omega)
+            assert torch.equal(b, e_full), (eta, omega)
+            assert stage.dev_entry_bytes(1) == deep_ref, (eta, omega)
+        stage.set_spatial_chunk(1, 1)
     finally:
         stage.close()
 

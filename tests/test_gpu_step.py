@@ -219,6 +219,64 @@ def test_state_machine_errors():
         lcb.lc_destroy(ctx)
 
 
+# stages whose frames are whole tiles of every kernel: 16 image rows (two 8-row conv tiles) of 64 / 32 pixels
+SP_BF16 = synth.StageConfig("sp_bf16", B=1, F=3, H=16, W=64, C_lat=4, C=320, C_deep=640, groups=32, n_res=2,
+                            heads=8, head_dim=40, dtype="bf16")
+SP_F32 = synth.StageConfig("sp_f32", B=2, F=2, H=16, W=32, C_lat=4, C=64, C_deep=128, groups=32, n_res=1,
+                           heads=1, head_dim=64, dtype="f32")
+
+
+@pytest.mark.parametrize("cfg", [SP_BF16, SP_F32], ids=lambda c: c.name)
+def test_spatial_chunk_equals_whole_frame_bitwise_and_matches_oracle(cfg):
+    """The literal spatial feature chunk (H/eta x W/omega blocks, one-pixel halo from the neighbouring blocks, split
+    GroupNorm sums, a block's queries against the whole frame's keys): bit-identical to the unchunked step for every
+    factor pair the stage admits, alone and inside frame chunks, on one lane and two; and equal to the oracle's own
+    block loops within the tolerance."""
+    stage, w = make_stage(cfg, seed=0, sharp=4.0, frame_chunk=0, token_chunk=0)
+    try:
+        x = synth.make_latents(cfg, 1)
+        xd = dev(stage, x)
+        ref_full, ref_cached = stage.empty(*x.shape), stage.empty(*x.shape)
+        stage.full_step(xd, ref_full, 0)
+        deep = synth.make_deep(cfg, 2)
+        stage.cache_write(1, dev(stage, deep))
+        stage.cached_step(xd, ref_cached, 1)
+        stage.sync()
+        deep_ref = stage.dev_entry_bytes(0)
+        pairs = [(2, 1), (1, 2), (2, 2)] if cfg.W == 64 else [(2, 1)]
+        for eta, omega in pairs:
+            for fc, lanes in [(0, 2), (2, 2), (1, 1)]:
+                print(f"[spatial] {cfg.name} eta={eta} omega={omega} frame chunk {fc} lanes {lanes}", flush=True)
+                stage.set_chunk(fc, 0)
+                stage.set_spatial_chunk(eta, omega)
+                stage.set_lanes(lanes)
+                stage.cache_write(1, dev(stage, deep))  # (a larger workspace, once it is needed, starts with empty slots)
+                a, b = stage.empty(*x.shape), stage.empty(*x.shape)
+                stage.full_step(xd, a, 0)
+                stage.cached_step(xd, b, 1)
+                stage.sync()
+                assert torch.equal(a, ref_full), (eta, omega, fc)
+                assert torch.equal(b, ref_cached), (eta, omega, fc)
+                assert stage.dev_entry_bytes(0) == deep_ref
+        orc = oracle_for(cfg, w)
+        orc.set_spatial_chunk(*pairs[-1])
+        orc.cache_write(1, deep)
+        check("cached_step eps (spatial chunk)", host(b), orc.cached_step(x, 1), cfg.dtype)
+        # factors that do not give whole tiles are refused and leave the setting as it was
+        for eta, omega, code in [(3, 1, lcb.LC_ERR_SHAPE), (4, 1, lcb.LC_ERR_SHAPE), (1, 4, lcb.LC_ERR_SHAPE),
+                                 (0, 1, lcb.LC_ERR_ARG)]:
+            with pytest.raises(lcb.LcError) as e:
+                lcb.lc_set_spatial_chunk(stage.ctx, eta, omega)
+            assert e.value.status == code, (eta, omega)
+        c2 = stage.empty(*x.shape)
+        stage.cached_step(xd, c2, 1)
+        stage.sync()
+        assert torch.equal(c2, ref_cached)
+        stage.set_spatial_chunk(1, 1)
+    finally:
+        stage.close()
+
+
 def test_double_destroy_and_failed_pinned_allocation():
     cfg = RAG_F32
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()

@@ -284,3 +284,61 @@ def test_schedule_counts_and_teacher_forcing():
     assert np.array_equal(o2.cached_step(xs[2], 0), eps[2])
     assert np.array_equal(o2.full_step(xs[3], 0), eps[3])
     assert np.allclose(xs[1], xs[0] - eps[0] / 7.0, atol=1e-15)
+
+
+# --------------------------------------------------------------------------- literal spatial chunk
+SP = synth.StageConfig("sp", B=2, F=3, H=16, W=12, C_lat=4, C=32, C_deep=64, groups=8, n_res=2, heads=2, head_dim=16,
+                       dtype="f32")
+
+
+def test_conv_block_with_halo_is_a_slice_of_the_whole_convolution():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((2, 3, 8, 10))
+    w = rng.standard_normal((4, 3, 3, 3))
+    b = rng.standard_normal(4)
+    whole = lo.conv3x3(x, w, b)  # (itself pinned by brute force and closed forms in test_oracle_ops.py)
+    for (y0, y1, x0, x1) in [(0, 8, 0, 10), (0, 4, 0, 5), (4, 8, 5, 10), (2, 6, 3, 7), (0, 2, 8, 10), (7, 8, 0, 1)]:
+        blk = lo.conv3x3_block(x, w, b, y0, y1, x0, x1)
+        assert np.max(np.abs(blk - whole[:, :, y0:y1, x0:x1])) < 1e-13, (y0, y1, x0, x1)
+    # the halo is what makes it so: the block convolved on its own (zeros around it) differs along its inner edges
+    alone = lo.conv3x3(np.ascontiguousarray(x[:, :, 2:6, 3:7]), w, b)
+    assert np.max(np.abs(alone - whole[:, :, 2:6, 3:7])) > 1e-2
+    assert np.max(np.abs(alone[:, :, 1:3, 1:3] - whole[:, :, 3:5, 4:6])) < 1e-13  # its interior does not
+    # against the scalar brute force directly, on a corner block
+    bf = np.array(brute.conv3x3(x.tolist(), w.tolist(), b.tolist()))[:, :, 4:8, 5:10]
+    assert np.max(np.abs(lo.conv3x3_block(x, w, b, 4, 8, 5, 10) - bf)) < 1e-12
+
+
+def test_group_norm_in_two_passes_over_blocks():
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((2, 8, 6, 8)) * 2.0 + 0.7
+    g, b = 1.0 + 0.1 * rng.standard_normal(8), 0.1 * rng.standard_normal(8)
+    blocks = [(0, 3, 0, 4), (0, 3, 4, 8), (3, 6, 0, 4), (3, 6, 4, 8)]
+    y = lo.group_norm_blocks(x, g, b, 4, 1e-5, blocks)
+    assert np.max(np.abs(y - lo.group_norm(x, g, b, 4, 1e-5))) < 1e-13
+    yb = np.array(brute.group_norm_silu(x.tolist(), g.tolist(), b.tolist(), 4, 1e-5, act=False))
+    assert np.max(np.abs(y - yb)) < 1e-12
+    with pytest.raises(AssertionError):  # blocks that do not tile the image
+        lo.group_norm_blocks(x, g, b, 4, 1e-5, blocks[:3])
+
+
+@pytest.mark.parametrize("eta,omega,fc", [(2, 1, 0), (1, 2, 0), (4, 3, 2), (8, 6, 0), (2, 2, 4)])
+def test_spatially_chunked_steps_equal_unchunked(eta, omega, fc):
+    w = {k: v.astype(np.float64) for k, v in synth.make_weights(SP, 0, sharp=4.0).items()}
+    x = synth.make_latents(SP, 1)
+    whole = lo.Oracle(SP, w)
+    ref = whole.full_step(x, 0)
+    o = lo.Oracle(SP, w)
+    o.set_spatial_chunk(eta, omega)
+    o.set_chunk(fc, 0)
+    full = o.full_step(x, 0)
+    assert np.max(np.abs(full - ref)) < 1e-12
+    assert np.max(np.abs(o.dev[0] - whole.dev[0])) < 1e-12
+    deep = synth.make_deep(SP, 2)
+    o.cache_write(1, deep)
+    whole.cache_write(1, deep)
+    assert np.max(np.abs(o.cached_step(x, 1) - whole.cached_step(x, 1))) < 1e-12
+    with pytest.raises(ValueError):
+        o.set_spatial_chunk(3, 1)   # 16 / 3
+    with pytest.raises(ValueError):
+        o.set_spatial_chunk(16, 1)  # blocks of one row: the deep feature under them has no whole row
