@@ -165,3 +165,96 @@ def make_activation(shape, seed: int, dtype: str = "f32", scale: float = 1.0) ->
     rng = np.random.default_rng(seed)
     a = rng.standard_normal(shape, dtype=np.float32) * np.float32(scale)
     return round_to_bf16(a) if dtype == "bf16" else a
+
+
+# --------------------------------------------------------------------------------------
+# Sliced decoding: a convolutional latent decoder (stand-in for the pretrained one)
+# --------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class DecoderConfig:
+    """Shape of the decoder of the sliced-decoding stage. N = frames (batch and frame axes merged), H x W the
+    latent size; widths = (C_0, ..., C_L): mid width and the width after each of the L 2x upsampling levels."""
+
+    name: str
+    N: int
+    H: int
+    W: int
+    C_lat: int
+    C_img: int
+    widths: Tuple[int, ...]
+    groups: int
+    heads: int
+    head_dim: int
+    dtype: str
+    slice_frames: int = 1
+    gn_eps: float = 1e-5
+
+    @property
+    def levels(self) -> int:
+        return len(self.widths) - 1
+
+    def with_(self, **kw) -> "DecoderConfig":
+        return replace(self, **kw)
+
+    def decode_flops(self) -> float:
+        """Algorithmic FLOPs of decoding all N frames."""
+        P = self.H * self.W
+        C0 = self.widths[0]
+        f = 2.0 * 9 * self.C_lat * C0 * P + 2 * 2.0 * 9 * C0 * C0 * P       # conv_in, two mid residual blocks
+        f += 8.0 * C0 * C0 * P + 4.0 * P * P * C0                            # attention block
+        for l in range(self.levels):
+            f += 2.0 * 9 * self.widths[l] ** 2 * P                            # residual block of the level
+            P *= 4
+            f += 2.0 * 9 * self.widths[l] * self.widths[l + 1] * P            # convolution after the upsampling
+        f += 2.0 * 9 * self.widths[-1] * self.C_img * P
+        return f * self.N
+
+
+DECODERS: Dict[str, DecoderConfig] = {
+    # tiny fp32 decoder on the latents of the tiny stage
+    "tiny": DecoderConfig("tiny", N=8, H=32, W=32, C_lat=4, C_img=3, widths=(64, 64, 64), groups=32, heads=1,
+                          head_dim=64, dtype="f32"),
+    # 512 x 512 video frames from 64 x 64 latents, 16 frames (the guidance halves are already combined)
+    "animatediff": DecoderConfig("animatediff", N=16, H=64, W=64, C_lat=4, C_img=3, widths=(320, 320, 192, 128),
+                                 groups=32, heads=8, head_dim=40, dtype="bf16"),
+}
+
+
+def decoder_weight_manifest(cfg: DecoderConfig) -> List[Tuple[str, Tuple[int, ...], str]]:
+    C0 = cfg.widths[0]
+    m: List[Tuple[str, Tuple[int, ...], str]] = [("conv_in.w", (C0, cfg.C_lat, 3, 3), "w"), ("conv_in.b", (C0,), "w")]
+
+    def res(prefix, C):
+        return [(f"{prefix}.gn_g", (C,), "g"), (f"{prefix}.gn_b", (C,), "b"), (f"{prefix}.w", (C, C, 3, 3), "w"),
+                (f"{prefix}.b", (C,), "w")]
+    m += res("mid.res0", C0)
+    m += [("mid.attn.gn_g", (C0,), "g"), ("mid.attn.gn_b", (C0,), "b")]
+    m += [(f"mid.attn.{k}", (C0, C0), "w") for k in ("wq", "wk", "wv", "wo")] + [("mid.attn.bo", (C0,), "w")]
+    m += res("mid.res1", C0)
+    for l in range(cfg.levels):
+        m += res(f"up{l}.res", cfg.widths[l])
+        m += [(f"up{l}.conv.w", (cfg.widths[l + 1], cfg.widths[l], 3, 3), "w"), (f"up{l}.conv.b", (cfg.widths[l + 1],), "w")]
+    CL = cfg.widths[-1]
+    m += [("out.gn_g", (CL,), "g"), ("out.gn_b", (CL,), "b"), ("out.w", (cfg.C_img, CL, 3, 3), "w"), ("out.b", (cfg.C_img,), "w")]
+    return m
+
+
+def make_decoder_weights(cfg: DecoderConfig, seed: int = 0, sharp: float = 1.0) -> Dict[str, np.ndarray]:
+    """Same recipe as make_weights: weights and biases ~N(0, 0.02), GroupNorm scale 1 + N(0, 0.02), shift N(0, 0.02)."""
+    rng = np.random.default_rng(seed)
+    out: Dict[str, np.ndarray] = {}
+    for name, shape, kind in decoder_weight_manifest(cfg):
+        a = rng.standard_normal(shape, dtype=np.float32) * np.float32(0.02)
+        if kind == "g":
+            a = a + np.float32(1.0)
+        if sharp != 1.0 and (name.endswith(".wq") or name.endswith(".wk")):
+            a = a * np.float32(sharp)
+        out[name] = round_to_bf16(a) if cfg.dtype == "bf16" else a
+    return out
+
+
+def make_decoder_latents(cfg: DecoderConfig, seed: int = 1) -> np.ndarray:
+    """Denoised latents z, shape [N, C_lat, H, W], ~N(0,1)."""
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal((cfg.N, cfg.C_lat, cfg.H, cfg.W), dtype=np.float32)
+    return round_to_bf16(a) if cfg.dtype == "bf16" else a

@@ -131,3 +131,39 @@ def stage(cfg, w, x, deep_in=None):
     u = conv3x3(group_norm_silu(cat, w["up.gn_g"], w["up.gn_b"], G, cfg.gn_eps), w["up.w"], w["up.b"])
     eps = conv3x3(group_norm_silu(u, w["out.gn_g"], w["out.gn_b"], G, cfg.gn_eps), w["out.w"], w["out.b"])
     return eps, deep
+
+
+def decoder(cfg, w, z):
+    """The latent decoder of the sliced-decoding stage on nested lists z [n][C_lat][H][W], one frame at a time:
+    conv_in, residual block, attention block, residual block, then per level residual block, nearest 2x
+    upsampling, convolution; GroupNorm, SiLU and a convolution at the end."""
+    G = cfg.groups
+
+    def add(a, b):
+        return [[[[a[n][c][i][j] + b[n][c][i][j] for j in range(len(a[0][0][0]))] for i in range(len(a[0][0]))]
+                 for c in range(len(a[0]))] for n in range(len(a))]
+
+    def res(h, p):
+        return add(h, conv3x3(group_norm_silu(h, w[p + ".gn_g"], w[p + ".gn_b"], G, cfg.gn_eps), w[p + ".w"], w[p + ".b"]))
+
+    out = []
+    for frame in z:
+        h = conv3x3([frame], w["conv_in.w"], w["conv_in.b"])
+        h = res(h, "mid.res0")
+        C, H, W = len(h[0]), len(h[0][0]), len(h[0][0][0])
+        g = group_norm_silu(h, w["mid.attn.gn_g"], w["mid.attn.gn_b"], G, cfg.gn_eps, act=False)
+        X = [[g[0][c][i][j] for c in range(C)] for i in range(H) for j in range(W)]
+        Y = attn_rows(X, w["mid.attn.wq"], w["mid.attn.wk"], w["mid.attn.wv"], w["mid.attn.wo"], w["mid.attn.bo"], cfg.heads)
+        for i in range(H):
+            for j in range(W):
+                for c in range(C):
+                    h[0][c][i][j] += Y[i * W + j][c]
+        h = res(h, "mid.res1")
+        for l in range(len(cfg.widths) - 1):
+            h = res(h, f"up{l}.res")
+            H, W = len(h[0][0]), len(h[0][0][0])
+            up = [[[[h[0][c][i // 2][j // 2] for j in range(2 * W)] for i in range(2 * H)] for c in range(len(h[0]))]]
+            h = conv3x3(up, w[f"up{l}.conv.w"], w[f"up{l}.conv.b"])
+        h = conv3x3(group_norm_silu(h, w["out.gn_g"], w["out.gn_b"], G, cfg.gn_eps), w["out.w"], w["out.b"])
+        out.append(h[0])
+    return out
