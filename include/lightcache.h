@@ -313,6 +313,58 @@ lc_status lc_op_up_conv(lc_ctx* ctx, const void* skip, const void* deep, void* u
 /* eps[frames, C_lat, H, W] (cfg dtype) = conv_out(SiLU(GroupNorm(u))), u float [frames*H*W, C]. */
 lc_status lc_op_conv_out(lc_ctx* ctx, const void* u, void* eps, int frames);
 
+/* ---- sliced decoding ("Feature chunk and Sliced Decoding" section) --------------------------------------------
+ * At the decoding stage the batch and frame axes are merged (F in R^{(B x T) x C x H x W}) and the decoder would
+ * take all frames at once; sliced decoding decodes the latent video `slice_frames` frames at a time (1 = frame by
+ * frame) and merges the images back in frame order. Every operator of the decoder works on one frame at a time, so
+ * the result does not depend on the slice size (bit for bit), and the workspace is sized by the slice.
+ * The paper uses its models' pretrained decoders and does not describe them; this is a stand-in of the usual shape:
+ *   conv_in 3x3 C_lat -> widths[0]; ResBlock, spatial self-attention block, ResBlock at widths[0];
+ *   level l = 0 .. levels-1: ResBlock(widths[l]), nearest 2x upsampling, conv3x3 widths[l] -> widths[l+1];
+ *   GroupNorm -> SiLU -> conv3x3 widths[levels] -> C_img.
+ * ResBlock(h) = h + conv3x3(SiLU(GroupNorm(h))); the attention block is h + proj(Attn(qkv(GroupNorm(h)))) with
+ * bias-free q/k/v, `heads` heads of `head_dim`, scale 1/sqrt(head_dim), output projection with bias. It runs on
+ * the kernels of the denoising stage. Calls only enqueue on the stream given at creation; lc_decoder_sync drains it.
+ * Requirements (else LC_ERR_SHAPE): sizes > 0; 0 <= levels <= LC_DEC_MAX_LEVELS; widths multiples of 64, <= 1024,
+ * divisible by groups; heads * head_dim == widths[0]; head_dim in {8, 16, 32, 40, 64}; C_lat <= 16; C_img <= 32. */
+#define LC_DEC_MAX_LEVELS 3
+typedef struct lc_decoder lc_decoder; /* opaque; owned by the library */
+typedef struct lc_decoder_config {
+  int32_t N, H, W;       /* frames (batch x frames merged), latent size */
+  int32_t C_lat, C_img;  /* latent channels, image channels */
+  int32_t levels;        /* 2x upsampling levels: images are H * 2^levels x W * 2^levels */
+  int32_t widths[LC_DEC_MAX_LEVELS + 1];
+  int32_t groups, heads, head_dim;
+  int32_t dtype;         /* lc_dtype of z, the images and the weights */
+  float gn_eps;
+} lc_decoder_config;
+/* all [device], cfg dtype, PyTorch layouts; packed private copies are made by lc_decoder_load_weights */
+typedef struct lc_decoder_weights {
+  const void *conv_in_w, *conv_in_b;
+  lc_gnconv_w mid_res[2];
+  lc_attn_w mid_attn;
+  lc_gnconv_w up_res[LC_DEC_MAX_LEVELS];
+  const void *up_conv_w[LC_DEC_MAX_LEVELS], *up_conv_b[LC_DEC_MAX_LEVELS];
+  lc_gnconv_w out; /* GroupNorm(widths[levels]) -> SiLU -> conv widths[levels] -> C_img */
+} lc_decoder_weights;
+
+lc_status lc_decoder_check_config(const lc_decoder_config* cfg);                     /* host only */
+/* Workspace a pass over slice_frames frames needs (0 or > N: all N frames): two maps of the largest stage per
+ * frame of the slice, statistics, and the attention block's q,k,v. 0 if cfg is invalid. Host only. */
+size_t lc_decoder_workspace_bytes(const lc_decoder_config* cfg, int slice_frames);
+const char* lc_decoder_last_error(const lc_decoder* dec);
+/* stream: hipStream_t owned by the caller, must outlive the decoder. */
+lc_status lc_decoder_create(const lc_decoder_config* cfg, void* stream, lc_decoder** out);
+lc_status lc_decoder_destroy(lc_decoder* dec);
+lc_status lc_decoder_load_weights(lc_decoder* dec, const lc_decoder_weights* w /* [host] struct of [device] ptrs */);
+/* arena: [device], 256-byte aligned, caller-owned; must cover lc_decoder_workspace_bytes of the slices used. */
+lc_status lc_decoder_set_workspace(lc_decoder* dec, void* arena, size_t bytes);
+/* z [device, N, C_lat, H, W] -> img [device, N, C_img, H * 2^levels, W * 2^levels], in passes of slice_frames
+ * frames. LC_ERR_NOMEM if the workspace is too small for that slice; LC_ERR_STATE without weights / workspace.
+ * z and img must stay valid until the stream has been synchronised. */
+lc_status lc_decode(lc_decoder* dec, const void* z, void* img, int slice_frames);
+lc_status lc_decoder_sync(lc_decoder* dec);
+
 #ifdef __cplusplus
 }
 #endif

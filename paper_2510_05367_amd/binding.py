@@ -66,6 +66,21 @@ class lc_profile(C.Structure):
                 ("dropped", C.c_int64)]
 
 
+LC_DEC_MAX_LEVELS = 3
+
+
+class lc_decoder_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("N", "H", "W", "C_lat", "C_img", "levels")] + \
+               [("widths", C.c_int32 * (LC_DEC_MAX_LEVELS + 1))] + \
+               [(n, C.c_int32) for n in ("groups", "heads", "head_dim", "dtype")] + [("gn_eps", C.c_float)]
+
+
+class lc_decoder_weights(C.Structure):
+    _fields_ = [("conv_in_w", C.c_void_p), ("conv_in_b", C.c_void_p), ("mid_res", lc_gnconv_w * 2), ("mid_attn", lc_attn_w),
+                ("up_res", lc_gnconv_w * LC_DEC_MAX_LEVELS), ("up_conv_w", C.c_void_p * LC_DEC_MAX_LEVELS),
+                ("up_conv_b", C.c_void_p * LC_DEC_MAX_LEVELS), ("out", lc_gnconv_w)]
+
+
 # name -> (restype, argtypes). Every symbol include/lightcache.h declares is listed here.
 _P, _I, _I64 = C.c_void_p, C.c_int, C.c_int64
 PROTOTYPES = {
@@ -100,6 +115,15 @@ PROTOTYPES = {
     "lc_reset_stats": (_I, [_P]),
     "lc_set_profiling": (_I, [_P, C.c_uint32]),
     "lc_get_profile": (_I, [_P, C.POINTER(lc_profile)]),
+    "lc_decoder_check_config": (_I, [C.POINTER(lc_decoder_config)]),
+    "lc_decoder_workspace_bytes": (C.c_size_t, [C.POINTER(lc_decoder_config), _I]),
+    "lc_decoder_last_error": (C.c_char_p, [_P]),
+    "lc_decoder_create": (_I, [C.POINTER(lc_decoder_config), _P, C.POINTER(_P)]),
+    "lc_decoder_destroy": (_I, [_P]),
+    "lc_decoder_load_weights": (_I, [_P, C.POINTER(lc_decoder_weights)]),
+    "lc_decoder_set_workspace": (_I, [_P, _P, C.c_size_t]),
+    "lc_decode": (_I, [_P, _P, _P, _I]),
+    "lc_decoder_sync": (_I, [_P]),
     "lc_op_conv_in": (_I, [_P, _P, _P, _I]),
     "lc_op_res_block": (_I, [_P, _I, _P, _P, _I]),
     "lc_op_qkv": (_I, [_P, _I, _P, _P, _I]),
@@ -314,6 +338,131 @@ def lc_op_up_conv(ctx, skip_ptr, deep_ptr, u_ptr, frames) -> None:
 
 def lc_op_conv_out(ctx, u_ptr, eps_ptr, frames) -> None:
     _check(lib().lc_op_conv_out(ctx, u_ptr, eps_ptr, frames), ctx)
+
+
+# ---- sliced decoding ---------------------------------------------------------------------------
+def _dcheck(status: int, dec) -> None:
+    if status != LC_OK:
+        msg = lib().lc_decoder_last_error(dec)
+        raise LcError(status, msg.decode() if msg else "")
+
+
+def make_decoder_config(cfg) -> lc_decoder_config:
+    """cfg: any object with the synth.DecoderConfig attributes."""
+    c = lc_decoder_config(N=cfg.N, H=cfg.H, W=cfg.W, C_lat=cfg.C_lat, C_img=cfg.C_img, levels=len(cfg.widths) - 1,
+                          groups=cfg.groups, heads=cfg.heads, head_dim=cfg.head_dim,
+                          dtype=LC_BF16 if cfg.dtype == "bf16" else LC_F32, gn_eps=cfg.gn_eps)
+    for i, wd in enumerate(cfg.widths):
+        c.widths[i] = wd
+    return c
+
+
+def lc_decoder_check_config(cfg: lc_decoder_config) -> None:
+    _dcheck(lib().lc_decoder_check_config(C.byref(cfg)), None)
+
+
+def lc_decoder_workspace_bytes(cfg: lc_decoder_config, slice_frames: int) -> int:
+    return lib().lc_decoder_workspace_bytes(C.byref(cfg), slice_frames)
+
+
+def lc_decoder_last_error(dec=None) -> str:
+    return lib().lc_decoder_last_error(dec).decode()
+
+
+def lc_decoder_create(cfg: lc_decoder_config, stream: int):
+    out = C.c_void_p()
+    _dcheck(lib().lc_decoder_create(C.byref(cfg), stream, C.byref(out)), None)
+    return out
+
+
+def lc_decoder_destroy(dec) -> None:
+    _dcheck(lib().lc_decoder_destroy(dec), None)
+
+
+def lc_decoder_load_weights(dec, w: lc_decoder_weights) -> None:
+    _dcheck(lib().lc_decoder_load_weights(dec, C.byref(w)), dec)
+
+
+def lc_decoder_set_workspace(dec, arena_ptr: int, nbytes: int) -> None:
+    _dcheck(lib().lc_decoder_set_workspace(dec, arena_ptr, nbytes), dec)
+
+
+def lc_decode(dec, z_ptr: int, img_ptr: int, slice_frames: int) -> None:
+    _dcheck(lib().lc_decode(dec, z_ptr, img_ptr, slice_frames), dec)
+
+
+def lc_decoder_sync(dec) -> None:
+    _dcheck(lib().lc_decoder_sync(dec), dec)
+
+
+class Decoder:
+    """The decoder of the sliced-decoding stage on the current GPU; torch owns memory and the stream.
+    `weights`: name -> numpy float32 array, names as in synth.decoder_weight_manifest."""
+
+    def __init__(self, cfg, weights, max_slice: int = 1, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
+        self.torch, self.cfg = torch, cfg
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self.ccfg = make_decoder_config(cfg)
+        lc_decoder_check_config(self.ccfg)
+        self.stream = torch.cuda.Stream(device=self.device)
+        self.dec = lc_decoder_create(self.ccfg, self.stream.cuda_stream)
+        t = {k: self.to_device(v) for k, v in weights.items()}
+        self.stream.synchronize()
+        p = lambda n: t[n].data_ptr()
+        gc = lambda pre: lc_gnconv_w(p(pre + ".gn_g"), p(pre + ".gn_b"), p(pre + ".w"), p(pre + ".b"))
+        w = lc_decoder_weights()
+        w.conv_in_w, w.conv_in_b = p("conv_in.w"), p("conv_in.b")
+        w.mid_res[0], w.mid_res[1] = gc("mid.res0"), gc("mid.res1")
+        w.mid_attn = lc_attn_w(*[p(f"mid.attn.{k}") for k in ("gn_g", "gn_b", "wq", "wk", "wv", "wo", "bo")])
+        for l in range(len(cfg.widths) - 1):
+            w.up_res[l] = gc(f"up{l}.res")
+            w.up_conv_w[l], w.up_conv_b[l] = p(f"up{l}.conv.w"), p(f"up{l}.conv.b")
+        w.out = gc("out")
+        lc_decoder_load_weights(self.dec, w)
+        del t
+        self.arena = None
+        self.ensure_workspace(max_slice)
+
+    def to_device(self, a):
+        with self.torch.cuda.stream(self.stream):
+            return self.torch.from_numpy(a).to(self.device).to(self.tdtype).contiguous()
+
+    def ensure_workspace(self, slice_frames: int) -> int:
+        need = lc_decoder_workspace_bytes(self.ccfg, slice_frames)
+        if self.arena is None or self.arena.numel() < need:
+            lc_decoder_sync(self.dec)
+            self.arena = None
+            self.arena = self.torch.empty(need, dtype=self.torch.uint8, device=self.device)
+            self.torch.cuda.synchronize(self.device)
+            lc_decoder_set_workspace(self.dec, self.arena.data_ptr(), self.arena.numel())
+        return need
+
+    def decode(self, z, slice_frames: int = 1):
+        c = self.cfg
+        s = 2 ** (len(c.widths) - 1)
+        with self.torch.cuda.stream(self.stream):
+            img = self.torch.empty(c.N, c.C_img, c.H * s, c.W * s, dtype=self.tdtype, device=self.device)
+        lc_decode(self.dec, z.data_ptr(), img.data_ptr(), slice_frames)
+        return img
+
+    def sync(self):
+        lc_decoder_sync(self.dec)
+
+    def close(self):
+        if self.dec is not None:
+            lc_decoder_destroy(self.dec)
+            self.dec = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 # ---- convenience holder: torch owns memory and streams, the library does the work ---------------

@@ -672,6 +672,7 @@ static hipError_t by_kind(hipStream_t s, const FusedDesc& d) {
   if (d.Cout_store != d.Cout) return hipErrorInvalidValue;
   if (d.taps == 9) {
     if (d.src == 2) return y32 ? by_width<T, float, 9, 2>(s, d) : by_width<T, T, 9, 2>(s, d);
+    if (d.src == 1 && y32) return by_width<T, float, 9, 1>(s, d);  // no activation (the decoder's conv after upsampling)
     if (d.src == 3 && y32) return by_width<T, float, 9, 3>(s, d);
     return hipErrorInvalidValue;
   }

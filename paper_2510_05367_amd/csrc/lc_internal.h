@@ -66,7 +66,7 @@ struct FusedDesc {
   int y_f32;     // 1: y is an fp32 stream tensor; 0: y has the operand type
   int taps;      // 9: 3x3 conv over [frames][H][W][Cin]; 1: linear layer over rows
   int src;       // 0: x has the operand type, used as is
-                 // 1: x is fp32, x * scale[f][c] + shift[f][c] (GroupNorm apply)
+                 // 1: x is fp32, x * scale[f][c] + shift[f][c] (GroupNorm apply; taps == 9: general kernel only)
                  // 2: the same followed by SiLU (taps == 9); taps == 1: x is a planar image
                  //    [frames][Cs][H][W] of the operand type and row r gathers the 3x3 neighbourhood of
                  //    pixel r, k = channel * 9 + tap (a first convolution as a linear layer; Cin = 64 >= 9 Cs)
@@ -186,6 +186,9 @@ hipError_t launch_pack_lin_w(hipStream_t s, int dt, const void* w, void* out, in
 // w[Cout][Cin] -> out[Cout][Cin_padded] with zero columns appended
 hipError_t launch_pad_rows(hipStream_t s, int dt, const void* w, void* out, int Cout, int Cin, int Cin_padded);
 hipError_t launch_to_f32(hipStream_t s, int dt, const void* src, float* dst, int n, int n_padded);
+// nearest 2x upsampling of fp32 rows [frames][H][W][C] -> [frames][2H][2W][C] (C % 4 == 0)
+hipError_t launch_up2_rows(hipStream_t s, const float* src, float* dst, int frames, int H, int W, int C);
+hipError_t launch_fill_f32(hipStream_t s, float* dst, int64_t n, float v);
 hipError_t launch_copy_rows(hipStream_t s, int dt, const void* src, void* dst, int64_t elems);
 
 }  // namespace lc

@@ -171,4 +171,35 @@ hipError_t launch_copy_rows(hipStream_t s, int dt, const void* src, void* dst, i
   return hipGetLastError();
 }
 
+// Nearest 2x upsampling of fp32 rows: dst[f][2H][2W][C] from src[f][H][W][C], 16 bytes per thread.
+__global__ __launch_bounds__(256) void up2_rows_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst, int H, int W,
+                                                       int C4, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C4);
+  int64_t p = i / C4;  // output pixel, frame-major
+  const int ox = (int)(p % (2 * W));
+  p /= 2 * W;
+  const int oy = (int)(p % (2 * H));
+  const int64_t f = p / (2 * H);
+  dst[i] = src[((f * H + (oy >> 1)) * W + (ox >> 1)) * C4 + c];
+}
+hipError_t launch_up2_rows(hipStream_t s, const float* src, float* dst, int frames, int H, int W, int C) {
+  if (C % 4) return hipErrorInvalidValue;
+  const int64_t total = (int64_t)frames * 4 * H * W * (C / 4);
+  if (total <= 0) return hipSuccess;
+  up2_rows_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const f32x4*)src, (f32x4*)dst, H, W, C / 4, total);
+  return hipGetLastError();
+}
+
+__global__ void fill_f32_kernel(float* __restrict__ dst, int64_t n, float v) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = v;
+}
+hipError_t launch_fill_f32(hipStream_t s, float* dst, int64_t n, float v) {
+  if (n <= 0) return hipSuccess;
+  fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(dst, n, v);
+  return hipGetLastError();
+}
+
 }  // namespace lc

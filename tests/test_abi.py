@@ -120,3 +120,26 @@ def test_token_chunk_bounds_the_temporal_pass():
     assert a > 0 and b > 0
     # 50 frames x 2304 positions = 115200 rows > 5 x 9216 = 46080 rows: the token chunk dominates
     assert a > b
+
+
+def test_decoder_config_checks_and_footprint_without_a_gpu():
+    cfg = synth.DECODERS["animatediff"]
+    c = lcb.make_decoder_config(cfg)
+    lcb.lc_decoder_check_config(c)
+    assert ctypes.sizeof(lcb.lc_decoder_config) == 4 * (6 + 4 + 4) + 4
+    one = lcb.lc_decoder_workspace_bytes(c, 1)
+    assert 0 < one < lcb.lc_decoder_workspace_bytes(c, 2) < lcb.lc_decoder_workspace_bytes(c, 0)
+    assert lcb.lc_decoder_workspace_bytes(c, -1) == 0
+    for field, value in [("levels", 4), ("groups", 7), ("heads", 3), ("head_dim", 24), ("C_lat", 17), ("N", 0), ("gn_eps", 0.0)]:
+        bad = lcb.make_decoder_config(cfg)
+        setattr(bad, field, value)
+        with pytest.raises(lcb.LcError) as e:
+            lcb.lc_decoder_check_config(bad)
+        assert e.value.status == lcb.LC_ERR_SHAPE, field
+        assert lcb.lc_decoder_workspace_bytes(bad, 1) == 0
+    bad = lcb.make_decoder_config(cfg)
+    bad.widths[1] = 100
+    with pytest.raises(lcb.LcError):
+        lcb.lc_decoder_check_config(bad)
+    for name in synth.DECODERS:
+        lcb.lc_decoder_check_config(lcb.make_decoder_config(synth.DECODERS[name]))
