@@ -491,6 +491,7 @@ def main():
         out["svdxt"] = workload_record(lcb, torch, synth, "svdxt", w, args.lanes)
         out["tiny"] = tiny_record(lcb, torch, synth, args.lanes)
         out["stress"] = stress_record(lcb, torch, synth, w, args.lanes, stats.weight_bytes)
+        out["sliced_decode"] = decode_record(lcb, torch, synth)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w)
     print(json.dumps(out))
@@ -596,6 +597,36 @@ def stress_record(lcb, torch, synth, w, lanes, wbytes):
                    "64 GB bound; it would only bite an implementation that materialises the fp32 scores "
                    "(2.7 GB per frame)")
     return rec
+
+
+def decode_record(lcb, torch, synth, reps=3):
+    """Sliced decoding of the AnimateDiff-sized latent video (16 frames of 64 x 64 -> 512 x 512): frame by frame, four
+    frames at a time and all at once; time per video and the workspace each needs (it is sized by the slice)."""
+    cfg = synth.DECODERS["animatediff"]
+    w = synth.make_decoder_weights(cfg, 0)
+    dec = lcb.Decoder(cfg, w, max_slice=cfg.N)
+    try:
+        z = dec.to_device(synth.make_decoder_latents(cfg, 1))
+        rec = {"workload": f"decoder stand-in, N={cfg.N} frames, latent {cfg.C_lat}x{cfg.H}x{cfg.W} -> {cfg.C_img}x"
+                           f"{cfg.H * 2 ** cfg.levels}x{cfg.W * 2 ** cfg.levels}, widths {list(cfg.widths)}, {cfg.dtype}",
+               "gflop_per_video": round(cfg.decode_flops() / 1e9, 1), "slices": []}
+        for sl in (1, 4, cfg.N):
+            dec.decode(z, sl)
+            dec.sync()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            ev[0].record(dec.stream)
+            for i in range(reps):
+                dec.decode(z, sl)
+                ev[i + 1].record(dec.stream)
+            dec.sync()
+            ms = statistics.median(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+            rec["slices"].append({"slice_frames": sl, "ms_per_video": round(ms, 3),
+                                  "tflops": round(cfg.decode_flops() / (ms * 1e-3) / 1e12, 1),
+                                  "workspace_gb": round(lcb.lc_decoder_workspace_bytes(dec.ccfg, sl) / 1e9, 4)})
+        return rec
+    finally:
+        dec.close()
+        torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":
