@@ -258,3 +258,84 @@ def make_decoder_latents(cfg: DecoderConfig, seed: int = 1) -> np.ndarray:
     rng = np.random.default_rng(seed)
     a = rng.standard_normal((cfg.N, cfg.C_lat, cfg.H, cfg.W), dtype=np.float32)
     return round_to_bf16(a) if cfg.dtype == "bf16" else a
+
+
+# --------------------------------------------------------------------------------------
+# Diffusion-transformer variant: a stack of adaLN-modulated blocks with a cached block range
+# --------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class DitConfig:
+    """B batch elements (2 with classifier-free guidance) of T tokens (all patches of all latent frames: the
+    attention is over the whole video) and width D; L blocks of which [cache_a, cache_b) are the cached deep part."""
+
+    name: str
+    B: int
+    T: int
+    D: int
+    heads: int
+    head_dim: int
+    L: int
+    cache_a: int
+    cache_b: int
+    dtype: str
+    mlp_ratio: int = 4
+    token_chunk: int = 0
+    ln_eps: float = 1e-6
+
+    def with_(self, **kw) -> "DitConfig":
+        return replace(self, **kw)
+
+    def block_flops(self) -> float:
+        """Algorithmic FLOPs of one block over all B * T tokens."""
+        P = self.B * self.T
+        return 8.0 * self.D * self.D * P + 4.0 * self.T * self.T * self.D * self.B + 4.0 * self.mlp_ratio * self.D * self.D * P
+
+    def cached_step_flops(self) -> float:
+        return (self.L - (self.cache_b - self.cache_a)) * self.block_flops()
+
+    def full_step_flops(self) -> float:
+        return self.L * self.block_flops()
+
+
+DITS: Dict[str, DitConfig] = {
+    "tiny": DitConfig("tiny", B=1, T=256, D=128, heads=2, head_dim=64, L=4, cache_a=1, cache_b=3, dtype="f32", token_chunk=64),
+    # a video DiT in the size class of the paper's DiT rows: 4 latent frames of 32 x 32 patches attended jointly
+    "video_dit": DitConfig("video_dit", B=2, T=4096, D=1024, heads=16, head_dim=64, L=12, cache_a=2, cache_b=10,
+                           dtype="bf16", token_chunk=1024),
+}
+
+
+def dit_weight_manifest(cfg: DitConfig) -> List[Tuple[str, Tuple[int, ...], str]]:
+    D, H = cfg.D, cfg.mlp_ratio * cfg.D
+    m: List[Tuple[str, Tuple[int, ...], str]] = []
+    for i in range(cfg.L):
+        m += [(f"blk{i}.wqkv", (3 * D, D), "w"), (f"blk{i}.bqkv", (3 * D,), "w"), (f"blk{i}.wo", (D, D), "w"),
+              (f"blk{i}.bo", (D,), "w"), (f"blk{i}.w1", (H, D), "w"), (f"blk{i}.b1", (H,), "w"),
+              (f"blk{i}.w2", (D, H), "w"), (f"blk{i}.b2", (D,), "w")]
+    return m
+
+
+def make_dit_weights(cfg: DitConfig, seed: int = 0, sharp: float = 1.0) -> Dict[str, np.ndarray]:
+    """All weights and biases ~N(0, 0.02); `sharp` multiplies the q and k rows of wqkv (peaked softmax)."""
+    rng = np.random.default_rng(seed)
+    out: Dict[str, np.ndarray] = {}
+    for name, shape, _ in dit_weight_manifest(cfg):
+        a = rng.standard_normal(shape, dtype=np.float32) * np.float32(0.02)
+        if sharp != 1.0 and name.endswith(".wqkv"):
+            a[:2 * cfg.D] *= np.float32(sharp)
+        out[name] = round_to_bf16(a) if cfg.dtype == "bf16" else a
+    return out
+
+
+def make_dit_hidden(cfg: DitConfig, seed: int = 1) -> np.ndarray:
+    """Hidden states entering the block stack, [B, T, D] float32, ~N(0,1)."""
+    return np.random.default_rng(seed).standard_normal((cfg.B, cfg.T, cfg.D), dtype=np.float32)
+
+
+def make_dit_modulation(cfg: DitConfig, seed: int = 2) -> np.ndarray:
+    """The adaLN vectors of every block, [L, B, 6, D] float32 in the order shift_msa, scale_msa, gate_msa,
+    shift_mlp, scale_mlp, gate_mlp: shifts and scales ~N(0, 0.1), gates 1 + N(0, 0.1)."""
+    a = np.random.default_rng(seed).standard_normal((cfg.L, cfg.B, 6, cfg.D), dtype=np.float32) * np.float32(0.1)
+    a[:, :, 2] += np.float32(1.0)
+    a[:, :, 5] += np.float32(1.0)
+    return a

@@ -167,3 +167,37 @@ def decoder(cfg, w, z):
         h = conv3x3(group_norm_silu(h, w["out.gn_g"], w["out.gn_b"], G, cfg.gn_eps), w["out.w"], w["out.b"])
         out.append(h[0])
     return out
+
+
+def dit_blocks(cfg, w, mod, x, i0, i1):
+    """Blocks [i0, i1) of the diffusion transformer on nested lists x [T][D] of ONE batch element with that element's
+    modulation mod[i] = six lists of D floats; scalar loops throughout. Returns the new x."""
+    T, D, H = len(x), cfg.D, cfg.mlp_ratio * cfg.D
+
+    def ln_mod(row, shift, scale):
+        mu = sum(row) / D
+        var = sum((v - mu) ** 2 for v in row) / D
+        r = 1.0 / math.sqrt(var + cfg.ln_eps)
+        return [(row[c] - mu) * r * (1.0 + scale[c]) + shift[c] for c in range(D)]
+
+    def lin(row, W, b):
+        return [b[o] + sum(W[o][c] * row[c] for c in range(len(row))) for o in range(len(W))]
+
+    x = [list(r) for r in x]
+    for i in range(i0, i1):
+        m = mod[i]
+        h = [ln_mod(r, m[0], m[1]) for r in x]
+        qkv = [lin(r, w[f"blk{i}.wqkv"], w[f"blk{i}.bqkv"]) for r in h]
+        O = attn_core([r[:D] for r in qkv], [r[D:2 * D] for r in qkv], [r[2 * D:] for r in qkv], cfg.heads)
+        for t in range(T):
+            y = lin(O[t], w[f"blk{i}.wo"], w[f"blk{i}.bo"])
+            for c in range(D):
+                x[t][c] += m[2][c] * y[c]
+        for t in range(T):
+            hrow = ln_mod(x[t], m[3], m[4])
+            u = lin(hrow, w[f"blk{i}.w1"], w[f"blk{i}.b1"])
+            u = [0.5 * v * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (v + 0.044715 * v ** 3))) for v in u]
+            y = lin(u, w[f"blk{i}.w2"], w[f"blk{i}.b2"])
+            for c in range(D):
+                x[t][c] += m[5][c] * y[c]
+    return x
