@@ -365,6 +365,59 @@ lc_status lc_decoder_set_workspace(lc_decoder* dec, void* arena, size_t bytes);
 lc_status lc_decode(lc_decoder* dec, const void* z, void* img, int slice_frames);
 lc_status lc_decoder_sync(lc_decoder* dec);
 
+/* ---- diffusion-transformer variant --------------------------------------------------------------------------
+ * The reuse rule of [AS] applied to a stack of L adaLN-modulated transformer blocks over the B x T tokens of a
+ * video (T = all patches of all latent frames: full 3-D attention per batch element). Blocks [cache_a, cache_b)
+ * are the cached deep part: what they add to the hidden states, Delta = x_b - x_a, is accumulated in a device slot
+ * at a normal step (lc_dit_full_step), swapped to pinned host memory and back like the U-Net's deep feature, and
+ * added back at a cache step (lc_dit_cached_step), which runs only blocks [0, cache_a) and [cache_b, L). In both
+ * kinds of step the deep part enters as x_a + Delta, so a cache step on the Delta of the same input reproduces the
+ * normal step bit for bit. The paper does not say which blocks of a DiT are cached; this split is a reading.
+ * One block: h = LN(x) (1 + scale_msa) + shift_msa; x += gate_msa * (Attn(h) Wo^T + bo); h = LN(x) (1 + scale_mlp)
+ * + shift_mlp; x += gate_mlp * (W2 gelu_tanh(W1 h + b1) + b2). LN: per token, biased variance, no affine; q,k,v
+ * projections with bias; `heads` heads of `head_dim`, scale 1/sqrt(head_dim). The modulation vectors are inputs.
+ * Feature chunk ([CHK]): token_chunk tokens per pass of LayerNorm / projections / MLP and queries per pass of the
+ * attention (against all keys); it never changes results. Hidden states and modulation are float at the boundary;
+ * weights have cfg dtype (bf16: MFMA operands bf16, accumulation and the residual stream fp32).
+ * Requirements (else LC_ERR_SHAPE): sizes > 0; D a multiple of 64, <= 2048; heads * head_dim == D; head_dim in
+ * {8, 16, 32, 40, 64}; L <= LC_DIT_MAX_BLOCKS; 0 <= cache_a <= cache_b <= L; mlp_ratio <= 8; 1 <= dev_slots <= 8;
+ * 0 <= host_slots <= 64. Conventions (streams, errors, lifetimes) as for the U-Net stage. */
+#define LC_DIT_MAX_BLOCKS 64
+typedef struct lc_dit lc_dit; /* opaque; owned by the library */
+typedef struct lc_dit_config {
+  int32_t B, T, D, heads, head_dim;
+  int32_t L, cache_a, cache_b, mlp_ratio;
+  int32_t dtype;  /* lc_dtype of the weights and of the MFMA operands */
+  float ln_eps;
+  int32_t host_slots, dev_slots;
+} lc_dit_config;
+/* [device], cfg dtype, PyTorch layouts: wqkv [3D, D] (q, k, v rows stacked), wo [D, D], w1 [mlp_ratio*D, D],
+ * w2 [D, mlp_ratio*D], biases [out]. Private copies are made by lc_dit_load_weights. */
+typedef struct lc_dit_block_w { const void *wqkv, *bqkv, *wo, *bo, *w1, *b1, *w2, *b2; } lc_dit_block_w;
+typedef struct lc_dit_weights { lc_dit_block_w blk[LC_DIT_MAX_BLOCKS]; } lc_dit_weights;
+
+lc_status lc_dit_check_config(const lc_dit_config* cfg);                 /* host only */
+size_t lc_dit_entry_bytes(const lc_dit_config* cfg);                     /* one Delta entry: B*T*D floats; host only */
+size_t lc_dit_workspace_bytes(const lc_dit_config* cfg, int token_chunk); /* footprint model; host only */
+const char* lc_dit_last_error(const lc_dit* ctx);
+lc_status lc_dit_create(const lc_dit_config* cfg, void* compute_stream, void* side_stream, lc_dit** out);
+lc_status lc_dit_destroy(lc_dit* ctx);
+lc_status lc_dit_load_weights(lc_dit* ctx, const lc_dit_weights* w /* [host] struct of [device] ptrs */);
+lc_status lc_dit_set_workspace(lc_dit* ctx, void* arena /* [device], 256-byte aligned */, size_t bytes);
+lc_status lc_dit_set_chunk(lc_dit* ctx, int token_chunk); /* 0 = unchunked; values above T clamp */
+/* x_in, x_out [device, B, T, D] float; mod [device, L, B, 6, D] float in the order shift_msa, scale_msa, gate_msa,
+ * shift_mlp, scale_mlp, gate_mlp. Normal step: all L blocks, Delta left in device slot dev_slot. Cache step: Delta
+ * read from dev_slot (LC_ERR_STATE if empty; waits on the GPU for a swap-in in flight). */
+lc_status lc_dit_full_step(lc_dit* ctx, const void* x_in, const void* mod, void* x_out, int dev_slot);
+lc_status lc_dit_cached_step(lc_dit* ctx, const void* x_in, const void* mod, void* x_out, int dev_slot);
+lc_status lc_dit_swap_out(lc_dit* ctx, int dev_slot, int host_slot); /* async D2H on the side stream */
+lc_status lc_dit_swap_in(lc_dit* ctx, int host_slot, int dev_slot);  /* async H2D on the side stream */
+lc_status lc_dit_sync(lc_dit* ctx);
+lc_status lc_dit_cache_write(lc_dit* ctx, int dev_slot, const void* delta /* [device, B, T, D] float */);
+lc_status lc_dit_cache_peek(lc_dit* ctx, int host_slot, const void** ptr /* [host] */, size_t* bytes);
+lc_status lc_dit_cache_dev_peek(lc_dit* ctx, int dev_slot, const void** ptr /* [device] */, size_t* bytes);
+lc_status lc_dit_get_counts(lc_dit* ctx, int64_t* full_steps, int64_t* cached_steps, int64_t* swaps_out, int64_t* swaps_in);
+
 #ifdef __cplusplus
 }
 #endif

@@ -81,6 +81,22 @@ class lc_decoder_weights(C.Structure):
                 ("up_conv_b", C.c_void_p * LC_DEC_MAX_LEVELS), ("out", lc_gnconv_w)]
 
 
+LC_DIT_MAX_BLOCKS = 64
+
+
+class lc_dit_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "T", "D", "heads", "head_dim", "L", "cache_a", "cache_b", "mlp_ratio", "dtype")] + \
+               [("ln_eps", C.c_float), ("host_slots", C.c_int32), ("dev_slots", C.c_int32)]
+
+
+class lc_dit_block_w(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wqkv", "bqkv", "wo", "bo", "w1", "b1", "w2", "b2")]
+
+
+class lc_dit_weights(C.Structure):
+    _fields_ = [("blk", lc_dit_block_w * LC_DIT_MAX_BLOCKS)]
+
+
 # name -> (restype, argtypes). Every symbol include/lightcache.h declares is listed here.
 _P, _I, _I64 = C.c_void_p, C.c_int, C.c_int64
 PROTOTYPES = {
@@ -124,6 +140,24 @@ PROTOTYPES = {
     "lc_decoder_set_workspace": (_I, [_P, _P, C.c_size_t]),
     "lc_decode": (_I, [_P, _P, _P, _I]),
     "lc_decoder_sync": (_I, [_P]),
+    "lc_dit_check_config": (_I, [C.POINTER(lc_dit_config)]),
+    "lc_dit_entry_bytes": (C.c_size_t, [C.POINTER(lc_dit_config)]),
+    "lc_dit_workspace_bytes": (C.c_size_t, [C.POINTER(lc_dit_config), _I]),
+    "lc_dit_last_error": (C.c_char_p, [_P]),
+    "lc_dit_create": (_I, [C.POINTER(lc_dit_config), _P, _P, C.POINTER(_P)]),
+    "lc_dit_destroy": (_I, [_P]),
+    "lc_dit_load_weights": (_I, [_P, C.POINTER(lc_dit_weights)]),
+    "lc_dit_set_workspace": (_I, [_P, _P, C.c_size_t]),
+    "lc_dit_set_chunk": (_I, [_P, _I]),
+    "lc_dit_full_step": (_I, [_P, _P, _P, _P, _I]),
+    "lc_dit_cached_step": (_I, [_P, _P, _P, _P, _I]),
+    "lc_dit_swap_out": (_I, [_P, _I, _I]),
+    "lc_dit_swap_in": (_I, [_P, _I, _I]),
+    "lc_dit_sync": (_I, [_P]),
+    "lc_dit_cache_write": (_I, [_P, _I, _P]),
+    "lc_dit_cache_peek": (_I, [_P, _I, C.POINTER(_P), C.POINTER(C.c_size_t)]),
+    "lc_dit_cache_dev_peek": (_I, [_P, _I, C.POINTER(_P), C.POINTER(C.c_size_t)]),
+    "lc_dit_get_counts": (_I, [_P] + [C.POINTER(C.c_int64)] * 4),
     "lc_op_conv_in": (_I, [_P, _P, _P, _I]),
     "lc_op_res_block": (_I, [_P, _I, _P, _P, _I]),
     "lc_op_qkv": (_I, [_P, _I, _P, _P, _I]),
@@ -457,6 +491,193 @@ class Decoder:
         if self.dec is not None:
             lc_decoder_destroy(self.dec)
             self.dec = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---- diffusion-transformer variant -----------------------------------------------------------------
+def _tcheck(status: int, ctx) -> None:
+    if status != LC_OK:
+        msg = lib().lc_dit_last_error(ctx)
+        raise LcError(status, msg.decode() if msg else "")
+
+
+def make_dit_config(cfg, host_slots: int = 1, dev_slots: int = 2) -> lc_dit_config:
+    """cfg: any object with the synth.DitConfig attributes."""
+    return lc_dit_config(B=cfg.B, T=cfg.T, D=cfg.D, heads=cfg.heads, head_dim=cfg.head_dim, L=cfg.L, cache_a=cfg.cache_a,
+                         cache_b=cfg.cache_b, mlp_ratio=cfg.mlp_ratio, dtype=LC_BF16 if cfg.dtype == "bf16" else LC_F32,
+                         ln_eps=cfg.ln_eps, host_slots=host_slots, dev_slots=dev_slots)
+
+
+def lc_dit_check_config(cfg: lc_dit_config) -> None:
+    _tcheck(lib().lc_dit_check_config(C.byref(cfg)), None)
+
+
+def lc_dit_entry_bytes(cfg: lc_dit_config) -> int:
+    return lib().lc_dit_entry_bytes(C.byref(cfg))
+
+
+def lc_dit_workspace_bytes(cfg: lc_dit_config, token_chunk: int) -> int:
+    return lib().lc_dit_workspace_bytes(C.byref(cfg), token_chunk)
+
+
+def lc_dit_last_error(ctx=None) -> str:
+    return lib().lc_dit_last_error(ctx).decode()
+
+
+def lc_dit_create(cfg: lc_dit_config, compute_stream: int, side_stream: int):
+    out = C.c_void_p()
+    _tcheck(lib().lc_dit_create(C.byref(cfg), compute_stream, side_stream, C.byref(out)), None)
+    return out
+
+
+def lc_dit_destroy(ctx) -> None:
+    _tcheck(lib().lc_dit_destroy(ctx), None)
+
+
+def lc_dit_load_weights(ctx, w: lc_dit_weights) -> None:
+    _tcheck(lib().lc_dit_load_weights(ctx, C.byref(w)), ctx)
+
+
+def lc_dit_set_workspace(ctx, arena_ptr: int, nbytes: int) -> None:
+    _tcheck(lib().lc_dit_set_workspace(ctx, arena_ptr, nbytes), ctx)
+
+
+def lc_dit_set_chunk(ctx, token_chunk: int) -> None:
+    _tcheck(lib().lc_dit_set_chunk(ctx, token_chunk), ctx)
+
+
+def lc_dit_full_step(ctx, x_in_ptr: int, mod_ptr: int, x_out_ptr: int, dev_slot: int) -> None:
+    _tcheck(lib().lc_dit_full_step(ctx, x_in_ptr, mod_ptr, x_out_ptr, dev_slot), ctx)
+
+
+def lc_dit_cached_step(ctx, x_in_ptr: int, mod_ptr: int, x_out_ptr: int, dev_slot: int) -> None:
+    _tcheck(lib().lc_dit_cached_step(ctx, x_in_ptr, mod_ptr, x_out_ptr, dev_slot), ctx)
+
+
+def lc_dit_swap_out(ctx, dev_slot: int, host_slot: int) -> None:
+    _tcheck(lib().lc_dit_swap_out(ctx, dev_slot, host_slot), ctx)
+
+
+def lc_dit_swap_in(ctx, host_slot: int, dev_slot: int) -> None:
+    _tcheck(lib().lc_dit_swap_in(ctx, host_slot, dev_slot), ctx)
+
+
+def lc_dit_sync(ctx) -> None:
+    _tcheck(lib().lc_dit_sync(ctx), ctx)
+
+
+def lc_dit_cache_write(ctx, dev_slot: int, delta_ptr: int) -> None:
+    _tcheck(lib().lc_dit_cache_write(ctx, dev_slot, delta_ptr), ctx)
+
+
+def lc_dit_cache_peek(ctx, host_slot: int):
+    p, n = C.c_void_p(), C.c_size_t()
+    _tcheck(lib().lc_dit_cache_peek(ctx, host_slot, C.byref(p), C.byref(n)), ctx)
+    return p.value, n.value
+
+
+def lc_dit_cache_dev_peek(ctx, dev_slot: int):
+    p, n = C.c_void_p(), C.c_size_t()
+    _tcheck(lib().lc_dit_cache_dev_peek(ctx, dev_slot, C.byref(p), C.byref(n)), ctx)
+    return p.value, n.value
+
+
+def lc_dit_get_counts(ctx):
+    v = [C.c_int64() for _ in range(4)]
+    _tcheck(lib().lc_dit_get_counts(ctx, *[C.byref(x) for x in v]), ctx)
+    return tuple(x.value for x in v)
+
+
+class Dit:
+    """The block stack of the diffusion-transformer variant on the current GPU; torch owns memory and streams.
+    `weights`: name -> numpy float32 array, names as in synth.dit_weight_manifest."""
+
+    def __init__(self, cfg, weights, host_slots: int = 1, dev_slots: int = 2, token_chunk: Optional[int] = None,
+                 device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
+        self.torch, self.cfg = torch, cfg
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self.ccfg = make_dit_config(cfg, host_slots, dev_slots)
+        lc_dit_check_config(self.ccfg)
+        self.compute = torch.cuda.Stream(device=self.device)
+        self.side = torch.cuda.Stream(device=self.device)
+        self.ctx = lc_dit_create(self.ccfg, self.compute.cuda_stream, self.side.cuda_stream)
+        with torch.cuda.stream(self.compute):
+            t = {k: torch.from_numpy(v).to(self.device).to(self.tdtype).contiguous() for k, v in weights.items()}
+        self.compute.synchronize()
+        w = lc_dit_weights()
+        for i in range(cfg.L):
+            w.blk[i] = lc_dit_block_w(*[t[f"blk{i}.{k}"].data_ptr() for k in ("wqkv", "bqkv", "wo", "bo", "w1", "b1", "w2", "b2")])
+        lc_dit_load_weights(self.ctx, w)
+        del t
+        self.arena = None
+        self._chunk = 0  # what a fresh context plans for: unchunked
+        self.set_chunk(cfg.token_chunk if token_chunk is None else token_chunk)
+
+    def to_device(self, a):
+        """numpy -> float32 device tensor (hidden states, modulation, Delta), on the compute stream."""
+        with self.torch.cuda.stream(self.compute):
+            return self.torch.from_numpy(a).to(self.device).float().contiguous()
+
+    def empty(self, *shape):
+        with self.torch.cuda.stream(self.compute):
+            return self.torch.empty(*shape, dtype=self.torch.float32, device=self.device)
+
+    def set_chunk(self, token_chunk: int) -> None:
+        need = max(lc_dit_workspace_bytes(self.ccfg, token_chunk), lc_dit_workspace_bytes(self.ccfg, self._chunk))
+        if self.arena is None or self.arena.numel() < need:
+            # an arena that covers the plan in force and the new one (a new workspace starts with empty slots)
+            lc_dit_sync(self.ctx)
+            self.arena = None
+            self.arena = self.torch.empty(need, dtype=self.torch.uint8, device=self.device)
+            self.torch.cuda.synchronize(self.device)
+            lc_dit_set_workspace(self.ctx, self.arena.data_ptr(), self.arena.numel())
+        lc_dit_set_chunk(self.ctx, token_chunk)
+        self._chunk = token_chunk
+
+    def full_step(self, x, mod, out, dev_slot: int = 0):
+        lc_dit_full_step(self.ctx, x.data_ptr(), mod.data_ptr(), out.data_ptr(), dev_slot)
+
+    def cached_step(self, x, mod, out, dev_slot: int = 0):
+        lc_dit_cached_step(self.ctx, x.data_ptr(), mod.data_ptr(), out.data_ptr(), dev_slot)
+
+    def swap_out(self, dev_slot: int, host_slot: int):
+        lc_dit_swap_out(self.ctx, dev_slot, host_slot)
+
+    def swap_in(self, host_slot: int, dev_slot: int):
+        lc_dit_swap_in(self.ctx, host_slot, dev_slot)
+
+    def cache_write(self, dev_slot: int, delta):
+        lc_dit_cache_write(self.ctx, dev_slot, delta.data_ptr())
+
+    def sync(self):
+        lc_dit_sync(self.ctx)
+
+    def host_entry_bytes(self, host_slot: int) -> bytes:
+        ptr, n = lc_dit_cache_peek(self.ctx, host_slot)
+        return C.string_at(ptr, n)
+
+    def dev_entry(self, dev_slot: int):
+        """The Delta in a device slot as a float32 tensor [B, T, D] (a copy)."""
+        ptr, n = lc_dit_cache_dev_peek(self.ctx, dev_slot)
+        self.sync()
+        off = ptr - self.arena.data_ptr()
+        c = self.cfg
+        return self.arena[off:off + n].view(self.torch.float32).reshape(c.B, c.T, c.D).clone()
+
+    def close(self):
+        if self.ctx is not None:
+            lc_dit_destroy(self.ctx)
+            self.ctx = None
 
     def __del__(self):
         try:

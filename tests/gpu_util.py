@@ -15,6 +15,9 @@ from paper_2510_05367_amd import synth
 #   extremes 7-8.2), so the same relative precision is an absolute error twice as large, and storing even the
 #   exact value in bf16 (8 significant bits) moves it by up to half an ulp <= 2^-8 |v| (0.031 at |v| = 8). The
 #   bound there is, element by element, 2e-2 * max(1, max|ref| / 4) + 2^-8 |ref|. rel-L2 <= 1e-2 holds unchanged.
+#   `wide_range=True`: the hidden states of the diffusion-transformer variant, which are not eps-like: inputs ~N(0,1)
+#   over millions of elements reach |x| = 5-6 and every block adds to them. The same relative precision as 2e-2 on
+#   a tensor within |.| < 4 is 2e-2 * max(1, max|ref| / 4) there (fp32 tensors: no storage term).
 TOL = {"f32": dict(rel=1e-4, abs=None), "bf16": dict(rel=1e-2, abs=2e-2)}
 BF16_HALF_ULP = 2.0 ** -8
 EPS_RANGE = 4.0  # |eps| stays below this in every workload
@@ -26,7 +29,7 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def check(name, got, ref, dtype, cache_entry=False):
+def check(name, got, ref, dtype, cache_entry=False, wide_range=False):
     """got: torch tensor or array; ref: float64 array of the same shape."""
     g = got.float().cpu().numpy() if isinstance(got, torch.Tensor) else np.asarray(got)
     assert g.shape == ref.shape, (name, g.shape, ref.shape)
@@ -39,8 +42,10 @@ def check(name, got, ref, dtype, cache_entry=False):
     assert r <= tol["rel"], msg
     if tol["abs"] is not None:
         bound = tol["abs"]
+        if cache_entry or wide_range:
+            bound = bound * max(1.0, float(np.max(np.abs(ref))) / EPS_RANGE)
         if cache_entry:
-            bound = bound * max(1.0, float(np.max(np.abs(ref))) / EPS_RANGE) + BF16_HALF_ULP * np.abs(ref)
+            bound = bound + BF16_HALF_ULP * np.abs(ref)
         assert np.all(np.abs(g.astype(np.float64) - ref) <= bound), msg
     return r, m
 
