@@ -492,6 +492,7 @@ def main():
         out["tiny"] = tiny_record(lcb, torch, synth, args.lanes)
         out["stress"] = stress_record(lcb, torch, synth, w, args.lanes, stats.weight_bytes)
         out["sliced_decode"] = decode_record(lcb, torch, synth)
+        out["video_dit"] = dit_record(lcb, torch, synth)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w)
     print(json.dumps(out))
@@ -626,6 +627,76 @@ def decode_record(lcb, torch, synth, reps=3):
         return rec
     finally:
         dec.close()
+        torch.cuda.empty_cache()
+
+
+def dit_record(lcb, torch, synth, steps=6):
+    """The diffusion-transformer variant: normal and cache step of a 12-block video DiT (blocks [2, 10) cached), and
+    a schedule with a normal step every `interval` steps, Delta swapped out and prefetched one step ahead."""
+    cfg = synth.DITS["video_dit"]
+    w = synth.make_dit_weights(cfg, 0)
+    dit = lcb.Dit(cfg, w, host_slots=2, dev_slots=2)
+    try:
+        x = dit.to_device(synth.make_dit_hidden(cfg, 1))
+        mod = dit.to_device(synth.make_dit_modulation(cfg, 2))
+        out = dit.empty(cfg.B, cfg.T, cfg.D)
+
+        def timed(fn, n):
+            fn()
+            dit.sync()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            ev[0].record(dit.compute)
+            for i in range(n):
+                fn()
+                ev[i + 1].record(dit.compute)
+            dit.sync()
+            return statistics.median(ev[i].elapsed_time(ev[i + 1]) for i in range(n))
+        ms_full = timed(lambda: dit.full_step(x, mod, out, 0), steps)
+        ms_cached = timed(lambda: dit.cached_step(x, mod, out, 0), steps)
+        rec = {"workload": f"video DiT stand-in: B={cfg.B}, T={cfg.T} tokens, D={cfg.D}, {cfg.heads} heads x {cfg.head_dim}, "
+                           f"L={cfg.L} blocks of which [{cfg.cache_a}, {cfg.cache_b}) are cached, {cfg.dtype}, token chunk {cfg.token_chunk}",
+               "normal_step_ms": round(ms_full, 3), "cache_step_ms": round(ms_cached, 3),
+               "normal_step_tflops": round(cfg.full_step_flops() / (ms_full * 1e-3) / 1e12, 1),
+               "cache_step_tflops": round(cfg.cached_step_flops() / (ms_cached * 1e-3) / 1e12, 1),
+               "entry_mb": round(lcb.lc_dit_entry_bytes(dit.ccfg) / 1e6, 1),
+               "workspace_gb": round(lcb.lc_dit_workspace_bytes(dit.ccfg, cfg.token_chunk) / 1e9, 4),
+               "workspace_unchunked_gb": round(lcb.lc_dit_workspace_bytes(dit.ccfg, 0) / 1e9, 4), "schedules": []}
+        n_steps = 12
+
+        def schedule(interval, swapping):
+            refresh, prefetched = -1, None
+            for t in range(n_steps):
+                slot = t % 2 if swapping else 0
+                if t % interval == 0:
+                    refresh += 1
+                    dit.full_step(x, mod, out, slot)
+                    if swapping:
+                        dit.swap_out(slot, refresh % 2)
+                else:
+                    if swapping and prefetched != (t, slot):
+                        dit.swap_in(refresh % 2, slot)
+                    dit.cached_step(x, mod, out, slot)
+                if swapping and t + 1 < n_steps and (t + 1) % interval != 0:
+                    dit.swap_in(refresh % 2, (t + 1) % 2)
+                    prefetched = (t + 1, (t + 1) % 2)
+        for interval in (1, 2, 3, 4):
+            row = {"interval": interval}
+            for name, swapping in (("resident", False), ("swapped", True)):
+                if interval == 1 and swapping:
+                    continue
+                schedule(interval, swapping)
+                dit.sync()
+                t0 = time.perf_counter()
+                schedule(interval, swapping)
+                dit.sync()
+                row[f"{name}_ms_per_step"] = round((time.perf_counter() - t0) * 1e3 / n_steps, 3)
+            rec["schedules"].append(row)
+        base = rec["schedules"][0]["resident_ms_per_step"]
+        for row in rec["schedules"]:
+            row["speedup_vs_every_step_normal"] = round(base / row.get("swapped_ms_per_step", row["resident_ms_per_step"]), 3)
+        return rec
+    finally:
+        dit.close()
         torch.cuda.empty_cache()
 
 
