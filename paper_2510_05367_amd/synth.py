@@ -339,3 +339,158 @@ def make_dit_modulation(cfg: DitConfig, seed: int = 2) -> np.ndarray:
     a[:, :, 2] += np.float32(1.0)
     a[:, :, 5] += np.float32(1.0)
     return a
+
+
+# --------------------------------------------------------------------------------------
+# U-Net stage with the block internals of the video U-Nets the paper ran (time-embedding residual blocks,
+# transformer blocks with cross-attention and a GEGLU feed-forward, frame positional encoding) and a
+# three-level deep branch
+# --------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class UnetConfig:
+    """B batch elements of F frames of H x W latents; widths C (H x W), C1 (H/2 x W/2), C2 (H/4 x W/4); heads of
+    head_dim channels; ctx_len conditioning tokens of ctx_dim channels; a time embedding of temb_dim channels."""
+
+    name: str
+    B: int
+    F: int
+    H: int
+    W: int
+    C_lat: int
+    C: int
+    C1: int
+    C2: int
+    groups: int
+    head_dim: int
+    ctx_len: int
+    ctx_dim: int
+    temb_dim: int
+    dtype: str
+    ff_mult: int = 4
+    gn_eps: float = 1e-5
+    ln_eps: float = 1e-5
+
+    @property
+    def N(self) -> int:
+        return self.B * self.F
+
+    def with_(self, **kw) -> "UnetConfig":
+        return replace(self, **kw)
+
+    # ---- algorithmic FLOPs (2 per multiply-add; norms, activations and softmax not counted) ----
+    def _rb(self, cin, cout, P):
+        f = 2.0 * 9 * cin * cout * P + 2.0 * 9 * cout * cout * P
+        return f + (2.0 * cin * cout * P if cin != cout else 0.0)
+
+    def _st(self, C, P):
+        lin = 2.0 * C * C * P * (2 + 4 + 2 + 3 * self.ff_mult)      # pin, pout; q,k,v,o; cross q,o; GEGLU feed-forward
+        return lin + 4.0 * P * P * C + 4.0 * P * self.ctx_len * C
+
+    def _tt(self, C, P):
+        return 2.0 * C * C * P * (2 + 4 + 3 * self.ff_mult) + 4.0 * P * self.F * C
+
+    def shallow_flops(self) -> float:
+        P = self.H * self.W
+        per = 2.0 * 9 * self.C_lat * self.C * P * 2 + self._rb(self.C, self.C, P) + self._rb(self.C + self.C1, self.C, P)
+        per += 2 * (self._st(self.C, P) + self._tt(self.C, P))
+        return per * self.N
+
+    def deep_flops(self) -> float:
+        P, P1, P2 = self.H * self.W, self.H * self.W // 4, self.H * self.W // 16
+        C, C1, C2 = self.C, self.C1, self.C2
+        per = 2.0 * 9 * C * C * P1 + self._rb(C, C1, P1) + self._st(C1, P1) + self._tt(C1, P1)
+        per += 2.0 * 9 * C1 * C1 * P2 + self._rb(C1, C2, P2) + self._rb(C2, C2, P2) + 2.0 * 9 * C2 * C2 * P1
+        per += self._rb(C1 + C2, C1, P1) + self._st(C1, P1) + self._tt(C1, P1) + 2.0 * 9 * C1 * C1 * P
+        return per * self.N
+
+    def cached_step_flops(self) -> float:
+        return self.shallow_flops()
+
+    def full_step_flops(self) -> float:
+        return self.shallow_flops() + self.deep_flops()
+
+
+UNETS: Dict[str, UnetConfig] = {
+    "tiny": UnetConfig("tiny", B=1, F=4, H=32, W=32, C_lat=4, C=64, C1=128, C2=128, groups=32, head_dim=32, ctx_len=7,
+                       ctx_dim=64, temb_dim=64, dtype="f32"),
+    # full widths at a quarter of the positions: the parity case of the bf16 path
+    "mid": UnetConfig("mid", B=2, F=8, H=32, W=32, C_lat=4, C=320, C1=640, C2=1280, groups=32, head_dim=40, ctx_len=77,
+                      ctx_dim=768, temb_dim=1280, dtype="bf16"),
+    # 512 x 512 video, 16 frames, guidance pair: widths, text tokens and time embedding of the SD-1.5 family
+    "sd15_video": UnetConfig("sd15_video", B=2, F=16, H=64, W=64, C_lat=4, C=320, C1=640, C2=1280, groups=32, head_dim=40,
+                             ctx_len=77, ctx_dim=768, temb_dim=1280, dtype="bf16"),
+}
+
+
+def _unet_rb(p, cin, cout, td):
+    m = [(f"{p}.gn1_g", (cin,), "g"), (f"{p}.gn1_b", (cin,), "b"), (f"{p}.conv1.w", (cout, cin, 3, 3), "w"), (f"{p}.conv1.b", (cout,), "w"),
+         (f"{p}.temb.w", (cout, td), "w"), (f"{p}.temb.b", (cout,), "w"), (f"{p}.gn2_g", (cout,), "g"), (f"{p}.gn2_b", (cout,), "b"),
+         (f"{p}.conv2.w", (cout, cout, 3, 3), "w"), (f"{p}.conv2.b", (cout,), "w")]
+    if cin != cout:
+        m += [(f"{p}.short.w", (cout, cin), "w"), (f"{p}.short.b", (cout,), "w")]
+    return m
+
+
+def _unet_tf(p, C, ctx_dim, fm):
+    """A transformer block; ctx_dim == 0: no cross-attention (the temporal block)."""
+    m = [(f"{p}.gn_g", (C,), "g"), (f"{p}.gn_b", (C,), "b"), (f"{p}.pin.w", (C, C), "w"), (f"{p}.pin.b", (C,), "w"),
+         (f"{p}.ln1_g", (C,), "g"), (f"{p}.ln1_b", (C,), "b")]
+    m += [(f"{p}.attn1.{k}", (C, C), "w") for k in ("wq", "wk", "wv", "wo")] + [(f"{p}.attn1.bo", (C,), "w")]
+    if ctx_dim:
+        m += [(f"{p}.ln2_g", (C,), "g"), (f"{p}.ln2_b", (C,), "b"), (f"{p}.attn2.wq", (C, C), "w"), (f"{p}.attn2.wk", (C, ctx_dim), "w"),
+              (f"{p}.attn2.wv", (C, ctx_dim), "w"), (f"{p}.attn2.wo", (C, C), "w"), (f"{p}.attn2.bo", (C,), "w")]
+    m += [(f"{p}.ln3_g", (C,), "g"), (f"{p}.ln3_b", (C,), "b"), (f"{p}.ff1.w", (2 * fm * C, C), "w"), (f"{p}.ff1.b", (2 * fm * C,), "w"),
+          (f"{p}.ff2.w", (C, fm * C), "w"), (f"{p}.ff2.b", (C,), "w"), (f"{p}.pout.w", (C, C), "w"), (f"{p}.pout.b", (C,), "w")]
+    return m
+
+
+UNET_RB = ("d0.rb", "d1.rb", "mid.rb0", "mid.rb1", "u1.rb", "u0.rb")   # residual blocks, in the order of the C interface
+UNET_ST = ("d0.st", "d1.st", "u1.st", "u0.st")                          # spatial transformer blocks
+UNET_TT = ("d0.tt", "d1.tt", "u1.tt", "u0.tt")                          # temporal transformer blocks
+
+
+def unet_weight_manifest(cfg: UnetConfig) -> List[Tuple[str, Tuple[int, ...], str]]:
+    """(name, shape, kind) of every weight, in generation order; kind 'w' weight or bias, 'g' norm scale, 'b' norm shift."""
+    C, C1, C2, Cl, td, cd, fm = cfg.C, cfg.C1, cfg.C2, cfg.C_lat, cfg.temb_dim, cfg.ctx_dim, cfg.ff_mult
+    m: List[Tuple[str, Tuple[int, ...], str]] = [("conv_in.w", (C, Cl, 3, 3), "w"), ("conv_in.b", (C,), "w")]
+    m += _unet_rb("d0.rb", C, C, td) + _unet_tf("d0.st", C, cd, fm) + _unet_tf("d0.tt", C, 0, fm)
+    m += [("d0.down.w", (C, C, 3, 3), "w"), ("d0.down.b", (C,), "w")]
+    m += _unet_rb("d1.rb", C, C1, td) + _unet_tf("d1.st", C1, cd, fm) + _unet_tf("d1.tt", C1, 0, fm)
+    m += [("d1.down.w", (C1, C1, 3, 3), "w"), ("d1.down.b", (C1,), "w")]
+    m += _unet_rb("mid.rb0", C1, C2, td) + _unet_rb("mid.rb1", C2, C2, td)
+    m += [("u2.up.w", (C2, C2, 3, 3), "w"), ("u2.up.b", (C2,), "w")]
+    m += _unet_rb("u1.rb", C1 + C2, C1, td) + _unet_tf("u1.st", C1, cd, fm) + _unet_tf("u1.tt", C1, 0, fm)
+    m += [("u1.up.w", (C1, C1, 3, 3), "w"), ("u1.up.b", (C1,), "w")]
+    m += _unet_rb("u0.rb", C + C1, C, td) + _unet_tf("u0.st", C, cd, fm) + _unet_tf("u0.tt", C, 0, fm)
+    m += [("out.gn_g", (C,), "g"), ("out.gn_b", (C,), "b"), ("out.w", (Cl, C, 3, 3), "w"), ("out.b", (Cl,), "w")]
+    return m
+
+
+def make_unet_weights(cfg: UnetConfig, seed: int = 0, sharp: float = 1.0) -> Dict[str, np.ndarray]:
+    """Weights and biases ~N(0, 0.02), norm scales 1 + N(0, 0.02), norm shifts N(0, 0.02); `sharp` multiplies the
+    query and key projections (peaked softmax)."""
+    rng = np.random.default_rng(seed)
+    out: Dict[str, np.ndarray] = {}
+    for name, shape, kind in unet_weight_manifest(cfg):
+        a = rng.standard_normal(shape, dtype=np.float32) * np.float32(0.02)
+        if kind == "g":
+            a = a + np.float32(1.0)
+        if sharp != 1.0 and (name.endswith(".wq") or name.endswith(".wk")):
+            a = a * np.float32(sharp)
+        out[name] = round_to_bf16(a) if cfg.dtype == "bf16" else a
+    return out
+
+
+def make_unet_inputs(cfg: UnetConfig, seed: int = 1):
+    """(x [B, F, C_lat, H, W], temb [B, temb_dim], ctx [B, ctx_len, ctx_dim]), all ~N(0, 1), in the storage type's values."""
+    rng = np.random.default_rng(seed)
+    fin = (lambda a: round_to_bf16(a)) if cfg.dtype == "bf16" else (lambda a: a)
+    x = fin(rng.standard_normal((cfg.B, cfg.F, cfg.C_lat, cfg.H, cfg.W), dtype=np.float32))
+    temb = fin(rng.standard_normal((cfg.B, cfg.temb_dim), dtype=np.float32))
+    ctx = fin(rng.standard_normal((cfg.B, cfg.ctx_len, cfg.ctx_dim), dtype=np.float32))
+    return x, temb, ctx
+
+
+def make_unet_deep(cfg: UnetConfig, seed: int = 2) -> np.ndarray:
+    """A stand-in cached feature, [B*F, C1, H, W] float32, ~N(0, 1)."""
+    return np.random.default_rng(seed).standard_normal((cfg.N, cfg.C1, cfg.H, cfg.W), dtype=np.float32)

@@ -201,3 +201,114 @@ def dit_blocks(cfg, w, mod, x, i0, i1):
             for c in range(D):
                 x[t][c] += m[5][c] * y[c]
     return x
+
+
+def unet_rb(cfg, w, p, x, temb):
+    """Residual block with a time embedding on nested lists x [N][Cin][H][W], temb [B][temb_dim] (frame n belongs to
+    batch element n // (N / B)): two GroupNorm-SiLU-conv3x3 stages, the projected SiLU(temb) added per channel
+    between them, a 1x1 shortcut when the block has one."""
+    N, Cin, H, W = len(x), len(x[0]), len(x[0][0]), len(x[0][0][0])
+    Cout = len(w[p + ".conv1.b"])
+    per = N // len(temb)
+    h = conv3x3(group_norm_silu(x, w[p + ".gn1_g"], w[p + ".gn1_b"], cfg.groups, cfg.gn_eps), w[p + ".conv1.w"], w[p + ".conv1.b"])
+    for n in range(N):
+        tb = temb[n // per]
+        st = [v / (1.0 + math.exp(-v)) for v in tb]
+        for o in range(Cout):
+            add = w[p + ".temb.b"][o] + sum(w[p + ".temb.w"][o][k] * st[k] for k in range(len(st)))
+            for i in range(H):
+                for j in range(W):
+                    h[n][o][i][j] += add
+    y = conv3x3(group_norm_silu(h, w[p + ".gn2_g"], w[p + ".gn2_b"], cfg.groups, cfg.gn_eps), w[p + ".conv2.w"], w[p + ".conv2.b"])
+    for n in range(N):
+        for o in range(Cout):
+            for i in range(H):
+                for j in range(W):
+                    if (p + ".short.w") in w:
+                        sc = w[p + ".short.b"][o] + sum(w[p + ".short.w"][o][c] * x[n][c][i][j] for c in range(Cin))
+                    else:
+                        sc = x[n][o][i][j]
+                    y[n][o][i][j] += sc
+    return y
+
+
+def unet_tf_rows(cfg, w, p, Z, ctx=None, pe=None):
+    """The token part of a transformer block on ONE sequence Z (rows of C floats, already projected in): self-attention
+    on LayerNorm'ed rows (+ pe[row] when given), cross-attention against the rows `ctx` when given, GEGLU feed-forward;
+    each with its residual. Returns the new rows."""
+    C = len(Z[0])
+    heads = C // cfg.head_dim
+
+    def ln(row, q):
+        mu = sum(row) / C
+        var = sum((v - mu) ** 2 for v in row) / C
+        r = 1.0 / math.sqrt(var + cfg.ln_eps)
+        return [(row[c] - mu) * r * w[f"{p}.{q}_g"][c] + w[f"{p}.{q}_b"][c] for c in range(C)]
+
+    def lin(row, W, b=None):
+        return [(b[o] if b is not None else 0.0) + sum(W[o][c] * row[c] for c in range(len(row))) for o in range(len(W))]
+
+    def attend(Qin, KVin, a):
+        O = attn_core([lin(r, w[f"{p}.{a}.wq"]) for r in Qin], [lin(r, w[f"{p}.{a}.wk"]) for r in KVin],
+                      [lin(r, w[f"{p}.{a}.wv"]) for r in KVin], heads)
+        return [lin(r, w[f"{p}.{a}.wo"], w[f"{p}.{a}.bo"]) for r in O]
+
+    Z = [list(r) for r in Z]
+    A = [ln(r, "ln1") for r in Z]
+    if pe is not None:
+        A = [[A[t][c] + pe[t][c] for c in range(C)] for t in range(len(A))]
+    Y = attend(A, A, "attn1")
+    Z = [[Z[t][c] + Y[t][c] for c in range(C)] for t in range(len(Z))]
+    if ctx is not None:
+        Y = attend([ln(r, "ln2") for r in Z], ctx, "attn2")
+        Z = [[Z[t][c] + Y[t][c] for c in range(C)] for t in range(len(Z))]
+    for t in range(len(Z)):
+        u = lin(ln(Z[t], "ln3"), w[p + ".ff1.w"], w[p + ".ff1.b"])
+        half = len(u) // 2
+        gl = [u[k] * (0.5 * u[half + k] * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (u[half + k] + 0.044715 * u[half + k] ** 3))))
+              for k in range(half)]
+        y = lin(gl, w[p + ".ff2.w"], w[p + ".ff2.b"])
+        for c in range(C):
+            Z[t][c] += y[c]
+    return Z
+
+
+def frame_pe(F, C):
+    """pe[f][2i] = sin(f / 10000^(2i/C)), pe[f][2i+1] = cos(f / 10000^(2i/C))."""
+    return [[(math.sin if c % 2 == 0 else math.cos)(f / 10000.0 ** ((c - c % 2) / C)) for c in range(C)] for f in range(F)]
+
+
+def unet_tf(cfg, w, p, x, ctx=None, temporal=False):
+    """A transformer block on nested lists x [N][C][H][W]: GroupNorm, projection in, the token part over the positions
+    of each frame (spatial; ctx [B][L][ctx_dim]) or over the F frames of each position with the frame positional encoding
+    (temporal), projection out, residual."""
+    N, C, H, W = len(x), len(x[0]), len(x[0][0]), len(x[0][0][0])
+    g = group_norm_silu(x, w[p + ".gn_g"], w[p + ".gn_b"], cfg.groups, cfg.gn_eps, act=False)
+
+    def lin(row, W_, b):
+        return [b[o] + sum(W_[o][c] * row[c] for c in range(len(row))) for o in range(len(W_))]
+
+    y = [[[[x[n][c][i][j] for j in range(W)] for i in range(H)] for c in range(C)] for n in range(N)]
+    if not temporal:
+        per = N // len(ctx)
+        for n in range(N):
+            Z = [lin([g[n][c][i][j] for c in range(C)], w[p + ".pin.w"], w[p + ".pin.b"]) for i in range(H) for j in range(W)]
+            Z = unet_tf_rows(cfg, w, p, Z, ctx=ctx[n // per])
+            for i in range(H):
+                for j in range(W):
+                    o = lin(Z[i * W + j], w[p + ".pout.w"], w[p + ".pout.b"])
+                    for c in range(C):
+                        y[n][c][i][j] += o[c]
+    else:
+        F = N // cfg.B
+        pe = frame_pe(F, C)
+        for b in range(cfg.B):
+            for i in range(H):
+                for j in range(W):
+                    Z = [lin([g[b * F + f][c][i][j] for c in range(C)], w[p + ".pin.w"], w[p + ".pin.b"]) for f in range(F)]
+                    Z = unet_tf_rows(cfg, w, p, Z, pe=pe)
+                    for f in range(F):
+                        o = lin(Z[f], w[p + ".pout.w"], w[p + ".pout.b"])
+                        for c in range(C):
+                            y[b * F + f][c][i][j] += o[c]
+    return y
