@@ -418,6 +418,87 @@ lc_status lc_dit_cache_peek(lc_dit* ctx, int host_slot, const void** ptr /* [hos
 lc_status lc_dit_cache_dev_peek(lc_dit* ctx, int dev_slot, const void** ptr /* [device] */, size_t* bytes);
 lc_status lc_dit_get_counts(lc_dit* ctx, int64_t* full_steps, int64_t* cached_steps, int64_t* swaps_out, int64_t* swaps_in);
 
+/* ---- U-Net stage with real block internals -------------------------------------------------------------------
+ * The normal and the cache step of [FC] / [AS] on a U-Net whose blocks are those of the video U-Nets the paper ran
+ * (it takes them from its pretrained models and does not describe them; synthetic weights here) and whose deep
+ * branch has three levels, so that the refresh interval of [AS] can be swept end to end:
+ *   RB(x; temb)  h = conv1(SiLU(GN(x))) + (W_t SiLU(temb) + b_t)[channel];  y = short(x) + conv2(SiLU(GN(h)));
+ *                short = identity, or a 1x1 convolution when the channel count changes
+ *   ST(x; ctx)   z = pin(GN(x)); z += SelfAttn(LN(z)); z += CrossAttn(LN(z), ctx); z += FF(LN(z)); y = x + pout(z);
+ *                tokens = the positions of one frame; FF(h) = W2 (a * gelu_tanh(g)) + b2 with [a, g] = W1 h + b1
+ *   TT(x)        z = pin(GN(x)); z += SelfAttn(LN(z) + PE); z += FF(LN(z)); y = x + pout(z); tokens = the F frames of
+ *                one position; PE[f, 2i] = sin(f / 10000^(2i/C)), PE[f, 2i+1] = cos(f / 10000^(2i/C))
+ *   shallow down s = TT(ST(RB(conv_in(x))))                                  C  at H x W
+ *   deep         d = TT(ST(RB(Down(s))));  e = UpC(RB(RB(Down(d))));         C1 at H/2 x W/2, C2 at H/4 x W/4
+ *                d = TT(ST(RB(Concat(d, e))));  deep = UpC(d)                the cached feature: C1 at H x W
+ *   shallow up   u = TT(ST(RB(Concat(s, deep))));  eps = conv_out(SiLU(GN(u)))
+ * Down = conv3x3 stride 2, UpC = conv3x3 after nearest 2x upsampling; attention: bias-free q/k/v, heads of head_dim
+ * channels (C / head_dim and C1 / head_dim heads), scale 1/sqrt(head_dim), output projection with bias; LayerNorm with
+ * affine. A normal step (lc_unet_full_step) runs everything and leaves `deep` in a device slot; a cache step
+ * (lc_unet_cached_step) runs the shallow blocks only and reads it from the slot. Entries are fp32, channels-last
+ * [B*F, H*W, C1]; swap-out / swap-in move them to / from pinned host memory on the side stream, as for the stage
+ * above. x, temb, ctx, eps and the weights have cfg dtype (bf16: MFMA operands bf16, accumulation and residual
+ * streams fp32). No feature chunk here: the step runs over all frames at once.
+ * Requirements (else LC_ERR_SHAPE): sizes > 0; H, W multiples of 4; C, C1, C2, ctx_dim multiples of 64, <= 2048;
+ * every width and C + C1, C1 + C2 divisible by groups; C, C1 multiples of head_dim; head_dim in {8, 16, 32, 40, 64};
+ * C_lat <= 16; ff_mult <= 4; F * 3 * C1 elements of cfg dtype within 128 KiB (one position's q,k,v of all frames
+ * in LDS); 1 <= dev_slots <= 8; 0 <= host_slots <= 64. Conventions (streams, errors, lifetimes) as above. */
+typedef struct lc_unet lc_unet; /* opaque; owned by the library */
+typedef struct lc_unet_config {
+  int32_t B, F, H, W, C_lat;
+  int32_t C, C1, C2;       /* widths at H x W, H/2 x W/2, H/4 x W/4 */
+  int32_t groups, head_dim;
+  int32_t ctx_len, ctx_dim; /* conditioning tokens per batch element and their width */
+  int32_t temb_dim, ff_mult;
+  int32_t dtype;
+  float gn_eps, ln_eps;
+  int32_t host_slots, dev_slots;
+} lc_unet_config;
+/* all [device], cfg dtype, PyTorch layouts ([out, in] / [out, in, 3, 3]); short_w / short_b NULL when Cin == Cout */
+typedef struct lc_unet_rb_w {
+  const void *gn1_g, *gn1_b, *conv1_w, *conv1_b, *temb_w, *temb_b, *gn2_g, *gn2_b, *conv2_w, *conv2_b, *short_w, *short_b;
+} lc_unet_rb_w;
+typedef struct lc_unet_attn_w { const void *wq, *wk, *wv, *wo, *bo; } lc_unet_attn_w;
+/* attn2 (cross-attention: wk, wv are [C, ctx_dim]) and ln2 are NULL in a temporal block */
+typedef struct lc_unet_tf_w {
+  const void *gn_g, *gn_b, *pin_w, *pin_b, *ln1_g, *ln1_b;
+  lc_unet_attn_w attn1;
+  const void *ln2_g, *ln2_b;
+  lc_unet_attn_w attn2;
+  const void *ln3_g, *ln3_b, *ff1_w, *ff1_b, *ff2_w, *ff2_b, *pout_w, *pout_b;
+} lc_unet_tf_w;
+typedef struct lc_unet_conv_w { const void *w, *b; } lc_unet_conv_w;
+typedef struct lc_unet_weights {
+  lc_unet_conv_w conv_in;
+  lc_unet_rb_w rb[6];   /* d0 (C -> C), d1 (C -> C1), mid0 (C1 -> C2), mid1 (C2 -> C2), u1 (C1 + C2 -> C1), u0 (C + C1 -> C) */
+  lc_unet_tf_w st[4];   /* d0 (C), d1 (C1), u1 (C1), u0 (C) */
+  lc_unet_tf_w tt[4];   /* the same places */
+  lc_unet_conv_w down[2]; /* d0 (C), d1 (C1) */
+  lc_unet_conv_w up[2];   /* u2 (C2), u1 (C1) */
+  const void *out_gn_g, *out_gn_b;
+  lc_unet_conv_w out;   /* C -> C_lat */
+} lc_unet_weights;
+
+lc_status lc_unet_check_config(const lc_unet_config* cfg);   /* host only */
+size_t lc_unet_entry_bytes(const lc_unet_config* cfg);       /* one cache entry: B*F*H*W*C1 floats; host only */
+size_t lc_unet_workspace_bytes(const lc_unet_config* cfg);   /* footprint model, device slots included; host only */
+const char* lc_unet_last_error(const lc_unet* ctx);
+lc_status lc_unet_create(const lc_unet_config* cfg, void* compute_stream, void* side_stream, lc_unet** out);
+lc_status lc_unet_destroy(lc_unet* ctx);
+lc_status lc_unet_load_weights(lc_unet* ctx, const lc_unet_weights* w /* [host] struct of [device] ptrs */);
+lc_status lc_unet_set_workspace(lc_unet* ctx, void* arena /* [device], 256-byte aligned */, size_t bytes);
+/* x [device, B, F, C_lat, H, W], temb [device, B, temb_dim], ctx [device, B, ctx_len, ctx_dim] -> eps [device, B, F,
+ * C_lat, H, W], all of cfg dtype. Cache step: LC_ERR_STATE if the slot is empty; waits on the GPU for a swap-in in
+ * flight. All four tensors must stay valid until the compute stream has been synchronised. */
+lc_status lc_unet_full_step(lc_unet* ctx, const void* x, const void* temb, const void* cond, void* eps, int dev_slot);
+lc_status lc_unet_cached_step(lc_unet* ctx, const void* x, const void* temb, const void* cond, void* eps, int dev_slot);
+lc_status lc_unet_swap_out(lc_unet* ctx, int dev_slot, int host_slot); /* async D2H on the side stream */
+lc_status lc_unet_swap_in(lc_unet* ctx, int host_slot, int dev_slot);  /* async H2D on the side stream */
+lc_status lc_unet_sync(lc_unet* ctx);
+lc_status lc_unet_cache_write(lc_unet* ctx, int dev_slot, const void* deep /* [device, B*F, H*W, C1] float */);
+lc_status lc_unet_cache_peek(lc_unet* ctx, int host_slot, const void** ptr /* [host] */, size_t* bytes);
+lc_status lc_unet_cache_dev_peek(lc_unet* ctx, int dev_slot, const void** ptr /* [device] */, size_t* bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -97,6 +97,37 @@ class lc_dit_weights(C.Structure):
     _fields_ = [("blk", lc_dit_block_w * LC_DIT_MAX_BLOCKS)]
 
 
+class lc_unet_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "F", "H", "W", "C_lat", "C", "C1", "C2", "groups", "head_dim", "ctx_len", "ctx_dim",
+                                         "temb_dim", "ff_mult", "dtype")] + \
+               [("gn_eps", C.c_float), ("ln_eps", C.c_float), ("host_slots", C.c_int32), ("dev_slots", C.c_int32)]
+
+
+class lc_unet_rb_w(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("gn1_g", "gn1_b", "conv1_w", "conv1_b", "temb_w", "temb_b", "gn2_g", "gn2_b", "conv2_w",
+                                          "conv2_b", "short_w", "short_b")]
+
+
+class lc_unet_attn_w(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "bo")]
+
+
+class lc_unet_tf_w(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("gn_g", "gn_b", "pin_w", "pin_b", "ln1_g", "ln1_b")] + [("attn1", lc_unet_attn_w)] + \
+               [(n, C.c_void_p) for n in ("ln2_g", "ln2_b")] + [("attn2", lc_unet_attn_w)] + \
+               [(n, C.c_void_p) for n in ("ln3_g", "ln3_b", "ff1_w", "ff1_b", "ff2_w", "ff2_b", "pout_w", "pout_b")]
+
+
+class lc_unet_conv_w(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("b", C.c_void_p)]
+
+
+class lc_unet_weights(C.Structure):
+    _fields_ = [("conv_in", lc_unet_conv_w), ("rb", lc_unet_rb_w * 6), ("st", lc_unet_tf_w * 4), ("tt", lc_unet_tf_w * 4),
+                ("down", lc_unet_conv_w * 2), ("up", lc_unet_conv_w * 2), ("out_gn_g", C.c_void_p), ("out_gn_b", C.c_void_p),
+                ("out", lc_unet_conv_w)]
+
+
 # name -> (restype, argtypes). Every symbol include/lightcache.h declares is listed here.
 _P, _I, _I64 = C.c_void_p, C.c_int, C.c_int64
 PROTOTYPES = {
@@ -158,6 +189,22 @@ PROTOTYPES = {
     "lc_dit_cache_peek": (_I, [_P, _I, C.POINTER(_P), C.POINTER(C.c_size_t)]),
     "lc_dit_cache_dev_peek": (_I, [_P, _I, C.POINTER(_P), C.POINTER(C.c_size_t)]),
     "lc_dit_get_counts": (_I, [_P] + [C.POINTER(C.c_int64)] * 4),
+    "lc_unet_check_config": (_I, [C.POINTER(lc_unet_config)]),
+    "lc_unet_entry_bytes": (C.c_size_t, [C.POINTER(lc_unet_config)]),
+    "lc_unet_workspace_bytes": (C.c_size_t, [C.POINTER(lc_unet_config)]),
+    "lc_unet_last_error": (C.c_char_p, [_P]),
+    "lc_unet_create": (_I, [C.POINTER(lc_unet_config), _P, _P, C.POINTER(_P)]),
+    "lc_unet_destroy": (_I, [_P]),
+    "lc_unet_load_weights": (_I, [_P, C.POINTER(lc_unet_weights)]),
+    "lc_unet_set_workspace": (_I, [_P, _P, C.c_size_t]),
+    "lc_unet_full_step": (_I, [_P, _P, _P, _P, _P, _I]),
+    "lc_unet_cached_step": (_I, [_P, _P, _P, _P, _P, _I]),
+    "lc_unet_swap_out": (_I, [_P, _I, _I]),
+    "lc_unet_swap_in": (_I, [_P, _I, _I]),
+    "lc_unet_sync": (_I, [_P]),
+    "lc_unet_cache_write": (_I, [_P, _I, _P]),
+    "lc_unet_cache_peek": (_I, [_P, _I, C.POINTER(_P), C.POINTER(C.c_size_t)]),
+    "lc_unet_cache_dev_peek": (_I, [_P, _I, C.POINTER(_P), C.POINTER(C.c_size_t)]),
     "lc_op_conv_in": (_I, [_P, _P, _P, _I]),
     "lc_op_res_block": (_I, [_P, _I, _P, _P, _I]),
     "lc_op_qkv": (_I, [_P, _I, _P, _P, _I]),
@@ -677,6 +724,199 @@ class Dit:
     def close(self):
         if self.ctx is not None:
             lc_dit_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---- U-Net stage with real block internals ------------------------------------------------------------
+def _ucheck(status: int, ctx) -> None:
+    if status != LC_OK:
+        msg = lib().lc_unet_last_error(ctx)
+        raise LcError(status, msg.decode() if msg else "")
+
+
+def make_unet_config(cfg, host_slots: int = 1, dev_slots: int = 2) -> lc_unet_config:
+    """cfg: any object with the synth.UnetConfig attributes."""
+    return lc_unet_config(B=cfg.B, F=cfg.F, H=cfg.H, W=cfg.W, C_lat=cfg.C_lat, C=cfg.C, C1=cfg.C1, C2=cfg.C2, groups=cfg.groups,
+                          head_dim=cfg.head_dim, ctx_len=cfg.ctx_len, ctx_dim=cfg.ctx_dim, temb_dim=cfg.temb_dim, ff_mult=cfg.ff_mult,
+                          dtype=LC_BF16 if cfg.dtype == "bf16" else LC_F32, gn_eps=cfg.gn_eps, ln_eps=cfg.ln_eps,
+                          host_slots=host_slots, dev_slots=dev_slots)
+
+
+def lc_unet_check_config(cfg: lc_unet_config) -> None:
+    _ucheck(lib().lc_unet_check_config(C.byref(cfg)), None)
+
+
+def lc_unet_entry_bytes(cfg: lc_unet_config) -> int:
+    return lib().lc_unet_entry_bytes(C.byref(cfg))
+
+
+def lc_unet_workspace_bytes(cfg: lc_unet_config) -> int:
+    return lib().lc_unet_workspace_bytes(C.byref(cfg))
+
+
+def lc_unet_last_error(ctx=None) -> str:
+    return lib().lc_unet_last_error(ctx).decode()
+
+
+def lc_unet_create(cfg: lc_unet_config, compute_stream: int, side_stream: int):
+    out = C.c_void_p()
+    _ucheck(lib().lc_unet_create(C.byref(cfg), compute_stream, side_stream, C.byref(out)), None)
+    return out
+
+
+def lc_unet_destroy(ctx) -> None:
+    _ucheck(lib().lc_unet_destroy(ctx), None)
+
+
+def lc_unet_load_weights(ctx, w: lc_unet_weights) -> None:
+    _ucheck(lib().lc_unet_load_weights(ctx, C.byref(w)), ctx)
+
+
+def lc_unet_set_workspace(ctx, arena_ptr: int, nbytes: int) -> None:
+    _ucheck(lib().lc_unet_set_workspace(ctx, arena_ptr, nbytes), ctx)
+
+
+def lc_unet_full_step(ctx, x_ptr: int, temb_ptr: int, cond_ptr: int, eps_ptr: int, dev_slot: int) -> None:
+    _ucheck(lib().lc_unet_full_step(ctx, x_ptr, temb_ptr, cond_ptr, eps_ptr, dev_slot), ctx)
+
+
+def lc_unet_cached_step(ctx, x_ptr: int, temb_ptr: int, cond_ptr: int, eps_ptr: int, dev_slot: int) -> None:
+    _ucheck(lib().lc_unet_cached_step(ctx, x_ptr, temb_ptr, cond_ptr, eps_ptr, dev_slot), ctx)
+
+
+def lc_unet_swap_out(ctx, dev_slot: int, host_slot: int) -> None:
+    _ucheck(lib().lc_unet_swap_out(ctx, dev_slot, host_slot), ctx)
+
+
+def lc_unet_swap_in(ctx, host_slot: int, dev_slot: int) -> None:
+    _ucheck(lib().lc_unet_swap_in(ctx, host_slot, dev_slot), ctx)
+
+
+def lc_unet_sync(ctx) -> None:
+    _ucheck(lib().lc_unet_sync(ctx), ctx)
+
+
+def lc_unet_cache_write(ctx, dev_slot: int, deep_ptr: int) -> None:
+    _ucheck(lib().lc_unet_cache_write(ctx, dev_slot, deep_ptr), ctx)
+
+
+def lc_unet_cache_peek(ctx, host_slot: int):
+    p, n = C.c_void_p(), C.c_size_t()
+    _ucheck(lib().lc_unet_cache_peek(ctx, host_slot, C.byref(p), C.byref(n)), ctx)
+    return p.value, n.value
+
+
+def lc_unet_cache_dev_peek(ctx, dev_slot: int):
+    p, n = C.c_void_p(), C.c_size_t()
+    _ucheck(lib().lc_unet_cache_dev_peek(ctx, dev_slot, C.byref(p), C.byref(n)), ctx)
+    return p.value, n.value
+
+
+UNET_RB = ("d0.rb", "d1.rb", "mid.rb0", "mid.rb1", "u1.rb", "u0.rb")
+UNET_TF = ("d0", "d1", "u1", "u0")
+
+
+class Unet:
+    """The U-Net stage with real block internals on the current GPU; torch owns memory and streams.
+    `weights`: name -> numpy float32 array, names as in synth.unet_weight_manifest."""
+
+    def __init__(self, cfg, weights, host_slots: int = 1, dev_slots: int = 2, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
+        self.torch, self.cfg = torch, cfg
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self.ccfg = make_unet_config(cfg, host_slots, dev_slots)
+        lc_unet_check_config(self.ccfg)
+        self.compute = torch.cuda.Stream(device=self.device)
+        self.side = torch.cuda.Stream(device=self.device)
+        self.ctx = lc_unet_create(self.ccfg, self.compute.cuda_stream, self.side.cuda_stream)
+        with torch.cuda.stream(self.compute):
+            t = {k: torch.from_numpy(v).to(self.device).to(self.tdtype).contiguous() for k, v in weights.items()}
+        self.compute.synchronize()
+        ptr = lambda name: t[name].data_ptr() if name in t else None
+        w = lc_unet_weights()
+        w.conv_in = lc_unet_conv_w(ptr("conv_in.w"), ptr("conv_in.b"))
+        for i, p in enumerate(UNET_RB):
+            w.rb[i] = lc_unet_rb_w(*[ptr(f"{p}.{k}") for k in ("gn1_g", "gn1_b", "conv1.w", "conv1.b", "temb.w", "temb.b", "gn2_g",
+                                                             "gn2_b", "conv2.w", "conv2.b", "short.w", "short.b")])
+        for kind, arr in (("st", w.st), ("tt", w.tt)):
+            for i, lvl in enumerate(UNET_TF):
+                p = f"{lvl}.{kind}"
+                q = lc_unet_tf_w()
+                for k in ("gn_g", "gn_b", "ln1_g", "ln1_b", "ln2_g", "ln2_b", "ln3_g", "ln3_b"):
+                    setattr(q, k, ptr(f"{p}.{k}"))
+                for k in ("pin", "ff1", "ff2", "pout"):
+                    setattr(q, k + "_w", ptr(f"{p}.{k}.w"))
+                    setattr(q, k + "_b", ptr(f"{p}.{k}.b"))
+                q.attn1 = lc_unet_attn_w(*[ptr(f"{p}.attn1.{k}") for k in ("wq", "wk", "wv", "wo", "bo")])
+                q.attn2 = lc_unet_attn_w(*[ptr(f"{p}.attn2.{k}") for k in ("wq", "wk", "wv", "wo", "bo")])
+                arr[i] = q
+        w.down[0] = lc_unet_conv_w(ptr("d0.down.w"), ptr("d0.down.b"))
+        w.down[1] = lc_unet_conv_w(ptr("d1.down.w"), ptr("d1.down.b"))
+        w.up[0] = lc_unet_conv_w(ptr("u2.up.w"), ptr("u2.up.b"))
+        w.up[1] = lc_unet_conv_w(ptr("u1.up.w"), ptr("u1.up.b"))
+        w.out_gn_g, w.out_gn_b = ptr("out.gn_g"), ptr("out.gn_b")
+        w.out = lc_unet_conv_w(ptr("out.w"), ptr("out.b"))
+        lc_unet_load_weights(self.ctx, w)
+        del t
+        need = lc_unet_workspace_bytes(self.ccfg)
+        with torch.cuda.stream(self.compute):
+            self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
+        self.compute.synchronize()
+        lc_unet_set_workspace(self.ctx, self.arena.data_ptr(), self.arena.numel())
+
+    def to_device(self, a, f32: bool = False):
+        """numpy -> device tensor of the stage's dtype (f32: float32, for cache entries), on the compute stream."""
+        with self.torch.cuda.stream(self.compute):
+            return self.torch.from_numpy(a).to(self.device).to(self.torch.float32 if f32 else self.tdtype).contiguous()
+
+    def empty(self, *shape):
+        with self.torch.cuda.stream(self.compute):
+            return self.torch.empty(*shape, dtype=self.tdtype, device=self.device)
+
+    def full_step(self, x, temb, ctx, eps, dev_slot: int = 0):
+        lc_unet_full_step(self.ctx, x.data_ptr(), temb.data_ptr(), ctx.data_ptr(), eps.data_ptr(), dev_slot)
+
+    def cached_step(self, x, temb, ctx, eps, dev_slot: int = 0):
+        lc_unet_cached_step(self.ctx, x.data_ptr(), temb.data_ptr(), ctx.data_ptr(), eps.data_ptr(), dev_slot)
+
+    def swap_out(self, dev_slot: int, host_slot: int):
+        lc_unet_swap_out(self.ctx, dev_slot, host_slot)
+
+    def swap_in(self, host_slot: int, dev_slot: int):
+        lc_unet_swap_in(self.ctx, host_slot, dev_slot)
+
+    def cache_write(self, dev_slot: int, deep):
+        """deep: float32 device tensor [B*F, H*W, C1] (channels last)."""
+        lc_unet_cache_write(self.ctx, dev_slot, deep.data_ptr())
+
+    def sync(self):
+        lc_unet_sync(self.ctx)
+
+    def host_entry_bytes(self, host_slot: int) -> bytes:
+        ptr, n = lc_unet_cache_peek(self.ctx, host_slot)
+        return C.string_at(ptr, n)
+
+    def dev_entry(self, dev_slot: int):
+        """The cached feature in a device slot as a float32 tensor [B*F, H*W, C1] (a copy)."""
+        ptr, n = lc_unet_cache_dev_peek(self.ctx, dev_slot)
+        self.sync()
+        off = ptr - self.arena.data_ptr()
+        c = self.cfg
+        return self.arena[off:off + n].view(self.torch.float32).reshape(c.B * c.F, c.H * c.W, c.C1).clone()
+
+    def close(self):
+        if self.ctx is not None:
+            lc_unet_destroy(self.ctx)
             self.ctx = None
 
     def __del__(self):

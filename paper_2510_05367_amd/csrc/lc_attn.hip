@@ -29,11 +29,14 @@ template <class T> __device__ __forceinline__ int vcol_inv(int c) { return vcol<
 // (a window of rows of qw tokens out of image rows of qstride tokens; a plain range has qw >= nq).
 // PRE: the q columns already hold q * log2(e) / sqrt(d) (the q,k,v projection scales them before it
 // rounds them); `scale_log2e` is then 1.
-template <class T, int D, int NQT, bool PRE>
+// XA (cross-attention): the keys are not the queries' own rows but rows [Tk] of stride ldk at kx, one set (with its
+// V^T) per group of kv_div consecutive frames; T_tok then counts the query tokens of a frame only.
+template <class T, int D, int NQT, bool PRE, bool XA = false>
 __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restrict__ qk, int ldq,
                                                            const T* __restrict__ vt, int Tp, T* __restrict__ out,
                                                            int T_tok, int C, int q0, int nq, int qw, int qstride,
-                                                           float scale_log2e) {
+                                                           float scale_log2e, const T* __restrict__ kx = nullptr,
+                                                           int ldk = 0, int Tk = 0, int kv_div = 1) {
   typedef Mma32<T> M;
   constexpr int VEC = Vec16<T>::N;
   constexpr int DP = (D + M::K - 1) / M::K * M::K;  // contraction length of Q K^T, padded
@@ -69,7 +72,11 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
   }
   const int ld = ldq;
   const T* __restrict__ base = qk + (int64_t)frame * T_tok * ld + head * D;
-  const T* __restrict__ vbase = vt + ((int64_t)frame * C + head * D) * Tp;
+  const int kvf = XA ? frame / kv_div : frame;  // whose keys and values
+  const int TK = XA ? Tk : T_tok;               // number of keys
+  const int ldkk = XA ? ldk : ld;
+  const T* __restrict__ kb = XA ? kx + (int64_t)kvf * Tk * ldk + head * D : base + C;
+  const T* __restrict__ vbase = vt + ((int64_t)kvf * C + head * D) * Tp;
   const int qblk = qb * (4 * NQT * 32) + wid * (NQT * 32);  // first query number of this wavefront
   auto token_of = [&](int qi) { const int r = qi / qw; return q0 + r * qstride + (qi - r * qw); };
 
@@ -107,8 +114,8 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
     for (int j = 0; j < NP; ++j) {
       const int i = tid + 256 * j;
       const int key = min(i / PK, kKeys - 1), pk = i % PK;
-      const int gk = min(k0 + key, T_tok - 1);  // clamped: keys beyond the sequence are masked later
-      kreg[j] = load16(base + (int64_t)gk * ld + C + pk * VEC);
+      const int gk = min(k0 + key, TK - 1);  // clamped: keys beyond the sequence are masked later
+      kreg[j] = load16(kb + (int64_t)gk * ldkk + pk * VEC);
     }
 #pragma unroll
     for (int j = 0; j < NPV; ++j) {
@@ -123,7 +130,7 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
       const int i = tid + 256 * j;
       if (i < kKeys * PK) *reinterpret_cast<Vec16<T>*>(&k_lds[buf][(i / PK) * KROW + (i % PK) * 16]) = kreg[j];
     }
-    const bool tail = k0 + kKeys > T_tok;
+    const bool tail = k0 + kKeys > TK;
 #pragma unroll
     for (int j = 0; j < NPV; ++j) {
       const int i = tid + 256 * j;
@@ -133,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
         if (tail) {  // column c of the stage holds the token whose vcol is c; zero what lies beyond T
 #pragma unroll
           for (int e = 0; e < VEC; ++e)
-            if (k0 + vcol_inv<T>(pk * VEC + e) >= T_tok) v.set(e, 0.f);
+            if (k0 + vcol_inv<T>(pk * VEC + e) >= TK) v.set(e, 0.f);
         }
         *reinterpret_cast<Vec16<T>*>(&v_lds[buf][dim * VROW + pk * 16]) = v;
       }
@@ -173,10 +180,10 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
   stash_kv(0, 0);
   __syncthreads();
 
-  const int nstage = (T_tok + kKeys - 1) / kKeys;
+  const int nstage = (TK + kKeys - 1) / kKeys;
   for (int st_i = 0; st_i < nstage; ++st_i) {
     const int k0 = st_i * kKeys, buf = st_i & 1;
-    const bool tail = k0 + kKeys > T_tok;  // uniform: some keys of this stage lie beyond the sequence
+    const bool tail = k0 + kKeys > TK;  // uniform: some keys of this stage lie beyond the sequence
     if (st_i + 1 < nstage) fetch_kv(k0 + kKeys);
 
     // ---- S^T sub-tiles [32 keys][32 queries]
@@ -201,13 +208,13 @@ __global__ __launch_bounds__(256, 2) void spatial_attn_kernel(const T* __restric
       if (tail) {
         // (the key indices are built from a value the compiler cannot see through: left alone it hoists
         // these 64 additions out of the branch and every stage pays for them)
-        int kb = k0 + 4 * hh;
-        asm volatile("" : "+v"(kb));
+        int kbi = k0 + 4 * hh;
+        asm volatile("" : "+v"(kbi));
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            if (kb + kt * 32 + 8 * (r >> 2) + (r & 3) >= T_tok) sc[t][kt][r] = -INFINITY;
+            if (kbi + kt * 32 + 8 * (r >> 2) + (r & 3) >= TK) sc[t][kt][r] = -INFINITY;
       }
       float mx = -INFINITY;
 #pragma unroll
@@ -371,6 +378,38 @@ hipError_t launch_spatial_attention_window(hipStream_t s, int dt, const void* qk
     return q_prescaled ? spatial_dispatch<bf16_t, 2, true>(LC_ARGS(bf16_t)) : spatial_dispatch<bf16_t, 2, false>(LC_ARGS(bf16_t));
   return q_prescaled ? spatial_dispatch<float, 1, true>(LC_ARGS(float)) : spatial_dispatch<float, 1, false>(LC_ARGS(float));
 #undef LC_ARGS
+}
+
+// Cross-attention: queries q[frames*Tq] (stride ldq, head h at column h*d) against keys k[(frames/kv_div)*Tk] (stride
+// ldk) and their V^T [(frames/kv_div)][C][Tp]; out [frames*Tq][C]. Frame f uses the keys of group f / kv_div.
+template <class T>
+static hipError_t cross_dispatch(hipStream_t s, const T* q, int ldq, const T* k, int ldk, const T* vt, int Tp, T* out, int frames,
+                                 int Tq, int Tk, int kv_div, int heads, int d) {
+  constexpr int NQT = sizeof(T) == 2 ? 2 : 1;
+  const int C = heads * d;
+  const float sl = 1.4426950408889634f / sqrtf((float)d);
+  dim3 grid((Tq + 4 * NQT * 32 - 1) / (4 * NQT * 32), heads, frames);
+#define LC_GO(D) spatial_attn_kernel<T, D, NQT, false, true><<<grid, 256, 0, s>>>(q, ldq, vt, Tp, out, Tq, C, 0, Tq, Tq, 0, sl, k, ldk, Tk, kv_div)
+  switch (d) {
+    case 8: LC_GO(8); break;
+    case 16: LC_GO(16); break;
+    case 32: LC_GO(32); break;
+    case 40: LC_GO(40); break;
+    case 64: LC_GO(64); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef LC_GO
+  return hipGetLastError();
+}
+hipError_t launch_cross_attention(hipStream_t s, int dt, const void* q, int ldq, const void* k, int ldk, const void* vt, int Tp,
+                                  void* out, int frames, int Tq, int Tk, int kv_div, int heads, int d) {
+  if (frames <= 0 || Tq <= 0) return hipSuccess;
+  if (Tk <= 0 || kv_div <= 0 || frames % kv_div || Tp % kKeys != 0 || Tp < Tk) return hipErrorInvalidValue;
+  if (dt == kBF16)
+    return cross_dispatch<bf16_t>(s, (const bf16_t*)q, ldq, (const bf16_t*)k, ldk, (const bf16_t*)vt, Tp, (bf16_t*)out, frames, Tq, Tk,
+                                  kv_div, heads, d);
+  return cross_dispatch<float>(s, (const float*)q, ldq, (const float*)k, ldk, (const float*)vt, Tp, (float*)out, frames, Tq, Tk, kv_div,
+                               heads, d);
 }
 
 // V^T in the layout the spatial kernel stages: vt[frame][c][vcol(t)] = v[frame*T + t][c] (v rows of stride ldv)

@@ -678,6 +678,7 @@ static hipError_t by_kind(hipStream_t s, const FusedDesc& d) {
   }
   if (d.taps == 1) {
     if (d.src == 1 && !d.y_f32) return by_width<T, T, 1, 1>(s, d);      // qkv: GroupNorm'ed fp32 rows -> operand type
+    if (d.src == 1) return by_width<T, float, 1, 1>(s, d);               // GroupNorm'ed fp32 rows -> fp32 stream (projection in)
     if (d.src == 0 && y32) return by_width<T, float, 1, 0>(s, d);        // proj: operand rows -> fp32 stream
     if (d.src == 0) return by_width<T, T, 1, 0>(s, d);                   // operand rows -> operand rows (transformer layers)
     return hipErrorInvalidValue;

@@ -157,6 +157,11 @@ hipError_t launch_spatial_attention(hipStream_t s, int dt, const void* qk, int l
 hipError_t launch_spatial_attention_window(hipStream_t s, int dt, const void* qk, int ldq, const void* vt, int Tp, void* out,
                                            int frames, int T, int heads, int d, int q0, int nq, int qw, int qstride,
                                            int q_prescaled);
+// Cross-attention core: queries q[frames*Tq] (row stride ldq; head h at column h*d) against the keys k[(frames /
+// kv_div)*Tk] (row stride ldk) and values vt[(frames / kv_div)][C][Tp] (layout as above) that every kv_div consecutive
+// frames share; out [frames*Tq][C]. Tk need not be a multiple of anything; Tp >= Tk, a multiple of 64.
+hipError_t launch_cross_attention(hipStream_t s, int dt, const void* q, int ldq, const void* k, int ldk, const void* vt, int Tp,
+                                  void* out, int frames, int Tq, int Tk, int kv_div, int heads, int d);
 // vt from plain value rows v[frames*T][C] of stride ldv
 hipError_t launch_make_vt(hipStream_t s, int dt, const void* v, int ldv, void* vt, int frames, int T, int Tp, int C);
 // qkv [(B*F)*P][3C] frame-major -> out same rows x C; attention over the F frames.

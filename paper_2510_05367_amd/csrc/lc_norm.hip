@@ -16,7 +16,9 @@ __global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, 
                                                        int rows_per_frame, int C) {
   constexpr int VEC = Vec16<T>::N;
   __shared__ float red[2][256 * VEC];
-  const int cv = C / VEC;
+  // a workgroup covers up to 256 packets of the channel axis; wider tensors take gridDim.z of them side by side
+  const int cv0 = blockIdx.z * 256;
+  const int cv = min(C / VEC - cv0, 256);
   const int R = 256 / cv;
   const int split = blockIdx.x, frame = blockIdx.y, splits = gridDim.x;
   const int tid = threadIdx.x;
@@ -27,7 +29,7 @@ __global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, 
   const int r0 = split * kStatRows;
   const int r1 = min(r0 + kStatRows, rows_per_frame);
   if (rsub < R) {
-    const T* base = x + ((int64_t)frame * rows_per_frame) * C + cvec * VEC;
+    const T* base = x + ((int64_t)frame * rows_per_frame) * C + (cv0 + cvec) * VEC;
     for (int r = r0 + rsub; r < r1; r += R) {
       Vec16<T> v = load16(base + (int64_t)r * C);
 #pragma unroll
@@ -45,13 +47,13 @@ __global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, 
   }
   __syncthreads();
   // channel c of row-slot j sits at red[.][(j*cv)*VEC + c]
-  for (int c = tid; c < C; c += 256) {
+  for (int c = tid; c < cv * VEC; c += 256) {
     float ss = 0.f, qq = 0.f;
     for (int j = 0; j < R; ++j) {
       ss += red[0][j * cv * VEC + c];
       qq += red[1][j * cv * VEC + c];
     }
-    float* p = partial + (((int64_t)frame * splits + split) * C + c) * 2;
+    float* p = partial + (((int64_t)frame * splits + split) * C + cv0 * VEC + c) * 2;
     p[0] = ss;
     p[1] = qq;
   }
@@ -60,7 +62,9 @@ __global__ __launch_bounds__(256) void gn_stats_kernel(const T* __restrict__ x, 
 hipError_t launch_gn_stats(hipStream_t s, int dt, const void* x, float* partial, int frames,
                            int rows_per_frame, int C) {
   if (frames <= 0) return hipSuccess;
-  dim3 grid(stat_splits(rows_per_frame), frames);
+  const int vec = dt == kBF16 ? 8 : 4;
+  if (C <= 0 || C % vec) return hipErrorInvalidValue;
+  dim3 grid(stat_splits(rows_per_frame), frames, (C / vec + 255) / 256);
   if (dt == kBF16)
     gn_stats_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t*)x, partial, rows_per_frame, C);
   else

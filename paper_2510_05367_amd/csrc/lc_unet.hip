@@ -1,0 +1,798 @@
+// The normal and the cache step on a U-Net with real block internals: residual blocks with two convolutions and a
+// time-embedding add, spatial transformer blocks (LayerNorm, self-attention, cross-attention, GEGLU feed-forward),
+// temporal transformer blocks with a sinusoidal frame encoding, strided down and upsampling convolutions, and a
+// three-level deep branch whose output is the cached feature ("Feature Calculation" paragraph and "Asynchronous
+// Swapping" section: a normal step stores it, a cache step runs the shallow blocks only and concatenates it).
+// The convolutions, GroupNorm statistics, linear layers and attention cores are the kernels of the denoising stage
+// (the cross-attention is the spatial kernel reading its keys from the conditioning tokens); new here are four
+// bandwidth kernels: LayerNorm with affine (+ frame encoding), GEGLU, the time-embedding bias, channel concat.
+// Activations are fp32 channels-last rows [frame][position][channel]; matrix operands have the stage's dtype.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/lightcache.h"
+#include "lc_internal.h"
+
+using namespace lc;
+
+namespace lc {
+
+// y[r][:] = LN(x[r][:]) * gamma + beta (+ pe[(r / rows_per_frame) % F][:]), one wavefront per row; biased variance.
+// x fp32, y of type T. D % 4 == 0, D <= 64 * 4 * LNA_MAXV.
+constexpr int LNA_MAXV = 8;
+template <class T>
+__global__ __launch_bounds__(256) void ln_affine_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
+                                                        const float* __restrict__ beta, const float* __restrict__ pe,
+                                                        T* __restrict__ y, int64_t rows, int D, int rows_per_frame, int F, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nv = D / 4;
+  const f32x4* xr = reinterpret_cast<const f32x4*>(x + row * D);
+  const f32x4* pr = pe ? reinterpret_cast<const f32x4*>(pe + (int64_t)((row / rows_per_frame) % F) * D) : nullptr;
+  f32x4 v[LNA_MAXV];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < LNA_MAXV; ++j) {
+    const int p = lane + 64 * j;
+    if (p < nv) {
+      v[j] = xr[p];
+      s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
+    }
+  }
+  const float mu = wave_sum(s) / (float)D;
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < LNA_MAXV; ++j) {
+    if (lane + 64 * j < nv) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float d = v[j][e] - mu;
+        q = fmaf(d, d, q);
+      }
+    }
+  }
+  const float rstd = 1.f / sqrtf(wave_sum(q) / (float)D + eps);
+#pragma unroll
+  for (int j = 0; j < LNA_MAXV; ++j) {
+    const int p = lane + 64 * j;
+    if (p < nv) {
+      const f32x4 g = reinterpret_cast<const f32x4*>(gamma)[p], b = reinterpret_cast<const f32x4*>(beta)[p];
+      float o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = fmaf((v[j][e] - mu) * rstd, g[e], b[e]);
+      if (pr) {
+        const f32x4 a = pr[p];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] += a[e];
+      }
+      T* dst = y + row * D + p * 4;
+      if constexpr (sizeof(T) == 2) {
+        bf16x4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = static_cast<bf16_t>(o[e]);
+        *reinterpret_cast<bf16x4*>(dst) = ov;
+      } else {
+        *reinterpret_cast<f32x4*>(dst) = f32x4{o[0], o[1], o[2], o[3]};
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ float gelu_tanh_u(float x) {
+  const float u = 0.7978845608028654f * fmaf(0.044715f * x * x, x, x);
+  const float t = 1.f - 2.f / (1.f + __expf(2.f * u));  // tanh(u)
+  return 0.5f * x * (1.f + t);
+}
+// g[r][k] = u[r][k] * gelu_tanh(u[r][M + k]); u [rows][2M], g [rows][M]; thread = one 16-byte packet of g
+template <class T>
+__global__ __launch_bounds__(256) void geglu_kernel(const T* __restrict__ u, T* __restrict__ g, int64_t rows, int M) {
+  constexpr int VEC = Vec16<T>::N;
+  const int ppr = M / VEC;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * ppr) return;
+  const int64_t r = i / ppr;
+  const int k = (int)(i - r * ppr) * VEC;
+  const Vec16<T> a = load16(u + r * 2 * M + k), b = load16(u + r * 2 * M + M + k);
+  Vec16<T> o;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) o.set(e, a.get(e) * gelu_tanh_u(b.get(e)));
+  store16(g + r * M + k, o);
+}
+
+// out[b][o] = bias[o] + bt[o] + sum_k wt[o][k] * SiLU(temb[b][k]): the per-channel constant a residual block adds
+// after its first convolution, folded into that convolution's bias. One wavefront per (b, o); fp32 throughout.
+template <class T>
+__global__ __launch_bounds__(256) void temb_bias_kernel(const T* __restrict__ temb, const float* __restrict__ wt,
+                                                        const float* __restrict__ bt, const float* __restrict__ bias,
+                                                        float* __restrict__ out, int B, int Cout, int td) {
+  const int lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= B * Cout) return;
+  const int b = item / Cout, o = item - b * Cout;
+  float acc = 0.f;
+  for (int k = lane; k < td; k += 64) acc = fmaf(wt[(int64_t)o * td + k], silu_f(to_f32(temb[(int64_t)b * td + k])), acc);
+  acc = wave_sum(acc);
+  if (lane == 0) out[item] = acc + bt[o] + bias[o];
+}
+
+// dst[r][0:Ca] = a[r][:], dst[r][Ca:Ca+Cb] = b[r][:]; fp32, Ca and Cb multiples of 4; thread = one 16-byte packet
+__global__ __launch_bounds__(256) void concat_rows_kernel(const float* __restrict__ a, const float* __restrict__ b,
+                                                          float* __restrict__ dst, int64_t rows, int Ca4, int Cb4) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int w = Ca4 + Cb4;
+  if (i >= rows * w) return;
+  const int64_t r = i / w;
+  const int c = (int)(i - r * w);
+  reinterpret_cast<f32x4*>(dst)[i] = c < Ca4 ? reinterpret_cast<const f32x4*>(a)[r * Ca4 + c]
+                                             : reinterpret_cast<const f32x4*>(b)[r * Cb4 + (c - Ca4)];
+}
+
+}  // namespace lc
+
+namespace {
+
+thread_local std::string g_uerr = "";
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct ConvP { void *w, *wt; float* b; };            // packed [Cout][9][Cin], the same in tile order (or nullptr), bias
+struct LinP { void* w; float* b; };                  // [Cout][Cin] operand type, fp32 bias (or nullptr)
+struct NormP { float *g, *b; };
+struct RbP { int cin, cout; NormP gn1, gn2; ConvP conv1, conv2; float *temb_w, *temb_b; LinP shortcut; };
+struct TfP {
+  int C; bool cross;
+  NormP gn, ln1, ln2, ln3;
+  LinP pin, qkv, wo1, q2, kv2, wo2, ff1, ff2, pout;
+  float* pe;  // [F][C] (temporal blocks)
+};
+
+struct UPlan {
+  size_t map_bytes;                // one work map: the largest fp32 map of any stage
+  size_t off_map[4], off_s, off_d1, off_slots, slot_bytes;
+  size_t off_part, off_scale, off_shift, off_one, off_zero, off_tb;
+  size_t off_a, off_qkv, off_vt, off_ao, off_u, off_g, off_kv, off_vtx;
+  size_t total;
+};
+
+}  // namespace
+
+struct lc_unet {
+  lc_unet_config cfg;
+  hipStream_t cs, ss;
+  UPlan plan;
+  char* arena;
+  size_t arena_bytes;
+  bool have_weights;
+  void* wblob;
+  float *cin_w, *cin_b;
+  RbP rb[6];
+  TfP st[4], tt[4];
+  ConvP down[2], up[2], out;
+  NormP out_gn;
+  std::vector<void*> host;
+  std::vector<char> host_filled, dev_filled, in_pending;
+  std::vector<hipEvent_t> ev_produced, ev_consumed, ev_in_done, ev_rd_done;
+  std::string err;
+};
+
+namespace {
+
+lc_status ufail(lc_unet* c, lc_status code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_uerr = buf;
+  return code;
+}
+#define LCU_HIP(c, expr)                                                                          \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) return ufail(c, LC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+#define LCU_TRY(expr)                     \
+  do {                                    \
+    const lc_status s_ = (expr);          \
+    if (s_ != LC_OK) return s_;           \
+  } while (0)
+
+lc_status check_ucfg(lc_unet* c, const lc_unet_config* g) {
+  if (!g) return ufail(c, LC_ERR_ARG, "config is NULL");
+  if (g->dtype != LC_F32 && g->dtype != LC_BF16) return ufail(c, LC_ERR_ARG, "dtype must be LC_F32 or LC_BF16");
+  if (g->B <= 0 || g->F <= 0 || g->H <= 0 || g->W <= 0 || g->C_lat <= 0 || g->C <= 0 || g->C1 <= 0 || g->C2 <= 0 || g->groups <= 0 ||
+      g->head_dim <= 0 || g->ctx_len <= 0 || g->ctx_dim <= 0 || g->temb_dim <= 0 || g->ff_mult <= 0)
+    return ufail(c, LC_ERR_SHAPE, "all sizes must be positive");
+  if (g->H % 4 || g->W % 4) return ufail(c, LC_ERR_SHAPE, "H and W must be multiples of 4");
+  for (int C : {g->C, g->C1, g->C2, g->ctx_dim})
+    if (C % 64 || C > 64 * 4 * LNA_MAXV) return ufail(c, LC_ERR_SHAPE, "C, C1, C2 and ctx_dim must be multiples of 64, at most %d", 64 * 4 * LNA_MAXV);
+  for (int C : {g->C, g->C1, g->C2, g->C + g->C1, g->C1 + g->C2})
+    if (C % g->groups || C / g->groups > 512) return ufail(c, LC_ERR_SHAPE, "every width (and C + C1, C1 + C2) must be divisible by groups");
+  const int d = g->head_dim;
+  if (!(d == 8 || d == 16 || d == 32 || d == 40 || d == 64)) return ufail(c, LC_ERR_SHAPE, "head_dim must be one of 8, 16, 32, 40, 64");
+  if (g->C % d || g->C1 % d) return ufail(c, LC_ERR_SHAPE, "C and C1 must be multiples of head_dim");
+  if (g->C_lat > 16) return ufail(c, LC_ERR_SHAPE, "C_lat must be <= 16");
+  if (g->ff_mult > 4) return ufail(c, LC_ERR_SHAPE, "ff_mult must be <= 4");
+  if ((size_t)g->F * 3 * std::max(g->C, g->C1) * dtype_size(g->dtype) > (size_t)128 << 10)
+    return ufail(c, LC_ERR_SHAPE, "F * 3 * max(C, C1) elements must fit 128 KiB");
+  if (g->dev_slots < 1 || g->dev_slots > 8) return ufail(c, LC_ERR_SHAPE, "dev_slots must be in [1, 8]");
+  if (g->host_slots < 0 || g->host_slots > 64) return ufail(c, LC_ERR_SHAPE, "host_slots must be in [0, 64]");
+  if (!(g->gn_eps > 0.f) || !(g->ln_eps > 0.f)) return ufail(c, LC_ERR_SHAPE, "gn_eps and ln_eps must be positive");
+  if ((int64_t)g->B * g->F * g->H * g->W > (int64_t)1 << 24) return ufail(c, LC_ERR_SHAPE, "too many positions");
+  return LC_OK;
+}
+
+inline size_t entry_bytes(const lc_unet_config& g) { return (size_t)g.B * g.F * g.H * g.W * g.C1 * 4; }
+
+// Arena: four work maps that each hold the largest fp32 map of any stage (the concatenated input of the
+// shallowest up block, or an upsampled map), the two skips kept across the deep branch, the device slots, the
+// GroupNorm scratch, and the token buffers of a transformer block at its largest (level 0 or level 1).
+UPlan make_uplan(const lc_unet_config& g) {
+  UPlan p;
+  const size_t es = dtype_size(g.dtype);
+  const int64_t N = (int64_t)g.B * g.F, P = (int64_t)g.H * g.W, P1 = P / 4;
+  const int64_t map_elems = N * std::max({P * (g.C + g.C1), P1 * (g.C1 + g.C2), P1 * g.C2, P * g.C1});
+  const int maxC = std::max({g.C + g.C1, g.C1 + g.C2, g.C2});
+  const int64_t tok = std::max(N * P * g.C, N * P1 * g.C1);  // rows * width of a transformer block, at its largest
+  const int64_t splits_c = std::max({(int64_t)stat_splits((int)P) * (g.C + g.C1), (int64_t)stat_splits((int)P1) * std::max(g.C1 + g.C2, g.C),
+                                     (int64_t)stat_splits((int)(P1 / 4)) * std::max(g.C1, g.C2)});
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  p.map_bytes = align_up((size_t)map_elems * 4);
+  for (int i = 0; i < 4; ++i) p.off_map[i] = take(p.map_bytes);
+  p.off_s = take((size_t)N * P * g.C * 4);
+  p.off_d1 = take((size_t)N * P1 * g.C1 * 4);
+  p.slot_bytes = align_up(entry_bytes(g));
+  p.off_slots = off; off += p.slot_bytes * g.dev_slots;
+  p.off_part = take((size_t)N * splits_c * 2 * 4);
+  p.off_scale = take((size_t)N * maxC * 4);
+  p.off_shift = take((size_t)N * maxC * 4);
+  p.off_one = take((size_t)N * maxC * 4);
+  p.off_zero = take((size_t)N * maxC * 4);
+  p.off_tb = take((size_t)g.B * std::max({g.C, g.C1, g.C2}) * 4);
+  p.off_a = take((size_t)tok * es);
+  p.off_qkv = take((size_t)tok * 3 * es);
+  p.off_vt = take((size_t)std::max(N * g.C * attn_tp((int)P), N * g.C1 * attn_tp((int)P1)) * es);
+  p.off_ao = take((size_t)tok * es);
+  p.off_u = take((size_t)tok * 2 * g.ff_mult * es);
+  p.off_g = take((size_t)tok * g.ff_mult * es);
+  p.off_kv = take((size_t)g.B * g.ctx_len * 2 * std::max(g.C, g.C1) * es);
+  p.off_vtx = take((size_t)g.B * std::max(g.C, g.C1) * attn_tp(g.ctx_len) * es);
+  p.total = off;
+  return p;
+}
+
+inline char* slot_ptr(lc_unet* c, int s) { return c->arena + c->plan.off_slots + c->plan.slot_bytes * s; }
+inline float* map_ptr(lc_unet* c, int i) { return (float*)(c->arena + c->plan.off_map[i]); }
+inline RowMap dense_map() { return RowMap{0, 0, 1 << 30}; }
+
+// ---- operators -------------------------------------------------------------------------------------------------
+// scale / shift of GroupNorm(x) for n frames of fp32 rows [rows][C]
+lc_status gn(lc_unet* c, const float* x, int n, int rows, int C, const NormP& w) {
+  const UPlan& p = c->plan;
+  float* part = (float*)(c->arena + p.off_part);
+  LCU_HIP(c, launch_gn_stats(c->cs, kF32, x, part, n, rows, C));
+  LCU_HIP(c, launch_gn_finalize(c->cs, part, C, stat_splits(rows), rows, 1.f, nullptr, 0, 0, 0, 0.f, w.g, w.b, c->cfg.groups,
+                                c->cfg.gn_eps, (float*)(c->arena + p.off_scale), (float*)(c->arena + p.off_shift), n));
+  return LC_OK;
+}
+
+// y = [res +] conv3x3(act(x)) over n frames; src 2: SiLU(GroupNorm(x)) with the scale / shift at hand (rows of frame
+// `f0` on), src 1: x as it is. planar: y is [n][Cout_store][H][W] of the stage's dtype (the last convolution).
+lc_status conv(lc_unet* c, const ConvP& w, const float* bias, int src, int Cin, int Cout, int n, int f0, int H, int W, const float* x,
+               const float* res, void* y, int planar, int Cout_store) {
+  const UPlan& p = c->plan;
+  FusedDesc f;
+  memset(&f, 0, sizeof f);
+  f.dt = c->cfg.dtype; f.y_f32 = planar ? 0 : 1; f.taps = 9; f.src = src; f.Cin = Cin; f.Cout = Cout; f.Cout_store = Cout_store;
+  f.w = w.w; f.w_tiles = w.wt; f.bias = bias; f.frames = n; f.H = H; f.W = W; f.x = x; f.res = res; f.y = y; f.planar_out = planar;
+  f.scale = (const float*)(c->arena + (src == 2 ? p.off_scale : p.off_one)) + (size_t)f0 * Cin;
+  f.shift = (const float*)(c->arena + (src == 2 ? p.off_shift : p.off_zero)) + (size_t)f0 * Cin;
+  f.in_map = f.out_map = dense_map();
+  LCU_HIP(c, launch_fused(c->cs, f));
+  return LC_OK;
+}
+
+// y[rows][Cout] = x[rows][Cin] W^T + bias [+ res]. src 0: x of the operand type; src 1: x fp32, multiplied by
+// scale[frame] and shifted (GroupNorm apply; unit = 1: taken as it is), frame = row / rows_per_frame.
+lc_status linear(lc_unet* c, const LinP& w, int Cin, int Cout, int64_t rows, int src, int unit, int rows_per_frame, const void* x,
+                 const float* res, void* y, int y32) {
+  const UPlan& p = c->plan;
+  FusedDesc f;
+  memset(&f, 0, sizeof f);
+  f.dt = c->cfg.dtype; f.y_f32 = y32; f.taps = 1; f.src = src; f.Cin = Cin; f.Cout = Cout; f.Cout_store = Cout; f.w = w.w; f.bias = w.b;
+  f.rows = rows; f.in_map = f.out_map = dense_map(); f.x = x; f.res = res; f.y = y;
+  if (src == 1) {
+    f.in_map = RowMap{0, rows_per_frame, rows_per_frame};
+    f.scale = (const float*)(c->arena + (unit ? p.off_one : p.off_scale));
+    f.shift = (const float*)(c->arena + (unit ? p.off_zero : p.off_shift));
+  }
+  LCU_HIP(c, launch_fused(c->cs, f));
+  return LC_OK;
+}
+
+lc_status ln(lc_unet* c, const float* z, const NormP& w, const float* pe, void* y, int64_t rows, int D, int rows_per_frame) {
+  const unsigned blocks = (unsigned)((rows + 3) / 4);
+  const lc_unet_config& g = c->cfg;
+  if (g.dtype == kBF16)
+    ln_affine_kernel<bf16_t><<<blocks, 256, 0, c->cs>>>(z, w.g, w.b, pe, (bf16_t*)y, rows, D, rows_per_frame, g.F, g.ln_eps);
+  else
+    ln_affine_kernel<float><<<blocks, 256, 0, c->cs>>>(z, w.g, w.b, pe, (float*)y, rows, D, rows_per_frame, g.F, g.ln_eps);
+  LCU_HIP(c, hipGetLastError());
+  return LC_OK;
+}
+
+// z += FF(LN(z)): GEGLU feed-forward on fp32 rows z, in place
+lc_status feed_forward(lc_unet* c, const TfP& w, float* z, int64_t rows, int rows_per_frame) {
+  const lc_unet_config& g = c->cfg;
+  const UPlan& p = c->plan;
+  const int C = w.C, M = g.ff_mult * C;
+  char *a = c->arena + p.off_a, *u = c->arena + p.off_u, *gl = c->arena + p.off_g;
+  LCU_TRY(ln(c, z, w.ln3, nullptr, a, rows, C, rows_per_frame));
+  LCU_TRY(linear(c, w.ff1, C, 2 * M, rows, 0, 0, 0, a, nullptr, u, 0));
+  const int64_t n16 = rows * M * (int64_t)dtype_size(g.dtype) / 16;
+  if (g.dtype == kBF16) geglu_kernel<bf16_t><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((const bf16_t*)u, (bf16_t*)gl, rows, M);
+  else geglu_kernel<float><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((const float*)u, (float*)gl, rows, M);
+  LCU_HIP(c, hipGetLastError());
+  return linear(c, w.ff2, M, C, rows, 0, 0, 0, gl, z, z, 1);
+}
+
+// Residual block: x [N][P][cin] fp32 -> y [N][P][cout] fp32 (y distinct from x); h and sc are work maps.
+lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int H, int W, const float* x, float* h, float* sc, float* y) {
+  const lc_unet_config& g = c->cfg;
+  const int N = g.B * g.F, P = H * W;
+  float* tb = (float*)(c->arena + c->plan.off_tb);
+  const unsigned blocks = (unsigned)((g.B * w.cout + 3) / 4);
+  if (g.dtype == kBF16)
+    temb_bias_kernel<bf16_t><<<blocks, 256, 0, c->cs>>>((const bf16_t*)temb, w.temb_w, w.temb_b, w.conv1.b, tb, g.B, w.cout, g.temb_dim);
+  else
+    temb_bias_kernel<float><<<blocks, 256, 0, c->cs>>>((const float*)temb, w.temb_w, w.temb_b, w.conv1.b, tb, g.B, w.cout, g.temb_dim);
+  LCU_HIP(c, hipGetLastError());
+  LCU_TRY(gn(c, x, N, P, w.cin, w.gn1));
+  for (int b = 0; b < g.B; ++b)  // the time embedding is one vector per batch element: its frames share a bias
+    LCU_TRY(conv(c, w.conv1, tb + (size_t)b * w.cout, 2, w.cin, w.cout, g.F, b * g.F, H, W, x + (size_t)b * g.F * P * w.cin, nullptr,
+                 h + (size_t)b * g.F * P * w.cout, 0, w.cout));
+  const float* res = x;
+  if (w.shortcut.w) {
+    LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, (int64_t)N * P, 1, 1, P, x, nullptr, sc, 1));
+    res = sc;
+  }
+  LCU_TRY(gn(c, h, N, P, w.cout, w.gn2));
+  return conv(c, w.conv2, w.conv2.b, 2, w.cout, w.cout, N, 0, H, W, h, res, y, 0, w.cout);
+}
+
+// Transformer block in place on x [N][P][C] fp32; z is a work map. Spatial: tokens = the P positions of a frame,
+// with cross-attention to cond [B][ctx_len][ctx_dim]; temporal: tokens = the F frames of a position.
+lc_status tf_block(lc_unet* c, const TfP& w, const void* cond, int H, int W, float* x, float* z) {
+  const lc_unet_config& g = c->cfg;
+  const UPlan& p = c->plan;
+  const int N = g.B * g.F, P = H * W, C = w.C, heads = C / g.head_dim;
+  const int64_t rows = (int64_t)N * P;
+  const size_t es = dtype_size(g.dtype);
+  char *a = c->arena + p.off_a, *qkv = c->arena + p.off_qkv, *vt = c->arena + p.off_vt, *ao = c->arena + p.off_ao;
+  LCU_TRY(gn(c, x, N, P, C, w.gn));
+  LCU_TRY(linear(c, w.pin, C, C, rows, 1, 0, P, x, nullptr, z, 1));
+  // self-attention
+  LCU_TRY(ln(c, z, w.ln1, w.pe, a, rows, C, P));
+  LCU_TRY(linear(c, w.qkv, C, 3 * C, rows, 0, 0, 0, a, nullptr, qkv, 0));
+  if (w.cross) {
+    const int Tp = attn_tp(P);
+    LCU_HIP(c, launch_make_vt(c->cs, g.dtype, qkv + (size_t)2 * C * es, 3 * C, vt, N, P, Tp, C));
+    LCU_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * C, vt, Tp, ao, N, P, heads, g.head_dim, 0, P, 0));
+  } else {
+    LCU_HIP(c, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, P, heads, g.head_dim));
+  }
+  LCU_TRY(linear(c, w.wo1, C, C, rows, 0, 0, 0, ao, z, z, 1));
+  if (w.cross) {  // queries from the tokens, keys and values from the conditioning tokens of the batch element
+    char *kv = c->arena + p.off_kv, *vtx = c->arena + p.off_vtx;
+    const int L = g.ctx_len, TpL = attn_tp(L);
+    LCU_TRY(ln(c, z, w.ln2, nullptr, a, rows, C, P));
+    LCU_TRY(linear(c, w.q2, C, C, rows, 0, 0, 0, a, nullptr, qkv, 0));
+    LCU_TRY(linear(c, w.kv2, g.ctx_dim, 2 * C, (int64_t)g.B * L, 0, 0, 0, cond, nullptr, kv, 0));
+    LCU_HIP(c, launch_make_vt(c->cs, g.dtype, kv + (size_t)C * es, 2 * C, vtx, g.B, L, TpL, C));
+    LCU_HIP(c, launch_cross_attention(c->cs, g.dtype, qkv, C, kv, 2 * C, vtx, TpL, ao, N, P, L, g.F, heads, g.head_dim));
+    LCU_TRY(linear(c, w.wo2, C, C, rows, 0, 0, 0, ao, z, z, 1));
+  }
+  LCU_TRY(feed_forward(c, w, z, rows, P));
+  return linear(c, w.pout, C, C, rows, 1, 1, P, z, x, x, 1);
+}
+
+lc_status down_conv(lc_unet* c, const ConvP& w, int C, int H, int W, const float* x, float* y) {
+  ConvDesc d;
+  memset(&d, 0, sizeof d);
+  d.dt = c->cfg.dtype; d.x_f32 = 1; d.y_f32 = 1; d.taps = 9; d.stride = 2; d.Cin = C; d.Cout = C; d.Cout_store = C;
+  d.w = w.w; d.bias = w.b; d.frames = c->cfg.B * c->cfg.F; d.H = H; d.W = W; d.x = x; d.y = y; d.out_map = dense_map();
+  LCU_HIP(c, launch_conv(c->cs, d));
+  return LC_OK;
+}
+
+// y [N][2H][2W][C] = conv3x3(nearest2x(x [N][H][W][C])); up is a work map
+lc_status up_conv(lc_unet* c, const ConvP& w, int C, int H, int W, const float* x, float* up, float* y) {
+  const int N = c->cfg.B * c->cfg.F;
+  LCU_HIP(c, launch_up2_rows(c->cs, x, up, N, H, W, C));
+  return conv(c, w, w.b, 1, C, C, N, 0, 2 * H, 2 * W, up, nullptr, y, 0, C);
+}
+
+lc_status concat(lc_unet* c, const float* a, int Ca, const float* b, int Cb, float* dst, int64_t rows) {
+  const int64_t n = rows * (Ca + Cb) / 4;
+  concat_rows_kernel<<<(unsigned)((n + 255) / 256), 256, 0, c->cs>>>(a, b, dst, rows, Ca / 4, Cb / 4);
+  LCU_HIP(c, hipGetLastError());
+  return LC_OK;
+}
+
+lc_status run_step(lc_unet* c, const void* x, const void* temb, const void* cond, void* eps, int slot, bool full) {
+  const lc_unet_config& g = c->cfg;
+  const UPlan& p = c->plan;
+  const int N = g.B * g.F, H = g.H, W = g.W, P = H * W;
+  float *m0 = map_ptr(c, 0), *m1 = map_ptr(c, 1), *m2 = map_ptr(c, 2), *m3 = map_ptr(c, 3);
+  float* s = (float*)(c->arena + p.off_s);
+  float* d1 = (float*)(c->arena + p.off_d1);
+  float* deep = (float*)slot_ptr(c, slot);
+  const int maxC = std::max({g.C + g.C1, g.C1 + g.C2, g.C2});
+  LCU_HIP(c, launch_fill_f32(c->cs, (float*)(c->arena + p.off_one), (int64_t)N * maxC, 1.f));
+  LCU_HIP(c, launch_fill_f32(c->cs, (float*)(c->arena + p.off_zero), (int64_t)N * maxC, 0.f));
+  // ---- shallow down: s = TT(ST(RB(conv_in(x))))
+  LCU_HIP(c, launch_conv_in(c->cs, g.dtype, x, m0, N, H, W, g.C_lat, g.C, c->cin_w, c->cin_b));
+  LCU_TRY(res_block(c, c->rb[0], temb, H, W, m0, m1, m2, s));
+  LCU_TRY(tf_block(c, c->st[0], cond, H, W, s, m0));
+  LCU_TRY(tf_block(c, c->tt[0], nullptr, H, W, s, m0));
+  if (full) {
+    const int H1 = H / 2, W1 = W / 2, H2 = H / 4, W2 = W / 4;
+    // ---- level 1 down: d1 = TT(ST(RB(Down(s))))
+    LCU_TRY(down_conv(c, c->down[0], g.C, H, W, s, m0));
+    LCU_TRY(res_block(c, c->rb[1], temb, H1, W1, m0, m1, m2, d1));
+    LCU_TRY(tf_block(c, c->st[1], cond, H1, W1, d1, m0));
+    LCU_TRY(tf_block(c, c->tt[1], nullptr, H1, W1, d1, m0));
+    // ---- level 2: e = UpC(RB(RB(Down(d1))))
+    LCU_TRY(down_conv(c, c->down[1], g.C1, H1, W1, d1, m0));
+    LCU_TRY(res_block(c, c->rb[2], temb, H2, W2, m0, m1, m2, m3));
+    LCU_TRY(res_block(c, c->rb[3], temb, H2, W2, m3, m1, m2, m0));
+    LCU_TRY(up_conv(c, c->up[0], g.C2, H2, W2, m0, m1, m2));      // e in m2 [N][P1][C2]
+    // ---- level 1 up: d = TT(ST(RB(Concat(d1, e))))
+    LCU_TRY(concat(c, d1, g.C1, m2, g.C2, m0, (int64_t)N * H1 * W1));
+    LCU_TRY(res_block(c, c->rb[4], temb, H1, W1, m0, m1, m2, m3));
+    LCU_TRY(tf_block(c, c->st[2], cond, H1, W1, m3, m0));
+    LCU_TRY(tf_block(c, c->tt[2], nullptr, H1, W1, m3, m0));
+    // ---- the cached feature: deep = UpC(d), written to the slot, which may still be the source of a swap-out
+    //      or the target of a swap-in on the side stream
+    LCU_HIP(c, hipStreamWaitEvent(c->cs, c->ev_rd_done[slot], 0));
+    LCU_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
+    c->in_pending[slot] = 0;
+    LCU_TRY(up_conv(c, c->up[1], g.C1, H1, W1, m3, m0, deep));
+    LCU_HIP(c, hipEventRecord(c->ev_produced[slot], c->cs));
+    c->dev_filled[slot] = 1;
+  } else if (c->in_pending[slot]) {
+    LCU_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
+    c->in_pending[slot] = 0;
+  }
+  // ---- shallow up: u = TT(ST(RB(Concat(s, deep)))); eps = conv_out(SiLU(GN(u)))
+  LCU_TRY(concat(c, s, g.C, deep, g.C1, m0, (int64_t)N * P));
+  LCU_HIP(c, hipEventRecord(c->ev_consumed[slot], c->cs));
+  LCU_TRY(res_block(c, c->rb[5], temb, H, W, m0, m1, m2, m3));
+  LCU_TRY(tf_block(c, c->st[3], cond, H, W, m3, m0));
+  LCU_TRY(tf_block(c, c->tt[3], nullptr, H, W, m3, m0));
+  LCU_TRY(gn(c, m3, N, P, g.C, c->out_gn));
+  return conv(c, c->out, c->out.b, 2, g.C, 32, N, 0, H, W, m3, nullptr, eps, 1, g.C_lat);
+}
+
+lc_status step_checks(lc_unet* c, const void* x, const void* temb, const void* cond, void* eps, int slot) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!x || !temb || !cond || !eps) return ufail(c, LC_ERR_ARG, "x, temb, cond and eps must not be NULL");
+  if (slot < 0 || slot >= c->cfg.dev_slots) return ufail(c, LC_ERR_ARG, "device slot %d out of range", slot);
+  if (!c->have_weights) return ufail(c, LC_ERR_STATE, "weights not loaded");
+  if (!c->arena) return ufail(c, LC_ERR_STATE, "workspace not set");
+  return LC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lc_unet_last_error(const lc_unet* c) { return c ? c->err.c_str() : g_uerr.c_str(); }
+lc_status lc_unet_check_config(const lc_unet_config* cfg) { return check_ucfg(nullptr, cfg); }
+size_t lc_unet_entry_bytes(const lc_unet_config* cfg) { return check_ucfg(nullptr, cfg) == LC_OK ? entry_bytes(*cfg) : 0; }
+size_t lc_unet_workspace_bytes(const lc_unet_config* cfg) { return check_ucfg(nullptr, cfg) == LC_OK ? make_uplan(*cfg).total : 0; }
+
+lc_status lc_unet_destroy(lc_unet* c) {
+  if (!c) return LC_OK;
+  (void)hipStreamSynchronize(c->cs);
+  (void)hipStreamSynchronize(c->ss);
+  for (void* p : c->host) (void)hipHostFree(p);
+  for (auto* v : {&c->ev_produced, &c->ev_consumed, &c->ev_in_done, &c->ev_rd_done})
+    for (hipEvent_t e : *v) (void)hipEventDestroy(e);
+  if (c->wblob) (void)hipFree(c->wblob);
+  delete c;
+  return LC_OK;
+}
+
+lc_status lc_unet_create(const lc_unet_config* cfg, void* compute_stream, void* side_stream, lc_unet** out) {
+  if (!out) return ufail(nullptr, LC_ERR_ARG, "out is NULL");
+  LCU_TRY(check_ucfg(nullptr, cfg));
+  if (!compute_stream || !side_stream || compute_stream == side_stream)
+    return ufail(nullptr, LC_ERR_ARG, "compute and side streams must be two distinct non-default streams");
+  lc_unet* c = new (std::nothrow) lc_unet();
+  if (!c) return ufail(nullptr, LC_ERR_NOMEM, "out of host memory");
+  c->cfg = *cfg;
+  c->cs = (hipStream_t)compute_stream; c->ss = (hipStream_t)side_stream;
+  c->plan = make_uplan(c->cfg);
+  c->arena = nullptr; c->arena_bytes = 0; c->have_weights = false; c->wblob = nullptr;
+  for (int i = 0; i < cfg->host_slots; ++i) {
+    void* p = nullptr;
+    if (hipHostMalloc(&p, entry_bytes(*cfg), hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      lc_unet_destroy(c);
+      return ufail(nullptr, LC_ERR_NOMEM, "hipHostMalloc (pinned cache bank) failed");
+    }
+    c->host.push_back(p);
+  }
+  c->host_filled.assign(cfg->host_slots, 0);
+  c->dev_filled.assign(cfg->dev_slots, 0);
+  c->in_pending.assign(cfg->dev_slots, 0);
+  for (auto* v : {&c->ev_produced, &c->ev_consumed, &c->ev_in_done, &c->ev_rd_done})
+    for (int i = 0; i < cfg->dev_slots; ++i) {
+      hipEvent_t e;
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+        lc_unet_destroy(c);
+        return ufail(nullptr, LC_ERR_HIP, "hipEventCreate failed");
+      }
+      v->push_back(e);
+    }
+  *out = c;
+  return LC_OK;
+}
+
+lc_status lc_unet_load_weights(lc_unet* c, const lc_unet_weights* w) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!w) return ufail(c, LC_ERR_ARG, "weights is NULL");
+  const lc_unet_config& g = c->cfg;
+  const int dt = g.dtype;
+  const size_t es = dtype_size(dt);
+  const int C = g.C, C1 = g.C1, C2 = g.C2;
+  const int rb_in[6] = {C, C, C1, C2, C1 + C2, C + C1}, rb_out[6] = {C, C1, C2, C2, C1, C};
+  const int tf_c[4] = {C, C1, C1, C};
+  // ---- every pointer present?
+  bool ok = w->conv_in.w && w->conv_in.b && w->out_gn_g && w->out_gn_b && w->out.w && w->out.b;
+  for (int i = 0; i < 6; ++i) {
+    const lc_unet_rb_w& r = w->rb[i];
+    ok = ok && r.gn1_g && r.gn1_b && r.conv1_w && r.conv1_b && r.temb_w && r.temb_b && r.gn2_g && r.gn2_b && r.conv2_w && r.conv2_b;
+    if (rb_in[i] != rb_out[i]) ok = ok && r.short_w && r.short_b;
+  }
+  for (int k = 0; k < 2; ++k)
+    for (int i = 0; i < 4; ++i) {
+      const lc_unet_tf_w& t = k ? w->tt[i] : w->st[i];
+      ok = ok && t.gn_g && t.gn_b && t.pin_w && t.pin_b && t.ln1_g && t.ln1_b && t.attn1.wq && t.attn1.wk && t.attn1.wv && t.attn1.wo &&
+           t.attn1.bo && t.ln3_g && t.ln3_b && t.ff1_w && t.ff1_b && t.ff2_w && t.ff2_b && t.pout_w && t.pout_b;
+      if (!k) ok = ok && t.ln2_g && t.ln2_b && t.attn2.wq && t.attn2.wk && t.attn2.wv && t.attn2.wo && t.attn2.bo;
+    }
+  for (int i = 0; i < 2; ++i) ok = ok && w->down[i].w && w->down[i].b && w->up[i].w && w->up[i].b;
+  if (!ok) return ufail(c, LC_ERR_ARG, "a weight pointer is NULL");
+
+  // ---- two passes over the same layout code: the first sizes the blob, the second fills it
+  LCU_HIP(c, hipStreamSynchronize(c->cs));
+  if (c->wblob) { LCU_HIP(c, hipFree(c->wblob)); c->wblob = nullptr; c->have_weights = false; }
+  hipStream_t s = c->cs;
+  char* base = nullptr;
+  size_t off = 0;
+  bool fill = false;
+  hipError_t herr = hipSuccess;
+  auto take = [&](size_t bytes) { char* o = base + off; off += align_up(bytes); return o; };
+  auto note = [&](hipError_t e) { if (herr == hipSuccess && e != hipSuccess) herr = e; };
+  auto f32 = [&](const void* src, int n) {  // a vector converted to fp32
+    float* d = (float*)take((size_t)n * 4);
+    if (fill) note(launch_to_f32(s, dt, src, d, n, n));
+    return d;
+  };
+  auto norm = [&](const void* gsrc, const void* bsrc, int n) { NormP q; q.g = f32(gsrc, n); q.b = f32(bsrc, n); return q; };
+  auto lin = [&](const void* wsrc, const void* bsrc, int cout, int cin) {  // [cout][cin] as it is
+    LinP q;
+    q.w = take((size_t)cout * cin * es);
+    if (fill) note(launch_copy_rows(s, dt, wsrc, q.w, (int64_t)cout * cin));
+    q.b = bsrc ? f32(bsrc, cout) : nullptr;
+    return q;
+  };
+  auto stack = [&](std::initializer_list<const void*> srcs, int cout_each, int cin) {  // matrices stacked on the output axis
+    LinP q;
+    q.w = take((size_t)srcs.size() * cout_each * cin * es);
+    q.b = nullptr;
+    size_t i = 0;
+    for (const void* src : srcs) {
+      if (fill) note(launch_copy_rows(s, dt, src, (char*)q.w + i * cout_each * cin * es, (int64_t)cout_each * cin));
+      ++i;
+    }
+    return q;
+  };
+  auto conv3 = [&](const void* wsrc, const void* bsrc, int cout, int cin, int cout_pad, bool tiles) {
+    ConvP q;
+    q.w = take((size_t)cout_pad * 9 * cin * es);
+    if (fill) note(launch_pack_conv_w(s, dt, wsrc, q.w, cout, cin, 9, cout_pad));
+    q.wt = nullptr;
+    if (tiles && dt == kBF16 && cout % 160 == 0 && cin % 64 == 0) {
+      q.wt = take((size_t)cout * 9 * cin * es);
+      if (fill) note(launch_pack_conv_w_tiles(s, dt, q.w, q.wt, cout, cin));
+    }
+    q.b = (float*)take((size_t)cout_pad * 4);
+    if (fill) note(launch_to_f32(s, dt, bsrc, q.b, cout, cout_pad));
+    return q;
+  };
+  auto layout = [&]() {
+    off = 0;
+    c->cin_w = (float*)take((size_t)g.C_lat * 9 * C * 4);
+    if (fill) note(launch_pack_conv_in_w(s, dt, w->conv_in.w, c->cin_w, C, g.C_lat));
+    c->cin_b = f32(w->conv_in.b, C);
+    for (int i = 0; i < 6; ++i) {
+      const lc_unet_rb_w& r = w->rb[i];
+      RbP& q = c->rb[i];
+      q.cin = rb_in[i]; q.cout = rb_out[i];
+      q.gn1 = norm(r.gn1_g, r.gn1_b, q.cin);
+      q.conv1 = conv3(r.conv1_w, r.conv1_b, q.cout, q.cin, q.cout, true);
+      q.temb_w = f32(r.temb_w, q.cout * g.temb_dim);
+      q.temb_b = f32(r.temb_b, q.cout);
+      q.gn2 = norm(r.gn2_g, r.gn2_b, q.cout);
+      q.conv2 = conv3(r.conv2_w, r.conv2_b, q.cout, q.cout, q.cout, true);
+      q.shortcut = LinP{nullptr, nullptr};
+      if (q.cin != q.cout) q.shortcut = lin(r.short_w, r.short_b, q.cout, q.cin);
+    }
+    for (int k = 0; k < 2; ++k)
+      for (int i = 0; i < 4; ++i) {
+        const lc_unet_tf_w& t = k ? w->tt[i] : w->st[i];
+        TfP& q = k ? c->tt[i] : c->st[i];
+        const int D = tf_c[i], M = g.ff_mult * D;
+        q.C = D; q.cross = !k;
+        q.gn = norm(t.gn_g, t.gn_b, D);
+        q.pin = lin(t.pin_w, t.pin_b, D, D);
+        q.ln1 = norm(t.ln1_g, t.ln1_b, D);
+        q.qkv = stack({t.attn1.wq, t.attn1.wk, t.attn1.wv}, D, D);
+        q.wo1 = lin(t.attn1.wo, t.attn1.bo, D, D);
+        q.ln2 = NormP{nullptr, nullptr};
+        q.q2 = q.kv2 = q.wo2 = LinP{nullptr, nullptr};
+        if (!k) {
+          q.ln2 = norm(t.ln2_g, t.ln2_b, D);
+          q.q2 = lin(t.attn2.wq, nullptr, D, D);
+          q.kv2 = stack({t.attn2.wk, t.attn2.wv}, D, g.ctx_dim);
+          q.wo2 = lin(t.attn2.wo, t.attn2.bo, D, D);
+        }
+        q.ln3 = norm(t.ln3_g, t.ln3_b, D);
+        q.ff1 = lin(t.ff1_w, t.ff1_b, 2 * M, D);
+        q.ff2 = lin(t.ff2_w, t.ff2_b, D, M);
+        q.pout = lin(t.pout_w, t.pout_b, D, D);
+        q.pe = nullptr;
+        if (k) {  // the frame encoding, computed in double and rounded once
+          q.pe = (float*)take((size_t)g.F * D * 4);
+          if (fill) {
+            std::vector<float> pe((size_t)g.F * D);
+            for (int f = 0; f < g.F; ++f)
+              for (int j = 0; j < D; ++j) {
+                const double ang = (double)f * std::exp(-std::log(10000.0) * (double)(j - j % 2) / (double)D);
+                pe[(size_t)f * D + j] = (float)(j % 2 ? std::cos(ang) : std::sin(ang));
+              }
+            note(hipMemcpy(q.pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice));
+          }
+        }
+      }
+    c->down[0] = conv3(w->down[0].w, w->down[0].b, C, C, C, false);
+    c->down[1] = conv3(w->down[1].w, w->down[1].b, C1, C1, C1, false);
+    c->up[0] = conv3(w->up[0].w, w->up[0].b, C2, C2, C2, false);
+    c->up[1] = conv3(w->up[1].w, w->up[1].b, C1, C1, C1, false);
+    c->out_gn = norm(w->out_gn_g, w->out_gn_b, C);
+    c->out = conv3(w->out.w, w->out.b, g.C_lat, C, 32, false);
+  };
+  layout();  // sizes only
+  const size_t total = off;
+  void* blob = nullptr;
+  if (hipMalloc(&blob, total) != hipSuccess) return ufail(c, LC_ERR_NOMEM, "hipMalloc of %zu bytes for the weights failed", total);
+  c->wblob = blob;
+  base = (char*)blob;
+  fill = true;
+  layout();
+  if (herr != hipSuccess) return ufail(c, LC_ERR_HIP, "packing the weights: %s", hipGetErrorString(herr));
+  LCU_HIP(c, hipStreamSynchronize(s));
+  c->have_weights = true;
+  return LC_OK;
+}
+
+lc_status lc_unet_set_workspace(lc_unet* c, void* arena, size_t bytes) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!arena) return ufail(c, LC_ERR_ARG, "arena is NULL");
+  if ((uintptr_t)arena % kAlign) return ufail(c, LC_ERR_ARG, "arena must be 256-byte aligned");
+  if (bytes < c->plan.total) return ufail(c, LC_ERR_NOMEM, "workspace of %zu bytes is smaller than the %zu needed", bytes, c->plan.total);
+  LCU_HIP(c, hipStreamSynchronize(c->cs));
+  LCU_HIP(c, hipStreamSynchronize(c->ss));
+  c->arena = (char*)arena; c->arena_bytes = bytes;
+  std::fill(c->dev_filled.begin(), c->dev_filled.end(), 0);
+  std::fill(c->in_pending.begin(), c->in_pending.end(), 0);
+  return LC_OK;
+}
+
+lc_status lc_unet_full_step(lc_unet* c, const void* x, const void* temb, const void* cond, void* eps, int dev_slot) {
+  LCU_TRY(step_checks(c, x, temb, cond, eps, dev_slot));
+  return run_step(c, x, temb, cond, eps, dev_slot, true);
+}
+
+lc_status lc_unet_cached_step(lc_unet* c, const void* x, const void* temb, const void* cond, void* eps, int dev_slot) {
+  LCU_TRY(step_checks(c, x, temb, cond, eps, dev_slot));
+  if (!c->dev_filled[dev_slot]) return ufail(c, LC_ERR_STATE, "cached step on empty device slot %d", dev_slot);
+  return run_step(c, x, temb, cond, eps, dev_slot, false);
+}
+
+static lc_status unet_swap_common(lc_unet* c, int dev_slot, int host_slot) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (dev_slot < 0 || dev_slot >= c->cfg.dev_slots) return ufail(c, LC_ERR_ARG, "device slot %d out of range", dev_slot);
+  if (host_slot < 0 || host_slot >= c->cfg.host_slots) return ufail(c, LC_ERR_ARG, "host slot %d out of range", host_slot);
+  if (!c->arena) return ufail(c, LC_ERR_STATE, "workspace not set");
+  return LC_OK;
+}
+
+lc_status lc_unet_swap_out(lc_unet* c, int dev_slot, int host_slot) {
+  LCU_TRY(unet_swap_common(c, dev_slot, host_slot));
+  if (!c->dev_filled[dev_slot]) return ufail(c, LC_ERR_STATE, "swap-out of empty device slot %d", dev_slot);
+  LCU_HIP(c, hipStreamWaitEvent(c->ss, c->ev_produced[dev_slot], 0));
+  LCU_HIP(c, hipMemcpyAsync(c->host[host_slot], slot_ptr(c, dev_slot), entry_bytes(c->cfg), hipMemcpyDeviceToHost, c->ss));
+  LCU_HIP(c, hipEventRecord(c->ev_rd_done[dev_slot], c->ss));
+  c->host_filled[host_slot] = 1;
+  return LC_OK;
+}
+
+lc_status lc_unet_swap_in(lc_unet* c, int host_slot, int dev_slot) {
+  LCU_TRY(unet_swap_common(c, dev_slot, host_slot));
+  if (!c->host_filled[host_slot]) return ufail(c, LC_ERR_STATE, "swap-in from empty host slot %d", host_slot);
+  LCU_HIP(c, hipStreamWaitEvent(c->ss, c->ev_consumed[dev_slot], 0));
+  LCU_HIP(c, hipStreamWaitEvent(c->ss, c->ev_produced[dev_slot], 0));
+  LCU_HIP(c, hipMemcpyAsync(slot_ptr(c, dev_slot), c->host[host_slot], entry_bytes(c->cfg), hipMemcpyHostToDevice, c->ss));
+  LCU_HIP(c, hipEventRecord(c->ev_in_done[dev_slot], c->ss));
+  c->in_pending[dev_slot] = 1;
+  c->dev_filled[dev_slot] = 1;
+  return LC_OK;
+}
+
+lc_status lc_unet_sync(lc_unet* c) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  LCU_HIP(c, hipStreamSynchronize(c->cs));
+  LCU_HIP(c, hipStreamSynchronize(c->ss));
+  return LC_OK;
+}
+
+lc_status lc_unet_cache_write(lc_unet* c, int dev_slot, const void* deep) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!deep) return ufail(c, LC_ERR_ARG, "deep is NULL");
+  if (dev_slot < 0 || dev_slot >= c->cfg.dev_slots) return ufail(c, LC_ERR_ARG, "device slot %d out of range", dev_slot);
+  if (!c->arena) return ufail(c, LC_ERR_STATE, "workspace not set");
+  LCU_HIP(c, hipStreamWaitEvent(c->cs, c->ev_rd_done[dev_slot], 0));
+  LCU_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[dev_slot], 0));
+  c->in_pending[dev_slot] = 0;
+  LCU_HIP(c, hipMemcpyAsync(slot_ptr(c, dev_slot), deep, entry_bytes(c->cfg), hipMemcpyDeviceToDevice, c->cs));
+  LCU_HIP(c, hipEventRecord(c->ev_produced[dev_slot], c->cs));
+  c->dev_filled[dev_slot] = 1;
+  return LC_OK;
+}
+
+lc_status lc_unet_cache_peek(lc_unet* c, int host_slot, const void** ptr, size_t* bytes) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!ptr || !bytes) return ufail(c, LC_ERR_ARG, "output pointer is NULL");
+  if (host_slot < 0 || host_slot >= c->cfg.host_slots) return ufail(c, LC_ERR_ARG, "host slot %d out of range", host_slot);
+  if (!c->host_filled[host_slot]) return ufail(c, LC_ERR_STATE, "host slot %d is empty", host_slot);
+  *ptr = c->host[host_slot];
+  *bytes = entry_bytes(c->cfg);
+  return LC_OK;
+}
+
+lc_status lc_unet_cache_dev_peek(lc_unet* c, int dev_slot, const void** ptr, size_t* bytes) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (!ptr || !bytes) return ufail(c, LC_ERR_ARG, "output pointer is NULL");
+  if (dev_slot < 0 || dev_slot >= c->cfg.dev_slots) return ufail(c, LC_ERR_ARG, "device slot %d out of range", dev_slot);
+  if (!c->arena) return ufail(c, LC_ERR_STATE, "workspace not set");
+  if (!c->dev_filled[dev_slot]) return ufail(c, LC_ERR_STATE, "device slot %d is empty", dev_slot);
+  *ptr = slot_ptr(c, dev_slot);
+  *bytes = entry_bytes(c->cfg);
+  return LC_OK;
+}
+
+}  // extern "C"

@@ -18,6 +18,12 @@ from paper_2510_05367_amd import synth
 #   `wide_range=True`: the hidden states of the diffusion-transformer variant, which are not eps-like: inputs ~N(0,1)
 #   over millions of elements reach |x| = 5-6 and every block adds to them. The same relative precision as 2e-2 on
 #   a tensor within |.| < 4 is 2e-2 * max(1, max|ref| / 4) there (fp32 tensors: no storage term).
+#   `chain=True`: the cached feature of the U-Net stage with real block internals, an fp32 intermediate at the end of
+#   a three-level deep branch (about 60 bf16 contractions deep, rms 4-5, extremes near 30): not eps-like in scale or
+#   depth. rel-L2 <= 1e-2 holds unchanged; the element-wise bound is the largest error that tolerance itself allows
+#   when the errors are spread evenly (Gaussian with rms 1e-2 * rms(ref), the expected maximum over M elements being
+#   sqrt(2 ln M) times that): 1e-2 * rms(ref) * sqrt(2 ln M). A misplaced or dropped element is off by rms(ref) itself,
+#   twenty times the bound. The eps that is computed from this feature is held to the plain bounds above.
 TOL = {"f32": dict(rel=1e-4, abs=None), "bf16": dict(rel=1e-2, abs=2e-2)}
 BF16_HALF_ULP = 2.0 ** -8
 EPS_RANGE = 4.0  # |eps| stays below this in every workload
@@ -29,7 +35,7 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def check(name, got, ref, dtype, cache_entry=False, wide_range=False):
+def check(name, got, ref, dtype, cache_entry=False, wide_range=False, chain=False):
     """got: torch tensor or array; ref: float64 array of the same shape."""
     g = got.float().cpu().numpy() if isinstance(got, torch.Tensor) else np.asarray(got)
     assert g.shape == ref.shape, (name, g.shape, ref.shape)
@@ -46,6 +52,8 @@ def check(name, got, ref, dtype, cache_entry=False, wide_range=False):
             bound = bound * max(1.0, float(np.max(np.abs(ref))) / EPS_RANGE)
         if cache_entry:
             bound = bound + BF16_HALF_ULP * np.abs(ref)
+        if chain:
+            bound = tol["rel"] * float(np.sqrt(np.mean(ref ** 2))) * float(np.sqrt(2.0 * np.log(ref.size)))
         assert np.all(np.abs(g.astype(np.float64) - ref) <= bound), msg
     return r, m
 

@@ -143,3 +143,31 @@ def test_decoder_config_checks_and_footprint_without_a_gpu():
         lcb.lc_decoder_check_config(bad)
     for name in synth.DECODERS:
         lcb.lc_decoder_check_config(lcb.make_decoder_config(synth.DECODERS[name]))
+
+
+def test_unet_config_checks_and_footprint_without_a_gpu():
+    cfg = synth.UNETS["sd15_video"]
+    c = lcb.make_unet_config(cfg)
+    lcb.lc_unet_check_config(c)
+    assert ctypes.sizeof(lcb.lc_unet_config) == 4 * 19
+    assert ctypes.sizeof(lcb.lc_unet_weights) == 8 * (2 + 6 * 12 + 8 * 26 + 4 + 4 + 2 + 2)
+    assert lcb.lc_unet_entry_bytes(c) == cfg.N * cfg.H * cfg.W * cfg.C1 * 4
+    ws = lcb.lc_unet_workspace_bytes(c)
+    assert ws > 2 * lcb.lc_unet_entry_bytes(c)   # the device slots are part of it
+    more = lcb.make_unet_config(cfg, dev_slots=3)
+    assert lcb.lc_unet_workspace_bytes(more) - ws == lcb.lc_unet_entry_bytes(c)
+    for field, value in [("H", 6), ("C", 100), ("C1", 4096), ("groups", 7), ("head_dim", 24), ("C_lat", 17), ("ff_mult", 5), ("F", 0),
+                         ("F", 64), ("ctx_dim", 100), ("dev_slots", 0), ("host_slots", 65), ("gn_eps", 0.0), ("ln_eps", -1.0)]:
+        bad = lcb.make_unet_config(cfg)
+        setattr(bad, field, value)
+        with pytest.raises(lcb.LcError) as e:
+            lcb.lc_unet_check_config(bad)
+        assert e.value.status == lcb.LC_ERR_SHAPE, field
+        assert lcb.lc_unet_workspace_bytes(bad) == 0 and lcb.lc_unet_entry_bytes(bad) == 0
+    bad = lcb.make_unet_config(cfg)
+    bad.dtype = 7
+    with pytest.raises(lcb.LcError) as e:
+        lcb.lc_unet_check_config(bad)
+    assert e.value.status == lcb.LC_ERR_ARG
+    for name in synth.UNETS:
+        lcb.lc_unet_check_config(lcb.make_unet_config(synth.UNETS[name]))
