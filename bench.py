@@ -493,6 +493,7 @@ def main():
         out["stress"] = stress_record(lcb, torch, synth, w, args.lanes, stats.weight_bytes)
         out["sliced_decode"] = decode_record(lcb, torch, synth)
         out["video_dit"] = dit_record(lcb, torch, synth)
+        out["unet"] = unet_record(lcb, torch, synth)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w)
     print(json.dumps(out))
@@ -661,6 +662,13 @@ def dit_record(lcb, torch, synth, steps=6):
                "entry_mb": round(lcb.lc_dit_entry_bytes(dit.ccfg) / 1e6, 1),
                "workspace_gb": round(lcb.lc_dit_workspace_bytes(dit.ccfg, cfg.token_chunk) / 1e9, 4),
                "workspace_unchunked_gb": round(lcb.lc_dit_workspace_bytes(dit.ccfg, 0) / 1e9, 4), "schedules": []}
+        # the token chunk trades workspace for launch size (results never change)
+        rec["token_chunks"] = []
+        for chunk in (512, 1024, 2048, 4096, 0):
+            dit.set_chunk(chunk)
+            rec["token_chunks"].append({"token_chunk": chunk, "normal_step_ms": round(timed(lambda: dit.full_step(x, mod, out, 0), 3), 3),
+                                        "workspace_gb": round(lcb.lc_dit_workspace_bytes(dit.ccfg, chunk) / 1e9, 4)})
+        dit.set_chunk(cfg.token_chunk)
         n_steps = 12
 
         def schedule(interval, swapping):
@@ -697,6 +705,77 @@ def dit_record(lcb, torch, synth, steps=6):
         return rec
     finally:
         dit.close()
+        torch.cuda.empty_cache()
+
+
+def unet_record(lcb, torch, synth, steps=5):
+    """The U-Net with real block internals (time-embedding residual blocks, transformer blocks with cross-attention
+    and GEGLU, frame encoding, three-level deep branch): normal and cache step, and schedules with a normal step every
+    `interval` steps, the cached feature swapped out and prefetched one step ahead."""
+    cfg = synth.UNETS["sd15_video"]
+    w = synth.make_unet_weights(cfg, 0)
+    net = lcb.Unet(cfg, w, host_slots=2, dev_slots=2)
+    try:
+        xa, ta, ca = synth.make_unet_inputs(cfg, 1)
+        x, temb, ctx = net.to_device(xa), net.to_device(ta), net.to_device(ca)
+        out = net.empty(*xa.shape)
+
+        def timed(fn, n):
+            fn()
+            net.sync()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            ev[0].record(net.compute)
+            for i in range(n):
+                fn()
+                ev[i + 1].record(net.compute)
+            net.sync()
+            return statistics.median(ev[i].elapsed_time(ev[i + 1]) for i in range(n))
+        ms_full = timed(lambda: net.full_step(x, temb, ctx, out, 0), steps)
+        ms_cached = timed(lambda: net.cached_step(x, temb, ctx, out, 0), steps)
+        rec = {"workload": f"video U-Net with real block internals, synthetic weights: B={cfg.B}, F={cfg.F}, {cfg.H}x{cfg.W} latents, "
+                           f"widths {cfg.C}/{cfg.C1}/{cfg.C2}, heads of {cfg.head_dim}, {cfg.ctx_len} x {cfg.ctx_dim} conditioning "
+                           f"tokens, time embedding {cfg.temb_dim}, {cfg.dtype}, all frames at once",
+               "normal_step_ms": round(ms_full, 3), "cache_step_ms": round(ms_cached, 3),
+               "normal_step_tflops": round(cfg.full_step_flops() / (ms_full * 1e-3) / 1e12, 1),
+               "cache_step_tflops": round(cfg.cached_step_flops() / (ms_cached * 1e-3) / 1e12, 1),
+               "entry_mb": round(lcb.lc_unet_entry_bytes(net.ccfg) / 1e6, 1),
+               "workspace_gb": round(lcb.lc_unet_workspace_bytes(net.ccfg) / 1e9, 4), "schedules": []}
+        n_steps = 12
+
+        def schedule(interval, swapping):
+            refresh, prefetched = -1, None
+            for t in range(n_steps):
+                slot = t % 2 if swapping else 0
+                if t % interval == 0:
+                    refresh += 1
+                    net.full_step(x, temb, ctx, out, slot)
+                    if swapping:
+                        net.swap_out(slot, refresh % 2)
+                else:
+                    if swapping and prefetched != (t, slot):
+                        net.swap_in(refresh % 2, slot)
+                    net.cached_step(x, temb, ctx, out, slot)
+                if swapping and t + 1 < n_steps and (t + 1) % interval != 0:
+                    net.swap_in(refresh % 2, (t + 1) % 2)
+                    prefetched = (t + 1, (t + 1) % 2)
+        for interval in (1, 2, 3, 5):
+            row = {"interval": interval}
+            for name, swapping in (("resident", False), ("swapped", True)):
+                if interval == 1 and swapping:
+                    continue
+                schedule(interval, swapping)
+                net.sync()
+                t0 = time.perf_counter()
+                schedule(interval, swapping)
+                net.sync()
+                row[f"{name}_ms_per_step"] = round((time.perf_counter() - t0) * 1e3 / n_steps, 3)
+            rec["schedules"].append(row)
+        base = rec["schedules"][0]["resident_ms_per_step"]
+        for row in rec["schedules"]:
+            row["speedup_vs_every_step_normal"] = round(base / row.get("swapped_ms_per_step", row["resident_ms_per_step"]), 3)
+        return rec
+    finally:
+        net.close()
         torch.cuda.empty_cache()
 
 

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblightcache.so")
-SOURCES = ["lc_api.hip", "lc_norm.hip", "lc_gemm.hip", "lc_convws.hip", "lc_linear.hip", "lc_conv.hip", "lc_attn.hip", "lc_misc.hip", "lc_decode.hip", "lc_dit.hip", "lc_unet.hip"]
+SOURCES = ["lc_api.hip", "lc_norm.hip", "lc_gemm.hip", "lc_convws.hip", "lc_linear.hip", "lc_lin2.hip", "lc_conv.hip", "lc_attn.hip", "lc_misc.hip", "lc_decode.hip", "lc_dit.hip", "lc_unet.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -568,6 +568,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
       orow = ok ? a.out_map(row0 + p) : 0;
     }
     if (!ok) continue;
+    // the residual (which may be y itself) of this pixel, all of it before the first store: a load placed after a
+    // store that may alias it cannot be moved up, and would pay a round trip to memory each
+    f32x4 rv[CO_T][4];
+    if (!PLANAR && R) {
+#pragma unroll
+      for (int i = 0; i < CO_T; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) rv[i][g] = *reinterpret_cast<const f32x4*>(R + orow * a.Cout_store + co0 + i * 32 + g * 8 + hh * 4);
+    }
 #pragma unroll
     for (int i = 0; i < CO_T; ++i) {
 #pragma unroll
@@ -600,9 +609,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
           }
           const int64_t o = orow * a.Cout_store + co;
           if (R) {
-            const f32x4 rv = *reinterpret_cast<const f32x4*>(R + o);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += rv[e];
+            for (int e = 0; e < 4; ++e) v[e] += rv[i][g][e];
           }
           if constexpr (sizeof(OT) == 2) {
             bf16x4 ov;
@@ -701,6 +709,11 @@ hipError_t launch_fused(hipStream_t s, const FusedDesc& d) {
     const hipError_t e = launch_conv_ws(s, d);
     if (e != hipErrorNotSupported) return e;
   }
+  if (d.taps == 1 && d.src == 0) {  // dense bf16 rows: the kernel with a ring of LDS stages
+    const hipError_t e = launch_lin2(s, d);
+    if (e != hipErrorNotSupported) return e;
+  }
+  if (d.y2) return hipErrorInvalidValue;  // only that kernel writes the rounded copy
   return d.dt == kBF16 ? by_kind<bf16_t>(s, d) : by_kind<float>(s, d);
 }
 

@@ -100,6 +100,8 @@ struct FusedDesc {
   const void* res;     // fp32, indexed like y; nullptr if none; may equal y only when taps == 1
   void* y;
   int planar_out;      // 1: y is [frame][Cout_store][H][W] of the operand type (Cout = 32, zero-padded w)
+  void* y2;            // taps == 1, src == 0, fp32 y of a bf16 stage over dense rows only: a copy of y rounded to the
+                       // operand type (what the next layer contracts), or nullptr
   // taps == 1 only: output channels >= yt_from are not stored in y (whose rows then have yt_from
   // channels) but transposed into yt[frame][Cout - yt_from][yt_Tp] at column (t & ~63) + vcol(t & 63),
   // frame = r / yt_T, t = r % yt_T (the V^T layout of the spatial attention kernel). yt == nullptr: off.
@@ -137,6 +139,9 @@ hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
 // taps == 9 of a bf16 stage with specialised wavefronts (lc_convws.hip): the same results as the general
 // kernel bit for bit; hipErrorNotSupported for shapes it does not cover. launch_fused tries it first.
 hipError_t launch_conv_ws(hipStream_t s, const FusedDesc& d);
+// taps == 1, src == 0 of a bf16 stage over dense rows (lc_lin2.hip: 256 x 160 tiles, operands streamed through a ring
+// of LDS stages); hipErrorNotSupported for shapes it does not cover. launch_fused tries it first.
+hipError_t launch_lin2(hipStream_t s, const FusedDesc& d);
 // taps == 1 with the weights resident in registers (needs w_frag); hipErrorNotSupported for shapes it does not cover
 hipError_t launch_linear(hipStream_t s, const FusedDesc& d);
 inline hipError_t launch_linear_any(hipStream_t s, const FusedDesc& d) {

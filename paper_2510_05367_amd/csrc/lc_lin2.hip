@@ -1,0 +1,227 @@
+// Linear layers over dense bf16 rows on gfx950: y[rows][N] = x[rows][K] W[N][K]^T (+ bias, + fp32 residual), the
+// projections and feed-forward layers of the transformer blocks, where K is a few hundred to a few thousand.
+//
+// One workgroup = 4 wavefronts = 256 rows x 160 (or 128) output channels; wavefront w owns rows [64 w, 64 w + 64) and
+// all channels (2 x 5 or 2 x 4 accumulator tiles of 32 x 32: every fragment of W feeds two MFMAs, every fragment of x
+// five or four), and
+// walks K in steps of 64 elements without splitting it. Both operands are K-major in memory, so a step's tiles are
+// rows of 128 bytes, brought from global memory straight into LDS (16 bytes per lane, no registers in between) into a
+// ring of three stages: the loads of step s + 2 are issued while step s is contracted, and the wait before a step
+// counts exactly the loads that are younger than the ones it needs. The 16-byte packet c of row r is parked in
+// slot c ^ ((r >> 1) & 7) of its row, which makes the fragment reads (32 consecutive rows, one slot) conflict-free
+// without padding. The product is not transposed (rows of x are the rows of the accumulator tile): a lane then holds
+// one output channel of 16 rows, and the 32 lanes of a half-wavefront store 32 consecutive channels of one row.
+//
+// Workgroups are dealt to the eight XCDs round robin in launch order, and each XCD has an L2 of its own: the
+// channel tiles of one row tile are mapped to the same XCD, so its L2 fetches that tile of x once.
+#include "lc_internal.h"
+
+namespace lc {
+
+namespace {
+
+constexpr int kKB = 128;                        // K bytes per step
+constexpr int kStages = 3;
+// a workgroup takes 128 MR rows (MR = 2, or 1 where few rows would leave most of the device idle) and 32 NT channels;
+// bytes of one ring stage: the x tile, then the W tile
+constexpr int lin2_stage(int NT, int MR) { return (128 * MR + NT * 32) * kKB; }
+static_assert(kStages * lin2_stage(5, 2) <= 160 * 1024, "fits the LDS of a compute unit");
+
+struct Lin2Args {
+  const bf16_t* x;     // [rows][K]
+  const bf16_t* w;     // [N][K]
+  const float* bias;   // [N] or nullptr
+  const float* res;    // fp32 [rows][N] or nullptr (may alias y)
+  void* y;             // [rows][N], bf16 or fp32
+  bf16_t* y2;          // fp32 output only: a copy of y rounded to bf16 (the next layer's operand), or nullptr
+  int64_t rows;
+  int K, N, ntm, ntn;
+  float q_scale;       // channels below q_cols are multiplied by this before they are rounded
+  int q_cols;
+};
+
+}  // namespace
+
+template <class OT, int NT, int MR>
+__global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
+  typedef Mma32<bf16_t> M;
+  constexpr int kM = 128 * MR, kN = NT * 32, kStage = lin2_stage(NT, MR);
+  constexpr int kXI = 4 * MR, kWI = NT;  // global->LDS instructions per wavefront per stage: x tile, W tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lp = lane & 31, hh = lane >> 5;
+  // (row tile, channel tile) of this workgroup: all channel tiles of a row tile on one XCD
+  const int lin = blockIdx.x, xcd = lin & 7, slot = lin >> 3;
+  const int mt = xcd + 8 * (slot / a.ntn), nt = slot - (slot / a.ntn) * a.ntn;
+  if (mt >= a.ntm) return;  // the grid is padded to whole rounds of eight row tiles
+  const int64_t m0 = (int64_t)mt * kM;
+  const int n0 = nt * kN;
+
+  // ---- global -> LDS: instruction i of a tile moves rows 8 i .. 8 i + 7; this lane moves the packet that lands
+  //      in slot (lane & 7) of row 8 i + (lane >> 3), i.e. global packet (lane & 7) ^ ((row >> 1) & 7)
+  const int lrow = lane >> 3;
+  const bf16_t* xsrc[kXI];
+  const bf16_t* wsrc[kWI];
+#pragma unroll
+  for (int j = 0; j < kXI; ++j) {
+    const int r = (wid + 4 * j) * 8 + lrow;
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    const int64_t gr = min(m0 + r, a.rows - 1);  // rows beyond the end: a valid row, never stored
+    xsrc[j] = a.x + gr * a.K + c * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < kWI; ++j) {
+    const int r = (wid + 4 * j) * 8 + lrow;
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    wsrc[j] = a.w + (int64_t)(n0 + r) * a.K + c * 8;
+  }
+  auto issue = [&](int step, int buf) {
+    unsigned char* xb = smem + buf * kStage;
+    unsigned char* wb = xb + kM * kKB;
+    const int kofs = step * 64;
+#ifdef __HIP_DEVICE_COMPILE__  // the host pass only needs the kernel's stub; it does not know this builtin
+#pragma unroll
+    for (int j = 0; j < kXI; ++j) __builtin_amdgcn_global_load_lds(xsrc[j] + kofs, xb + (wid + 4 * j) * 1024, 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < kWI; ++j) __builtin_amdgcn_global_load_lds(wsrc[j] + kofs, wb + (wid + 4 * j) * 1024, 16, 0, 0);
+#else
+    (void)xb; (void)wb; (void)kofs;
+#endif
+  };
+
+  f32x16 acc[MR][NT];
+#pragma unroll
+  for (int j = 0; j < MR; ++j)
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+  // fragment addresses inside a stage: row * 128 + ((slot ^ key) << 4), slot = hh + 2 kk
+  const int xrow0 = wid * (32 * MR) + lp, xkey = (xrow0 >> 1) & 7;  // (+32 does not change the key)
+  const int wkey = (lp >> 1) & 7;
+  auto xfrag = [&](const unsigned char* st, int j, int kk) {
+    return M::load((const bf16_t*)(st + (xrow0 + 32 * j) * kKB + (((hh + 2 * kk) ^ xkey) << 4)));
+  };
+  auto wfrag = [&](const unsigned char* st, int i, int kk) {
+    return M::load((const bf16_t*)(st + kM * kKB + (32 * i + lp) * kKB + (((hh + 2 * kk) ^ wkey) << 4)));
+  };
+
+  const int nsteps = a.K / 64;
+  issue(0, 0);
+  if (nsteps > 1) issue(1, 1);
+  for (int s = 0; s < nsteps; ++s) {
+    // the loads of step s have landed (for every wavefront, after the barrier); those of step s + 1 may be in flight
+    if (s + 1 < nsteps) barrier_keep<kXI + kWI>();
+    else barrier_keep<0>();
+    if (s + 2 < nsteps) issue(s + 2, (s + 2) % kStages);  // into the stage that was read in step s - 1
+    const unsigned char* st = smem + (s % kStages) * kStage;
+    typename M::Frag xf[2][MR], wf[2][NT];
+#pragma unroll
+    for (int j = 0; j < MR; ++j) xf[0][j] = xfrag(st, j, 0);
+#pragma unroll
+    for (int i = 0; i < NT; ++i) wf[0][i] = wfrag(st, i, 0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kk + 1 < 4) {  // the fragments of the next k-step are requested before this one's MFMAs
+#pragma unroll
+        for (int j = 0; j < MR; ++j) xf[(kk + 1) & 1][j] = xfrag(st, j, kk + 1);
+#pragma unroll
+        for (int i = 0; i < NT; ++i) wf[(kk + 1) & 1][i] = wfrag(st, i, kk + 1);
+      }
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < MR; ++j) M::mma(xf[kk & 1][j], wf[kk & 1][i], acc[j][i]);
+    }
+  }
+
+  // ---- epilogue: lane holds channel n0 + 32 i + lp of rows m0 + 32 MR wid + 32 j + 8 (r / 4) + 4 hh + r % 4
+  OT* Y = (OT*)a.y;
+  const float* R = a.res;
+  float bias_l[NT], mul_l[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const int co = n0 + 32 * i + lp;
+    bias_l[i] = a.bias ? a.bias[co] : 0.f;
+    mul_l[i] = co < a.q_cols ? a.q_scale : 1.f;
+  }
+  // The residual (which may be y itself: every element is read and written by the same lane) is fetched for a whole
+  // 32-row half at once, before the first store of that half: a load placed after a store that may alias it cannot
+  // be moved up by the compiler, and one round trip per element would cost more than the whole contraction.
+#pragma unroll
+  for (int j = 0; j < MR; ++j) {
+    const int64_t rbase = m0 + wid * (32 * MR) + 32 * j + 4 * hh;
+    float rv[16][NT];
+    if (R) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = min(rbase + 8 * (r >> 2) + (r & 3), a.rows - 1);
+#pragma unroll
+        for (int i = 0; i < NT; ++i) rv[r][i] = R[row * a.N + n0 + 32 * i + lp];
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t row = rbase + 8 * (r >> 2) + (r & 3);
+      if (row >= a.rows) continue;
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        float v = (acc[j][i][r] + bias_l[i]) * mul_l[i];
+        if (R) v += rv[r][i];
+        Y[row * a.N + n0 + 32 * i + lp] = from_f32<OT>(v);
+        if (sizeof(OT) == 4 && a.y2) a.y2[row * a.N + n0 + 32 * i + lp] = static_cast<bf16_t>(v);
+      }
+    }
+  }
+}
+
+// taps == 1, src == 0 of a bf16 stage with dense rows, Cin % 64 == 0 and Cout % 160 == 0 or % 128 == 0;
+// hipErrorNotSupported for what it does not cover (the general kernel then runs). Which kernel runs depends on the
+// layer's widths only, never on the number of rows: a chunked pass must give the bits of the unchunked one.
+// (hipFuncSetAttribute is called once per instantiation and process: one device.)
+template <class OT, int NT, int MR>
+static hipError_t run_lin2_mr(hipStream_t s, Lin2Args a) {
+  constexpr int lds = kStages * lin2_stage(NT, MR);
+  a.ntm = (int)((a.rows + 128 * MR - 1) / (128 * MR));
+  static bool done = false;  // per instantiation
+  if (!done) {
+    hipError_t e = hipFuncSetAttribute((const void*)lin2_kernel<OT, NT, MR>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    done = true;
+  }
+  const unsigned grid = (unsigned)((a.ntm + 7) / 8 * 8 * a.ntn);
+  lin2_kernel<OT, NT, MR><<<grid, 256, lds, s>>>(a);
+  return hipGetLastError();
+}
+// The row tile is chosen by how many tiles there are (every output element is the same sequence of MFMAs over K
+// whatever the tile it falls in: the choice never shows in the bits).
+template <class OT, int NT>
+static hipError_t run_lin2(hipStream_t s, Lin2Args a) {
+  a.ntn = a.N / (NT * 32);
+  const int64_t big_tiles = (a.rows + 255) / 256 * a.ntn;
+  return big_tiles >= 256 ? run_lin2_mr<OT, NT, 2>(s, a) : run_lin2_mr<OT, NT, 1>(s, a);
+}
+
+hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
+  if (d.dt != kBF16 || d.taps != 1 || d.src != 0 || d.yt || d.stat || d.win_w || d.planar_out) return hipErrorNotSupported;
+  if (d.Cin % 64 || d.Cin <= 0 || (d.Cout % 160 && d.Cout % 128) || d.Cout_store != d.Cout) return hipErrorNotSupported;
+  auto dense = [&](const RowMap& m) { return m.base == 0 && (m.rows_per_seg >= d.rows || m.seg_stride == m.rows_per_seg); };
+  if (!dense(d.in_map) || !dense(d.out_map)) return hipErrorNotSupported;
+  if (d.res && !d.y_f32) return hipErrorNotSupported;
+  if (d.q_cols && (d.bias || d.res)) return hipErrorInvalidValue;
+  if (d.y2 && !d.y_f32) return hipErrorInvalidValue;
+  if (d.rows <= 0) return hipSuccess;
+  if (d.rows > (int64_t)1 << 30) return hipErrorNotSupported;
+  Lin2Args a;
+  a.x = (const bf16_t*)d.x; a.w = (const bf16_t*)d.w; a.bias = d.bias; a.res = (const float*)d.res; a.y = d.y;
+  a.y2 = (bf16_t*)d.y2;
+  a.rows = d.rows; a.K = d.Cin; a.N = d.Cout;
+  a.ntm = a.ntn = 0;
+  a.q_scale = d.q_cols ? d.q_scale : 1.f; a.q_cols = d.q_cols;
+  if (d.Cout % 160 == 0) return d.y_f32 ? run_lin2<float, 5>(s, a) : run_lin2<bf16_t, 5>(s, a);
+  return d.y_f32 ? run_lin2<float, 4>(s, a) : run_lin2<bf16_t, 4>(s, a);
+}
+
+}  // namespace lc

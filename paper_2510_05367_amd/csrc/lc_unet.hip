@@ -124,6 +124,26 @@ __global__ __launch_bounds__(256) void temb_bias_kernel(const T* __restrict__ te
   if (lane == 0) out[item] = acc + bt[o] + bias[o];
 }
 
+// y[r][:] = bf16(x[r][:] * scale[f][:] + shift[f][:]), f = r / rows_per_frame: GroupNorm applied to fp32 rows and
+// rounded once, the operand of the projection into a transformer block. Thread = 8 channels of one row.
+__global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__ x, const float* __restrict__ scale,
+                                                       const float* __restrict__ shift, bf16_t* __restrict__ y, int64_t rows,
+                                                       int C8, int rows_per_frame) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * C8) return;
+  const int64_t r = i / C8;
+  const int c = (int)(i - r * C8) * 8;
+  const int64_t f = r / rows_per_frame;
+  float v[8], sc[8], sh[8];
+  load_f<float, 8>(x + r * C8 * 8 + c, v);
+  load_f<float, 8>(scale + f * C8 * 8 + c, sc);
+  load_f<float, 8>(shift + f * C8 * 8 + c, sh);
+  Vec16<bf16_t> o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o.set(e, fmaf(v[e], sc[e], sh[e]));
+  store16(y + r * C8 * 8 + c, o);
+}
+
 // dst[r][0:Ca] = a[r][:], dst[r][Ca:Ca+Cb] = b[r][:]; fp32, Ca and Cb multiples of 4; thread = one 16-byte packet
 __global__ __launch_bounds__(256) void concat_rows_kernel(const float* __restrict__ a, const float* __restrict__ b,
                                                           float* __restrict__ dst, int64_t rows, int Ca4, int Cb4) {
@@ -305,12 +325,12 @@ lc_status conv(lc_unet* c, const ConvP& w, const float* bias, int src, int Cin, 
 // y[rows][Cout] = x[rows][Cin] W^T + bias [+ res]. src 0: x of the operand type; src 1: x fp32, multiplied by
 // scale[frame] and shifted (GroupNorm apply; unit = 1: taken as it is), frame = row / rows_per_frame.
 lc_status linear(lc_unet* c, const LinP& w, int Cin, int Cout, int64_t rows, int src, int unit, int rows_per_frame, const void* x,
-                 const float* res, void* y, int y32) {
+                 const float* res, void* y, int y32, void* y2 = nullptr) {
   const UPlan& p = c->plan;
   FusedDesc f;
   memset(&f, 0, sizeof f);
   f.dt = c->cfg.dtype; f.y_f32 = y32; f.taps = 1; f.src = src; f.Cin = Cin; f.Cout = Cout; f.Cout_store = Cout; f.w = w.w; f.bias = w.b;
-  f.rows = rows; f.in_map = f.out_map = dense_map(); f.x = x; f.res = res; f.y = y;
+  f.rows = rows; f.in_map = f.out_map = dense_map(); f.x = x; f.res = res; f.y = y; f.y2 = y2;
   if (src == 1) {
     f.in_map = RowMap{0, rows_per_frame, rows_per_frame};
     f.scale = (const float*)(c->arena + (unit ? p.off_one : p.off_scale));
@@ -332,7 +352,8 @@ lc_status ln(lc_unet* c, const float* z, const NormP& w, const float* pe, void* 
 }
 
 // z += FF(LN(z)): GEGLU feed-forward on fp32 rows z, in place
-lc_status feed_forward(lc_unet* c, const TfP& w, float* z, int64_t rows, int rows_per_frame) {
+// (zb: where a bf16 stage also leaves the new z rounded to bf16, the operand of the projection out; or nullptr)
+lc_status feed_forward(lc_unet* c, const TfP& w, float* z, int64_t rows, int rows_per_frame, void* zb) {
   const lc_unet_config& g = c->cfg;
   const UPlan& p = c->plan;
   const int C = w.C, M = g.ff_mult * C;
@@ -343,7 +364,7 @@ lc_status feed_forward(lc_unet* c, const TfP& w, float* z, int64_t rows, int row
   if (g.dtype == kBF16) geglu_kernel<bf16_t><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((const bf16_t*)u, (bf16_t*)gl, rows, M);
   else geglu_kernel<float><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((const float*)u, (float*)gl, rows, M);
   LCU_HIP(c, hipGetLastError());
-  return linear(c, w.ff2, M, C, rows, 0, 0, 0, gl, z, z, 1);
+  return linear(c, w.ff2, M, C, rows, 0, 0, 0, gl, z, z, 1, zb);
 }
 
 // Residual block: x [N][P][cin] fp32 -> y [N][P][cout] fp32 (y distinct from x); h and sc are work maps.
@@ -363,7 +384,18 @@ lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int H, int W, co
                  h + (size_t)b * g.F * P * w.cout, 0, w.cout));
   const float* res = x;
   if (w.shortcut.w) {
-    LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, (int64_t)N * P, 1, 1, P, x, nullptr, sc, 1));
+    const int64_t rows = (int64_t)N * P;
+    if (g.dtype == kBF16 && w.cout % 160 == 0 && w.cin % 64 == 0 && (size_t)rows * w.cin <= (size_t)N * g.H * g.W * g.C * 2 * g.ff_mult) {
+      // x rounded to bf16 in a pass of its own (into the feed-forward's buffer, idle here), then dense bf16 rows
+      bf16_t* xb = (bf16_t*)(c->arena + c->plan.off_u);
+      const int64_t n = rows * (w.cin / 8);
+      gn_apply_kernel<<<(unsigned)((n + 255) / 256), 256, 0, c->cs>>>(x, (const float*)(c->arena + c->plan.off_one),
+                                                                     (const float*)(c->arena + c->plan.off_zero), xb, rows, w.cin / 8, P);
+      LCU_HIP(c, hipGetLastError());
+      LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, rows, 0, 0, 0, xb, nullptr, sc, 1));
+    } else {
+      LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, rows, 1, 1, P, x, nullptr, sc, 1));
+    }
     res = sc;
   }
   LCU_TRY(gn(c, h, N, P, w.cout, w.gn2));
@@ -380,7 +412,18 @@ lc_status tf_block(lc_unet* c, const TfP& w, const void* cond, int H, int W, flo
   const size_t es = dtype_size(g.dtype);
   char *a = c->arena + p.off_a, *qkv = c->arena + p.off_qkv, *vt = c->arena + p.off_vt, *ao = c->arena + p.off_ao;
   LCU_TRY(gn(c, x, N, P, C, w.gn));
-  LCU_TRY(linear(c, w.pin, C, C, rows, 1, 0, P, x, nullptr, z, 1));
+  // where the dense-row kernel applies (bf16, width a multiple of 160) the projections' operands are rounded in
+  // passes of their own and contracted as dense bf16 rows; otherwise they are converted inside the contraction
+  const bool b16 = g.dtype == kBF16 && C % 160 == 0;
+  if (b16) {
+    const int64_t n = rows * (C / 8);
+    gn_apply_kernel<<<(unsigned)((n + 255) / 256), 256, 0, c->cs>>>(x, (const float*)(c->arena + p.off_scale),
+                                                                   (const float*)(c->arena + p.off_shift), (bf16_t*)a, rows, C / 8, P);
+    LCU_HIP(c, hipGetLastError());
+    LCU_TRY(linear(c, w.pin, C, C, rows, 0, 0, 0, a, nullptr, z, 1));
+  } else {
+    LCU_TRY(linear(c, w.pin, C, C, rows, 1, 0, P, x, nullptr, z, 1));
+  }
   // self-attention
   LCU_TRY(ln(c, z, w.ln1, w.pe, a, rows, C, P));
   LCU_TRY(linear(c, w.qkv, C, 3 * C, rows, 0, 0, 0, a, nullptr, qkv, 0));
@@ -402,7 +445,8 @@ lc_status tf_block(lc_unet* c, const TfP& w, const void* cond, int H, int W, flo
     LCU_HIP(c, launch_cross_attention(c->cs, g.dtype, qkv, C, kv, 2 * C, vtx, TpL, ao, N, P, L, g.F, heads, g.head_dim));
     LCU_TRY(linear(c, w.wo2, C, C, rows, 0, 0, 0, ao, z, z, 1));
   }
-  LCU_TRY(feed_forward(c, w, z, rows, P));
+  LCU_TRY(feed_forward(c, w, z, rows, P, b16 ? a : nullptr));
+  if (b16) return linear(c, w.pout, C, C, rows, 0, 0, 0, a, x, x, 1);
   return linear(c, w.pout, C, C, rows, 1, 1, P, z, x, x, 1);
 }
 
