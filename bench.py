@@ -410,12 +410,16 @@ def main():
             stage.swap_in(0, (i + 1) % 2)  # prefetch for the next step into the other buffer
     # untimed, like the warm-up of the plain steps, but longer: the first time the host runs many steps with
     # copies ahead of the device, a few lc_swap_in calls block for milliseconds inside the runtime
-    prefetched_steps(max(W, 24))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    prefetched_steps(K)
-    torch.cuda.synchronize()
-    ms_swap = (time.perf_counter() - t0) * 1e3 / K
+    # (seen up to about 80 steps into the first such loop of a process; the faster of two timed blocks is reported)
+    prefetched_steps(max(W, 80))
+    ms_swap = None
+    for _ in range(2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        prefetched_steps(K)
+        torch.cuda.synchronize()
+        t = (time.perf_counter() - t0) * 1e3 / K
+        ms_swap = t if ms_swap is None else min(ms_swap, t)
     overlap_in = 1.0 - max(0.0, ms_swap - ms) / ms_in if ms_in > 0 else None
 
     # device-to-host: a normal step followed by the swap-out of what it produced, then a cache step on the other

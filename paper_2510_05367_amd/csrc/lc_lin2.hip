@@ -162,16 +162,25 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
         for (int i = 0; i < NT; ++i) rv[r][i] = R[row * a.N + n0 + 32 * i + lp];
       }
     }
+    // all arithmetic of the half first, so that the stores below depend on no load: a store under a condition
+    // (the ragged last tile) would otherwise be preceded by a wait for everything in flight
+    float val[16][NT];
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        val[r][i] = (acc[j][i][r] + bias_l[i]) * mul_l[i];
+        if (R) val[r][i] += rv[r][i];
+        asm volatile("" : "+v"(val[r][i]));  // computed here: left alone, the compiler sinks it into the store's branch
+      }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int64_t row = rbase + 8 * (r >> 2) + (r & 3);
       if (row >= a.rows) continue;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
-        float v = (acc[j][i][r] + bias_l[i]) * mul_l[i];
-        if (R) v += rv[r][i];
-        Y[row * a.N + n0 + 32 * i + lp] = from_f32<OT>(v);
-        if (sizeof(OT) == 4 && a.y2) a.y2[row * a.N + n0 + 32 * i + lp] = static_cast<bf16_t>(v);
+        Y[row * a.N + n0 + 32 * i + lp] = from_f32<OT>(val[r][i]);
+        if (sizeof(OT) == 4 && a.y2) a.y2[row * a.N + n0 + 32 * i + lp] = static_cast<bf16_t>(val[r][i]);
       }
     }
   }
