@@ -713,7 +713,7 @@ hipError_t launch_fused(hipStream_t s, const FusedDesc& d) {
     const hipError_t e = launch_lin2(s, d);
     if (e != hipErrorNotSupported) return e;
   }
-  if (d.y2) return hipErrorInvalidValue;  // only that kernel writes the rounded copy
+  if (d.y2 || d.act) return hipErrorInvalidValue;  // only that kernel writes the rounded copy / applies an activation
   return d.dt == kBF16 ? by_kind<bf16_t>(s, d) : by_kind<float>(s, d);
 }
 

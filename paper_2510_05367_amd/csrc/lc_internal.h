@@ -100,6 +100,9 @@ struct FusedDesc {
   const void* res;     // fp32, indexed like y; nullptr if none; may equal y only when taps == 1
   void* y;
   int planar_out;      // 1: y is [frame][Cout_store][H][W] of the operand type (Cout = 32, zero-padded w)
+  int act;             // taps == 1, src == 0 of a bf16 stage over dense rows, operand-type y, no residual only:
+                       // 0 none; 1: y = gelu_tanh(x W^T + b); 2 (GEGLU): the rows of W come in alternating blocks of 32
+                       // "value" and 32 "gate" channels and y, Cout / 2 wide, is value * gelu_tanh(gate)
   void* y2;            // taps == 1, src == 0, fp32 y of a bf16 stage over dense rows only: a copy of y rounded to the
                        // operand type (what the next layer contracts), or nullptr
   // taps == 1 only: output channels >= yt_from are not stored in y (whose rows then have yt_from

@@ -38,6 +38,7 @@ struct Lin2Args {
   int K, N, ntm, ntn;
   float q_scale;       // channels below q_cols are multiplied by this before they are rounded
   int q_cols;
+  int act;             // 0 none, 1 GELU, 2 GEGLU over alternating 32-channel blocks (y is then N / 2 wide)
 };
 
 }  // namespace
@@ -171,8 +172,28 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
       for (int i = 0; i < NT; ++i) {
         val[r][i] = (acc[j][i][r] + bias_l[i]) * mul_l[i];
         if (R) val[r][i] += rv[r][i];
+        if (sizeof(OT) == 2 && a.act == 1) val[r][i] = gelu_tanh_fast(val[r][i]);
         asm volatile("" : "+v"(val[r][i]));  // computed here: left alone, the compiler sinks it into the store's branch
       }
+    if constexpr (sizeof(OT) == 2 && NT % 2 == 0) {
+      if (a.act == 2) {  // GEGLU: column tile 2 q holds 32 values, tile 2 q + 1 their gates; N / 2 channels leave
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+#pragma unroll
+          for (int q = 0; q < NT / 2; ++q) {
+            val[r][q] = val[r][2 * q] * gelu_tanh_fast(val[r][2 * q + 1]);
+            asm volatile("" : "+v"(val[r][q]));
+          }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t row = rbase + 8 * (r >> 2) + (r & 3);
+          if (row >= a.rows) continue;
+#pragma unroll
+          for (int q = 0; q < NT / 2; ++q) Y[row * (a.N / 2) + n0 / 2 + 32 * q + lp] = from_f32<OT>(val[r][q]);
+        }
+        continue;
+      }
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int64_t row = rbase + 8 * (r >> 2) + (r & 3);
@@ -221,6 +242,8 @@ hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
   if (d.res && !d.y_f32) return hipErrorNotSupported;
   if (d.q_cols && (d.bias || d.res)) return hipErrorInvalidValue;
   if (d.y2 && !d.y_f32) return hipErrorInvalidValue;
+  if (d.act && (d.y_f32 || d.res || d.q_cols || d.act > 2)) return hipErrorInvalidValue;
+  if (d.act == 2 && d.Cout % 128) return hipErrorNotSupported;
   if (d.rows <= 0) return hipSuccess;
   if (d.rows > (int64_t)1 << 30) return hipErrorNotSupported;
   Lin2Args a;
@@ -229,6 +252,8 @@ hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
   a.rows = d.rows; a.K = d.Cin; a.N = d.Cout;
   a.ntm = a.ntn = 0;
   a.q_scale = d.q_cols ? d.q_scale : 1.f; a.q_cols = d.q_cols;
+  a.act = d.act;
+  if (d.act == 2) return run_lin2<bf16_t, 4>(s, a);  // (an even number of column tiles: value / gate pairs)
   if (d.Cout % 160 == 0) return d.y_f32 ? run_lin2<float, 5>(s, a) : run_lin2<bf16_t, 5>(s, a);
   return d.y_f32 ? run_lin2<float, 4>(s, a) : run_lin2<bf16_t, 4>(s, a);
 }

@@ -87,11 +87,6 @@ __global__ __launch_bounds__(256) void ln_affine_kernel(const float* __restrict_
   }
 }
 
-__device__ __forceinline__ float gelu_tanh_u(float x) {
-  const float u = 0.7978845608028654f * fmaf(0.044715f * x * x, x, x);
-  const float t = 1.f - 2.f / (1.f + __expf(2.f * u));  // tanh(u)
-  return 0.5f * x * (1.f + t);
-}
 // g[r][k] = u[r][k] * gelu_tanh(u[r][M + k]); u [rows][2M], g [rows][M]; thread = one 16-byte packet of g
 template <class T>
 __global__ __launch_bounds__(256) void geglu_kernel(const T* __restrict__ u, T* __restrict__ g, int64_t rows, int M) {
@@ -104,7 +99,7 @@ __global__ __launch_bounds__(256) void geglu_kernel(const T* __restrict__ u, T* 
   const Vec16<T> a = load16(u + r * 2 * M + k), b = load16(u + r * 2 * M + M + k);
   Vec16<T> o;
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) o.set(e, a.get(e) * gelu_tanh_u(b.get(e)));
+  for (int e = 0; e < VEC; ++e) o.set(e, a.get(e) * gelu_tanh_f(b.get(e)));
   store16(g + r * M + k, o);
 }
 
@@ -170,6 +165,7 @@ struct NormP { float *g, *b; };
 struct RbP { int cin, cout; NormP gn1, gn2; ConvP conv1, conv2; float *temb_w, *temb_b; LinP shortcut; };
 struct TfP {
   int C; bool cross;
+  bool ff_fused;  // ff1's rows are stored in alternating blocks of 32 value and 32 gate channels: its kernel applies the GEGLU
   NormP gn, ln1, ln2, ln3;
   LinP pin, qkv, wo1, q2, kv2, wo2, ff1, ff2, pout;
   float* pe;  // [F][C] (temporal blocks)
@@ -325,12 +321,12 @@ lc_status conv(lc_unet* c, const ConvP& w, const float* bias, int src, int Cin, 
 // y[rows][Cout] = x[rows][Cin] W^T + bias [+ res]. src 0: x of the operand type; src 1: x fp32, multiplied by
 // scale[frame] and shifted (GroupNorm apply; unit = 1: taken as it is), frame = row / rows_per_frame.
 lc_status linear(lc_unet* c, const LinP& w, int Cin, int Cout, int64_t rows, int src, int unit, int rows_per_frame, const void* x,
-                 const float* res, void* y, int y32, void* y2 = nullptr) {
+                 const float* res, void* y, int y32, void* y2 = nullptr, int act = 0) {
   const UPlan& p = c->plan;
   FusedDesc f;
   memset(&f, 0, sizeof f);
   f.dt = c->cfg.dtype; f.y_f32 = y32; f.taps = 1; f.src = src; f.Cin = Cin; f.Cout = Cout; f.Cout_store = Cout; f.w = w.w; f.bias = w.b;
-  f.rows = rows; f.in_map = f.out_map = dense_map(); f.x = x; f.res = res; f.y = y; f.y2 = y2;
+  f.rows = rows; f.in_map = f.out_map = dense_map(); f.x = x; f.res = res; f.y = y; f.y2 = y2; f.act = act;
   if (src == 1) {
     f.in_map = RowMap{0, rows_per_frame, rows_per_frame};
     f.scale = (const float*)(c->arena + (unit ? p.off_one : p.off_scale));
@@ -359,6 +355,10 @@ lc_status feed_forward(lc_unet* c, const TfP& w, float* z, int64_t rows, int row
   const int C = w.C, M = g.ff_mult * C;
   char *a = c->arena + p.off_a, *u = c->arena + p.off_u, *gl = c->arena + p.off_g;
   LCU_TRY(ln(c, z, w.ln3, nullptr, a, rows, C, rows_per_frame));
+  if (w.ff_fused) {  // value * gelu(gate) in the first layer's epilogue: the 2M-wide tensor never exists
+    LCU_TRY(linear(c, w.ff1, C, 2 * M, rows, 0, 0, 0, a, nullptr, gl, 0, nullptr, 2));
+    return linear(c, w.ff2, M, C, rows, 0, 0, 0, gl, z, z, 1, zb);
+  }
   LCU_TRY(linear(c, w.ff1, C, 2 * M, rows, 0, 0, 0, a, nullptr, u, 0));
   const int64_t n16 = rows * M * (int64_t)dtype_size(g.dtype) / 16;
   if (g.dtype == kBF16) geglu_kernel<bf16_t><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((const bf16_t*)u, (bf16_t*)gl, rows, M);
@@ -654,6 +654,21 @@ lc_status lc_unet_load_weights(lc_unet* c, const lc_unet_weights* w) {
     }
     return q;
   };
+  // the first feed-forward layer of a bf16 stage: rows [0, M) are the values, [M, 2M) the gates; stored as
+  // value block 0, gate block 0, value block 1, ... (blocks of 32 rows), the order the fused GEGLU epilogue pairs
+  auto lin_geglu = [&](const void* wsrc, const void* bsrc, int M, int cin) {
+    LinP q;
+    q.w = take((size_t)2 * M * cin * es);
+    q.b = (float*)take((size_t)2 * M * 4);
+    if (fill)
+      for (int m = 0; m < M / 32; ++m)
+        for (int h = 0; h < 2; ++h) {
+          const size_t srow = (size_t)h * M + 32 * m, drow = (size_t)64 * m + 32 * h;
+          note(launch_copy_rows(s, dt, (const char*)wsrc + srow * cin * es, (char*)q.w + drow * cin * es, (int64_t)32 * cin));
+          note(launch_to_f32(s, dt, (const char*)bsrc + srow * es, q.b + drow, 32, 32));
+        }
+    return q;
+  };
   auto conv3 = [&](const void* wsrc, const void* bsrc, int cout, int cin, int cout_pad, bool tiles) {
     ConvP q;
     q.w = take((size_t)cout_pad * 9 * cin * es);
@@ -705,7 +720,8 @@ lc_status lc_unet_load_weights(lc_unet* c, const lc_unet_weights* w) {
           q.wo2 = lin(t.attn2.wo, t.attn2.bo, D, D);
         }
         q.ln3 = norm(t.ln3_g, t.ln3_b, D);
-        q.ff1 = lin(t.ff1_w, t.ff1_b, 2 * M, D);
+        q.ff_fused = dt == kBF16;
+        q.ff1 = q.ff_fused ? lin_geglu(t.ff1_w, t.ff1_b, M, D) : lin(t.ff1_w, t.ff1_b, 2 * M, D);
         q.ff2 = lin(t.ff2_w, t.ff2_b, D, M);
         q.pout = lin(t.pout_w, t.pout_b, D, D);
         q.pe = nullptr;
