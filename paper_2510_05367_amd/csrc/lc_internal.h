@@ -142,8 +142,8 @@ hipError_t launch_fused(hipStream_t s, const FusedDesc& d);
 // taps == 9 of a bf16 stage with specialised wavefronts (lc_convws.hip): the same results as the general
 // kernel bit for bit; hipErrorNotSupported for shapes it does not cover. launch_fused tries it first.
 hipError_t launch_conv_ws(hipStream_t s, const FusedDesc& d);
-// taps == 1, src == 0 of a bf16 stage over dense rows (lc_lin2.hip: 256 x 160 tiles, operands streamed through a ring
-// of LDS stages); hipErrorNotSupported for shapes it does not cover. launch_fused tries it first.
+// taps == 1, src == 0 of a bf16 stage (lc_lin2.hip: 256 x 160 tiles, operands streamed through a ring of LDS stages);
+// hipErrorNotSupported for widths it does not cover, never because of the rows. launch_fused tries it first.
 hipError_t launch_lin2(hipStream_t s, const FusedDesc& d);
 // taps == 1 with the weights resident in registers (needs w_frag); hipErrorNotSupported for shapes it does not cover
 hipError_t launch_linear(hipStream_t s, const FusedDesc& d);

@@ -39,6 +39,7 @@ struct Lin2Args {
   float q_scale;       // channels below q_cols are multiplied by this before they are rounded
   int q_cols;
   int act;             // 0 none, 1 GELU, 2 GEGLU over alternating 32-channel blocks (y is then N / 2 wide)
+  RowMap in_map, out_map;  // dense row r is row in_map(r) of x and row out_map(r) of y / res / y2
 };
 
 }  // namespace
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
   for (int j = 0; j < kXI; ++j) {
     const int r = (wid + 4 * j) * 8 + lrow;
     const int c = (lane & 7) ^ ((r >> 1) & 7);
-    const int64_t gr = min(m0 + r, a.rows - 1);  // rows beyond the end: a valid row, never stored
+    const int64_t gr = a.in_map(min(m0 + r, a.rows - 1));  // rows beyond the end: a valid row, never stored
     xsrc[j] = a.x + gr * a.K + c * 8;
   }
 #pragma unroll
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
     if (R) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t row = min(rbase + 8 * (r >> 2) + (r & 3), a.rows - 1);
+        const int64_t row = a.out_map(min(rbase + 8 * (r >> 2) + (r & 3), a.rows - 1));
 #pragma unroll
         for (int i = 0; i < NT; ++i) rv[r][i] = R[row * a.N + n0 + 32 * i + lp];
       }
@@ -186,8 +187,9 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
           }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int64_t row = rbase + 8 * (r >> 2) + (r & 3);
-          if (row >= a.rows) continue;
+          const int64_t dr = rbase + 8 * (r >> 2) + (r & 3);
+          if (dr >= a.rows) continue;
+          const int64_t row = a.out_map(dr);
 #pragma unroll
           for (int q = 0; q < NT / 2; ++q) Y[row * (a.N / 2) + n0 / 2 + 32 * q + lp] = from_f32<OT>(val[r][q]);
         }
@@ -196,8 +198,9 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int64_t row = rbase + 8 * (r >> 2) + (r & 3);
-      if (row >= a.rows) continue;
+      const int64_t dr = rbase + 8 * (r >> 2) + (r & 3);
+      if (dr >= a.rows) continue;
+      const int64_t row = a.out_map(dr);
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
         Y[row * a.N + n0 + 32 * i + lp] = from_f32<OT>(val[r][i]);
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
   }
 }
 
-// taps == 1, src == 0 of a bf16 stage with dense rows, Cin % 64 == 0 and Cout % 160 == 0 or % 128 == 0;
+// taps == 1, src == 0 of a bf16 stage, Cin % 64 == 0 and Cout % 160 == 0 or % 128 == 0 (rows through any row map);
 // hipErrorNotSupported for what it does not cover (the general kernel then runs). Which kernel runs depends on the
 // layer's widths only, never on the number of rows: a chunked pass must give the bits of the unchunked one.
 // (hipFuncSetAttribute is called once per instantiation and process: one device.)
@@ -237,8 +240,7 @@ static hipError_t run_lin2(hipStream_t s, Lin2Args a) {
 hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
   if (d.dt != kBF16 || d.taps != 1 || d.src != 0 || d.yt || d.stat || d.win_w || d.planar_out) return hipErrorNotSupported;
   if (d.Cin % 64 || d.Cin <= 0 || (d.Cout % 160 && d.Cout % 128) || d.Cout_store != d.Cout) return hipErrorNotSupported;
-  auto dense = [&](const RowMap& m) { return m.base == 0 && (m.rows_per_seg >= d.rows || m.seg_stride == m.rows_per_seg); };
-  if (!dense(d.in_map) || !dense(d.out_map)) return hipErrorNotSupported;
+  if (d.in_map.rows_per_seg <= 0 || d.out_map.rows_per_seg <= 0) return hipErrorInvalidValue;
   if (d.res && !d.y_f32) return hipErrorNotSupported;
   if (d.q_cols && (d.bias || d.res)) return hipErrorInvalidValue;
   if (d.y2 && !d.y_f32) return hipErrorInvalidValue;
@@ -253,6 +255,7 @@ hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
   a.ntm = a.ntn = 0;
   a.q_scale = d.q_cols ? d.q_scale : 1.f; a.q_cols = d.q_cols;
   a.act = d.act;
+  a.in_map = d.in_map; a.out_map = d.out_map;
   if (d.act == 2) return run_lin2<bf16_t, 4>(s, a);  // (an even number of column tiles: value / gate pairs)
   if (d.Cout % 160 == 0) return d.y_f32 ? run_lin2<float, 5>(s, a) : run_lin2<bf16_t, 5>(s, a);
   return d.y_f32 ? run_lin2<float, 4>(s, a) : run_lin2<bf16_t, 4>(s, a);
