@@ -330,6 +330,8 @@ def main():
                     help="warm-up and the timed steps only, then a short JSON line (the command rocprofv3 is pointed at)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain device copy of 256 MiB three times (reference for hardware byte counters)")
+    ap.add_argument("--only", default=None, choices=["sliced_decode", "video_dit", "unet"],
+                    help="run one of the further records alone and print it (the command rocprofv3 is pointed at for them)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -343,6 +345,11 @@ def main():
     if not os.path.exists(lcb.LIB_PATH):
         from paper_2510_05367_amd import build as lcbuild
         lcbuild.build_library()
+    if args.only:
+        fn = {"sliced_decode": decode_record, "video_dit": dit_record, "unet": unet_record}[args.only]
+        kw = {"steps_only": True} if (args.only == "unet" and args.steps_only) else {}
+        print(json.dumps({args.only: fn(lcb, torch, synth, **kw)}))
+        return
 
     cfg = synth.CONFIGS[args.workload]
     fc = cfg.frame_chunk if args.frame_chunk is None else args.frame_chunk
@@ -712,7 +719,7 @@ def dit_record(lcb, torch, synth, steps=6):
         torch.cuda.empty_cache()
 
 
-def unet_record(lcb, torch, synth, steps=5):
+def unet_record(lcb, torch, synth, steps=5, steps_only=False):
     """The U-Net with real block internals (time-embedding residual blocks, transformer blocks with cross-attention
     and GEGLU, frame encoding, three-level deep branch): normal and cache step, and schedules with a normal step every
     `interval` steps, the cached feature swapped out and prefetched one step ahead."""
@@ -744,6 +751,8 @@ def unet_record(lcb, torch, synth, steps=5):
                "cache_step_tflops": round(cfg.cached_step_flops() / (ms_cached * 1e-3) / 1e12, 1),
                "entry_mb": round(lcb.lc_unet_entry_bytes(net.ccfg) / 1e6, 1),
                "workspace_gb": round(lcb.lc_unet_workspace_bytes(net.ccfg) / 1e9, 4), "schedules": []}
+        if steps_only:  # what a kernel trace is pointed at: 1 + steps normal steps, then as many cache steps
+            return rec
         n_steps = 12
 
         def schedule(interval, swapping):
