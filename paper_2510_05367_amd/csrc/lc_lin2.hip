@@ -44,7 +44,9 @@ struct Lin2Args {
 
 }  // namespace
 
-template <class OT, int NT, int MR>
+// MAPPED: rows go through the row maps (a 64-bit division per row: kept out of the common, dense case, where the
+// host folds the maps' offsets into the pointers; the arithmetic, and so every bit of the result, is the same)
+template <class OT, int NT, int MR, bool MAPPED>
 __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
   typedef Mma32<bf16_t> M;
   constexpr int kM = 128 * MR, kN = NT * 32, kStage = lin2_stage(NT, MR);
@@ -69,7 +71,8 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
   for (int j = 0; j < kXI; ++j) {
     const int r = (wid + 4 * j) * 8 + lrow;
     const int c = (lane & 7) ^ ((r >> 1) & 7);
-    const int64_t gr = a.in_map(min(m0 + r, a.rows - 1));  // rows beyond the end: a valid row, never stored
+    int64_t gr = min(m0 + r, a.rows - 1);  // rows beyond the end: a valid row, never stored
+    if (MAPPED) gr = a.in_map(gr);
     xsrc[j] = a.x + gr * a.K + c * 8;
   }
 #pragma unroll
@@ -159,7 +162,8 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
     if (R) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t row = a.out_map(min(rbase + 8 * (r >> 2) + (r & 3), a.rows - 1));
+        int64_t row = min(rbase + 8 * (r >> 2) + (r & 3), a.rows - 1);
+        if (MAPPED) row = a.out_map(row);
 #pragma unroll
         for (int i = 0; i < NT; ++i) rv[r][i] = R[row * a.N + n0 + 32 * i + lp];
       }
@@ -189,7 +193,7 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
         for (int r = 0; r < 16; ++r) {
           const int64_t dr = rbase + 8 * (r >> 2) + (r & 3);
           if (dr >= a.rows) continue;
-          const int64_t row = a.out_map(dr);
+          const int64_t row = MAPPED ? a.out_map(dr) : dr;
 #pragma unroll
           for (int q = 0; q < NT / 2; ++q) Y[row * (a.N / 2) + n0 / 2 + 32 * q + lp] = from_f32<OT>(val[r][q]);
         }
@@ -200,7 +204,7 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
     for (int r = 0; r < 16; ++r) {
       const int64_t dr = rbase + 8 * (r >> 2) + (r & 3);
       if (dr >= a.rows) continue;
-      const int64_t row = a.out_map(dr);
+      const int64_t row = MAPPED ? a.out_map(dr) : dr;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
         Y[row * a.N + n0 + 32 * i + lp] = from_f32<OT>(val[r][i]);
@@ -214,19 +218,32 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
 // hipErrorNotSupported for what it does not cover (the general kernel then runs). Which kernel runs depends on the
 // layer's widths only, never on the number of rows: a chunked pass must give the bits of the unchunked one.
 // (hipFuncSetAttribute is called once per instantiation and process: one device.)
-template <class OT, int NT, int MR>
-static hipError_t run_lin2_mr(hipStream_t s, Lin2Args a) {
+template <class OT, int NT, int MR, bool MAPPED>
+static hipError_t run_lin2_k(hipStream_t s, const Lin2Args& a) {
   constexpr int lds = kStages * lin2_stage(NT, MR);
-  a.ntm = (int)((a.rows + 128 * MR - 1) / (128 * MR));
   static bool done = false;  // per instantiation
   if (!done) {
-    hipError_t e = hipFuncSetAttribute((const void*)lin2_kernel<OT, NT, MR>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = hipFuncSetAttribute((const void*)lin2_kernel<OT, NT, MR, MAPPED>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     done = true;
   }
   const unsigned grid = (unsigned)((a.ntm + 7) / 8 * 8 * a.ntn);
-  lin2_kernel<OT, NT, MR><<<grid, 256, lds, s>>>(a);
+  lin2_kernel<OT, NT, MR, MAPPED><<<grid, 256, lds, s>>>(a);
   return hipGetLastError();
+}
+template <class OT, int NT, int MR>
+static hipError_t run_lin2_mr(hipStream_t s, Lin2Args a) {
+  a.ntm = (int)((a.rows + 128 * MR - 1) / (128 * MR));
+  // a map that is the identity up to an offset (one segment, or segments that follow each other) is folded into
+  // the pointers
+  auto plain = [&](const RowMap& m) { return m.rows_per_seg >= a.rows || m.seg_stride == m.rows_per_seg; };
+  if (!plain(a.in_map) || !plain(a.out_map)) return run_lin2_k<OT, NT, MR, true>(s, a);
+  const int64_t nout = a.act == 2 ? a.N / 2 : a.N;
+  a.x += a.in_map.base * a.K;
+  a.y = (OT*)a.y + a.out_map.base * nout;
+  if (a.res) a.res += a.out_map.base * nout;
+  if (a.y2) a.y2 += a.out_map.base * nout;
+  return run_lin2_k<OT, NT, MR, false>(s, a);
 }
 // The row tile is chosen by how many tiles there are (every output element is the same sequence of MFMAs over K
 // whatever the tile it falls in: the choice never shows in the bits).

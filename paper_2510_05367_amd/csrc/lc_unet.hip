@@ -321,12 +321,13 @@ lc_status conv(lc_unet* c, const ConvP& w, const float* bias, int src, int Cin, 
 // y[rows][Cout] = x[rows][Cin] W^T + bias [+ res]. src 0: x of the operand type; src 1: x fp32, multiplied by
 // scale[frame] and shifted (GroupNorm apply; unit = 1: taken as it is), frame = row / rows_per_frame.
 lc_status linear(lc_unet* c, const LinP& w, int Cin, int Cout, int64_t rows, int src, int unit, int rows_per_frame, const void* x,
-                 const float* res, void* y, int y32, void* y2 = nullptr, int act = 0) {
+                 const float* res, void* y, int y32, void* y2 = nullptr, int act = 0, int q_cols = 0) {
   const UPlan& p = c->plan;
   FusedDesc f;
   memset(&f, 0, sizeof f);
   f.dt = c->cfg.dtype; f.y_f32 = y32; f.taps = 1; f.src = src; f.Cin = Cin; f.Cout = Cout; f.Cout_store = Cout; f.w = w.w; f.bias = w.b;
   f.rows = rows; f.in_map = f.out_map = dense_map(); f.x = x; f.res = res; f.y = y; f.y2 = y2; f.act = act;
+  if (q_cols) { f.q_cols = q_cols; f.q_scale = attn_q_scale(c->cfg.head_dim); }  // softmax scale folded into q
   if (src == 1) {
     f.in_map = RowMap{0, rows_per_frame, rows_per_frame};
     f.scale = (const float*)(c->arena + (unit ? p.off_one : p.off_scale));
@@ -426,11 +427,13 @@ lc_status tf_block(lc_unet* c, const TfP& w, const void* cond, int H, int W, flo
   }
   // self-attention
   LCU_TRY(ln(c, z, w.ln1, w.pe, a, rows, C, P));
-  LCU_TRY(linear(c, w.qkv, C, 3 * C, rows, 0, 0, 0, a, nullptr, qkv, 0));
+  // (spatial: the q columns leave the projection multiplied by log2(e) / sqrt(d), as the attention kernel's
+  // cheaper softmax path wants them)
+  LCU_TRY(linear(c, w.qkv, C, 3 * C, rows, 0, 0, 0, a, nullptr, qkv, 0, nullptr, 0, w.cross ? C : 0));
   if (w.cross) {
     const int Tp = attn_tp(P);
     LCU_HIP(c, launch_make_vt(c->cs, g.dtype, qkv + (size_t)2 * C * es, 3 * C, vt, N, P, Tp, C));
-    LCU_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * C, vt, Tp, ao, N, P, heads, g.head_dim, 0, P, 0));
+    LCU_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * C, vt, Tp, ao, N, P, heads, g.head_dim, 0, P, 1));
   } else {
     LCU_HIP(c, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, P, heads, g.head_dim));
   }

@@ -25,8 +25,8 @@ def asm(tmp_path_factory):
 
 
 def kernels(asm):
-    names = re.findall(r"^(_ZN2lc11lin2_kernelI(?:f|DF16b)Li(\d)ELi(\d)E[^:\n]*):", asm, flags=re.M)
-    assert len(names) == 8  # {fp32, bf16 output} x {160, 128 channels} x {256, 128 rows}
+    names = re.findall(r"^(_ZN2lc11lin2_kernelI(?:f|DF16b)Li(\d)ELi(\d)ELb[01]E[^:\n]*):", asm, flags=re.M)
+    assert len(names) == 16  # {fp32, bf16 output} x {160, 128 channels} x {256, 128 rows} x {dense, mapped rows}
     for name, nt, mr in names:
         start = asm.index("\n" + name + ":")
         yield name, int(nt), int(mr), asm[start:asm.index(".Lfunc_end", start)]
