@@ -201,6 +201,20 @@ def roofline_of(lcb, torch, stage, cfg, fc, family, step, K, peak):
         achieved = work / (avg_ms * 1e-3) / 1e9
         r = {"kernel": family, "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
              "frac": round(achieved / PEAK_HBM_GBS, 4), "bytes_per_launch": work}
+    if family == "sattn":
+        # context for the MFMA fraction: the kernel also issues one v_exp_f32 per score, on the quarter-rate
+        # transcendental unit (256 CUs x 4 SIMDs x 4 lanes per clock at 2.4 GHz = 9.83e12 per second), and pads the
+        # head size to MFMA tiles (contraction of K Q^T to a multiple of 16, rows of V^T to a multiple of 32)
+        frames = work / (4.0 * cfg.T * cfg.T * cfg.head_dim * cfg.heads)
+        exps = frames * cfg.heads * cfg.T * cfg.T
+        pad_qk = (cfg.head_dim + 15) // 16 * 16
+        pad_pv = (cfg.head_dim + 31) // 32 * 32
+        padded = frames * cfg.heads * 2.0 * cfg.T * cfg.T * (pad_qk + pad_pv)
+        r["context"] = {"exp_per_launch": exps, "exp_floor_ms": round(exps / 9.83e12 * 1e3, 5),
+                        "executed_flops_per_launch": padded, "mfma_floor_ms": round(padded / (peak * 1e12) * 1e3, 5),
+                        "note": "the counter summary under profiles/ shows the matrix pipe and the transcendental unit "
+                                "taking turns (42 % and 48 % busy): the sum of the two floors is what the kernel "
+                                "is measured against in DESIGN.md"}
     r.update({"traffic": measured_traffic(family, cfg.name, fc), "traffic_unit": "bytes/launch",
               "avg_launch_ms": round(avg_ms, 5), "launches_per_step": d["launches"] // K,
               "total_ms_per_step": round(d["ms"] / K, 4)})
@@ -499,6 +513,10 @@ def main():
     torch.cuda.empty_cache()
 
     if not args.no_extra and args.workload == "animatediff":
+        # the 25-step schedule (normal step when t % 3 == 0, the entry swapped out after it and prefetched one step
+        # ahead) on the headline shapes, frame chunks 16, 8, 4, 2: latency, peak HBM and swap overlap per chunk
+        out["schedule_25_steps_interval_3"] = [
+            schedule_record(lcb, torch, synth, cfg, w, c, 0, 25, 3, 2, 3, args.lanes) for c in (16, 8, 4, 2)]
         out["svdxt"] = workload_record(lcb, torch, synth, "svdxt", w, args.lanes)
         out["tiny"] = tiny_record(lcb, torch, synth, args.lanes)
         out["stress"] = stress_record(lcb, torch, synth, w, args.lanes, stats.weight_bytes)
