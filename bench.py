@@ -35,11 +35,11 @@ PEAK_HBM_GBS = 8000.0
 # WRITE_SIZE runs summarised under profiles/ (fetch x 2.0, the factor a plain copy of known size gave). Valid only
 # for the kernel sources the counters were taken with: `sha256_16` covers the listed files, else traffic is null.
 TRAFFIC = {
-    "conv_up": {"sources": ("lc_convws.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "31bb2c43b18a8fdb",
+    "conv_up": {"sources": ("lc_convws.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "9f27ba249d998d07",
                 "bytes_per_launch": 83.6e6 + 22.3e6},
-    "sattn": {"sources": ("lc_attn.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "",
+    "sattn": {"sources": ("lc_attn.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "7aacbd5d82e993a6",
               "bytes_per_launch": 61.0e6 + 12.6e6},
-    "conv_res": {"sources": ("lc_convws.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "31bb2c43b18a8fdb",
+    "conv_res": {"sources": ("lc_convws.hip", "lc_common.h", "lc_internal.h"), "sha256_16": "9f27ba249d998d07",
                  "bytes_per_launch": 54.5e6 + 22.3e6},
 }
 TRAFFIC_WORKLOAD = ("animatediff", 4)
