@@ -213,8 +213,8 @@ def roofline_of(lcb, torch, stage, cfg, fc, family, step, K, peak):
         r["context"] = {"exp_per_launch": exps, "exp_floor_ms": round(exps / 9.83e12 * 1e3, 5),
                         "executed_flops_per_launch": padded, "mfma_floor_ms": round(padded / (peak * 1e12) * 1e3, 5),
                         "note": "the counter summary under profiles/ shows the matrix pipe and the transcendental unit "
-                                "taking turns (42 % and 48 % busy): the sum of the two floors is what the kernel "
-                                "is measured against in DESIGN.md"}
+                                "taking turns (42 % and 48 % busy): the sum of the two floors is what the kernel's "
+                                "launch time compares with"}
     r.update({"traffic": measured_traffic(family, cfg.name, fc), "traffic_unit": "bytes/launch",
               "avg_launch_ms": round(avg_ms, 5), "launches_per_step": d["launches"] // K,
               "total_ms_per_step": round(d["ms"] / K, 4)})
@@ -348,7 +348,7 @@ def main():
                     help="run one of the further records alone and print it (the command rocprofv3 is pointed at for them)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
 
     import torch
     from paper_2510_05367_amd import binding as lcb
