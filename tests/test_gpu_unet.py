@@ -114,6 +114,37 @@ def test_invariants_bitwise(cfg):
         net.close()
 
 
+def test_benchmark_size_invariants():
+    """The benchmark's configuration (2 x 16 frames of 64 x 64, widths 320 / 640 / 1280), which the oracle cannot run in a
+    test's time: the properties that hold at any size. A cache step on the entry its own normal step left reproduces
+    that step bit for bit, a second normal step reproduces the first, the entry survives a swap round trip byte for
+    byte, and eps has the scale the smaller cases have against the oracle (finite, std within 0.3 .. 1.5)."""
+    cfg = synth.UNETS["sd15_video"]
+    w = synth.make_unet_weights(cfg, 0)
+    net = lcb.Unet(cfg, w, host_slots=1, dev_slots=2)
+    try:
+        x, temb, ctx = synth.make_unet_inputs(cfg, 1)
+        xd, td, cd = net.to_device(x), net.to_device(temb), net.to_device(ctx)
+        full, cached, again, swapped = (net.empty(*x.shape) for _ in range(4))
+        net.full_step(xd, td, cd, full, 0)
+        net.cached_step(xd, td, cd, cached, 0)
+        net.swap_out(0, 0)
+        net.full_step(xd, td, cd, again, 1)
+        net.sync()
+        assert bool(torch.isfinite(full).all()) and 0.3 < float(full.float().std()) < 1.5
+        assert torch.equal(cached, full) and torch.equal(again, full)
+        d0 = net.dev_entry(0)
+        assert torch.equal(net.dev_entry(1), d0)
+        assert net.host_entry_bytes(0) == d0.cpu().numpy().tobytes()
+        net.cache_write(1, torch.zeros_like(d0))
+        net.swap_in(0, 1)
+        net.cached_step(xd, td, cd, swapped, 1)
+        net.sync()
+        assert torch.equal(swapped, full)
+    finally:
+        net.close()
+
+
 def test_schedule_with_prefetch_matches_resident():
     """9 steps, a normal step every 3rd, the entry swapped out after it and prefetched one step ahead into the other
     device slot; free-running (x <- x - 0.1 * eps). Bit-identical to the run that keeps the entry resident."""
