@@ -21,11 +21,12 @@ namespace lc {
 namespace {
 
 constexpr int kKB = 128;                        // K bytes per step
-constexpr int kStages = 3;
+constexpr int kMaxStages = 3;
 // a workgroup takes 128 MR rows (MR = 2, or 1 where few rows would leave most of the device idle) and 32 NT channels;
 // bytes of one ring stage: the x tile, then the W tile
 constexpr int lin2_stage(int NT, int MR) { return (128 * MR + NT * 32) * kKB; }
-static_assert(kStages * lin2_stage(5, 2) <= 160 * 1024, "fits the LDS of a compute unit");
+static_assert(kMaxStages * lin2_stage(5, 2) <= 160 * 1024, "fits the LDS of a compute unit");
+static_assert(2 * 2 * lin2_stage(5, 1) <= 160 * 1024, "two workgroups of the two-stage form fit it together");
 
 struct Lin2Args {
   const bf16_t* x;     // [rows][K]
@@ -46,9 +47,14 @@ struct Lin2Args {
 
 // MAPPED: rows go through the row maps (a 64-bit division per row: kept out of the common, dense case, where the
 // host folds the maps' offsets into the pointers; the arithmetic, and so every bit of the result, is the same)
-template <class OT, int NT, int MR, bool MAPPED>
-__global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
+// ST: stages of the ring. 3: one workgroup per compute unit, loads two steps ahead. 2 (with the 128-row tile): two
+// workgroups share a compute unit (LDS and registers are budgeted for that) and cover each other's waits - for the
+// short contractions, where a tile is mostly prologue and epilogue.
+template <class OT, int NT, int MR, bool MAPPED, int ST>
+__global__ __launch_bounds__(256, ST == 2 ? 2 : 1) void lin2_kernel(Lin2Args a) {
   typedef Mma32<bf16_t> M;
+  static_assert(ST == 3 || (ST == 2 && MR == 1), "two stages go with the small tile");
+  constexpr int kStages = ST;
   constexpr int kM = 128 * MR, kN = NT * 32, kStage = lin2_stage(NT, MR);
   constexpr int kXI = 4 * MR, kWI = NT;  // global->LDS instructions per wavefront per stage: x tile, W tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -115,12 +121,14 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
 
   const int nsteps = a.K / 64;
   issue(0, 0);
-  if (nsteps > 1) issue(1, 1);
+  if (ST == 3 && nsteps > 1) issue(1, 1);
   for (int s = 0; s < nsteps; ++s) {
-    // the loads of step s have landed (for every wavefront, after the barrier); those of step s + 1 may be in flight
-    if (s + 1 < nsteps) barrier_keep<kXI + kWI>();
+    // the loads of step s have landed (for every wavefront, after the barrier); with three stages those of step
+    // s + 1 may be in flight
+    if (ST == 3 && s + 1 < nsteps) barrier_keep<kXI + kWI>();
     else barrier_keep<0>();
-    if (s + 2 < nsteps) issue(s + 2, (s + 2) % kStages);  // into the stage that was read in step s - 1
+    // the next request goes into the stage that was read in step s - 1
+    if (s + ST - 1 < nsteps) issue(s + ST - 1, (s + ST - 1) % kStages);
     const unsigned char* st = smem + (s % kStages) * kStage;
     typename M::Frag xf[2][MR], wf[2][NT];
 #pragma unroll
@@ -218,40 +226,42 @@ __global__ __launch_bounds__(256) void lin2_kernel(Lin2Args a) {
 // hipErrorNotSupported for what it does not cover (the general kernel then runs). Which kernel runs depends on the
 // layer's widths only, never on the number of rows: a chunked pass must give the bits of the unchunked one.
 // (hipFuncSetAttribute is called once per instantiation and process: one device.)
-template <class OT, int NT, int MR, bool MAPPED>
+template <class OT, int NT, int MR, bool MAPPED, int ST>
 static hipError_t run_lin2_k(hipStream_t s, const Lin2Args& a) {
-  constexpr int lds = kStages * lin2_stage(NT, MR);
+  constexpr int lds = ST * lin2_stage(NT, MR);
   static bool done = false;  // per instantiation
   if (!done) {
-    hipError_t e = hipFuncSetAttribute((const void*)lin2_kernel<OT, NT, MR, MAPPED>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = hipFuncSetAttribute((const void*)lin2_kernel<OT, NT, MR, MAPPED, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     done = true;
   }
   const unsigned grid = (unsigned)((a.ntm + 7) / 8 * 8 * a.ntn);
-  lin2_kernel<OT, NT, MR, MAPPED><<<grid, 256, lds, s>>>(a);
+  lin2_kernel<OT, NT, MR, MAPPED, ST><<<grid, 256, lds, s>>>(a);
   return hipGetLastError();
 }
-template <class OT, int NT, int MR>
+template <class OT, int NT, int MR, int ST>
 static hipError_t run_lin2_mr(hipStream_t s, Lin2Args a) {
   a.ntm = (int)((a.rows + 128 * MR - 1) / (128 * MR));
   // a map that is the identity up to an offset (one segment, or segments that follow each other) is folded into
   // the pointers
   auto plain = [&](const RowMap& m) { return m.rows_per_seg >= a.rows || m.seg_stride == m.rows_per_seg; };
-  if (!plain(a.in_map) || !plain(a.out_map)) return run_lin2_k<OT, NT, MR, true>(s, a);
+  if (!plain(a.in_map) || !plain(a.out_map)) return run_lin2_k<OT, NT, MR, true, ST>(s, a);
   const int64_t nout = a.act == 2 ? a.N / 2 : a.N;
   a.x += a.in_map.base * a.K;
   a.y = (OT*)a.y + a.out_map.base * nout;
   if (a.res) a.res += a.out_map.base * nout;
   if (a.y2) a.y2 += a.out_map.base * nout;
-  return run_lin2_k<OT, NT, MR, false>(s, a);
+  return run_lin2_k<OT, NT, MR, false, ST>(s, a);
 }
 // The row tile is chosen by how many tiles there are (every output element is the same sequence of MFMAs over K
 // whatever the tile it falls in: the choice never shows in the bits).
 template <class OT, int NT>
 static hipError_t run_lin2(hipStream_t s, Lin2Args a) {
   a.ntn = a.N / (NT * 32);
+  // short contractions: the small tile with two workgroups per compute unit
+  if (a.K <= 640) return run_lin2_mr<OT, NT, 1, 2>(s, a);
   const int64_t big_tiles = (a.rows + 255) / 256 * a.ntn;
-  return big_tiles >= 256 ? run_lin2_mr<OT, NT, 2>(s, a) : run_lin2_mr<OT, NT, 1>(s, a);
+  return big_tiles >= 256 ? run_lin2_mr<OT, NT, 2, 3>(s, a) : run_lin2_mr<OT, NT, 1, 3>(s, a);
 }
 
 hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
