@@ -441,8 +441,8 @@ lc_status lc_dit_get_counts(lc_dit* ctx, int64_t* full_steps, int64_t* cached_st
  * streams fp32). No feature chunk here: the step runs over all frames at once.
  * Requirements (else LC_ERR_SHAPE): sizes > 0; H, W multiples of 4; C, C1, C2, ctx_dim multiples of 64, <= 2048;
  * every width and C + C1, C1 + C2 divisible by groups; C, C1 multiples of head_dim; head_dim in {8, 16, 32, 40, 64};
- * C_lat <= 16; ff_mult <= 4; F * 3 * C1 elements of cfg dtype within 128 KiB (one position's q,k,v of all frames
- * in LDS); 1 <= dev_slots <= 8; 0 <= host_slots <= 64. Conventions (streams, errors, lifetimes) as above. */
+ * C_lat <= 16; ff_mult <= 4; F * 3 * max(C, C1) elements of cfg dtype within 128 KiB (one position's q,k,v of all
+ * frames in LDS); 1 <= dev_slots <= 8; 0 <= host_slots <= 64. Conventions (streams, errors, lifetimes) as above. */
 typedef struct lc_unet lc_unet; /* opaque; owned by the library */
 typedef struct lc_unet_config {
   int32_t B, F, H, W, C_lat;
