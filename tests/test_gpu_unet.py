@@ -81,6 +81,14 @@ def test_full_width_steps_match_oracle():
     run_case(MID, odtype=np.float32, sharp=1.0, chain=True)
 
 
+@pytest.mark.slow
+def test_full_resolution_steps_match_oracle():
+    """The benchmark's U-Net at its full widths and full 64 x 64 latents (4096 tokens per frame: the tile and token
+    geometry of the timed configuration), one batch element of 2 frames so that the float32 oracle stays under a
+    minute (8 frames pass too, in three minutes; the 8-frame temporal path is what the half-resolution case covers)."""
+    run_case(synth.UNETS["sd15_video"].with_(name="sd15_video_b1_f2", B=1, F=2), odtype=np.float32, sharp=1.0, chain=True)
+
+
 @pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16], ids=lambda c: c.name)
 def test_invariants_bitwise(cfg):
     w = synth.make_unet_weights(cfg, 0, sharp=4.0)
