@@ -804,6 +804,14 @@ def unet_record(lcb, torch, synth, steps=5, steps_only=False):
         base = rec["schedules"][0]["resident_ms_per_step"]
         for row in rec["schedules"]:
             row["speedup_vs_every_step_normal"] = round(base / row.get("swapped_ms_per_step", row["resident_ms_per_step"]), 3)
+        # feature chunk: frames per chunk in the per-frame blocks, as many rows of all frames in the temporal ones
+        rec["frame_chunks"] = []
+        for fc in (16, 8, 4, 2):
+            net.set_chunk(fc)
+            rec["frame_chunks"].append({"frame_chunk": fc, "normal_step_ms": round(timed(lambda: net.full_step(x, temb, ctx, out, 0), steps), 3),
+                                        "cache_step_ms": round(timed(lambda: net.cached_step(x, temb, ctx, out, 0), steps), 3),
+                                        "workspace_gb": round(lcb.lc_unet_chunk_workspace_bytes(net.ccfg, fc) / 1e9, 4)})
+        net.set_chunk(0)
         return rec
     finally:
         net.close()

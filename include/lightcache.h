@@ -438,7 +438,16 @@ lc_status lc_dit_get_counts(lc_dit* ctx, int64_t* full_steps, int64_t* cached_st
  * (lc_unet_cached_step) runs the shallow blocks only and reads it from the slot. Entries are fp32, channels-last
  * [B*F, H*W, C1]; swap-out / swap-in move them to / from pinned host memory on the side stream, as for the stage
  * above. x, temb, ctx, eps and the weights have cfg dtype (bf16: MFMA operands bf16, accumulation and residual
- * streams fp32). No feature chunk here: the step runs over all frames at once.
+ * streams fp32).
+ * Feature chunk ("Feature chunk" section): lc_unet_set_chunk(frame_chunk) makes every block work on a chunk at a
+ * time. The residual blocks, the spatial transformer blocks and the resampling convolutions, which treat frames
+ * independently, take frame_chunk of the B*F frames at H x W and twice as many at each level down (a frame there has
+ * a quarter of the positions and twice the channels: a chunk's maps keep their size); a temporal block, whose tokens
+ * are the frames of a position, takes ceil(positions * chunk frames / (B*F)) positions of every frame (the same number
+ * of rows) and never splits the frame axis. What lives inside a block (the concatenated input, hidden map and shortcut of a residual block,
+ * the upsampled map, the token buffers of a transformer block) then has the size of one chunk; what passes
+ * between blocks (three maps, the two skips, the device slots) keeps the size of all frames. Results are the same
+ * bit for bit at every setting.
  * Requirements (else LC_ERR_SHAPE): sizes > 0; H, W multiples of 4; C, C1, C2, ctx_dim multiples of 64, <= 2048;
  * every width and C + C1, C1 + C2 divisible by groups; C, C1 multiples of head_dim; head_dim in {8, 16, 32, 40, 64};
  * C_lat <= 16; ff_mult <= 4; F * 3 * max(C, C1) elements of cfg dtype within 128 KiB (one position's q,k,v of all
@@ -481,12 +490,17 @@ typedef struct lc_unet_weights {
 
 lc_status lc_unet_check_config(const lc_unet_config* cfg);   /* host only */
 size_t lc_unet_entry_bytes(const lc_unet_config* cfg);       /* one cache entry: B*F*H*W*C1 floats; host only */
-size_t lc_unet_workspace_bytes(const lc_unet_config* cfg);   /* footprint model, device slots included; host only */
+size_t lc_unet_workspace_bytes(const lc_unet_config* cfg);   /* footprint model, device slots included, all frames at
+                                                                 once (the largest over all chunk settings); host only */
+size_t lc_unet_chunk_workspace_bytes(const lc_unet_config* cfg, int frame_chunk); /* the same at a chunk setting */
 const char* lc_unet_last_error(const lc_unet* ctx);
 lc_status lc_unet_create(const lc_unet_config* cfg, void* compute_stream, void* side_stream, lc_unet** out);
 lc_status lc_unet_destroy(lc_unet* ctx);
 lc_status lc_unet_load_weights(lc_unet* ctx, const lc_unet_weights* w /* [host] struct of [device] ptrs */);
 lc_status lc_unet_set_workspace(lc_unet* ctx, void* arena /* [device], 256-byte aligned */, size_t bytes);
+/* 0 = all frames at once; values above B*F clamp. LC_ERR_NOMEM if the workspace at hand is smaller than the setting
+ * needs. The device slots keep their place and contents. Not while a step is in flight. */
+lc_status lc_unet_set_chunk(lc_unet* ctx, int frame_chunk);
 /* x [device, B, F, C_lat, H, W], temb [device, B, temb_dim], ctx [device, B, ctx_len, ctx_dim] -> eps [device, B, F,
  * C_lat, H, W], all of cfg dtype. Cache step: LC_ERR_STATE if the slot is empty; waits on the GPU for a swap-in in
  * flight. All four tensors must stay valid until the compute stream has been synchronised. */

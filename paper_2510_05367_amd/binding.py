@@ -192,6 +192,8 @@ PROTOTYPES = {
     "lc_unet_check_config": (_I, [C.POINTER(lc_unet_config)]),
     "lc_unet_entry_bytes": (C.c_size_t, [C.POINTER(lc_unet_config)]),
     "lc_unet_workspace_bytes": (C.c_size_t, [C.POINTER(lc_unet_config)]),
+    "lc_unet_chunk_workspace_bytes": (C.c_size_t, [C.POINTER(lc_unet_config), _I]),
+    "lc_unet_set_chunk": (_I, [_P, _I]),
     "lc_unet_last_error": (C.c_char_p, [_P]),
     "lc_unet_create": (_I, [C.POINTER(lc_unet_config), _P, _P, C.POINTER(_P)]),
     "lc_unet_destroy": (_I, [_P]),
@@ -760,6 +762,14 @@ def lc_unet_workspace_bytes(cfg: lc_unet_config) -> int:
     return lib().lc_unet_workspace_bytes(C.byref(cfg))
 
 
+def lc_unet_chunk_workspace_bytes(cfg: lc_unet_config, frame_chunk: int) -> int:
+    return lib().lc_unet_chunk_workspace_bytes(C.byref(cfg), frame_chunk)
+
+
+def lc_unet_set_chunk(ctx, frame_chunk: int) -> None:
+    _ucheck(lib().lc_unet_set_chunk(ctx, frame_chunk), ctx)
+
+
 def lc_unet_last_error(ctx=None) -> str:
     return lib().lc_unet_last_error(ctx).decode()
 
@@ -824,9 +834,11 @@ UNET_TF = ("d0", "d1", "u1", "u0")
 
 class Unet:
     """The U-Net stage with real block internals on the current GPU; torch owns memory and streams.
-    `weights`: name -> numpy float32 array, names as in synth.unet_weight_manifest."""
+    `weights`: name -> numpy float32 array, names as in synth.unet_weight_manifest. `frame_chunk`: the feature chunk
+    the workspace is sized for (None: all frames at once, which every later set_chunk fits)."""
 
-    def __init__(self, cfg, weights, host_slots: int = 1, dev_slots: int = 2, device: str = "cuda:0"):
+    def __init__(self, cfg, weights, host_slots: int = 1, dev_slots: int = 2, device: str = "cuda:0",
+                 frame_chunk: Optional[int] = None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
@@ -868,11 +880,18 @@ class Unet:
         w.out = lc_unet_conv_w(ptr("out.w"), ptr("out.b"))
         lc_unet_load_weights(self.ctx, w)
         del t
-        need = lc_unet_workspace_bytes(self.ccfg)
+        if frame_chunk:
+            lc_unet_set_chunk(self.ctx, frame_chunk)
+        need = lc_unet_chunk_workspace_bytes(self.ccfg, frame_chunk or 0)
         with torch.cuda.stream(self.compute):
             self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
         self.compute.synchronize()
         lc_unet_set_workspace(self.ctx, self.arena.data_ptr(), self.arena.numel())
+
+    def set_chunk(self, frame_chunk: int):
+        """Frames per chunk from the next step on (0: all frames at once); the cached entries stay where they are."""
+        self.sync()
+        lc_unet_set_chunk(self.ctx, frame_chunk)
 
     def to_device(self, a, f32: bool = False):
         """numpy -> device tensor of the stage's dtype (f32: float32, for cache entries), on the compute stream."""

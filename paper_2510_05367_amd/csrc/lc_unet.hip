@@ -119,18 +119,21 @@ __global__ __launch_bounds__(256) void temb_bias_kernel(const T* __restrict__ te
   if (lane == 0) out[item] = acc + bt[o] + bias[o];
 }
 
-// y[r][:] = bf16(x[r][:] * scale[f][:] + shift[f][:]), f = r / rows_per_frame: GroupNorm applied to fp32 rows and
+// y[r][:] = bf16(x[m(r)][:] * scale[f][:] + shift[f][:]), f = r / rows_per_frame: GroupNorm applied to fp32 rows and
 // rounded once, the operand of the projection into a transformer block. Thread = 8 channels of one row.
+// MAPPED: the dense rows are gathered through the row map (a chunk of positions out of every frame).
+template <bool MAPPED>
 __global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__ x, const float* __restrict__ scale,
                                                        const float* __restrict__ shift, bf16_t* __restrict__ y, int64_t rows,
-                                                       int C8, int rows_per_frame) {
+                                                       int C8, int rows_per_frame, RowMap m) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= rows * C8) return;
   const int64_t r = i / C8;
   const int c = (int)(i - r * C8) * 8;
   const int64_t f = r / rows_per_frame;
+  const int64_t sr = MAPPED ? m(r) : r;
   float v[8], sc[8], sh[8];
-  load_f<float, 8>(x + r * C8 * 8 + c, v);
+  load_f<float, 8>(x + sr * C8 * 8 + c, v);
   load_f<float, 8>(scale + f * C8 * 8 + c, sc);
   load_f<float, 8>(shift + f * C8 * 8 + c, sh);
   Vec16<bf16_t> o;
@@ -172,10 +175,12 @@ struct TfP {
 };
 
 struct UPlan {
-  size_t map_bytes;                // one work map: the largest fp32 map of any stage
-  size_t off_map[4], off_s, off_d1, off_slots, slot_bytes;
-  size_t off_part, off_scale, off_shift, off_one, off_zero, off_tb;
-  size_t off_a, off_qkv, off_vt, off_ao, off_u, off_g, off_kv, off_vtx;
+  int nc[3];         // frames per chunk at H x W, H/2 x W/2, H/4 x W/4
+  size_t map_bytes;  // one map of all frames: the largest tensor that passes between two blocks
+  size_t off_map[3], off_s, off_d1, off_slots, slot_bytes;
+  size_t off_part, off_scale, off_shift, off_one, off_zero, off_tb, off_kv, off_vtx;
+  size_t off_xc, off_h, off_sc, off_xb, off_up;                   // one chunk inside a residual block or a resampling
+  size_t off_z, off_a, off_qkv, off_vt, off_ao, off_u, off_g;     // one chunk inside a transformer block (same memory)
   size_t total;
 };
 
@@ -184,6 +189,7 @@ struct UPlan {
 struct lc_unet {
   lc_unet_config cfg;
   hipStream_t cs, ss;
+  int frame_chunk;
   UPlan plan;
   char* arena;
   size_t arena_bytes;
@@ -249,22 +255,37 @@ lc_status check_ucfg(lc_unet* c, const lc_unet_config* g) {
 
 inline size_t entry_bytes(const lc_unet_config& g) { return (size_t)g.B * g.F * g.H * g.W * g.C1 * 4; }
 
-// Arena: four work maps that each hold the largest fp32 map of any stage (the concatenated input of the
-// shallowest up block, or an upsampled map), the two skips kept across the deep branch, the device slots, the
-// GroupNorm scratch, and the token buffers of a transformer block at its largest (level 0 or level 1).
-UPlan make_uplan(const lc_unet_config& g) {
+// Positions of every frame that one pass of a temporal block takes when the per-frame blocks take nc of the N
+// frames: the same number of rows, rounded up to whole positions.
+inline int pos_chunk(int P, int nc, int N) { return (int)(((int64_t)P * nc + N - 1) / N); }
+
+// Frames per chunk at a level: twice as many at each level down, where a frame has a quarter of the positions and
+// twice the channels, so that a chunk's maps keep their size (and the launches their fill).
+inline int level_chunk(int frame_chunk, int level, int N) {
+  if (frame_chunk <= 0 || frame_chunk > N) return N;
+  return (int)std::min<int64_t>(N, (int64_t)frame_chunk << level);
+}
+
+// Arena. Of all frames: three maps for the tensors that pass between blocks, the two skips kept across the deep
+// branch, the device slots, the GroupNorm scale / shift. Of one chunk (nc frames in the per-frame blocks, as many
+// rows of all frames in the temporal ones): the inside of a residual block (concatenated input, hidden map,
+// shortcut) or of a resampling (upsampled map), and, in the same memory, the token buffers of a transformer block.
+UPlan make_uplan(const lc_unet_config& g, int frame_chunk) {
   UPlan p;
   const size_t es = dtype_size(g.dtype);
-  const int64_t N = (int64_t)g.B * g.F, P = (int64_t)g.H * g.W, P1 = P / 4;
-  const int64_t map_elems = N * std::max({P * (g.C + g.C1), P1 * (g.C1 + g.C2), P1 * g.C2, P * g.C1});
+  const int64_t N = (int64_t)g.B * g.F, P = (int64_t)g.H * g.W, P1 = P / 4, P2 = P / 16;
+  for (int l = 0; l < 3; ++l) p.nc[l] = level_chunk(frame_chunk, l, (int)N);
+  const int64_t nc0 = p.nc[0], nc1 = p.nc[1], nc2 = p.nc[2];
   const int maxC = std::max({g.C + g.C1, g.C1 + g.C2, g.C2});
-  const int64_t tok = std::max(N * P * g.C, N * P1 * g.C1);  // rows * width of a transformer block, at its largest
+  const int64_t full = N * std::max({P * g.C, P1 * g.C, P1 * g.C1, P1 * g.C2, P2 * g.C1, P2 * g.C2});
+  // rows * width of a transformer block's chunk at its largest (level 0 or level 1)
+  const int64_t tok = N * std::max((int64_t)pos_chunk((int)P, p.nc[0], (int)N) * g.C, (int64_t)pos_chunk((int)P1, p.nc[1], (int)N) * g.C1);
   const int64_t splits_c = std::max({(int64_t)stat_splits((int)P) * (g.C + g.C1), (int64_t)stat_splits((int)P1) * std::max(g.C1 + g.C2, g.C),
-                                     (int64_t)stat_splits((int)(P1 / 4)) * std::max(g.C1, g.C2)});
+                                     (int64_t)stat_splits((int)P2) * std::max(g.C1, g.C2)});
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
-  p.map_bytes = align_up((size_t)map_elems * 4);
-  for (int i = 0; i < 4; ++i) p.off_map[i] = take(p.map_bytes);
+  p.map_bytes = align_up((size_t)full * 4);
+  for (int i = 0; i < 3; ++i) p.off_map[i] = take(p.map_bytes);
   p.off_s = take((size_t)N * P * g.C * 4);
   p.off_d1 = take((size_t)N * P1 * g.C1 * 4);
   p.slot_bytes = align_up(entry_bytes(g));
@@ -275,15 +296,28 @@ UPlan make_uplan(const lc_unet_config& g) {
   p.off_one = take((size_t)N * maxC * 4);
   p.off_zero = take((size_t)N * maxC * 4);
   p.off_tb = take((size_t)g.B * std::max({g.C, g.C1, g.C2}) * 4);
-  p.off_a = take((size_t)tok * es);
-  p.off_qkv = take((size_t)tok * 3 * es);
-  p.off_vt = take((size_t)std::max(N * g.C * attn_tp((int)P), N * g.C1 * attn_tp((int)P1)) * es);
-  p.off_ao = take((size_t)tok * es);
-  p.off_u = take((size_t)tok * 2 * g.ff_mult * es);
-  p.off_g = take((size_t)tok * g.ff_mult * es);
   p.off_kv = take((size_t)g.B * g.ctx_len * 2 * std::max(g.C, g.C1) * es);
   p.off_vtx = take((size_t)g.B * std::max(g.C, g.C1) * attn_tp(g.ctx_len) * es);
-  p.total = off;
+  const size_t chunk0 = off;
+  // ---- one chunk, residual blocks and resamplings
+  const int64_t cat = std::max(nc0 * P * (g.C + g.C1), nc1 * P1 * (g.C1 + g.C2));
+  const int64_t hid = std::max({nc0 * P * g.C, nc1 * P1 * g.C1, nc2 * P2 * g.C2});
+  p.off_xc = take((size_t)cat * 4);
+  p.off_h = take((size_t)hid * 4);
+  p.off_sc = take((size_t)hid * 4);
+  p.off_xb = take(g.dtype == kBF16 ? (size_t)cat * es : 0);
+  p.off_up = take((size_t)std::max(nc1 * P1 * g.C2, nc0 * P * g.C1) * 4);
+  const size_t end_rb = off;
+  // ---- one chunk, transformer blocks
+  off = chunk0;
+  p.off_z = take((size_t)tok * 4);
+  p.off_a = take((size_t)tok * es);
+  p.off_qkv = take((size_t)tok * 3 * es);
+  p.off_vt = take((size_t)std::max(nc0 * g.C * attn_tp((int)P), nc1 * g.C1 * attn_tp((int)P1)) * es);
+  p.off_ao = take((size_t)tok * es);
+  p.off_u = take(g.dtype == kBF16 ? 0 : (size_t)tok * 2 * g.ff_mult * es);  // (bf16: the GEGLU is fused, no 2M-wide tensor)
+  p.off_g = take((size_t)tok * g.ff_mult * es);
+  p.total = std::max(off, end_rb);
   return p;
 }
 
@@ -291,8 +325,27 @@ inline char* slot_ptr(lc_unet* c, int s) { return c->arena + c->plan.off_slots +
 inline float* map_ptr(lc_unet* c, int i) { return (float*)(c->arena + c->plan.off_map[i]); }
 inline RowMap dense_map() { return RowMap{0, 0, 1 << 30}; }
 
+// fn(n0, n) for every chunk [n0, n0 + n) of the N frames, at the chunk size of a level
+template <class Fn>
+lc_status frame_chunks(lc_unet* c, int level, Fn fn) {
+  const int N = c->cfg.B * c->cfg.F, nc = c->plan.nc[level];
+  for (int n0 = 0; n0 < N; n0 += nc) LCU_TRY(fn(n0, std::min(nc, N - n0)));
+  return LC_OK;
+}
+// fn(b, i0, n) for every run of frames of the chunk [n0, n0 + nc) that lies in one batch element b: frames
+// i0 ... i0 + n - 1 counted from the chunk's first
+template <class Fn>
+lc_status batch_runs(const lc_unet_config& g, int n0, int nc, Fn fn) {
+  for (int f = n0; f < n0 + nc;) {
+    const int b = f / g.F, e = std::min(n0 + nc, (b + 1) * g.F);
+    LCU_TRY(fn(b, f - n0, e - f));
+    f = e;
+  }
+  return LC_OK;
+}
+
 // ---- operators -------------------------------------------------------------------------------------------------
-// scale / shift of GroupNorm(x) for n frames of fp32 rows [rows][C]
+// scale / shift (frame 0 of x first) of GroupNorm(x) for n frames of fp32 rows [rows][C]
 lc_status gn(lc_unet* c, const float* x, int n, int rows, int C, const NormP& w) {
   const UPlan& p = c->plan;
   float* part = (float*)(c->arena + p.off_part);
@@ -302,7 +355,7 @@ lc_status gn(lc_unet* c, const float* x, int n, int rows, int C, const NormP& w)
   return LC_OK;
 }
 
-// y = [res +] conv3x3(act(x)) over n frames; src 2: SiLU(GroupNorm(x)) with the scale / shift at hand (rows of frame
+// y = [res +] conv3x3(act(x)) over n frames; src 2: SiLU(GroupNorm(x)) with the scale / shift at hand (those of frame
 // `f0` on), src 1: x as it is. planar: y is [n][Cout_store][H][W] of the stage's dtype (the last convolution).
 lc_status conv(lc_unet* c, const ConvP& w, const float* bias, int src, int Cin, int Cout, int n, int f0, int H, int W, const float* x,
                const float* res, void* y, int planar, int Cout_store) {
@@ -318,22 +371,38 @@ lc_status conv(lc_unet* c, const ConvP& w, const float* bias, int src, int Cin, 
   return LC_OK;
 }
 
-// y[rows][Cout] = x[rows][Cin] W^T + bias [+ res]. src 0: x of the operand type; src 1: x fp32, multiplied by
-// scale[frame] and shifted (GroupNorm apply; unit = 1: taken as it is), frame = row / rows_per_frame.
-lc_status linear(lc_unet* c, const LinP& w, int Cin, int Cout, int64_t rows, int src, int unit, int rows_per_frame, const void* x,
-                 const float* res, void* y, int y32, void* y2 = nullptr, int act = 0, int q_cols = 0) {
-  const UPlan& p = c->plan;
+// What a linear layer does beyond y = x W^T + bias.
+struct LinOpt {
+  const float* res = nullptr;  // fp32, added; rows as y's
+  void* y2 = nullptr;          // a copy of y rounded to the operand type
+  int act = 0, q_cols = 0;
+  // x is fp32 and row r is multiplied by scale[r / in_map.rows_per_seg] and shifted (GroupNorm apply) on the way in
+  const float *scale = nullptr, *shift = nullptr;
+  RowMap in_map = RowMap{0, 0, 1 << 30}, out_map = RowMap{0, 0, 1 << 30};
+};
+
+// y[out_map(r)][Cout] = x[in_map(r)][Cin] W^T + bias [+ res], r < rows; x of the operand type unless o.scale is set
+lc_status linear(lc_unet* c, const LinP& w, int Cin, int Cout, int64_t rows, const void* x, void* y, int y32, const LinOpt& o = LinOpt()) {
   FusedDesc f;
   memset(&f, 0, sizeof f);
-  f.dt = c->cfg.dtype; f.y_f32 = y32; f.taps = 1; f.src = src; f.Cin = Cin; f.Cout = Cout; f.Cout_store = Cout; f.w = w.w; f.bias = w.b;
-  f.rows = rows; f.in_map = f.out_map = dense_map(); f.x = x; f.res = res; f.y = y; f.y2 = y2; f.act = act;
-  if (q_cols) { f.q_cols = q_cols; f.q_scale = attn_q_scale(c->cfg.head_dim); }  // softmax scale folded into q
-  if (src == 1) {
-    f.in_map = RowMap{0, rows_per_frame, rows_per_frame};
-    f.scale = (const float*)(c->arena + (unit ? p.off_one : p.off_scale));
-    f.shift = (const float*)(c->arena + (unit ? p.off_zero : p.off_shift));
-  }
+  f.dt = c->cfg.dtype; f.y_f32 = y32; f.taps = 1; f.src = o.scale ? 1 : 0; f.Cin = Cin; f.Cout = Cout; f.Cout_store = Cout; f.w = w.w;
+  f.bias = w.b; f.rows = rows; f.in_map = o.in_map; f.out_map = o.out_map; f.x = x; f.res = o.res; f.y = y; f.y2 = o.y2; f.act = o.act;
+  f.scale = o.scale; f.shift = o.shift;
+  if (o.q_cols) { f.q_cols = o.q_cols; f.q_scale = attn_q_scale(c->cfg.head_dim); }  // softmax scale folded into q
   LCU_HIP(c, launch_fused(c->cs, f));
+  return LC_OK;
+}
+
+// y (bf16, dense rows) = x[m(r)] * scale[r / rows_per_frame] + shift[...]
+lc_status gn_apply(lc_unet* c, const float* x, const float* scale, const float* shift, void* y, int64_t rows, int C, int rows_per_frame,
+                   RowMap m) {
+  const int64_t n = rows * (C / 8);
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (m.rows_per_seg >= rows || m.seg_stride == m.rows_per_seg)  // consecutive rows from m.base on
+    gn_apply_kernel<false><<<blocks, 256, 0, c->cs>>>(x + m.base * C, scale, shift, (bf16_t*)y, rows, C / 8, rows_per_frame, m);
+  else
+    gn_apply_kernel<true><<<blocks, 256, 0, c->cs>>>(x, scale, shift, (bf16_t*)y, rows, C / 8, rows_per_frame, m);
+  LCU_HIP(c, hipGetLastError());
   return LC_OK;
 }
 
@@ -355,118 +424,21 @@ lc_status feed_forward(lc_unet* c, const TfP& w, float* z, int64_t rows, int row
   const UPlan& p = c->plan;
   const int C = w.C, M = g.ff_mult * C;
   char *a = c->arena + p.off_a, *u = c->arena + p.off_u, *gl = c->arena + p.off_g;
+  LinOpt back;
+  back.res = z; back.y2 = zb;
   LCU_TRY(ln(c, z, w.ln3, nullptr, a, rows, C, rows_per_frame));
   if (w.ff_fused) {  // value * gelu(gate) in the first layer's epilogue: the 2M-wide tensor never exists
-    LCU_TRY(linear(c, w.ff1, C, 2 * M, rows, 0, 0, 0, a, nullptr, gl, 0, nullptr, 2));
-    return linear(c, w.ff2, M, C, rows, 0, 0, 0, gl, z, z, 1, zb);
+    LinOpt geglu;
+    geglu.act = 2;
+    LCU_TRY(linear(c, w.ff1, C, 2 * M, rows, a, gl, 0, geglu));
+    return linear(c, w.ff2, M, C, rows, gl, z, 1, back);
   }
-  LCU_TRY(linear(c, w.ff1, C, 2 * M, rows, 0, 0, 0, a, nullptr, u, 0));
+  LCU_TRY(linear(c, w.ff1, C, 2 * M, rows, a, u, 0));
   const int64_t n16 = rows * M * (int64_t)dtype_size(g.dtype) / 16;
   if (g.dtype == kBF16) geglu_kernel<bf16_t><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((const bf16_t*)u, (bf16_t*)gl, rows, M);
   else geglu_kernel<float><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((const float*)u, (float*)gl, rows, M);
   LCU_HIP(c, hipGetLastError());
-  return linear(c, w.ff2, M, C, rows, 0, 0, 0, gl, z, z, 1, zb);
-}
-
-// Residual block: x [N][P][cin] fp32 -> y [N][P][cout] fp32 (y distinct from x); h and sc are work maps.
-lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int H, int W, const float* x, float* h, float* sc, float* y) {
-  const lc_unet_config& g = c->cfg;
-  const int N = g.B * g.F, P = H * W;
-  float* tb = (float*)(c->arena + c->plan.off_tb);
-  const unsigned blocks = (unsigned)((g.B * w.cout + 3) / 4);
-  if (g.dtype == kBF16)
-    temb_bias_kernel<bf16_t><<<blocks, 256, 0, c->cs>>>((const bf16_t*)temb, w.temb_w, w.temb_b, w.conv1.b, tb, g.B, w.cout, g.temb_dim);
-  else
-    temb_bias_kernel<float><<<blocks, 256, 0, c->cs>>>((const float*)temb, w.temb_w, w.temb_b, w.conv1.b, tb, g.B, w.cout, g.temb_dim);
-  LCU_HIP(c, hipGetLastError());
-  LCU_TRY(gn(c, x, N, P, w.cin, w.gn1));
-  for (int b = 0; b < g.B; ++b)  // the time embedding is one vector per batch element: its frames share a bias
-    LCU_TRY(conv(c, w.conv1, tb + (size_t)b * w.cout, 2, w.cin, w.cout, g.F, b * g.F, H, W, x + (size_t)b * g.F * P * w.cin, nullptr,
-                 h + (size_t)b * g.F * P * w.cout, 0, w.cout));
-  const float* res = x;
-  if (w.shortcut.w) {
-    const int64_t rows = (int64_t)N * P;
-    if (g.dtype == kBF16 && w.cout % 160 == 0 && w.cin % 64 == 0 && (size_t)rows * w.cin <= (size_t)N * g.H * g.W * g.C * 2 * g.ff_mult) {
-      // x rounded to bf16 in a pass of its own (into the feed-forward's buffer, idle here), then dense bf16 rows
-      bf16_t* xb = (bf16_t*)(c->arena + c->plan.off_u);
-      const int64_t n = rows * (w.cin / 8);
-      gn_apply_kernel<<<(unsigned)((n + 255) / 256), 256, 0, c->cs>>>(x, (const float*)(c->arena + c->plan.off_one),
-                                                                     (const float*)(c->arena + c->plan.off_zero), xb, rows, w.cin / 8, P);
-      LCU_HIP(c, hipGetLastError());
-      LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, rows, 0, 0, 0, xb, nullptr, sc, 1));
-    } else {
-      LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, rows, 1, 1, P, x, nullptr, sc, 1));
-    }
-    res = sc;
-  }
-  LCU_TRY(gn(c, h, N, P, w.cout, w.gn2));
-  return conv(c, w.conv2, w.conv2.b, 2, w.cout, w.cout, N, 0, H, W, h, res, y, 0, w.cout);
-}
-
-// Transformer block in place on x [N][P][C] fp32; z is a work map. Spatial: tokens = the P positions of a frame,
-// with cross-attention to cond [B][ctx_len][ctx_dim]; temporal: tokens = the F frames of a position.
-lc_status tf_block(lc_unet* c, const TfP& w, const void* cond, int H, int W, float* x, float* z) {
-  const lc_unet_config& g = c->cfg;
-  const UPlan& p = c->plan;
-  const int N = g.B * g.F, P = H * W, C = w.C, heads = C / g.head_dim;
-  const int64_t rows = (int64_t)N * P;
-  const size_t es = dtype_size(g.dtype);
-  char *a = c->arena + p.off_a, *qkv = c->arena + p.off_qkv, *vt = c->arena + p.off_vt, *ao = c->arena + p.off_ao;
-  LCU_TRY(gn(c, x, N, P, C, w.gn));
-  // where the dense-row kernel applies (bf16, width a multiple of 160) the projections' operands are rounded in
-  // passes of their own and contracted as dense bf16 rows; otherwise they are converted inside the contraction
-  const bool b16 = g.dtype == kBF16 && C % 160 == 0;
-  if (b16) {
-    const int64_t n = rows * (C / 8);
-    gn_apply_kernel<<<(unsigned)((n + 255) / 256), 256, 0, c->cs>>>(x, (const float*)(c->arena + p.off_scale),
-                                                                   (const float*)(c->arena + p.off_shift), (bf16_t*)a, rows, C / 8, P);
-    LCU_HIP(c, hipGetLastError());
-    LCU_TRY(linear(c, w.pin, C, C, rows, 0, 0, 0, a, nullptr, z, 1));
-  } else {
-    LCU_TRY(linear(c, w.pin, C, C, rows, 1, 0, P, x, nullptr, z, 1));
-  }
-  // self-attention
-  LCU_TRY(ln(c, z, w.ln1, w.pe, a, rows, C, P));
-  // (spatial: the q columns leave the projection multiplied by log2(e) / sqrt(d), as the attention kernel's
-  // cheaper softmax path wants them)
-  LCU_TRY(linear(c, w.qkv, C, 3 * C, rows, 0, 0, 0, a, nullptr, qkv, 0, nullptr, 0, w.cross ? C : 0));
-  if (w.cross) {
-    const int Tp = attn_tp(P);
-    LCU_HIP(c, launch_make_vt(c->cs, g.dtype, qkv + (size_t)2 * C * es, 3 * C, vt, N, P, Tp, C));
-    LCU_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * C, vt, Tp, ao, N, P, heads, g.head_dim, 0, P, 1));
-  } else {
-    LCU_HIP(c, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, P, heads, g.head_dim));
-  }
-  LCU_TRY(linear(c, w.wo1, C, C, rows, 0, 0, 0, ao, z, z, 1));
-  if (w.cross) {  // queries from the tokens, keys and values from the conditioning tokens of the batch element
-    char *kv = c->arena + p.off_kv, *vtx = c->arena + p.off_vtx;
-    const int L = g.ctx_len, TpL = attn_tp(L);
-    LCU_TRY(ln(c, z, w.ln2, nullptr, a, rows, C, P));
-    LCU_TRY(linear(c, w.q2, C, C, rows, 0, 0, 0, a, nullptr, qkv, 0));
-    LCU_TRY(linear(c, w.kv2, g.ctx_dim, 2 * C, (int64_t)g.B * L, 0, 0, 0, cond, nullptr, kv, 0));
-    LCU_HIP(c, launch_make_vt(c->cs, g.dtype, kv + (size_t)C * es, 2 * C, vtx, g.B, L, TpL, C));
-    LCU_HIP(c, launch_cross_attention(c->cs, g.dtype, qkv, C, kv, 2 * C, vtx, TpL, ao, N, P, L, g.F, heads, g.head_dim));
-    LCU_TRY(linear(c, w.wo2, C, C, rows, 0, 0, 0, ao, z, z, 1));
-  }
-  LCU_TRY(feed_forward(c, w, z, rows, P, b16 ? a : nullptr));
-  if (b16) return linear(c, w.pout, C, C, rows, 0, 0, 0, a, x, x, 1);
-  return linear(c, w.pout, C, C, rows, 1, 1, P, z, x, x, 1);
-}
-
-lc_status down_conv(lc_unet* c, const ConvP& w, int C, int H, int W, const float* x, float* y) {
-  ConvDesc d;
-  memset(&d, 0, sizeof d);
-  d.dt = c->cfg.dtype; d.x_f32 = 1; d.y_f32 = 1; d.taps = 9; d.stride = 2; d.Cin = C; d.Cout = C; d.Cout_store = C;
-  d.w = w.w; d.bias = w.b; d.frames = c->cfg.B * c->cfg.F; d.H = H; d.W = W; d.x = x; d.y = y; d.out_map = dense_map();
-  LCU_HIP(c, launch_conv(c->cs, d));
-  return LC_OK;
-}
-
-// y [N][2H][2W][C] = conv3x3(nearest2x(x [N][H][W][C])); up is a work map
-lc_status up_conv(lc_unet* c, const ConvP& w, int C, int H, int W, const float* x, float* up, float* y) {
-  const int N = c->cfg.B * c->cfg.F;
-  LCU_HIP(c, launch_up2_rows(c->cs, x, up, N, H, W, C));
-  return conv(c, w, w.b, 1, C, C, N, 0, 2 * H, 2 * W, up, nullptr, y, 0, C);
+  return linear(c, w.ff2, M, C, rows, gl, z, 1, back);
 }
 
 lc_status concat(lc_unet* c, const float* a, int Ca, const float* b, int Cb, float* dst, int64_t rows) {
@@ -476,11 +448,188 @@ lc_status concat(lc_unet* c, const float* a, int Ca, const float* b, int Cb, flo
   return LC_OK;
 }
 
+// Residual block on [N][P][cin] fp32 -> y [N][P][cout] fp32 (y none of the inputs), a chunk of frames at a time. The
+// input is xa, or, when Cb > 0, the channel concatenation of xa [N][P][Ca] and xb [N][P][Cb], put together chunk by
+// chunk: the concatenated tensor of all frames never exists.
+lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int level, const float* xa, int Ca, const float* xb, int Cb, float* y) {
+  const lc_unet_config& g = c->cfg;
+  const UPlan& p = c->plan;
+  const int H = g.H >> level, W = g.W >> level, P = H * W;
+  float* tb = (float*)(c->arena + p.off_tb);
+  float *xc = (float*)(c->arena + p.off_xc), *h = (float*)(c->arena + p.off_h), *sc = (float*)(c->arena + p.off_sc);
+  const unsigned blocks = (unsigned)((g.B * w.cout + 3) / 4);
+  if (g.dtype == kBF16)
+    temb_bias_kernel<bf16_t><<<blocks, 256, 0, c->cs>>>((const bf16_t*)temb, w.temb_w, w.temb_b, w.conv1.b, tb, g.B, w.cout, g.temb_dim);
+  else
+    temb_bias_kernel<float><<<blocks, 256, 0, c->cs>>>((const float*)temb, w.temb_w, w.temb_b, w.conv1.b, tb, g.B, w.cout, g.temb_dim);
+  LCU_HIP(c, hipGetLastError());
+  return frame_chunks(c, level, [&](int n0, int nc) -> lc_status {
+    const float* x = xa + (size_t)n0 * P * Ca;
+    if (Cb) {
+      LCU_TRY(concat(c, x, Ca, xb + (size_t)n0 * P * Cb, Cb, xc, (int64_t)nc * P));
+      x = xc;
+    }
+    LCU_TRY(gn(c, x, nc, P, w.cin, w.gn1));
+    // the time embedding is one vector per batch element: its frames share a bias
+    LCU_TRY(batch_runs(g, n0, nc, [&](int b, int i0, int n) {
+      return conv(c, w.conv1, tb + (size_t)b * w.cout, 2, w.cin, w.cout, n, i0, H, W, x + (size_t)i0 * P * w.cin, nullptr,
+                  h + (size_t)i0 * P * w.cout, 0, w.cout);
+    }));
+    const float* res = x;
+    if (w.shortcut.w) {
+      const int64_t rows = (int64_t)nc * P;
+      if (g.dtype == kBF16 && w.cout % 160 == 0) {
+        // x rounded to bf16 in a pass of its own, then contracted as dense bf16 rows
+        void* xb16 = c->arena + p.off_xb;
+        LCU_TRY(gn_apply(c, x, (const float*)(c->arena + p.off_one), (const float*)(c->arena + p.off_zero), xb16, rows, w.cin, P, dense_map()));
+        LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, rows, xb16, sc, 1));
+      } else {
+        LinOpt o;
+        o.scale = (const float*)(c->arena + p.off_one); o.shift = (const float*)(c->arena + p.off_zero); o.in_map = RowMap{0, P, P};
+        LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, rows, x, sc, 1, o));
+      }
+      res = sc;
+    }
+    LCU_TRY(gn(c, h, nc, P, w.cout, w.gn2));
+    return conv(c, w.conv2, w.conv2.b, 2, w.cout, w.cout, nc, 0, H, W, h, res, y + (size_t)n0 * P * w.cout, 0, w.cout);
+  });
+}
+
+// The inside of a transformer block on `rows` rows gathered from x by m (m.rows_per_seg consecutive ones per frame):
+// projection in, self-attention, cross-attention (spatial blocks), feed-forward, projection out and the residual,
+// written back through m. scale / shift: GroupNorm of x, the frame of the first row first. attend / cross run the
+// attention core from the chunk's q,k,v (or q) buffer into its attention-output buffer.
+template <class Attend, class Cross>
+lc_status tf_rows(lc_unet* c, const TfP& w, float* x, RowMap m, const float* scale, const float* shift, int64_t rows, Attend attend,
+                  Cross cross) {
+  const lc_unet_config& g = c->cfg;
+  const UPlan& p = c->plan;
+  const int C = w.C, rpf = m.rows_per_seg;
+  float* z = (float*)(c->arena + p.off_z);
+  char *a = c->arena + p.off_a, *qkv = c->arena + p.off_qkv, *ao = c->arena + p.off_ao;
+  // where the dense-row kernel applies (bf16, width a multiple of 160) the projections' operands are rounded in
+  // passes of their own and contracted as dense bf16 rows; otherwise they are converted inside the contraction
+  const bool b16 = g.dtype == kBF16 && C % 160 == 0;
+  if (b16) {
+    LCU_TRY(gn_apply(c, x, scale, shift, a, rows, C, rpf, m));
+    LCU_TRY(linear(c, w.pin, C, C, rows, a, z, 1));
+  } else {
+    LinOpt o;
+    o.scale = scale; o.shift = shift; o.in_map = m;
+    LCU_TRY(linear(c, w.pin, C, C, rows, x, z, 1, o));
+  }
+  LinOpt onto_z;
+  onto_z.res = z;
+  // self-attention (spatial: the q columns leave the projection multiplied by log2(e) / sqrt(d), as the attention
+  // kernel's cheaper softmax path wants them)
+  LCU_TRY(ln(c, z, w.ln1, w.pe, a, rows, C, rpf));
+  LinOpt q_scaled;
+  q_scaled.q_cols = w.cross ? C : 0;
+  LCU_TRY(linear(c, w.qkv, C, 3 * C, rows, a, qkv, 0, q_scaled));
+  LCU_TRY(attend());
+  LCU_TRY(linear(c, w.wo1, C, C, rows, ao, z, 1, onto_z));
+  if (w.cross) {  // queries from the tokens, keys and values from the conditioning tokens of the batch element
+    LCU_TRY(ln(c, z, w.ln2, nullptr, a, rows, C, rpf));
+    LCU_TRY(linear(c, w.q2, C, C, rows, a, qkv, 0));
+    LCU_TRY(cross());
+    LCU_TRY(linear(c, w.wo2, C, C, rows, ao, z, 1, onto_z));
+  }
+  LCU_TRY(feed_forward(c, w, z, rows, rpf, b16 ? a : nullptr));
+  LinOpt back;
+  back.res = x; back.out_map = m;
+  if (b16) return linear(c, w.pout, C, C, rows, a, x, 1, back);
+  back.scale = (const float*)(c->arena + p.off_one); back.shift = (const float*)(c->arena + p.off_zero); back.in_map = RowMap{0, rpf, rpf};
+  return linear(c, w.pout, C, C, rows, z, x, 1, back);
+}
+
+// Spatial transformer block in place on x [N][P][C] fp32, a chunk of frames at a time: tokens = the P positions of a
+// frame, with cross-attention to cond [B][ctx_len][ctx_dim].
+lc_status st_block(lc_unet* c, const TfP& w, const void* cond, int level, float* x) {
+  const lc_unet_config& g = c->cfg;
+  const UPlan& p = c->plan;
+  const int N = g.B * g.F, P = (g.H >> level) * (g.W >> level), C = w.C, heads = C / g.head_dim, Tp = attn_tp(P), L = g.ctx_len, TpL = attn_tp(L);
+  const size_t es = dtype_size(g.dtype);
+  char *qkv = c->arena + p.off_qkv, *vt = c->arena + p.off_vt, *ao = c->arena + p.off_ao, *kv = c->arena + p.off_kv,
+       *vtx = c->arena + p.off_vtx;
+  LCU_TRY(gn(c, x, N, P, C, w.gn));
+  // keys and values of the conditioning tokens: the same for every frame of a batch element
+  LCU_TRY(linear(c, w.kv2, g.ctx_dim, 2 * C, (int64_t)g.B * L, cond, kv, 0));
+  LCU_HIP(c, launch_make_vt(c->cs, g.dtype, kv + (size_t)C * es, 2 * C, vtx, g.B, L, TpL, C));
+  return frame_chunks(c, level, [&](int n0, int nc) -> lc_status {
+    auto attend = [&]() -> lc_status {
+      LCU_HIP(c, launch_make_vt(c->cs, g.dtype, qkv + (size_t)2 * C * es, 3 * C, vt, nc, P, Tp, C));
+      LCU_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * C, vt, Tp, ao, nc, P, heads, g.head_dim, 0, P, 1));
+      return LC_OK;
+    };
+    auto cross = [&]() -> lc_status {
+      return batch_runs(g, n0, nc, [&](int b, int i0, int n) -> lc_status {
+        const size_t r0 = (size_t)i0 * P * C * es;
+        LCU_HIP(c, launch_cross_attention(c->cs, g.dtype, qkv + r0, C, kv + (size_t)b * L * 2 * C * es, 2 * C,
+                                          vtx + (size_t)b * C * TpL * es, TpL, ao + r0, n, P, L, n, heads, g.head_dim));
+        return LC_OK;
+      });
+    };
+    const float* scale = (const float*)(c->arena + p.off_scale) + (size_t)n0 * C;
+    const float* shift = (const float*)(c->arena + p.off_shift) + (size_t)n0 * C;
+    return tf_rows(c, w, x + (size_t)n0 * P * C, RowMap{0, P, P}, scale, shift, (int64_t)nc * P, attend, cross);
+  });
+}
+
+// Temporal transformer block in place on x [N][P][C] fp32: tokens = the F frames of a position, a chunk of positions
+// (of every frame) at a time. The GroupNorm statistics are those of the whole frames, taken before any position is
+// rewritten.
+lc_status tt_block(lc_unet* c, const TfP& w, int level, float* x) {
+  const lc_unet_config& g = c->cfg;
+  const UPlan& p = c->plan;
+  const int N = g.B * g.F, P = (g.H >> level) * (g.W >> level), C = w.C, heads = C / g.head_dim;
+  char *qkv = c->arena + p.off_qkv, *ao = c->arena + p.off_ao;
+  LCU_TRY(gn(c, x, N, P, C, w.gn));
+  const float* scale = (const float*)(c->arena + p.off_scale);
+  const float* shift = (const float*)(c->arena + p.off_shift);
+  const int pc = pos_chunk(P, p.nc[level], N);
+  for (int p0 = 0; p0 < P; p0 += pc) {
+    const int n = std::min(pc, P - p0);
+    auto attend = [&]() -> lc_status {
+      LCU_HIP(c, launch_temporal_attention(c->cs, g.dtype, qkv, ao, g.B, g.F, n, heads, g.head_dim));
+      return LC_OK;
+    };
+    auto cross = []() -> lc_status { return LC_OK; };
+    LCU_TRY(tf_rows(c, w, x, RowMap{p0, P, n}, scale, shift, (int64_t)N * n, attend, cross));
+  }
+  return LC_OK;
+}
+
+// y [N][H/2][W/2][C] (level `level`) = conv3x3 of stride 2 over x [N][H][W][C] (the level above)
+lc_status down_conv(lc_unet* c, const ConvP& w, int C, int level, const float* x, float* y) {
+  const int H = c->cfg.H >> (level - 1), W = c->cfg.W >> (level - 1);
+  return frame_chunks(c, level, [&](int n0, int nc) -> lc_status {
+    ConvDesc d;
+    memset(&d, 0, sizeof d);
+    d.dt = c->cfg.dtype; d.x_f32 = 1; d.y_f32 = 1; d.taps = 9; d.stride = 2; d.Cin = C; d.Cout = C; d.Cout_store = C;
+    d.w = w.w; d.bias = w.b; d.frames = nc; d.H = H; d.W = W; d.x = x + (size_t)n0 * H * W * C; d.y = y + (size_t)n0 * (H / 2) * (W / 2) * C;
+    d.out_map = dense_map();
+    LCU_HIP(c, launch_conv(c->cs, d));
+    return LC_OK;
+  });
+}
+
+// y [N][2H][2W][C] (level `level`) = conv3x3(nearest2x(x [N][H][W][C])) (the level below); the upsampled map exists
+// for one chunk of frames at a time
+lc_status up_conv(lc_unet* c, const ConvP& w, int C, int level, const float* x, float* y) {
+  const int H = c->cfg.H >> (level + 1), W = c->cfg.W >> (level + 1);
+  float* up = (float*)(c->arena + c->plan.off_up);
+  return frame_chunks(c, level, [&](int n0, int nc) -> lc_status {
+    LCU_HIP(c, launch_up2_rows(c->cs, x + (size_t)n0 * H * W * C, up, nc, H, W, C));
+    return conv(c, w, w.b, 1, C, C, nc, 0, 2 * H, 2 * W, up, nullptr, y + (size_t)n0 * 4 * H * W * C, 0, C);
+  });
+}
+
 lc_status run_step(lc_unet* c, const void* x, const void* temb, const void* cond, void* eps, int slot, bool full) {
   const lc_unet_config& g = c->cfg;
   const UPlan& p = c->plan;
   const int N = g.B * g.F, H = g.H, W = g.W, P = H * W;
-  float *m0 = map_ptr(c, 0), *m1 = map_ptr(c, 1), *m2 = map_ptr(c, 2), *m3 = map_ptr(c, 3);
+  const size_t es = dtype_size(g.dtype);
+  float *m0 = map_ptr(c, 0), *m1 = map_ptr(c, 1), *m2 = map_ptr(c, 2);
   float* s = (float*)(c->arena + p.off_s);
   float* d1 = (float*)(c->arena + p.off_d1);
   float* deep = (float*)slot_ptr(c, slot);
@@ -488,33 +637,35 @@ lc_status run_step(lc_unet* c, const void* x, const void* temb, const void* cond
   LCU_HIP(c, launch_fill_f32(c->cs, (float*)(c->arena + p.off_one), (int64_t)N * maxC, 1.f));
   LCU_HIP(c, launch_fill_f32(c->cs, (float*)(c->arena + p.off_zero), (int64_t)N * maxC, 0.f));
   // ---- shallow down: s = TT(ST(RB(conv_in(x))))
-  LCU_HIP(c, launch_conv_in(c->cs, g.dtype, x, m0, N, H, W, g.C_lat, g.C, c->cin_w, c->cin_b));
-  LCU_TRY(res_block(c, c->rb[0], temb, H, W, m0, m1, m2, s));
-  LCU_TRY(tf_block(c, c->st[0], cond, H, W, s, m0));
-  LCU_TRY(tf_block(c, c->tt[0], nullptr, H, W, s, m0));
+  LCU_TRY(frame_chunks(c, 0, [&](int n0, int nc) -> lc_status {
+    LCU_HIP(c, launch_conv_in(c->cs, g.dtype, (const char*)x + (size_t)n0 * g.C_lat * P * es, m0 + (size_t)n0 * P * g.C, nc, H, W, g.C_lat,
+                              g.C, c->cin_w, c->cin_b));
+    return LC_OK;
+  }));
+  LCU_TRY(res_block(c, c->rb[0], temb, 0, m0, g.C, nullptr, 0, s));
+  LCU_TRY(st_block(c, c->st[0], cond, 0, s));
+  LCU_TRY(tt_block(c, c->tt[0], 0, s));
   if (full) {
-    const int H1 = H / 2, W1 = W / 2, H2 = H / 4, W2 = W / 4;
     // ---- level 1 down: d1 = TT(ST(RB(Down(s))))
-    LCU_TRY(down_conv(c, c->down[0], g.C, H, W, s, m0));
-    LCU_TRY(res_block(c, c->rb[1], temb, H1, W1, m0, m1, m2, d1));
-    LCU_TRY(tf_block(c, c->st[1], cond, H1, W1, d1, m0));
-    LCU_TRY(tf_block(c, c->tt[1], nullptr, H1, W1, d1, m0));
+    LCU_TRY(down_conv(c, c->down[0], g.C, 1, s, m0));
+    LCU_TRY(res_block(c, c->rb[1], temb, 1, m0, g.C, nullptr, 0, d1));
+    LCU_TRY(st_block(c, c->st[1], cond, 1, d1));
+    LCU_TRY(tt_block(c, c->tt[1], 1, d1));
     // ---- level 2: e = UpC(RB(RB(Down(d1))))
-    LCU_TRY(down_conv(c, c->down[1], g.C1, H1, W1, d1, m0));
-    LCU_TRY(res_block(c, c->rb[2], temb, H2, W2, m0, m1, m2, m3));
-    LCU_TRY(res_block(c, c->rb[3], temb, H2, W2, m3, m1, m2, m0));
-    LCU_TRY(up_conv(c, c->up[0], g.C2, H2, W2, m0, m1, m2));      // e in m2 [N][P1][C2]
+    LCU_TRY(down_conv(c, c->down[1], g.C1, 2, d1, m0));
+    LCU_TRY(res_block(c, c->rb[2], temb, 2, m0, g.C1, nullptr, 0, m1));
+    LCU_TRY(res_block(c, c->rb[3], temb, 2, m1, g.C2, nullptr, 0, m0));
+    LCU_TRY(up_conv(c, c->up[0], g.C2, 1, m0, m2));                // e in m2 [N][P1][C2]
     // ---- level 1 up: d = TT(ST(RB(Concat(d1, e))))
-    LCU_TRY(concat(c, d1, g.C1, m2, g.C2, m0, (int64_t)N * H1 * W1));
-    LCU_TRY(res_block(c, c->rb[4], temb, H1, W1, m0, m1, m2, m3));
-    LCU_TRY(tf_block(c, c->st[2], cond, H1, W1, m3, m0));
-    LCU_TRY(tf_block(c, c->tt[2], nullptr, H1, W1, m3, m0));
+    LCU_TRY(res_block(c, c->rb[4], temb, 1, d1, g.C1, m2, g.C2, m1));
+    LCU_TRY(st_block(c, c->st[2], cond, 1, m1));
+    LCU_TRY(tt_block(c, c->tt[2], 1, m1));
     // ---- the cached feature: deep = UpC(d), written to the slot, which may still be the source of a swap-out
     //      or the target of a swap-in on the side stream
     LCU_HIP(c, hipStreamWaitEvent(c->cs, c->ev_rd_done[slot], 0));
     LCU_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
     c->in_pending[slot] = 0;
-    LCU_TRY(up_conv(c, c->up[1], g.C1, H1, W1, m3, m0, deep));
+    LCU_TRY(up_conv(c, c->up[1], g.C1, 0, m1, deep));
     LCU_HIP(c, hipEventRecord(c->ev_produced[slot], c->cs));
     c->dev_filled[slot] = 1;
   } else if (c->in_pending[slot]) {
@@ -522,13 +673,15 @@ lc_status run_step(lc_unet* c, const void* x, const void* temb, const void* cond
     c->in_pending[slot] = 0;
   }
   // ---- shallow up: u = TT(ST(RB(Concat(s, deep)))); eps = conv_out(SiLU(GN(u)))
-  LCU_TRY(concat(c, s, g.C, deep, g.C1, m0, (int64_t)N * P));
+  LCU_TRY(res_block(c, c->rb[5], temb, 0, s, g.C, deep, g.C1, m1));
   LCU_HIP(c, hipEventRecord(c->ev_consumed[slot], c->cs));
-  LCU_TRY(res_block(c, c->rb[5], temb, H, W, m0, m1, m2, m3));
-  LCU_TRY(tf_block(c, c->st[3], cond, H, W, m3, m0));
-  LCU_TRY(tf_block(c, c->tt[3], nullptr, H, W, m3, m0));
-  LCU_TRY(gn(c, m3, N, P, g.C, c->out_gn));
-  return conv(c, c->out, c->out.b, 2, g.C, 32, N, 0, H, W, m3, nullptr, eps, 1, g.C_lat);
+  LCU_TRY(st_block(c, c->st[3], cond, 0, m1));
+  LCU_TRY(tt_block(c, c->tt[3], 0, m1));
+  return frame_chunks(c, 0, [&](int n0, int nc) -> lc_status {
+    LCU_TRY(gn(c, m1 + (size_t)n0 * P * g.C, nc, P, g.C, c->out_gn));
+    return conv(c, c->out, c->out.b, 2, g.C, 32, nc, 0, H, W, m1 + (size_t)n0 * P * g.C, nullptr, (char*)eps + (size_t)n0 * g.C_lat * P * es, 1,
+                g.C_lat);
+  });
 }
 
 lc_status step_checks(lc_unet* c, const void* x, const void* temb, const void* cond, void* eps, int slot) {
@@ -547,7 +700,12 @@ extern "C" {
 const char* lc_unet_last_error(const lc_unet* c) { return c ? c->err.c_str() : g_uerr.c_str(); }
 lc_status lc_unet_check_config(const lc_unet_config* cfg) { return check_ucfg(nullptr, cfg); }
 size_t lc_unet_entry_bytes(const lc_unet_config* cfg) { return check_ucfg(nullptr, cfg) == LC_OK ? entry_bytes(*cfg) : 0; }
-size_t lc_unet_workspace_bytes(const lc_unet_config* cfg) { return check_ucfg(nullptr, cfg) == LC_OK ? make_uplan(*cfg).total : 0; }
+size_t lc_unet_workspace_bytes(const lc_unet_config* cfg) { return check_ucfg(nullptr, cfg) == LC_OK ? make_uplan(*cfg, 0).total : 0; }
+size_t lc_unet_chunk_workspace_bytes(const lc_unet_config* cfg, int frame_chunk) {
+  if (check_ucfg(nullptr, cfg) != LC_OK) return 0;
+  if (frame_chunk < 0) { g_uerr = "frame_chunk must be >= 0"; return 0; }
+  return make_uplan(*cfg, frame_chunk).total;
+}
 
 lc_status lc_unet_destroy(lc_unet* c) {
   if (!c) return LC_OK;
@@ -570,7 +728,8 @@ lc_status lc_unet_create(const lc_unet_config* cfg, void* compute_stream, void* 
   if (!c) return ufail(nullptr, LC_ERR_NOMEM, "out of host memory");
   c->cfg = *cfg;
   c->cs = (hipStream_t)compute_stream; c->ss = (hipStream_t)side_stream;
-  c->plan = make_uplan(c->cfg);
+  c->frame_chunk = 0;
+  c->plan = make_uplan(c->cfg, 0);
   c->arena = nullptr; c->arena_bytes = 0; c->have_weights = false; c->wblob = nullptr;
   for (int i = 0; i < cfg->host_slots; ++i) {
     void* p = nullptr;
@@ -772,6 +931,17 @@ lc_status lc_unet_set_workspace(lc_unet* c, void* arena, size_t bytes) {
   c->arena = (char*)arena; c->arena_bytes = bytes;
   std::fill(c->dev_filled.begin(), c->dev_filled.end(), 0);
   std::fill(c->in_pending.begin(), c->in_pending.end(), 0);
+  return LC_OK;
+}
+
+lc_status lc_unet_set_chunk(lc_unet* c, int frame_chunk) {
+  if (!c) return ufail(nullptr, LC_ERR_ARG, "ctx is NULL");
+  if (frame_chunk < 0) return ufail(c, LC_ERR_ARG, "frame_chunk must be >= 0");
+  const UPlan np = make_uplan(c->cfg, frame_chunk);
+  if (c->arena && np.total > c->arena_bytes)
+    return ufail(c, LC_ERR_NOMEM, "chunk setting needs %zu bytes, workspace has %zu", np.total, c->arena_bytes);
+  c->frame_chunk = frame_chunk;  // (the skips and the device slots sit at chunk-independent offsets)
+  c->plan = np;
   return LC_OK;
 }
 

@@ -156,6 +156,15 @@ def test_unet_config_checks_and_footprint_without_a_gpu():
     assert ws > 2 * lcb.lc_unet_entry_bytes(c)   # the device slots are part of it
     more = lcb.make_unet_config(cfg, dev_slots=3)
     assert lcb.lc_unet_workspace_bytes(more) - ws == lcb.lc_unet_entry_bytes(c)
+    # feature chunk: what lives inside a block scales with the chunk, what passes between blocks does not
+    by_chunk = {fc: lcb.lc_unet_chunk_workspace_bytes(c, fc) for fc in (0, 1, 2, 4, 8, 16, 32, 40)}
+    assert by_chunk[0] == by_chunk[32] == by_chunk[40] == ws
+    assert by_chunk[1] < by_chunk[2] < by_chunk[4] < by_chunk[8] < by_chunk[16] < by_chunk[32]
+    inside = {fc: by_chunk[fc] - by_chunk[1] for fc in (2, 4, 8, 16, 32)}
+    for fc in (4, 8, 16, 32):   # linear in the chunk, up to the 256-byte rounding of each buffer
+        assert abs(inside[fc] - (fc - 1) * inside[2]) <= 1 << 14, fc
+    assert by_chunk[4] < 0.6 * ws
+    assert lcb.lc_unet_chunk_workspace_bytes(c, -1) == 0
     for field, value in [("H", 6), ("C", 100), ("C1", 4096), ("groups", 7), ("head_dim", 24), ("C_lat", 17), ("ff_mult", 5), ("F", 0),
                          ("F", 64), ("ctx_dim", 100), ("dev_slots", 0), ("host_slots", 65), ("gn_eps", 0.0), ("ln_eps", -1.0)]:
         bad = lcb.make_unet_config(cfg)

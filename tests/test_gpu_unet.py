@@ -1,6 +1,7 @@
 """GPU parity of the U-Net stage with real block internals: normal and cache steps through the C ABI against the CPU
 oracle (eps and the cached feature), the method's invariants (cache step on its own cache entry == normal step, bit
-for bit; the cache bank byte-identical), a refresh-interval schedule with swapping, errors."""
+for bit; the cache bank byte-identical; every feature-chunk setting == all frames at once, bit for bit), a
+refresh-interval schedule with swapping, errors."""
 import numpy as np
 import pytest
 import torch
@@ -35,11 +36,11 @@ def to_rows(deep, cfg):
     return np.ascontiguousarray(deep.transpose(0, 2, 3, 1)).reshape(cfg.N, cfg.H * cfg.W, cfg.C1)
 
 
-def run_case(cfg, odtype=np.float64, sharp=4.0, chain=False):
-    print(f"\n[case] {cfg.name} B={cfg.B} F={cfg.F} {cfg.H}x{cfg.W} C={cfg.C}/{cfg.C1}/{cfg.C2} d={cfg.head_dim} ctx {cfg.ctx_len}x{cfg.ctx_dim} {cfg.dtype}",
+def run_case(cfg, odtype=np.float64, sharp=4.0, chain=False, frame_chunk=None):
+    print(f"\n[case] {cfg.name} chunk={frame_chunk} B={cfg.B} F={cfg.F} {cfg.H}x{cfg.W} C={cfg.C}/{cfg.C1}/{cfg.C2} d={cfg.head_dim} ctx {cfg.ctx_len}x{cfg.ctx_dim} {cfg.dtype}",
           flush=True)
     w = synth.make_unet_weights(cfg, 0, sharp=sharp)
-    net = lcb.Unet(cfg, w, host_slots=1, dev_slots=2)
+    net = lcb.Unet(cfg, w, host_slots=1, dev_slots=2, frame_chunk=frame_chunk)
     try:
         x, temb, ctx = synth.make_unet_inputs(cfg, 1)
         xd, td, cd = net.to_device(x), net.to_device(temb), net.to_device(ctx)
@@ -69,6 +70,82 @@ def run_case(cfg, odtype=np.float64, sharp=4.0, chain=False):
 @pytest.mark.parametrize("cfg", [TINY, SMALL_F32, SMALL_BF16], ids=lambda c: c.name)
 def test_steps_match_oracle(cfg):
     run_case(cfg)
+
+
+@pytest.mark.parametrize("cfg,frame_chunk", [(SMALL_F32, 2), (SMALL_BF16, 3)], ids=["small_f32-2", "small_bf16-3"])
+def test_chunked_steps_match_oracle(cfg, frame_chunk):
+    """The same comparison with the feature chunk on, in a workspace sized for the chunk: 2 of 6 frames (every chunk
+    inside one batch element), and 3 of 16 (a ragged last chunk, chunks that straddle the two batch elements, position
+    chunks of the temporal blocks that end inside an image row)."""
+    run_case(cfg, frame_chunk=frame_chunk)
+
+
+@pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16], ids=lambda c: c.name)
+def test_chunked_equals_unchunked_bitwise(cfg):
+    """Every chunk setting gives the normal step's eps, the cached feature and the cache step's eps of the run over all
+    frames at once, bit for bit; the cached entries survive a change of the setting."""
+    w = synth.make_unet_weights(cfg, 0, sharp=4.0)
+    net = lcb.Unet(cfg, w, host_slots=1, dev_slots=2)
+    try:
+        x, temb, ctx = synth.make_unet_inputs(cfg, 1)
+        xd, td, cd = net.to_device(x), net.to_device(temb), net.to_device(ctx)
+        x2, t2, c2 = (net.to_device(a) for a in synth.make_unet_inputs(cfg, 8))
+        ref, ref2 = net.empty(*x.shape), net.empty(*x.shape)
+        net.full_step(xd, td, cd, ref, 0)
+        net.cached_step(x2, t2, c2, ref2, 0)
+        net.sync()
+        d0 = net.dev_entry(0)
+        assert bool(torch.isfinite(ref).all()) and not torch.equal(ref, ref2)
+        whole = lcb.lc_unet_workspace_bytes(net.ccfg)
+        for fc in (1, 2, 3, cfg.F, cfg.N - 1, cfg.N, cfg.N + 5):
+            print(f"[chunk] {cfg.name} frame_chunk {fc}", flush=True)
+            net.set_chunk(fc)
+            assert lcb.lc_unet_chunk_workspace_bytes(net.ccfg, fc) <= whole
+            out2 = net.empty(*x.shape)
+            net.cached_step(x2, t2, c2, out2, 0)  # on the entry the unchunked normal step left
+            net.sync()
+            assert torch.equal(out2, ref2), fc
+            out, out3 = net.empty(*x.shape), net.empty(*x.shape)
+            net.full_step(xd, td, cd, out, 1)
+            net.cached_step(x2, t2, c2, out3, 1)
+            net.sync()
+            assert torch.equal(out, ref), fc
+            assert torch.equal(net.dev_entry(1), d0), fc
+            assert torch.equal(out3, ref2), fc
+        net.set_chunk(0)
+        again = net.empty(*x.shape)
+        net.full_step(xd, td, cd, again, 0)
+        net.sync()
+        assert torch.equal(again, ref)
+    finally:
+        net.close()
+
+
+def test_benchmark_size_chunked_equals_unchunked():
+    """The benchmark's configuration with a feature chunk of 4 of its 32 frames, in a workspace sized for that chunk,
+    against the run over all frames at once in a workspace of its own: eps of the normal step, the cached feature and
+    eps of a cache step agree bit for bit."""
+    cfg = synth.UNETS["sd15_video"]
+    w = synth.make_unet_weights(cfg, 0)
+    x, temb, ctx = synth.make_unet_inputs(cfg, 1)
+    results = []
+    for fc in (None, 4):
+        net = lcb.Unet(cfg, w, host_slots=0, dev_slots=1, frame_chunk=fc)
+        try:
+            print(f"[chunk] sd15_video frame_chunk {fc}: workspace {net.arena.numel() / 1e9:.3f} GB", flush=True)
+            xd, td, cd = net.to_device(x), net.to_device(temb), net.to_device(ctx)
+            full, cached = net.empty(*x.shape), net.empty(*x.shape)
+            net.full_step(xd, td, cd, full, 0)
+            net.cached_step(xd, td, cd, cached, 0)
+            net.sync()
+            results.append((full.clone(), cached.clone(), net.dev_entry(0), net.arena.numel()))
+        finally:
+            net.close()
+            del net
+    (f0, c0, d0, b0), (f1, c1, d1, b1) = results
+    assert bool(torch.isfinite(f0).all())
+    assert torch.equal(f1, f0) and torch.equal(c1, c0) and torch.equal(d1, d0)
+    assert b1 < 0.6 * b0
 
 
 @pytest.mark.slow
@@ -214,6 +291,7 @@ def test_unet_errors():
         small = torch.empty(1 << 16, dtype=torch.uint8, device=net.device)
         assert status(lcb.lc_unet_set_workspace, net.ctx, small.data_ptr(), small.numel()) == lcb.LC_ERR_NOMEM
         assert status(lcb.lc_unet_set_workspace, net.ctx, small.data_ptr() + 8, small.numel()) == lcb.LC_ERR_ARG
+        assert status(net.set_chunk, -1) == lcb.LC_ERR_ARG
         assert status(lcb.lc_unet_full_step, net.ctx, None, td.data_ptr(), cd.data_ptr(), out.data_ptr(), 0) == lcb.LC_ERR_ARG
         assert status(lcb.lc_unet_load_weights, net.ctx, lcb.lc_unet_weights()) == lcb.LC_ERR_ARG
         net.full_step(xd, td, cd, out, 0)
