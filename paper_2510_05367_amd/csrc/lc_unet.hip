@@ -178,7 +178,7 @@ struct UPlan {
   int nc[3];         // frames per chunk at H x W, H/2 x W/2, H/4 x W/4
   size_t map_bytes;  // one map of all frames: the largest tensor that passes between two blocks
   size_t off_map[3], off_s, off_d1, off_slots, slot_bytes;
-  size_t off_part, off_scale, off_shift, off_one, off_zero, off_tb, off_kv, off_vtx;
+  size_t off_part, off_parta, off_partb, off_scale, off_shift, off_one, off_zero, off_tb, off_kv, off_vtx;
   size_t off_xc, off_h, off_sc, off_xb, off_up;                   // one chunk inside a residual block or a resampling
   size_t off_z, off_a, off_qkv, off_vt, off_ao, off_u, off_g;     // one chunk inside a transformer block (same memory)
   size_t total;
@@ -196,6 +196,7 @@ struct lc_unet {
   bool have_weights;
   void* wblob;
   float *cin_w, *cin_b;
+  void* cin_wp;  // conv_in weights as rows [C][64] of the operand type (k = plane * 9 + tap, zero padded), or nullptr
   RbP rb[6];
   TfP st[4], tt[4];
   ConvP down[2], up[2], out;
@@ -280,8 +281,15 @@ UPlan make_uplan(const lc_unet_config& g, int frame_chunk) {
   const int64_t full = N * std::max({P * g.C, P1 * g.C, P1 * g.C1, P1 * g.C2, P2 * g.C1, P2 * g.C2});
   // rows * width of a transformer block's chunk at its largest (level 0 or level 1)
   const int64_t tok = N * std::max((int64_t)pos_chunk((int)P, p.nc[0], (int)N) * g.C, (int64_t)pos_chunk((int)P1, p.nc[1], (int)N) * g.C1);
-  const int64_t splits_c = std::max({(int64_t)stat_splits((int)P) * (g.C + g.C1), (int64_t)stat_splits((int)P1) * std::max(g.C1 + g.C2, g.C),
-                                     (int64_t)stat_splits((int)P2) * std::max(g.C1, g.C2)});
+  // partial sums per frame: the statistics kernel's 64-row splits, or the (at most twice as many) 32-pixel splits
+  // that the convolutions write beside their output, times the widest tensor of the level
+  auto splits_of = [&](int lvl) {
+    const int H = g.H >> lvl, W = g.W >> lvl;
+    return (int64_t)std::max({stat_splits(H * W), conv_stat_splits(H, W), (H * W + 31) / 32});
+  };
+  const int64_t splits_c = std::max({splits_of(0) * (g.C + g.C1), splits_of(1) * std::max(g.C1 + g.C2, g.C), splits_of(2) * std::max(g.C1, g.C2)});
+  // the same for what one block hands to the next: a block's output of all frames
+  const int64_t splits_o = std::max({splits_of(0) * g.C, splits_of(1) * g.C1, splits_of(2) * g.C2});
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   p.map_bytes = align_up((size_t)full * 4);
@@ -291,6 +299,8 @@ UPlan make_uplan(const lc_unet_config& g, int frame_chunk) {
   p.slot_bytes = align_up(entry_bytes(g));
   p.off_slots = off; off += p.slot_bytes * g.dev_slots;
   p.off_part = take((size_t)N * splits_c * 2 * 4);
+  p.off_parta = take((size_t)N * splits_o * 2 * 4);
+  p.off_partb = take((size_t)N * splits_o * 2 * 4);
   p.off_scale = take((size_t)N * maxC * 4);
   p.off_shift = take((size_t)N * maxC * 4);
   p.off_one = take((size_t)N * maxC * 4);
@@ -345,20 +355,28 @@ lc_status batch_runs(const lc_unet_config& g, int n0, int nc, Fn fn) {
 }
 
 // ---- operators -------------------------------------------------------------------------------------------------
-// scale / shift (frame 0 of x first) of GroupNorm(x) for n frames of fp32 rows [rows][C]
-lc_status gn(lc_unet* c, const float* x, int n, int rows, int C, const NormP& w) {
+// Partial sums [frame][splits][C][2] of a tensor, written by the kernel that produced it (part == nullptr: none)
+struct Stats { const float* part; int splits; };
+
+// scale / shift (frame 0 first) of a GroupNorm over n frames of [rows][C] from the partial sums of its input
+lc_status gn_fold(lc_unet* c, Stats st, int n, int rows, int C, const NormP& w) {
   const UPlan& p = c->plan;
-  float* part = (float*)(c->arena + p.off_part);
-  LCU_HIP(c, launch_gn_stats(c->cs, kF32, x, part, n, rows, C));
-  LCU_HIP(c, launch_gn_finalize(c->cs, part, C, stat_splits(rows), rows, 1.f, nullptr, 0, 0, 0, 0.f, w.g, w.b, c->cfg.groups,
-                                c->cfg.gn_eps, (float*)(c->arena + p.off_scale), (float*)(c->arena + p.off_shift), n));
+  LCU_HIP(c, launch_gn_finalize(c->cs, st.part, C, st.splits, rows, 1.f, nullptr, 0, 0, 0, 0.f, w.g, w.b, c->cfg.groups, c->cfg.gn_eps,
+                                (float*)(c->arena + p.off_scale), (float*)(c->arena + p.off_shift), n));
   return LC_OK;
+}
+// the same from the tensor itself, fp32 rows x: a pass of the statistics kernel first
+lc_status gn(lc_unet* c, const float* x, int n, int rows, int C, const NormP& w) {
+  float* part = (float*)(c->arena + c->plan.off_part);
+  LCU_HIP(c, launch_gn_stats(c->cs, kF32, x, part, n, rows, C));
+  return gn_fold(c, Stats{part, stat_splits(rows)}, n, rows, C, w);
 }
 
 // y = [res +] conv3x3(act(x)) over n frames; src 2: SiLU(GroupNorm(x)) with the scale / shift at hand (those of frame
 // `f0` on), src 1: x as it is. planar: y is [n][Cout_store][H][W] of the stage's dtype (the last convolution).
+// stat: where the partial sums of y go ([frame of the launch][conv_stat_splits(H, W)][Cout][2]), or nullptr.
 lc_status conv(lc_unet* c, const ConvP& w, const float* bias, int src, int Cin, int Cout, int n, int f0, int H, int W, const float* x,
-               const float* res, void* y, int planar, int Cout_store) {
+               const float* res, void* y, int planar, int Cout_store, float* stat = nullptr) {
   const UPlan& p = c->plan;
   FusedDesc f;
   memset(&f, 0, sizeof f);
@@ -367,6 +385,7 @@ lc_status conv(lc_unet* c, const ConvP& w, const float* bias, int src, int Cin, 
   f.scale = (const float*)(c->arena + (src == 2 ? p.off_scale : p.off_one)) + (size_t)f0 * Cin;
   f.shift = (const float*)(c->arena + (src == 2 ? p.off_shift : p.off_zero)) + (size_t)f0 * Cin;
   f.in_map = f.out_map = dense_map();
+  if (stat) { f.stat = stat; f.stat_splits = conv_stat_splits(H, W); }
   LCU_HIP(c, launch_fused(c->cs, f));
   return LC_OK;
 }
@@ -450,13 +469,18 @@ lc_status concat(lc_unet* c, const float* a, int Ca, const float* b, int Cb, flo
 
 // Residual block on [N][P][cin] fp32 -> y [N][P][cout] fp32 (y none of the inputs), a chunk of frames at a time. The
 // input is xa, or, when Cb > 0, the channel concatenation of xa [N][P][Ca] and xb [N][P][Cb], put together chunk by
-// chunk: the concatenated tensor of all frames never exists.
-lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int level, const float* xa, int Ca, const float* xb, int Cb, float* y) {
+// chunk: the concatenated tensor of all frames never exists. in: the partial sums of xa (all frames), if its producer
+// wrote them and there is no xb. out: where those of y go (all frames), or nullptr. The convolutions write the partial
+// sums of what they store, so the second GroupNorm, and the one of the block that follows, need no pass of their own.
+lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int level, const float* xa, int Ca, const float* xb, int Cb, float* y,
+                    Stats in = Stats{nullptr, 0}, float* out = nullptr) {
   const lc_unet_config& g = c->cfg;
   const UPlan& p = c->plan;
   const int H = g.H >> level, W = g.W >> level, P = H * W;
   float* tb = (float*)(c->arena + p.off_tb);
   float *xc = (float*)(c->arena + p.off_xc), *h = (float*)(c->arena + p.off_h), *sc = (float*)(c->arena + p.off_sc);
+  float* part = (float*)(c->arena + p.off_part);
+  const int cs = conv_stat_splits(H, W);
   const unsigned blocks = (unsigned)((g.B * w.cout + 3) / 4);
   if (g.dtype == kBF16)
     temb_bias_kernel<bf16_t><<<blocks, 256, 0, c->cs>>>((const bf16_t*)temb, w.temb_w, w.temb_b, w.conv1.b, tb, g.B, w.cout, g.temb_dim);
@@ -469,11 +493,13 @@ lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int level, const
       LCU_TRY(concat(c, x, Ca, xb + (size_t)n0 * P * Cb, Cb, xc, (int64_t)nc * P));
       x = xc;
     }
-    LCU_TRY(gn(c, x, nc, P, w.cin, w.gn1));
+    if (in.part && !Cb) LCU_TRY(gn_fold(c, Stats{in.part + (size_t)n0 * in.splits * w.cin * 2, in.splits}, nc, P, w.cin, w.gn1));
+    else LCU_TRY(gn(c, x, nc, P, w.cin, w.gn1));
     // the time embedding is one vector per batch element: its frames share a bias
+    // (the scale / shift of x are folded by now: the partial sums of h may take the scratch)
     LCU_TRY(batch_runs(g, n0, nc, [&](int b, int i0, int n) {
       return conv(c, w.conv1, tb + (size_t)b * w.cout, 2, w.cin, w.cout, n, i0, H, W, x + (size_t)i0 * P * w.cin, nullptr,
-                  h + (size_t)i0 * P * w.cout, 0, w.cout);
+                  h + (size_t)i0 * P * w.cout, 0, w.cout, part + (size_t)i0 * cs * w.cout * 2);
     }));
     const float* res = x;
     if (w.shortcut.w) {
@@ -490,8 +516,9 @@ lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int level, const
       }
       res = sc;
     }
-    LCU_TRY(gn(c, h, nc, P, w.cout, w.gn2));
-    return conv(c, w.conv2, w.conv2.b, 2, w.cout, w.cout, nc, 0, H, W, h, res, y + (size_t)n0 * P * w.cout, 0, w.cout);
+    LCU_TRY(gn_fold(c, Stats{part, cs}, nc, P, w.cout, w.gn2));
+    return conv(c, w.conv2, w.conv2.b, 2, w.cout, w.cout, nc, 0, H, W, h, res, y + (size_t)n0 * P * w.cout, 0, w.cout,
+                out ? out + (size_t)n0 * cs * w.cout * 2 : nullptr);
   });
 }
 
@@ -544,14 +571,16 @@ lc_status tf_rows(lc_unet* c, const TfP& w, float* x, RowMap m, const float* sca
 
 // Spatial transformer block in place on x [N][P][C] fp32, a chunk of frames at a time: tokens = the P positions of a
 // frame, with cross-attention to cond [B][ctx_len][ctx_dim].
-lc_status st_block(lc_unet* c, const TfP& w, const void* cond, int level, float* x) {
+// in: the partial sums of x, if its producer wrote them.
+lc_status st_block(lc_unet* c, const TfP& w, const void* cond, int level, float* x, Stats in = Stats{nullptr, 0}) {
   const lc_unet_config& g = c->cfg;
   const UPlan& p = c->plan;
   const int N = g.B * g.F, P = (g.H >> level) * (g.W >> level), C = w.C, heads = C / g.head_dim, Tp = attn_tp(P), L = g.ctx_len, TpL = attn_tp(L);
   const size_t es = dtype_size(g.dtype);
   char *qkv = c->arena + p.off_qkv, *vt = c->arena + p.off_vt, *ao = c->arena + p.off_ao, *kv = c->arena + p.off_kv,
        *vtx = c->arena + p.off_vtx;
-  LCU_TRY(gn(c, x, N, P, C, w.gn));
+  if (in.part) LCU_TRY(gn_fold(c, in, N, P, C, w.gn));
+  else LCU_TRY(gn(c, x, N, P, C, w.gn));
   // keys and values of the conditioning tokens: the same for every frame of a batch element
   LCU_TRY(linear(c, w.kv2, g.ctx_dim, 2 * C, (int64_t)g.B * L, cond, kv, 0));
   LCU_HIP(c, launch_make_vt(c->cs, g.dtype, kv + (size_t)C * es, 2 * C, vtx, g.B, L, TpL, C));
@@ -636,29 +665,41 @@ lc_status run_step(lc_unet* c, const void* x, const void* temb, const void* cond
   const int maxC = std::max({g.C + g.C1, g.C1 + g.C2, g.C2});
   LCU_HIP(c, launch_fill_f32(c->cs, (float*)(c->arena + p.off_one), (int64_t)N * maxC, 1.f));
   LCU_HIP(c, launch_fill_f32(c->cs, (float*)(c->arena + p.off_zero), (int64_t)N * maxC, 0.f));
+  // Partial sums of a block's output for the GroupNorm that reads it next, written by the convolution that stores it
+  // (two buffers: a residual block reads its input's while it writes its output's).
+  float *pa = (float*)(c->arena + p.off_parta), *pb = (float*)(c->arena + p.off_partb);
+  const int cs0 = conv_stat_splits(H, W), cs1 = conv_stat_splits(H / 2, W / 2), cs2 = conv_stat_splits(H / 4, W / 4);
   // ---- shallow down: s = TT(ST(RB(conv_in(x))))
+  Stats cin_st{nullptr, 0};
   LCU_TRY(frame_chunks(c, 0, [&](int n0, int nc) -> lc_status {
-    LCU_HIP(c, launch_conv_in(c->cs, g.dtype, (const char*)x + (size_t)n0 * g.C_lat * P * es, m0 + (size_t)n0 * P * g.C, nc, H, W, g.C_lat,
-                              g.C, c->cin_w, c->cin_b));
+    const char* xc = (const char*)x + (size_t)n0 * g.C_lat * P * es;
+    float* y = m0 + (size_t)n0 * P * g.C;
+    // the tiled kernel where the shape allows it (a property of the configuration, never of the chunk)
+    hipError_t e = c->cin_wp ? launch_conv_in_tile(c->cs, g.dtype, xc, c->cin_wp, c->cin_b, y, pa + (size_t)n0 * (P / 32) * g.C * 2, nc, H, W,
+                                                   g.C_lat, g.C, Win{0, 0, 0, 0})
+                             : hipErrorNotSupported;
+    if (e == hipSuccess) { cin_st = Stats{pa, P / 32}; return LC_OK; }
+    if (e != hipErrorNotSupported) LCU_HIP(c, e);
+    LCU_HIP(c, launch_conv_in(c->cs, g.dtype, xc, y, nc, H, W, g.C_lat, g.C, c->cin_w, c->cin_b));
     return LC_OK;
   }));
-  LCU_TRY(res_block(c, c->rb[0], temb, 0, m0, g.C, nullptr, 0, s));
-  LCU_TRY(st_block(c, c->st[0], cond, 0, s));
+  LCU_TRY(res_block(c, c->rb[0], temb, 0, m0, g.C, nullptr, 0, s, cin_st, pb));
+  LCU_TRY(st_block(c, c->st[0], cond, 0, s, Stats{pb, cs0}));
   LCU_TRY(tt_block(c, c->tt[0], 0, s));
   if (full) {
     // ---- level 1 down: d1 = TT(ST(RB(Down(s))))
     LCU_TRY(down_conv(c, c->down[0], g.C, 1, s, m0));
-    LCU_TRY(res_block(c, c->rb[1], temb, 1, m0, g.C, nullptr, 0, d1));
-    LCU_TRY(st_block(c, c->st[1], cond, 1, d1));
+    LCU_TRY(res_block(c, c->rb[1], temb, 1, m0, g.C, nullptr, 0, d1, Stats{nullptr, 0}, pa));
+    LCU_TRY(st_block(c, c->st[1], cond, 1, d1, Stats{pa, cs1}));
     LCU_TRY(tt_block(c, c->tt[1], 1, d1));
     // ---- level 2: e = UpC(RB(RB(Down(d1))))
     LCU_TRY(down_conv(c, c->down[1], g.C1, 2, d1, m0));
-    LCU_TRY(res_block(c, c->rb[2], temb, 2, m0, g.C1, nullptr, 0, m1));
-    LCU_TRY(res_block(c, c->rb[3], temb, 2, m1, g.C2, nullptr, 0, m0));
+    LCU_TRY(res_block(c, c->rb[2], temb, 2, m0, g.C1, nullptr, 0, m1, Stats{nullptr, 0}, pa));
+    LCU_TRY(res_block(c, c->rb[3], temb, 2, m1, g.C2, nullptr, 0, m0, Stats{pa, cs2}, nullptr));
     LCU_TRY(up_conv(c, c->up[0], g.C2, 1, m0, m2));                // e in m2 [N][P1][C2]
     // ---- level 1 up: d = TT(ST(RB(Concat(d1, e))))
-    LCU_TRY(res_block(c, c->rb[4], temb, 1, d1, g.C1, m2, g.C2, m1));
-    LCU_TRY(st_block(c, c->st[2], cond, 1, m1));
+    LCU_TRY(res_block(c, c->rb[4], temb, 1, d1, g.C1, m2, g.C2, m1, Stats{nullptr, 0}, pa));
+    LCU_TRY(st_block(c, c->st[2], cond, 1, m1, Stats{pa, cs1}));
     LCU_TRY(tt_block(c, c->tt[2], 1, m1));
     // ---- the cached feature: deep = UpC(d), written to the slot, which may still be the source of a swap-out
     //      or the target of a swap-in on the side stream
@@ -673,9 +714,9 @@ lc_status run_step(lc_unet* c, const void* x, const void* temb, const void* cond
     c->in_pending[slot] = 0;
   }
   // ---- shallow up: u = TT(ST(RB(Concat(s, deep)))); eps = conv_out(SiLU(GN(u)))
-  LCU_TRY(res_block(c, c->rb[5], temb, 0, s, g.C, deep, g.C1, m1));
+  LCU_TRY(res_block(c, c->rb[5], temb, 0, s, g.C, deep, g.C1, m1, Stats{nullptr, 0}, pa));
   LCU_HIP(c, hipEventRecord(c->ev_consumed[slot], c->cs));
-  LCU_TRY(st_block(c, c->st[3], cond, 0, m1));
+  LCU_TRY(st_block(c, c->st[3], cond, 0, m1, Stats{pa, cs0}));
   LCU_TRY(tt_block(c, c->tt[3], 0, m1));
   return frame_chunks(c, 0, [&](int n0, int nc) -> lc_status {
     LCU_TRY(gn(c, m1 + (size_t)n0 * P * g.C, nc, P, g.C, c->out_gn));
@@ -849,6 +890,11 @@ lc_status lc_unet_load_weights(lc_unet* c, const lc_unet_weights* w) {
     c->cin_w = (float*)take((size_t)g.C_lat * 9 * C * 4);
     if (fill) note(launch_pack_conv_in_w(s, dt, w->conv_in.w, c->cin_w, C, g.C_lat));
     c->cin_b = f32(w->conv_in.b, C);
+    c->cin_wp = nullptr;
+    if (dt == kBF16 && g.C_lat * 9 <= 48) {  // what the tiled first convolution reads
+      c->cin_wp = take((size_t)C * 64 * es);
+      if (fill) note(launch_pad_rows(s, dt, w->conv_in.w, c->cin_wp, C, g.C_lat * 9, 64));
+    }
     for (int i = 0; i < 6; ++i) {
       const lc_unet_rb_w& r = w->rb[i];
       RbP& q = c->rb[i];
