@@ -16,6 +16,8 @@
 // channel tiles of one row tile are mapped to the same XCD, so its L2 fetches that tile of x once.
 #include "lc_internal.h"
 
+#include <type_traits>
+
 namespace lc {
 
 namespace {
@@ -44,6 +46,38 @@ struct Lin2Args {
 };
 
 }  // namespace
+
+
+// bf16 stores of a 32-row half tile, two channels per lane: lanes l and l ^ 1 hold channels c, c + 1 of the same rows;
+// they trade halves so that the even lane holds both channels of the even row of a pair and the odd lane both of the
+// odd row, and each stores 4 bytes: a wavefront instruction then writes 64 consecutive bytes of two rows instead of
+// 64 bytes of one with 2-byte stores. NV: column tiles (32 channels each) in val's second index.
+template <int NV, int NTV, bool MAPPED>
+__device__ __forceinline__ void store_pairs(const float (&val)[16][NTV], bf16_t* __restrict__ Y, int ldy, int c0, int64_t rbase,
+                                            int64_t rows, const RowMap& out_map, int lane, std::integral_constant<bool, MAPPED>) {
+  const int lp = lane & 31;
+  const bool odd = lane & 1;
+  // v_perm_b32 selectors (bytes 0-3: own pair, 4-7: the neighbour's): even (own lo, neighbour's lo), odd (neighbour's hi, own hi)
+  const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+#pragma unroll
+  for (int rp = 0; rp < 16; rp += 2) {
+    uint32_t out[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      bf16x2 p2;
+      p2[0] = static_cast<bf16_t>(val[rp][i]);
+      p2[1] = static_cast<bf16_t>(val[rp + 1][i]);
+      const uint32_t own = __builtin_bit_cast(uint32_t, p2);
+      const uint32_t nb = (uint32_t)__builtin_amdgcn_mov_dpp((int)own, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+      out[i] = __builtin_amdgcn_perm(nb, own, sel);
+    }
+    const int64_t dr = rbase + 8 * (rp >> 2) + (rp & 3) + (odd ? 1 : 0);
+    if (dr >= rows) continue;
+    const int64_t row = MAPPED ? out_map(dr) : dr;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) *reinterpret_cast<uint32_t*>(Y + row * ldy + c0 + 32 * i + (lp & ~1)) = out[i];
+  }
+}
 
 // MAPPED: rows go through the row maps (a 64-bit division per row: kept out of the common, dense case, where the
 // host folds the maps' offsets into the pointers; the arithmetic, and so every bit of the result, is the same)
@@ -197,27 +231,22 @@ __global__ __launch_bounds__(256, ST == 2 ? 2 : 1) void lin2_kernel(Lin2Args a) 
             val[r][q] = val[r][2 * q] * gelu_tanh_fast(val[r][2 * q + 1]);
             asm volatile("" : "+v"(val[r][q]));
           }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int64_t dr = rbase + 8 * (r >> 2) + (r & 3);
-          if (dr >= a.rows) continue;
-          const int64_t row = MAPPED ? a.out_map(dr) : dr;
-#pragma unroll
-          for (int q = 0; q < NT / 2; ++q) Y[row * (a.N / 2) + n0 / 2 + 32 * q + lp] = from_f32<OT>(val[r][q]);
-        }
+        store_pairs<NT / 2>(val, (bf16_t*)a.y, a.N / 2, n0 / 2, rbase, a.rows, a.out_map, lane, std::integral_constant<bool, MAPPED>{});
         continue;
       }
     }
+    if constexpr (sizeof(OT) == 2) {
+      store_pairs<NT>(val, (bf16_t*)a.y, a.N, n0, rbase, a.rows, a.out_map, lane, std::integral_constant<bool, MAPPED>{});
+    } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int64_t dr = rbase + 8 * (r >> 2) + (r & 3);
-      if (dr >= a.rows) continue;
-      const int64_t row = MAPPED ? a.out_map(dr) : dr;
+      for (int r = 0; r < 16; ++r) {
+        const int64_t dr = rbase + 8 * (r >> 2) + (r & 3);
+        if (dr >= a.rows) continue;
+        const int64_t row = MAPPED ? a.out_map(dr) : dr;
 #pragma unroll
-      for (int i = 0; i < NT; ++i) {
-        Y[row * a.N + n0 + 32 * i + lp] = from_f32<OT>(val[r][i]);
-        if (sizeof(OT) == 4 && a.y2) a.y2[row * a.N + n0 + 32 * i + lp] = static_cast<bf16_t>(val[r][i]);
+        for (int i = 0; i < NT; ++i) Y[row * a.N + n0 + 32 * i + lp] = from_f32<OT>(val[r][i]);
       }
+      if (a.y2) store_pairs<NT>(val, a.y2, a.N, n0, rbase, a.rows, a.out_map, lane, std::integral_constant<bool, MAPPED>{});
     }
   }
 }

@@ -23,7 +23,7 @@ def w64_of(w):
     return {k: v.astype(np.float64) for k, v in w.items()}
 
 
-@pytest.mark.parametrize("cfg,chunk", [(DIT_F32, 0), (DIT_F32, 64), (DIT_BF16, 70), (DIT_BF16_W, 32)], ids=lambda v: getattr(v, "name", str(v)))
+@pytest.mark.parametrize("cfg,chunk", [(DIT_F32, 0), (DIT_F32, 64), (DIT_BF16, 70), (DIT_BF16, 33), (DIT_BF16_W, 32)], ids=lambda v: getattr(v, "name", str(v)))
 def test_steps_match_oracle(cfg, chunk):
     print(f"\n[case] {cfg.name} B={cfg.B} T={cfg.T} D={cfg.D} L={cfg.L} cached [{cfg.cache_a},{cfg.cache_b}) chunk {chunk}", flush=True)
     w = synth.make_dit_weights(cfg, 0, sharp=8.0)  # logit std of about 8: a peaked softmax
