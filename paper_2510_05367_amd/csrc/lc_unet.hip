@@ -5,7 +5,8 @@
 // Swapping" section: a normal step stores it, a cache step runs the shallow blocks only and concatenates it).
 // The convolutions, GroupNorm statistics, linear layers and attention cores are the kernels of the denoising stage
 // (the cross-attention is the spatial kernel reading its keys from the conditioning tokens); new here are four
-// bandwidth kernels: LayerNorm with affine (+ frame encoding), GEGLU, the time-embedding bias, channel concat.
+// bandwidth kernels: LayerNorm with affine (+ frame encoding), GEGLU, the time-embedding bias, channel concat (with the
+// statistics and the rounding of the concatenated rows in the same pass).
 // Activations are fp32 channels-last rows [frame][position][channel]; matrix operands have the stage's dtype.
 #include <hip/hip_runtime.h>
 
@@ -142,16 +143,63 @@ __global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__
   store16(y + r * C8 * 8 + c, o);
 }
 
-// dst[r][0:Ca] = a[r][:], dst[r][Ca:Ca+Cb] = b[r][:]; fp32, Ca and Cb multiples of 4; thread = one 16-byte packet
-__global__ __launch_bounds__(256) void concat_rows_kernel(const float* __restrict__ a, const float* __restrict__ b,
-                                                          float* __restrict__ dst, int64_t rows, int Ca4, int Cb4) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int w = Ca4 + Cb4;
-  if (i >= rows * w) return;
-  const int64_t r = i / w;
-  const int c = (int)(i - r * w);
-  reinterpret_cast<f32x4*>(dst)[i] = c < Ca4 ? reinterpret_cast<const f32x4*>(a)[r * Ca4 + c]
-                                             : reinterpret_cast<const f32x4*>(b)[r * Cb4 + (c - Ca4)];
+// dst[r][0:Ca] = a[r][:], dst[r][Ca:Ca+Cb] = b[r][:] (fp32, Ca and Cb multiples of 4), fused with what the residual
+// block needs of the concatenated rows next: their GroupNorm partial sums (partial[frame][split][Ca + Cb][2], 64-row splits as the statistics kernel writes them, folded in
+// the same fixed order) and, when yb != nullptr, a copy rounded to bf16 (the operand of the 1x1 shortcut). One
+// workgroup = one split of one frame and up to 256 packets of 4 channels (gridDim.z of them side by side).
+__global__ __launch_bounds__(256) void concat_stats_kernel(const float* __restrict__ a, const float* __restrict__ b,
+                                                           float* __restrict__ dst, bf16_t* __restrict__ yb,
+                                                           float* __restrict__ partial, int rows_per_frame, int Ca4, int Cb4) {
+  __shared__ float red[2][256 * 4];
+  const int W4 = Ca4 + Cb4;
+  const int cv0 = blockIdx.z * 256;
+  const int cv = min(W4 - cv0, 256);
+  const int R = 256 / cv;
+  const int split = blockIdx.x, frame = blockIdx.y, splits = gridDim.x;
+  const int tid = threadIdx.x;
+  const int cvec = tid % cv, rsub = tid / cv;
+  float s4[4] = {0.f, 0.f, 0.f, 0.f}, q4[4] = {0.f, 0.f, 0.f, 0.f};
+  const int r0 = split * kStatRows;
+  const int r1 = min(r0 + kStatRows, rows_per_frame);
+  if (rsub < R) {
+    const int c = cv0 + cvec;
+    const bool from_a = c < Ca4;
+    const f32x4* src = from_a ? reinterpret_cast<const f32x4*>(a) + (int64_t)frame * rows_per_frame * Ca4 + c
+                              : reinterpret_cast<const f32x4*>(b) + (int64_t)frame * rows_per_frame * Cb4 + (c - Ca4);
+    const int ld = from_a ? Ca4 : Cb4;
+    for (int r = r0 + rsub; r < r1; r += R) {
+      const f32x4 v = src[(int64_t)r * ld];
+      const int64_t o = ((int64_t)frame * rows_per_frame + r) * W4 + c;
+      reinterpret_cast<f32x4*>(dst)[o] = v;
+      if (yb) {
+        bf16x4 h;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = static_cast<bf16_t>(v[e]);
+        reinterpret_cast<bf16x4*>(yb)[o] = h;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s4[e] += v[e];
+        q4[e] = fmaf(v[e], v[e], q4[e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    red[0][tid * 4 + e] = s4[e];
+    red[1][tid * 4 + e] = q4[e];
+  }
+  __syncthreads();
+  for (int c = tid; c < cv * 4; c += 256) {
+    float ss = 0.f, qq = 0.f;
+    for (int j = 0; j < R; ++j) {
+      ss += red[0][j * cv * 4 + c];
+      qq += red[1][j * cv * 4 + c];
+    }
+    float* pp = partial + (((int64_t)frame * splits + split) * (W4 * 4) + cv0 * 4 + c) * 2;
+    pp[0] = ss;
+    pp[1] = qq;
+  }
 }
 
 }  // namespace lc
@@ -460,9 +508,13 @@ lc_status feed_forward(lc_unet* c, const TfP& w, float* z, int64_t rows, int row
   return linear(c, w.ff2, M, C, rows, gl, z, 1, back);
 }
 
-lc_status concat(lc_unet* c, const float* a, int Ca, const float* b, int Cb, float* dst, int64_t rows) {
-  const int64_t n = rows * (Ca + Cb) / 4;
-  concat_rows_kernel<<<(unsigned)((n + 255) / 256), 256, 0, c->cs>>>(a, b, dst, rows, Ca / 4, Cb / 4);
+// dst [n][rows][Ca + Cb] = the channel concatenation of a and b, with its GroupNorm partial sums (64-row splits) into
+// the scratch and, when yb != nullptr, a bf16 copy: one pass instead of a concatenation, a statistics pass and a rounding
+// pass over the widest tensor of the step
+lc_status concat_stats(lc_unet* c, const float* a, int Ca, const float* b, int Cb, float* dst, void* yb, int n, int rows) {
+  const int W4 = (Ca + Cb) / 4;
+  dim3 grid(stat_splits(rows), n, (W4 + 255) / 256);
+  concat_stats_kernel<<<grid, 256, 0, c->cs>>>(a, b, dst, (bf16_t*)yb, (float*)(c->arena + c->plan.off_part), rows, Ca / 4, Cb / 4);
   LCU_HIP(c, hipGetLastError());
   return LC_OK;
 }
@@ -489,12 +541,18 @@ lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int level, const
   LCU_HIP(c, hipGetLastError());
   return frame_chunks(c, level, [&](int n0, int nc) -> lc_status {
     const float* x = xa + (size_t)n0 * P * Ca;
+    // (a shortcut through the dense-row kernel contracts x rounded to bf16)
+    const bool short16 = w.shortcut.w && g.dtype == kBF16 && w.cout % 160 == 0;
+    void* xb16 = c->arena + p.off_xb;
     if (Cb) {
-      LCU_TRY(concat(c, x, Ca, xb + (size_t)n0 * P * Cb, Cb, xc, (int64_t)nc * P));
+      LCU_TRY(concat_stats(c, x, Ca, xb + (size_t)n0 * P * Cb, Cb, xc, short16 ? xb16 : nullptr, nc, P));
       x = xc;
+      LCU_TRY(gn_fold(c, Stats{part, stat_splits(P)}, nc, P, w.cin, w.gn1));
+    } else if (in.part) {
+      LCU_TRY(gn_fold(c, Stats{in.part + (size_t)n0 * in.splits * w.cin * 2, in.splits}, nc, P, w.cin, w.gn1));
+    } else {
+      LCU_TRY(gn(c, x, nc, P, w.cin, w.gn1));
     }
-    if (in.part && !Cb) LCU_TRY(gn_fold(c, Stats{in.part + (size_t)n0 * in.splits * w.cin * 2, in.splits}, nc, P, w.cin, w.gn1));
-    else LCU_TRY(gn(c, x, nc, P, w.cin, w.gn1));
     // the time embedding is one vector per batch element: its frames share a bias
     // (the scale / shift of x are folded by now: the partial sums of h may take the scratch)
     LCU_TRY(batch_runs(g, n0, nc, [&](int b, int i0, int n) {
@@ -504,10 +562,10 @@ lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int level, const
     const float* res = x;
     if (w.shortcut.w) {
       const int64_t rows = (int64_t)nc * P;
-      if (g.dtype == kBF16 && w.cout % 160 == 0) {
-        // x rounded to bf16 in a pass of its own, then contracted as dense bf16 rows
-        void* xb16 = c->arena + p.off_xb;
-        LCU_TRY(gn_apply(c, x, (const float*)(c->arena + p.off_one), (const float*)(c->arena + p.off_zero), xb16, rows, w.cin, P, dense_map()));
+      if (short16) {
+        // x rounded to bf16 (by the concatenation, else in a pass of its own), then contracted as dense bf16 rows
+        if (!Cb)
+          LCU_TRY(gn_apply(c, x, (const float*)(c->arena + p.off_one), (const float*)(c->arena + p.off_zero), xb16, rows, w.cin, P, dense_map()));
         LCU_TRY(linear(c, w.shortcut, w.cin, w.cout, rows, xb16, sc, 1));
       } else {
         LinOpt o;
