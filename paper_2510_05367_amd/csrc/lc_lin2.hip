@@ -43,6 +43,12 @@ struct Lin2Args {
   int q_cols;
   int act;             // 0 none, 1 GELU, 2 GEGLU over alternating 32-channel blocks (y is then N / 2 wide)
   RowMap in_map, out_map;  // dense row r is row in_map(r) of x and row out_map(r) of y / res / y2
+  // bf16 output over dense rows only: channels >= yt_from are not stored in y (whose rows then have yt_from channels)
+  // but transposed into yt[r / yt_T][N - yt_from][yt_Tp] at column (t & ~63) + vcol(t & 63), t = r % yt_T: the V^T
+  // layout of the spatial attention kernel. nullptr: off. yt_from a multiple of the channel tile, yt_T of 4.
+  bf16_t* yt;
+  int yt_from, yt_T, yt_Tp;
+  int ldy;  // channels per row of y (yt_from with yt, else N; N / 2 after a GEGLU)
 };
 
 }  // namespace
@@ -222,6 +228,27 @@ __global__ __launch_bounds__(256, ST == 2 ? 2 : 1) void lin2_kernel(Lin2Args a) 
         if (sizeof(OT) == 2 && a.act == 1) val[r][i] = gelu_tanh_fast(val[r][i]);
         asm volatile("" : "+v"(val[r][i]));  // computed here: left alone, the compiler sinks it into the store's branch
       }
+    if constexpr (sizeof(OT) == 2) {
+      if (a.yt && n0 >= a.yt_from) {  // (uniform over the workgroup) a lane holds 4 consecutive rows of a channel: 8 bytes of V^T
+        const int Cv = a.N - a.yt_from;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int64_t dr = rbase + 8 * g;
+          if (dr >= a.rows) continue;  // (rows come in fours)
+          const int64_t f = dr / a.yt_T;
+          const int t = (int)(dr - f * a.yt_T);
+          bf16_t* dst = a.yt + (f * Cv + (n0 - a.yt_from) + lp) * a.yt_Tp + (t & ~63) + vcol<bf16_t>(t & 63);
+#pragma unroll
+          for (int i = 0; i < NT; ++i) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16_t>(val[4 * g + e][i]);
+            *reinterpret_cast<bf16x4*>(dst + (int64_t)32 * i * a.yt_Tp) = o;
+          }
+        }
+        continue;
+      }
+    }
     if constexpr (sizeof(OT) == 2 && NT % 2 == 0) {
       if (a.act == 2) {  // GEGLU: column tile 2 q holds 32 values, tile 2 q + 1 their gates; N / 2 channels leave
 #pragma unroll
@@ -236,7 +263,7 @@ __global__ __launch_bounds__(256, ST == 2 ? 2 : 1) void lin2_kernel(Lin2Args a) 
       }
     }
     if constexpr (sizeof(OT) == 2) {
-      store_pairs<NT>(val, (bf16_t*)a.y, a.N, n0, rbase, a.rows, a.out_map, lane, std::integral_constant<bool, MAPPED>{});
+      store_pairs<NT>(val, (bf16_t*)a.y, a.ldy, n0, rbase, a.rows, a.out_map, lane, std::integral_constant<bool, MAPPED>{});
     } else {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -274,8 +301,8 @@ static hipError_t run_lin2_mr(hipStream_t s, Lin2Args a) {
   // a map that is the identity up to an offset (one segment, or segments that follow each other) is folded into
   // the pointers
   auto plain = [&](const RowMap& m) { return m.rows_per_seg >= a.rows || m.seg_stride == m.rows_per_seg; };
-  if (!plain(a.in_map) || !plain(a.out_map)) return run_lin2_k<OT, NT, MR, true, ST>(s, a);
-  const int64_t nout = a.act == 2 ? a.N / 2 : a.N;
+  if (!plain(a.in_map) || !plain(a.out_map)) return a.yt ? hipErrorInvalidValue : run_lin2_k<OT, NT, MR, true, ST>(s, a);
+  const int64_t nout = a.ldy;
   a.x += a.in_map.base * a.K;
   a.y = (OT*)a.y + a.out_map.base * nout;
   if (a.res) a.res += a.out_map.base * nout;
@@ -294,7 +321,7 @@ static hipError_t run_lin2(hipStream_t s, Lin2Args a) {
 }
 
 hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
-  if (d.dt != kBF16 || d.taps != 1 || d.src != 0 || d.yt || d.stat || d.win_w || d.planar_out) return hipErrorNotSupported;
+  if (d.dt != kBF16 || d.taps != 1 || d.src != 0 || d.stat || d.win_w || d.planar_out) return hipErrorNotSupported;
   if (d.Cin % 64 || d.Cin <= 0 || (d.Cout % 160 && d.Cout % 128) || d.Cout_store != d.Cout) return hipErrorNotSupported;
   if (d.in_map.rows_per_seg <= 0 || d.out_map.rows_per_seg <= 0) return hipErrorInvalidValue;
   if (d.res && !d.y_f32) return hipErrorNotSupported;
@@ -302,6 +329,12 @@ hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
   if (d.y2 && !d.y_f32) return hipErrorInvalidValue;
   if (d.act && (d.y_f32 || d.res || d.q_cols || d.act > 2)) return hipErrorInvalidValue;
   if (d.act == 2 && d.Cout % 128) return hipErrorNotSupported;
+  if (d.yt) {  // the transposed tail: whole channel tiles of a bf16 output, rows in fours
+    const int tile = d.Cout % 160 == 0 ? 160 : 128;
+    if (d.y_f32 || d.res || d.act || d.y2) return hipErrorInvalidValue;
+    if (d.yt_from <= 0 || d.yt_from >= d.Cout || d.yt_from % tile || d.yt_T <= 0 || d.yt_T % 4 || d.rows % 4 || d.yt_Tp % 64 || d.yt_Tp < d.yt_T)
+      return hipErrorNotSupported;
+  }
   if (d.rows <= 0) return hipSuccess;
   if (d.rows > (int64_t)1 << 30) return hipErrorNotSupported;
   Lin2Args a;
@@ -312,6 +345,8 @@ hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
   a.q_scale = d.q_cols ? d.q_scale : 1.f; a.q_cols = d.q_cols;
   a.act = d.act;
   a.in_map = d.in_map; a.out_map = d.out_map;
+  a.yt = (bf16_t*)d.yt; a.yt_from = d.yt_from; a.yt_T = d.yt_T; a.yt_Tp = d.yt_Tp;
+  a.ldy = d.yt ? d.yt_from : (d.act == 2 ? d.Cout / 2 : d.Cout);
   if (d.act == 2) return run_lin2<bf16_t, 4>(s, a);  // (an even number of column tiles: value / gate pairs)
   if (d.Cout % 160 == 0) return d.y_f32 ? run_lin2<float, 5>(s, a) : run_lin2<bf16_t, 5>(s, a);
   return d.y_f32 ? run_lin2<float, 4>(s, a) : run_lin2<bf16_t, 4>(s, a);

@@ -446,6 +446,10 @@ struct LinOpt {
   // x is fp32 and row r is multiplied by scale[r / in_map.rows_per_seg] and shifted (GroupNorm apply) on the way in
   const float *scale = nullptr, *shift = nullptr;
   RowMap in_map = RowMap{0, 0, 1 << 30}, out_map = RowMap{0, 0, 1 << 30};
+  // channels >= yt_from leave transposed, as the V^T [frame][Cout - yt_from][yt_Tp] the spatial attention kernel
+  // stages (frames of yt_T rows); y then has yt_from channels per row
+  void* yt = nullptr;
+  int yt_from = 0, yt_T = 0, yt_Tp = 0;
 };
 
 // y[out_map(r)][Cout] = x[in_map(r)][Cin] W^T + bias [+ res], r < rows; x of the operand type unless o.scale is set
@@ -455,6 +459,7 @@ lc_status linear(lc_unet* c, const LinP& w, int Cin, int Cout, int64_t rows, con
   f.dt = c->cfg.dtype; f.y_f32 = y32; f.taps = 1; f.src = o.scale ? 1 : 0; f.Cin = Cin; f.Cout = Cout; f.Cout_store = Cout; f.w = w.w;
   f.bias = w.b; f.rows = rows; f.in_map = o.in_map; f.out_map = o.out_map; f.x = x; f.res = o.res; f.y = y; f.y2 = o.y2; f.act = o.act;
   f.scale = o.scale; f.shift = o.shift;
+  f.yt = o.yt; f.yt_from = o.yt_from; f.yt_T = o.yt_T; f.yt_Tp = o.yt_Tp;
   if (o.q_cols) { f.q_cols = o.q_cols; f.q_scale = attn_q_scale(c->cfg.head_dim); }  // softmax scale folded into q
   LCU_HIP(c, launch_fused(c->cs, f));
   return LC_OK;
@@ -586,7 +591,7 @@ lc_status res_block(lc_unet* c, const RbP& w, const void* temb, int level, const
 // attention core from the chunk's q,k,v (or q) buffer into its attention-output buffer.
 template <class Attend, class Cross>
 lc_status tf_rows(lc_unet* c, const TfP& w, float* x, RowMap m, const float* scale, const float* shift, int64_t rows, Attend attend,
-                  Cross cross) {
+                  Cross cross, void* vt = nullptr, int vt_Tp = 0) {
   const lc_unet_config& g = c->cfg;
   const UPlan& p = c->plan;
   const int C = w.C, rpf = m.rows_per_seg;
@@ -610,6 +615,9 @@ lc_status tf_rows(lc_unet* c, const TfP& w, float* x, RowMap m, const float* sca
   LCU_TRY(ln(c, z, w.ln1, w.pe, a, rows, C, rpf));
   LinOpt q_scaled;
   q_scaled.q_cols = w.cross ? C : 0;
+  if (vt) {  // spatial: q and k as rows of 2C channels, v transposed straight from the projection's epilogue
+    q_scaled.yt = vt; q_scaled.yt_from = 2 * C; q_scaled.yt_T = rpf; q_scaled.yt_Tp = vt_Tp;
+  }
   LCU_TRY(linear(c, w.qkv, C, 3 * C, rows, a, qkv, 0, q_scaled));
   LCU_TRY(attend());
   LCU_TRY(linear(c, w.wo1, C, C, rows, ao, z, 1, onto_z));
@@ -644,8 +652,7 @@ lc_status st_block(lc_unet* c, const TfP& w, const void* cond, int level, float*
   LCU_HIP(c, launch_make_vt(c->cs, g.dtype, kv + (size_t)C * es, 2 * C, vtx, g.B, L, TpL, C));
   return frame_chunks(c, level, [&](int n0, int nc) -> lc_status {
     auto attend = [&]() -> lc_status {
-      LCU_HIP(c, launch_make_vt(c->cs, g.dtype, qkv + (size_t)2 * C * es, 3 * C, vt, nc, P, Tp, C));
-      LCU_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * C, vt, Tp, ao, nc, P, heads, g.head_dim, 0, P, 1));
+      LCU_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 2 * C, vt, Tp, ao, nc, P, heads, g.head_dim, 0, P, 1));
       return LC_OK;
     };
     auto cross = [&]() -> lc_status {
@@ -658,7 +665,7 @@ lc_status st_block(lc_unet* c, const TfP& w, const void* cond, int level, float*
     };
     const float* scale = (const float*)(c->arena + p.off_scale) + (size_t)n0 * C;
     const float* shift = (const float*)(c->arena + p.off_shift) + (size_t)n0 * C;
-    return tf_rows(c, w, x + (size_t)n0 * P * C, RowMap{0, P, P}, scale, shift, (int64_t)nc * P, attend, cross);
+    return tf_rows(c, w, x + (size_t)n0 * P * C, RowMap{0, P, P}, scale, shift, (int64_t)nc * P, attend, cross, vt, Tp);
   });
 }
 
