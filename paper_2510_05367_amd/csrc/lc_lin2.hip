@@ -1,16 +1,18 @@
 // Linear layers over dense bf16 rows on gfx950: y[rows][N] = x[rows][K] W[N][K]^T (+ bias, + fp32 residual), the
 // projections and feed-forward layers of the transformer blocks, where K is a few hundred to a few thousand.
 //
-// One workgroup = 4 wavefronts = 256 rows x 160 (or 128) output channels; wavefront w owns rows [64 w, 64 w + 64) and
-// all channels (2 x 5 or 2 x 4 accumulator tiles of 32 x 32: every fragment of W feeds two MFMAs, every fragment of x
-// five or four), and
-// walks K in steps of 64 elements without splitting it. Both operands are K-major in memory, so a step's tiles are
-// rows of 128 bytes, brought from global memory straight into LDS (16 bytes per lane, no registers in between) into a
-// ring of three stages: the loads of step s + 2 are issued while step s is contracted, and the wait before a step
-// counts exactly the loads that are younger than the ones it needs. The 16-byte packet c of row r is parked in
-// slot c ^ ((r >> 1) & 7) of its row, which makes the fragment reads (32 consecutive rows, one slot) conflict-free
-// without padding. The product is not transposed (rows of x are the rows of the accumulator tile): a lane then holds
-// one output channel of 16 rows, and the 32 lanes of a half-wavefront store 32 consecutive channels of one row.
+// One workgroup = 4 wavefronts = 128 rows x 160 (or 128) output channels; wavefront w owns rows [32 w, 32 w + 32) and
+// all channels (5 or 4 accumulator tiles of 32 x 32: every fragment of x feeds five or four MFMAs), and walks K in
+// steps of 64 elements without splitting it. Both operands are K-major in memory, so a step's tiles are rows of 128
+// bytes, brought from global memory straight into LDS (16 bytes per lane, no registers in between) into a ring of two
+// stages: the loads of step s + 1 are issued as soon as those of step s have landed. Two workgroups share a compute
+// unit (2 x 74 KB of LDS, 256 registers each) and cover each other's prologue, waits and epilogue. (The first design,
+// a 256-row tile with a ring of three stages and one workgroup per compute unit, was slower at every K measured: by
+// 6 % at K = 1280, by 13-22 % from K = 1024 to 4096 where the output is narrow.) The 16-byte packet c of row r is
+// parked in slot c ^ ((r >> 1) & 7) of its row, which makes the fragment reads (32 consecutive rows, one slot)
+// conflict-free without padding. The product is not transposed (rows of x are the rows of the accumulator tile): a
+// lane then holds one output channel of 16 rows, and the 32 lanes of a half-wavefront hold 32 consecutive channels of
+// one row.
 //
 // Workgroups are dealt to the eight XCDs round robin in launch order, and each XCD has an L2 of its own: the
 // channel tiles of one row tile are mapped to the same XCD, so its L2 fetches that tile of x once.
@@ -23,12 +25,10 @@ namespace lc {
 namespace {
 
 constexpr int kKB = 128;                        // K bytes per step
-constexpr int kMaxStages = 3;
-// a workgroup takes 128 MR rows (MR = 2, or 1 where few rows would leave most of the device idle) and 32 NT channels;
-// bytes of one ring stage: the x tile, then the W tile
-constexpr int lin2_stage(int NT, int MR) { return (128 * MR + NT * 32) * kKB; }
-static_assert(kMaxStages * lin2_stage(5, 2) <= 160 * 1024, "fits the LDS of a compute unit");
-static_assert(2 * 2 * lin2_stage(5, 1) <= 160 * 1024, "two workgroups of the two-stage form fit it together");
+constexpr int kStages = 2;
+// a workgroup takes 128 rows and 32 NT channels; bytes of one ring stage: the x tile, then the W tile
+constexpr int lin2_stage(int NT) { return (128 + NT * 32) * kKB; }
+static_assert(2 * kStages * lin2_stage(5) <= 160 * 1024, "two workgroups fit the LDS of a compute unit together");
 
 struct Lin2Args {
   const bf16_t* x;     // [rows][K]
@@ -87,15 +87,11 @@ __device__ __forceinline__ void store_pairs(const float (&val)[16][NTV], bf16_t*
 
 // MAPPED: rows go through the row maps (a 64-bit division per row: kept out of the common, dense case, where the
 // host folds the maps' offsets into the pointers; the arithmetic, and so every bit of the result, is the same)
-// ST: stages of the ring. 3: one workgroup per compute unit, loads two steps ahead. 2 (with the 128-row tile): two
-// workgroups share a compute unit (LDS and registers are budgeted for that) and cover each other's waits - for the
-// short contractions, where a tile is mostly prologue and epilogue.
-template <class OT, int NT, int MR, bool MAPPED, int ST>
-__global__ __launch_bounds__(256, ST == 2 ? 2 : 1) void lin2_kernel(Lin2Args a) {
+template <class OT, int NT, bool MAPPED>
+__global__ __launch_bounds__(256, 2) void lin2_kernel(Lin2Args a) {
   typedef Mma32<bf16_t> M;
-  static_assert(ST == 3 || (ST == 2 && MR == 1), "two stages go with the small tile");
-  constexpr int kStages = ST;
-  constexpr int kM = 128 * MR, kN = NT * 32, kStage = lin2_stage(NT, MR);
+  constexpr int MR = 1;  // 32-row accumulator tiles per wavefront along the rows
+  constexpr int kM = 128 * MR, kN = NT * 32, kStage = lin2_stage(NT);
   constexpr int kXI = 4 * MR, kWI = NT;  // global->LDS instructions per wavefront per stage: x tile, W tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -161,14 +157,11 @@ __global__ __launch_bounds__(256, ST == 2 ? 2 : 1) void lin2_kernel(Lin2Args a) 
 
   const int nsteps = a.K / 64;
   issue(0, 0);
-  if (ST == 3 && nsteps > 1) issue(1, 1);
   for (int s = 0; s < nsteps; ++s) {
-    // the loads of step s have landed (for every wavefront, after the barrier); with three stages those of step
-    // s + 1 may be in flight
-    if (ST == 3 && s + 1 < nsteps) barrier_keep<kXI + kWI>();
-    else barrier_keep<0>();
+    // the loads of step s have landed (for every wavefront, after the barrier), and every wavefront has read step s - 1
+    barrier_keep<0>();
     // the next request goes into the stage that was read in step s - 1
-    if (s + ST - 1 < nsteps) issue(s + ST - 1, (s + ST - 1) % kStages);
+    if (s + 1 < nsteps) issue(s + 1, (s + 1) % kStages);
     const unsigned char* st = smem + (s % kStages) * kStage;
     typename M::Frag xf[2][MR], wf[2][NT];
 #pragma unroll
@@ -282,42 +275,33 @@ __global__ __launch_bounds__(256, ST == 2 ? 2 : 1) void lin2_kernel(Lin2Args a) 
 // hipErrorNotSupported for what it does not cover (the general kernel then runs). Which kernel runs depends on the
 // layer's widths only, never on the number of rows: a chunked pass must give the bits of the unchunked one.
 // (hipFuncSetAttribute is called once per instantiation and process: one device.)
-template <class OT, int NT, int MR, bool MAPPED, int ST>
+template <class OT, int NT, bool MAPPED>
 static hipError_t run_lin2_k(hipStream_t s, const Lin2Args& a) {
-  constexpr int lds = ST * lin2_stage(NT, MR);
+  constexpr int lds = kStages * lin2_stage(NT);
   static bool done = false;  // per instantiation
   if (!done) {
-    hipError_t e = hipFuncSetAttribute((const void*)lin2_kernel<OT, NT, MR, MAPPED, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = hipFuncSetAttribute((const void*)lin2_kernel<OT, NT, MAPPED>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     done = true;
   }
   const unsigned grid = (unsigned)((a.ntm + 7) / 8 * 8 * a.ntn);
-  lin2_kernel<OT, NT, MR, MAPPED, ST><<<grid, 256, lds, s>>>(a);
+  lin2_kernel<OT, NT, MAPPED><<<grid, 256, lds, s>>>(a);
   return hipGetLastError();
 }
-template <class OT, int NT, int MR, int ST>
-static hipError_t run_lin2_mr(hipStream_t s, Lin2Args a) {
-  a.ntm = (int)((a.rows + 128 * MR - 1) / (128 * MR));
+template <class OT, int NT>
+static hipError_t run_lin2(hipStream_t s, Lin2Args a) {
+  a.ntn = a.N / (NT * 32);
+  a.ntm = (int)((a.rows + 127) / 128);
   // a map that is the identity up to an offset (one segment, or segments that follow each other) is folded into
   // the pointers
   auto plain = [&](const RowMap& m) { return m.rows_per_seg >= a.rows || m.seg_stride == m.rows_per_seg; };
-  if (!plain(a.in_map) || !plain(a.out_map)) return a.yt ? hipErrorInvalidValue : run_lin2_k<OT, NT, MR, true, ST>(s, a);
+  if (!plain(a.in_map) || !plain(a.out_map)) return a.yt ? hipErrorInvalidValue : run_lin2_k<OT, NT, true>(s, a);
   const int64_t nout = a.ldy;
   a.x += a.in_map.base * a.K;
   a.y = (OT*)a.y + a.out_map.base * nout;
   if (a.res) a.res += a.out_map.base * nout;
   if (a.y2) a.y2 += a.out_map.base * nout;
-  return run_lin2_k<OT, NT, MR, false, ST>(s, a);
-}
-// The row tile is chosen by how many tiles there are (every output element is the same sequence of MFMAs over K
-// whatever the tile it falls in: the choice never shows in the bits).
-template <class OT, int NT>
-static hipError_t run_lin2(hipStream_t s, Lin2Args a) {
-  a.ntn = a.N / (NT * 32);
-  // short contractions: the small tile with two workgroups per compute unit
-  if (a.K <= 640) return run_lin2_mr<OT, NT, 1, 2>(s, a);
-  const int64_t big_tiles = (a.rows + 255) / 256 * a.ntn;
-  return big_tiles >= 256 ? run_lin2_mr<OT, NT, 2, 3>(s, a) : run_lin2_mr<OT, NT, 1, 3>(s, a);
+  return run_lin2_k<OT, NT, false>(s, a);
 }
 
 hipError_t launch_lin2(hipStream_t s, const FusedDesc& d) {
