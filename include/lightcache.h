@@ -376,8 +376,9 @@ lc_status lc_decoder_sync(lc_decoder* dec);
  * One block: h = LN(x) (1 + scale_msa) + shift_msa; x += gate_msa * (Attn(h) Wo^T + bo); h = LN(x) (1 + scale_mlp)
  * + shift_mlp; x += gate_mlp * (W2 gelu_tanh(W1 h + b1) + b2). LN: per token, biased variance, no affine; q,k,v
  * projections with bias; `heads` heads of `head_dim`, scale 1/sqrt(head_dim). The modulation vectors are inputs.
- * Feature chunk ([CHK]): token_chunk tokens per pass of LayerNorm / projections / MLP and queries per pass of the
- * attention (against all keys); it never changes results. Hidden states and modulation are float at the boundary;
+ * Feature chunk ([CHK]): token_chunk of the B*T tokens of a step per pass of LayerNorm / projections / MLP (a pass may
+ * run across batch elements: every row looks up its own modulation) and min(token_chunk, T) queries of every batch
+ * element per pass of the attention (against all keys); it never changes results. Hidden states and modulation are float at the boundary;
  * weights have cfg dtype (bf16: MFMA operands bf16, accumulation and the residual stream fp32).
  * Requirements (else LC_ERR_SHAPE): sizes > 0; D a multiple of 64, <= 2048; heads * head_dim == D; head_dim in
  * {8, 16, 32, 40, 64}; L <= LC_DIT_MAX_BLOCKS; 0 <= cache_a <= cache_b <= L; mlp_ratio <= 8; 1 <= dev_slots <= 8;
@@ -404,7 +405,7 @@ lc_status lc_dit_create(const lc_dit_config* cfg, void* compute_stream, void* si
 lc_status lc_dit_destroy(lc_dit* ctx);
 lc_status lc_dit_load_weights(lc_dit* ctx, const lc_dit_weights* w /* [host] struct of [device] ptrs */);
 lc_status lc_dit_set_workspace(lc_dit* ctx, void* arena /* [device], 256-byte aligned */, size_t bytes);
-lc_status lc_dit_set_chunk(lc_dit* ctx, int token_chunk); /* 0 = unchunked; values above T clamp */
+lc_status lc_dit_set_chunk(lc_dit* ctx, int token_chunk); /* 0 = unchunked; values above B*T clamp */
 /* x_in, x_out [device, B, T, D] float; mod [device, L, B, 6, D] float in the order shift_msa, scale_msa, gate_msa,
  * shift_mlp, scale_mlp, gate_mlp. Normal step: all L blocks, Delta left in device slot dev_slot. Cache step: Delta
  * read from dev_slot (LC_ERR_STATE if empty; waits on the GPU for a swap-in in flight). */

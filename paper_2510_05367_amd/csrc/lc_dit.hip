@@ -26,11 +26,16 @@ namespace lc {
 // variance and no affine of its own. x, add fp32; y of type T. D % 4 == 0, D <= 64 * 4 * LN_MAXV.
 constexpr int LN_MAXV = 8;
 template <class T>
-__global__ __launch_bounds__(256) void ln_mod_kernel(const float* __restrict__ x, const float* __restrict__ add, const float* __restrict__ shift,
-                                                     const float* __restrict__ scale, T* __restrict__ y, int rows, int D, float eps) {
+__global__ __launch_bounds__(256) void ln_mod_kernel(const float* __restrict__ x, const float* __restrict__ add, const float* __restrict__ mod,
+                                                     int which_shift, int which_scale, T* __restrict__ y, int rows, int D, float eps,
+                                                     int64_t row0, int T_tok) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
+  // the modulation vectors of the row's batch element: mod [B][6][D] of this block, row0 + row = b * T_tok + token
+  const int64_t b = (row0 + row) / T_tok;
+  const float* __restrict__ shift = mod + (b * 6 + which_shift) * D;
+  const float* __restrict__ scale = mod + (b * 6 + which_scale) * D;
   const int nv = D / 4;  // 16-byte packets per row
   const f32x4* xr = reinterpret_cast<const f32x4*>(x + (int64_t)row * D);
   const f32x4* ar = add ? reinterpret_cast<const f32x4*>(add + (int64_t)row * D) : nullptr;
@@ -89,15 +94,18 @@ __global__ __launch_bounds__(256) void gelu_kernel(T* __restrict__ h, int64_t n1
   reinterpret_cast<Vec16<T>*>(h)[i] = v;
 }
 
-// dst[r][c] += gate[c] * t[r][c] (gate == nullptr: dst += t); all fp32, D % 4 == 0
-__global__ __launch_bounds__(256) void gate_add_kernel(float* __restrict__ dst, const float* __restrict__ t, const float* __restrict__ gate,
-                                                       int64_t n4, int D4) {
+// dst[r][c] += gate[b(r)][c] * t[r][c], gate = vector `which` of mod [B][6][D], b(r) = (row0 + r) / T_tok
+// (mod == nullptr: dst += t); all fp32, D % 4 == 0
+__global__ __launch_bounds__(256) void gate_add_kernel(float* __restrict__ dst, const float* __restrict__ t, const float* __restrict__ mod,
+                                                       int which, int64_t n4, int D4, int64_t row0, int T_tok) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
   f32x4 d = reinterpret_cast<f32x4*>(dst)[i];
   const f32x4 v = reinterpret_cast<const f32x4*>(t)[i];
-  if (gate) {
-    const f32x4 g = reinterpret_cast<const f32x4*>(gate)[i % D4];
+  if (mod) {
+    const int64_t r = i / D4;
+    const int64_t b = (row0 + r) / T_tok;
+    const f32x4 g = reinterpret_cast<const f32x4*>(mod + (b * 6 + which) * D4 * 4)[i - r * D4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) d[e] = fmaf(g[e], v[e], d[e]);
   } else {
@@ -116,7 +124,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct BlkW { void *wqkv, *wo, *w1, *w2; float *bqkv, *bo, *b1, *b2; };
 struct TPlan {
-  int tc;  // tokens per chunk
+  int tc;  // rows per chunk of the per-row layers (LayerNorm, projections, MLP): tokens of the B*T of a step
+  int qc;  // queries per batch element and attention launch
   size_t off_x, off_slots, slot_bytes, off_qkv, off_vt, off_ao, off_xn, off_hid, off_t, total;
 };
 
@@ -182,7 +191,10 @@ TPlan make_tplan(const lc_dit_config& g, int token_chunk) {
   TPlan p;
   const size_t es = dtype_size(g.dtype);
   const int64_t R = (int64_t)g.B * g.T;
-  p.tc = (token_chunk <= 0 || token_chunk > g.T) ? g.T : token_chunk;
+  // the per-row layers walk the B*T rows of a step in chunks that may run across batch elements (all rows at once
+  // without a chunk); attention takes the same number of queries of every batch element, at most all T
+  p.tc = (token_chunk <= 0 || token_chunk > R) ? (int)R : token_chunk;
+  p.qc = std::min(p.tc, g.T);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   p.off_x = take((size_t)R * g.D * 4);
@@ -200,9 +212,8 @@ TPlan make_tplan(const lc_dit_config& g, int token_chunk) {
 
 inline size_t entry_bytes(const lc_dit_config& g) { return (size_t)g.B * g.T * g.D * 4; }
 inline char* slot_ptr(lc_dit* c, int s) { return c->arena + c->plan.off_slots + c->plan.slot_bytes * s; }
-inline const float* mod_ptr(const lc_dit* c, const float* mod, int blk, int b, int which) {
-  return mod + (((int64_t)blk * c->cfg.B + b) * 6 + which) * c->cfg.D;
-}
+// the six modulation vectors of every batch element for block blk: [B][6][D]
+inline const float* mod_blk(const lc_dit* c, const float* mod, int blk) { return mod + (int64_t)blk * c->cfg.B * 6 * c->cfg.D; }
 
 // y[rows][Cout] = x[rows][Cin] W^T + bias; x of the operand type, y fp32 (y32) or of the operand type
 lc_status linear(lc_dit* c, const void* w, const float* bias, int Cin, int Cout, int64_t rows, const void* x, void* y, int y32,
@@ -215,20 +226,24 @@ lc_status linear(lc_dit* c, const void* w, const float* bias, int Cin, int Cout,
   return LC_OK;
 }
 
-lc_status ln_mod(lc_dit* c, const float* x, const float* add, const float* shift, const float* scale, void* y, int rows) {
+// y = LN(x [+ add]) * (1 + scale) + shift for `rows` rows starting at row r0 of the step; the modulation vectors are
+// those of each row's batch element
+lc_status ln_mod(lc_dit* c, const float* x, const float* add, const float* mod, int which_shift, int which_scale, void* y, int rows,
+                 int64_t r0) {
   const lc_dit_config& g = c->cfg;
   const unsigned blocks = (unsigned)((rows + 3) / 4);
   if (g.dtype == kBF16)
-    ln_mod_kernel<bf16_t><<<blocks, 256, 0, c->cs>>>(x, add, shift, scale, (bf16_t*)y, rows, g.D, g.ln_eps);
+    ln_mod_kernel<bf16_t><<<blocks, 256, 0, c->cs>>>(x, add, mod, which_shift, which_scale, (bf16_t*)y, rows, g.D, g.ln_eps, r0, g.T);
   else
-    ln_mod_kernel<float><<<blocks, 256, 0, c->cs>>>(x, add, shift, scale, (float*)y, rows, g.D, g.ln_eps);
+    ln_mod_kernel<float><<<blocks, 256, 0, c->cs>>>(x, add, mod, which_shift, which_scale, (float*)y, rows, g.D, g.ln_eps, r0, g.T);
   LCT_HIP(c, hipGetLastError());
   return LC_OK;
 }
 
-lc_status gate_add(lc_dit* c, float* dst, const float* t, const float* gate, int64_t rows) {
+// dst += gate * t over `rows` rows starting at row r0 of the step (mod == nullptr: dst += t)
+lc_status gate_add(lc_dit* c, float* dst, const float* t, const float* mod, int which, int64_t rows, int64_t r0) {
   const int64_t n4 = rows * c->cfg.D / 4;
-  gate_add_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, c->cs>>>(dst, t, gate, n4, c->cfg.D / 4);
+  gate_add_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, c->cs>>>(dst, t, mod, which, n4, c->cfg.D / 4, r0, c->cfg.T);
   LCT_HIP(c, hipGetLastError());
   return LC_OK;
 }
@@ -239,8 +254,10 @@ lc_status run_block(lc_dit* c, int i, const float* mod, float* x, const float* d
   const lc_dit_config& g = c->cfg;
   const TPlan& p = c->plan;
   const int D = g.D, T = g.T, H = g.mlp_ratio * g.D, Tp = attn_tp(T);
+  const int64_t R = (int64_t)g.B * T;
   const size_t es = dtype_size(g.dtype);
   const BlkW& w = c->blk[i];
+  const float* m = mod_blk(c, mod, i);
   char* qkv = c->arena + p.off_qkv;
   char* vt = c->arena + p.off_vt;
   char* ao = c->arena + p.off_ao;
@@ -249,41 +266,35 @@ lc_status run_block(lc_dit* c, int i, const float* mod, float* x, const float* d
   float* t = (float*)(c->arena + p.off_t);
   lc_status s;
   // ---- attention branch: q,k,v of every token first
-  for (int b = 0; b < g.B; ++b)
-    for (int t0 = 0; t0 < T; t0 += p.tc) {
-      const int n = std::min(p.tc, T - t0);
-      const int64_t r0 = (int64_t)b * T + t0;
-      if ((s = ln_mod(c, x + r0 * D, delta ? delta + r0 * D : nullptr, mod_ptr(c, mod, i, b, 0), mod_ptr(c, mod, i, b, 1), xn, n)) != LC_OK) return s;
-      if ((s = linear(c, w.wqkv, w.bqkv, D, 3 * D, n, xn, qkv + r0 * 3 * D * es, 0)) != LC_OK) return s;
-    }
+  for (int64_t r0 = 0; r0 < R; r0 += p.tc) {
+    const int n = (int)std::min<int64_t>(p.tc, R - r0);
+    if ((s = ln_mod(c, x + r0 * D, delta ? delta + r0 * D : nullptr, m, 0, 1, xn, n, r0)) != LC_OK) return s;
+    if ((s = linear(c, w.wqkv, w.bqkv, D, 3 * D, n, xn, qkv + r0 * 3 * D * es, 0)) != LC_OK) return s;
+  }
   LCT_HIP(c, launch_make_vt(c->cs, g.dtype, qkv + (size_t)2 * D * es, 3 * D, vt, g.B, T, Tp, D));
-  for (int q0 = 0; q0 < T; q0 += p.tc)  // a chunk of queries of every batch element against all keys
-    LCT_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * D, vt, Tp, ao, g.B, T, g.heads, g.head_dim, q0, std::min(q0 + p.tc, T), 0));
-  for (int b = 0; b < g.B; ++b)
-    for (int t0 = 0; t0 < T; t0 += p.tc) {
-      const int n = std::min(p.tc, T - t0);
-      const int64_t r0 = (int64_t)b * T + t0;
-      if ((s = linear(c, w.wo, w.bo, D, D, n, ao + r0 * D * es, t, 1)) != LC_OK) return s;
-      if ((s = gate_add(c, dst + r0 * D, t, mod_ptr(c, mod, i, b, 2), n)) != LC_OK) return s;
-    }
+  for (int q0 = 0; q0 < T; q0 += p.qc)  // a chunk of queries of every batch element against all keys
+    LCT_HIP(c, launch_spatial_attention(c->cs, g.dtype, qkv, 3 * D, vt, Tp, ao, g.B, T, g.heads, g.head_dim, q0, std::min(q0 + p.qc, T), 0));
+  for (int64_t r0 = 0; r0 < R; r0 += p.tc) {
+    const int n = (int)std::min<int64_t>(p.tc, R - r0);
+    if ((s = linear(c, w.wo, w.bo, D, D, n, ao + r0 * D * es, t, 1)) != LC_OK) return s;
+    if ((s = gate_add(c, dst + r0 * D, t, m, 2, n, r0)) != LC_OK) return s;
+  }
   // ---- MLP branch, chunk by chunk
-  for (int b = 0; b < g.B; ++b)
-    for (int t0 = 0; t0 < T; t0 += p.tc) {
-      const int n = std::min(p.tc, T - t0);
-      const int64_t r0 = (int64_t)b * T + t0;
-      if ((s = ln_mod(c, x + r0 * D, delta ? delta + r0 * D : nullptr, mod_ptr(c, mod, i, b, 3), mod_ptr(c, mod, i, b, 4), xn, n)) != LC_OK) return s;
-      // (a bf16 stage whose hidden width the dense-row kernel covers applies the GELU in that kernel's epilogue)
-      const bool fused = g.dtype == kBF16 && (H % 160 == 0 || H % 128 == 0);
-      if ((s = linear(c, w.w1, w.b1, D, H, n, xn, hid, 0, fused ? 1 : 0)) != LC_OK) return s;
-      if (!fused) {
-        const int64_t n16 = (int64_t)n * H * es / 16;
-        if (g.dtype == kBF16) gelu_kernel<bf16_t><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((bf16_t*)hid, n16);
-        else gelu_kernel<float><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((float*)hid, n16);
-        LCT_HIP(c, hipGetLastError());
-      }
-      if ((s = linear(c, w.w2, w.b2, H, D, n, hid, t, 1)) != LC_OK) return s;
-      if ((s = gate_add(c, dst + r0 * D, t, mod_ptr(c, mod, i, b, 5), n)) != LC_OK) return s;
+  for (int64_t r0 = 0; r0 < R; r0 += p.tc) {
+    const int n = (int)std::min<int64_t>(p.tc, R - r0);
+    if ((s = ln_mod(c, x + r0 * D, delta ? delta + r0 * D : nullptr, m, 3, 4, xn, n, r0)) != LC_OK) return s;
+    // (a bf16 stage whose hidden width the dense-row kernel covers applies the GELU in that kernel's epilogue)
+    const bool fused = g.dtype == kBF16 && (H % 160 == 0 || H % 128 == 0);
+    if ((s = linear(c, w.w1, w.b1, D, H, n, xn, hid, 0, fused ? 1 : 0)) != LC_OK) return s;
+    if (!fused) {
+      const int64_t n16 = (int64_t)n * H * es / 16;
+      if (g.dtype == kBF16) gelu_kernel<bf16_t><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((bf16_t*)hid, n16);
+      else gelu_kernel<float><<<(unsigned)((n16 + 255) / 256), 256, 0, c->cs>>>((float*)hid, n16);
+      LCT_HIP(c, hipGetLastError());
     }
+    if ((s = linear(c, w.w2, w.b2, H, D, n, hid, t, 1)) != LC_OK) return s;
+    if ((s = gate_add(c, dst + r0 * D, t, m, 5, n, r0)) != LC_OK) return s;
+  }
   return LC_OK;
 }
 
@@ -311,7 +322,7 @@ lc_status run_step(lc_dit* c, const void* x_in, const void* mod, void* x_out, in
     LCT_HIP(c, hipStreamWaitEvent(c->cs, c->ev_in_done[slot], 0));
     c->in_pending[slot] = 0;
   }
-  if ((s = gate_add(c, x, delta, nullptr, R)) != LC_OK) return s;  // x_b = x_a + Delta, at both kinds of step
+  if ((s = gate_add(c, x, delta, nullptr, 0, R, 0)) != LC_OK) return s;  // x_b = x_a + Delta, at both kinds of step
   LCT_HIP(c, hipEventRecord(c->ev_consumed[slot], c->cs));
   for (int i = g.cache_b; i < g.L; ++i)
     if ((s = run_block(c, i, m, x, nullptr, x)) != LC_OK) return s;
